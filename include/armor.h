@@ -1,0 +1,133 @@
+/*
+ * armor.h -- C ABI of the MI355X (gfx950) implementation of ARMOR's per-layer factorization:
+ * fit  W-bar ~= A * S * B  with A, B block-diagonal wrappers and S = W' (.) M an N:M-sparse core
+ * (Sec. 3.1, Eq. 1) by block coordinate descent on the layer-wise proxy loss (Sec. 3.2, Eq. 2;
+ * Sec. 3.3, Alg. 1-3).
+ *
+ * General conventions
+ *   - Every pointer is a DEVICE pointer unless a comment says "host".  The caller owns every
+ *     buffer; the library never allocates or frees device memory: scratch comes from the `ws`
+ *     argument, sized by the matching *_workspace_bytes() query.  All device buffers must be
+ *     16-byte aligned.
+ *   - Matrices are row-major.  W[i*d_in + j] couples output i with input j (Sec. 2).  The sparse
+ *     axis is d_in: a group is M consecutive columns of one row (Sec. 2).  Block-diagonal wrappers
+ *     are stored as [d/d_block][d_block][d_block], A[i][p][q] = (A^(i))_pq (Sec. 3.1).
+ *   - mask_bits holds one byte per group, [d_out][d_in/M]; bit p set = column p of the group kept.
+ *     In unstructured mode a byte covers 8 consecutive columns.
+ *   - Calls are asynchronous on `hip_stream` (a hipStream_t passed as void*; NULL = default
+ *     stream), return a status code, never throw and never print.  Argument errors are detected
+ *     on the host before any launch.  Results are deterministic: no floating-point atomics.
+ *   - d_block must divide d_out and d_in and be one of 32, 64, 128, 256; M must divide d_block,
+ *     1 <= N < M <= 8.
+ */
+#ifndef ARMOR_H
+#define ARMOR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ARMOR_OK = 0,
+    ARMOR_ERR_NULL = 1,      /* a required pointer is NULL */
+    ARMOR_ERR_SHAPE = 2,     /* d_block does not divide d_out/d_in, M does not divide d_block, bad N/M, ... */
+    ARMOR_ERR_DTYPE = 3,     /* unknown armor_dtype */
+    ARMOR_ERR_WORKSPACE = 4, /* ws is NULL or ws_bytes too small */
+    ARMOR_ERR_ALIGN = 5,     /* a device buffer is not 16-byte aligned */
+    ARMOR_ERR_DEVICE = 6,    /* a HIP call failed; see armor_last_hip_error() */
+    ARMOR_ERR_UNSUPPORTED = 7 /* valid request that this build does not implement */
+} armor_status;
+
+typedef enum { ARMOR_F32 = 0, ARMOR_BF16 = 1 } armor_dtype;
+
+/* Options of armor_factorize_layer.  Zero-initialise for the defaults. */
+typedef struct {
+    int32_t selection;          /* group selection heuristic (Sec. 3.3.2, App. E.1): 0 = L1-weighted random
+                                   (default), 1 = L1 greedy, 2 = L2-weighted random, 3 = uniform random */
+    int32_t sparsity;           /* 0 = N:M (both BCD steps); 1 = unstructured: continuous step only (Sec. 4.5) */
+    int64_t unstructured_keep;  /* sparsity==1: number of kept entries (global top-k of the importance) */
+    uint64_t seed;              /* seed of the counter-based selection hash */
+    int32_t denormalize;        /* 1: fold r2 into the rows of A and r1 into the columns of B (Sec. 3.2) */
+    int32_t reserved;
+} armor_opts;
+
+const char *armor_status_string(armor_status s);
+/* hipError_t (as int) of the last failed HIP call made by this library on the calling thread. host. */
+int armor_last_hip_error(void);
+
+/*
+ * Gram matrix of the calibration activations (Sec. 2; the loss of Eq. 2 uses its diagonal).
+ *   X   [n_tokens x d_in], leading dimension ldx (elements), fp32 or bf16; one token per row
+ *       (this is the paper's X^T).
+ *   H   [d_in x d_in] fp32, leading dimension ldh.  accumulate = 0: H = X^T X;  1: H += X^T X,
+ *       so a caller can stream token chunks.  Both triangles are written.
+ * d_in must be a multiple of 32; n_tokens >= 0 (0 leaves H unchanged / zeroes it).
+ */
+armor_status armor_gram(const void *X, armor_dtype x_dtype, int64_t n_tokens, int64_t d_in, int64_t ldx,
+                        float *H, int64_t ldh, int accumulate, void *hip_stream);
+
+/* D[j] = H[j][j]  (the weights ||X_j||^2 of Eq. 2). */
+armor_status armor_gram_diag(const float *H, int64_t d_in, int64_t ldh, float *D, void *hip_stream);
+
+/*
+ * Row/column normalisation of Sec. 3.2:  r1[j] = ||W[:,j]||,  r2[i] = ||W[i,:]/r1||,
+ * Wbar = W / r1 / r2.  A zero norm is replaced by 1.  W fp32 or bf16; outputs fp32.
+ * ws: armor_normalize_workspace_bytes(d_out, d_in).
+ */
+size_t armor_normalize_workspace_bytes(int64_t d_out, int64_t d_in);
+armor_status armor_normalize(const void *W, armor_dtype w_dtype, int64_t d_out, int64_t d_in, float *Wbar,
+                             float *r1 /*[d_in]*/, float *r2 /*[d_out]*/, void *ws, size_t ws_bytes,
+                             void *hip_stream);
+
+/*
+ * Proxy loss of Eq. 2:  L = sum_ij (Wbar - A S B)_ij^2 * H_jj.
+ *   A [d_out/b][b][b] or NULL (= identity);  B [d_in/b][b][b] or NULL (= identity);
+ *   S dense [d_out x d_in] (zeros at pruned positions);
+ *   H: ldh > 0: the Gram matrix, only its diagonal is read;  ldh == 0: H is the vector D [d_in].
+ *   loss_out: one double in DEVICE memory.
+ */
+size_t armor_proxy_loss_workspace_bytes(int64_t d_out, int64_t d_in, int64_t d_block);
+armor_status armor_proxy_loss(const float *Wbar, const float *A, const float *S, const float *B, const float *H,
+                              int64_t ldh, int64_t d_out, int64_t d_in, int64_t d_block, double *loss_out,
+                              void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * The whole BCD loop (Alg. 1): normalise W, initialise by Eq. 3 (A = B = I, top-N of every group by
+ * Wbar^2 * H_jj), then n_iters times { continuous update (Alg. 2: sequential gradient steps on A, B,
+ * W' with step 1/beta, App. D) ; sparse-core update (Alg. 3: one group per block, all C(M,N) masks,
+ * closed-form least squares of Eq. 7/8) }.
+ *   W          [d_out x d_in] fp32 or bf16 (not modified)
+ *   H, ldh     as in armor_proxy_loss
+ *   A, S, B    outputs; S is the core W' (.) M as a dense matrix with exact zeros at pruned positions
+ *   mask_bits  output, [d_out][d_in/M] bytes (unstructured: [d_out][d_in/8]); may be NULL
+ *   r1, r2     outputs [d_in], [d_out] (normalisation scales); may be NULL
+ *   loss_trace output, n_iters+1 doubles in DEVICE memory, L(theta_0..theta_n) in the normalised
+ *              space; loss_trace[0] is the loss of plain N:M pruning (Sec. 3.4).  May be NULL.
+ *   loss_cont_trace  optional, n_iters doubles: loss after the continuous step of each iteration.
+ * With opts->denormalize = 0 (default) A, S, B live in the normalised space:
+ *   W ~= diag(r2) (A S B) diag(r1).
+ */
+size_t armor_factorize_workspace_bytes(int64_t d_out, int64_t d_in, int64_t d_block, int N, int M,
+                                       const armor_opts *opts);
+armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const float *H, int64_t ldh, int64_t d_out,
+                                   int64_t d_in, int64_t d_block, int N, int M, int n_iters,
+                                   const armor_opts *opts, float *A, float *S, float *B, uint8_t *mask_bits,
+                                   float *r1, float *r2, double *loss_trace, double *loss_cont_trace, void *ws,
+                                   size_t ws_bytes, void *hip_stream);
+
+/*
+ * Compressed N:M storage of the core (the form an N:M sparse matmul consumes):
+ *   values [d_out][d_in/M*N]  the kept entries of each group in increasing column order
+ *          (fp32 or bf16 per v_dtype);
+ *   meta   [d_out][d_in/M*N]  one byte per kept entry: its column inside the group (0..M-1).
+ */
+armor_status armor_pack_nm(const float *S, const uint8_t *mask_bits, int64_t d_out, int64_t d_in, int N, int M,
+                           void *values, armor_dtype v_dtype, uint8_t *meta, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ARMOR_H */

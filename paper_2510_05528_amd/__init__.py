@@ -1,0 +1,11 @@
+"""MI355X-native ARMOR per-layer factorization: thin Python binding over the C ABI (include/armor.h).
+
+Only argument marshalling happens here; every step of the path runs in the HIP kernels of
+libarmor.so.  torch is used for device memory and streams.  There is no CPU fallback: if the
+library is missing, every call raises.
+"""
+from .binding import (ARMOR_BF16, ARMOR_F32, ArmorError, factorize_layer, factorize_workspace_bytes, gram,
+                      gram_diag, load_library, normalize, pack_nm, proxy_loss, unpack_mask)
+
+__all__ = ["ARMOR_BF16", "ARMOR_F32", "ArmorError", "factorize_layer", "factorize_workspace_bytes", "gram",
+           "gram_diag", "load_library", "normalize", "pack_nm", "proxy_loss", "unpack_mask"]

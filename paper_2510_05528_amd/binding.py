@@ -1,0 +1,222 @@
+"""ctypes binding of libarmor.so.  Function names mirror the C entry points (armor_<name>)."""
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libarmor.so")
+
+ARMOR_F32, ARMOR_BF16 = 0, 1
+
+EXPORTED = ["armor_status_string", "armor_last_hip_error", "armor_gram", "armor_gram_diag",
+            "armor_normalize_workspace_bytes", "armor_normalize", "armor_proxy_loss_workspace_bytes",
+            "armor_proxy_loss", "armor_factorize_workspace_bytes", "armor_factorize_layer", "armor_pack_nm"]
+
+
+class ArmorError(RuntimeError):
+    pass
+
+
+class ArmorOpts(ctypes.Structure):
+    _fields_ = [("selection", ctypes.c_int32), ("sparsity", ctypes.c_int32), ("unstructured_keep", ctypes.c_int64),
+                ("seed", ctypes.c_uint64), ("denormalize", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+
+
+_lib = None
+_vp, _i64, _int, _sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_size_t
+
+
+def load_library():
+    """Load libarmor.so (built by __graft_entry__.build()).  Raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ArmorError("libarmor.so is not built (%s); run __graft_entry__.build()" % _LIB_PATH)
+    lib = ctypes.CDLL(_LIB_PATH)
+    lib.armor_status_string.restype = ctypes.c_char_p
+    lib.armor_status_string.argtypes = [_int]
+    lib.armor_last_hip_error.restype = _int
+    lib.armor_gram.argtypes = [_vp, _int, _i64, _i64, _i64, _vp, _i64, _int, _vp]
+    lib.armor_gram_diag.argtypes = [_vp, _i64, _i64, _vp, _vp]
+    lib.armor_normalize_workspace_bytes.restype = _sz
+    lib.armor_normalize_workspace_bytes.argtypes = [_i64, _i64]
+    lib.armor_normalize.argtypes = [_vp, _int, _i64, _i64, _vp, _vp, _vp, _vp, _sz, _vp]
+    lib.armor_proxy_loss_workspace_bytes.restype = _sz
+    lib.armor_proxy_loss_workspace_bytes.argtypes = [_i64, _i64, _i64]
+    lib.armor_proxy_loss.argtypes = [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _i64, _vp, _vp, _sz, _vp]
+    lib.armor_factorize_workspace_bytes.restype = _sz
+    lib.armor_factorize_workspace_bytes.argtypes = [_i64, _i64, _i64, _int, _int, ctypes.POINTER(ArmorOpts)]
+    lib.armor_factorize_layer.argtypes = [_vp, _int, _vp, _i64, _i64, _i64, _i64, _int, _int, _int,
+                                          ctypes.POINTER(ArmorOpts), _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz,
+                                          _vp]
+    lib.armor_pack_nm.argtypes = [_vp, _vp, _i64, _i64, _int, _int, _vp, _int, _vp, _vp]
+    _lib = lib
+    return lib
+
+
+def _check(status):
+    if status != 0:
+        lib = load_library()
+        msg = lib.armor_status_string(status).decode()
+        if status == 6:
+            msg += " (hipError %d)" % lib.armor_last_hip_error()
+        raise ArmorError("armor status %d: %s" % (status, msg))
+
+
+def _torch():
+    import torch
+    return torch
+
+
+def _stream():
+    return _vp(_torch().cuda.current_stream().cuda_stream)
+
+
+def _ptr(t):
+    return _vp(t.data_ptr()) if t is not None else _vp(0)
+
+
+def _dtype_code(t):
+    torch = _torch()
+    if t.dtype == torch.float32:
+        return ARMOR_F32
+    if t.dtype == torch.bfloat16:
+        return ARMOR_BF16
+    raise ArmorError("unsupported dtype %s" % t.dtype)
+
+
+def _dev_f32(t, name):
+    torch = _torch()
+    if not (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()):
+        raise ArmorError("%s must be a contiguous fp32 device tensor" % name)
+    return t
+
+
+def gram(X, H=None, accumulate=False):
+    """H (+)= X^T X.  X [n_tokens, d_in] fp32/bf16 on the device; returns H [d_in, d_in] fp32."""
+    torch = _torch()
+    lib = load_library()
+    if not (X.is_cuda and X.dim() == 2 and X.stride(1) == 1):
+        raise ArmorError("X must be a 2-D device tensor with unit column stride")
+    n, d_in = X.shape
+    if H is None:
+        if accumulate:
+            raise ArmorError("accumulate needs an existing H")
+        H = torch.empty((d_in, d_in), device=X.device, dtype=torch.float32)
+    _dev_f32(H, "H")
+    _check(lib.armor_gram(_ptr(X), _dtype_code(X), n, d_in, X.stride(0), _ptr(H), H.stride(0), int(accumulate), _stream()))
+    return H
+
+
+def gram_diag(H):
+    torch = _torch()
+    lib = load_library()
+    _dev_f32(H, "H")
+    D = torch.empty(H.shape[0], device=H.device, dtype=torch.float32)
+    _check(lib.armor_gram_diag(_ptr(H), H.shape[0], H.stride(0), _ptr(D), _stream()))
+    return D
+
+
+def normalize(W):
+    """Returns (Wbar, r1, r2) of the row/column normalisation."""
+    torch = _torch()
+    lib = load_library()
+    if not (W.is_cuda and W.is_contiguous()):
+        raise ArmorError("W must be a contiguous device tensor")
+    d_out, d_in = W.shape
+    Wbar = torch.empty((d_out, d_in), device=W.device, dtype=torch.float32)
+    r1 = torch.empty(d_in, device=W.device, dtype=torch.float32)
+    r2 = torch.empty(d_out, device=W.device, dtype=torch.float32)
+    nbytes = lib.armor_normalize_workspace_bytes(d_out, d_in)
+    ws = torch.empty(nbytes, device=W.device, dtype=torch.uint8)
+    _check(lib.armor_normalize(_ptr(W), _dtype_code(W), d_out, d_in, _ptr(Wbar), _ptr(r1), _ptr(r2), _ptr(ws), nbytes,
+                               _stream()))
+    return Wbar, r1, r2
+
+
+def _h_args(H, d_in):
+    """H is either the Gram matrix [d_in, d_in] or the vector D [d_in]."""
+    _dev_f32(H, "H")
+    if H.dim() == 2:
+        return H.stride(0)
+    if H.dim() == 1 and H.shape[0] == d_in:
+        return 0
+    raise ArmorError("H must be [d_in, d_in] or [d_in]")
+
+
+def proxy_loss(Wbar, A, S, B, H, d_block=None):
+    """Proxy loss as a 1-element float64 device tensor.  A or B may be None (identity)."""
+    torch = _torch()
+    lib = load_library()
+    _dev_f32(Wbar, "Wbar"), _dev_f32(S, "S")
+    d_out, d_in = Wbar.shape
+    b = d_block or (A.shape[-1] if A is not None else B.shape[-1])
+    ldh = _h_args(H, d_in)
+    out = torch.zeros(1, device=Wbar.device, dtype=torch.float64)
+    nbytes = lib.armor_proxy_loss_workspace_bytes(d_out, d_in, b)
+    ws = torch.empty(max(nbytes, 256), device=Wbar.device, dtype=torch.uint8)
+    _check(lib.armor_proxy_loss(_ptr(Wbar), _ptr(A), _ptr(S), _ptr(B), _ptr(H), ldh, d_out, d_in, b, _ptr(out), _ptr(ws),
+                                nbytes, _stream()))
+    return out
+
+
+def factorize_workspace_bytes(d_out, d_in, d_block, N, M, sparsity=0):
+    lib = load_library()
+    o = ArmorOpts(sparsity=sparsity)
+    return lib.armor_factorize_workspace_bytes(d_out, d_in, d_block, N, M, ctypes.byref(o))
+
+
+def factorize_layer(W, H, d_block, N, M, n_iters, seed=0, selection=0, sparsity=0, unstructured_keep=0,
+                    denormalize=False, ws=None, want_cont_trace=False):
+    """Run the BCD loop.  Returns dict(A, S, B, mask_bits, r1, r2, loss_trace[, loss_cont_trace])."""
+    torch = _torch()
+    lib = load_library()
+    if not (W.is_cuda and W.is_contiguous()):
+        raise ArmorError("W must be a contiguous device tensor")
+    d_out, d_in = W.shape
+    ldh = _h_args(H, d_in)
+    dev = W.device
+    o = ArmorOpts(selection=selection, sparsity=sparsity, unstructured_keep=unstructured_keep, seed=seed,
+                  denormalize=int(denormalize))
+    nbytes = lib.armor_factorize_workspace_bytes(d_out, d_in, d_block, N, M, ctypes.byref(o))
+    if nbytes == 0:
+        _check(2)
+    if ws is None or ws.numel() < nbytes:
+        ws = torch.empty(nbytes, device=dev, dtype=torch.uint8)
+    mg = 8 if sparsity == 1 else M
+    A = torch.empty((d_out // d_block, d_block, d_block), device=dev, dtype=torch.float32)
+    B = torch.empty((d_in // d_block, d_block, d_block), device=dev, dtype=torch.float32)
+    S = torch.empty((d_out, d_in), device=dev, dtype=torch.float32)
+    mask_bits = torch.empty((d_out, d_in // mg), device=dev, dtype=torch.uint8)
+    r1 = torch.empty(d_in, device=dev, dtype=torch.float32)
+    r2 = torch.empty(d_out, device=dev, dtype=torch.float32)
+    trace = torch.zeros(n_iters + 1, device=dev, dtype=torch.float64)
+    ctrace = torch.zeros(max(n_iters, 1), device=dev, dtype=torch.float64) if want_cont_trace else None
+    _check(lib.armor_factorize_layer(_ptr(W), _dtype_code(W), _ptr(H), ldh, d_out, d_in, d_block, N, M, n_iters,
+                                     ctypes.byref(o), _ptr(A), _ptr(S), _ptr(B), _ptr(mask_bits), _ptr(r1), _ptr(r2),
+                                     _ptr(trace), _ptr(ctrace), _ptr(ws), ws.numel(), _stream()))
+    out = dict(A=A, S=S, B=B, mask_bits=mask_bits, r1=r1, r2=r2, loss_trace=trace, ws=ws)
+    if want_cont_trace:
+        out["loss_cont_trace"] = ctrace[:n_iters]
+    return out
+
+
+def pack_nm(S, mask_bits, N, M, bf16=False):
+    torch = _torch()
+    lib = load_library()
+    _dev_f32(S, "S")
+    d_out, d_in = S.shape
+    values = torch.empty((d_out, d_in // M * N), device=S.device, dtype=torch.bfloat16 if bf16 else torch.float32)
+    meta = torch.empty((d_out, d_in // M * N), device=S.device, dtype=torch.uint8)
+    _check(lib.armor_pack_nm(_ptr(S), _ptr(mask_bits), d_out, d_in, N, M, _ptr(values), ARMOR_BF16 if bf16 else ARMOR_F32,
+                             _ptr(meta), _stream()))
+    return values, meta
+
+
+def unpack_mask(mask_bits, M):
+    """Host helper: [d_out, d_in/M] bytes -> [d_out, d_in] 0/1 array."""
+    mb = np.asarray(mask_bits, dtype=np.uint8)
+    bits = (mb[..., None] >> np.arange(M, dtype=np.uint8)) & 1
+    return bits.reshape(mb.shape[0], mb.shape[1] * M).astype(np.uint8)

@@ -1,0 +1,323 @@
+// C ABI of the library (see include/armor.h) and the host-side iteration driver (Alg. 1).
+// The driver only validates, carves the caller's workspace and enqueues kernels on one stream:
+// nothing is allocated, nothing synchronises, every scalar of the iteration (step sizes, losses)
+// is produced and consumed on the device.
+#include "../../include/armor.h"
+#include "armor_internal.h"
+
+#include <algorithm>
+#include <cstring>
+
+using namespace armor;
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+armor_status check_hip() {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        g_last_hip_error = (int)e;
+        return ARMOR_ERR_DEVICE;
+    }
+    return ARMOR_OK;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int device_cus() {
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+            cus = n;
+        else
+            cus = 256;
+    }
+    return cus;
+}
+
+// How many chunks to split the accumulation axis of a gradient phase into: workgroup (k, c) walks
+// `chunk` blocks and leaves one b x b partial.  Cost model in units of one block's chain time:
+// rounds * (chunk + a small charge for writing the partial); finer splits balance the tail.
+int choose_nsplit(int n_outer, int n_inner, int b) {
+    const int slots = device_cus() * (b >= 128 ? 1 : 2);
+    int best = 1;
+    double best_cost = 1e300;
+    for (int ns = 1; ns <= n_inner && ns <= chain_max_nsplit(); ++ns) {
+        int chunk = (n_inner + ns - 1) / ns;
+        int eff = (n_inner + chunk - 1) / chunk; // splits that actually hold work
+        if (eff != ns) continue;
+        long wgs = (long)n_outer * ns;
+        long rounds = (wgs + slots - 1) / slots;
+        double cost = (double)rounds * (chunk + 0.08);
+        if (cost < best_cost - 1e-12) { best_cost = cost; best = ns; }
+    }
+    return best;
+}
+
+struct Carver {
+    char *base;
+    size_t off;
+    explicit Carver(void *p) : base(reinterpret_cast<char *>(p)), off(0) {}
+    template <typename T> T *take(size_t count) {
+        off = (off + 255) & ~size_t(255);
+        T *r = base ? reinterpret_cast<T *>(base + off) : nullptr;
+        off += count * sizeof(T);
+        return r;
+    }
+};
+
+struct FactorWs {
+    float *Wbar, *G, *D, *gpart, *beta_part, *loss_part, *loss_part2, *K, *colnorm2, *fro2A, *fro2K, *cn_partial,
+        *r1, *r2;
+    double *scalars;
+    uint8_t *mask;
+    void *unstructured;
+    int nsA, nsB, cn_chunks;
+    size_t bytes;
+};
+
+int colnorm_chunks(int64_t d_out) { return (int)std::max<int64_t>(1, std::min<int64_t>(64, d_out / 64)); }
+
+armor_status validate_shape(int64_t d_out, int64_t d_in, int64_t b) {
+    if (d_out <= 0 || d_in <= 0 || b <= 0) return ARMOR_ERR_SHAPE;
+    if (d_out % b != 0 || d_in % b != 0) return ARMOR_ERR_SHAPE;
+    if (b != 32 && b != 64 && b != 128 && b != 256) return ARMOR_ERR_SHAPE;
+    if (d_out / b > 1 << 20 || d_in / b > 1 << 20 || (d_out / b) * (d_in / b) > (int64_t)1 << 30) return ARMOR_ERR_SHAPE;
+    return ARMOR_OK;
+}
+
+Dims make_dims(int64_t d_out, int64_t d_in, int64_t b) {
+    Dims d;
+    d.d_out = d_out; d.d_in = d_in; d.b = (int)b;
+    d.nbi = (int)(d_out / b); d.nbj = (int)(d_in / b); d.nblocks = d.nbi * d.nbj;
+    return d;
+}
+
+FactorWs carve_factor(void *ws, const Dims &d, int mask_group, const armor_opts *opts) {
+    FactorWs f;
+    Carver c(ws);
+    const size_t P = (size_t)d.d_out * d.d_in, bb = (size_t)d.b * d.b;
+    f.nsA = choose_nsplit(d.nbi, d.nbj, d.b);
+    f.nsB = choose_nsplit(d.nbj, d.nbi, d.b);
+    f.cn_chunks = colnorm_chunks(d.d_out);
+    f.Wbar = c.take<float>(P);
+    f.G = c.take<float>(P);
+    f.D = c.take<float>(d.d_in);
+    f.gpart = c.take<float>(std::max((size_t)d.nbi * f.nsA, (size_t)d.nbj * f.nsB) * bb);
+    f.beta_part = c.take<float>(d.nblocks);
+    f.loss_part = c.take<float>(d.nblocks);
+    f.loss_part2 = c.take<float>(d.nblocks);
+    f.K = c.take<float>((size_t)d.nbj * bb);
+    f.colnorm2 = c.take<float>(d.d_out);
+    f.fro2A = c.take<float>(d.nbi);
+    f.fro2K = c.take<float>(d.nbj);
+    f.cn_partial = c.take<float>((size_t)f.cn_chunks * d.d_in);
+    f.r1 = c.take<float>(d.d_in);
+    f.r2 = c.take<float>(d.d_out);
+    f.scalars = c.take<double>(8);
+    f.mask = c.take<uint8_t>((size_t)d.d_out * (d.d_in / mask_group));
+    f.unstructured = nullptr;
+    (void)opts;
+    f.bytes = (c.off + 255) & ~size_t(255);
+    return f;
+}
+
+armor_status validate_nm(int N, int M, int64_t b) {
+    if (M != 2 && M != 4 && M != 8) return ARMOR_ERR_SHAPE;
+    if (N < 1 || N >= M) return ARMOR_ERR_SHAPE;
+    if (b % M != 0) return ARMOR_ERR_SHAPE;
+    return ARMOR_OK;
+}
+
+} // namespace
+
+extern "C" {
+
+const char *armor_status_string(armor_status s) {
+    switch (s) {
+    case ARMOR_OK: return "ok";
+    case ARMOR_ERR_NULL: return "null pointer";
+    case ARMOR_ERR_SHAPE: return "bad shape";
+    case ARMOR_ERR_DTYPE: return "bad dtype";
+    case ARMOR_ERR_WORKSPACE: return "workspace missing or too small";
+    case ARMOR_ERR_ALIGN: return "buffer not 16-byte aligned";
+    case ARMOR_ERR_DEVICE: return "HIP error";
+    case ARMOR_ERR_UNSUPPORTED: return "unsupported configuration";
+    }
+    return "unknown status";
+}
+
+int armor_last_hip_error(void) { return g_last_hip_error; }
+
+armor_status armor_gram(const void *X, armor_dtype x_dtype, int64_t n_tokens, int64_t d_in, int64_t ldx, float *H,
+                        int64_t ldh, int accumulate, void *hip_stream) {
+    if (!H || (!X && n_tokens > 0)) return ARMOR_ERR_NULL;
+    if (x_dtype != ARMOR_F32 && x_dtype != ARMOR_BF16) return ARMOR_ERR_DTYPE;
+    if (d_in <= 0 || d_in % 32 != 0 || n_tokens < 0 || ldx < d_in || ldh < d_in) return ARMOR_ERR_SHAPE;
+    if (!aligned16(X) || !aligned16(H)) return ARMOR_ERR_ALIGN;
+    launch_gram(X, x_dtype == ARMOR_BF16, n_tokens, d_in, ldx, H, ldh, accumulate, (hipStream_t)hip_stream);
+    return check_hip();
+}
+
+armor_status armor_gram_diag(const float *H, int64_t d_in, int64_t ldh, float *D, void *hip_stream) {
+    if (!H || !D) return ARMOR_ERR_NULL;
+    if (d_in <= 0 || ldh < d_in) return ARMOR_ERR_SHAPE;
+    launch_diag(H, d_in, ldh, D, (hipStream_t)hip_stream);
+    return check_hip();
+}
+
+size_t armor_normalize_workspace_bytes(int64_t d_out, int64_t d_in) {
+    if (d_out <= 0 || d_in <= 0) return 0;
+    return (size_t)colnorm_chunks(d_out) * (size_t)d_in * sizeof(float) + 256;
+}
+
+armor_status armor_normalize(const void *W, armor_dtype w_dtype, int64_t d_out, int64_t d_in, float *Wbar, float *r1,
+                             float *r2, void *ws, size_t ws_bytes, void *hip_stream) {
+    if (!W || !Wbar || !r1 || !r2) return ARMOR_ERR_NULL;
+    if (w_dtype != ARMOR_F32 && w_dtype != ARMOR_BF16) return ARMOR_ERR_DTYPE;
+    if (d_out <= 0 || d_in <= 0) return ARMOR_ERR_SHAPE;
+    if (!ws || ws_bytes < armor_normalize_workspace_bytes(d_out, d_in)) return ARMOR_ERR_WORKSPACE;
+    if (!aligned16(W) || !aligned16(Wbar) || !aligned16(ws)) return ARMOR_ERR_ALIGN;
+    hipStream_t s = (hipStream_t)hip_stream;
+    Carver c(ws);
+    int chunks = colnorm_chunks(d_out);
+    float *partial = c.take<float>((size_t)chunks * d_in);
+    launch_colnorm(W, w_dtype == ARMOR_BF16, d_out, d_in, partial, chunks, r1, s);
+    launch_rownorm_scale(W, w_dtype == ARMOR_BF16, d_out, d_in, r1, r2, Wbar, s);
+    return check_hip();
+}
+
+size_t armor_proxy_loss_workspace_bytes(int64_t d_out, int64_t d_in, int64_t d_block) {
+    if (validate_shape(d_out, d_in, d_block) != ARMOR_OK) return 0;
+    Dims d = make_dims(d_out, d_in, d_block);
+    Carver c(nullptr);
+    c.take<float>(d.d_in);
+    c.take<float>((size_t)d.nbi * d.b * d.b);
+    c.take<float>((size_t)d.nbj * d.b * d.b);
+    c.take<float>(d.nblocks);
+    return c.off + 256;
+}
+
+armor_status armor_proxy_loss(const float *Wbar, const float *A, const float *S, const float *B, const float *H,
+                              int64_t ldh, int64_t d_out, int64_t d_in, int64_t d_block, double *loss_out, void *ws,
+                              size_t ws_bytes, void *hip_stream) {
+    if (!Wbar || !S || !H || !loss_out) return ARMOR_ERR_NULL;
+    armor_status st = validate_shape(d_out, d_in, d_block);
+    if (st != ARMOR_OK) return st;
+    if (ldh != 0 && ldh < d_in) return ARMOR_ERR_SHAPE;
+    if (d_block == 256) return ARMOR_ERR_UNSUPPORTED;
+    if (!ws || ws_bytes < armor_proxy_loss_workspace_bytes(d_out, d_in, d_block)) return ARMOR_ERR_WORKSPACE;
+    if (!aligned16(Wbar) || !aligned16(S) || !aligned16(ws) || (A && !aligned16(A)) || (B && !aligned16(B)))
+        return ARMOR_ERR_ALIGN;
+    hipStream_t s = (hipStream_t)hip_stream;
+    Dims d = make_dims(d_out, d_in, d_block);
+    Carver c(ws);
+    float *D = c.take<float>(d.d_in);
+    float *Ai = c.take<float>((size_t)d.nbi * d.b * d.b);
+    float *Bi = c.take<float>((size_t)d.nbj * d.b * d.b);
+    float *loss_part = c.take<float>(d.nblocks);
+    if (ldh > 0) launch_diag(H, d_in, ldh, D, s);
+    else if (hipMemcpyAsync(D, H, sizeof(float) * d_in, hipMemcpyDeviceToDevice, s) != hipSuccess) return check_hip();
+    if (!A) { launch_init_identity(Ai, d.nbi, d.b, s); A = Ai; }
+    if (!B) { launch_init_identity(Bi, d.nbj, d.b, s); B = Bi; }
+    launch_phase_A(d, Wbar, S, A, B, D, 1, nullptr, nullptr, loss_part, true, s);
+    launch_sum_to_double(loss_part, d.nblocks, loss_out, s);
+    return check_hip();
+}
+
+size_t armor_factorize_workspace_bytes(int64_t d_out, int64_t d_in, int64_t d_block, int N, int M,
+                                       const armor_opts *opts) {
+    if (validate_shape(d_out, d_in, d_block) != ARMOR_OK) return 0;
+    const bool unstructured = opts && opts->sparsity == 1;
+    if (!unstructured && validate_nm(N, M, d_block) != ARMOR_OK) return 0;
+    Dims d = make_dims(d_out, d_in, d_block);
+    FactorWs f = carve_factor(nullptr, d, unstructured ? 8 : M, opts);
+    return f.bytes;
+}
+
+armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const float *H, int64_t ldh, int64_t d_out,
+                                   int64_t d_in, int64_t d_block, int N, int M, int n_iters, const armor_opts *opts,
+                                   float *A, float *S, float *B, uint8_t *mask_bits, float *r1, float *r2,
+                                   double *loss_trace, double *loss_cont_trace, void *ws, size_t ws_bytes,
+                                   void *hip_stream) {
+    if (!W || !H || !A || !S || !B) return ARMOR_ERR_NULL;
+    if (w_dtype != ARMOR_F32 && w_dtype != ARMOR_BF16) return ARMOR_ERR_DTYPE;
+    armor_status st = validate_shape(d_out, d_in, d_block);
+    if (st != ARMOR_OK) return st;
+    armor_opts o;
+    std::memset(&o, 0, sizeof(o));
+    if (opts) o = *opts;
+    const bool unstructured = o.sparsity == 1;
+    if (o.sparsity != 0 && o.sparsity != 1) return ARMOR_ERR_SHAPE;
+    if (o.selection < 0 || o.selection > 3) return ARMOR_ERR_SHAPE;
+    if (!unstructured) {
+        st = validate_nm(N, M, d_block);
+        if (st != ARMOR_OK) return st;
+    } else if (o.unstructured_keep < 0 || o.unstructured_keep > d_out * d_in) {
+        return ARMOR_ERR_SHAPE;
+    }
+    if (n_iters < 0 || (ldh != 0 && ldh < d_in)) return ARMOR_ERR_SHAPE;
+    if (d_block == 256 || unstructured) return ARMOR_ERR_UNSUPPORTED;
+    const int mask_group = unstructured ? 8 : M;
+    Dims d = make_dims(d_out, d_in, d_block);
+    if (!ws) return ARMOR_ERR_WORKSPACE;
+    FactorWs f = carve_factor(ws, d, mask_group, &o);
+    if (ws_bytes < f.bytes) return ARMOR_ERR_WORKSPACE;
+    if (!aligned16(W) || !aligned16(A) || !aligned16(S) || !aligned16(B) || !aligned16(ws) || (ldh > 0 && !aligned16(H)))
+        return ARMOR_ERR_ALIGN;
+    hipStream_t s = (hipStream_t)hip_stream;
+    uint8_t *mask = mask_bits ? mask_bits : f.mask;
+    float *r1p = r1 ? r1 : f.r1, *r2p = r2 ? r2 : f.r2;
+
+    // weights of Eq. 2
+    if (ldh > 0) launch_diag(H, d_in, ldh, f.D, s);
+    else if (hipMemcpyAsync(f.D, H, sizeof(float) * d_in, hipMemcpyDeviceToDevice, s) != hipSuccess) return check_hip();
+    // Alg. 1: normalise, initialise
+    launch_colnorm(W, w_dtype == ARMOR_BF16, d_out, d_in, f.cn_partial, f.cn_chunks, r1p, s);
+    launch_rownorm_scale(W, w_dtype == ARMOR_BF16, d_out, d_in, r1p, r2p, f.Wbar, s);
+    launch_init_identity(A, d.nbi, d.b, s);
+    launch_init_identity(B, d.nbj, d.b, s);
+    launch_init_nm(f.Wbar, f.D, d_out, d_in, N, M, S, mask, s);
+    st = check_hip();
+    if (st != ARMOR_OK) return st;
+
+    for (int t = 1; t <= n_iters; ++t) {
+        // continuous step (Alg. 2), each gradient at the already-updated parameters (Lemma 1)
+        launch_phase_A(d, f.Wbar, S, A, B, f.D, f.nsA, f.gpart, f.beta_part, f.loss_part, false, s);
+        launch_update_wrapper(A, d.nbi, d.b, f.gpart, f.nsA, f.beta_part, d.nblocks, f.loss_part,
+                              loss_trace ? loss_trace + (t - 1) : nullptr, s);
+        launch_phase_B(d, f.Wbar, S, A, B, f.D, f.nsB, f.gpart, f.beta_part, s);
+        launch_update_wrapper(B, d.nbj, d.b, f.gpart, f.nsB, f.beta_part, d.nblocks, nullptr, nullptr, s);
+        launch_wrapper_grams(d, A, B, f.D, f.colnorm2, f.fro2A, f.K, f.fro2K, s);
+        launch_finalize_betaW(f.fro2A, d.nbi, f.fro2K, d.nbj, f.scalars, s);
+        launch_phase_G(d, f.Wbar, S, A, B, f.D, mask, mask_group, f.scalars, nullptr, nullptr, 0, s);
+        // sparse-core step (Alg. 3)
+        launch_phase_G(d, f.Wbar, S, A, B, f.D, mask, mask_group, f.scalars, f.G, f.loss_part2, 1, s);
+        launch_sparse_step(d, f.G, S, mask, f.K, f.colnorm2, N, M, o.selection, o.seed, t, f.loss_part2,
+                           loss_cont_trace ? loss_cont_trace + (t - 1) : nullptr, s);
+        if ((t & 15) == 0) {
+            st = check_hip();
+            if (st != ARMOR_OK) return st;
+        }
+    }
+    if (loss_trace) {
+        launch_phase_A(d, f.Wbar, S, A, B, f.D, 1, nullptr, nullptr, f.loss_part, true, s);
+        launch_sum_to_double(f.loss_part, d.nblocks, loss_trace + n_iters, s);
+    }
+    if (o.denormalize) launch_denormalize(A, B, r1p, r2p, d_out, d_in, d.b, s);
+    return check_hip();
+}
+
+armor_status armor_pack_nm(const float *S, const uint8_t *mask_bits, int64_t d_out, int64_t d_in, int N, int M,
+                           void *values, armor_dtype v_dtype, uint8_t *meta, void *hip_stream) {
+    if (!S || !mask_bits || !values || !meta) return ARMOR_ERR_NULL;
+    if (v_dtype != ARMOR_F32 && v_dtype != ARMOR_BF16) return ARMOR_ERR_DTYPE;
+    if (d_out <= 0 || d_in <= 0 || (M != 2 && M != 4 && M != 8) || N < 1 || N >= M || d_in % M != 0) return ARMOR_ERR_SHAPE;
+    launch_pack_nm(S, mask_bits, d_out, d_in, N, M, values, v_dtype == ARMOR_BF16, meta, (hipStream_t)hip_stream);
+    return check_hip();
+}
+
+} // extern "C"

@@ -1,0 +1,64 @@
+// Internal launch interface between the C ABI (armor_api.hip) and the kernel files.
+// Everything here takes raw device pointers and a stream; nothing allocates.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace armor {
+
+struct Dims {
+    int64_t d_out, d_in;
+    int b;        // block size of the wrappers (Sec. 3.1)
+    int nbi, nbj; // number of row / column blocks
+    int nblocks;  // nbi * nbj
+};
+
+// ---- fused per-block chains (chain.hip) -------------------------------------------------------
+// A-phase of Alg. 2: per block S = C B, R = Wbar - A S, partial grad_A, ||S D S^T||_F, block loss.
+void launch_phase_A(const Dims &d, const float *Wbar, const float *C, const float *A, const float *B,
+                    const float *D, int nsplit, float *gpart, float *beta_part, float *loss_part,
+                    bool loss_only, hipStream_t s);
+// B-phase: S' = A C, R = Wbar - S' B, partial grad_B, ||S'^T S'||_F ||D^j||_F.
+void launch_phase_B(const Dims &d, const float *Wbar, const float *C, const float *A, const float *B,
+                    const float *D, int nsplit, float *gpart, float *beta_part, hipStream_t s);
+// Core gradient G = A^T ((Wbar - A C B) D) B^T per block.
+//   mode 0 (W'-step of Alg. 2): C += (2/beta_W) G on kept entries, beta_W read from scalars[2].
+//   mode 1 (Alg. 3 input): Gout = -2 G (unmasked), block loss to loss_part.
+void launch_phase_G(const Dims &d, const float *Wbar, float *C, const float *A, const float *B, const float *D,
+                    const uint8_t *mask, int mask_group, const double *scalars, float *Gout, float *loss_part,
+                    int mode, hipStream_t s);
+// Per wrapper block: ||A^i[:,p]||^2, ||A^iT A^i||_F^2; K^j = B^j D^j B^jT, ||K^j||_F^2.
+void launch_wrapper_grams(const Dims &d, const float *A, const float *B, const float *D, float *colnorm2,
+                          float *fro2A, float *K, float *fro2K, hipStream_t s);
+int chain_max_nsplit();
+
+// ---- small kernels (small.hip) ----------------------------------------------------------------
+void launch_colnorm(const void *W, int bf16, int64_t d_out, int64_t d_in, float *partial, int nchunk, float *r1,
+                    hipStream_t s);
+void launch_rownorm_scale(const void *W, int bf16, int64_t d_out, int64_t d_in, const float *r1, float *r2,
+                          float *Wbar, hipStream_t s);
+void launch_init_identity(float *A, int nblk, int b, hipStream_t s);
+void launch_init_nm(const float *Wbar, const float *D, int64_t d_out, int64_t d_in, int N, int M, float *C,
+                    uint8_t *mask, hipStream_t s);
+void launch_diag(const float *H, int64_t d_in, int64_t ldh, float *D, hipStream_t s);
+// A -= (sum of partials)/beta, beta = 2 * sum(beta_part); optionally trace_out = sum(loss_part).
+void launch_update_wrapper(float *A, int nblk, int b, const float *gpart, int nsplit, const float *beta_part,
+                           int nblocks, const float *loss_part, double *trace_out, hipStream_t s);
+void launch_finalize_betaW(const float *fro2A, int nbi, const float *fro2K, int nbj, double *scalars, hipStream_t s);
+void launch_sum_to_double(const float *part, int n, double *out, hipStream_t s);
+void launch_sparse_step(const Dims &d, const float *G, float *C, uint8_t *mask, const float *K,
+                        const float *colnorm2, int N, int M, int selection, uint64_t seed, int64_t t,
+                        const float *loss_part, double *loss_cont_out, hipStream_t s);
+void launch_denormalize(float *A, float *B, const float *r1, const float *r2, int64_t d_out, int64_t d_in, int b,
+                        hipStream_t s);
+void launch_pack_nm(const float *S, const uint8_t *mask, int64_t d_out, int64_t d_in, int N, int M, void *values,
+                    int bf16, uint8_t *meta, hipStream_t s);
+void launch_unstructured_init(const float *Wbar, const float *D, int64_t d_out, int64_t d_in, int64_t keep,
+                              float *C, uint8_t *mask, void *ws, hipStream_t s);
+size_t unstructured_init_ws_bytes(int64_t d_out, int64_t d_in);
+
+// ---- Gram (gram.hip) --------------------------------------------------------------------------
+void launch_gram(const void *X, int bf16, int64_t n, int64_t d_in, int64_t ldx, float *H, int64_t ldh,
+                 int accumulate, hipStream_t s);
+
+} // namespace armor

@@ -1,0 +1,109 @@
+// Gram matrix of the calibration activations, H (+)= X^T X (Sec. 2; Eq. 2 uses its diagonal).
+// X is [n_tokens x d_in] row-major, so the token index is the contraction index and both MFMA
+// operands are read "k-major" straight from a row-major chunk of X staged in LDS.
+// Only tile pairs (ta <= tb) are computed; the mirror tile is written from the same accumulators.
+#include "armor_internal.h"
+
+namespace armor {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+__device__ __forceinline__ float gram_bf16_to_float(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
+
+template <int T> struct GramCfg;
+template <> struct GramCfg<32>  { static constexpr int WM = 1, WN = 1, TM = 1, TN = 1; };
+template <> struct GramCfg<64>  { static constexpr int WM = 2, WN = 2, TM = 1, TN = 1; };
+template <> struct GramCfg<128> { static constexpr int WM = 2, WN = 4, TM = 2, TN = 1; };
+
+// fp32 MFMA path (exact products of the inputs, fp32 accumulation); bf16 inputs are widened on load.
+template <int T, bool BF16>
+__global__ __launch_bounds__(GramCfg<T>::WM *GramCfg<T>::WN * 64) void gram_f32_kernel(
+    const void *__restrict__ X, int64_t n, int64_t ldx, int ntile, float *__restrict__ H, int64_t ldh,
+    int accumulate) {
+    using G = GramCfg<T>;
+    constexpr int NT = G::WM * G::WN * 64, KC = 16, TM = G::TM, TN = G::TN;
+    __shared__ float Xa[KC][T];
+    __shared__ float Xb[KC][T];
+    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, l32 = lane & 31, kh = lane >> 5;
+    int ta = 0, rem = blockIdx.x;
+    while (rem >= ntile - ta) { rem -= ntile - ta; ++ta; }
+    const int tb = ta + rem;
+    const int wm0 = (w % G::WM) * TM * 32, wn0 = (w / G::WM) * TN * 32;
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int a = 0; a < TM; ++a)
+#pragma unroll
+        for (int c = 0; c < TN; ++c)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][c][r] = 0.f;
+
+    for (int64_t t0 = 0; t0 < n; t0 += KC) {
+        __syncthreads();
+        for (int e = tid; e < KC * T; e += NT) {
+            int k = e / T, c = e % T;
+            int64_t t = t0 + k;
+            float va = 0.f, vb = 0.f;
+            if (t < n) {
+                if (BF16) {
+                    const uint16_t *x = reinterpret_cast<const uint16_t *>(X) + t * ldx;
+                    va = gram_bf16_to_float(x[(int64_t)ta * T + c]);
+                    vb = gram_bf16_to_float(x[(int64_t)tb * T + c]);
+                } else {
+                    const float *x = reinterpret_cast<const float *>(X) + t * ldx;
+                    va = x[(int64_t)ta * T + c];
+                    vb = x[(int64_t)tb * T + c];
+                }
+            }
+            Xa[k][c] = va;
+            Xb[k][c] = vb;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < KC; k += 2) {
+            float a[TM], b[TN];
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm) a[tm] = Xa[k + kh][wm0 + tm * 32 + l32];
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn) b[tn] = Xb[k + kh][wn0 + tn * 32 + l32];
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn)
+                    acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[tm], b[tn], acc[tm][tn], 0, 0, 0);
+        }
+    }
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                int64_t row = (int64_t)ta * T + wm0 + tm * 32 + (r >> 2) * 8 + kh * 4 + (r & 3);
+                int64_t col = (int64_t)tb * T + wn0 + tn * 32 + l32;
+                float v = acc[tm][tn][r];
+                float *h = H + row * ldh + col;
+                *h = accumulate ? *h + v : v;
+                if (ta != tb) {
+                    float *hm = H + col * ldh + row;
+                    *hm = accumulate ? *hm + v : v;
+                }
+            }
+}
+
+void launch_gram(const void *X, int bf16, int64_t n, int64_t d_in, int64_t ldx, float *H, int64_t ldh,
+                 int accumulate, hipStream_t s) {
+    int T = (d_in % 128 == 0) ? 128 : (d_in % 64 == 0) ? 64 : 32;
+    int ntile = (int)(d_in / T);
+    dim3 grid((unsigned)(ntile * (ntile + 1) / 2));
+#define ARMOR_GRAM_CASE(tt)                                                                                        \
+    if (T == tt) {                                                                                                 \
+        dim3 block(GramCfg<tt>::WM * GramCfg<tt>::WN * 64);                                                        \
+        if (bf16) hipLaunchKernelGGL((gram_f32_kernel<tt, true>), grid, block, 0, s, X, n, ldx, ntile, H, ldh, accumulate);  \
+        else      hipLaunchKernelGGL((gram_f32_kernel<tt, false>), grid, block, 0, s, X, n, ldx, ntile, H, ldh, accumulate); \
+        return;                                                                                                    \
+    }
+    ARMOR_GRAM_CASE(128) ARMOR_GRAM_CASE(64) ARMOR_GRAM_CASE(32)
+#undef ARMOR_GRAM_CASE
+}
+
+} // namespace armor

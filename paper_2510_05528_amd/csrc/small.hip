@@ -1,0 +1,542 @@
+// HBM-bound and small kernels around the contraction chains: normalisation (Sec. 3.2),
+// initialisation (Eq. 3), wrapper updates (Alg. 2), the sparse-core step (Alg. 3, Eq. 6-8),
+// denormalisation and N:M packing.  gfx950; 64-wide waves; every reduction has a fixed order.
+#include "armor_internal.h"
+
+namespace armor {
+
+__device__ __forceinline__ float bf16_bits_to_float(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
+
+template <bool BF16> __device__ __forceinline__ float load_w(const void *W, int64_t idx) {
+    if (BF16) return bf16_bits_to_float(reinterpret_cast<const uint16_t *>(W)[idx]);
+    return reinterpret_cast<const float *>(W)[idx];
+}
+
+// deterministic sum over a 256-thread workgroup; result in every thread
+__device__ __forceinline__ double block_sum_256(double v, double *red) {
+    const int tid = threadIdx.x;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    __syncthreads();
+    if ((tid & 63) == 0) red[tid >> 6] = v;
+    __syncthreads();
+    return (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+// ------------------------------------------------------------------------------------------------
+// normalisation (Sec. 3.2)
+// ------------------------------------------------------------------------------------------------
+template <bool BF16>
+__global__ __launch_bounds__(256) void colnorm_partial_kernel(const void *__restrict__ W, int64_t d_out,
+                                                              int64_t d_in, int nchunk,
+                                                              float *__restrict__ partial) {
+    int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    int c = blockIdx.y;
+    int64_t rows = (d_out + nchunk - 1) / nchunk, r0 = c * rows, r1 = min(d_out, r0 + rows);
+    if (j >= d_in) return;
+    float s = 0.f;
+    for (int64_t i = r0; i < r1; ++i) {
+        float w = load_w<BF16>(W, i * d_in + j);
+        s += w * w;
+    }
+    partial[(int64_t)c * d_in + j] = s;
+}
+
+__global__ __launch_bounds__(256) void colnorm_final_kernel(const float *__restrict__ partial, int64_t d_in,
+                                                            int nchunk, float *__restrict__ r1) {
+    int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (j >= d_in) return;
+    double s = 0.0;
+    for (int c = 0; c < nchunk; ++c) s += (double)partial[(int64_t)c * d_in + j];
+    float r = (float)sqrt(s);
+    r1[j] = r > 0.f ? r : 1.f;
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void rownorm_scale_kernel(const void *__restrict__ W, int64_t d_in,
+                                                            const float *__restrict__ r1, float *__restrict__ r2,
+                                                            float *__restrict__ Wbar) {
+    __shared__ double red[4];
+    const int64_t i = blockIdx.x;
+    double s = 0.0;
+    for (int64_t j = threadIdx.x; j < d_in; j += 256) {
+        float w1 = load_w<BF16>(W, i * d_in + j) / r1[j];
+        s += (double)w1 * (double)w1;
+    }
+    s = block_sum_256(s, red);
+    float r = (float)sqrt(s);
+    r = r > 0.f ? r : 1.f;
+    if (threadIdx.x == 0) r2[i] = r;
+    for (int64_t j = threadIdx.x; j < d_in; j += 256)
+        Wbar[i * d_in + j] = (load_w<BF16>(W, i * d_in + j) / r1[j]) / r;
+}
+
+void launch_colnorm(const void *W, int bf16, int64_t d_out, int64_t d_in, float *partial, int nchunk, float *r1,
+                    hipStream_t s) {
+    dim3 grid((unsigned)((d_in + 255) / 256), nchunk);
+    if (bf16) hipLaunchKernelGGL(colnorm_partial_kernel<true>, grid, dim3(256), 0, s, W, d_out, d_in, nchunk, partial);
+    else      hipLaunchKernelGGL(colnorm_partial_kernel<false>, grid, dim3(256), 0, s, W, d_out, d_in, nchunk, partial);
+    hipLaunchKernelGGL(colnorm_final_kernel, dim3((unsigned)((d_in + 255) / 256)), dim3(256), 0, s, partial, d_in,
+                       nchunk, r1);
+}
+
+void launch_rownorm_scale(const void *W, int bf16, int64_t d_out, int64_t d_in, const float *r1, float *r2,
+                          float *Wbar, hipStream_t s) {
+    if (bf16) hipLaunchKernelGGL(rownorm_scale_kernel<true>, dim3((unsigned)d_out), dim3(256), 0, s, W, d_in, r1, r2, Wbar);
+    else      hipLaunchKernelGGL(rownorm_scale_kernel<false>, dim3((unsigned)d_out), dim3(256), 0, s, W, d_in, r1, r2, Wbar);
+}
+
+// ------------------------------------------------------------------------------------------------
+// initialisation (Eq. 3)
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void init_identity_kernel(float *__restrict__ A, int64_t total, int b) {
+    int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= total) return;
+    int64_t within = e % ((int64_t)b * b);
+    A[e] = (within / b == within % b) ? 1.f : 0.f;
+}
+
+void launch_init_identity(float *A, int nblk, int b, hipStream_t s) {
+    int64_t total = (int64_t)nblk * b * b;
+    hipLaunchKernelGGL(init_identity_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, A, total, b);
+}
+
+// One thread per group of M columns: importance I = (w*w)*D_j in fp32, keep the N largest
+// (equal scores: lower column wins), C = Wbar (.) M, one mask byte per group.
+template <int M>
+__global__ __launch_bounds__(256) void init_nm_kernel(const float *__restrict__ Wbar, const float *__restrict__ D,
+                                                      int64_t d_in, int64_t ngroups, int N, float *__restrict__ C,
+                                                      uint8_t *__restrict__ mask) {
+    int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (g >= ngroups) return;
+    int64_t gpr = d_in / M, col0 = (g % gpr) * M, base = (g / gpr) * d_in + col0;
+    float w[M], sc[M];
+#pragma unroll
+    for (int p = 0; p < M; ++p) {
+        w[p] = Wbar[base + p];
+        float ww = __fmul_rn(w[p], w[p]);
+        sc[p] = __fmul_rn(ww, D[col0 + p]);
+    }
+    uint32_t bits = 0;
+#pragma unroll
+    for (int p = 0; p < M; ++p) {
+        int rank = 0;
+#pragma unroll
+        for (int q = 0; q < M; ++q) rank += (sc[q] > sc[p] || (sc[q] == sc[p] && q < p)) ? 1 : 0;
+        bool keep = rank < N;
+        bits |= keep ? (1u << p) : 0u;
+        C[base + p] = keep ? w[p] : 0.f;
+    }
+    mask[g] = (uint8_t)bits;
+}
+
+void launch_init_nm(const float *Wbar, const float *D, int64_t d_out, int64_t d_in, int N, int M, float *C,
+                    uint8_t *mask, hipStream_t s) {
+    int64_t ngroups = d_out * (d_in / M);
+    dim3 grid((unsigned)((ngroups + 255) / 256));
+    switch (M) {
+    case 2: hipLaunchKernelGGL(init_nm_kernel<2>, grid, dim3(256), 0, s, Wbar, D, d_in, ngroups, N, C, mask); break;
+    case 4: hipLaunchKernelGGL(init_nm_kernel<4>, grid, dim3(256), 0, s, Wbar, D, d_in, ngroups, N, C, mask); break;
+    case 8: hipLaunchKernelGGL(init_nm_kernel<8>, grid, dim3(256), 0, s, Wbar, D, d_in, ngroups, N, C, mask); break;
+    default: break;
+    }
+}
+
+__global__ __launch_bounds__(256) void diag_kernel(const float *__restrict__ H, int64_t d_in, int64_t ldh,
+                                                   float *__restrict__ D) {
+    int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (j < d_in) D[j] = H[j * ldh + j];
+}
+
+void launch_diag(const float *H, int64_t d_in, int64_t ldh, float *D, hipStream_t s) {
+    hipLaunchKernelGGL(diag_kernel, dim3((unsigned)((d_in + 255) / 256)), dim3(256), 0, s, H, d_in, ldh, D);
+}
+
+// ------------------------------------------------------------------------------------------------
+// wrapper update (Alg. 2):  X^(k) <- X^(k) - grad^(k) / beta,  beta = 2 * sum of the per-block
+// summands of Eq. 9 / Eq. 10, grad^(k) = sum of the nsplit partials the chain kernel left.
+// A zero beta leaves X unchanged.  Workgroup (k, q) updates slice q of block k; every workgroup
+// re-derives beta in the same fixed order.  Workgroup (0,0) also writes the loss of the previous
+// iterate (sum of the block losses) when trace_out is given.
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void update_wrapper_kernel(float *__restrict__ X, int b, const float *__restrict__ gpart,
+                                                             int nsplit, const float *__restrict__ beta_part,
+                                                             int nblocks, const float *__restrict__ loss_part,
+                                                             double *__restrict__ trace_out) {
+    __shared__ double red[4];
+    const int tid = threadIdx.x, k = blockIdx.x, q = blockIdx.y, nq = gridDim.y;
+    double s = 0.0;
+    for (int e = tid; e < nblocks; e += 256) s += (double)beta_part[e];
+    const double beta = 2.0 * block_sum_256(s, red);
+    if (trace_out != nullptr && k == 0 && q == 0) {
+        double l = 0.0;
+        for (int e = tid; e < nblocks; e += 256) l += (double)loss_part[e];
+        l = block_sum_256(l, red);
+        if (tid == 0) *trace_out = l;
+    }
+    if (!(beta > 0.0)) return;
+    const int bb = b * b, per = (bb + nq - 1) / nq, e0 = q * per, e1 = min(bb, e0 + per);
+    for (int e = e0 + tid; e < e1; e += 256) {
+        double g = 0.0;
+        for (int c = 0; c < nsplit; ++c) g += (double)gpart[((int64_t)k * nsplit + c) * bb + e];
+        float *x = X + (int64_t)k * bb + e;
+        *x = (float)((double)*x - g / beta);
+    }
+}
+
+void launch_update_wrapper(float *A, int nblk, int b, const float *gpart, int nsplit, const float *beta_part,
+                           int nblocks, const float *loss_part, double *trace_out, hipStream_t s) {
+    int nq = (b * b + 2047) / 2048;
+    hipLaunchKernelGGL(update_wrapper_kernel, dim3(nblk, nq), dim3(256), 0, s, A, b, gpart, nsplit, beta_part, nblocks,
+                       loss_part, trace_out);
+}
+
+// beta_W' = 2 ||A^T A||_F ||B D B^T||_F (Eq. 11) from the per-block squared norms -> scalars[2]
+__global__ __launch_bounds__(256) void finalize_betaW_kernel(const float *__restrict__ fro2A, int nbi,
+                                                             const float *__restrict__ fro2K, int nbj,
+                                                             double *__restrict__ scalars) {
+    __shared__ double red[4];
+    double a = 0.0, k = 0.0;
+    for (int e = threadIdx.x; e < nbi; e += 256) a += (double)fro2A[e];
+    for (int e = threadIdx.x; e < nbj; e += 256) k += (double)fro2K[e];
+    a = block_sum_256(a, red);
+    k = block_sum_256(k, red);
+    if (threadIdx.x == 0) scalars[2] = 2.0 * sqrt(a) * sqrt(k);
+}
+
+void launch_finalize_betaW(const float *fro2A, int nbi, const float *fro2K, int nbj, double *scalars, hipStream_t s) {
+    hipLaunchKernelGGL(finalize_betaW_kernel, dim3(1), dim3(256), 0, s, fro2A, nbi, fro2K, nbj, scalars);
+}
+
+__global__ __launch_bounds__(256) void sum_to_double_kernel(const float *__restrict__ part, int n,
+                                                            double *__restrict__ out) {
+    __shared__ double red[4];
+    double a = 0.0;
+    for (int e = threadIdx.x; e < n; e += 256) a += (double)part[e];
+    a = block_sum_256(a, red);
+    if (threadIdx.x == 0) *out = a;
+}
+
+void launch_sum_to_double(const float *part, int n, double *out, hipStream_t s) {
+    hipLaunchKernelGGL(sum_to_double_kernel, dim3(1), dim3(256), 0, s, part, n, out);
+}
+
+// ------------------------------------------------------------------------------------------------
+// sparse-core step (Alg. 3).  One workgroup per block (i,j).
+//  1. Scores: g_kappa = L1 (or L2) norm of the M entries of group kappa = i'*(b/M)+k of the
+//     unmasked core gradient (Sec. 3.3.2); draw one group by an exponential race on a counter
+//     hash: key = -ln(u)/g, smallest key wins, ties to the lower kappa.
+//  2. For every N-subset s of the group (lexicographic order), Eq. 7:
+//        gain_s = q_s^T (K_ss)^+ q_s / ||a||^2,   w_s = (K_ss)^+ q_s / ||a||^2   (Eq. 8)
+//     with K = B^j D^j B^jT (so K_ss = B' D B'^T), a = column i' of A^i, and
+//        q_p = B_p D DeltaW^T a = (A^T (R D) B^T)[i', p] + ||a||^2 sum_p' K[p,p'] c_p'
+//     because DeltaW = R + a (c^T B_group) (Eq. 6); the first term is -Gfull/2, already in HBM.
+//  3. Largest gain wins (first in order on ties); write weights and mask byte.
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint64_t mix64(uint64_t z) {
+    z ^= z >> 30; z *= 0xBF58476D1CE4E5B9ULL;
+    z ^= z >> 27; z *= 0x94D049BB133111EBULL;
+    z ^= z >> 31;
+    return z;
+}
+
+__device__ __forceinline__ float hash_uniform(uint64_t seed, uint64_t ctr) {
+    uint64_t z = mix64(seed + 0x9E3779B97F4A7C15ULL * ctr);
+    return (float)((z >> 40) + 1ULL) * (1.0f / 16777216.0f);
+}
+
+// w = G^+ q for a symmetric PSD N x N matrix (Moore-Penrose, eigenvalues <= 1e-12 * max dropped),
+// returns q^T G^+ q.  Cyclic Jacobi, fully unrolled so everything stays in registers.
+template <int N> __device__ double pinv_solve(double (&G)[N][N], const double (&q)[N], double (&w)[N]) {
+    if (N == 1) {
+        w[0] = G[0][0] > 0.0 ? q[0] / G[0][0] : 0.0;
+        return w[0] * q[0];
+    }
+    double V[N][N];
+#pragma unroll
+    for (int p = 0; p < N; ++p)
+#pragma unroll
+        for (int r = 0; r < N; ++r) V[p][r] = (p == r) ? 1.0 : 0.0;
+    for (int sweep = 0; sweep < 60; ++sweep) {
+        double off = 0.0, dg = 0.0;
+#pragma unroll
+        for (int p = 0; p < N; ++p)
+#pragma unroll
+            for (int r = 0; r < N; ++r) {
+                if (p != r) off += G[p][r] * G[p][r];
+                else dg += G[p][r] * G[p][r];
+            }
+        if (off <= 1e-30 * dg || off == 0.0) break;
+#pragma unroll
+        for (int p = 0; p < N - 1; ++p)
+#pragma unroll
+            for (int r = p + 1; r < N; ++r) {
+                double apq = G[p][r];
+                if (apq != 0.0) {
+                    double theta = (G[r][r] - G[p][p]) / (2.0 * apq);
+                    double t = (theta >= 0.0 ? 1.0 : -1.0) / (fabs(theta) + sqrt(theta * theta + 1.0));
+                    double c = 1.0 / sqrt(t * t + 1.0), s = t * c;
+#pragma unroll
+                    for (int k = 0; k < N; ++k) {
+                        double gkp = G[k][p], gkq = G[k][r];
+                        G[k][p] = c * gkp - s * gkq;
+                        G[k][r] = s * gkp + c * gkq;
+                    }
+#pragma unroll
+                    for (int k = 0; k < N; ++k) {
+                        double gpk = G[p][k], gqk = G[r][k];
+                        G[p][k] = c * gpk - s * gqk;
+                        G[r][k] = s * gpk + c * gqk;
+                    }
+#pragma unroll
+                    for (int k = 0; k < N; ++k) {
+                        double vkp = V[k][p], vkq = V[k][r];
+                        V[k][p] = c * vkp - s * vkq;
+                        V[k][r] = s * vkp + c * vkq;
+                    }
+                }
+            }
+    }
+    double lmax = 0.0;
+#pragma unroll
+    for (int k = 0; k < N; ++k) lmax = fmax(lmax, G[k][k]);
+#pragma unroll
+    for (int p = 0; p < N; ++p) w[p] = 0.0;
+    double gain = 0.0;
+    if (lmax <= 0.0) return 0.0;
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+        double lam = G[k][k];
+        if (lam > 1e-12 * lmax) {
+            double proj = 0.0;
+#pragma unroll
+            for (int p = 0; p < N; ++p) proj += V[p][k] * q[p];
+#pragma unroll
+            for (int p = 0; p < N; ++p) w[p] += V[p][k] * proj / lam;
+            gain += proj * proj / lam;
+        }
+    }
+    return gain;
+}
+
+constexpr int binom(int n, int k) { return (k == 0 || k == n) ? 1 : binom(n - 1, k - 1) + binom(n - 1, k); }
+
+template <int N, int M>
+__global__ __launch_bounds__(256) void sparse_step_kernel(const float *__restrict__ G, float *__restrict__ C,
+                                                          uint8_t *__restrict__ mask, const float *__restrict__ K,
+                                                          const float *__restrict__ colnorm2, int64_t d_in, int b,
+                                                          int nbj, int nblocks, int selection, uint64_t seed,
+                                                          int64_t t, const float *__restrict__ loss_part,
+                                                          double *__restrict__ loss_cont_out) {
+    constexpr int NPAT = binom(M, N);
+    __shared__ float s_key[4];
+    __shared__ int s_kap[4];
+    __shared__ float s_gain[NPAT];
+    __shared__ double s_q[M], s_K[M][M], s_red[4];
+    __shared__ int s_best;
+    const int tid = threadIdx.x, blk = blockIdx.x, i = blk / nbj, j = blk % nbj;
+    const int gpr = b / M, gpb = b * gpr;
+
+    if (blk == 0 && loss_cont_out != nullptr) { // loss after the continuous step = sum of block losses
+        double l = 0.0;
+        for (int e = tid; e < nblocks; e += 256) l += (double)loss_part[e];
+        l = block_sum_256(l, s_red);
+        if (tid == 0) *loss_cont_out = l;
+    }
+
+    // ---- 1. selection ----
+    float best_key = INFINITY;
+    int best_kap = 0x7fffffff;
+    const float *Gij = G + (int64_t)i * b * d_in + (int64_t)j * b;
+    for (int kap = tid; kap < gpb; kap += 256) {
+        int ip = kap / gpr, k = kap % gpr;
+        const float *g = Gij + (int64_t)ip * d_in + k * M;
+        float v[M];
+        if (M == 4) {
+            float4 x = *reinterpret_cast<const float4 *>(g);
+            v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
+        } else {
+#pragma unroll
+            for (int p = 0; p < M; ++p) v[p] = g[p];
+        }
+        float score;
+        if (selection == 2) {
+            double a = 0.0;
+#pragma unroll
+            for (int p = 0; p < M; ++p) a += (double)v[p] * (double)v[p];
+            score = (float)sqrt(a);
+        } else {
+            double a = 0.0;
+#pragma unroll
+            for (int p = 0; p < M; ++p) a += (double)fabsf(v[p]);
+            score = (float)a;
+        }
+        if (selection == 3) score = 1.f;
+        float key;
+        if (selection == 1) {
+            key = -score;
+        } else {
+            uint64_t ctr = (uint64_t)(((int64_t)t * nblocks + blk) * gpb + kap) + 1ULL;
+            float u = hash_uniform(seed, ctr);
+            key = score > 0.f ? (-logf(u)) / score : INFINITY;
+        }
+        if (key < best_key) { best_key = key; best_kap = kap; }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        float ok = __shfl_xor(best_key, off, 64);
+        int oa = __shfl_xor(best_kap, off, 64);
+        if (ok < best_key || (ok == best_key && oa < best_kap)) { best_key = ok; best_kap = oa; }
+    }
+    if ((tid & 63) == 0) { s_key[tid >> 6] = best_key; s_kap[tid >> 6] = best_kap; }
+    __syncthreads();
+    best_key = s_key[0]; best_kap = s_kap[0];
+#pragma unroll
+    for (int w = 1; w < 4; ++w)
+        if (s_key[w] < best_key || (s_key[w] == best_key && s_kap[w] < best_kap)) { best_key = s_key[w]; best_kap = s_kap[w]; }
+    if (best_kap == 0x7fffffff) best_kap = 0; // every key was +inf (or NaN): the first group
+    const int ip = best_kap / gpr, k0 = (best_kap % gpr) * M;
+    const double a2 = (double)colnorm2[(int64_t)i * b + ip];
+    if (!(a2 > 0.0)) return; // a = 0: the block cannot move (uniform across the workgroup)
+
+    // ---- 2. operands of Eq. 7 for the drawn group ----
+    float *crow = C + ((int64_t)i * b + ip) * d_in + (int64_t)j * b + k0;
+    const float *Kj = K + (int64_t)j * b * b;
+    if (tid < M * M) s_K[tid / M][tid % M] = (double)Kj[(k0 + tid / M) * b + k0 + tid % M];
+    __syncthreads();
+    if (tid < M) {
+        double acc = 0.0;
+#pragma unroll
+        for (int pp = 0; pp < M; ++pp) acc += s_K[tid][pp] * (double)crow[pp];
+        s_q[tid] = -0.5 * (double)Gij[(int64_t)ip * d_in + k0 + tid] + a2 * acc;
+    }
+    __syncthreads();
+
+    // ---- 3. sweep: thread x handles the x-th subset in lexicographic order ----
+    int sub[N];
+    double w[N];
+    if (tid < NPAT) {
+#pragma unroll
+        for (int p = 0; p < N; ++p) sub[p] = p;
+        for (int step = 0; step < tid; ++step) { // advance to the tid-th subset
+            int p = N - 1;
+            while (p >= 0 && sub[p] == M - N + p) --p;
+            ++sub[p];
+            for (int r = p + 1; r < N; ++r) sub[r] = sub[r - 1] + 1;
+        }
+        double Gs[N][N], qs[N];
+#pragma unroll
+        for (int x = 0; x < N; ++x) {
+            qs[x] = s_q[sub[x]];
+#pragma unroll
+            for (int y = 0; y < N; ++y) Gs[x][y] = s_K[sub[x]][sub[y]];
+        }
+        double gain = pinv_solve<N>(Gs, qs, w) / a2;
+        s_gain[tid] = (float)gain;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int bi = 0;
+        float bg = s_gain[0];
+        for (int x = 1; x < NPAT; ++x)
+            if (s_gain[x] > bg) { bg = s_gain[x]; bi = x; }
+        s_best = bi;
+    }
+    __syncthreads();
+    if (tid == s_best) {
+        float out[M];
+        uint32_t bits = 0;
+#pragma unroll
+        for (int p = 0; p < M; ++p) out[p] = 0.f;
+#pragma unroll
+        for (int x = 0; x < N; ++x) {
+            out[sub[x]] = (float)(w[x] / a2);
+            bits |= 1u << sub[x];
+        }
+#pragma unroll
+        for (int p = 0; p < M; ++p) crow[p] = out[p];
+        mask[((int64_t)i * b + ip) * (d_in / M) + ((int64_t)j * b + k0) / M] = (uint8_t)bits;
+    }
+}
+
+void launch_sparse_step(const Dims &d, const float *G, float *C, uint8_t *mask, const float *K,
+                        const float *colnorm2, int N, int M, int selection, uint64_t seed, int64_t t,
+                        const float *loss_part, double *loss_cont_out, hipStream_t s) {
+#define ARMOR_SPARSE_CASE(n, m)                                                                               \
+    if (N == n && M == m) {                                                                                   \
+        hipLaunchKernelGGL((sparse_step_kernel<n, m>), dim3(d.nblocks), dim3(256), 0, s, G, C, mask, K, colnorm2, \
+                           d.d_in, d.b, d.nbj, d.nblocks, selection, seed, t, loss_part, loss_cont_out);     \
+        return;                                                                                               \
+    }
+    ARMOR_SPARSE_CASE(1, 2)
+    ARMOR_SPARSE_CASE(1, 4) ARMOR_SPARSE_CASE(2, 4) ARMOR_SPARSE_CASE(3, 4)
+    ARMOR_SPARSE_CASE(1, 8) ARMOR_SPARSE_CASE(2, 8) ARMOR_SPARSE_CASE(3, 8) ARMOR_SPARSE_CASE(4, 8)
+    ARMOR_SPARSE_CASE(5, 8) ARMOR_SPARSE_CASE(6, 8) ARMOR_SPARSE_CASE(7, 8)
+#undef ARMOR_SPARSE_CASE
+}
+
+// ------------------------------------------------------------------------------------------------
+// epilogue: denormalisation (Sec. 3.2) and compressed N:M storage
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void denormalize_kernel(float *__restrict__ A, float *__restrict__ B,
+                                                          const float *__restrict__ r1, const float *__restrict__ r2,
+                                                          int64_t na, int64_t nb, int b) {
+    int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e < na) {
+        int64_t blk = e / ((int64_t)b * b), p = (e / b) % b;
+        A[e] = (float)((double)A[e] * (double)r2[blk * b + p]);
+    } else if (e < na + nb) {
+        int64_t f = e - na, blk = f / ((int64_t)b * b), q = f % b;
+        B[f] = (float)((double)B[f] * (double)r1[blk * b + q]);
+    }
+}
+
+void launch_denormalize(float *A, float *B, const float *r1, const float *r2, int64_t d_out, int64_t d_in, int b,
+                        hipStream_t s) {
+    int64_t na = d_out * b, nb = d_in * b;
+    hipLaunchKernelGGL(denormalize_kernel, dim3((unsigned)((na + nb + 255) / 256)), dim3(256), 0, s, A, B, r1, r2, na,
+                       nb, b);
+}
+
+__device__ __forceinline__ uint16_t float_to_bf16_rne(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40); // NaN stays NaN
+    return (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+}
+
+// one thread per group: the N kept values in increasing column order + their in-group columns
+template <int M, bool BF16>
+__global__ __launch_bounds__(256) void pack_nm_kernel(const float *__restrict__ S, const uint8_t *__restrict__ mask,
+                                                      int64_t ngroups, int N, void *__restrict__ values,
+                                                      uint8_t *__restrict__ meta) {
+    int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (g >= ngroups) return;
+    uint32_t bits = mask[g];
+    int x = 0;
+#pragma unroll
+    for (int p = 0; p < M; ++p) {
+        if (((bits >> p) & 1u) && x < N) {
+            float v = S[g * M + p];
+            if (BF16) reinterpret_cast<uint16_t *>(values)[g * N + x] = float_to_bf16_rne(v);
+            else      reinterpret_cast<float *>(values)[g * N + x] = v;
+            meta[g * N + x] = (uint8_t)p;
+            ++x;
+        }
+    }
+}
+
+void launch_pack_nm(const float *S, const uint8_t *mask, int64_t d_out, int64_t d_in, int N, int M, void *values,
+                    int bf16, uint8_t *meta, hipStream_t s) {
+    int64_t ngroups = d_out * (d_in / M);
+    dim3 grid((unsigned)((ngroups + 255) / 256));
+#define ARMOR_PACK_CASE(m)                                                                                         \
+    if (M == m) {                                                                                                  \
+        if (bf16) hipLaunchKernelGGL((pack_nm_kernel<m, true>), grid, dim3(256), 0, s, S, mask, ngroups, N, values, meta);  \
+        else      hipLaunchKernelGGL((pack_nm_kernel<m, false>), grid, dim3(256), 0, s, S, mask, ngroups, N, values, meta); \
+        return;                                                                                                    \
+    }
+    ARMOR_PACK_CASE(2) ARMOR_PACK_CASE(4) ARMOR_PACK_CASE(8)
+#undef ARMOR_PACK_CASE
+}
+
+} // namespace armor

@@ -1,0 +1,209 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element, on the
+same seeded inputs.  Bars (stated by the benchmark spec): N:M structure bit-exact, mask agreement >= 99.9 %,
+A / S / B relative Frobenius error <= 1e-3, losses within 0.5 % relative."""
+import sys
+
+import numpy as np
+import pytest
+
+from paper_2510_05528_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def armor():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    import paper_2510_05528_amd as armor
+    armor.load_library()      # raises if the HIP library is not built: no fallback
+    return armor
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch
+    return torch
+
+
+def dev(torch, a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+def relfro(a, b):
+    return float(np.linalg.norm(a.astype(np.float64) - b.astype(np.float64)) / max(np.linalg.norm(b.astype(np.float64)), 1e-300))
+
+
+def make_layer(d_out, d_in, n_tokens, seed, act_outliers=(0.0, 1.0)):
+    W = synth.make_weight(d_out, d_in, seed=seed)
+    X = synth.make_calibration(n_tokens, d_in, seed=seed, outlier_frac=act_outliers[0], outlier_scale=act_outliers[1])
+    return W, X
+
+
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("n,d_in,bf16", [(512, 256, False), (70, 96, False), (333, 384, True), (16, 32, False), (1, 64, True)])
+def test_gram(armor, torch, orc, n, d_in, bf16):
+    say("gram", n, d_in, bf16)
+    X = synth.make_calibration(n, d_in, seed=4, outlier_frac=0.02, outlier_scale=20.0)
+    if bf16:
+        bits = synth.to_bf16_bits(X)
+        Xd = dev(torch, bits.view(np.int16)).view(torch.bfloat16)
+        Xh = synth.bf16_bits_to_f32(bits)
+    else:
+        Xd, Xh = dev(torch, X), X
+    H = armor.gram(Xd)
+    ref = orc.gram(Xh)
+    got = H.cpu().numpy()
+    scale = np.sqrt(np.outer(np.diag(ref), np.diag(ref)))     # |H_ab| <= sqrt(H_aa H_bb)
+    assert np.max(np.abs(got - ref) / scale) < 2e-5
+    np.testing.assert_array_equal(got, got.T)
+    # streaming: two chunks accumulate to the same matrix
+    if n >= 16:
+        h = n // 2
+        H2 = armor.gram(Xd[:h])
+        armor.gram(Xd[h:], H=H2, accumulate=True)
+        assert np.max(np.abs(H2.cpu().numpy() - ref) / scale) < 2e-5
+    D = armor.gram_diag(H).cpu().numpy()
+    np.testing.assert_array_equal(D, np.diag(got))
+
+
+@pytest.mark.parametrize("d_out,d_in,bf16", [(256, 256, False), (96, 160, False), (384, 640, True)])
+def test_normalize(armor, torch, orc, d_out, d_in, bf16):
+    say("normalize", d_out, d_in, bf16)
+    W = synth.make_weight(d_out, d_in, seed=2)
+    W[:, 5] = 0
+    if bf16:
+        bits = synth.to_bf16_bits(W)
+        Wd = dev(torch, bits.view(np.int16)).view(torch.bfloat16)
+        Wh = synth.bf16_bits_to_f32(bits)
+    else:
+        Wd, Wh = dev(torch, W), W
+    Wbar, r1, r2 = armor.normalize(Wd)
+    eb, e1, e2 = orc.normalize(Wh)
+    np.testing.assert_allclose(r1.cpu().numpy(), e1, rtol=2e-6)
+    np.testing.assert_allclose(r2.cpu().numpy(), e2, rtol=2e-6)
+    np.testing.assert_allclose(Wbar.cpu().numpy(), eb, rtol=3e-6, atol=1e-12)
+
+
+@pytest.mark.parametrize("d_out,d_in,b", [(64, 96, 32), (128, 192, 64), (256, 384, 128)])
+def test_proxy_loss(armor, torch, orc, d_out, d_in, b):
+    say("proxy_loss", d_out, d_in, b)
+    rng = np.random.default_rng(1)
+    Wbar = rng.standard_normal((d_out, d_in)).astype(np.float32)
+    D = (rng.random(d_in) * 5 + 0.1).astype(np.float32)
+    A = (np.eye(b)[None] + 0.1 * rng.standard_normal((d_out // b, b, b))).astype(np.float32)
+    B = (np.eye(b)[None] + 0.1 * rng.standard_normal((d_in // b, b, b))).astype(np.float32)
+    C, _ = orc.init_nm(Wbar, D, 2, 4)
+    got = armor.proxy_loss(dev(torch, Wbar), dev(torch, A), dev(torch, C), dev(torch, B), dev(torch, D)).item()
+    assert got == pytest.approx(orc.proxy_loss(Wbar, A, C, B, D), rel=2e-5)
+    # identity wrappers (NULL) = plain masked loss; H given as a full matrix uses only its diagonal
+    H = np.diag(D) + 0.01
+    np.fill_diagonal(H, D)
+    got = armor.proxy_loss(dev(torch, Wbar), None, dev(torch, C), None, dev(torch, H.astype(np.float32)), d_block=b).item()
+    expect = ((Wbar.astype(np.float64) - C) ** 2 * D[None, :]).sum()
+    assert got == pytest.approx(expect, rel=2e-5)
+
+
+def check_factorization(armor, torch, orc, W, D, b, N, M, n_iters, seed, selection=0, tag=""):
+    d_out, d_in = W.shape
+    say("factorize", tag, d_out, d_in, "b", b, N, M, "iters", n_iters, "seed", seed, "sel", selection)
+    out = armor.factorize_layer(dev(torch, W), dev(torch, D), b, N, M, n_iters, seed=seed, selection=selection,
+                                want_cont_trace=True)
+    torch.cuda.synchronize()
+    ref = orc.factorize_layer(W, D, b, N, M, n_iters, seed=seed, selection=selection)
+    tr = out["loss_trace"].cpu().numpy()
+    ct = out["loss_cont_trace"].cpu().numpy()
+    mask = armor.unpack_mask(out["mask_bits"].cpu().numpy(), M)
+    S = out["S"].cpu().numpy()
+    # bit-exact structure
+    assert np.all(mask.reshape(d_out, d_in // M, M).sum(-1) == N)
+    assert np.all(S[mask == 0] == 0)
+    agree = float((mask == ref["mask"]).mean())
+    eA, eB, eS = relfro(out["A"].cpu().numpy(), ref["A"]), relfro(out["B"].cpu().numpy(), ref["B"]), relfro(S, ref["C"])
+    say("   mask agreement %.6f  relF A %.2e B %.2e S %.2e  loss %.6g->%.6g (oracle %.6g)" %
+        (agree, eA, eB, eS, tr[0], tr[-1], ref["loss_trace"][-1]))
+    assert agree >= 0.999
+    assert eA <= 1e-3 and eB <= 1e-3 and eS <= 1e-3
+    np.testing.assert_allclose(tr, ref["loss_trace"], rtol=5e-3)
+    if n_iters > 0:
+        np.testing.assert_allclose(ct, ref["loss_cont_trace"], rtol=5e-3)
+        tol = 1e-6 * tr[0]
+        assert np.all(np.diff(tr) <= tol)                       # Thm. 1 on the device trace
+        assert np.all(ct <= tr[:-1] + tol) and np.all(tr[1:] <= ct + tol)
+    np.testing.assert_allclose(out["r1"].cpu().numpy(), ref["r1"], rtol=2e-6)
+    np.testing.assert_allclose(out["r2"].cpu().numpy(), ref["r2"], rtol=2e-6)
+    # the reported final loss is the loss of the returned factors (oracle evaluates them)
+    Wbar = ref["Wbar"]
+    assert tr[-1] == pytest.approx(orc.proxy_loss(Wbar, out["A"].cpu().numpy(), S, out["B"].cpu().numpy(), D), rel=1e-4)
+    return out, ref
+
+
+def test_factorize_config1(armor, torch, orc):
+    """BASELINE config 1: 256x256 fp32, 512 calibration tokens, 2:4, d_block 32, 20 iterations, seed 0."""
+    W, X = make_layer(256, 256, 512, seed=0)
+    H = armor.gram(dev(torch, X))
+    D = armor.gram_diag(H).cpu().numpy()
+    np.testing.assert_allclose(D, np.diag(orc.gram(X)), rtol=1e-5)
+    check_factorization(armor, torch, orc, W, D, 32, 2, 4, 20, seed=0, tag="cfg1")
+
+
+@pytest.mark.parametrize("d_out,d_in,b,iters", [(128, 192, 64, 6), (384, 640, 128, 5), (640, 256, 128, 4), (96, 160, 32, 8)])
+def test_factorize_shapes(armor, torch, orc, d_out, d_in, b, iters):
+    """Several blocks in both directions, non-square block grids, every chain instantiation."""
+    W, X = make_layer(d_out, d_in, 300, seed=3, act_outliers=(0.01, 20.0))
+    D = np.diag(orc.gram(X)).astype(np.float32)
+    check_factorization(armor, torch, orc, W, D, b, 2, 4, iters, seed=11)
+
+
+@pytest.mark.parametrize("sel", [1, 2, 3])
+def test_factorize_selection_modes(armor, torch, orc, sel):
+    W, X = make_layer(128, 128, 200, seed=5)
+    D = np.diag(orc.gram(X)).astype(np.float32)
+    check_factorization(armor, torch, orc, W, D, 32, 2, 4, 6, seed=2, selection=sel)
+
+
+@pytest.mark.parametrize("N,M", [(4, 8), (1, 4), (3, 4), (5, 8), (6, 8), (1, 2)])
+def test_factorize_general_nm(armor, torch, orc, N, M):
+    W, X = make_layer(128, 192, 200, seed=6)
+    D = np.diag(orc.gram(X)).astype(np.float32)
+    check_factorization(armor, torch, orc, W, D, 64, N, M, 5, seed=4)
+
+
+def test_factorize_zero_iterations_is_plain_nm_pruning(armor, torch, orc):
+    W, X = make_layer(64, 128, 100, seed=7)
+    D = np.diag(orc.gram(X)).astype(np.float32)
+    out, ref = check_factorization(armor, torch, orc, W, D, 32, 2, 4, 0, seed=0)
+    np.testing.assert_array_equal(armor.unpack_mask(out["mask_bits"].cpu().numpy(), 4), ref["mask"])
+    np.testing.assert_array_equal(out["A"].cpu().numpy(), ref["A"])
+
+
+def test_factorize_is_deterministic(armor, torch):
+    W, X = make_layer(128, 128, 100, seed=8)
+    D = (X.astype(np.float64) ** 2).sum(0).astype(np.float32)
+    a = armor.factorize_layer(dev(torch, W), dev(torch, D), 64, 2, 4, 5, seed=1)
+    b = armor.factorize_layer(dev(torch, W), dev(torch, D), 64, 2, 4, 5, seed=1)
+    for k in ("A", "S", "B", "mask_bits", "loss_trace"):
+        assert torch.equal(a[k], b[k]), k
+
+
+def test_denormalize_and_pack(armor, torch, orc):
+    W, X = make_layer(128, 128, 100, seed=9)
+    D = (X.astype(np.float64) ** 2).sum(0).astype(np.float32)
+    plain = armor.factorize_layer(dev(torch, W), dev(torch, D), 32, 2, 4, 3, seed=1)
+    folded = armor.factorize_layer(dev(torch, W), dev(torch, D), 32, 2, 4, 3, seed=1, denormalize=True)
+    A2, B2 = orc.denormalize(plain["A"].cpu().numpy(), plain["B"].cpu().numpy(), plain["r1"].cpu().numpy(),
+                             plain["r2"].cpu().numpy())
+    np.testing.assert_allclose(folded["A"].cpu().numpy(), A2, rtol=1e-6)
+    np.testing.assert_allclose(folded["B"].cpu().numpy(), B2, rtol=1e-6)
+    vals, meta = armor.pack_nm(plain["S"], plain["mask_bits"], 2, 4)
+    mask = armor.unpack_mask(plain["mask_bits"].cpu().numpy(), 4)
+    ev, ei = orc.pack_nm(plain["S"].cpu().numpy(), mask, 2, 4)
+    np.testing.assert_array_equal(vals.cpu().numpy(), ev)
+    np.testing.assert_array_equal(meta.cpu().numpy(), ei)
+    vb, _ = armor.pack_nm(plain["S"], plain["mask_bits"], 2, 4, bf16=True)
+    np.testing.assert_array_equal(vb.view(torch.int16).cpu().numpy().view(np.uint16), synth.to_bf16_bits(ev))

@@ -1,0 +1,61 @@
+"""The C-ABI library loads on a machine without a GPU and exports every symbol the header declares."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "armor.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(armor_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported():
+    from paper_2510_05528_amd import binding
+    lib = binding.load_library()
+    names = _declared_symbols()
+    assert set(names) == set(binding.EXPORTED), (names, binding.EXPORTED)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_status_strings_and_host_side_validation():
+    """Argument errors are detected on the host before any launch (no GPU needed)."""
+    from paper_2510_05528_amd import binding
+    lib = binding.load_library()
+    assert lib.armor_status_string(0) == b"ok"
+    assert lib.armor_status_string(2) == b"bad shape"
+    # workspace queries are pure host arithmetic; bad shapes give 0
+    assert lib.armor_factorize_workspace_bytes(256, 256, 32, 2, 4, None) > 2 * 256 * 256 * 4
+    assert lib.armor_factorize_workspace_bytes(256, 250, 32, 2, 4, None) == 0      # b does not divide d_in
+    assert lib.armor_factorize_workspace_bytes(256, 256, 48, 2, 4, None) == 0      # unsupported block size
+    assert lib.armor_factorize_workspace_bytes(256, 256, 32, 4, 4, None) == 0      # N >= M
+    assert lib.armor_factorize_workspace_bytes(256, 256, 32, 2, 3, None) == 0      # M not 2/4/8
+    assert lib.armor_proxy_loss_workspace_bytes(128, 128, 64) > 0
+    # null pointers / bad shapes are rejected without touching the device
+    assert lib.armor_gram(None, 0, 16, 64, 64, None, 64, 0, None) == 1
+    buf = (ctypes.c_float * 64)()
+    p = ctypes.cast(buf, ctypes.c_void_p)
+    assert lib.armor_gram(p, 0, 16, 48, 48, p, 48, 0, None) == 2                   # d_in not a multiple of 32
+    assert lib.armor_gram(p, 7, 16, 64, 64, p, 64, 0, None) == 3                   # dtype
+    assert lib.armor_factorize_layer(None, 0, None, 0, 64, 64, 32, 2, 4, 1, None, None, None, None, None, None, None,
+                                     None, None, None, 0, None) == 1
+    assert lib.armor_factorize_layer(p, 0, p, 0, 64, 64, 32, 2, 4, 1, None, p, p, p, None, None, None, None, None, None,
+                                     0, None) == 4                                # no workspace
+    assert lib.armor_factorize_layer(p, 0, p, 0, 64, 60, 32, 2, 4, 1, None, p, p, p, None, None, None, None, None, p,
+                                     1 << 30, None) == 2
+    assert lib.armor_pack_nm(p, p, 4, 16, 2, 5, p, 0, p, None) == 2
+
+
+def test_product_package_does_not_import_the_oracle():
+    """The product path must not route through the CPU oracle."""
+    pkg = os.path.join(ROOT, "paper_2510_05528_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                src = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in src and "from oracle" not in src and "liboracle" not in src, f
