@@ -1,0 +1,151 @@
+#!/usr/bin/env python3
+"""Benchmark of the ARMOR per-layer factorization hot path on one MI355X.
+
+One "step" is one pass of the whole hot path over one synthetic layer: Gram of the calibration
+activations (armor_gram + armor_gram_diag), then armor_factorize_layer (normalise, initialise,
+n_iters BCD iterations, final loss) and armor_pack_nm, with W and X already resident in HBM.
+Workload (default): the Llama-7B-shaped attention projection of the baseline configs:
+W 4096x4096 bf16, X 262144x4096 bf16, H fp32, 2:4 along d_in, d_block 128, 50 BCD iterations.
+
+Prints ONE JSON line.  `value` = BCD iterations per second over the whole step.
+`roofline` is for the chain kernel family that takes the most time, from HIP events the library
+records around each of its launches during the timed steps.  `cpu_baseline` times the CPU oracle
+(test infrastructure, never tuned) on a bounded sample of the same layer.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+WORKLOADS = {
+    # name: (d_out, d_in, n_tokens, d_block, N, M, n_iters, w_bf16, x_bf16, act_outlier_frac, act_outlier_scale)
+    "llama7b_attn_4096x4096_b128_2:4_50it": (4096, 4096, 262144, 128, 2, 4, 50, True, True, 0.005, 20.0),
+    "small_256x256_b32_2:4_20it": (256, 256, 512, 32, 2, 4, 20, False, False, 0.0, 1.0),
+}
+DEFAULT = "llama7b_attn_4096x4096_b128_2:4_50it"
+
+FP32_MFMA_PEAK = 157.3e12  # MI355X dense fp32 matrix peak, FLOP/s
+
+
+def chain_algorithmic_flops(kind, d_out, d_in, b, N, M):
+    """Algorithmic flops of one launch of a chain kernel: 2*P*b per dense b-deep block product,
+    N/M of that where the N:M core itself is an operand, half for the symmetric Gram-type product."""
+    P = d_out * d_in
+    unit = 2.0 * P * b
+    sparse = unit * N / M
+    if kind in ("phase_A", "phase_B"):
+        return sparse + unit + unit + 0.5 * unit
+    return sparse + 3 * unit  # phase_GW / phase_GS
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default=DEFAULT, choices=sorted(WORKLOADS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-iters", type=int, default=2)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (every box has one GPU); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2510_05528_amd as armor
+    from paper_2510_05528_amd import synth
+
+    armor.load_library()
+    dev = torch.device("cuda:0")
+    d_out, d_in, n_tok, b, N, M, n_iters, w_bf16, x_bf16, ofrac, oscale = WORKLOADS[args.workload]
+
+    # ---- synthetic inputs, resident in HBM before any timed region ----
+    W = synth.torch_weight(d_out, d_in, 0, dev, bf16=w_bf16)
+    X = synth.torch_calibration(n_tok, d_in, 0, dev, outlier_frac=ofrac, outlier_scale=oscale,
+                                dtype=torch.bfloat16 if x_bf16 else torch.float32)
+    H = torch.empty((d_in, d_in), device=dev, dtype=torch.float32)
+    ws = torch.empty(armor.factorize_workspace_bytes(d_out, d_in, b, N, M), device=dev, dtype=torch.uint8)
+    torch.cuda.synchronize()
+
+    def step():
+        armor.gram(X, H=H)
+        D = armor.gram_diag(H)
+        out = armor.factorize_layer(W, D, b, N, M, n_iters, seed=0, ws=ws)
+        vals, meta = armor.pack_nm(out["S"], out["mask_bits"], N, M, bf16=True)
+        return out, D, vals, meta
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    armor.profile_enable(True)
+    armor.profile_read()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        out, D, vals, meta = step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    prof = armor.profile_read()
+    armor.profile_enable(False)
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    value = n_iters / (ms_per_step * 1e-3)
+
+    # ---- roofline of the dominant chain kernel, from the library's HIP events ----
+    kernels = {}
+    for k, (ms, cnt) in prof.items():
+        if cnt > 0:
+            kernels[k] = {"launches": int(cnt), "avg_ms": ms / cnt, "total_ms_per_step": ms / args.steps}
+    chain = {k: v for k, v in kernels.items() if k.startswith("phase_")}
+    dom = max(chain, key=lambda k: chain[k]["total_ms_per_step"])
+    flops = chain_algorithmic_flops(dom, d_out, d_in, b, N, M)
+    achieved = flops / (chain[dom]["avg_ms"] * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": FP32_MFMA_PEAK / 1e12,
+                "unit": "TFLOP/s", "frac": achieved / (FP32_MFMA_PEAK / 1e12), "traffic": None,
+                "algorithmic_flops_per_launch": flops, "avg_launch_ms": chain[dom]["avg_ms"]}
+    for k in chain:
+        kernels[k]["tflops_algorithmic"] = chain_algorithmic_flops(k, d_out, d_in, b, N, M) / (chain[k]["avg_ms"] * 1e-3) / 1e12
+    if "gram" in kernels:
+        kernels["gram"]["tflops_algorithmic"] = n_tok * d_in * (d_in + 1) / (kernels["gram"]["avg_ms"] * 1e-3) / 1e12
+
+    trace = out["loss_trace"].cpu().numpy()
+    result = {
+        "metric": "BCD iterations/sec per layer", "value": value, "unit": "iterations/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": args.workload, "d_out": d_out, "d_in": d_in, "n_tokens": n_tok, "d_block": b,
+                   "pattern": "%d:%d" % (N, M), "n_iters": n_iters,
+                   "step": "gram + gram_diag + factorize_layer + pack_nm"},
+        "s_per_layer": ms_per_step * 1e-3,
+        "loss_first_last": [float(trace[0]), float(trace[-1])],
+        "roofline": roofline,
+        "kernels": kernels,
+    }
+
+    # ---- CPU oracle on a bounded sample of the same layer (reported baseline, not the target) ----
+    if not args.no_cpu_baseline:
+        import oracle
+        oracle.build()
+        Wh = W.float().cpu().numpy()
+        Dh = D.cpu().numpy()
+        cpu_iters = args.cpu_iters if d_out * d_in > 1 << 20 else n_iters
+        c0 = time.perf_counter()
+        ref = oracle.factorize_layer(Wh, Dh, b, N, M, cpu_iters, seed=0)
+        c1 = time.perf_counter()
+        cores = int(os.environ.get("OMP_NUM_THREADS", "0")) or (os.cpu_count() or 1)
+        result["cpu_baseline"] = {
+            "value": cpu_iters / (c1 - c0), "unit": "iterations/s", "cores": cores, "kind": "oracle",
+            "sample": "%d of %d BCD iterations of the same %dx%d layer (normalise + init + iterations + per-iteration "
+                      "loss; Gram excluded, D taken from the GPU Gram); %.1f s wall" % (cpu_iters, n_iters, d_out, d_in, c1 - c0),
+        }
+        # cheap cross-check of the timed run against the oracle's first iterations
+        result["cpu_baseline"]["loss_trace_rel_err_first_iters"] = float(
+            np.max(np.abs(trace[:cpu_iters + 1] - ref["loss_trace"]) / ref["loss_trace"]))
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -59,6 +59,25 @@ const char *armor_status_string(armor_status s);
 int armor_last_hip_error(void);
 
 /*
+ * Optional per-kernel timing (host-side; not thread-safe; off by default).  While enabled, the
+ * library brackets each instrumented kernel launch with two HIP events recorded on the caller's
+ * stream (events are host resources created on first use and kept; no device memory).
+ * armor_profile_read() waits for the recorded events, returns per kind the summed elapsed
+ * milliseconds and the number of launches into two HOST arrays of ARMOR_PROF_KINDS entries, and
+ * resets the record.  Kinds: the Gram kernel (Sec. 2), the three gradient chains of Alg. 2
+ * (A step, B step, W' step), the core-gradient chain feeding Alg. 3, and the Alg. 3 kernel.
+ */
+#define ARMOR_PROF_GRAM 0
+#define ARMOR_PROF_PHASE_A 1
+#define ARMOR_PROF_PHASE_B 2
+#define ARMOR_PROF_PHASE_GW 3
+#define ARMOR_PROF_PHASE_GS 4
+#define ARMOR_PROF_SPARSE 5
+#define ARMOR_PROF_KINDS 6
+armor_status armor_profile_enable(int on);
+armor_status armor_profile_read(double *ms_total /*host [ARMOR_PROF_KINDS]*/, int64_t *launches /*host*/);
+
+/*
  * Gram matrix of the calibration activations (Sec. 2; the loss of Eq. 2 uses its diagonal).
  *   X   [n_tokens x d_in], leading dimension ldx (elements), fp32 or bf16; one token per row
  *       (this is the paper's X^T).

@@ -9,7 +9,9 @@ _LIB_PATH = os.path.join(_HERE, "libarmor.so")
 
 ARMOR_F32, ARMOR_BF16 = 0, 1
 
-EXPORTED = ["armor_status_string", "armor_last_hip_error", "armor_gram", "armor_gram_diag",
+PROF_KINDS = ["gram", "phase_A", "phase_B", "phase_GW", "phase_GS", "sparse_step"]
+
+EXPORTED = ["armor_status_string", "armor_last_hip_error", "armor_profile_enable", "armor_profile_read", "armor_gram", "armor_gram_diag",
             "armor_normalize_workspace_bytes", "armor_normalize", "armor_proxy_loss_workspace_bytes",
             "armor_proxy_loss", "armor_factorize_workspace_bytes", "armor_factorize_layer", "armor_pack_nm"]
 
@@ -38,6 +40,8 @@ def load_library():
     lib.armor_status_string.restype = ctypes.c_char_p
     lib.armor_status_string.argtypes = [_int]
     lib.armor_last_hip_error.restype = _int
+    lib.armor_profile_enable.argtypes = [_int]
+    lib.armor_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
     lib.armor_gram.argtypes = [_vp, _int, _i64, _i64, _i64, _vp, _i64, _int, _vp]
     lib.armor_gram_diag.argtypes = [_vp, _i64, _i64, _vp, _vp]
     lib.armor_normalize_workspace_bytes.restype = _sz
@@ -92,6 +96,18 @@ def _dev_f32(t, name):
     if not (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()):
         raise ArmorError("%s must be a contiguous fp32 device tensor" % name)
     return t
+
+
+def profile_enable(on=True):
+    _check(load_library().armor_profile_enable(int(on)))
+
+
+def profile_read():
+    """{kind: (total_ms, launches)} since the last read; waits for the recorded events."""
+    ms = (ctypes.c_double * len(PROF_KINDS))()
+    cnt = (ctypes.c_int64 * len(PROF_KINDS))()
+    _check(load_library().armor_profile_read(ms, cnt))
+    return {k: (ms[i], cnt[i]) for i, k in enumerate(PROF_KINDS)}
 
 
 def gram(X, H=None, accumulate=False):

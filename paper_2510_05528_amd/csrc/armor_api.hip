@@ -7,6 +7,7 @@
 
 #include <algorithm>
 #include <cstring>
+#include <vector>
 
 using namespace armor;
 
@@ -22,6 +23,44 @@ armor_status check_hip() {
     }
     return ARMOR_OK;
 }
+
+// Optional per-kernel timing with HIP events recorded on the caller's stream around each
+// instrumented launch (host-side bookkeeping only; off by default).
+struct Profiler {
+    bool on = false;
+    std::vector<hipEvent_t> pool;
+    size_t used = 0;
+    struct Rec { int kind; size_t e0; };
+    std::vector<Rec> recs;
+    static constexpr size_t kMaxEvents = 1 << 15;
+    int begin(int kind, hipStream_t s) {
+        if (!on) return -1;
+        if (used + 2 > pool.size()) {
+            if (pool.size() + 2 > kMaxEvents) return -1;
+            hipEvent_t a, b;
+            if (hipEventCreate(&a) != hipSuccess) return -1;
+            if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); return -1; }
+            pool.push_back(a);
+            pool.push_back(b);
+        }
+        size_t e0 = used;
+        used += 2;
+        (void)hipEventRecord(pool[e0], s);
+        recs.push_back({kind, e0});
+        return (int)e0;
+    }
+    void end(int tok, hipStream_t s) {
+        if (tok >= 0) (void)hipEventRecord(pool[(size_t)tok + 1], s);
+    }
+};
+Profiler g_prof;
+
+struct ProfScope {
+    int tok;
+    hipStream_t s;
+    ProfScope(int kind, hipStream_t st) : tok(g_prof.begin(kind, st)), s(st) {}
+    ~ProfScope() { g_prof.end(tok, s); }
+};
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -152,13 +191,41 @@ const char *armor_status_string(armor_status s) {
 
 int armor_last_hip_error(void) { return g_last_hip_error; }
 
+armor_status armor_profile_enable(int on) {
+    g_prof.on = on != 0;
+    return ARMOR_OK;
+}
+
+armor_status armor_profile_read(double *ms_total, int64_t *launches) {
+    if (!ms_total || !launches) return ARMOR_ERR_NULL;
+    for (int k = 0; k < ARMOR_PROF_KINDS; ++k) { ms_total[k] = 0.0; launches[k] = 0; }
+    armor_status st = ARMOR_OK;
+    for (const auto &r : g_prof.recs) {
+        float ms = 0.f;
+        if (hipEventSynchronize(g_prof.pool[r.e0 + 1]) != hipSuccess ||
+            hipEventElapsedTime(&ms, g_prof.pool[r.e0], g_prof.pool[r.e0 + 1]) != hipSuccess) {
+            st = check_hip();
+            if (st == ARMOR_OK) st = ARMOR_ERR_DEVICE;
+            break;
+        }
+        ms_total[r.kind] += (double)ms;
+        launches[r.kind] += 1;
+    }
+    g_prof.recs.clear();
+    g_prof.used = 0;
+    return st;
+}
+
 armor_status armor_gram(const void *X, armor_dtype x_dtype, int64_t n_tokens, int64_t d_in, int64_t ldx, float *H,
                         int64_t ldh, int accumulate, void *hip_stream) {
     if (!H || (!X && n_tokens > 0)) return ARMOR_ERR_NULL;
     if (x_dtype != ARMOR_F32 && x_dtype != ARMOR_BF16) return ARMOR_ERR_DTYPE;
     if (d_in <= 0 || d_in % 32 != 0 || n_tokens < 0 || ldx < d_in || ldh < d_in) return ARMOR_ERR_SHAPE;
     if (!aligned16(X) || !aligned16(H)) return ARMOR_ERR_ALIGN;
-    launch_gram(X, x_dtype == ARMOR_BF16, n_tokens, d_in, ldx, H, ldh, accumulate, (hipStream_t)hip_stream);
+    {
+        ProfScope ps(ARMOR_PROF_GRAM, (hipStream_t)hip_stream);
+        launch_gram(X, x_dtype == ARMOR_BF16, n_tokens, d_in, ldx, H, ldh, accumulate, (hipStream_t)hip_stream);
+    }
     return check_hip();
 }
 
@@ -223,7 +290,7 @@ armor_status armor_proxy_loss(const float *Wbar, const float *A, const float *S,
     else if (hipMemcpyAsync(D, H, sizeof(float) * d_in, hipMemcpyDeviceToDevice, s) != hipSuccess) return check_hip();
     if (!A) { launch_init_identity(Ai, d.nbi, d.b, s); A = Ai; }
     if (!B) { launch_init_identity(Bi, d.nbj, d.b, s); B = Bi; }
-    launch_phase_A(d, Wbar, S, A, B, D, 1, nullptr, nullptr, loss_part, true, s);
+    launch_phase_A(d, Wbar, S, A, B, D, choose_nsplit(d.nbi, d.nbj, d.b), nullptr, nullptr, loss_part, true, s);
     launch_sum_to_double(loss_part, d.nblocks, loss_out, s);
     return check_hip();
 }
@@ -286,25 +353,40 @@ armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const flo
 
     for (int t = 1; t <= n_iters; ++t) {
         // continuous step (Alg. 2), each gradient at the already-updated parameters (Lemma 1)
-        launch_phase_A(d, f.Wbar, S, A, B, f.D, f.nsA, f.gpart, f.beta_part, f.loss_part, false, s);
+        {
+            ProfScope ps(ARMOR_PROF_PHASE_A, s);
+            launch_phase_A(d, f.Wbar, S, A, B, f.D, f.nsA, f.gpart, f.beta_part, f.loss_part, false, s);
+        }
         launch_update_wrapper(A, d.nbi, d.b, f.gpart, f.nsA, f.beta_part, d.nblocks, f.loss_part,
                               loss_trace ? loss_trace + (t - 1) : nullptr, s);
-        launch_phase_B(d, f.Wbar, S, A, B, f.D, f.nsB, f.gpart, f.beta_part, s);
+        {
+            ProfScope ps(ARMOR_PROF_PHASE_B, s);
+            launch_phase_B(d, f.Wbar, S, A, B, f.D, f.nsB, f.gpart, f.beta_part, s);
+        }
         launch_update_wrapper(B, d.nbj, d.b, f.gpart, f.nsB, f.beta_part, d.nblocks, nullptr, nullptr, s);
         launch_wrapper_grams(d, A, B, f.D, f.colnorm2, f.fro2A, f.K, f.fro2K, s);
         launch_finalize_betaW(f.fro2A, d.nbi, f.fro2K, d.nbj, f.scalars, s);
-        launch_phase_G(d, f.Wbar, S, A, B, f.D, mask, mask_group, f.scalars, nullptr, nullptr, 0, s);
+        {
+            ProfScope ps(ARMOR_PROF_PHASE_GW, s);
+            launch_phase_G(d, f.Wbar, S, A, B, f.D, mask, mask_group, f.scalars, nullptr, nullptr, 0, s);
+        }
         // sparse-core step (Alg. 3)
-        launch_phase_G(d, f.Wbar, S, A, B, f.D, mask, mask_group, f.scalars, f.G, f.loss_part2, 1, s);
-        launch_sparse_step(d, f.G, S, mask, f.K, f.colnorm2, N, M, o.selection, o.seed, t, f.loss_part2,
-                           loss_cont_trace ? loss_cont_trace + (t - 1) : nullptr, s);
+        {
+            ProfScope ps(ARMOR_PROF_PHASE_GS, s);
+            launch_phase_G(d, f.Wbar, S, A, B, f.D, mask, mask_group, f.scalars, f.G, f.loss_part2, 1, s);
+        }
+        {
+            ProfScope ps(ARMOR_PROF_SPARSE, s);
+            launch_sparse_step(d, f.G, S, mask, f.K, f.colnorm2, N, M, o.selection, o.seed, t, f.loss_part2,
+                               loss_cont_trace ? loss_cont_trace + (t - 1) : nullptr, s);
+        }
         if ((t & 15) == 0) {
             st = check_hip();
             if (st != ARMOR_OK) return st;
         }
     }
     if (loss_trace) {
-        launch_phase_A(d, f.Wbar, S, A, B, f.D, 1, nullptr, nullptr, f.loss_part, true, s);
+        launch_phase_A(d, f.Wbar, S, A, B, f.D, f.nsA, nullptr, nullptr, f.loss_part, true, s);
         launch_sum_to_double(f.loss_part, d.nblocks, loss_trace + n_iters, s);
     }
     if (o.denormalize) launch_denormalize(A, B, r1p, r2p, d_out, d_in, d.b, s);
