@@ -50,6 +50,9 @@ def main():
     ap.add_argument("--workload", default=DEFAULT, choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-iters", type=int, default=2)
+    ap.add_argument("--tokens", type=int, default=0,
+                    help="override the number of calibration tokens (profiling runs only; the reported "
+                         "workload name gets a suffix)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (every box has one GPU); use --gpus 1", file=sys.stderr)
@@ -63,6 +66,10 @@ def main():
     armor.load_library()
     dev = torch.device("cuda:0")
     d_out, d_in, n_tok, b, N, M, n_iters, w_bf16, x_bf16, ofrac, oscale = WORKLOADS[args.workload]
+    workload_name = args.workload
+    if args.tokens > 0:
+        n_tok = args.tokens
+        workload_name += "_tokens%d" % n_tok
 
     # ---- synthetic inputs, resident in HBM before any timed region ----
     W = synth.torch_weight(d_out, d_in, 0, dev, bf16=w_bf16)
@@ -116,7 +123,7 @@ def main():
         "metric": "BCD iterations/sec per layer", "value": value, "unit": "iterations/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": args.workload, "d_out": d_out, "d_in": d_in, "n_tokens": n_tok, "d_block": b,
+        "config": {"workload": workload_name, "d_out": d_out, "d_in": d_in, "n_tokens": n_tok, "d_block": b,
                    "pattern": "%d:%d" % (N, M), "n_iters": n_iters,
                    "step": "gram + gram_diag + factorize_layer + pack_nm"},
         "s_per_layer": ms_per_step * 1e-3,

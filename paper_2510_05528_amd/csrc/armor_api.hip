@@ -77,11 +77,14 @@ int device_cus() {
     return cus;
 }
 
+// Workgroups of a chain kernel that are resident at once (one per CU at b = 128: LDS-bound).
+int chain_slots(int b) { return device_cus() * (b >= 128 ? 1 : 2); }
+
 // How many chunks to split the accumulation axis of a gradient phase into: workgroup (k, c) walks
 // `chunk` blocks and leaves one b x b partial.  Cost model in units of one block's chain time:
 // rounds * (chunk + a small charge for writing the partial); finer splits balance the tail.
 int choose_nsplit(int n_outer, int n_inner, int b) {
-    const int slots = device_cus() * (b >= 128 ? 1 : 2);
+    const int slots = chain_slots(b);
     int best = 1;
     double best_cost = 1e300;
     for (int ns = 1; ns <= n_inner && ns <= chain_max_nsplit(); ++ns) {
@@ -368,12 +371,12 @@ armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const flo
         launch_finalize_betaW(f.fro2A, d.nbi, f.fro2K, d.nbj, f.scalars, s);
         {
             ProfScope ps(ARMOR_PROF_PHASE_GW, s);
-            launch_phase_G(d, f.Wbar, S, A, B, f.D, mask, mask_group, f.scalars, nullptr, nullptr, 0, s);
+            launch_phase_G(d, f.Wbar, S, A, B, f.D, mask, mask_group, f.scalars, nullptr, nullptr, 0, chain_slots(d.b), s);
         }
         // sparse-core step (Alg. 3)
         {
             ProfScope ps(ARMOR_PROF_PHASE_GS, s);
-            launch_phase_G(d, f.Wbar, S, A, B, f.D, mask, mask_group, f.scalars, f.G, f.loss_part2, 1, s);
+            launch_phase_G(d, f.Wbar, S, A, B, f.D, mask, mask_group, f.scalars, f.G, f.loss_part2, 1, chain_slots(d.b), s);
         }
         {
             ProfScope ps(ARMOR_PROF_SPARSE, s);

@@ -26,7 +26,7 @@ void launch_phase_B(const Dims &d, const float *Wbar, const float *C, const floa
 //   mode 1 (Alg. 3 input): Gout = -2 G (unmasked), block loss to loss_part.
 void launch_phase_G(const Dims &d, const float *Wbar, float *C, const float *A, const float *B, const float *D,
                     const uint8_t *mask, int mask_group, const double *scalars, float *Gout, float *loss_part,
-                    int mode, hipStream_t s);
+                    int mode, int grid_cap, hipStream_t s);
 // Per wrapper block: ||A^i[:,p]||^2, ||A^iT A^i||_F^2; K^j = B^j D^j B^jT, ||K^j||_F^2.
 void launch_wrapper_grams(const Dims &d, const float *A, const float *B, const float *D, float *colnorm2,
                           float *fro2A, float *K, float *fro2K, hipStream_t s);

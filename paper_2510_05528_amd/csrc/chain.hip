@@ -11,14 +11,28 @@
 // read per block; intermediates never leave the CU.
 #include "armor_internal.h"
 
+#include <algorithm>
+
 namespace armor {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
+// Hides a per-lane offset from loop-invariant code motion: without it the compiler hoists every
+// unrolled address of the epilogues out of the block loop and keeps hundreds of them live across
+// the matrix products (spilling accumulators), instead of re-deriving each with one add.
+__device__ __forceinline__ int opaque(int x) {
+    asm volatile("" : "+v"(x));
+    return x;
+}
+
 template <int B> struct Cfg;
 template <> struct Cfg<32>  { static constexpr int WM = 1, WN = 1, TM = 1, TN = 1; };
 template <> struct Cfg<64>  { static constexpr int WM = 2, WN = 2, TM = 1, TN = 1; };
-template <> struct Cfg<128> { static constexpr int WM = 2, WN = 4, TM = 2, TN = 1; };
+#ifndef ARMOR_CFG128
+#define ARMOR_CFG128 2, 4, 2, 1
+#endif
+template <int WM_, int WN_, int TM_, int TN_> struct CfgT { static constexpr int WM = WM_, WN = WN_, TM = TM_, TN = TN_; };
+template <> struct Cfg<128> : CfgT<ARMOR_CFG128> {};
 
 template <int B> struct Chain {
     static constexpr int WM = Cfg<B>::WM, WN = Cfg<B>::WN, TM = Cfg<B>::TM, TN = Cfg<B>::TN;
@@ -50,60 +64,115 @@ template <int B> struct Chain {
         }
         __device__ int row(int tm, int r) const { return wm0 + tm * 32 + (r >> 2) * 8 + kh * 4 + (r & 3); }
         __device__ int col(int tn) const { return wn0 + tn * 32 + l32; }
+        // 32-bit element offset of accumulator element (tm,tn,r) in a row-major matrix of leading
+        // dimension ld, split into a per-lane part and a wave-uniform part so that the address is
+        // "uniform base + one VGPR" and nothing 64-bit per element stays live.
+        __device__ int lane_off(int ld) const { return (wm0 + kh * 4) * ld + wn0 + l32; }
+        __device__ static int unif_off(int tm, int tn, int r, int ld) {
+            return (tm * 32 + (r >> 2) * 8 + (r & 3)) * ld + tn * 32;
+        }
     };
 
-    // global (row-major, leading dimension ld) -> LDS tile
-    __device__ static void load_tile(float *T, const float *__restrict__ g, int64_t ld, int tid) {
-        constexpr int V = B * B / 4, PER = V / NT;
-        static_assert(V % NT == 0, "tile load must divide evenly");
-        float4 v[PER];
+    // global (row-major, leading dimension ld) -> registers -> LDS tile, in two halves so that the
+    // global loads of the next operand can stay in flight underneath a matrix product.
+    static constexpr int PER = B * B / 4 / NT;
+    static_assert((B * B / 4) % NT == 0, "tile load must divide evenly");
+    struct TileRegs { float4 v[PER]; };
+
+    // Loader lane mapping: every group of 32 lanes covers 4 rows x 8 float4 columns, so a global
+    // load instruction still reads whole 128-byte lines while the four scalar LDS writes of a
+    // float4 (stride 16 B across lanes of a row, +1 bank per row with the odd pitch) hit 32
+    // different banks.
+    static constexpr int ROWS_PER_IT = NT / (B / 4); // tile rows covered by one pass of the workgroup
+    __device__ static __forceinline__ int loader_row(int tid) { return ((tid >> 5) / (B / 32)) * 4 + ((tid & 31) >> 3); }
+    __device__ static __forceinline__ int loader_c4(int tid) { return ((tid >> 5) % (B / 32)) * 8 + (tid & 7); }
+
+    __device__ static __forceinline__ void gload_tile(TileRegs &t, const float *__restrict__ g, int ld, int tid) {
+        const int off0 = opaque(loader_row(tid) * ld + loader_c4(tid) * 4);
+#pragma unroll
+        for (int it = 0; it < PER; ++it)
+            t.v[it] = *reinterpret_cast<const float4 *>(g + (off0 + it * ROWS_PER_IT * ld));
+    }
+
+    __device__ static __forceinline__ void lstore_tile(float *T, const TileRegs &t, int tid) {
+        float *d0 = T + opaque(loader_row(tid) * P + loader_c4(tid) * 4);
 #pragma unroll
         for (int it = 0; it < PER; ++it) {
-            int idx = it * NT + tid, r = idx / (B / 4), c4 = idx % (B / 4);
-            v[it] = *reinterpret_cast<const float4 *>(g + (int64_t)r * ld + c4 * 4);
-        }
-#pragma unroll
-        for (int it = 0; it < PER; ++it) {
-            int idx = it * NT + tid, r = idx / (B / 4), c4 = idx % (B / 4);
-            float *t = T + r * P + c4 * 4;
-            t[0] = v[it].x; t[1] = v[it].y; t[2] = v[it].z; t[3] = v[it].w;
+            float *d = d0 + it * ROWS_PER_IT * P;
+            d[0] = t.v[it].x; d[1] = t.v[it].y; d[2] = t.v[it].z; d[3] = t.v[it].w;
         }
     }
 
+    __device__ static void load_tile(float *T, const float *__restrict__ g, int ld, int tid) {
+        TileRegs t;
+        gload_tile(t, g, ld, tid);
+        lstore_tile(T, t, tid);
+    }
+
     __device__ static void store_acc(float *T, const Acc &acc, const Pos &p) {
+        float *d0 = T + opaque(p.lane_off(P));
 #pragma unroll
         for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
             for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) T[p.row(tm, r) * P + p.col(tn)] = acc.v[tm][tn][r];
+                for (int r = 0; r < 16; ++r) d0[Pos::unif_off(tm, tn, r, P)] = acc.v[tm][tn][r];
     }
 
     // acc += op(L) * op(R) over the b inner indices.  op(L)(m,k) = LT ? L[k][m] : L[m][k];
     // op(R)(k,n) = RT ? R[n][k] : R[k][n];  SCALE multiplies op(L)(m,k) by Dk[k].
+    // Operands are fetched one group of G k-steps ahead of the MFMAs that consume them (two
+    // register sets), so LDS latency is covered by the wave's own matrix work.
+    static constexpr int G = 2;
+    struct Frag { float a[G][TM], b[G][TN]; };
+
     template <bool LT, bool RT, bool SCALE>
-    __device__ static void mma(Acc &acc, const float *__restrict__ L, const float *__restrict__ R,
-                               const float *__restrict__ Dk, const Pos &p) {
-#pragma unroll 8
-        for (int k = 0; k < B; k += 2) {
-            int kk = k + p.kh;
-            float a[TM], b[TN];
+    __device__ static __forceinline__ void fetch(Frag &f, int k0, const float *__restrict__ L,
+                                                 const float *__restrict__ R, const float *__restrict__ Dk,
+                                                 const Pos &p) {
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            int kk = k0 + 2 * g + p.kh;
 #pragma unroll
             for (int tm = 0; tm < TM; ++tm) {
                 int m = p.wm0 + tm * 32 + p.l32;
-                a[tm] = LT ? L[kk * P + m] : L[m * P + kk];
-                if (SCALE) a[tm] *= Dk[kk];
+                f.a[g][tm] = LT ? L[kk * P + m] : L[m * P + kk];
             }
 #pragma unroll
             for (int tn = 0; tn < TN; ++tn) {
                 int n = p.wn0 + tn * 32 + p.l32;
-                b[tn] = RT ? R[n * P + kk] : R[kk * P + n];
+                f.b[g][tn] = RT ? R[n * P + kk] : R[kk * P + n];
             }
+            if (SCALE) {
+                float dk = Dk[kk];
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm) f.a[g][tm] *= dk;
+            }
+        }
+    }
+
+    __device__ static __forceinline__ void issue(Acc &acc, const Frag &f) {
+#pragma unroll
+        for (int g = 0; g < G; ++g)
 #pragma unroll
             for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
                 for (int tn = 0; tn < TN; ++tn)
-                    acc.v[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[tm], b[tn], acc.v[tm][tn], 0, 0, 0);
+                    acc.v[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a[g][tm], f.b[g][tn], acc.v[tm][tn], 0, 0, 0);
+    }
+
+    template <bool LT, bool RT, bool SCALE>
+    __device__ static void mma(Acc &acc, const float *__restrict__ L, const float *__restrict__ R,
+                               const float *__restrict__ Dk, const Pos &p) {
+        static_assert(B % (4 * G) == 0, "two groups per trip");
+        Frag f0, f1;
+        fetch<LT, RT, SCALE>(f0, 0, L, R, Dk, p);
+#pragma unroll 1
+        for (int k = 0; k < B; k += 4 * G) {
+            fetch<LT, RT, SCALE>(f1, k + 2 * G, L, R, Dk, p);
+            issue(acc, f0);
+            if (k + 4 * G < B) fetch<LT, RT, SCALE>(f0, k + 4 * G, L, R, Dk, p);
+            issue(acc, f1);
         }
     }
 
@@ -129,6 +198,15 @@ template <int B> struct Smem {
 };
 
 // ------------------------------------------------------------------------------------------------
+// Scheduling common to the three chains below: every global read of an operand tile is issued
+// into registers one matrix product before the tile is needed and only written to LDS after that
+// product (gload_tile ... mma ... lstore_tile), Wbar is read straight into the accumulator layout
+// underneath the product whose result it is subtracted from, and the first tiles of the next block
+// are requested underneath the last product of the current one.  With one workgroup per CU (two
+// 66 KB tiles fill LDS) this is what keeps HBM/L2 latency off the critical path.
+// ------------------------------------------------------------------------------------------------
+
+// ------------------------------------------------------------------------------------------------
 // A-phase (Alg. 2, first gradient step; App. D.1).  Workgroup (i, c) walks the column blocks j of
 // its chunk c and accumulates  sum_j (R D)^(i,j) S^(i,j)T  in registers.
 //   gpart[(i*nsplit + c)][b][b] = -2 * that sum          (partial grad_A^(i))
@@ -145,30 +223,34 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_A_kernel(
     __shared__ Smem<B> sm;
     const int tid = threadIdx.x;
     const typename CH::Pos p(tid);
+    const int ldw = (int)d_in, woff = p.lane_off(ldw);
     const int i = blockIdx.x / nsplit, c = blockIdx.x % nsplit;
     const int chunk = (nbj + nsplit - 1) / nsplit;
     const int j0 = c * chunk, j1 = min(nbj, j0 + chunk);
     typename CH::Acc gacc, acc;
+    typename CH::TileRegs t0;
     gacc.zero();
+    if (j0 < j1) CH::gload_tile(t0, C + (int64_t)i * B * d_in + (int64_t)j0 * B, ldw, tid);
     for (int j = j0; j < j1; ++j) {
-        const float *Cij = C + (int64_t)i * B * d_in + (int64_t)j * B;
         const float *Wij = Wbar + (int64_t)i * B * d_in + (int64_t)j * B;
-        CH::load_tile(sm.X, Cij, d_in, tid);
-        CH::load_tile(sm.Y, Bw + (int64_t)j * B * B, B, tid);
+        CH::lstore_tile(sm.X, t0, tid);
+        CH::gload_tile(t0, Bw + (int64_t)j * B * B, B, tid);
         if (tid < B) sm.Dl[tid] = D[(int64_t)j * B + tid];
+        CH::lstore_tile(sm.Y, t0, tid);
         __syncthreads();
+        CH::gload_tile(t0, A + (int64_t)i * B * B, B, tid);
         acc.zero();
         CH::template mma<false, false, false>(acc, sm.X, sm.Y, nullptr, p); // S = C B
         __syncthreads();
         CH::store_acc(sm.X, acc, p);
-        CH::load_tile(sm.Y, A + (int64_t)i * B * B, B, tid);
+        CH::lstore_tile(sm.Y, t0, tid);
         float wb[CH::TM][CH::TN][16];
 #pragma unroll
         for (int tm = 0; tm < CH::TM; ++tm)
 #pragma unroll
             for (int tn = 0; tn < CH::TN; ++tn)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) wb[tm][tn][r] = Wij[(int64_t)p.row(tm, r) * d_in + p.col(tn)];
+                for (int r = 0; r < 16; ++r) wb[tm][tn][r] = Wij[opaque(woff) + CH::Pos::unif_off(tm, tn, r, ldw)];
         __syncthreads();
         acc.zero();
         CH::template mma<false, false, false>(acc, sm.Y, sm.X, nullptr, p); // What = A S
@@ -190,6 +272,10 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_A_kernel(
         if (!LOSS_ONLY) {
             CH::store_acc(sm.Y, acc, p); // R D
             __syncthreads();
+        }
+        if (j + 1 < j1) // next block's core tile (HBM), underneath the remaining products
+            CH::gload_tile(t0, C + (int64_t)i * B * d_in + (int64_t)(j + 1) * B, ldw, tid);
+        if (!LOSS_ONLY) {
             CH::template mma<false, true, false>(gacc, sm.Y, sm.X, nullptr, p); // += (R D) S^T
             acc.zero();
             CH::template mma<false, true, true>(acc, sm.X, sm.X, sm.Dl, p); // (S D) S^T
@@ -212,7 +298,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_A_kernel(
 #pragma unroll
             for (int tn = 0; tn < CH::TN; ++tn)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) gp[p.row(tm, r) * B + p.col(tn)] = -2.f * gacc.v[tm][tn][r];
+                for (int r = 0; r < 16; ++r) gp[opaque(p.lane_off(B)) + CH::Pos::unif_off(tm, tn, r, B)] = -2.f * gacc.v[tm][tn][r];
     }
 }
 
@@ -231,34 +317,38 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_B_kernel(
     __shared__ Smem<B> sm;
     const int tid = threadIdx.x;
     const typename CH::Pos p(tid);
+    const int ldw = (int)d_in, woff = p.lane_off(ldw);
     const int j = blockIdx.x / nsplit, c = blockIdx.x % nsplit;
     const int chunk = (nbi + nsplit - 1) / nsplit;
     const int i0 = c * chunk, i1 = min(nbi, i0 + chunk);
     typename CH::Acc gacc, acc;
+    typename CH::TileRegs t0;
     gacc.zero();
+    if (i0 < i1) CH::gload_tile(t0, C + (int64_t)i0 * B * d_in + (int64_t)j * B, ldw, tid);
     if (tid < B) sm.Dl[tid] = D[(int64_t)j * B + tid];
     __syncthreads();
     float dn2 = 0.f;
     if (tid == 0)
         for (int q = 0; q < B; ++q) dn2 += sm.Dl[q] * sm.Dl[q];
     for (int i = i0; i < i1; ++i) {
-        const float *Cij = C + (int64_t)i * B * d_in + (int64_t)j * B;
         const float *Wij = Wbar + (int64_t)i * B * d_in + (int64_t)j * B;
-        CH::load_tile(sm.X, Cij, d_in, tid);
-        CH::load_tile(sm.Y, A + (int64_t)i * B * B, B, tid);
+        CH::lstore_tile(sm.X, t0, tid);
+        CH::gload_tile(t0, A + (int64_t)i * B * B, B, tid);
+        CH::lstore_tile(sm.Y, t0, tid);
         __syncthreads();
+        CH::gload_tile(t0, Bw + (int64_t)j * B * B, B, tid);
         acc.zero();
         CH::template mma<false, false, false>(acc, sm.Y, sm.X, nullptr, p); // S' = A C
         __syncthreads();
         CH::store_acc(sm.X, acc, p);
-        CH::load_tile(sm.Y, Bw + (int64_t)j * B * B, B, tid);
+        CH::lstore_tile(sm.Y, t0, tid);
         float wb[CH::TM][CH::TN][16];
 #pragma unroll
         for (int tm = 0; tm < CH::TM; ++tm)
 #pragma unroll
             for (int tn = 0; tn < CH::TN; ++tn)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) wb[tm][tn][r] = Wij[(int64_t)p.row(tm, r) * d_in + p.col(tn)];
+                for (int r = 0; r < 16; ++r) wb[tm][tn][r] = Wij[opaque(woff) + CH::Pos::unif_off(tm, tn, r, ldw)];
         __syncthreads();
         acc.zero();
         CH::template mma<false, false, false>(acc, sm.X, sm.Y, nullptr, p); // What = S' B
@@ -273,6 +363,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_B_kernel(
         __syncthreads();
         CH::store_acc(sm.Y, acc, p); // R D
         __syncthreads();
+        if (i + 1 < i1) CH::gload_tile(t0, C + (int64_t)(i + 1) * B * d_in + (int64_t)j * B, ldw, tid);
         CH::template mma<true, false, false>(gacc, sm.X, sm.Y, nullptr, p); // += S'^T (R D)
         acc.zero();
         CH::template mma<true, false, false>(acc, sm.X, sm.X, nullptr, p); // S'^T S'
@@ -293,7 +384,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_B_kernel(
 #pragma unroll
         for (int tn = 0; tn < CH::TN; ++tn)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) gp[p.row(tm, r) * B + p.col(tn)] = -2.f * gacc.v[tm][tn][r];
+            for (int r = 0; r < 16; ++r) gp[opaque(p.lane_off(B)) + CH::Pos::unif_off(tm, tn, r, B)] = -2.f * gacc.v[tm][tn][r];
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -301,96 +392,133 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_B_kernel(
 //   MODE 0: the W' step of Alg. 2:  C <- C + (2 / beta_W') G on kept entries (Eq. 11).
 //   MODE 1: Gout = -2 G for every entry (the selection scores and the q-vectors of Alg. 3 read
 //           it), and the block loss (= loss after the continuous step) to loss_part.
-// One workgroup per block; blocks are independent.
+// Blocks are independent; workgroup w handles blocks w, w + gridDim.x, ...
 // ------------------------------------------------------------------------------------------------
 template <int B, int MODE>
 __global__ __launch_bounds__(Chain<B>::NT) void phase_G_kernel(
     const float *__restrict__ Wbar, float *__restrict__ C, const float *__restrict__ A,
     const float *__restrict__ Bw, const float *__restrict__ D, const uint8_t *__restrict__ mask, int mask_group,
-    const double *__restrict__ scalars, int64_t d_in, int nbj, float *__restrict__ Gout,
+    const double *__restrict__ scalars, int64_t d_in, int nbj, int nblocks, float *__restrict__ Gout,
     float *__restrict__ loss_part) {
     using CH = Chain<B>;
     __shared__ Smem<B> sm;
     const int tid = threadIdx.x;
     const typename CH::Pos p(tid);
-    const int i = blockIdx.x / nbj, j = blockIdx.x % nbj;
-    float *Cij = C + (int64_t)i * B * d_in + (int64_t)j * B;
-    const float *Wij = Wbar + (int64_t)i * B * d_in + (int64_t)j * B;
+    const int ldw = (int)d_in, woff = p.lane_off(ldw);
     typename CH::Acc acc;
-    CH::load_tile(sm.X, Cij, d_in, tid);
-    CH::load_tile(sm.Y, A + (int64_t)i * B * B, B, tid);
-    if (tid < B) sm.Dl[tid] = D[(int64_t)j * B + tid];
-    __syncthreads();
-    acc.zero();
-    CH::template mma<false, false, false>(acc, sm.Y, sm.X, nullptr, p); // S' = A C
-    __syncthreads();
-    CH::store_acc(sm.X, acc, p);
-    CH::load_tile(sm.Y, Bw + (int64_t)j * B * B, B, tid);
-    float wb[CH::TM][CH::TN][16];
-#pragma unroll
-    for (int tm = 0; tm < CH::TM; ++tm)
-#pragma unroll
-        for (int tn = 0; tn < CH::TN; ++tn)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) wb[tm][tn][r] = Wij[(int64_t)p.row(tm, r) * d_in + p.col(tn)];
-    __syncthreads();
-    acc.zero();
-    CH::template mma<false, false, false>(acc, sm.X, sm.Y, nullptr, p); // What = S' B
-    float lsum = 0.f;
-#pragma unroll
-    for (int tm = 0; tm < CH::TM; ++tm)
-#pragma unroll
-        for (int tn = 0; tn < CH::TN; ++tn) {
-            float dj = sm.Dl[p.col(tn)];
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                float res = wb[tm][tn][r] - acc.v[tm][tn][r];
-                lsum += res * res * dj;
-                acc.v[tm][tn][r] = res * dj;
-            }
-        }
-    if (MODE == 1) {
-        float ltot = CH::block_sum(lsum, sm.red, tid);
-        if (tid == 0) loss_part[blockIdx.x] = ltot;
-    }
-    __syncthreads();
-    CH::store_acc(sm.X, acc, p); // R D   (Y still holds B^j)
-    __syncthreads();
-    acc.zero();
-    CH::template mma<false, true, false>(acc, sm.X, sm.Y, nullptr, p); // U = (R D) B^T
-    __syncthreads();
-    CH::store_acc(sm.X, acc, p);
-    CH::load_tile(sm.Y, A + (int64_t)i * B * B, B, tid);
-    __syncthreads();
-    acc.zero();
-    CH::template mma<true, false, false>(acc, sm.Y, sm.X, nullptr, p); // G = A^T U
+    typename CH::TileRegs t0, tc;
+    float eta2 = 0.f;
     if (MODE == 0) {
         const double bw = scalars[2];
-        const float eta2 = bw > 0.0 ? (float)(2.0 / bw) : 0.f;
-        const int64_t mrow = d_in / mask_group;
+        eta2 = bw > 0.0 ? (float)(2.0 / bw) : 0.f;
+    }
+    const int64_t mrow = d_in / mask_group;
+    int blk = blockIdx.x;
+    if (blk < nblocks) CH::gload_tile(t0, C + (int64_t)(blk / nbj) * B * d_in + (int64_t)(blk % nbj) * B, ldw, tid);
+    for (; blk < nblocks; blk += gridDim.x) {
+        const int i = blk / nbj, j = blk % nbj;
+        float *Cij = C + (int64_t)i * B * d_in + (int64_t)j * B;
+        const float *Wij = Wbar + (int64_t)i * B * d_in + (int64_t)j * B;
+        CH::lstore_tile(sm.X, t0, tid);
+        CH::gload_tile(t0, A + (int64_t)i * B * B, B, tid);
+        if (tid < B) sm.Dl[tid] = D[(int64_t)j * B + tid];
+        CH::lstore_tile(sm.Y, t0, tid);
+        __syncthreads();
+        CH::gload_tile(t0, Bw + (int64_t)j * B * B, B, tid);
+        acc.zero();
+        CH::template mma<false, false, false>(acc, sm.Y, sm.X, nullptr, p); // S' = A C
+        __syncthreads();
+        CH::store_acc(sm.X, acc, p);
+        CH::lstore_tile(sm.Y, t0, tid);
+        {
+            float wb[CH::TM][CH::TN][16];
 #pragma unroll
-        for (int tm = 0; tm < CH::TM; ++tm)
+            for (int tm = 0; tm < CH::TM; ++tm)
 #pragma unroll
-            for (int tn = 0; tn < CH::TN; ++tn)
+                for (int tn = 0; tn < CH::TN; ++tn)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    int row = p.row(tm, r), col = p.col(tn);
-                    int64_t gcol = (int64_t)j * B + col;
-                    uint8_t mb = mask[((int64_t)i * B + row) * mrow + gcol / mask_group];
-                    if ((mb >> (gcol % mask_group)) & 1) {
-                        float *cp = Cij + (int64_t)row * d_in + col;
-                        *cp = *cp + eta2 * acc.v[tm][tn][r];
+                    for (int r = 0; r < 16; ++r) wb[tm][tn][r] = Wij[opaque(woff) + CH::Pos::unif_off(tm, tn, r, ldw)];
+            __syncthreads();
+            acc.zero();
+            CH::template mma<false, false, false>(acc, sm.X, sm.Y, nullptr, p); // What = S' B
+            float lsum = 0.f;
+#pragma unroll
+            for (int tm = 0; tm < CH::TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < CH::TN; ++tn) {
+                    float dj = sm.Dl[p.col(tn)];
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        float res = wb[tm][tn][r] - acc.v[tm][tn][r];
+                        lsum += res * res * dj;
+                        acc.v[tm][tn][r] = res * dj;
                     }
                 }
-    } else {
-        float *Gij = Gout + (int64_t)i * B * d_in + (int64_t)j * B;
+            if (MODE == 1) {
+                float ltot = CH::block_sum(lsum, sm.red, tid);
+                if (tid == 0) loss_part[blk] = ltot;
+            }
+        }
+        __syncthreads();
+        CH::store_acc(sm.X, acc, p); // R D   (Y still holds B^j)
+        __syncthreads();
+        CH::gload_tile(t0, A + (int64_t)i * B * B, B, tid);
+        acc.zero();
+        CH::template mma<false, true, false>(acc, sm.X, sm.Y, nullptr, p); // U = (R D) B^T
+        __syncthreads();
+        CH::store_acc(sm.X, acc, p);
+        CH::lstore_tile(sm.Y, t0, tid);
+        // operands of the epilogue and the next block's core tile, underneath the last product
+        uint32_t mraw[CH::PER][2];
+        if (MODE == 0) {
+            CH::gload_tile(tc, Cij, ldw, tid); // this block's core again (L2), in the coalesced loader layout
 #pragma unroll
-        for (int tm = 0; tm < CH::TM; ++tm)
+            for (int it = 0; it < CH::PER; ++it) {
+                const int row = it * CH::ROWS_PER_IT + CH::loader_row(tid);
+                const int64_t gcol = (int64_t)j * B + CH::loader_c4(tid) * 4;
+                const uint8_t *mp = mask + ((int64_t)i * B + row) * mrow + gcol / mask_group;
+                mraw[it][0] = mp[0];
+                mraw[it][1] = mask_group == 2 ? mp[1] : 0u;
+            }
+        }
+        const int nblk = blk + gridDim.x;
+        if (nblk < nblocks)
+            CH::gload_tile(t0, C + (int64_t)(nblk / nbj) * B * d_in + (int64_t)(nblk % nbj) * B, ldw, tid);
+        __syncthreads();
+        acc.zero();
+        CH::template mma<true, false, false>(acc, sm.Y, sm.X, nullptr, p); // G = A^T U
+        if (MODE == 0) {
+            // C <- C + (2/beta) G on kept entries, as one coalesced float4 pass: G goes through LDS
+            __syncthreads();
+            CH::store_acc(sm.X, acc, p);
+            __syncthreads();
+            const int off0 = opaque(CH::loader_row(tid) * ldw + CH::loader_c4(tid) * 4);
+            const int lrow = opaque(CH::loader_row(tid)), c4 = opaque(CH::loader_c4(tid));
 #pragma unroll
-            for (int tn = 0; tn < CH::TN; ++tn)
+            for (int it = 0; it < CH::PER; ++it) {
+                const int row = it * CH::ROWS_PER_IT + lrow;
+                const int shift = (int)(((int64_t)j * B + c4 * 4) % mask_group);
+                const uint32_t nib = mask_group == 2 ? ((mraw[it][0] & 3u) | ((mraw[it][1] & 3u) << 2))
+                                                     : ((mraw[it][0] >> shift) & 0xFu);
+                const float *g = sm.X + row * CH::P + c4 * 4;
+                float4 v = tc.v[it];
+                if (nib & 1u) v.x += eta2 * g[0];
+                if (nib & 2u) v.y += eta2 * g[1];
+                if (nib & 4u) v.z += eta2 * g[2];
+                if (nib & 8u) v.w += eta2 * g[3];
+                *reinterpret_cast<float4 *>(Cij + (off0 + it * CH::ROWS_PER_IT * ldw)) = v;
+            }
+        } else {
+            float *Gij = Gout + (int64_t)i * B * d_in + (int64_t)j * B;
 #pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    Gij[(int64_t)p.row(tm, r) * d_in + p.col(tn)] = -2.f * acc.v[tm][tn][r];
+            for (int tm = 0; tm < CH::TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < CH::TN; ++tn)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        Gij[opaque(woff) + CH::Pos::unif_off(tm, tn, r, ldw)] = -2.f * acc.v[tm][tn][r];
+        }
+        __syncthreads();
     }
 }
 
@@ -471,15 +599,15 @@ void launch_phase_B(const Dims &d, const float *Wbar, const float *C, const floa
 
 void launch_phase_G(const Dims &d, const float *Wbar, float *C, const float *A, const float *B, const float *D,
                     const uint8_t *mask, int mask_group, const double *scalars, float *Gout, float *loss_part,
-                    int mode, hipStream_t s) {
+                    int mode, int grid_cap, hipStream_t s) {
     ARMOR_DISPATCH_B(d.b, {
-        dim3 grid(d.nblocks), block(Chain<BB>::NT);
+        dim3 grid(std::min(d.nblocks, grid_cap)), block(Chain<BB>::NT);
         if (mode == 0)
             hipLaunchKernelGGL((phase_G_kernel<BB, 0>), grid, block, 0, s, Wbar, C, A, B, D, mask, mask_group,
-                               scalars, d.d_in, d.nbj, Gout, loss_part);
+                               scalars, d.d_in, d.nbj, d.nblocks, Gout, loss_part);
         else
             hipLaunchKernelGGL((phase_G_kernel<BB, 1>), grid, block, 0, s, Wbar, C, A, B, D, mask, mask_group,
-                               scalars, d.d_in, d.nbj, Gout, loss_part);
+                               scalars, d.d_in, d.nbj, d.nblocks, Gout, loss_part);
     });
 }
 

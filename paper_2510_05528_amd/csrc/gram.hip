@@ -90,8 +90,132 @@ __global__ __launch_bounds__(GramCfg<T>::WM *GramCfg<T>::WN * 64) void gram_f32_
             }
 }
 
+// ------------------------------------------------------------------------------------------------
+// bf16 MFMA path (v_mfma_f32_32x32x16_bf16, fp32 accumulation) for bf16 activations.
+// Workgroup = 8 waves, output tile 256 x 256 (wave patch 128 x 64 = 4 x 2 accumulator tiles), so a
+// token contributes 2 * 256 * 256 flops per 1 KB read: the kernel is bounded by MFMA issue and L2
+// bandwidth, not HBM.  The MFMA operands want 8 consecutive *tokens* of one channel per lane, while
+// X is channel-contiguous: each thread transposes an 8 token x 8 channel patch in registers
+// (v_perm_b32) on its way from global memory to LDS.  LDS holds [channel][64 tokens] bf16 per
+// operand and stage (128 B rows, no padding); the 16-byte token group g of channel ch sits in slot
+// g ^ ((ch ^ (ch >> 3)) & 7), which keeps both the transposed writes (lanes vary ch >> 3) and the
+// operand reads (lanes vary ch & 7) spread over all banks.  Two LDS stages + a register prefetch
+// of the next 64-token chunk overlap global loads with MFMA work.
+// ------------------------------------------------------------------------------------------------
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+__global__ __launch_bounds__(512) void gram_bf16_kernel(const uint16_t *__restrict__ X, int64_t ldx, int ntile,
+                                                        float *__restrict__ H, int64_t ldh, int accumulate,
+                                                        int64_t t_begin, int64_t t_end) {
+    constexpr int T = 256, KC = 64, TM = 4, TN = 2;
+    __shared__ uint4 lds[2][2][T * 8]; // [stage][operand][channel * 8 + slot]
+    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, l32 = lane & 31, kh = lane >> 5;
+    int ta = 0, rem = blockIdx.x;
+    while (rem >= ntile - ta) { rem -= ntile - ta; ++ta; }
+    const int tb = ta + rem;
+    const bool diag = ta == tb;
+    const int wm0 = (w & 1) * 128, wn0 = (w >> 1) * 64;
+
+    // loader role: operand, 8-channel column, 8-token row group
+    const int op = tid >> 8, lr = tid & 255, chblk = lr & 31, tokblk = lr >> 5;
+    const bool loader = !(diag && op == 1);
+    const uint16_t *xcol = X + (int64_t)(op ? tb : ta) * T + chblk * 8;
+    uint4 pre[8];
+    auto gload = [&](int64_t t0) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            int64_t row = t0 + tokblk * 8 + i;
+            pre[i] = make_uint4(0u, 0u, 0u, 0u);
+            if (loader && row < t_end) pre[i] = *reinterpret_cast<const uint4 *>(xcol + row * ldx);
+        }
+    };
+    auto lstore = [&](int stage) {
+        if (!loader) return;
+        const uint32_t *r[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) r[i] = reinterpret_cast<const uint32_t *>(&pre[i]);
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            const uint32_t sel = (c & 1) ? 0x07060302u : 0x05040100u;
+            uint4 o;
+            o.x = __builtin_amdgcn_perm(r[1][c >> 1], r[0][c >> 1], sel);
+            o.y = __builtin_amdgcn_perm(r[3][c >> 1], r[2][c >> 1], sel);
+            o.z = __builtin_amdgcn_perm(r[5][c >> 1], r[4][c >> 1], sel);
+            o.w = __builtin_amdgcn_perm(r[7][c >> 1], r[6][c >> 1], sel);
+            int ch = chblk * 8 + c;
+            int slot = tokblk ^ ((ch ^ (ch >> 3)) & 7);
+            lds[stage][op][ch * 8 + slot] = o;
+        }
+    };
+
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int a = 0; a < TM; ++a)
+#pragma unroll
+        for (int c = 0; c < TN; ++c)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][c][r] = 0.f;
+
+    const int64_t nchunks = (t_end - t_begin + KC - 1) / KC;
+    if (nchunks > 0) {
+        gload(t_begin);
+        lstore(0);
+    }
+    __syncthreads();
+    for (int64_t ci = 0; ci < nchunks; ++ci) {
+        const int st = (int)(ci & 1);
+        if (ci + 1 < nchunks) gload(t_begin + (ci + 1) * KC);
+        const uint4 *La = lds[st][0];
+        const uint4 *Lb = lds[st][diag ? 0 : 1];
+#pragma unroll
+        for (int ks = 0; ks < KC / 16; ++ks) {
+            const int g = ks * 2 + kh;
+            bf16x8 a[TM], b[TN];
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm) {
+                int ch = wm0 + tm * 32 + l32;
+                a[tm] = __builtin_bit_cast(bf16x8, La[ch * 8 + (g ^ ((ch ^ (ch >> 3)) & 7))]);
+            }
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn) {
+                int ch = wn0 + tn * 32 + l32;
+                b[tn] = __builtin_bit_cast(bf16x8, Lb[ch * 8 + (g ^ ((ch ^ (ch >> 3)) & 7))]);
+            }
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn)
+                    acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[tm], b[tn], acc[tm][tn], 0, 0, 0);
+        }
+        if (ci + 1 < nchunks) lstore(st ^ 1);
+        __syncthreads();
+    }
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                int64_t row = (int64_t)ta * T + wm0 + tm * 32 + (r >> 2) * 8 + kh * 4 + (r & 3);
+                int64_t col = (int64_t)tb * T + wn0 + tn * 32 + l32;
+                float v = acc[tm][tn][r];
+                float *h = H + row * ldh + col;
+                *h = accumulate ? *h + v : v;
+                if (!diag) {
+                    float *hm = H + col * ldh + row;
+                    *hm = accumulate ? *hm + v : v;
+                }
+            }
+}
+
 void launch_gram(const void *X, int bf16, int64_t n, int64_t d_in, int64_t ldx, float *H, int64_t ldh,
                  int accumulate, hipStream_t s) {
+    if (bf16 && d_in % 256 == 0 && ldx % 8 == 0) {
+        int nt = (int)(d_in / 256);
+        hipLaunchKernelGGL(gram_bf16_kernel, dim3((unsigned)(nt * (nt + 1) / 2)), dim3(512), 0, s,
+                           reinterpret_cast<const uint16_t *>(X), ldx, nt, H, ldh, accumulate, (int64_t)0, n);
+        return;
+    }
     int T = (d_in % 128 == 0) ? 128 : (d_in % 64 == 0) ? 64 : 32;
     int ntile = (int)(d_in / T);
     dim3 grid((unsigned)(ntile * (ntile + 1) / 2));

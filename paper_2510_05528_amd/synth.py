@@ -72,14 +72,10 @@ def torch_weight(d_out, d_in, seed, device, outlier_frac=0.02, outlier_scale=8.0
 
 
 def torch_mixing(d_in, seed, device):
+    """Lambda^{1/2} Q^T on the device; the QR itself runs on the host (numpy, seeded)."""
     import torch
-    g = torch.Generator(device=device)
-    g.manual_seed(2000 + seed)
-    G = torch.randn((d_in, d_in), generator=g, device=device, dtype=torch.float32)
-    Q, Rr = torch.linalg.qr(G)
-    Q = Q * torch.sign(torch.diagonal(Rr))[None, :]
-    lam = 1.0 / (1.0 + torch.arange(d_in, device=device, dtype=torch.float32) / 8.0)
-    return torch.sqrt(lam)[:, None] * Q.T
+    rng = np.random.default_rng([seed, 3])
+    return torch.from_numpy(_mixing(d_in, rng).astype(np.float32)).to(device)
 
 
 def torch_calibration(n_tokens, d_in, seed, device, outlier_frac=0.005, outlier_scale=20.0,
