@@ -39,7 +39,8 @@ def chain_algorithmic_flops(kind, d_out, d_in, b, N, M):
     sparse = unit * N / M
     if kind in ("phase_A", "phase_B"):
         return sparse + unit + unit + 0.5 * unit
-    return sparse + 3 * unit  # phase_GW / phase_GS
+    # phase_WS: S' = A C (core operand), What, U, G, V = (G.M) K (N:M-sparse operand), Z = (A^T A) V
+    return sparse + 3 * unit + sparse + unit
 
 
 def main():

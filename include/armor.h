@@ -64,16 +64,15 @@ int armor_last_hip_error(void);
  * stream (events are host resources created on first use and kept; no device memory).
  * armor_profile_read() waits for the recorded events, returns per kind the summed elapsed
  * milliseconds and the number of launches into two HOST arrays of ARMOR_PROF_KINDS entries, and
- * resets the record.  Kinds: the Gram kernel (Sec. 2), the three gradient chains of Alg. 2
- * (A step, B step, W' step), the core-gradient chain feeding Alg. 3, and the Alg. 3 kernel.
+ * resets the record.  Kinds: the Gram kernel (Sec. 2), the A-step and B-step chains of Alg. 2,
+ * the chain that fuses the W' step with the core gradient feeding Alg. 3, and the Alg. 3 kernel.
  */
 #define ARMOR_PROF_GRAM 0
 #define ARMOR_PROF_PHASE_A 1
 #define ARMOR_PROF_PHASE_B 2
-#define ARMOR_PROF_PHASE_GW 3
-#define ARMOR_PROF_PHASE_GS 4
-#define ARMOR_PROF_SPARSE 5
-#define ARMOR_PROF_KINDS 6
+#define ARMOR_PROF_PHASE_WS 3
+#define ARMOR_PROF_SPARSE 4
+#define ARMOR_PROF_KINDS 5
 armor_status armor_profile_enable(int on);
 armor_status armor_profile_read(double *ms_total /*host [ARMOR_PROF_KINDS]*/, int64_t *launches /*host*/);
 

@@ -9,7 +9,7 @@ _LIB_PATH = os.path.join(_HERE, "libarmor.so")
 
 ARMOR_F32, ARMOR_BF16 = 0, 1
 
-PROF_KINDS = ["gram", "phase_A", "phase_B", "phase_GW", "phase_GS", "sparse_step"]
+PROF_KINDS = ["gram", "phase_A", "phase_B", "phase_WS", "sparse_step"]
 
 EXPORTED = ["armor_status_string", "armor_last_hip_error", "armor_profile_enable", "armor_profile_read", "armor_gram", "armor_gram_diag",
             "armor_normalize_workspace_bytes", "armor_normalize", "armor_proxy_loss_workspace_bytes",

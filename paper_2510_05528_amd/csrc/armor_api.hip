@@ -112,7 +112,7 @@ struct Carver {
 };
 
 struct FactorWs {
-    float *Wbar, *G, *D, *gpart, *beta_part, *loss_part, *loss_part2, *K, *colnorm2, *fro2A, *fro2K, *cn_partial,
+    float *Wbar, *G, *D, *gpart, *beta_part, *loss_part, *loss_part2, *K, *AtA, *colnorm2, *fro2A, *fro2K, *cn_partial,
         *r1, *r2;
     double *scalars;
     uint8_t *mask;
@@ -153,6 +153,7 @@ FactorWs carve_factor(void *ws, const Dims &d, int mask_group, const armor_opts 
     f.loss_part = c.take<float>(d.nblocks);
     f.loss_part2 = c.take<float>(d.nblocks);
     f.K = c.take<float>((size_t)d.nbj * bb);
+    f.AtA = c.take<float>((size_t)d.nbi * bb);
     f.colnorm2 = c.take<float>(d.d_out);
     f.fro2A = c.take<float>(d.nbi);
     f.fro2K = c.take<float>(d.nbj);
@@ -367,16 +368,13 @@ armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const flo
             launch_phase_B(d, f.Wbar, S, A, B, f.D, f.nsB, f.gpart, f.beta_part, s);
         }
         launch_update_wrapper(B, d.nbj, d.b, f.gpart, f.nsB, f.beta_part, d.nblocks, nullptr, nullptr, s);
-        launch_wrapper_grams(d, A, B, f.D, f.colnorm2, f.fro2A, f.K, f.fro2K, s);
+        launch_wrapper_grams(d, A, B, f.D, f.colnorm2, f.fro2A, f.AtA, f.K, f.fro2K, s);
         launch_finalize_betaW(f.fro2A, d.nbi, f.fro2K, d.nbj, f.scalars, s);
+        // W' step fused with the core gradient at the updated core; then the sparse-core step (Alg. 3)
         {
-            ProfScope ps(ARMOR_PROF_PHASE_GW, s);
-            launch_phase_G(d, f.Wbar, S, A, B, f.D, mask, mask_group, f.scalars, nullptr, nullptr, 0, chain_slots(d.b), s);
-        }
-        // sparse-core step (Alg. 3)
-        {
-            ProfScope ps(ARMOR_PROF_PHASE_GS, s);
-            launch_phase_G(d, f.Wbar, S, A, B, f.D, mask, mask_group, f.scalars, f.G, f.loss_part2, 1, chain_slots(d.b), s);
+            ProfScope ps(ARMOR_PROF_PHASE_WS, s);
+            launch_phase_WS(d, f.Wbar, S, A, B, f.D, f.AtA, f.K, mask, mask_group, f.scalars, f.G, f.loss_part2,
+                            chain_slots(d.b), s);
         }
         {
             ProfScope ps(ARMOR_PROF_SPARSE, s);

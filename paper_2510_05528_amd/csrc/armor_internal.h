@@ -27,9 +27,14 @@ void launch_phase_B(const Dims &d, const float *Wbar, const float *C, const floa
 void launch_phase_G(const Dims &d, const float *Wbar, float *C, const float *A, const float *B, const float *D,
                     const uint8_t *mask, int mask_group, const double *scalars, float *Gout, float *loss_part,
                     int mode, int grid_cap, hipStream_t s);
-// Per wrapper block: ||A^i[:,p]||^2, ||A^iT A^i||_F^2; K^j = B^j D^j B^jT, ||K^j||_F^2.
+// Per wrapper block: A^iT A^i, its diagonal ||A^i[:,p]||^2 and ||A^iT A^i||_F^2; K^j = B^j D^j B^jT, ||K^j||_F^2.
 void launch_wrapper_grams(const Dims &d, const float *A, const float *B, const float *D, float *colnorm2,
-                          float *fro2A, float *K, float *fro2K, hipStream_t s);
+                          float *fro2A, float *AtA, float *K, float *fro2K, hipStream_t s);
+// W' step fused with the core gradient at the updated core (N:M mode): C += (2/beta_W) G (.) M,
+// Gout = -2 (G - (2/beta_W) (A^T A)(G (.) M) K), block loss after the continuous step to loss_part.
+void launch_phase_WS(const Dims &d, const float *Wbar, float *C, const float *A, const float *B, const float *D,
+                     const float *AtA, const float *K, const uint8_t *mask, int mask_group, const double *scalars,
+                     float *Gout, float *loss_part, int grid_cap, hipStream_t s);
 int chain_max_nsplit();
 
 // ---- small kernels (small.hip) ----------------------------------------------------------------

@@ -523,14 +523,171 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_G_kernel(
 }
 
 // ------------------------------------------------------------------------------------------------
+// W' step of Alg. 2 fused with the core gradient that Alg. 3 needs afterwards (N:M mode).
+// With G = A^T ((Wbar - A C B) D) B^T, Delta = G (.) M and eta = 2 / beta_W' (Eq. 11):
+//     C_new = C + eta * Delta                                        (the W' step, App. D.3)
+//     G_new = A^T ((Wbar - A C_new B) D) B^T = G - eta * (A^T A) Delta (B D B^T)
+//     L(C_new) = L(C) - 2 eta ||Delta||_F^2 + eta^2 <Delta, (A^T A) Delta (B D B^T)>
+// so the gradient at the updated core costs two more b-deep products on tiles that are already
+// on the CU (Delta, and the precomputed wrapper Grams A^T A and K = B D B^T) instead of a second
+// pass of four.  Gout = -2 G_new (unmasked; selection scores and q-vectors of Alg. 3 read it),
+// loss_part[block] = block loss after the continuous step.
+// ------------------------------------------------------------------------------------------------
+template <int B>
+__global__ __launch_bounds__(Chain<B>::NT) void phase_WS_kernel(
+    const float *__restrict__ Wbar, float *__restrict__ C, const float *__restrict__ A,
+    const float *__restrict__ Bw, const float *__restrict__ D, const float *__restrict__ AtA,
+    const float *__restrict__ K, const uint8_t *__restrict__ mask, int mask_group,
+    const double *__restrict__ scalars, int64_t d_in, int nbj, int nblocks, float *__restrict__ Gout,
+    float *__restrict__ loss_part) {
+    using CH = Chain<B>;
+    __shared__ Smem<B> sm;
+    const int tid = threadIdx.x;
+    const typename CH::Pos p(tid);
+    const int ldw = (int)d_in, woff = p.lane_off(ldw);
+    typename CH::Acc acc, acc2;
+    typename CH::TileRegs t0;
+    const double bw = scalars[2];
+    const float eta2 = bw > 0.0 ? (float)(2.0 / bw) : 0.f; // eta of the comment above
+    const int64_t mrow = d_in / mask_group;
+    int blk = blockIdx.x;
+    if (blk < nblocks) CH::gload_tile(t0, C + (int64_t)(blk / nbj) * B * d_in + (int64_t)(blk % nbj) * B, ldw, tid);
+    for (; blk < nblocks; blk += gridDim.x) {
+        const int i = blk / nbj, j = blk % nbj;
+        float *Cij = C + (int64_t)i * B * d_in + (int64_t)j * B;
+        const float *Wij = Wbar + (int64_t)i * B * d_in + (int64_t)j * B;
+        CH::lstore_tile(sm.X, t0, tid);
+        CH::gload_tile(t0, A + (int64_t)i * B * B, B, tid);
+        if (tid < B) sm.Dl[tid] = D[(int64_t)j * B + tid];
+        CH::lstore_tile(sm.Y, t0, tid);
+        __syncthreads();
+        CH::gload_tile(t0, Bw + (int64_t)j * B * B, B, tid);
+        acc.zero();
+        CH::template mma<false, false, false>(acc, sm.Y, sm.X, nullptr, p); // S' = A C
+        __syncthreads();
+        CH::store_acc(sm.X, acc, p);
+        CH::lstore_tile(sm.Y, t0, tid);
+        float lsum = 0.f;
+        {
+            float wb[CH::TM][CH::TN][16];
+#pragma unroll
+            for (int tm = 0; tm < CH::TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < CH::TN; ++tn)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) wb[tm][tn][r] = Wij[opaque(woff) + CH::Pos::unif_off(tm, tn, r, ldw)];
+            __syncthreads();
+            acc.zero();
+            CH::template mma<false, false, false>(acc, sm.X, sm.Y, nullptr, p); // What = S' B
+#pragma unroll
+            for (int tm = 0; tm < CH::TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < CH::TN; ++tn) {
+                    float dj = sm.Dl[p.col(tn)];
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        float res = wb[tm][tn][r] - acc.v[tm][tn][r];
+                        lsum += res * res * dj;
+                        acc.v[tm][tn][r] = res * dj;
+                    }
+                }
+        }
+        __syncthreads();
+        CH::store_acc(sm.X, acc, p); // R D   (Y still holds B^j)
+        __syncthreads();
+        CH::gload_tile(t0, A + (int64_t)i * B * B, B, tid);
+        acc.zero();
+        CH::template mma<false, true, false>(acc, sm.X, sm.Y, nullptr, p); // U = (R D) B^T
+        __syncthreads();
+        CH::store_acc(sm.X, acc, p);
+        CH::lstore_tile(sm.Y, t0, tid);
+        // current core values and mask bytes in the accumulator layout, underneath the next product
+        float cv[CH::TM][CH::TN][16];
+        uint32_t mraw[CH::TM][CH::TN][16];
+#pragma unroll
+        for (int tm = 0; tm < CH::TM; ++tm)
+#pragma unroll
+            for (int tn = 0; tn < CH::TN; ++tn) {
+                const int64_t gcol = (int64_t)j * B + p.col(tn);
+                const uint8_t *mp = mask + ((int64_t)i * B + opaque(p.wm0 + p.kh * 4)) * mrow + gcol / mask_group;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    cv[tm][tn][r] = Cij[opaque(woff) + CH::Pos::unif_off(tm, tn, r, ldw)];
+                    mraw[tm][tn][r] = mp[(int64_t)(tm * 32 + (r >> 2) * 8 + (r & 3)) * mrow];
+                }
+            }
+        CH::gload_tile(t0, K + (int64_t)j * B * B, B, tid);
+        __syncthreads();
+        acc.zero();
+        CH::template mma<true, false, false>(acc, sm.Y, sm.X, nullptr, p); // G = A^T U   (stays in acc)
+        // W' step on kept entries; Delta = G (.) M goes to LDS for the two extra products
+        uint32_t keep[CH::TM][CH::TN];
+        float dd = 0.f;
+        __syncthreads();
+        {
+            float *d0 = sm.X + opaque(p.lane_off(CH::P));
+#pragma unroll
+            for (int tm = 0; tm < CH::TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < CH::TN; ++tn) {
+                    const int sh = (int)(((int64_t)j * B + p.col(tn)) % mask_group);
+                    keep[tm][tn] = 0u;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const bool kp = (mraw[tm][tn][r] >> sh) & 1u;
+                        keep[tm][tn] |= (kp ? 1u : 0u) << r;
+                        const float dl = kp ? acc.v[tm][tn][r] : 0.f;
+                        dd += dl * dl;
+                        d0[CH::Pos::unif_off(tm, tn, r, CH::P)] = dl;
+                        if (kp) Cij[opaque(woff) + CH::Pos::unif_off(tm, tn, r, ldw)] = cv[tm][tn][r] + eta2 * dl;
+                    }
+                }
+        }
+        CH::lstore_tile(sm.Y, t0, tid); // K^j
+        __syncthreads();
+        CH::gload_tile(t0, AtA + (int64_t)i * B * B, B, tid);
+        acc2.zero();
+        CH::template mma<false, false, false>(acc2, sm.X, sm.Y, nullptr, p); // V = Delta K
+        __syncthreads();
+        CH::store_acc(sm.X, acc2, p);
+        CH::lstore_tile(sm.Y, t0, tid); // A^T A (symmetric)
+        __syncthreads();
+        const int nblk = blk + gridDim.x;
+        if (nblk < nblocks)
+            CH::gload_tile(t0, C + (int64_t)(nblk / nbj) * B * d_in + (int64_t)(nblk % nbj) * B, ldw, tid);
+        acc2.zero();
+        CH::template mma<false, false, false>(acc2, sm.Y, sm.X, nullptr, p); // Z = (A^T A) V
+        float dz = 0.f;
+        {
+            float *Gij = Gout + (int64_t)i * B * d_in + (int64_t)j * B;
+#pragma unroll
+            for (int tm = 0; tm < CH::TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < CH::TN; ++tn)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const float g = acc.v[tm][tn][r], z = acc2.v[tm][tn][r];
+                        if ((keep[tm][tn] >> r) & 1u) dz += g * z;
+                        Gij[opaque(woff) + CH::Pos::unif_off(tm, tn, r, ldw)] = -2.f * (g - eta2 * z);
+                    }
+        }
+        float ltot = CH::block_sum(lsum - 2.f * eta2 * dd + eta2 * eta2 * dz, sm.red, tid);
+        if (tid == 0) loss_part[blk] = ltot;
+        __syncthreads();
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
 // Small Gram-type products of the wrappers themselves (Eq. 11 and the shortcuts of Alg. 3):
-//   blockIdx <  nbi : colnorm2[i*b+p] = ||A^(i)[:,p]||^2 (= ||a||^2 of Eq. 7), fro2A[i] = ||A^iT A^i||_F^2
+//   blockIdx <  nbi : AtA^(i) = A^(i)T A^(i), colnorm2[i*b+p] = its diagonal = ||A^(i)[:,p]||^2 (the ||a||^2 of
+//                     Eq. 7), fro2A[i] = ||A^iT A^i||_F^2
 //   blockIdx >= nbi : K^(j) = B^(j) D^(j) B^(j)T (holds every B' D B'^T of Eq. 7), fro2K[j] = ||K^j||_F^2
 // ------------------------------------------------------------------------------------------------
 template <int B>
 __global__ __launch_bounds__(Chain<B>::NT) void wrapper_grams_kernel(
     const float *__restrict__ A, const float *__restrict__ Bw, const float *__restrict__ D, int nbi,
-    float *__restrict__ colnorm2, float *__restrict__ fro2A, float *__restrict__ K, float *__restrict__ fro2K) {
+    float *__restrict__ colnorm2, float *__restrict__ fro2A, float *__restrict__ AtA, float *__restrict__ K,
+    float *__restrict__ fro2K) {
     using CH = Chain<B>;
     __shared__ Smem<B> sm;
     const int tid = threadIdx.x;
@@ -554,8 +711,8 @@ __global__ __launch_bounds__(Chain<B>::NT) void wrapper_grams_kernel(
                 float v = acc.v[tm][tn][r];
                 f2 += v * v;
                 int row = p.row(tm, r), col = p.col(tn);
-                if (isA) { if (row == col) colnorm2[(int64_t)idx * B + row] = v; }
-                else K[(int64_t)idx * B * B + row * B + col] = v;
+                if (isA && row == col) colnorm2[(int64_t)idx * B + row] = v;
+                (isA ? AtA : K)[(int64_t)idx * B * B + row * B + col] = v;
             }
     float ftot = CH::block_sum(f2, sm.red, tid);
     if (tid == 0) (isA ? fro2A : fro2K)[idx] = ftot;
@@ -612,10 +769,21 @@ void launch_phase_G(const Dims &d, const float *Wbar, float *C, const float *A, 
 }
 
 void launch_wrapper_grams(const Dims &d, const float *A, const float *B, const float *D, float *colnorm2,
-                          float *fro2A, float *K, float *fro2K, hipStream_t s) {
+                          float *fro2A, float *AtA, float *K, float *fro2K, hipStream_t s) {
     ARMOR_DISPATCH_B(d.b, {
         dim3 grid(d.nbi + d.nbj), block(Chain<BB>::NT);
-        hipLaunchKernelGGL((wrapper_grams_kernel<BB>), grid, block, 0, s, A, B, D, d.nbi, colnorm2, fro2A, K, fro2K);
+        hipLaunchKernelGGL((wrapper_grams_kernel<BB>), grid, block, 0, s, A, B, D, d.nbi, colnorm2, fro2A, AtA, K,
+                           fro2K);
+    });
+}
+
+void launch_phase_WS(const Dims &d, const float *Wbar, float *C, const float *A, const float *B, const float *D,
+                     const float *AtA, const float *K, const uint8_t *mask, int mask_group, const double *scalars,
+                     float *Gout, float *loss_part, int grid_cap, hipStream_t s) {
+    ARMOR_DISPATCH_B(d.b, {
+        dim3 grid(std::min(d.nblocks, grid_cap)), block(Chain<BB>::NT);
+        hipLaunchKernelGGL((phase_WS_kernel<BB>), grid, block, 0, s, Wbar, C, A, B, D, AtA, K, mask, mask_group,
+                           scalars, d.d_in, d.nbj, d.nblocks, Gout, loss_part);
     });
 }
 
