@@ -117,6 +117,7 @@ struct FactorWs {
     double *scalars;
     uint8_t *mask;
     void *unstructured;
+    float *big_scratch;
     int nsA, nsB, cn_chunks;
     size_t bytes;
 };
@@ -162,8 +163,9 @@ FactorWs carve_factor(void *ws, const Dims &d, int mask_group, const armor_opts 
     f.r2 = c.take<float>(d.d_out);
     f.scalars = c.take<double>(8);
     f.mask = c.take<uint8_t>((size_t)d.d_out * (d.d_in / mask_group));
-    f.unstructured = nullptr;
-    (void)opts;
+    f.unstructured = (opts && opts->sparsity == 1)
+                         ? c.take<char>(unstructured_init_ws_bytes(d.d_out, d.d_in)) : nullptr;
+    f.big_scratch = d.b > 128 ? c.take<float>(big_scratch_floats(d, chain_slots(d.b))) : nullptr;
     f.bytes = (c.off + 255) & ~size_t(255);
     return f;
 }
@@ -269,6 +271,7 @@ size_t armor_proxy_loss_workspace_bytes(int64_t d_out, int64_t d_in, int64_t d_b
     c.take<float>((size_t)d.nbi * d.b * d.b);
     c.take<float>((size_t)d.nbj * d.b * d.b);
     c.take<float>(d.nblocks);
+    if (d.b > 128) c.take<float>(big_scratch_floats(d, chain_slots(d.b)));
     return c.off + 256;
 }
 
@@ -279,7 +282,6 @@ armor_status armor_proxy_loss(const float *Wbar, const float *A, const float *S,
     armor_status st = validate_shape(d_out, d_in, d_block);
     if (st != ARMOR_OK) return st;
     if (ldh != 0 && ldh < d_in) return ARMOR_ERR_SHAPE;
-    if (d_block == 256) return ARMOR_ERR_UNSUPPORTED;
     if (!ws || ws_bytes < armor_proxy_loss_workspace_bytes(d_out, d_in, d_block)) return ARMOR_ERR_WORKSPACE;
     if (!aligned16(Wbar) || !aligned16(S) || !aligned16(ws) || (A && !aligned16(A)) || (B && !aligned16(B)))
         return ARMOR_ERR_ALIGN;
@@ -290,11 +292,16 @@ armor_status armor_proxy_loss(const float *Wbar, const float *A, const float *S,
     float *Ai = c.take<float>((size_t)d.nbi * d.b * d.b);
     float *Bi = c.take<float>((size_t)d.nbj * d.b * d.b);
     float *loss_part = c.take<float>(d.nblocks);
+    float *big = d.b > 128 ? c.take<float>(big_scratch_floats(d, chain_slots(d.b))) : nullptr;
     if (ldh > 0) launch_diag(H, d_in, ldh, D, s);
     else if (hipMemcpyAsync(D, H, sizeof(float) * d_in, hipMemcpyDeviceToDevice, s) != hipSuccess) return check_hip();
     if (!A) { launch_init_identity(Ai, d.nbi, d.b, s); A = Ai; }
     if (!B) { launch_init_identity(Bi, d.nbj, d.b, s); B = Bi; }
-    launch_phase_A(d, Wbar, S, A, B, D, choose_nsplit(d.nbi, d.nbj, d.b), nullptr, nullptr, loss_part, true, s);
+    if (d.b > 128)
+        launch_big_phase_A(d, Wbar, S, A, B, D, choose_nsplit(d.nbi, d.nbj, d.b), nullptr, nullptr, loss_part, true,
+                           chain_slots(d.b), big, s);
+    else
+        launch_phase_A(d, Wbar, S, A, B, D, choose_nsplit(d.nbi, d.nbj, d.b), nullptr, nullptr, loss_part, true, s);
     launch_sum_to_double(loss_part, d.nblocks, loss_out, s);
     return check_hip();
 }
@@ -331,7 +338,8 @@ armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const flo
         return ARMOR_ERR_SHAPE;
     }
     if (n_iters < 0 || (ldh != 0 && ldh < d_in)) return ARMOR_ERR_SHAPE;
-    if (d_block == 256 || unstructured) return ARMOR_ERR_UNSUPPORTED;
+    if (unstructured && d_in % 8 != 0) return ARMOR_ERR_SHAPE;
+    if ((int64_t)d_in * d_block >= ((int64_t)1 << 31)) return ARMOR_ERR_SHAPE; // 32-bit tile offsets
     const int mask_group = unstructured ? 8 : M;
     Dims d = make_dims(d_out, d_in, d_block);
     if (!ws) return ARMOR_ERR_WORKSPACE;
@@ -351,35 +359,58 @@ armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const flo
     launch_rownorm_scale(W, w_dtype == ARMOR_BF16, d_out, d_in, r1p, r2p, f.Wbar, s);
     launch_init_identity(A, d.nbi, d.b, s);
     launch_init_identity(B, d.nbj, d.b, s);
-    launch_init_nm(f.Wbar, f.D, d_out, d_in, N, M, S, mask, s);
+    if (unstructured)
+        launch_unstructured_init(f.Wbar, f.D, d_out, d_in, o.unstructured_keep, S, mask,
+                                 reinterpret_cast<uint32_t *>(f.G), f.unstructured, s);
+    else
+        launch_init_nm(f.Wbar, f.D, d_out, d_in, N, M, S, mask, s);
     st = check_hip();
     if (st != ARMOR_OK) return st;
 
+    const bool big = d.b > 128;
+    const int slots = chain_slots(d.b);
+    auto run_phase_A = [&](bool loss_only) {
+        if (big) launch_big_phase_A(d, f.Wbar, S, A, B, f.D, f.nsA, f.gpart, f.beta_part, f.loss_part, loss_only, slots,
+                                    f.big_scratch, s);
+        else launch_phase_A(d, f.Wbar, S, A, B, f.D, f.nsA, f.gpart, f.beta_part, f.loss_part, loss_only, s);
+    };
     for (int t = 1; t <= n_iters; ++t) {
         // continuous step (Alg. 2), each gradient at the already-updated parameters (Lemma 1)
         {
             ProfScope ps(ARMOR_PROF_PHASE_A, s);
-            launch_phase_A(d, f.Wbar, S, A, B, f.D, f.nsA, f.gpart, f.beta_part, f.loss_part, false, s);
+            run_phase_A(false);
         }
         launch_update_wrapper(A, d.nbi, d.b, f.gpart, f.nsA, f.beta_part, d.nblocks, f.loss_part,
                               loss_trace ? loss_trace + (t - 1) : nullptr, s);
         {
             ProfScope ps(ARMOR_PROF_PHASE_B, s);
-            launch_phase_B(d, f.Wbar, S, A, B, f.D, f.nsB, f.gpart, f.beta_part, s);
+            if (big) launch_big_phase_B(d, f.Wbar, S, A, B, f.D, f.nsB, f.gpart, f.beta_part, slots, f.big_scratch, s);
+            else launch_phase_B(d, f.Wbar, S, A, B, f.D, f.nsB, f.gpart, f.beta_part, s);
         }
         launch_update_wrapper(B, d.nbj, d.b, f.gpart, f.nsB, f.beta_part, d.nblocks, nullptr, nullptr, s);
-        launch_wrapper_grams(d, A, B, f.D, f.colnorm2, f.fro2A, f.AtA, f.K, f.fro2K, s);
+        if (big) launch_big_wrapper_grams(d, A, B, f.D, f.colnorm2, f.fro2A, f.AtA, f.K, f.fro2K, s);
+        else launch_wrapper_grams(d, A, B, f.D, f.colnorm2, f.fro2A, f.AtA, f.K, f.fro2K, s);
         launch_finalize_betaW(f.fro2A, d.nbi, f.fro2K, d.nbj, f.scalars, s);
-        // W' step fused with the core gradient at the updated core; then the sparse-core step (Alg. 3)
-        {
+        if (unstructured) {
+            // Sec. 4.5: continuous step only.  W' step on the kept entries, no core-gradient follow-up.
             ProfScope ps(ARMOR_PROF_PHASE_WS, s);
-            launch_phase_WS(d, f.Wbar, S, A, B, f.D, f.AtA, f.K, mask, mask_group, f.scalars, f.G, f.loss_part2,
-                            chain_slots(d.b), s);
-        }
-        {
-            ProfScope ps(ARMOR_PROF_SPARSE, s);
-            launch_sparse_step(d, f.G, S, mask, f.K, f.colnorm2, N, M, o.selection, o.seed, t, f.loss_part2,
-                               loss_cont_trace ? loss_cont_trace + (t - 1) : nullptr, s);
+            if (big) launch_big_phase_WS(d, f.Wbar, S, A, B, f.D, f.AtA, f.K, mask, mask_group, f.scalars, nullptr,
+                                         nullptr, false, slots, f.big_scratch, s);
+            else launch_phase_G(d, f.Wbar, S, A, B, f.D, mask, mask_group, f.scalars, nullptr, nullptr, 0, slots, s);
+        } else {
+            // W' step fused with the core gradient at the updated core; then the sparse-core step (Alg. 3)
+            {
+                ProfScope ps(ARMOR_PROF_PHASE_WS, s);
+                if (big) launch_big_phase_WS(d, f.Wbar, S, A, B, f.D, f.AtA, f.K, mask, mask_group, f.scalars, f.G,
+                                             f.loss_part2, true, slots, f.big_scratch, s);
+                else launch_phase_WS(d, f.Wbar, S, A, B, f.D, f.AtA, f.K, mask, mask_group, f.scalars, f.G,
+                                     f.loss_part2, slots, s);
+            }
+            {
+                ProfScope ps(ARMOR_PROF_SPARSE, s);
+                launch_sparse_step(d, f.G, S, mask, f.K, f.colnorm2, N, M, o.selection, o.seed, t, f.loss_part2,
+                                   loss_cont_trace ? loss_cont_trace + (t - 1) : nullptr, s);
+            }
         }
         if ((t & 15) == 0) {
             st = check_hip();
@@ -387,9 +418,12 @@ armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const flo
         }
     }
     if (loss_trace) {
-        launch_phase_A(d, f.Wbar, S, A, B, f.D, f.nsA, nullptr, nullptr, f.loss_part, true, s);
+        run_phase_A(true);
         launch_sum_to_double(f.loss_part, d.nblocks, loss_trace + n_iters, s);
     }
+    if (unstructured && loss_trace && loss_cont_trace && n_iters > 0 &&
+        hipMemcpyAsync(loss_cont_trace, loss_trace + 1, sizeof(double) * n_iters, hipMemcpyDeviceToDevice, s) != hipSuccess)
+        return check_hip(); // no sparse step: the loss after the continuous step is the loss of the iterate
     if (o.denormalize) launch_denormalize(A, B, r1p, r2p, d_out, d_in, d.b, s);
     return check_hip();
 }

@@ -37,6 +37,21 @@ void launch_phase_WS(const Dims &d, const float *Wbar, float *C, const float *A,
                      float *Gout, float *loss_part, int grid_cap, hipStream_t s);
 int chain_max_nsplit();
 
+// ---- the same chains on 128 x 128 sub-tiles for d_block = 256 (chain_big.hip) ------------------
+// scratch: big_scratch_floats(d, grid_cap) floats; grid_cap bounds the number of workgroups.
+size_t big_scratch_floats(const Dims &d, int max_wgs);
+void launch_big_phase_A(const Dims &d, const float *Wbar, const float *C, const float *A, const float *B,
+                        const float *D, int nsplit, float *gpart, float *beta_part, float *loss_part, bool loss_only,
+                        int grid_cap, float *scratch, hipStream_t s);
+void launch_big_phase_B(const Dims &d, const float *Wbar, const float *C, const float *A, const float *B,
+                        const float *D, int nsplit, float *gpart, float *beta_part, int grid_cap, float *scratch,
+                        hipStream_t s);
+void launch_big_phase_WS(const Dims &d, const float *Wbar, float *C, const float *A, const float *B, const float *D,
+                         const float *AtA, const float *K, const uint8_t *mask, int mask_group, const double *scalars,
+                         float *Gout, float *loss_part, bool fused, int grid_cap, float *scratch, hipStream_t s);
+void launch_big_wrapper_grams(const Dims &d, const float *A, const float *B, const float *D, float *colnorm2,
+                              float *fro2A, float *AtA, float *K, float *fro2K, hipStream_t s);
+
 // ---- small kernels (small.hip) ----------------------------------------------------------------
 void launch_colnorm(const void *W, int bf16, int64_t d_out, int64_t d_in, float *partial, int nchunk, float *r1,
                     hipStream_t s);
@@ -59,7 +74,7 @@ void launch_denormalize(float *A, float *B, const float *r1, const float *r2, in
 void launch_pack_nm(const float *S, const uint8_t *mask, int64_t d_out, int64_t d_in, int N, int M, void *values,
                     int bf16, uint8_t *meta, hipStream_t s);
 void launch_unstructured_init(const float *Wbar, const float *D, int64_t d_out, int64_t d_in, int64_t keep,
-                              float *C, uint8_t *mask, void *ws, hipStream_t s);
+                              float *C, uint8_t *mask, uint32_t *score_buf, void *ws, hipStream_t s);
 size_t unstructured_init_ws_bytes(int64_t d_out, int64_t d_in);
 
 // ---- Gram (gram.hip) --------------------------------------------------------------------------

@@ -1,0 +1,362 @@
+// Chains for wrapper blocks larger than one LDS tile (d_block = 256): the same products as
+// chain.hip, computed on 128 x 128 sub-tiles.  A b x b operand no longer fits in LDS (256 KB), so
+// the intermediates of a block (S or S', R D, U, Delta, V) live in a per-workgroup scratch area in
+// global memory that is written and re-read by the same workgroup only and therefore stays in
+// L2; every sub-product streams its two operand sub-tiles through the two LDS tile slots.
+// At b = 256 each product has 64 flop/B of arithmetic intensity even unfused, so the extra L2
+// round trips cost little against the fp32 MFMA time.
+#include "chain_common.h"
+
+#include <algorithm>
+
+namespace armor {
+
+namespace {
+
+constexpr int TB = 128; // sub-tile edge
+using CH = Chain<TB>;
+
+// acc over the NS inner sub-tiles of  op(L) (pt, :) * op(R) (:, qt)  for every output sub-tile,
+// then epi(pt, qt, acc).  L, R: b x b row-major with leading dimensions ldl, ldr (global memory;
+// may be this workgroup's scratch: the leading barrier orders its earlier stores before the loads).
+template <int NS, bool LT, bool RT, bool SCALE, class Epi>
+__device__ __forceinline__ void big_mma(Smem<TB> &sm, int tid, const CH::Pos &p, const float *__restrict__ L, int ldl,
+                                        const float *__restrict__ R, int ldr, const float *__restrict__ Dk,
+                                        Epi &&epi) {
+    for (int pt = 0; pt < NS; ++pt)
+        for (int qt = 0; qt < NS; ++qt) {
+            CH::Acc acc;
+            acc.zero();
+            for (int rt = 0; rt < NS; ++rt) {
+                const float *Ls = LT ? L + (rt * TB) * ldl + pt * TB : L + (pt * TB) * ldl + rt * TB;
+                const float *Rs = RT ? R + (qt * TB) * ldr + rt * TB : R + (rt * TB) * ldr + qt * TB;
+                __syncthreads();
+                CH::load_tile(sm.X, Ls, ldl, tid);
+                CH::load_tile(sm.Y, Rs, ldr, tid);
+                if (SCALE && tid < TB) sm.Dl[tid] = Dk[rt * TB + tid];
+                __syncthreads();
+                CH::template mma<LT, RT, SCALE>(acc, sm.X, sm.Y, sm.Dl, p);
+            }
+            epi(pt, qt, acc);
+        }
+}
+
+// visit every accumulator element of output sub-tile (pt, qt): f(off, value&) with off the element
+// offset in a row-major matrix of leading dimension ld
+template <class F>
+__device__ __forceinline__ void for_acc(CH::Acc &acc, const CH::Pos &p, int pt, int qt, int ld, F &&f) {
+    const int base = opaque((pt * TB + p.wm0 + p.kh * 4) * ld + qt * TB + p.wn0 + p.l32);
+#pragma unroll
+    for (int tm = 0; tm < CH::TM; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < CH::TN; ++tn)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) f(base + CH::Pos::unif_off(tm, tn, r, ld), acc.v[tm][tn][r], tm, tn, r);
+}
+
+// ---- A-phase (see chain.hip) -------------------------------------------------------------------
+template <int NS, bool LOSS_ONLY>
+__global__ __launch_bounds__(CH::NT) void big_phase_A_kernel(
+    const float *__restrict__ Wbar, const float *__restrict__ C, const float *__restrict__ A,
+    const float *__restrict__ Bw, const float *__restrict__ D, int64_t d_in, int nbj, int nsplit, int nitems,
+    float *__restrict__ gpart, float *__restrict__ beta_part, float *__restrict__ loss_part,
+    float *__restrict__ scratch) {
+    constexpr int b = NS * TB;
+    __shared__ Smem<TB> sm;
+    const int tid = threadIdx.x;
+    const CH::Pos p(tid);
+    const int ldw = (int)d_in;
+    float *s0 = scratch + (int64_t)blockIdx.x * 2 * b * b, *s1 = s0 + b * b;
+    const int chunk = (nbj + nsplit - 1) / nsplit;
+    for (int item = blockIdx.x; item < nitems; item += gridDim.x) { // item = (row block i, chunk c)
+    const int i = item / nsplit, c = item % nsplit;
+    const int j0 = c * chunk, j1 = min(nbj, j0 + chunk);
+    float *gp = gpart + (int64_t)item * b * b;
+    const float *Ai = A + (int64_t)i * b * b;
+    for (int j = j0; j < j1; ++j) {
+        const float *Cij = C + (int64_t)i * b * d_in + (int64_t)j * b;
+        const float *Wij = Wbar + (int64_t)i * b * d_in + (int64_t)j * b;
+        const float *Bj = Bw + (int64_t)j * b * b, *Dj = D + (int64_t)j * b;
+        big_mma<NS, false, false, false>(sm, tid, p, Cij, ldw, Bj, b, nullptr, [&](int pt, int qt, CH::Acc &acc) {
+            for_acc(acc, p, pt, qt, b, [&](int off, float v, int, int, int) { s0[off] = v; }); // S = C B
+        });
+        float lsum = 0.f;
+        big_mma<NS, false, false, false>(sm, tid, p, Ai, b, s0, b, nullptr, [&](int pt, int qt, CH::Acc &acc) {
+            const int wbase = opaque((pt * TB + p.wm0 + p.kh * 4) * ldw + qt * TB + p.wn0 + p.l32);
+#pragma unroll
+            for (int tm = 0; tm < CH::TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < CH::TN; ++tn) {
+                    const float dj = Dj[qt * TB + p.col(tn)];
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        float res = Wij[wbase + CH::Pos::unif_off(tm, tn, r, ldw)] - acc.v[tm][tn][r];
+                        lsum += res * res * dj;
+                        acc.v[tm][tn][r] = res * dj;
+                    }
+                }
+            if (!LOSS_ONLY) for_acc(acc, p, pt, qt, b, [&](int off, float v, int, int, int) { s1[off] = v; });
+        });
+        float ltot = CH::block_sum(lsum, sm.red, tid);
+        if (tid == 0) loss_part[i * nbj + j] = ltot;
+        if (!LOSS_ONLY) {
+            const bool first = j == j0;
+            big_mma<NS, false, true, false>(sm, tid, p, s1, b, s0, b, nullptr, [&](int pt, int qt, CH::Acc &acc) {
+                for_acc(acc, p, pt, qt, b, [&](int off, float v, int, int, int) {
+                    gp[off] = (first ? 0.f : gp[off]) - 2.f * v; // += -2 (R D) S^T, same workgroup, fixed order
+                });
+            });
+            float f2 = 0.f;
+            big_mma<NS, false, true, true>(sm, tid, p, s0, b, s0, b, Dj, [&](int, int, CH::Acc &acc) {
+#pragma unroll
+                for (int tm = 0; tm < CH::TM; ++tm)
+#pragma unroll
+                    for (int tn = 0; tn < CH::TN; ++tn)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) f2 += acc.v[tm][tn][r] * acc.v[tm][tn][r];
+            });
+            float ftot = CH::block_sum(f2, sm.red, tid);
+            if (tid == 0) beta_part[i * nbj + j] = sqrtf(ftot);
+        }
+    }
+    }
+}
+
+// ---- B-phase -----------------------------------------------------------------------------------
+template <int NS>
+__global__ __launch_bounds__(CH::NT) void big_phase_B_kernel(
+    const float *__restrict__ Wbar, const float *__restrict__ C, const float *__restrict__ A,
+    const float *__restrict__ Bw, const float *__restrict__ D, int64_t d_in, int nbi, int nbj, int nsplit,
+    int nitems, float *__restrict__ gpart, float *__restrict__ beta_part, float *__restrict__ scratch) {
+    constexpr int b = NS * TB;
+    __shared__ Smem<TB> sm;
+    const int tid = threadIdx.x;
+    const CH::Pos p(tid);
+    const int ldw = (int)d_in;
+    float *s0 = scratch + (int64_t)blockIdx.x * 2 * b * b, *s1 = s0 + b * b;
+    const int chunk = (nbi + nsplit - 1) / nsplit;
+    for (int item = blockIdx.x; item < nitems; item += gridDim.x) { // item = (column block j, chunk c)
+    const int j = item / nsplit, c = item % nsplit;
+    const int i0 = c * chunk, i1 = min(nbi, i0 + chunk);
+    float *gp = gpart + (int64_t)item * b * b;
+    const float *Bj = Bw + (int64_t)j * b * b, *Dj = D + (int64_t)j * b;
+    float dn2 = 0.f;
+    if (tid == 0)
+        for (int q = 0; q < b; ++q) dn2 += Dj[q] * Dj[q];
+    for (int i = i0; i < i1; ++i) {
+        const float *Cij = C + (int64_t)i * b * d_in + (int64_t)j * b;
+        const float *Wij = Wbar + (int64_t)i * b * d_in + (int64_t)j * b;
+        const float *Ai = A + (int64_t)i * b * b;
+        big_mma<NS, false, false, false>(sm, tid, p, Ai, b, Cij, ldw, nullptr, [&](int pt, int qt, CH::Acc &acc) {
+            for_acc(acc, p, pt, qt, b, [&](int off, float v, int, int, int) { s0[off] = v; }); // S' = A C
+        });
+        big_mma<NS, false, false, false>(sm, tid, p, s0, b, Bj, b, nullptr, [&](int pt, int qt, CH::Acc &acc) {
+            const int wbase = opaque((pt * TB + p.wm0 + p.kh * 4) * ldw + qt * TB + p.wn0 + p.l32);
+#pragma unroll
+            for (int tm = 0; tm < CH::TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < CH::TN; ++tn) {
+                    const float dj = Dj[qt * TB + p.col(tn)];
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        acc.v[tm][tn][r] = (Wij[wbase + CH::Pos::unif_off(tm, tn, r, ldw)] - acc.v[tm][tn][r]) * dj;
+                }
+            for_acc(acc, p, pt, qt, b, [&](int off, float v, int, int, int) { s1[off] = v; }); // R D
+        });
+        const bool first = i == i0;
+        big_mma<NS, true, false, false>(sm, tid, p, s0, b, s1, b, nullptr, [&](int pt, int qt, CH::Acc &acc) {
+            for_acc(acc, p, pt, qt, b, [&](int off, float v, int, int, int) {
+                gp[off] = (first ? 0.f : gp[off]) - 2.f * v; // += -2 S'^T (R D)
+            });
+        });
+        float f2 = 0.f;
+        big_mma<NS, true, false, false>(sm, tid, p, s0, b, s0, b, nullptr, [&](int, int, CH::Acc &acc) {
+#pragma unroll
+            for (int tm = 0; tm < CH::TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < CH::TN; ++tn)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) f2 += acc.v[tm][tn][r] * acc.v[tm][tn][r];
+        });
+        float ftot = CH::block_sum(f2, sm.red, tid);
+        if (tid == 0) beta_part[i * nbj + j] = sqrtf(ftot) * sqrtf(dn2);
+    }
+    }
+}
+
+// ---- W' step (FUSED = false) or W' step + core gradient at the updated core (FUSED = true) --------
+template <int NS, bool FUSED>
+__global__ __launch_bounds__(CH::NT) void big_phase_WS_kernel(
+    const float *__restrict__ Wbar, float *__restrict__ C, const float *__restrict__ A,
+    const float *__restrict__ Bw, const float *__restrict__ D, const float *__restrict__ AtA,
+    const float *__restrict__ K, const uint8_t *__restrict__ mask, int mask_group,
+    const double *__restrict__ scalars, int64_t d_in, int nbj, int nblocks, float *__restrict__ Gout,
+    float *__restrict__ loss_part, float *__restrict__ scratch) {
+    constexpr int b = NS * TB;
+    __shared__ Smem<TB> sm;
+    const int tid = threadIdx.x;
+    const CH::Pos p(tid);
+    const int ldw = (int)d_in;
+    const double bw = scalars[2];
+    const float eta2 = bw > 0.0 ? (float)(2.0 / bw) : 0.f;
+    const int64_t mrow = d_in / mask_group;
+    float *s0 = scratch + (int64_t)blockIdx.x * 2 * b * b, *s1 = s0 + b * b;
+    for (int blk = blockIdx.x; blk < nblocks; blk += gridDim.x) {
+        const int i = blk / nbj, j = blk % nbj;
+        float *Cij = C + (int64_t)i * b * d_in + (int64_t)j * b;
+        const float *Wij = Wbar + (int64_t)i * b * d_in + (int64_t)j * b;
+        const float *Ai = A + (int64_t)i * b * b, *Bj = Bw + (int64_t)j * b * b, *Dj = D + (int64_t)j * b;
+        float *Gij = FUSED ? Gout + (int64_t)i * b * d_in + (int64_t)j * b : nullptr;
+        big_mma<NS, false, false, false>(sm, tid, p, Ai, b, Cij, ldw, nullptr, [&](int pt, int qt, CH::Acc &acc) {
+            for_acc(acc, p, pt, qt, b, [&](int off, float v, int, int, int) { s0[off] = v; }); // S' = A C
+        });
+        float lsum = 0.f;
+        big_mma<NS, false, false, false>(sm, tid, p, s0, b, Bj, b, nullptr, [&](int pt, int qt, CH::Acc &acc) {
+            const int wbase = opaque((pt * TB + p.wm0 + p.kh * 4) * ldw + qt * TB + p.wn0 + p.l32);
+#pragma unroll
+            for (int tm = 0; tm < CH::TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < CH::TN; ++tn) {
+                    const float dj = Dj[qt * TB + p.col(tn)];
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        float res = Wij[wbase + CH::Pos::unif_off(tm, tn, r, ldw)] - acc.v[tm][tn][r];
+                        lsum += res * res * dj;
+                        acc.v[tm][tn][r] = res * dj;
+                    }
+                }
+            for_acc(acc, p, pt, qt, b, [&](int off, float v, int, int, int) { s1[off] = v; }); // R D
+        });
+        big_mma<NS, false, true, false>(sm, tid, p, s1, b, Bj, b, nullptr, [&](int pt, int qt, CH::Acc &acc) {
+            for_acc(acc, p, pt, qt, b, [&](int off, float v, int, int, int) { s0[off] = v; }); // U = (R D) B^T
+        });
+        float dd = 0.f;
+        big_mma<NS, true, false, false>(sm, tid, p, Ai, b, s0, b, nullptr, [&](int pt, int qt, CH::Acc &acc) {
+            // G = A^T U: W' step on kept entries; Delta -> s1, raw G -> Gout (fused mode)
+            const int cbase = opaque((pt * TB + p.wm0 + p.kh * 4) * ldw + qt * TB + p.wn0 + p.l32);
+            const int sbase = opaque((pt * TB + p.wm0 + p.kh * 4) * b + qt * TB + p.wn0 + p.l32);
+#pragma unroll
+            for (int tm = 0; tm < CH::TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < CH::TN; ++tn) {
+                    const int64_t gcol = (int64_t)j * b + qt * TB + p.col(tn);
+                    const int sh = (int)(gcol % mask_group);
+                    const uint8_t *mp = mask + ((int64_t)i * b + pt * TB + p.wm0 + p.kh * 4) * mrow + gcol / mask_group;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const uint32_t mb = mp[(int64_t)(tm * 32 + (r >> 2) * 8 + (r & 3)) * mrow];
+                        const bool kp = (mb >> sh) & 1u;
+                        const float g = acc.v[tm][tn][r], dl = kp ? g : 0.f;
+                        dd += dl * dl;
+                        if (kp) {
+                            float *cp = Cij + cbase + CH::Pos::unif_off(tm, tn, r, ldw);
+                            *cp = *cp + eta2 * dl;
+                        }
+                        if (FUSED) {
+                            s1[sbase + CH::Pos::unif_off(tm, tn, r, b)] = dl;
+                            Gij[cbase + CH::Pos::unif_off(tm, tn, r, ldw)] = g;
+                        }
+                    }
+                }
+        });
+        if (FUSED) {
+            big_mma<NS, false, false, false>(sm, tid, p, s1, b, K + (int64_t)j * b * b, b, nullptr,
+                                             [&](int pt, int qt, CH::Acc &acc) {
+                for_acc(acc, p, pt, qt, b, [&](int off, float v, int, int, int) { s0[off] = v; }); // V = Delta K
+            });
+            float dz = 0.f;
+            big_mma<NS, false, false, false>(sm, tid, p, AtA + (int64_t)i * b * b, b, s0, b, nullptr,
+                                             [&](int pt, int qt, CH::Acc &acc) {
+                // Z = (A^T A) V:  G_new = G - eta Z;  <Delta, Z>
+                const int cbase = opaque((pt * TB + p.wm0 + p.kh * 4) * ldw + qt * TB + p.wn0 + p.l32);
+                const int sbase = opaque((pt * TB + p.wm0 + p.kh * 4) * b + qt * TB + p.wn0 + p.l32);
+#pragma unroll
+                for (int tm = 0; tm < CH::TM; ++tm)
+#pragma unroll
+                    for (int tn = 0; tn < CH::TN; ++tn)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            float *gp = Gij + cbase + CH::Pos::unif_off(tm, tn, r, ldw);
+                            const float z = acc.v[tm][tn][r];
+                            dz += s1[sbase + CH::Pos::unif_off(tm, tn, r, b)] * z;
+                            *gp = -2.f * (*gp - eta2 * z);
+                        }
+            });
+            float ltot = CH::block_sum(lsum - 2.f * eta2 * dd + eta2 * eta2 * dz, sm.red, tid);
+            if (tid == 0) loss_part[blk] = ltot;
+        }
+    }
+}
+
+// ---- wrapper Grams -----------------------------------------------------------------------------
+template <int NS>
+__global__ __launch_bounds__(CH::NT) void big_wrapper_grams_kernel(
+    const float *__restrict__ A, const float *__restrict__ Bw, const float *__restrict__ D, int nbi,
+    float *__restrict__ colnorm2, float *__restrict__ fro2A, float *__restrict__ AtA, float *__restrict__ K,
+    float *__restrict__ fro2K) {
+    constexpr int b = NS * TB;
+    __shared__ Smem<TB> sm;
+    const int tid = threadIdx.x;
+    const CH::Pos p(tid);
+    const bool isA = (int)blockIdx.x < nbi;
+    const int idx = isA ? blockIdx.x : blockIdx.x - nbi;
+    const float *src = (isA ? A : Bw) + (int64_t)idx * b * b;
+    float *dst = (isA ? AtA : K) + (int64_t)idx * b * b;
+    float f2 = 0.f;
+    auto epi = [&](int pt, int qt, CH::Acc &acc) {
+        for_acc(acc, p, pt, qt, b, [&](int off, float v, int, int, int) {
+            f2 += v * v;
+            dst[off] = v;
+            if (isA && off / b == off % b) colnorm2[(int64_t)idx * b + off / b] = v;
+        });
+    };
+    if (isA) big_mma<NS, true, false, false>(sm, tid, p, src, b, src, b, nullptr, epi);          // A^T A
+    else     big_mma<NS, false, true, true>(sm, tid, p, src, b, src, b, D + (int64_t)idx * b, epi); // (B D) B^T
+    float ftot = CH::block_sum(f2, sm.red, tid);
+    if (tid == 0) (isA ? fro2A : fro2K)[idx] = ftot;
+}
+
+} // namespace
+
+size_t big_scratch_floats(const Dims &d, int max_wgs) { return (size_t)max_wgs * 2 * d.b * d.b; }
+
+void launch_big_phase_A(const Dims &d, const float *Wbar, const float *C, const float *A, const float *B,
+                        const float *D, int nsplit, float *gpart, float *beta_part, float *loss_part, bool loss_only,
+                        int grid_cap, float *scratch, hipStream_t s) {
+    const int nitems = d.nbi * nsplit;
+    dim3 grid(std::min(nitems, grid_cap)), block(CH::NT);
+    if (loss_only)
+        hipLaunchKernelGGL((big_phase_A_kernel<2, true>), grid, block, 0, s, Wbar, C, A, B, D, d.d_in, d.nbj, nsplit,
+                           nitems, gpart, beta_part, loss_part, scratch);
+    else
+        hipLaunchKernelGGL((big_phase_A_kernel<2, false>), grid, block, 0, s, Wbar, C, A, B, D, d.d_in, d.nbj, nsplit,
+                           nitems, gpart, beta_part, loss_part, scratch);
+}
+
+void launch_big_phase_B(const Dims &d, const float *Wbar, const float *C, const float *A, const float *B,
+                        const float *D, int nsplit, float *gpart, float *beta_part, int grid_cap, float *scratch,
+                        hipStream_t s) {
+    const int nitems = d.nbj * nsplit;
+    hipLaunchKernelGGL((big_phase_B_kernel<2>), dim3(std::min(nitems, grid_cap)), dim3(CH::NT), 0, s, Wbar, C, A, B, D,
+                       d.d_in, d.nbi, d.nbj, nsplit, nitems, gpart, beta_part, scratch);
+}
+
+void launch_big_phase_WS(const Dims &d, const float *Wbar, float *C, const float *A, const float *B, const float *D,
+                         const float *AtA, const float *K, const uint8_t *mask, int mask_group, const double *scalars,
+                         float *Gout, float *loss_part, bool fused, int grid_cap, float *scratch, hipStream_t s) {
+    dim3 grid(std::min(d.nblocks, grid_cap)), block(CH::NT);
+    if (fused)
+        hipLaunchKernelGGL((big_phase_WS_kernel<2, true>), grid, block, 0, s, Wbar, C, A, B, D, AtA, K, mask,
+                           mask_group, scalars, d.d_in, d.nbj, d.nblocks, Gout, loss_part, scratch);
+    else
+        hipLaunchKernelGGL((big_phase_WS_kernel<2, false>), grid, block, 0, s, Wbar, C, A, B, D, AtA, K, mask,
+                           mask_group, scalars, d.d_in, d.nbj, d.nblocks, Gout, loss_part, scratch);
+}
+
+void launch_big_wrapper_grams(const Dims &d, const float *A, const float *B, const float *D, float *colnorm2,
+                              float *fro2A, float *AtA, float *K, float *fro2K, hipStream_t s) {
+    hipLaunchKernelGGL((big_wrapper_grams_kernel<2>), dim3(d.nbi + d.nbj), dim3(CH::NT), 0, s, A, B, D, d.nbi,
+                       colnorm2, fro2A, AtA, K, fro2K);
+}
+
+} // namespace armor

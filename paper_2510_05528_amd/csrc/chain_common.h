@@ -1,0 +1,189 @@
+// Building blocks shared by the chain kernels: wave tiling, LDS tile movement and the LDS-resident
+// fp32 MFMA product (v_mfma_f32_32x32x2_f32) on b x (b+1) tiles.  gfx950 only.
+#pragma once
+#include "armor_internal.h"
+
+namespace armor {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+// Hides a per-lane offset from loop-invariant code motion: without it the compiler hoists every
+// unrolled address of the epilogues out of the block loop and keeps hundreds of them live across
+// the matrix products (spilling accumulators), instead of re-deriving each with one add.
+__device__ __forceinline__ int opaque(int x) {
+    asm volatile("" : "+v"(x));
+    return x;
+}
+
+template <int B> struct Cfg;
+template <> struct Cfg<32>  { static constexpr int WM = 1, WN = 1, TM = 1, TN = 1; };
+template <> struct Cfg<64>  { static constexpr int WM = 2, WN = 2, TM = 1, TN = 1; };
+// 8 waves at b = 128, each owning a 64 x 32 patch: two waves share a SIMD, so one wave's LDS reads
+// and address arithmetic overlap the other's MFMA issue (measured: same loop rate as 4 waves of
+// 64 x 64 or 16 waves of 32 x 32, but the only shape that leaves registers for operand prefetch).
+template <> struct Cfg<128> { static constexpr int WM = 2, WN = 4, TM = 2, TN = 1; };
+
+template <int B> struct Chain {
+    static constexpr int WM = Cfg<B>::WM, WN = Cfg<B>::WN, TM = Cfg<B>::TM, TN = Cfg<B>::TN;
+    static constexpr int NW = WM * WN, NT = NW * 64, P = B + 1;
+    static constexpr int TILE_FLOATS = B * P;
+    static_assert(WM * TM * 32 == B && WN * TN * 32 == B, "wave tiling must cover the block");
+
+    struct Acc {
+        floatx16 v[TM][TN];
+        __device__ void zero() {
+#pragma unroll
+            for (int a = 0; a < TM; ++a)
+#pragma unroll
+                for (int c = 0; c < TN; ++c)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) v[a][c][r] = 0.f;
+        }
+    };
+
+    // position of this lane's accumulator element r of sub-tile (tm,tn) inside the b x b block
+    struct Pos {
+        int wm0, wn0, l32, kh;
+        __device__ Pos(int tid) {
+            int w = tid >> 6, lane = tid & 63;
+            wm0 = (w % WM) * TM * 32;
+            wn0 = (w / WM) * TN * 32;
+            l32 = lane & 31;
+            kh = lane >> 5;
+        }
+        __device__ int row(int tm, int r) const { return wm0 + tm * 32 + (r >> 2) * 8 + kh * 4 + (r & 3); }
+        __device__ int col(int tn) const { return wn0 + tn * 32 + l32; }
+        // 32-bit element offset of accumulator element (tm,tn,r) in a row-major matrix of leading
+        // dimension ld, split into a per-lane part and a wave-uniform part so that the address is
+        // "uniform base + one VGPR" and nothing 64-bit per element stays live.
+        __device__ int lane_off(int ld) const { return (wm0 + kh * 4) * ld + wn0 + l32; }
+        __device__ static int unif_off(int tm, int tn, int r, int ld) {
+            return (tm * 32 + (r >> 2) * 8 + (r & 3)) * ld + tn * 32;
+        }
+    };
+
+    // global (row-major, leading dimension ld) -> registers -> LDS tile, in two halves so that the
+    // global loads of the next operand can stay in flight underneath a matrix product.
+    static constexpr int PER = B * B / 4 / NT;
+    static_assert((B * B / 4) % NT == 0, "tile load must divide evenly");
+    struct TileRegs { float4 v[PER]; };
+
+    // Loader lane mapping: every group of 32 lanes covers 4 rows x 8 float4 columns, so a global
+    // load instruction still reads whole 128-byte lines while the four scalar LDS writes of a
+    // float4 (stride 16 B across lanes of a row, +1 bank per row with the odd pitch) hit 32
+    // different banks.
+    static constexpr int ROWS_PER_IT = NT / (B / 4); // tile rows covered by one pass of the workgroup
+    __device__ static __forceinline__ int loader_row(int tid) { return ((tid >> 5) / (B / 32)) * 4 + ((tid & 31) >> 3); }
+    __device__ static __forceinline__ int loader_c4(int tid) { return ((tid >> 5) % (B / 32)) * 8 + (tid & 7); }
+
+    __device__ static __forceinline__ void gload_tile(TileRegs &t, const float *__restrict__ g, int ld, int tid) {
+        const int off0 = opaque(loader_row(tid) * ld + loader_c4(tid) * 4);
+#pragma unroll
+        for (int it = 0; it < PER; ++it)
+            t.v[it] = *reinterpret_cast<const float4 *>(g + (off0 + it * ROWS_PER_IT * ld));
+    }
+
+    __device__ static __forceinline__ void lstore_tile(float *T, const TileRegs &t, int tid) {
+        float *d0 = T + opaque(loader_row(tid) * P + loader_c4(tid) * 4);
+#pragma unroll
+        for (int it = 0; it < PER; ++it) {
+            float *d = d0 + it * ROWS_PER_IT * P;
+            d[0] = t.v[it].x; d[1] = t.v[it].y; d[2] = t.v[it].z; d[3] = t.v[it].w;
+        }
+    }
+
+    __device__ static void load_tile(float *T, const float *__restrict__ g, int ld, int tid) {
+        TileRegs t;
+        gload_tile(t, g, ld, tid);
+        lstore_tile(T, t, tid);
+    }
+
+    __device__ static void store_acc(float *T, const Acc &acc, const Pos &p) {
+        float *d0 = T + opaque(p.lane_off(P));
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) d0[Pos::unif_off(tm, tn, r, P)] = acc.v[tm][tn][r];
+    }
+
+    // acc += op(L) * op(R) over the b inner indices.  op(L)(m,k) = LT ? L[k][m] : L[m][k];
+    // op(R)(k,n) = RT ? R[n][k] : R[k][n];  SCALE multiplies op(L)(m,k) by Dk[k].
+    // Operands are fetched one group of G k-steps ahead of the MFMAs that consume them (two
+    // register sets), so LDS latency is covered by the wave's own matrix work.
+    static constexpr int G = 2;
+    struct Frag { float a[G][TM], b[G][TN]; };
+
+    template <bool LT, bool RT, bool SCALE>
+    __device__ static __forceinline__ void fetch(Frag &f, int k0, const float *__restrict__ L,
+                                                 const float *__restrict__ R, const float *__restrict__ Dk,
+                                                 const Pos &p) {
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            int kk = k0 + 2 * g + p.kh;
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm) {
+                int m = p.wm0 + tm * 32 + p.l32;
+                f.a[g][tm] = LT ? L[kk * P + m] : L[m * P + kk];
+            }
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn) {
+                int n = p.wn0 + tn * 32 + p.l32;
+                f.b[g][tn] = RT ? R[n * P + kk] : R[kk * P + n];
+            }
+            if (SCALE) {
+                float dk = Dk[kk];
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm) f.a[g][tm] *= dk;
+            }
+        }
+    }
+
+    __device__ static __forceinline__ void issue(Acc &acc, const Frag &f) {
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn)
+                    acc.v[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a[g][tm], f.b[g][tn], acc.v[tm][tn], 0, 0, 0);
+    }
+
+    template <bool LT, bool RT, bool SCALE>
+    __device__ static void mma(Acc &acc, const float *__restrict__ L, const float *__restrict__ R,
+                               const float *__restrict__ Dk, const Pos &p) {
+        static_assert(B % (4 * G) == 0, "two groups per trip");
+        Frag f0, f1;
+        fetch<LT, RT, SCALE>(f0, 0, L, R, Dk, p);
+#pragma unroll 1
+        for (int k = 0; k < B; k += 4 * G) {
+            fetch<LT, RT, SCALE>(f1, k + 2 * G, L, R, Dk, p);
+            issue(acc, f0);
+            if (k + 4 * G < B) fetch<LT, RT, SCALE>(f0, k + 4 * G, L, R, Dk, p);
+            issue(acc, f1);
+        }
+    }
+
+    // deterministic block-wide sum; result valid in thread 0.  red: NW floats of LDS.
+    __device__ static float block_sum(float v, float *red, int tid) {
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+        __syncthreads();
+        if ((tid & 63) == 0) red[tid >> 6] = v;
+        __syncthreads();
+        float s = 0.f;
+        if (tid == 0)
+            for (int w = 0; w < NW; ++w) s += red[w];
+        return s;
+    }
+};
+
+template <int B> struct Smem {
+    float X[Chain<B>::TILE_FLOATS];
+    float Y[Chain<B>::TILE_FLOATS];
+    float Dl[B];
+    float red[16];
+};
+
+} // namespace armor

@@ -3,6 +3,8 @@
 // denormalisation and N:M packing.  gfx950; 64-wide waves; every reduction has a fixed order.
 #include "armor_internal.h"
 
+#include <algorithm>
+
 namespace armor {
 
 __device__ __forceinline__ float bf16_bits_to_float(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
@@ -473,6 +475,170 @@ void launch_sparse_step(const Dims &d, const float *G, float *C, uint8_t *mask, 
     ARMOR_SPARSE_CASE(1, 8) ARMOR_SPARSE_CASE(2, 8) ARMOR_SPARSE_CASE(3, 8) ARMOR_SPARSE_CASE(4, 8)
     ARMOR_SPARSE_CASE(5, 8) ARMOR_SPARSE_CASE(6, 8) ARMOR_SPARSE_CASE(7, 8)
 #undef ARMOR_SPARSE_CASE
+}
+
+// ------------------------------------------------------------------------------------------------
+// unstructured initial mask (Sec. 4.5; the count-budget optimum of Eq. 2 for the plain core):
+// keep the `keep` largest importances (w*w)*D_j of the whole matrix, equal importances going to
+// the lower linear index.  Exact selection without sorting: the fp32 bit pattern of a
+// non-negative score orders like an unsigned integer, so three histogram passes (11 + 11 + 10
+// bits, integer atomics only) find the bit-exact threshold T and the number r of entries equal
+// to T to admit; an ordered prefix count over the ties admits the r first ones.
+// state[0] = prefix value, state[1] = remaining k, state[2] = r (ties to admit), state[3] = T.
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void us_score_kernel(const float *__restrict__ Wbar, const float *__restrict__ D,
+                                                       int64_t P, int64_t d_in, uint32_t *__restrict__ score) {
+    int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= P) return;
+    float w = Wbar[e];
+    score[e] = __float_as_uint(__fmul_rn(__fmul_rn(w, w), D[e % d_in]));
+}
+
+__global__ __launch_bounds__(256) void us_zero_kernel(uint32_t *__restrict__ hist, int n, uint32_t *__restrict__ state,
+                                                      int64_t keep) {
+    int e = blockIdx.x * 256 + threadIdx.x;
+    if (e < n) hist[e] = 0u;
+    if (e == 0) { state[0] = 0u; state[1] = 0u; state[2] = 0u; state[3] = 0u;
+                  reinterpret_cast<unsigned long long *>(state + 4)[0] = (unsigned long long)keep; }
+}
+
+// histogram of bits [shift, shift+nbits) over the entries whose higher bits equal the prefix
+__global__ __launch_bounds__(256) void us_hist_kernel(const uint32_t *__restrict__ score, int64_t P, int shift,
+                                                      int nbits, const uint32_t *__restrict__ state,
+                                                      uint32_t *__restrict__ hist) {
+    __shared__ uint32_t lh[2048];
+    for (int e = threadIdx.x; e < 2048; e += 256) lh[e] = 0u;
+    __syncthreads();
+    const uint32_t prefix = state[0];
+    const int hi = shift + nbits;
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < P; e += (int64_t)gridDim.x * 256) {
+        uint32_t v = score[e];
+        bool match = hi >= 32 ? true : ((v >> hi) == (prefix >> hi));
+        if (match) atomicAdd(&lh[(v >> shift) & ((1u << nbits) - 1u)], 1u);
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < (1 << nbits); e += 256)
+        if (lh[e]) atomicAdd(&hist[e], lh[e]);
+}
+
+// walk the bins from the top until the remaining budget is met; fix those bits of the threshold
+__global__ void us_select_kernel(uint32_t *__restrict__ hist, int shift, int nbits, uint32_t *__restrict__ state,
+                                 int last) {
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    unsigned long long k = reinterpret_cast<unsigned long long *>(state + 4)[0];
+    uint32_t prefix = state[0];
+    int bin = (1 << nbits) - 1;
+    for (; bin > 0; --bin) {
+        if ((unsigned long long)hist[bin] >= k) break;
+        k -= hist[bin];
+    }
+    prefix |= (uint32_t)bin << shift;
+    state[0] = prefix;
+    reinterpret_cast<unsigned long long *>(state + 4)[0] = k; // budget left inside this bin
+    if (last) {
+        state[3] = prefix;                                       // T
+        unsigned long long ties = hist[bin];
+        state[2] = (uint32_t)(k < ties ? k : ties);              // r: ties to admit (k <= ties unless keep > P)
+    }
+    for (int e = 0; e < (1 << nbits); ++e) hist[e] = 0u;
+}
+
+// one byte of mask (8 consecutive entries) per thread; chunk = 2048 entries per workgroup
+__global__ __launch_bounds__(256) void us_tie_count_kernel(const uint32_t *__restrict__ score, int64_t P,
+                                                           const uint32_t *__restrict__ state,
+                                                           uint32_t *__restrict__ tie_count) {
+    __shared__ uint32_t cnt;
+    if (threadIdx.x == 0) cnt = 0u;
+    __syncthreads();
+    const uint32_t T = state[3];
+    int64_t e0 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 8;
+    uint32_t c = 0;
+    for (int q = 0; q < 8; ++q)
+        if (e0 + q < P && score[e0 + q] == T) ++c;
+    if (c) atomicAdd(&cnt, c);
+    __syncthreads();
+    if (threadIdx.x == 0) tie_count[blockIdx.x] = cnt;
+}
+
+__global__ __launch_bounds__(256) void us_tie_scan_kernel(const uint32_t *__restrict__ tie_count, int64_t nchunks,
+                                                          unsigned long long *__restrict__ tie_offset) {
+    // exclusive prefix sum by one workgroup: each thread owns a contiguous slice
+    __shared__ unsigned long long part[256];
+    const int64_t per = (nchunks + 255) / 256, a = threadIdx.x * per, b = min(nchunks, a + per);
+    unsigned long long s = 0;
+    for (int64_t e = a; e < b; ++e) s += tie_count[e];
+    part[threadIdx.x] = s;
+    __syncthreads();
+    unsigned long long base = 0;
+    for (int t = 0; t < (int)threadIdx.x; ++t) base += part[t];
+    for (int64_t e = a; e < b; ++e) { tie_offset[e] = base; base += tie_count[e]; }
+}
+
+__global__ __launch_bounds__(256) void us_apply_kernel(const float *__restrict__ Wbar, const uint32_t *__restrict__ score,
+                                                       int64_t P, const uint32_t *__restrict__ state,
+                                                       const unsigned long long *__restrict__ tie_offset,
+                                                       float *__restrict__ C, uint8_t *__restrict__ mask) {
+    __shared__ uint32_t wsum[4];
+    const uint32_t T = state[3], r = state[2];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int64_t e0 = ((int64_t)blockIdx.x * 256 + tid) * 8;
+    uint32_t sc[8], c = 0;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        sc[q] = e0 + q < P ? score[e0 + q] : 0xffffffffu;
+        c += (e0 + q < P && sc[q] == T) ? 1u : 0u;
+    }
+    // ordered exclusive prefix of the tie counts inside the workgroup
+    uint32_t incl = c;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        uint32_t o = __shfl_up(incl, off, 64);
+        if (lane >= off) incl += o;
+    }
+    if (lane == 63) wsum[w] = incl;
+    __syncthreads();
+    unsigned long long rank = tie_offset[blockIdx.x] + (incl - c);
+    for (int t = 0; t < w; ++t) rank += wsum[t];
+    if (e0 >= P) return;
+    uint32_t bits = 0;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        if (e0 + q >= P) break;
+        bool keep = sc[q] > T;
+        if (sc[q] == T) { keep = rank < (unsigned long long)r; ++rank; }
+        bits |= keep ? (1u << q) : 0u;
+        C[e0 + q] = keep ? Wbar[e0 + q] : 0.f;
+    }
+    mask[e0 / 8] = (uint8_t)bits;
+}
+
+size_t unstructured_init_ws_bytes(int64_t d_out, int64_t d_in) {
+    int64_t P = d_out * d_in, nchunks = (P + 2047) / 2048;
+    return (size_t)(2048 + 16) * 4 + (size_t)nchunks * (4 + 8) + 1024;
+}
+
+// score_buf: P uint32 of scratch (the caller lends the core-gradient buffer); ws: unstructured_init_ws_bytes
+void launch_unstructured_init(const float *Wbar, const float *D, int64_t d_out, int64_t d_in, int64_t keep,
+                              float *C, uint8_t *mask, uint32_t *score_buf, void *ws, hipStream_t s) {
+    const int64_t P = d_out * d_in, nchunks = (P + 2047) / 2048;
+    char *base = reinterpret_cast<char *>(ws);
+    uint32_t *hist = reinterpret_cast<uint32_t *>(base);
+    uint32_t *state = hist + 2048; // 8 words: [0] prefix [2] r [3] T [4..5] 64-bit budget
+    size_t off = ((size_t)(2048 + 16) * 4 + 255) & ~size_t(255);
+    unsigned long long *tie_offset = reinterpret_cast<unsigned long long *>(base + off);
+    uint32_t *tie_count = reinterpret_cast<uint32_t *>(base + off + (size_t)nchunks * 8);
+    hipLaunchKernelGGL(us_zero_kernel, dim3(8), dim3(256), 0, s, hist, 2048, state, keep);
+    hipLaunchKernelGGL(us_score_kernel, dim3((unsigned)((P + 255) / 256)), dim3(256), 0, s, Wbar, D, P, d_in, score_buf);
+    const int grid = (int)std::min<int64_t>((P + 255) / 256, 4096);
+    const int shifts[3] = {21, 10, 0}, nbits[3] = {11, 11, 10};
+    for (int pass = 0; pass < 3; ++pass) {
+        hipLaunchKernelGGL(us_hist_kernel, dim3(grid), dim3(256), 0, s, score_buf, P, shifts[pass], nbits[pass], state, hist);
+        hipLaunchKernelGGL(us_select_kernel, dim3(1), dim3(64), 0, s, hist, shifts[pass], nbits[pass], state, pass == 2);
+    }
+    hipLaunchKernelGGL(us_tie_count_kernel, dim3((unsigned)nchunks), dim3(256), 0, s, score_buf, P, state, tie_count);
+    hipLaunchKernelGGL(us_tie_scan_kernel, dim3(1), dim3(256), 0, s, tie_count, nchunks, tie_offset);
+    hipLaunchKernelGGL(us_apply_kernel, dim3((unsigned)nchunks), dim3(256), 0, s, Wbar, score_buf, P, state, tie_offset, C,
+                       mask);
 }
 
 // ------------------------------------------------------------------------------------------------

@@ -91,7 +91,7 @@ def test_normalize(armor, torch, orc, d_out, d_in, bf16):
     np.testing.assert_allclose(Wbar.cpu().numpy(), eb, rtol=3e-6, atol=1e-12)
 
 
-@pytest.mark.parametrize("d_out,d_in,b", [(64, 96, 32), (128, 192, 64), (256, 384, 128)])
+@pytest.mark.parametrize("d_out,d_in,b", [(64, 96, 32), (128, 192, 64), (256, 384, 128), (512, 768, 256)])
 def test_proxy_loss(armor, torch, orc, d_out, d_in, b):
     say("proxy_loss", d_out, d_in, b)
     rng = np.random.default_rng(1)
@@ -173,6 +173,52 @@ def test_factorize_general_nm(armor, torch, orc, N, M):
     W, X = make_layer(128, 192, 200, seed=6)
     D = np.diag(orc.gram(X)).astype(np.float32)
     check_factorization(armor, torch, orc, W, D, 64, N, M, 5, seed=4)
+
+
+@pytest.mark.parametrize("d_out,d_in,N,M,iters", [(512, 768, 2, 4, 3), (768, 256, 4, 8, 3)])
+def test_factorize_block256(armor, torch, orc, d_out, d_in, N, M, iters):
+    """d_block = 256 (the 70B-shaped stress config): sub-tiled chains with L2-resident scratch."""
+    W, X = make_layer(d_out, d_in, 300, seed=12, act_outliers=(0.01, 20.0))
+    D = np.diag(orc.gram(X)).astype(np.float32)
+    check_factorization(armor, torch, orc, W, D, 256, N, M, iters, seed=5)
+
+
+@pytest.mark.parametrize("d_out,d_in,b,keep_frac", [(128, 192, 64, 0.5), (256, 256, 128, 0.5), (512, 512, 256, 0.5), (96, 160, 32, 0.3)])
+def test_factorize_unstructured(armor, torch, orc, d_out, d_in, b, keep_frac):
+    """50 % unstructured: global top-k initial mask, continuous step only (Sec. 4.5)."""
+    W, X = make_layer(d_out, d_in, 200, seed=13, act_outliers=(0.01, 20.0))
+    D = np.diag(orc.gram(X)).astype(np.float32)
+    keep = int(d_out * d_in * keep_frac)
+    n_iters = 4
+    say("unstructured", d_out, d_in, b, keep)
+    out = armor.factorize_layer(dev(torch, W), dev(torch, D), b, 2, 4, n_iters, sparsity=1, unstructured_keep=keep,
+                                want_cont_trace=True)
+    torch.cuda.synchronize()
+    ref = orc.factorize_layer(W, D, b, 2, 4, n_iters, sparsity=1, keep=keep)
+    mask = armor.unpack_mask(out["mask_bits"].cpu().numpy(), 8)
+    S = out["S"].cpu().numpy()
+    assert mask.sum() == keep                                   # exact count
+    assert np.all(S[mask == 0] == 0)
+    assert float((mask == ref["mask"]).mean()) >= 0.999
+    tr = out["loss_trace"].cpu().numpy()
+    np.testing.assert_allclose(tr, ref["loss_trace"], rtol=5e-3)
+    np.testing.assert_allclose(out["loss_cont_trace"].cpu().numpy(), tr[1:], rtol=0, atol=0)
+    assert np.all(np.diff(tr) <= 1e-6 * tr[0])
+    for k, rk in (("A", "A"), ("B", "B"), ("S", "C")):
+        assert relfro(out[k].cpu().numpy(), ref[rk]) <= 1e-3, k
+
+
+def test_unstructured_ties_go_to_lower_index(armor, torch, orc):
+    """All-equal importances: the kept set must be exactly the first `keep` entries in row-major order."""
+    d_out, d_in, b = 64, 64, 32
+    W = np.ones((d_out, d_in), dtype=np.float32)
+    D = np.ones(d_in, dtype=np.float32)
+    for keep in (0, 1, 2049, 4095, 4096):
+        out = armor.factorize_layer(dev(torch, W), dev(torch, D), b, 2, 4, 0, sparsity=1, unstructured_keep=keep)
+        mask = armor.unpack_mask(out["mask_bits"].cpu().numpy(), 8).ravel()
+        expect = np.zeros(d_out * d_in, dtype=np.uint8)
+        expect[:keep] = 1
+        np.testing.assert_array_equal(mask, expect)
 
 
 def test_factorize_zero_iterations_is_plain_nm_pruning(armor, torch, orc):
