@@ -78,10 +78,11 @@ def main():
                                 dtype=torch.bfloat16 if x_bf16 else torch.float32)
     H = torch.empty((d_in, d_in), device=dev, dtype=torch.float32)
     ws = torch.empty(armor.factorize_workspace_bytes(d_out, d_in, b, N, M), device=dev, dtype=torch.uint8)
+    gws = torch.empty(max(armor.gram_workspace_bytes(n_tok, d_in, x_bf16), 256), device=dev, dtype=torch.uint8)
     torch.cuda.synchronize()
 
     def step():
-        armor.gram(X, H=H)
+        armor.gram(X, H=H, ws=gws)
         D = armor.gram_diag(H)
         out = armor.factorize_layer(W, D, b, N, M, n_iters, seed=0, ws=ws)
         vals, meta = armor.pack_nm(out["S"], out["mask_bits"], N, M, bf16=True)

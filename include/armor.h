@@ -83,9 +83,14 @@ armor_status armor_profile_read(double *ms_total /*host [ARMOR_PROF_KINDS]*/, in
  *   H   [d_in x d_in] fp32, leading dimension ldh.  accumulate = 0: H = X^T X;  1: H += X^T X,
  *       so a caller can stream token chunks.  Both triangles are written.
  * d_in must be a multiple of 32; n_tokens >= 0 (0 leaves H unchanged / zeroes it).
+ *   ws  optional scratch of armor_gram_workspace_bytes() bytes (may be NULL / 0): lets the bf16 kernel
+ *       split the token axis into slices whose partial tiles are summed in a fixed order, which
+ *       fills the GPU when d_in/256 gives few output tiles.  Results do not depend on timing, but the
+ *       slice count (and so the rounding of the sums) depends on whether ws is given.
  */
+size_t armor_gram_workspace_bytes(int64_t n_tokens, int64_t d_in, armor_dtype x_dtype);
 armor_status armor_gram(const void *X, armor_dtype x_dtype, int64_t n_tokens, int64_t d_in, int64_t ldx,
-                        float *H, int64_t ldh, int accumulate, void *hip_stream);
+                        float *H, int64_t ldh, int accumulate, void *ws, size_t ws_bytes, void *hip_stream);
 
 /* D[j] = H[j][j]  (the weights ||X_j||^2 of Eq. 2). */
 armor_status armor_gram_diag(const float *H, int64_t d_in, int64_t ldh, float *D, void *hip_stream);

@@ -11,7 +11,8 @@ ARMOR_F32, ARMOR_BF16 = 0, 1
 
 PROF_KINDS = ["gram", "phase_A", "phase_B", "phase_WS", "sparse_step"]
 
-EXPORTED = ["armor_status_string", "armor_last_hip_error", "armor_profile_enable", "armor_profile_read", "armor_gram", "armor_gram_diag",
+EXPORTED = ["armor_status_string", "armor_last_hip_error", "armor_profile_enable", "armor_profile_read",
+            "armor_gram_workspace_bytes", "armor_gram", "armor_gram_diag",
             "armor_normalize_workspace_bytes", "armor_normalize", "armor_proxy_loss_workspace_bytes",
             "armor_proxy_loss", "armor_factorize_workspace_bytes", "armor_factorize_layer", "armor_pack_nm"]
 
@@ -42,7 +43,9 @@ def load_library():
     lib.armor_last_hip_error.restype = _int
     lib.armor_profile_enable.argtypes = [_int]
     lib.armor_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
-    lib.armor_gram.argtypes = [_vp, _int, _i64, _i64, _i64, _vp, _i64, _int, _vp]
+    lib.armor_gram_workspace_bytes.restype = _sz
+    lib.armor_gram_workspace_bytes.argtypes = [_i64, _i64, _int]
+    lib.armor_gram.argtypes = [_vp, _int, _i64, _i64, _i64, _vp, _i64, _int, _vp, _sz, _vp]
     lib.armor_gram_diag.argtypes = [_vp, _i64, _i64, _vp, _vp]
     lib.armor_normalize_workspace_bytes.restype = _sz
     lib.armor_normalize_workspace_bytes.argtypes = [_i64, _i64]
@@ -110,8 +113,13 @@ def profile_read():
     return {k: (ms[i], cnt[i]) for i, k in enumerate(PROF_KINDS)}
 
 
-def gram(X, H=None, accumulate=False):
-    """H (+)= X^T X.  X [n_tokens, d_in] fp32/bf16 on the device; returns H [d_in, d_in] fp32."""
+def gram_workspace_bytes(n_tokens, d_in, bf16=True):
+    return load_library().armor_gram_workspace_bytes(n_tokens, d_in, ARMOR_BF16 if bf16 else ARMOR_F32)
+
+
+def gram(X, H=None, accumulate=False, ws=None):
+    """H (+)= X^T X.  X [n_tokens, d_in] fp32/bf16 on the device; returns H [d_in, d_in] fp32.
+    ws: optional uint8 device tensor of gram_workspace_bytes() bytes (allocated here if None)."""
     torch = _torch()
     lib = load_library()
     if not (X.is_cuda and X.dim() == 2 and X.stride(1) == 1):
@@ -122,7 +130,11 @@ def gram(X, H=None, accumulate=False):
             raise ArmorError("accumulate needs an existing H")
         H = torch.empty((d_in, d_in), device=X.device, dtype=torch.float32)
     _dev_f32(H, "H")
-    _check(lib.armor_gram(_ptr(X), _dtype_code(X), n, d_in, X.stride(0), _ptr(H), H.stride(0), int(accumulate), _stream()))
+    need = lib.armor_gram_workspace_bytes(n, d_in, _dtype_code(X))
+    if need > 0 and (ws is None or ws.numel() < need):
+        ws = torch.empty(need, device=X.device, dtype=torch.uint8)
+    _check(lib.armor_gram(_ptr(X), _dtype_code(X), n, d_in, X.stride(0), _ptr(H), H.stride(0), int(accumulate),
+                          _ptr(ws) if need > 0 else _vp(0), ws.numel() if need > 0 else 0, _stream()))
     return H
 
 

@@ -222,15 +222,21 @@ armor_status armor_profile_read(double *ms_total, int64_t *launches) {
     return st;
 }
 
+size_t armor_gram_workspace_bytes(int64_t n_tokens, int64_t d_in, armor_dtype x_dtype) {
+    if (n_tokens <= 0 || d_in <= 0) return 0;
+    return gram_workspace_bytes(n_tokens, d_in, x_dtype == ARMOR_BF16);
+}
+
 armor_status armor_gram(const void *X, armor_dtype x_dtype, int64_t n_tokens, int64_t d_in, int64_t ldx, float *H,
-                        int64_t ldh, int accumulate, void *hip_stream) {
+                        int64_t ldh, int accumulate, void *ws, size_t ws_bytes, void *hip_stream) {
     if (!H || (!X && n_tokens > 0)) return ARMOR_ERR_NULL;
     if (x_dtype != ARMOR_F32 && x_dtype != ARMOR_BF16) return ARMOR_ERR_DTYPE;
     if (d_in <= 0 || d_in % 32 != 0 || n_tokens < 0 || ldx < d_in || ldh < d_in) return ARMOR_ERR_SHAPE;
-    if (!aligned16(X) || !aligned16(H)) return ARMOR_ERR_ALIGN;
+    if (!aligned16(X) || !aligned16(H) || (ws && !aligned16(ws))) return ARMOR_ERR_ALIGN;
     {
         ProfScope ps(ARMOR_PROF_GRAM, (hipStream_t)hip_stream);
-        launch_gram(X, x_dtype == ARMOR_BF16, n_tokens, d_in, ldx, H, ldh, accumulate, (hipStream_t)hip_stream);
+        launch_gram(X, x_dtype == ARMOR_BF16, n_tokens, d_in, ldx, H, ldh, accumulate, ws, ws ? ws_bytes : 0,
+                    (hipStream_t)hip_stream);
     }
     return check_hip();
 }

@@ -78,7 +78,9 @@ void launch_unstructured_init(const float *Wbar, const float *D, int64_t d_out, 
 size_t unstructured_init_ws_bytes(int64_t d_out, int64_t d_in);
 
 // ---- Gram (gram.hip) --------------------------------------------------------------------------
+// ws (optional): gram_workspace_bytes() bytes for split-K partial tiles; without it one slice is used.
+size_t gram_workspace_bytes(int64_t n, int64_t d_in, int bf16);
 void launch_gram(const void *X, int bf16, int64_t n, int64_t d_in, int64_t ldx, float *H, int64_t ldh,
-                 int accumulate, hipStream_t s);
+                 int accumulate, void *ws, size_t ws_bytes, hipStream_t s);
 
 } // namespace armor

@@ -104,10 +104,20 @@ __global__ __launch_bounds__(GramCfg<T>::WM *GramCfg<T>::WN * 64) void gram_f32_
 // ------------------------------------------------------------------------------------------------
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
+// blockIdx.y = token slice (split-K): slice s covers tokens [s*slice_len, (s+1)*slice_len) and, when
+// part != nullptr, writes its upper-triangular tile to part[s] ([d_in x d_in], no mirror) for the
+// fixed-order reduction below; with part == nullptr (one slice) it writes / accumulates H directly.
 __global__ __launch_bounds__(512) void gram_bf16_kernel(const uint16_t *__restrict__ X, int64_t ldx, int ntile,
                                                         float *__restrict__ H, int64_t ldh, int accumulate,
-                                                        int64_t t_begin, int64_t t_end) {
+                                                        int64_t n_tokens, int64_t slice_len,
+                                                        float *__restrict__ part, int64_t d_in) {
     constexpr int T = 256, KC = 64, TM = 4, TN = 2;
+    const int64_t t_begin = (int64_t)blockIdx.y * slice_len, t_end = min(n_tokens, t_begin + slice_len);
+    if (part != nullptr) {
+        H = part + (int64_t)blockIdx.y * d_in * d_in;
+        ldh = d_in;
+        accumulate = 0;
+    }
     __shared__ uint4 lds[2][2][T * 8]; // [stage][operand][channel * 8 + slot]
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, l32 = lane & 31, kh = lane >> 5;
     int ta = 0, rem = blockIdx.x;
@@ -201,19 +211,86 @@ __global__ __launch_bounds__(512) void gram_bf16_kernel(const uint16_t *__restri
                 float v = acc[tm][tn][r];
                 float *h = H + row * ldh + col;
                 *h = accumulate ? *h + v : v;
-                if (!diag) {
+                if (!diag && part == nullptr) {
                     float *hm = H + col * ldh + row;
                     *hm = accumulate ? *hm + v : v;
                 }
             }
 }
 
+// H (+)= sum over slices, in slice order, of the upper-triangular tiles in part[]; mirror tiles are
+// written through an LDS transpose so both stores are row-contiguous.  One workgroup per 32 x 32
+// sub-block: blockIdx.x = tile pair, blockIdx.y = sub-block inside the 256 x 256 tile.
+__global__ __launch_bounds__(256) void gram_reduce_kernel(const float *__restrict__ part, int nslices, int64_t d_in,
+                                                          int ntile, float *__restrict__ H, int64_t ldh,
+                                                          int accumulate) {
+    __shared__ float tr[32][33];
+    int ta = 0, rem = blockIdx.x;
+    while (rem >= ntile - ta) { rem -= ntile - ta; ++ta; }
+    const int tb = ta + rem;
+    const int sr = blockIdx.y / 8, sc = blockIdx.y % 8;
+    const int64_t row0 = (int64_t)ta * 256 + sr * 32, col0 = (int64_t)tb * 256 + sc * 32;
+    const int c = threadIdx.x & 31, r0 = threadIdx.x >> 5; // 8 rows per pass
+#pragma unroll
+    for (int pass = 0; pass < 4; ++pass) {
+        const int r = pass * 8 + r0;
+        float v = 0.f;
+        for (int sl = 0; sl < nslices; ++sl) v += part[((int64_t)sl * d_in + row0 + r) * d_in + col0 + c];
+        tr[r][c] = v;
+        float *h = H + (row0 + r) * ldh + col0 + c;
+        *h = accumulate ? *h + v : v;
+    }
+    if (ta == tb) return; // a diagonal tile holds both of its triangles already
+    __syncthreads();
+#pragma unroll
+    for (int pass = 0; pass < 4; ++pass) {
+        const int r = pass * 8 + r0;
+        float *hm = H + (col0 + r) * ldh + row0 + c;
+        const float v = tr[c][r];
+        *hm = accumulate ? *hm + v : v;
+    }
+}
+
+// Split-K plan for the bf16 kernel: with one 128 KB-LDS workgroup per CU, `pairs` tile pairs alone
+// leave CUs idle (136 pairs at d_in = 4096); slicing the tokens S ways gives pairs * S workgroups.
+// Cost model: rounds * (tokens per slice + a fixed per-workgroup overhead).
+static int gram_slices(int64_t n, int64_t d_in, size_t ws_bytes) {
+    int dev = 0, cus = 256;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+        cus = 256;
+    const int64_t nt = d_in / 256, pairs = nt * (nt + 1) / 2;
+    int best = 1;
+    double best_cost = 1e300;
+    for (int S = 1; S <= 32; ++S) {
+        if (S > 1 && (size_t)S * d_in * d_in * sizeof(float) > ws_bytes) break;
+        int64_t len = ((n + S - 1) / S + 63) / 64 * 64;
+        if (S > 1 && len < 2048) break;
+        int64_t rounds = (pairs * S + cus - 1) / cus;
+        double cost = (double)rounds * ((double)len + 768.0);
+        if (cost < best_cost * 0.97) { best_cost = cost; best = S; }
+    }
+    return best;
+}
+
+size_t gram_workspace_bytes(int64_t n, int64_t d_in, int bf16) {
+    if (!bf16 || d_in % 256 != 0) return 0;
+    int S = gram_slices(n, d_in, (size_t)4 << 30);
+    return S > 1 ? (size_t)S * d_in * d_in * sizeof(float) : 0;
+}
+
 void launch_gram(const void *X, int bf16, int64_t n, int64_t d_in, int64_t ldx, float *H, int64_t ldh,
-                 int accumulate, hipStream_t s) {
+                 int accumulate, void *ws, size_t ws_bytes, hipStream_t s) {
     if (bf16 && d_in % 256 == 0 && ldx % 8 == 0) {
-        int nt = (int)(d_in / 256);
-        hipLaunchKernelGGL(gram_bf16_kernel, dim3((unsigned)(nt * (nt + 1) / 2)), dim3(512), 0, s,
-                           reinterpret_cast<const uint16_t *>(X), ldx, nt, H, ldh, accumulate, (int64_t)0, n);
+        int nt = (int)(d_in / 256), pairs = nt * (nt + 1) / 2;
+        int S = ws ? gram_slices(n, d_in, ws_bytes) : 1;
+        int64_t len = S > 1 ? ((n + S - 1) / S + 63) / 64 * 64 : n;
+        float *part = S > 1 ? reinterpret_cast<float *>(ws) : nullptr;
+        hipLaunchKernelGGL(gram_bf16_kernel, dim3((unsigned)pairs, (unsigned)S), dim3(512), 0, s,
+                           reinterpret_cast<const uint16_t *>(X), ldx, nt, H, ldh, accumulate, n, len, part, d_in);
+        if (S > 1)
+            hipLaunchKernelGGL(gram_reduce_kernel, dim3((unsigned)pairs, 64), dim3(256), 0, s, part, S, d_in, nt, H, ldh,
+                               accumulate);
         return;
     }
     int T = (d_in % 128 == 0) ? 128 : (d_in % 64 == 0) ? 64 : 32;

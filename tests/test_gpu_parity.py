@@ -47,7 +47,8 @@ def make_layer(d_out, d_in, n_tokens, seed, act_outliers=(0.0, 1.0)):
 
 # ---------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("n,d_in,bf16", [(512, 256, False), (70, 96, False), (333, 384, True), (16, 32, False), (1, 64, True),
-                                         (333, 512, True), (64, 256, True), (1000, 768, True), (129, 256, True)])
+                                         (333, 512, True), (64, 256, True), (1000, 768, True), (129, 256, True),
+                                         (8192, 256, True), (9000, 512, True)])
 def test_gram(armor, torch, orc, n, d_in, bf16):
     say("gram", n, d_in, bf16)
     X = synth.make_calibration(n, d_in, seed=4, outlier_frac=0.02, outlier_scale=20.0)

@@ -37,11 +37,11 @@ def test_status_strings_and_host_side_validation():
     assert lib.armor_factorize_workspace_bytes(256, 256, 32, 2, 3, None) == 0      # M not 2/4/8
     assert lib.armor_proxy_loss_workspace_bytes(128, 128, 64) > 0
     # null pointers / bad shapes are rejected without touching the device
-    assert lib.armor_gram(None, 0, 16, 64, 64, None, 64, 0, None) == 1
+    assert lib.armor_gram(None, 0, 16, 64, 64, None, 64, 0, None, 0, None) == 1
     buf = (ctypes.c_float * 64)()
     p = ctypes.cast(buf, ctypes.c_void_p)
-    assert lib.armor_gram(p, 0, 16, 48, 48, p, 48, 0, None) == 2                   # d_in not a multiple of 32
-    assert lib.armor_gram(p, 7, 16, 64, 64, p, 64, 0, None) == 3                   # dtype
+    assert lib.armor_gram(p, 0, 16, 48, 48, p, 48, 0, None, 0, None) == 2                   # d_in not a multiple of 32
+    assert lib.armor_gram(p, 7, 16, 64, 64, p, 64, 0, None, 0, None) == 3                   # dtype
     assert lib.armor_factorize_layer(None, 0, None, 0, 64, 64, 32, 2, 4, 1, None, None, None, None, None, None, None,
                                      None, None, None, 0, None) == 1
     assert lib.armor_factorize_layer(p, 0, p, 0, 64, 64, 32, 2, 4, 1, None, p, p, p, None, None, None, None, None, None,
