@@ -54,7 +54,21 @@ def main():
     ap.add_argument("--tokens", type=int, default=0,
                     help="override the number of calibration tokens (profiling runs only; the reported "
                          "workload name gets a suffix)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain device copy of known size (256 MiB read + 256 MiB written, 3 times) "
+                         "so that rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings can be scaled")
     args = ap.parse_args()
+    if args.copy_calibration:
+        import torch
+        src = torch.ones(64 * 1024 * 1024, device="cuda:0", dtype=torch.float32)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": {"bytes_read": src.numel() * 4, "bytes_written": src.numel() * 4,
+                                               "copies": 3}}))
+        return
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (every box has one GPU); use --gpus 1", file=sys.stderr)
         sys.exit(2)

@@ -46,19 +46,35 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_A_kernel(
     const int chunk = (nbj + nsplit - 1) / nsplit;
     const int j0 = c * chunk, j1 = min(nbj, j0 + chunk);
     typename CH::Acc gacc, acc;
-    typename CH::TileRegs t0;
+    typename CH::TileRegs t0, t1;
     gacc.zero();
-    if (j0 < j1) CH::gload_tile(t0, C + (int64_t)i * B * d_in + (int64_t)j0 * B, ldw, tid);
+    if (j0 < j1) {
+        CH::gload_tile(t0, C + (int64_t)i * B * d_in + (int64_t)j0 * B, ldw, tid);
+        CH::gload_tile(t1, Bw + (int64_t)j0 * B * B, B, tid);
+    }
     for (int j = j0; j < j1; ++j) {
         const float *Wij = Wbar + (int64_t)i * B * d_in + (int64_t)j * B;
         CH::lstore_tile(sm.X, t0, tid);
-        CH::gload_tile(t0, Bw + (int64_t)j * B * B, B, tid);
+        CH::lstore_tile(sm.Y, t1, tid);
         if (tid < B) sm.Dl[tid] = D[(int64_t)j * B + tid];
-        CH::lstore_tile(sm.Y, t0, tid);
         __syncthreads();
         CH::gload_tile(t0, A + (int64_t)i * B * B, B, tid);
         acc.zero();
         CH::template mma<false, false, false>(acc, sm.X, sm.Y, nullptr, p); // S = C B
+        // Everything downstream needs S only as S sqrt(D) (columns scaled): (R D) S^T = (R sqrt D)(S sqrt D)^T,
+        // S D S^T = (S sqrt D)(S sqrt D)^T, and A S = (A S sqrt D) / sqrt D column by column.  Scaling here
+        // once keeps the per-k multiply out of the product loops.  A zero weight gives a zero column.
+        float sq[CH::TN], isq[CH::TN];
+#pragma unroll
+        for (int tn = 0; tn < CH::TN; ++tn) {
+            const float dj = sm.Dl[p.col(tn)];
+            sq[tn] = sqrtf(dj);
+            isq[tn] = dj > 0.f ? 1.f / sq[tn] : 0.f;
+#pragma unroll
+            for (int tm = 0; tm < CH::TM; ++tm)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc.v[tm][tn][r] *= sq[tn];
+        }
         __syncthreads();
         CH::store_acc(sm.X, acc, p);
         CH::lstore_tile(sm.Y, t0, tid);
@@ -71,32 +87,33 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_A_kernel(
                 for (int r = 0; r < 16; ++r) wb[tm][tn][r] = Wij[opaque(woff) + CH::Pos::unif_off(tm, tn, r, ldw)];
         __syncthreads();
         acc.zero();
-        CH::template mma<false, false, false>(acc, sm.Y, sm.X, nullptr, p); // What = A S
+        CH::template mma<false, false, false>(acc, sm.Y, sm.X, nullptr, p); // A (S sqrt D)
         float lsum = 0.f;
 #pragma unroll
         for (int tm = 0; tm < CH::TM; ++tm)
 #pragma unroll
             for (int tn = 0; tn < CH::TN; ++tn) {
-                float dj = sm.Dl[p.col(tn)];
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    float res = wb[tm][tn][r] - acc.v[tm][tn][r];
-                    lsum += res * res * dj;
-                    acc.v[tm][tn][r] = res * dj;
+                    float res = (wb[tm][tn][r] - acc.v[tm][tn][r] * isq[tn]) * sq[tn]; // R sqrt(D)
+                    lsum += res * res;
+                    acc.v[tm][tn][r] = res;
                 }
             }
         float ltot = CH::block_sum(lsum, sm.red, tid); // (has barriers: every wave is done reading Y)
         if (tid == 0) loss_part[i * nbj + j] = ltot;
         if (!LOSS_ONLY) {
-            CH::store_acc(sm.Y, acc, p); // R D
+            CH::store_acc(sm.Y, acc, p); // R sqrt(D)
             __syncthreads();
         }
-        if (j + 1 < j1) // next block's core tile (HBM), underneath the remaining products
+        if (j + 1 < j1) { // next block's first operands, underneath the remaining products
             CH::gload_tile(t0, C + (int64_t)i * B * d_in + (int64_t)(j + 1) * B, ldw, tid);
+            CH::gload_tile(t1, Bw + (int64_t)(j + 1) * B * B, B, tid);
+        }
         if (!LOSS_ONLY) {
             CH::template mma<false, true, false>(gacc, sm.Y, sm.X, nullptr, p); // += (R D) S^T
             acc.zero();
-            CH::template mma<false, true, true>(acc, sm.X, sm.X, sm.Dl, p); // (S D) S^T
+            CH::template mma<false, true, false>(acc, sm.X, sm.X, nullptr, p); // S D S^T
             float f2 = 0.f;
 #pragma unroll
             for (int tm = 0; tm < CH::TM; ++tm)
@@ -140,9 +157,12 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_B_kernel(
     const int chunk = (nbi + nsplit - 1) / nsplit;
     const int i0 = c * chunk, i1 = min(nbi, i0 + chunk);
     typename CH::Acc gacc, acc;
-    typename CH::TileRegs t0;
+    typename CH::TileRegs t0, t1;
     gacc.zero();
-    if (i0 < i1) CH::gload_tile(t0, C + (int64_t)i0 * B * d_in + (int64_t)j * B, ldw, tid);
+    if (i0 < i1) {
+        CH::gload_tile(t0, C + (int64_t)i0 * B * d_in + (int64_t)j * B, ldw, tid);
+        CH::gload_tile(t1, A + (int64_t)i0 * B * B, B, tid);
+    }
     if (tid < B) sm.Dl[tid] = D[(int64_t)j * B + tid];
     __syncthreads();
     float dn2 = 0.f;
@@ -151,8 +171,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_B_kernel(
     for (int i = i0; i < i1; ++i) {
         const float *Wij = Wbar + (int64_t)i * B * d_in + (int64_t)j * B;
         CH::lstore_tile(sm.X, t0, tid);
-        CH::gload_tile(t0, A + (int64_t)i * B * B, B, tid);
-        CH::lstore_tile(sm.Y, t0, tid);
+        CH::lstore_tile(sm.Y, t1, tid);
         __syncthreads();
         CH::gload_tile(t0, Bw + (int64_t)j * B * B, B, tid);
         acc.zero();
@@ -181,7 +200,10 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_B_kernel(
         __syncthreads();
         CH::store_acc(sm.Y, acc, p); // R D
         __syncthreads();
-        if (i + 1 < i1) CH::gload_tile(t0, C + (int64_t)(i + 1) * B * d_in + (int64_t)j * B, ldw, tid);
+        if (i + 1 < i1) {
+            CH::gload_tile(t0, C + (int64_t)(i + 1) * B * d_in + (int64_t)j * B, ldw, tid);
+            CH::gload_tile(t1, A + (int64_t)(i + 1) * B * B, B, tid);
+        }
         CH::template mma<true, false, false>(gacc, sm.X, sm.Y, nullptr, p); // += S'^T (R D)
         acc.zero();
         CH::template mma<true, false, false>(acc, sm.X, sm.X, nullptr, p); // S'^T S'

@@ -157,8 +157,7 @@ void launch_diag(const float *H, int64_t d_in, int64_t ldh, float *D, hipStream_
 // ------------------------------------------------------------------------------------------------
 // wrapper update (Alg. 2):  X^(k) <- X^(k) - grad^(k) / beta,  beta = 2 * sum of the per-block
 // summands of Eq. 9 / Eq. 10, grad^(k) = sum of the nsplit partials the chain kernel left.
-// A zero beta leaves X unchanged.  Workgroup (k, q) updates slice q of block k; every workgroup
-// re-derives beta in the same fixed order.  Workgroup (0,0) also writes the loss of the previous
+// A zero beta leaves X unchanged.  Workgroup (k, q) updates 256 entries of block k, one per thread; every workgroup re-derives beta in the same fixed order.  Workgroup (0,0) also writes the loss of the previous
 // iterate (sum of the block losses) when trace_out is given.
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void update_wrapper_kernel(float *__restrict__ X, int b, const float *__restrict__ gpart,
@@ -166,29 +165,33 @@ __global__ __launch_bounds__(256) void update_wrapper_kernel(float *__restrict__
                                                              int nblocks, const float *__restrict__ loss_part,
                                                              double *__restrict__ trace_out) {
     __shared__ double red[4];
-    const int tid = threadIdx.x, k = blockIdx.x, q = blockIdx.y, nq = gridDim.y;
+    const int tid = threadIdx.x, k = blockIdx.x, q = blockIdx.y;
+    const int bb = b * b, e = q * 256 + tid;
+    // the partial gradients of this element first (independent loads in flight together, summed in
+    // chunk order)
+    const bool live = e < bb;
+    double g = 0.0;
+    if (live) {
+#pragma unroll 8
+        for (int c = 0; c < nsplit; ++c) g += (double)gpart[((int64_t)k * nsplit + c) * bb + e];
+    }
+    const float xold = live ? X[(int64_t)k * bb + e] : 0.f;
     double s = 0.0;
-    for (int e = tid; e < nblocks; e += 256) s += (double)beta_part[e];
+    for (int i = tid; i < nblocks; i += 256) s += (double)beta_part[i];
     const double beta = 2.0 * block_sum_256(s, red);
     if (trace_out != nullptr && k == 0 && q == 0) {
         double l = 0.0;
-        for (int e = tid; e < nblocks; e += 256) l += (double)loss_part[e];
+        for (int i = tid; i < nblocks; i += 256) l += (double)loss_part[i];
         l = block_sum_256(l, red);
         if (tid == 0) *trace_out = l;
     }
-    if (!(beta > 0.0)) return;
-    const int bb = b * b, per = (bb + nq - 1) / nq, e0 = q * per, e1 = min(bb, e0 + per);
-    for (int e = e0 + tid; e < e1; e += 256) {
-        double g = 0.0;
-        for (int c = 0; c < nsplit; ++c) g += (double)gpart[((int64_t)k * nsplit + c) * bb + e];
-        float *x = X + (int64_t)k * bb + e;
-        *x = (float)((double)*x - g / beta);
-    }
+    if (!(beta > 0.0) || !live) return;
+    X[(int64_t)k * bb + e] = (float)((double)xold - g / beta);
 }
 
 void launch_update_wrapper(float *A, int nblk, int b, const float *gpart, int nsplit, const float *beta_part,
                            int nblocks, const float *loss_part, double *trace_out, hipStream_t s) {
-    int nq = (b * b + 2047) / 2048;
+    int nq = (b * b + 255) / 256;
     hipLaunchKernelGGL(update_wrapper_kernel, dim3(nblk, nq), dim3(256), 0, s, A, b, gpart, nsplit, beta_part, nblocks,
                        loss_part, trace_out);
 }
@@ -253,6 +256,32 @@ template <int N> __device__ double pinv_solve(double (&G)[N][N], const double (&
     if (N == 1) {
         w[0] = G[0][0] > 0.0 ? q[0] / G[0][0] : 0.0;
         return w[0] * q[0];
+    }
+    if (N == 2) { // one Jacobi rotation diagonalises a symmetric 2 x 2 matrix exactly
+        const double a = G[0][0], b = G[0][N - 1], d = G[N - 1][N - 1];
+        double c = 1.0, sn = 0.0, t = 0.0;
+        if (b != 0.0) {
+            const double theta = (d - a) / (2.0 * b);
+            t = (theta >= 0.0 ? 1.0 : -1.0) / (fabs(theta) + sqrt(theta * theta + 1.0));
+            c = 1.0 / sqrt(t * t + 1.0);
+            sn = t * c;
+        }
+        const double lam[2] = {a - t * b, d + t * b};      // eigenvalues
+        const double vec[2][2] = {{c, -sn}, {sn, c}};       // their eigenvectors
+        const double lmax = fmax(lam[0], lam[1]);
+        w[0] = 0.0;
+        w[N - 1] = 0.0;
+        if (lmax <= 0.0) return 0.0;
+        double gain = 0.0;
+#pragma unroll
+        for (int k = 0; k < 2; ++k)
+            if (lam[k] > 1e-12 * lmax) {
+                const double proj = vec[k][0] * q[0] + vec[k][1] * q[N - 1], pl = proj / lam[k];
+                w[0] += vec[k][0] * pl;
+                w[N - 1] += vec[k][1] * pl;
+                gain += proj * pl;
+            }
+        return gain;
     }
     double V[N][N];
 #pragma unroll
@@ -350,39 +379,53 @@ __global__ __launch_bounds__(256) void sparse_step_kernel(const float *__restric
     float best_key = INFINITY;
     int best_kap = 0x7fffffff;
     const float *Gij = G + (int64_t)i * b * d_in + (int64_t)j * b;
-    for (int kap = tid; kap < gpb; kap += 256) {
-        int ip = kap / gpr, k = kap % gpr;
-        const float *g = Gij + (int64_t)ip * d_in + k * M;
-        float v[M];
-        if (M == 4) {
-            float4 x = *reinterpret_cast<const float4 *>(g);
-            v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
-        } else {
+    constexpr int U = 4; // groups per thread whose loads are in flight together
+    for (int kap0 = tid; kap0 < gpb; kap0 += 256 * U) {
+        float v[U][M];
 #pragma unroll
-            for (int p = 0; p < M; ++p) v[p] = g[p];
-        }
-        float score;
-        if (selection == 2) {
-            double a = 0.0;
+        for (int u = 0; u < U; ++u) {
+            const int kap = kap0 + u * 256;
+            if (kap < gpb) {
+                const float *g = Gij + (int64_t)(kap / gpr) * d_in + (kap % gpr) * M;
+                if (M == 4) {
+                    float4 x = *reinterpret_cast<const float4 *>(g);
+                    v[u][0] = x.x; v[u][1] = x.y; v[u][2] = x.z; v[u][3] = x.w;
+                } else {
 #pragma unroll
-            for (int p = 0; p < M; ++p) a += (double)v[p] * (double)v[p];
-            score = (float)sqrt(a);
-        } else {
-            double a = 0.0;
+                    for (int p = 0; p < M; ++p) v[u][p] = g[p];
+                }
+            } else {
 #pragma unroll
-            for (int p = 0; p < M; ++p) a += (double)fabsf(v[p]);
-            score = (float)a;
+                for (int p = 0; p < M; ++p) v[u][p] = 0.f;
+            }
         }
-        if (selection == 3) score = 1.f;
-        float key;
-        if (selection == 1) {
-            key = -score;
-        } else {
-            uint64_t ctr = (uint64_t)(((int64_t)t * nblocks + blk) * gpb + kap) + 1ULL;
-            float u = hash_uniform(seed, ctr);
-            key = score > 0.f ? (-logf(u)) / score : INFINITY;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int kap = kap0 + u * 256;
+            if (kap >= gpb) break;
+            float score;
+            if (selection == 2) {
+                float a = 0.f;
+#pragma unroll
+                for (int p = 0; p < M; ++p) a = fmaf(v[u][p], v[u][p], a);
+                score = sqrtf(a);
+            } else {
+                float a = 0.f;
+#pragma unroll
+                for (int p = 0; p < M; ++p) a += fabsf(v[u][p]);
+                score = a;
+            }
+            if (selection == 3) score = 1.f;
+            float key;
+            if (selection == 1) {
+                key = -score;
+            } else {
+                uint64_t ctr = (uint64_t)(((int64_t)t * nblocks + blk) * gpb + kap) + 1ULL;
+                float u01 = hash_uniform(seed, ctr);
+                key = score > 0.f ? (-__logf(u01)) / score : INFINITY;
+            }
+            if (key < best_key) { best_key = key; best_kap = kap; }
         }
-        if (key < best_key) { best_key = key; best_kap = kap; }
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) {
@@ -398,29 +441,39 @@ __global__ __launch_bounds__(256) void sparse_step_kernel(const float *__restric
         if (s_key[w] < best_key || (s_key[w] == best_key && s_kap[w] < best_kap)) { best_key = s_key[w]; best_kap = s_kap[w]; }
     if (best_kap == 0x7fffffff) best_kap = 0; // every key was +inf (or NaN): the first group
     const int ip = best_kap / gpr, k0 = (best_kap % gpr) * M;
-    const double a2 = (double)colnorm2[(int64_t)i * b + ip];
-    if (!(a2 > 0.0)) return; // a = 0: the block cannot move (uniform across the workgroup)
 
-    // ---- 2. operands of Eq. 7 for the drawn group ----
+    // ---- 2. operands of Eq. 7 for the drawn group: one round of independent loads ----
     float *crow = C + ((int64_t)i * b + ip) * d_in + (int64_t)j * b + k0;
     const float *Kj = K + (int64_t)j * b * b;
+    __shared__ double s_c[M], s_g[M], s_a2;
     if (tid < M * M) s_K[tid / M][tid % M] = (double)Kj[(k0 + tid / M) * b + k0 + tid % M];
+    if (tid >= 64 && tid < 64 + M) {
+        s_c[tid - 64] = (double)crow[tid - 64];
+        s_g[tid - 64] = (double)Gij[(int64_t)ip * d_in + k0 + tid - 64];
+    }
+    if (tid == 128) s_a2 = (double)colnorm2[(int64_t)i * b + ip];
     __syncthreads();
+    const double a2 = s_a2;
+    if (!(a2 > 0.0)) return; // a = 0: the block cannot move (uniform across the workgroup)
     if (tid < M) {
         double acc = 0.0;
 #pragma unroll
-        for (int pp = 0; pp < M; ++pp) acc += s_K[tid][pp] * (double)crow[pp];
-        s_q[tid] = -0.5 * (double)Gij[(int64_t)ip * d_in + k0 + tid] + a2 * acc;
+        for (int pp = 0; pp < M; ++pp) acc += s_K[tid][pp] * s_c[pp];
+        s_q[tid] = -0.5 * s_g[tid] + a2 * acc;
     }
     __syncthreads();
 
     // ---- 3. sweep: thread x handles the x-th subset in lexicographic order ----
+    // (the sweep threads sit in wave blk % 4, so that co-resident workgroups do not all queue their
+    // fp64 work on the same SIMD)
     int sub[N];
     double w[N];
-    if (tid < NPAT) {
+    static_assert(NPAT <= 128, "the sweep threads must fit in the workgroup from any wave offset");
+    const int sw = (tid - 64 * (blk & 3)) & 255; // sweep-thread index
+    if (sw < NPAT) {
 #pragma unroll
         for (int p = 0; p < N; ++p) sub[p] = p;
-        for (int step = 0; step < tid; ++step) { // advance to the tid-th subset
+        for (int step = 0; step < sw; ++step) { // advance to the sw-th subset
             int p = N - 1;
             while (p >= 0 && sub[p] == M - N + p) --p;
             ++sub[p];
@@ -434,7 +487,7 @@ __global__ __launch_bounds__(256) void sparse_step_kernel(const float *__restric
             for (int y = 0; y < N; ++y) Gs[x][y] = s_K[sub[x]][sub[y]];
         }
         double gain = pinv_solve<N>(Gs, qs, w) / a2;
-        s_gain[tid] = (float)gain;
+        s_gain[sw] = (float)gain;
     }
     __syncthreads();
     if (tid == 0) {
@@ -445,7 +498,7 @@ __global__ __launch_bounds__(256) void sparse_step_kernel(const float *__restric
         s_best = bi;
     }
     __syncthreads();
-    if (tid == s_best) {
+    if (sw == s_best) {
         float out[M];
         uint32_t bits = 0;
 #pragma unroll
