@@ -30,6 +30,15 @@ DEFAULT = "llama7b_attn_4096x4096_b128_2:4_50it"
 
 FP32_MFMA_PEAK = 157.3e12  # MI355X dense fp32 matrix peak, FLOP/s
 
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by what the
+# same counter reads for a plain 256 MiB device copy (factors 2.000 and 1.000); see
+# profiles/chain_kernels_llama7b_attn_pmc.txt.  Keyed by (workload, kernel); other workloads: null.
+MEASURED_TRAFFIC_BYTES = {
+    ("llama7b_attn_4096x4096_b128_2:4_50it", "phase_WS"): (253.1 + 128.0) * 2 ** 20,
+    ("llama7b_attn_4096x4096_b128_2:4_50it", "phase_A"): (186.2 + 16.1) * 2 ** 20,
+    ("llama7b_attn_4096x4096_b128_2:4_50it", "phase_B"): (194.3 + 16.0) * 2 ** 20,
+}
+
 
 def chain_algorithmic_flops(kind, d_out, d_in, b, N, M):
     """Algorithmic flops of one launch of a chain kernel: 2*P*b per dense b-deep block product,
@@ -127,7 +136,8 @@ def main():
     flops = chain_algorithmic_flops(dom, d_out, d_in, b, N, M)
     achieved = flops / (chain[dom]["avg_ms"] * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": FP32_MFMA_PEAK / 1e12,
-                "unit": "TFLOP/s", "frac": achieved / (FP32_MFMA_PEAK / 1e12), "traffic": None,
+                "unit": "TFLOP/s", "frac": achieved / (FP32_MFMA_PEAK / 1e12),
+                "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, dom)),
                 "algorithmic_flops_per_launch": flops, "avg_launch_ms": chain[dom]["avg_ms"]}
     for k in chain:
         kernels[k]["tflops_algorithmic"] = chain_algorithmic_flops(k, d_out, d_in, b, N, M) / (chain[k]["avg_ms"] * 1e-3) / 1e12

@@ -402,7 +402,7 @@ armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const flo
             ProfScope ps(ARMOR_PROF_PHASE_WS, s);
             if (big) launch_big_phase_WS(d, f.Wbar, S, A, B, f.D, f.AtA, f.K, mask, mask_group, f.scalars, nullptr,
                                          nullptr, false, slots, f.big_scratch, s);
-            else launch_phase_G(d, f.Wbar, S, A, B, f.D, mask, mask_group, f.scalars, nullptr, nullptr, 0, slots, s);
+            else launch_phase_W(d, f.Wbar, S, A, B, f.D, mask, mask_group, f.scalars, slots, s);
         } else {
             // W' step fused with the core gradient at the updated core; then the sparse-core step (Alg. 3)
             {

@@ -21,12 +21,10 @@ void launch_phase_A(const Dims &d, const float *Wbar, const float *C, const floa
 // B-phase: S' = A C, R = Wbar - S' B, partial grad_B, ||S'^T S'||_F ||D^j||_F.
 void launch_phase_B(const Dims &d, const float *Wbar, const float *C, const float *A, const float *B,
                     const float *D, int nsplit, float *gpart, float *beta_part, hipStream_t s);
-// Core gradient G = A^T ((Wbar - A C B) D) B^T per block.
-//   mode 0 (W'-step of Alg. 2): C += (2/beta_W) G on kept entries, beta_W read from scalars[2].
-//   mode 1 (Alg. 3 input): Gout = -2 G (unmasked), block loss to loss_part.
-void launch_phase_G(const Dims &d, const float *Wbar, float *C, const float *A, const float *B, const float *D,
-                    const uint8_t *mask, int mask_group, const double *scalars, float *Gout, float *loss_part,
-                    int mode, int grid_cap, hipStream_t s);
+// W' step of Alg. 2 alone (unstructured mode): C += (2/beta_W) (A^T ((Wbar - A C B) D) B^T) (.) M, beta_W
+// read from scalars[2].  grid_cap workgroups at most, each walking blocks w, w + grid, ...
+void launch_phase_W(const Dims &d, const float *Wbar, float *C, const float *A, const float *B, const float *D,
+                    const uint8_t *mask, int mask_group, const double *scalars, int grid_cap, hipStream_t s);
 // Per wrapper block: A^iT A^i, its diagonal ||A^i[:,p]||^2 and ||A^iT A^i||_F^2; K^j = B^j D^j B^jT, ||K^j||_F^2.
 void launch_wrapper_grams(const Dims &d, const float *A, const float *B, const float *D, float *colnorm2,
                           float *fro2A, float *AtA, float *K, float *fro2K, hipStream_t s);

@@ -228,18 +228,15 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_B_kernel(
 }
 
 // ------------------------------------------------------------------------------------------------
-// Core gradient (App. D.3 without the mask):  G^(i,j) = A^(i)T ((Wbar - A C B) D)^(i,j) B^(j)T.
-//   MODE 0: the W' step of Alg. 2:  C <- C + (2 / beta_W') G on kept entries (Eq. 11).
-//   MODE 1: Gout = -2 G for every entry (the selection scores and the q-vectors of Alg. 3 read
-//           it), and the block loss (= loss after the continuous step) to loss_part.
+// W' step of Alg. 2 on its own (unstructured mode, Sec. 4.5, where no sparse-core step follows):
+//   G^(i,j) = A^(i)T ((Wbar - A C B) D)^(i,j) B^(j)T   (App. D.3),   C <- C + (2 / beta_W') G (.) M   (Eq. 11).
 // Blocks are independent; workgroup w handles blocks w, w + gridDim.x, ...
 // ------------------------------------------------------------------------------------------------
-template <int B, int MODE>
-__global__ __launch_bounds__(Chain<B>::NT) void phase_G_kernel(
+template <int B>
+__global__ __launch_bounds__(Chain<B>::NT) void phase_W_kernel(
     const float *__restrict__ Wbar, float *__restrict__ C, const float *__restrict__ A,
     const float *__restrict__ Bw, const float *__restrict__ D, const uint8_t *__restrict__ mask, int mask_group,
-    const double *__restrict__ scalars, int64_t d_in, int nbj, int nblocks, float *__restrict__ Gout,
-    float *__restrict__ loss_part) {
+    const double *__restrict__ scalars, int64_t d_in, int nbj, int nblocks) {
     using CH = Chain<B>;
     __shared__ Smem<B> sm;
     const int tid = threadIdx.x;
@@ -247,11 +244,8 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_G_kernel(
     const int ldw = (int)d_in, woff = p.lane_off(ldw);
     typename CH::Acc acc;
     typename CH::TileRegs t0, tc;
-    float eta2 = 0.f;
-    if (MODE == 0) {
-        const double bw = scalars[2];
-        eta2 = bw > 0.0 ? (float)(2.0 / bw) : 0.f;
-    }
+    const double bw = scalars[2];
+    const float eta2 = bw > 0.0 ? (float)(2.0 / bw) : 0.f;
     const int64_t mrow = d_in / mask_group;
     int blk = blockIdx.x;
     if (blk < nblocks) CH::gload_tile(t0, C + (int64_t)(blk / nbj) * B * d_in + (int64_t)(blk % nbj) * B, ldw, tid);
@@ -281,23 +275,14 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_G_kernel(
             __syncthreads();
             acc.zero();
             CH::template mma<false, false, false>(acc, sm.X, sm.Y, nullptr, p); // What = S' B
-            float lsum = 0.f;
 #pragma unroll
             for (int tm = 0; tm < CH::TM; ++tm)
 #pragma unroll
                 for (int tn = 0; tn < CH::TN; ++tn) {
                     float dj = sm.Dl[p.col(tn)];
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        float res = wb[tm][tn][r] - acc.v[tm][tn][r];
-                        lsum += res * res * dj;
-                        acc.v[tm][tn][r] = res * dj;
-                    }
+                    for (int r = 0; r < 16; ++r) acc.v[tm][tn][r] = (wb[tm][tn][r] - acc.v[tm][tn][r]) * dj;
                 }
-            if (MODE == 1) {
-                float ltot = CH::block_sum(lsum, sm.red, tid);
-                if (tid == 0) loss_part[blk] = ltot;
-            }
         }
         __syncthreads();
         CH::store_acc(sm.X, acc, p); // R D   (Y still holds B^j)
@@ -310,16 +295,14 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_G_kernel(
         CH::lstore_tile(sm.Y, t0, tid);
         // operands of the epilogue and the next block's core tile, underneath the last product
         uint32_t mraw[CH::PER][2];
-        if (MODE == 0) {
-            CH::gload_tile(tc, Cij, ldw, tid); // this block's core again (L2), in the coalesced loader layout
+        CH::gload_tile(tc, Cij, ldw, tid); // this block's core again (L2), in the coalesced loader layout
 #pragma unroll
-            for (int it = 0; it < CH::PER; ++it) {
-                const int row = it * CH::ROWS_PER_IT + CH::loader_row(tid);
-                const int64_t gcol = (int64_t)j * B + CH::loader_c4(tid) * 4;
-                const uint8_t *mp = mask + ((int64_t)i * B + row) * mrow + gcol / mask_group;
-                mraw[it][0] = mp[0];
-                mraw[it][1] = mask_group == 2 ? mp[1] : 0u;
-            }
+        for (int it = 0; it < CH::PER; ++it) {
+            const int row = it * CH::ROWS_PER_IT + CH::loader_row(tid);
+            const int64_t gcol = (int64_t)j * B + CH::loader_c4(tid) * 4;
+            const uint8_t *mp = mask + ((int64_t)i * B + row) * mrow + gcol / mask_group;
+            mraw[it][0] = mp[0];
+            mraw[it][1] = mask_group == 2 ? mp[1] : 0u;
         }
         const int nblk = blk + gridDim.x;
         if (nblk < nblocks)
@@ -327,7 +310,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_G_kernel(
         __syncthreads();
         acc.zero();
         CH::template mma<true, false, false>(acc, sm.Y, sm.X, nullptr, p); // G = A^T U
-        if (MODE == 0) {
+        {
             // C <- C + (2/beta) G on kept entries, as one coalesced float4 pass: G goes through LDS
             __syncthreads();
             CH::store_acc(sm.X, acc, p);
@@ -348,15 +331,6 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_G_kernel(
                 if (nib & 8u) v.w += eta2 * g[3];
                 *reinterpret_cast<float4 *>(Cij + (off0 + it * CH::ROWS_PER_IT * ldw)) = v;
             }
-        } else {
-            float *Gij = Gout + (int64_t)i * B * d_in + (int64_t)j * B;
-#pragma unroll
-            for (int tm = 0; tm < CH::TM; ++tm)
-#pragma unroll
-                for (int tn = 0; tn < CH::TN; ++tn)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        Gij[opaque(woff) + CH::Pos::unif_off(tm, tn, r, ldw)] = -2.f * acc.v[tm][tn][r];
         }
         __syncthreads();
     }
@@ -594,17 +568,12 @@ void launch_phase_B(const Dims &d, const float *Wbar, const float *C, const floa
     });
 }
 
-void launch_phase_G(const Dims &d, const float *Wbar, float *C, const float *A, const float *B, const float *D,
-                    const uint8_t *mask, int mask_group, const double *scalars, float *Gout, float *loss_part,
-                    int mode, int grid_cap, hipStream_t s) {
+void launch_phase_W(const Dims &d, const float *Wbar, float *C, const float *A, const float *B, const float *D,
+                    const uint8_t *mask, int mask_group, const double *scalars, int grid_cap, hipStream_t s) {
     ARMOR_DISPATCH_B(d.b, {
         dim3 grid(std::min(d.nblocks, grid_cap)), block(Chain<BB>::NT);
-        if (mode == 0)
-            hipLaunchKernelGGL((phase_G_kernel<BB, 0>), grid, block, 0, s, Wbar, C, A, B, D, mask, mask_group,
-                               scalars, d.d_in, d.nbj, d.nblocks, Gout, loss_part);
-        else
-            hipLaunchKernelGGL((phase_G_kernel<BB, 1>), grid, block, 0, s, Wbar, C, A, B, D, mask, mask_group,
-                               scalars, d.d_in, d.nbj, d.nblocks, Gout, loss_part);
+        hipLaunchKernelGGL((phase_W_kernel<BB>), grid, block, 0, s, Wbar, C, A, B, D, mask, mask_group, scalars,
+                           d.d_in, d.nbj, d.nblocks);
     });
 }
 
