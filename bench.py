@@ -28,6 +28,25 @@ WORKLOADS = {
 }
 DEFAULT = "llama7b_attn_4096x4096_b128_2:4_50it"
 
+# Multi-matrix workloads (the other baseline configs; not the default bench line).  Each input site
+# gets one Gram; every matrix is factorized from its site's diagonal.  One step = all Grams + all
+# factorizations + packing.  sites: name -> (d_in, generator); matrices: (name, d_out, site).
+BLOCK_WORKLOADS = {
+    "llama7b_mlp_b128_2:4_50it": dict(
+        tokens=262144, d_block=128, patterns=[(2, 4, 0)], n_iters=50, hidden=4096,
+        sites={"mlp_in": 4096, "down_in": 11008},
+        matrices=[("gate", 11008, "mlp_in"), ("up", 11008, "mlp_in"), ("down", 4096, "down_in")]),
+    "llama3_8b_block_b128_2:4_50it": dict(
+        tokens=262144, d_block=128, patterns=[(2, 4, 0)], n_iters=50, hidden=4096,
+        sites={"qkv_in": 4096, "o_in": 4096, "mlp_in": 4096, "down_in": 14336},
+        matrices=[("q", 4096, "qkv_in"), ("k", 1024, "qkv_in"), ("v", 1024, "qkv_in"), ("o", 4096, "o_in"),
+                  ("gate", 14336, "mlp_in"), ("up", 14336, "mlp_in"), ("down", 4096, "down_in")]),
+    "llama3_70b_mlp_b256_2:4_4:8_unstructured_30it": dict(
+        tokens=131072, d_block=256, patterns=[(2, 4, 0), (4, 8, 0), (2, 4, 1)], n_iters=30, hidden=8192,
+        sites={"mlp_in": 8192, "down_in": 28672},
+        matrices=[("gate", 28672, "mlp_in"), ("up", 28672, "mlp_in"), ("down", 8192, "down_in")]),
+}
+
 FP32_MFMA_PEAK = 157.3e12  # MI355X dense fp32 matrix peak, FLOP/s
 
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by what the
@@ -52,12 +71,86 @@ def chain_algorithmic_flops(kind, d_out, d_in, b, N, M):
     return sparse + 3 * unit + sparse + unit
 
 
+def run_block_workload(args, armor, synth, torch, dev):
+    """Whole-block wall time for a multi-matrix workload; prints one JSON line."""
+    cfg = BLOCK_WORKLOADS[args.workload]
+    n_tok = args.tokens or cfg["tokens"]
+    b, n_iters, hidden = cfg["d_block"], cfg["n_iters"], cfg["hidden"]
+    # inputs: one hidden-width activation matrix per hidden-width site; the MLP down site is SiLU(gate)*up of it
+    weights = {name: synth.torch_weight(d_out, cfg["sites"][site], 100 + k, dev)
+               for k, (name, d_out, site) in enumerate(cfg["matrices"])}
+    X = {}
+    for k, (site, width) in enumerate(cfg["sites"].items()):
+        if width == hidden:
+            X[site] = synth.torch_calibration(n_tok, width, 10 + k, dev, outlier_frac=0.005, outlier_scale=20.0)
+    for site, width in cfg["sites"].items():
+        if width != hidden:  # scale the projections so that the activations are O(1) at the 0.02 init scale
+            X[site] = synth.torch_mlp_down_inputs(X["mlp_in"], weights["gate"] * 8.0, weights["up"] * 8.0)
+    H = {site: torch.empty((w, w), device=dev, dtype=torch.float32) for site, w in cfg["sites"].items()}
+    gws_bytes = max(armor.gram_workspace_bytes(n_tok, w, True) for w in cfg["sites"].values())
+    gws = torch.empty(max(gws_bytes, 256), device=dev, dtype=torch.uint8)
+    ws_bytes = 0
+    for (name, d_out, site) in cfg["matrices"]:
+        for (N, M, sp) in cfg["patterns"]:
+            ws_bytes = max(ws_bytes, armor.factorize_workspace_bytes(d_out, cfg["sites"][site], b, N, M, sparsity=sp))
+    ws = torch.empty(ws_bytes, device=dev, dtype=torch.uint8)
+    torch.cuda.synchronize()
+
+    def step(timings=None):
+        D = {}
+        for site in cfg["sites"]:
+            armor.gram(X[site], H=H[site], ws=gws)
+            D[site] = armor.gram_diag(H[site])
+        last = None
+        for (name, d_out, site) in cfg["matrices"]:
+            d_in = cfg["sites"][site]
+            for (N, M, sp) in cfg["patterns"]:
+                if timings is not None:
+                    torch.cuda.synchronize()
+                    t0 = time.perf_counter()
+                out = armor.factorize_layer(weights[name], D[site], b, N, M, n_iters, seed=0, sparsity=sp,
+                                            unstructured_keep=(d_out * d_in) // 2 if sp else 0, ws=ws)
+                if not sp:
+                    armor.pack_nm(out["S"], out["mask_bits"], N, M, bf16=True)
+                if timings is not None:
+                    torch.cuda.synchronize()
+                    tag = "%s_%dx%d_%s" % (name, d_out, d_in, "unstructured" if sp else "%d:%d" % (N, M))
+                    timings[tag] = timings.get(tag, 0.0) + (time.perf_counter() - t0)
+                last = out
+        return last
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        out = step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    per = {}
+    step(per)  # one extra, untimed-in-aggregate pass with a sync per matrix for the breakdown
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    total_iters = n_iters * len(cfg["matrices"]) * len(cfg["patterns"])
+    tr = out["loss_trace"].cpu().numpy()
+    print(json.dumps({
+        "metric": "BCD iterations/sec per layer", "value": total_iters / (ms_per_step * 1e-3), "unit": "iterations/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": args.workload + ("_tokens%d" % n_tok if args.tokens else ""), "n_tokens": n_tok,
+                   "d_block": b, "n_iters": n_iters, "matrices": len(cfg["matrices"]), "grams": len(cfg["sites"]),
+                   "step": "all Grams + every factorize_layer (+ pack_nm) of the block"},
+        "whole_block_wall_s": ms_per_step * 1e-3,
+        "per_matrix": {k: {"s": v, "iterations_per_s": n_iters / v} for k, v in per.items()},
+        "last_loss_first_last": [float(tr[0]), float(tr[-1])],
+    }))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default=DEFAULT, choices=sorted(WORKLOADS))
+    ap.add_argument("--workload", default=DEFAULT, choices=sorted(WORKLOADS) + sorted(BLOCK_WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-iters", type=int, default=2)
     ap.add_argument("--tokens", type=int, default=0,
@@ -89,6 +182,9 @@ def main():
 
     armor.load_library()
     dev = torch.device("cuda:0")
+    if args.workload in BLOCK_WORKLOADS:
+        run_block_workload(args, armor, synth, torch, dev)
+        return
     d_out, d_in, n_tok, b, N, M, n_iters, w_bf16, x_bf16, ofrac, oscale = WORKLOADS[args.workload]
     workload_name = args.workload
     if args.tokens > 0:
