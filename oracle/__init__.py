@@ -213,6 +213,53 @@ def factorize_layer(W, D, b, N, M, n_iters, seed=0, selection=0, sparsity=0, kee
                 loss_cont_trace=ctrace[:n_iters])
 
 
+def adam_update(Wbar, D, mask, A, C, B, state, t, lr=1e-4, b1=0.9, b2=0.999, eps=1e-8):
+    """One joint Adam step at iteration t (1-based).  state: dict of mA, vA, mB, vB, mC, vC (fp32 arrays,
+    updated in place on copies).  Returns new (A, C, B, state)."""
+    Wbar, D = _f32(Wbar), _f32(D)
+    A, C, B = _f32(A).copy(), _f32(C).copy(), _f32(B).copy()
+    mask = np.ascontiguousarray(mask, dtype=np.uint8)
+    st = {k: _f32(v).copy() for k, v in state.items()}
+    d_out, d_in = Wbar.shape
+    b = A.shape[-1]
+    lib().oracle_adam_update(_p(Wbar, _f32p), _p(D, _f32p), _p(mask, _u8p), _i64(d_out), _i64(d_in), _i64(b),
+                             _p(A, _f32p), _p(C, _f32p), _p(B, _f32p), _p(st["mA"], _f32p), _p(st["vA"], _f32p),
+                             _p(st["mB"], _f32p), _p(st["vB"], _f32p), _p(st["mC"], _f32p), _p(st["vC"], _f32p),
+                             ctypes.c_double(lr), ctypes.c_double(b1), ctypes.c_double(b2), ctypes.c_double(eps),
+                             _i64(t))
+    return A, C, B, st
+
+
+def adam_state(d_out, d_in, b):
+    z = lambda *shape: np.zeros(shape, dtype=np.float32)
+    return dict(mA=z(d_out // b, b, b), vA=z(d_out // b, b, b), mB=z(d_in // b, b, b), vB=z(d_in // b, b, b),
+                mC=z(d_out, d_in), vC=z(d_out, d_in))
+
+
+def factorize_layer_adam(W, D, b, N, M, n_iters, seed=0, selection=0, sparsity=0, keep=0, lr=1e-4, b1=0.9, b2=0.999,
+                         eps=1e-8):
+    """Outer loop with the joint Adam continuous step; same outputs as factorize_layer."""
+    W, D = _f32(W), _f32(D)
+    d_out, d_in = W.shape
+    A = np.empty((d_out // b, b, b), dtype=np.float32)
+    B = np.empty((d_in // b, b, b), dtype=np.float32)
+    C = np.empty((d_out, d_in), dtype=np.float32)
+    Wbar = np.empty((d_out, d_in), dtype=np.float32)
+    mask = np.empty((d_out, d_in), dtype=np.uint8)
+    r1 = np.empty(d_in, dtype=np.float32)
+    r2 = np.empty(d_out, dtype=np.float32)
+    trace = np.zeros(n_iters + 1, dtype=np.float64)
+    ctrace = np.zeros(max(n_iters, 1), dtype=np.float64)
+    lib().oracle_factorize_layer_adam(_p(W, _f32p), _p(D, _f32p), _i64(d_out), _i64(d_in), _i64(b), ctypes.c_int(N),
+                                      ctypes.c_int(M), ctypes.c_int(n_iters), ctypes.c_uint64(seed),
+                                      ctypes.c_int(selection), ctypes.c_int(sparsity), _i64(keep),
+                                      ctypes.c_double(lr), ctypes.c_double(b1), ctypes.c_double(b2),
+                                      ctypes.c_double(eps), _p(A, _f32p), _p(C, _f32p), _p(B, _f32p), _p(mask, _u8p),
+                                      _p(Wbar, _f32p), _p(r1, _f32p), _p(r2, _f32p), _p(trace, _f64p), _p(ctrace, _f64p))
+    return dict(A=A, C=C, B=B, mask=mask, Wbar=Wbar, r1=r1, r2=r2, loss_trace=trace,
+                loss_cont_trace=ctrace[:n_iters])
+
+
 def denormalize(A, B, r1, r2):
     A, B = _f32(A).copy(), _f32(B).copy()
     r1, r2 = _f32(r1), _f32(r2)

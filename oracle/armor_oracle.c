@@ -11,6 +11,7 @@
  *   - proxy loss .................................... Sec. 3.2, Eq. 2 (weights are diag(X X^T) only)
  *   - initialisation ................................ Sec. 3.3, Eq. 3
  *   - continuous update (sequential GD, 1/beta) ..... Sec. 3.3.1, Alg. 2, Lemma 1, App. D (Eq. 9-11)
+ *   - continuous update (joint Adam, as run in practice) Sec. 3.3.1, App. F
  *   - sparse-core update ............................ Sec. 3.3.2, App. B.1 (Eq. 5-8), Alg. 3
  *   - outer loop .................................... Alg. 1
  *   - N:M generalisation, unstructured mode ......... Sec. 4.5
@@ -682,6 +683,75 @@ void oracle_factorize_layer(const float *W, const float *D, int64_t d_out, int64
                                       NULL, NULL);
         loss_trace[t] = oracle_proxy_loss(Wbar, A, C, B, D, d_out, d_in, b);
     }
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Joint Adam continuous step (Sec. 3.3.1: what the authors run in practice; App. F gives the
+ * learning rate 1e-4).  One gradient evaluation at the current point for A, B and W' together,
+ * then the published Adam update (Kingma & Ba, Alg. 1, with bias correction) on each parameter:
+ *     m <- b1 m + (1-b1) g ;  v <- b2 v + (1-b2) g^2 ;
+ *     theta <- theta - lr * (m / (1-b1^t)) / (sqrt(v / (1-b2^t)) + eps)
+ * Readings (the paper gives only the learning rate): b1 = 0.9, b2 = 0.999, eps = 1e-8 (the
+ * optimiser's published defaults); the moments of W' are kept per entry and never reset; a pruned
+ * entry sees a zero gradient, so its moments only decay, and its value stays exactly zero (it does
+ * not enter A (W' . M) B; a re-admitted entry is overwritten by Eq. 8).  Moments are fp32 state,
+ * arithmetic in fp64.  t is the 1-based iteration.  No monotonicity guarantee (Sec. 3.3.1).
+ * ------------------------------------------------------------------------------------------ */
+static void adam_apply(float *theta, float *m, float *v, const double *g, const uint8_t *mask, int64_t n,
+                       double lr, double b1, double b2, double eps, int64_t t) {
+    double c1 = 1.0 - pow(b1, (double)t), c2 = 1.0 - pow(b2, (double)t);
+    for (int64_t e = 0; e < n; ++e) {
+        double ge = (mask == NULL || mask[e]) ? g[e] : 0.0;
+        double me = b1 * (double)m[e] + (1.0 - b1) * ge;
+        double ve = b2 * (double)v[e] + (1.0 - b2) * ge * ge;
+        m[e] = (float)me;
+        v[e] = (float)ve;
+        if (mask == NULL || mask[e])
+            theta[e] = (float)((double)theta[e] - lr * (me / c1) / (sqrt(ve / c2) + eps));
+    }
+}
+
+void oracle_adam_update(const float *Wbar, const float *D, const uint8_t *mask, int64_t d_out, int64_t d_in,
+                        int64_t b, float *A, float *C, float *B, float *mA, float *vA, float *mB, float *vB,
+                        float *mC, float *vC, double lr, double b1, double b2, double eps, int64_t t) {
+    dims_t d = mk_dims(d_out, d_in, b);
+    int64_t P = d_out * d_in, na = d.nbi * b * b, nb = d.nbj * b * b;
+    double *Wb = to_double(Wbar, P), *Dd = to_double(D, d_in), *Cd = to_double(C, P), *Ad = to_double(A, na),
+           *Bd = to_double(B, nb), *gA = dalloc(na), *gB = dalloc(nb), *G = dalloc(P);
+    grad_beta_A(Wb, Ad, Cd, Bd, Dd, d, gA, NULL);          /* all three at the same point */
+    grad_beta_B(Wb, Ad, Cd, Bd, Dd, d, gB, NULL);
+    core_gradient(Wb, Ad, Cd, Bd, Dd, d, G, NULL);
+    adam_apply(A, mA, vA, gA, NULL, na, lr, b1, b2, eps, t);
+    adam_apply(B, mB, vB, gB, NULL, nb, lr, b1, b2, eps, t);
+    adam_apply(C, mC, vC, G, mask, P, lr, b1, b2, eps, t);
+    free(Wb); free(Dd); free(Cd); free(Ad); free(Bd); free(gA); free(gB); free(G);
+}
+
+/* Alg. 1 with the joint Adam continuous step.  Same outputs as oracle_factorize_layer. */
+void oracle_factorize_layer_adam(const float *W, const float *D, int64_t d_out, int64_t d_in, int64_t b, int N,
+                                 int M, int n_iters, uint64_t seed, int selection, int sparsity, int64_t keep,
+                                 double lr, double b1, double b2, double eps, float *A, float *C, float *B,
+                                 uint8_t *mask, float *Wbar, float *r1, float *r2, double *loss_trace,
+                                 double *loss_cont_trace) {
+    dims_t d = mk_dims(d_out, d_in, b);
+    int64_t P = d_out * d_in, na = d.nbi * b * b, nb = d.nbj * b * b;
+    float *mA = (float *)calloc((size_t)na, 4), *vA = (float *)calloc((size_t)na, 4),
+          *mB = (float *)calloc((size_t)nb, 4), *vB = (float *)calloc((size_t)nb, 4),
+          *mC = (float *)calloc((size_t)P, 4), *vC = (float *)calloc((size_t)P, 4);
+    oracle_normalize(W, d_out, d_in, Wbar, r1, r2);
+    oracle_init_identity(A, d.nbi, b);
+    oracle_init_identity(B, d.nbj, b);
+    if (sparsity == 0) oracle_init_nm(Wbar, D, d_out, d_in, N, M, C, mask);
+    else oracle_init_unstructured(Wbar, D, d_out, d_in, keep, C, mask);
+    loss_trace[0] = oracle_proxy_loss(Wbar, A, C, B, D, d_out, d_in, b);
+    for (int t = 1; t <= n_iters; ++t) {
+        oracle_adam_update(Wbar, D, mask, d_out, d_in, b, A, C, B, mA, vA, mB, vB, mC, vC, lr, b1, b2, eps, t);
+        if (loss_cont_trace) loss_cont_trace[t - 1] = oracle_proxy_loss(Wbar, A, C, B, D, d_out, d_in, b);
+        if (sparsity == 0)
+            oracle_sparse_core_update(Wbar, A, B, D, d_out, d_in, b, N, M, seed, t, selection, C, mask, NULL, NULL);
+        loss_trace[t] = oracle_proxy_loss(Wbar, A, C, B, D, d_out, d_in, b);
+    }
+    free(mA); free(vA); free(mB); free(vB); free(mC); free(vC);
 }
 
 /* ------------------------------------------------------------------------------------------

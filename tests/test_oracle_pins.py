@@ -565,3 +565,73 @@ def test_bf16_rounding_helper():
     bits = synth.to_bf16_bits(x)
     ref = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
     np.testing.assert_array_equal(bits, ref)
+
+
+# ---------------------------------------------------------------------------------------------
+# joint Adam continuous step (Sec. 3.3.1, App. F)
+# ---------------------------------------------------------------------------------------------
+def _np_adam(theta, m, v, g, t, lr, b1, b2, eps):
+    """Independent restatement of the published Adam update (with bias correction), fp64."""
+    m = b1 * m + (1 - b1) * g
+    v = b2 * v + (1 - b2) * g * g
+    mhat, vhat = m / (1 - b1 ** t), v / (1 - b2 ** t)
+    return theta - lr * mhat / (np.sqrt(vhat) + eps), m, v
+
+
+def test_adam_step_matches_published_update_rule(orc):
+    rng = np.random.default_rng(61)
+    d_out, d_in, b = 8, 12, 4
+    Wbar, D, A, B, C, mask = rand_state(rng, d_out, d_in, b, perturb=0.2)
+    st = orc.adam_state(d_out, d_in, b)
+    lr, b1, b2, eps = 1e-2, 0.9, 0.999, 1e-8
+    A64, B64, C64 = A.astype(np.float64), B.astype(np.float64), C.astype(np.float64)
+    m = {k: np.zeros_like(x) for k, x in (("A", A64), ("B", B64), ("C", C64))}
+    v = {k: np.zeros_like(x) for k, x in (("A", A64), ("B", B64), ("C", C64))}
+    Ao, Co, Bo = A, C, B
+    for t in (1, 2, 3):
+        # gradients of all three at the same point (pinned above by finite differences)
+        gA, _ = orc.grad_A(Wbar, Ao, Co, Bo, D)
+        gB, _ = orc.grad_B(Wbar, Ao, Co, Bo, D)
+        gC, _ = orc.grad_core(Wbar, Ao, Co, Bo, D)
+        gC = gC * mask
+        eA, m["A"], v["A"] = _np_adam(Ao.astype(np.float64), m["A"], v["A"], gA, t, lr, b1, b2, eps)
+        eB, m["B"], v["B"] = _np_adam(Bo.astype(np.float64), m["B"], v["B"], gB, t, lr, b1, b2, eps)
+        eC, m["C"], v["C"] = _np_adam(Co.astype(np.float64), m["C"], v["C"], gC, t, lr, b1, b2, eps)
+        eC = np.where(mask == 1, eC, 0.0)                       # pruned entries stay exactly zero
+        Ao, Co, Bo, st = orc.adam_update(Wbar, D, mask, Ao, Co, Bo, st, t, lr=lr, b1=b1, b2=b2, eps=eps)
+        np.testing.assert_allclose(Ao, eA, rtol=2e-6, atol=1e-7)
+        np.testing.assert_allclose(Bo, eB, rtol=2e-6, atol=1e-7)
+        np.testing.assert_allclose(Co, eC, rtol=2e-6, atol=1e-7)
+        assert np.all(Co[mask == 0] == 0)
+        np.testing.assert_allclose(st["mC"], m["C"], rtol=2e-6, atol=1e-9)
+        np.testing.assert_allclose(st["vA"], v["A"], rtol=2e-6, atol=1e-12)
+        m = {k: st["m" + k].astype(np.float64) for k in m}      # moments are fp32 state between steps
+        v = {k: st["v" + k].astype(np.float64) for k in v}
+
+
+def test_adam_first_step_moves_by_lr_against_the_gradient_sign(orc):
+    """t = 1: m_hat = g, v_hat = g^2, so every entry with |g| >> eps moves by lr * sign(-g)."""
+    rng = np.random.default_rng(67)
+    d_out, d_in, b = 8, 8, 4
+    Wbar, D, A, B, C, mask = rand_state(rng, d_out, d_in, b, perturb=0.2)
+    gA, _ = orc.grad_A(Wbar, A, C, B, D)
+    lr = 1e-3
+    A1, C1, B1, _ = orc.adam_update(Wbar, D, mask, A, C, B, orc.adam_state(d_out, d_in, b), 1, lr=lr)
+    big = np.abs(gA) > 1e-3
+    np.testing.assert_allclose((A1.astype(np.float64) - A)[big], -lr * np.sign(gA[big]), rtol=1e-3)
+
+
+def test_factorize_adam_reduces_loss_and_keeps_structure(orc):
+    d_out, d_in, b = 32, 48, 16
+    W = synth.make_weight(d_out, d_in, seed=1, outlier_frac=0.05)
+    X = synth.make_calibration(96, d_in, seed=1)
+    D = np.diag(orc.gram(X)).astype(np.float32)
+    out = orc.factorize_layer_adam(W, D, b, 2, 4, n_iters=40, seed=3, lr=1e-3)
+    tr, ct = out["loss_trace"], out["loss_cont_trace"]
+    assert tr[-1] < 0.9 * tr[0]                                  # moves far faster than the 1/beta steps
+    assert np.all(tr[1:] <= ct * (1 + 1e-9))                     # Lemma 2 still holds for the sparse step
+    assert np.all(out["mask"].reshape(d_out, d_in // 4, 4).sum(-1) == 2)
+    assert np.all(out["C"][out["mask"] == 0] == 0)
+    assert tr[-1] == pytest.approx(dense_loss(out["Wbar"], out["A"], out["C"], out["B"], D), rel=1e-9)
+    gd = orc.factorize_layer(W, D, b, 2, 4, n_iters=40, seed=3)
+    assert tr[0] == gd["loss_trace"][0]                          # same initial point
