@@ -67,7 +67,10 @@ def chain_algorithmic_flops(kind, d_out, d_in, b, N, M):
     sparse = unit * N / M
     if kind in ("phase_A", "phase_B"):
         return sparse + unit + unit + 0.5 * unit
+    if kind == "phase_GS":  # S' = A C (core operand), What, U, G
+        return sparse + 3 * unit
     # phase_WS: S' = A C (core operand), What, U, G, V = (G.M) K (N:M-sparse operand), Z = (A^T A) V
+    # phase_FB: S = C B (core operand), What, grad_A, T, C^T T (core operand), T B^T
     return sparse + 3 * unit + sparse + unit
 
 
@@ -151,6 +154,9 @@ def main():
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default=DEFAULT, choices=sorted(WORKLOADS) + sorted(BLOCK_WORKLOADS))
+    ap.add_argument("--variant", default="gd", choices=["gd", "adam"],
+                    help="continuous step: sequential 1/beta gradient steps (default; the monotone variant) or the "
+                         "joint Adam step the authors run in practice (lr 1e-4)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-iters", type=int, default=2)
     ap.add_argument("--tokens", type=int, default=0,
@@ -186,7 +192,8 @@ def main():
         run_block_workload(args, armor, synth, torch, dev)
         return
     d_out, d_in, n_tok, b, N, M, n_iters, w_bf16, x_bf16, ofrac, oscale = WORKLOADS[args.workload]
-    workload_name = args.workload
+    workload_name = args.workload + ("_adam" if args.variant == "adam" else "")
+    variant = 1 if args.variant == "adam" else 0
     if args.tokens > 0:
         n_tok = args.tokens
         workload_name += "_tokens%d" % n_tok
@@ -196,14 +203,14 @@ def main():
     X = synth.torch_calibration(n_tok, d_in, 0, dev, outlier_frac=ofrac, outlier_scale=oscale,
                                 dtype=torch.bfloat16 if x_bf16 else torch.float32)
     H = torch.empty((d_in, d_in), device=dev, dtype=torch.float32)
-    ws = torch.empty(armor.factorize_workspace_bytes(d_out, d_in, b, N, M), device=dev, dtype=torch.uint8)
+    ws = torch.empty(armor.factorize_workspace_bytes(d_out, d_in, b, N, M, variant=variant), device=dev, dtype=torch.uint8)
     gws = torch.empty(max(armor.gram_workspace_bytes(n_tok, d_in, x_bf16), 256), device=dev, dtype=torch.uint8)
     torch.cuda.synchronize()
 
     def step():
         armor.gram(X, H=H, ws=gws)
         D = armor.gram_diag(H)
-        out = armor.factorize_layer(W, D, b, N, M, n_iters, seed=0, ws=ws)
+        out = armor.factorize_layer(W, D, b, N, M, n_iters, seed=0, ws=ws, variant=variant)
         vals, meta = armor.pack_nm(out["S"], out["mask_bits"], N, M, bf16=True)
         return out, D, vals, meta
 
@@ -262,7 +269,10 @@ def main():
         Dh = D.cpu().numpy()
         cpu_iters = args.cpu_iters if d_out * d_in > 1 << 20 else n_iters
         c0 = time.perf_counter()
-        ref = oracle.factorize_layer(Wh, Dh, b, N, M, cpu_iters, seed=0)
+        if variant == 1:
+            ref = oracle.factorize_layer_adam(Wh, Dh, b, N, M, cpu_iters, seed=0)
+        else:
+            ref = oracle.factorize_layer(Wh, Dh, b, N, M, cpu_iters, seed=0)
         c1 = time.perf_counter()
         cores = int(os.environ.get("OMP_NUM_THREADS", "0")) or (os.cpu_count() or 1)
         result["cpu_baseline"] = {

@@ -51,7 +51,13 @@ typedef struct {
     int64_t unstructured_keep;  /* sparsity==1: number of kept entries (global top-k of the importance) */
     uint64_t seed;              /* seed of the counter-based selection hash */
     int32_t denormalize;        /* 1: fold r2 into the rows of A and r1 into the columns of B (Sec. 3.2) */
-    int32_t reserved;
+    int32_t variant;            /* continuous step (Sec. 3.3.1): 0 = sequential gradient steps with 1/beta step
+                                   sizes (Alg. 2; monotone, default), 1 = joint Adam on A, B, W' (what the authors
+                                   run in practice; one forward/backward pass per iteration; d_block <= 128) */
+    double lr;                  /* Adam learning rate; 0 = 1e-4 (App. F) */
+    double adam_beta1;          /* 0 = 0.9   (the optimiser's published default; the paper gives none) */
+    double adam_beta2;          /* 0 = 0.999 */
+    double adam_eps;            /* 0 = 1e-8  */
 } armor_opts;
 
 const char *armor_status_string(armor_status s);
@@ -72,7 +78,9 @@ int armor_last_hip_error(void);
 #define ARMOR_PROF_PHASE_B 2
 #define ARMOR_PROF_PHASE_WS 3
 #define ARMOR_PROF_SPARSE 4
-#define ARMOR_PROF_KINDS 5
+#define ARMOR_PROF_PHASE_FB 5 /* joint-Adam forward/backward chain */
+#define ARMOR_PROF_PHASE_GS 6 /* core-gradient chain of the joint-Adam variant */
+#define ARMOR_PROF_KINDS 7
 armor_status armor_profile_enable(int on);
 armor_status armor_profile_read(double *ms_total /*host [ARMOR_PROF_KINDS]*/, int64_t *launches /*host*/);
 

@@ -9,7 +9,7 @@ _LIB_PATH = os.path.join(_HERE, "libarmor.so")
 
 ARMOR_F32, ARMOR_BF16 = 0, 1
 
-PROF_KINDS = ["gram", "phase_A", "phase_B", "phase_WS", "sparse_step"]
+PROF_KINDS = ["gram", "phase_A", "phase_B", "phase_WS", "sparse_step", "phase_FB", "phase_GS"]
 
 EXPORTED = ["armor_status_string", "armor_last_hip_error", "armor_profile_enable", "armor_profile_read",
             "armor_gram_workspace_bytes", "armor_gram", "armor_gram_diag",
@@ -23,7 +23,9 @@ class ArmorError(RuntimeError):
 
 class ArmorOpts(ctypes.Structure):
     _fields_ = [("selection", ctypes.c_int32), ("sparsity", ctypes.c_int32), ("unstructured_keep", ctypes.c_int64),
-                ("seed", ctypes.c_uint64), ("denormalize", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+                ("seed", ctypes.c_uint64), ("denormalize", ctypes.c_int32), ("variant", ctypes.c_int32),
+                ("lr", ctypes.c_double), ("adam_beta1", ctypes.c_double), ("adam_beta2", ctypes.c_double),
+                ("adam_eps", ctypes.c_double)]
 
 
 _lib = None
@@ -190,14 +192,15 @@ def proxy_loss(Wbar, A, S, B, H, d_block=None):
     return out
 
 
-def factorize_workspace_bytes(d_out, d_in, d_block, N, M, sparsity=0):
+def factorize_workspace_bytes(d_out, d_in, d_block, N, M, sparsity=0, variant=0):
     lib = load_library()
-    o = ArmorOpts(sparsity=sparsity)
+    o = ArmorOpts(sparsity=sparsity, variant=variant)
     return lib.armor_factorize_workspace_bytes(d_out, d_in, d_block, N, M, ctypes.byref(o))
 
 
 def factorize_layer(W, H, d_block, N, M, n_iters, seed=0, selection=0, sparsity=0, unstructured_keep=0,
-                    denormalize=False, ws=None, want_cont_trace=False):
+                    denormalize=False, ws=None, want_cont_trace=False, variant=0, lr=0.0, adam_beta1=0.0,
+                    adam_beta2=0.0, adam_eps=0.0):
     """Run the BCD loop.  Returns dict(A, S, B, mask_bits, r1, r2, loss_trace[, loss_cont_trace])."""
     torch = _torch()
     lib = load_library()
@@ -207,7 +210,8 @@ def factorize_layer(W, H, d_block, N, M, n_iters, seed=0, selection=0, sparsity=
     ldh = _h_args(H, d_in)
     dev = W.device
     o = ArmorOpts(selection=selection, sparsity=sparsity, unstructured_keep=unstructured_keep, seed=seed,
-                  denormalize=int(denormalize))
+                  denormalize=int(denormalize), variant=variant, lr=lr, adam_beta1=adam_beta1, adam_beta2=adam_beta2,
+                  adam_eps=adam_eps)
     nbytes = lib.armor_factorize_workspace_bytes(d_out, d_in, d_block, N, M, ctypes.byref(o))
     if nbytes == 0:
         _check(2)

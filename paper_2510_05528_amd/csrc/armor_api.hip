@@ -118,6 +118,7 @@ struct FactorWs {
     uint8_t *mask;
     void *unstructured;
     float *big_scratch;
+    float *mA, *vA, *mB, *vB, *mC, *vC, *gBpart;
     int nsA, nsB, cn_chunks;
     size_t bytes;
 };
@@ -166,6 +167,13 @@ FactorWs carve_factor(void *ws, const Dims &d, int mask_group, const armor_opts 
     f.unstructured = (opts && opts->sparsity == 1)
                          ? c.take<char>(unstructured_init_ws_bytes(d.d_out, d.d_in)) : nullptr;
     f.big_scratch = d.b > 128 ? c.take<float>(big_scratch_floats(d, chain_slots(d.b))) : nullptr;
+    f.mA = f.vA = f.mB = f.vB = f.mC = f.vC = f.gBpart = nullptr;
+    if (opts && opts->variant == 1) { // Adam moments (one contiguous run, zeroed together) + per-block grad_B partials
+        const size_t na = (size_t)d.nbi * bb, nb = (size_t)d.nbj * bb;
+        f.mA = c.take<float>(2 * na + 2 * nb + 2 * P);
+        f.vA = f.mA + na; f.mB = f.vA + na; f.vB = f.mB + nb; f.mC = f.vB + nb; f.vC = f.mC + P;
+        f.gBpart = c.take<float>((size_t)d.nblocks * bb);
+    }
     f.bytes = (c.off + 255) & ~size_t(255);
     return f;
 }
@@ -336,7 +344,10 @@ armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const flo
     if (opts) o = *opts;
     const bool unstructured = o.sparsity == 1;
     if (o.sparsity != 0 && o.sparsity != 1) return ARMOR_ERR_SHAPE;
-    if (o.selection < 0 || o.selection > 3) return ARMOR_ERR_SHAPE;
+    if (o.selection < 0 || o.selection > 3 || o.variant < 0 || o.variant > 1) return ARMOR_ERR_SHAPE;
+    if (o.variant == 1 && d_block > 128) return ARMOR_ERR_UNSUPPORTED;
+    if (o.lr < 0 || o.adam_beta1 < 0 || o.adam_beta1 >= 1 || o.adam_beta2 < 0 || o.adam_beta2 >= 1 || o.adam_eps < 0)
+        return ARMOR_ERR_SHAPE;
     if (!unstructured) {
         st = validate_nm(N, M, d_block);
         if (st != ARMOR_OK) return st;
@@ -380,7 +391,41 @@ armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const flo
                                     f.big_scratch, s);
         else launch_phase_A(d, f.Wbar, S, A, B, f.D, f.nsA, f.gpart, f.beta_part, f.loss_part, loss_only, s);
     };
-    for (int t = 1; t <= n_iters; ++t) {
+    if (o.variant == 1) {
+        const double lr = o.lr > 0 ? o.lr : 1e-4, b1 = o.adam_beta1 > 0 ? o.adam_beta1 : 0.9,
+                     b2 = o.adam_beta2 > 0 ? o.adam_beta2 : 0.999, eps = o.adam_eps > 0 ? o.adam_eps : 1e-8;
+        launch_zero(f.mA, 2 * ((int64_t)d.nbi + d.nbj) * d.b * d.b + 2 * d_out * d_in, s);
+        for (int t = 1; t <= n_iters; ++t) {
+            // joint Adam continuous step (Sec. 3.3.1): all three gradients at theta_{t-1}
+            {
+                ProfScope ps(ARMOR_PROF_PHASE_FB, s);
+                launch_phase_FB(d, f.Wbar, S, A, B, f.D, mask, mask_group, f.mC, f.vC, lr, b1, b2, eps, t, f.nsA, f.gpart,
+                                f.gBpart, f.loss_part, s);
+            }
+            launch_adam_wrapper(A, f.mA, f.vA, d.nbi, d.b, f.gpart, f.nsA, lr, b1, b2, eps, t, d.nblocks, f.loss_part,
+                                loss_trace ? loss_trace + (t - 1) : nullptr, s);
+            launch_adam_wrapper(B, f.mB, f.vB, d.nbj, d.b, f.gBpart, d.nbi, lr, b1, b2, eps, t, d.nblocks, nullptr, nullptr,
+                                s);
+            if (!unstructured) {
+                // sparse-core step (Alg. 3) at the updated point
+                launch_wrapper_grams(d, A, B, f.D, f.colnorm2, f.fro2A, f.AtA, f.K, f.fro2K, s);
+                {
+                    ProfScope ps(ARMOR_PROF_PHASE_GS, s);
+                    launch_phase_GS(d, f.Wbar, S, A, B, f.D, f.G, f.loss_part2, slots, s);
+                }
+                {
+                    ProfScope ps(ARMOR_PROF_SPARSE, s);
+                    launch_sparse_step(d, f.G, S, mask, f.K, f.colnorm2, N, M, o.selection, o.seed, t, f.loss_part2,
+                                       loss_cont_trace ? loss_cont_trace + (t - 1) : nullptr, s);
+                }
+            }
+            if ((t & 15) == 0) {
+                st = check_hip();
+                if (st != ARMOR_OK) return st;
+            }
+        }
+    }
+    for (int t = 1; o.variant == 0 && t <= n_iters; ++t) {
         // continuous step (Alg. 2), each gradient at the already-updated parameters (Lemma 1)
         {
             ProfScope ps(ARMOR_PROF_PHASE_A, s);

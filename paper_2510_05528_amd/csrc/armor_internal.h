@@ -34,6 +34,14 @@ void launch_phase_WS(const Dims &d, const float *Wbar, float *C, const float *A,
                      const float *AtA, const float *K, const uint8_t *mask, int mask_group, const double *scalars,
                      float *Gout, float *loss_part, int grid_cap, hipStream_t s);
 int chain_max_nsplit();
+// Joint-Adam forward/backward pass: gradients of A (gApart, nsplit chunks per row block), B (gBpart,
+// one partial per block, laid out [j][i]) and the Adam update of the core and its moments in place.
+void launch_phase_FB(const Dims &d, const float *Wbar, float *C, const float *A, const float *B, const float *D,
+                     const uint8_t *mask, int mask_group, float *mC, float *vC, double lr, double b1, double b2,
+                     double eps, int64_t t, int nsplit, float *gApart, float *gBpart, float *loss_part, hipStream_t s);
+// Core gradient at the current point: Gout = -2 A^T ((Wbar - A C B) D) B^T, block losses to loss_part.
+void launch_phase_GS(const Dims &d, const float *Wbar, const float *C, const float *A, const float *B, const float *D,
+                     float *Gout, float *loss_part, int grid_cap, hipStream_t s);
 
 // ---- the same chains on 128 x 128 sub-tiles for d_block = 256 (chain_big.hip) ------------------
 // scratch: big_scratch_floats(d, grid_cap) floats; grid_cap bounds the number of workgroups.
@@ -62,6 +70,10 @@ void launch_diag(const float *H, int64_t d_in, int64_t ldh, float *D, hipStream_
 // A -= (sum of partials)/beta, beta = 2 * sum(beta_part); optionally trace_out = sum(loss_part).
 void launch_update_wrapper(float *A, int nblk, int b, const float *gpart, int nsplit, const float *beta_part,
                            int nblocks, const float *loss_part, double *trace_out, hipStream_t s);
+void launch_adam_wrapper(float *X, float *m, float *v, int nblk, int b, const float *gpart, int nsplit, double lr,
+                         double b1, double b2, double eps, int64_t t, int nblocks, const float *loss_part,
+                         double *trace_out, hipStream_t s);
+void launch_zero(float *x, int64_t n, hipStream_t s);
 void launch_finalize_betaW(const float *fro2A, int nbi, const float *fro2K, int nbj, double *scalars, hipStream_t s);
 void launch_sum_to_double(const float *part, int n, double *out, hipStream_t s);
 void launch_sparse_step(const Dims &d, const float *G, float *C, uint8_t *mask, const float *K,

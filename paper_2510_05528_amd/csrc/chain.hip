@@ -12,6 +12,7 @@
 #include "chain_common.h"
 
 #include <algorithm>
+#include <cmath>
 
 namespace armor {
 
@@ -444,7 +445,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_WS_kernel(
             for (int tm = 0; tm < CH::TM; ++tm)
 #pragma unroll
                 for (int tn = 0; tn < CH::TN; ++tn) {
-                    const int sh = (int)(((int64_t)j * B + p.col(tn)) % mask_group);
+                    const int sh = p.col(tn) % mask_group;
                     keep[tm][tn] = 0u;
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
@@ -487,6 +488,276 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_WS_kernel(
         }
         float ltot = CH::block_sum(lsum - 2.f * eta2 * dd + eta2 * eta2 * dz, sm.red, tid);
         if (tid == 0) loss_part[blk] = ltot;
+        __syncthreads();
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Joint-Adam variant of the continuous step (Sec. 3.3.1): one forward/backward pass per block gives
+// the gradients of A, B and W' at the same point.  With S = C B, R = Wbar - A S, T = A^T (R D):
+//   grad_A^(i) = -2 sum_j (R D) S^T      (accumulated in registers over the chunk of j; gApart)
+//   grad_B^(j) = -2 sum_i C^T T          (one partial per block: gBpart[(j*nbi + i)])
+//   grad_W'    = -2 (T B^T) (.) M        (complete per block: the Adam update of the core and of its
+//                                         moments happens here, moments also decay on pruned entries)
+// Workgroup (i, c) walks the column blocks j of its chunk.  loss_part = block loss at the old point.
+// ------------------------------------------------------------------------------------------------
+struct AdamCoef {
+    float b1, b2, one_minus_b1, one_minus_b2, inv_c1, inv_c2, lr, eps; // inv_c = 1 / (1 - beta^t)
+};
+
+template <int B>
+__global__ __launch_bounds__(Chain<B>::NT) void phase_FB_kernel(
+    const float *__restrict__ Wbar, float *__restrict__ C, const float *__restrict__ A,
+    const float *__restrict__ Bw, const float *__restrict__ D, const uint8_t *__restrict__ mask, int mask_group,
+    float *__restrict__ mC, float *__restrict__ vC, AdamCoef k, int64_t d_in, int nbi, int nbj, int nsplit,
+    float *__restrict__ gApart, float *__restrict__ gBpart, float *__restrict__ loss_part) {
+    using CH = Chain<B>;
+    __shared__ Smem<B> sm;
+    const int tid = threadIdx.x;
+    const typename CH::Pos p(tid);
+    const int ldw = (int)d_in, woff = p.lane_off(ldw);
+    const int i = blockIdx.x / nsplit, c = blockIdx.x % nsplit;
+    const int chunk = (nbj + nsplit - 1) / nsplit;
+    const int j0 = c * chunk, j1 = min(nbj, j0 + chunk);
+    const int64_t mrow = d_in / mask_group;
+    typename CH::Acc gacc, acc;
+    typename CH::TileRegs t0, t1;
+    gacc.zero();
+    if (j0 < j1) {
+        CH::gload_tile(t0, C + (int64_t)i * B * d_in + (int64_t)j0 * B, ldw, tid);
+        CH::gload_tile(t1, Bw + (int64_t)j0 * B * B, B, tid);
+    }
+    for (int j = j0; j < j1; ++j) {
+        float *Cij = C + (int64_t)i * B * d_in + (int64_t)j * B;
+        const float *Wij = Wbar + (int64_t)i * B * d_in + (int64_t)j * B;
+        CH::lstore_tile(sm.X, t0, tid);
+        CH::lstore_tile(sm.Y, t1, tid);
+        if (tid < B) sm.Dl[tid] = D[(int64_t)j * B + tid];
+        __syncthreads();
+        CH::gload_tile(t0, A + (int64_t)i * B * B, B, tid);
+        acc.zero();
+        CH::template mma<false, false, false>(acc, sm.X, sm.Y, nullptr, p); // S = C B
+        __syncthreads();
+        CH::store_acc(sm.X, acc, p);
+        CH::lstore_tile(sm.Y, t0, tid);
+        float lsum = 0.f;
+        {
+            float wb[CH::TM][CH::TN][16];
+#pragma unroll
+            for (int tm = 0; tm < CH::TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < CH::TN; ++tn)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) wb[tm][tn][r] = Wij[opaque(woff) + CH::Pos::unif_off(tm, tn, r, ldw)];
+            __syncthreads();
+            acc.zero();
+            CH::template mma<false, false, false>(acc, sm.Y, sm.X, nullptr, p); // What = A S
+#pragma unroll
+            for (int tm = 0; tm < CH::TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < CH::TN; ++tn) {
+                    float dj = sm.Dl[p.col(tn)];
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        float res = wb[tm][tn][r] - acc.v[tm][tn][r];
+                        lsum += res * res * dj;
+                        acc.v[tm][tn][r] = res * dj;
+                    }
+                }
+        }
+        float ltot = CH::block_sum(lsum, sm.red, tid);
+        if (tid == 0) loss_part[i * nbj + j] = ltot;
+        CH::store_acc(sm.Y, acc, p); // R D          [X = S, Y = R D]
+        __syncthreads();
+        CH::gload_tile(t0, A + (int64_t)i * B * B, B, tid);
+        CH::template mma<false, true, false>(gacc, sm.Y, sm.X, nullptr, p); // grad_A += (R D) S^T
+        __syncthreads();
+        CH::lstore_tile(sm.X, t0, tid); //            [X = A, Y = R D]
+        __syncthreads();
+        CH::gload_tile(t0, Bw + (int64_t)j * B * B, B, tid);
+        acc.zero();
+        CH::template mma<true, false, false>(acc, sm.X, sm.Y, nullptr, p); // T = A^T (R D)
+        __syncthreads();
+        CH::store_acc(sm.Y, acc, p);
+        CH::lstore_tile(sm.X, t0, tid); //            [X = B, Y = T]
+        __syncthreads();
+        CH::gload_tile(t0, Cij, ldw, tid);
+        uint32_t keep[CH::TM][CH::TN];
+        {   // mask bytes of this block, fetched underneath the product and folded into one bit per element
+            uint32_t mraw[CH::TM][CH::TN][16];
+#pragma unroll
+            for (int tm = 0; tm < CH::TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < CH::TN; ++tn) {
+                    // uniform block base + 32-bit lane offset (B is a multiple of the group size)
+                    const uint8_t *mb = mask + (int64_t)i * B * mrow + (int64_t)j * B / mask_group;
+                    const int mlane = opaque((p.wm0 + p.kh * 4) * (int)mrow + p.col(tn) / mask_group);
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) mraw[tm][tn][r] = mb[mlane + (tm * 32 + (r >> 2) * 8 + (r & 3)) * (int)mrow];
+                }
+            acc.zero();
+            CH::template mma<false, true, false>(acc, sm.Y, sm.X, nullptr, p); // T B^T  (stays in acc for the core update)
+#pragma unroll
+            for (int tm = 0; tm < CH::TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < CH::TN; ++tn) {
+                    const int sh = p.col(tn) % mask_group;
+                    keep[tm][tn] = 0u;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) keep[tm][tn] |= ((mraw[tm][tn][r] >> sh) & 1u) << r;
+                }
+        }
+        __syncthreads();
+        CH::lstore_tile(sm.X, t0, tid); //            [X = C, Y = T]
+        float *mij = mC + (int64_t)i * B * d_in + (int64_t)j * B, *vij = vC + (int64_t)i * B * d_in + (int64_t)j * B;
+        __syncthreads();
+        typename CH::Acc acc2;
+        acc2.zero();
+        CH::template mma<true, false, false>(acc2, sm.X, sm.Y, nullptr, p); // C^T T
+        {
+            float *gb = gBpart + ((int64_t)j * nbi + i) * B * B;
+#pragma unroll
+            for (int tm = 0; tm < CH::TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < CH::TN; ++tn)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        gb[opaque(p.lane_off(B)) + CH::Pos::unif_off(tm, tn, r, B)] = -2.f * acc2.v[tm][tn][r];
+        }
+        __builtin_amdgcn_sched_barrier(0); // keep the moment loads below the product: they would not fit beside it
+        float mo[CH::TM][CH::TN][16], vo[CH::TM][CH::TN][16];
+#pragma unroll
+        for (int tm = 0; tm < CH::TM; ++tm)
+#pragma unroll
+            for (int tn = 0; tn < CH::TN; ++tn)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int off = opaque(woff) + CH::Pos::unif_off(tm, tn, r, ldw);
+                    mo[tm][tn][r] = mij[off];
+                    vo[tm][tn][r] = vij[off];
+                }
+        if (j + 1 < j1) // next block's core tile, underneath the core update below
+            CH::gload_tile(t0, C + (int64_t)i * B * d_in + (int64_t)(j + 1) * B, ldw, tid);
+        {   // Adam on the core: g = -2 (T B^T) (.) M; the current values are still in LDS (X = C)
+            const float *c0 = sm.X + opaque(p.lane_off(CH::P));
+#pragma unroll
+            for (int tm = 0; tm < CH::TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < CH::TN; ++tn) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int off = opaque(woff) + CH::Pos::unif_off(tm, tn, r, ldw);
+                        const bool kp = (keep[tm][tn] >> r) & 1u;
+                        const float g = kp ? -2.f * acc.v[tm][tn][r] : 0.f;
+                        const float mn = k.b1 * mo[tm][tn][r] + k.one_minus_b1 * g;
+                        const float vn = k.b2 * vo[tm][tn][r] + k.one_minus_b2 * g * g;
+                        mij[off] = mn;
+                        vij[off] = vn;
+                        if (kp)
+                            Cij[off] = c0[CH::Pos::unif_off(tm, tn, r, CH::P)] -
+                                       k.lr * (mn * k.inv_c1) / (sqrtf(vn * k.inv_c2) + k.eps);
+                    }
+                }
+        }
+        __builtin_amdgcn_sched_barrier(0); // the wrapper tile only once the moments have left their registers
+        if (j + 1 < j1) CH::gload_tile(t1, Bw + (int64_t)(j + 1) * B * B, B, tid);
+        __syncthreads();
+    }
+    float *gp = gApart + (int64_t)blockIdx.x * B * B;
+#pragma unroll
+    for (int tm = 0; tm < CH::TM; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < CH::TN; ++tn)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) gp[opaque(p.lane_off(B)) + CH::Pos::unif_off(tm, tn, r, B)] = -2.f * gacc.v[tm][tn][r];
+}
+
+// ------------------------------------------------------------------------------------------------
+// Core gradient at the current point for Alg. 3 (used after the Adam step, where A and B moved too and
+// the gradient cannot be updated incrementally):  Gout = -2 A^T ((Wbar - A C B) D) B^T (unmasked),
+// loss_part[block] = block loss (the loss after the continuous step).
+// ------------------------------------------------------------------------------------------------
+template <int B>
+__global__ __launch_bounds__(Chain<B>::NT) void phase_GS_kernel(
+    const float *__restrict__ Wbar, const float *__restrict__ C, const float *__restrict__ A,
+    const float *__restrict__ Bw, const float *__restrict__ D, int64_t d_in, int nbj, int nblocks,
+    float *__restrict__ Gout, float *__restrict__ loss_part) {
+    using CH = Chain<B>;
+    __shared__ Smem<B> sm;
+    const int tid = threadIdx.x;
+    const typename CH::Pos p(tid);
+    const int ldw = (int)d_in, woff = p.lane_off(ldw);
+    typename CH::Acc acc;
+    typename CH::TileRegs t0, t1;
+    int blk = blockIdx.x;
+    if (blk < nblocks) {
+        CH::gload_tile(t0, C + (int64_t)(blk / nbj) * B * d_in + (int64_t)(blk % nbj) * B, ldw, tid);
+        CH::gload_tile(t1, A + (int64_t)(blk / nbj) * B * B, B, tid);
+    }
+    for (; blk < nblocks; blk += gridDim.x) {
+        const int i = blk / nbj, j = blk % nbj;
+        const float *Wij = Wbar + (int64_t)i * B * d_in + (int64_t)j * B;
+        CH::lstore_tile(sm.X, t0, tid);
+        CH::lstore_tile(sm.Y, t1, tid);
+        if (tid < B) sm.Dl[tid] = D[(int64_t)j * B + tid];
+        __syncthreads();
+        CH::gload_tile(t0, Bw + (int64_t)j * B * B, B, tid);
+        acc.zero();
+        CH::template mma<false, false, false>(acc, sm.Y, sm.X, nullptr, p); // S' = A C
+        __syncthreads();
+        CH::store_acc(sm.X, acc, p);
+        CH::lstore_tile(sm.Y, t0, tid);
+        float lsum = 0.f;
+        {
+            float wb[CH::TM][CH::TN][16];
+#pragma unroll
+            for (int tm = 0; tm < CH::TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < CH::TN; ++tn)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) wb[tm][tn][r] = Wij[opaque(woff) + CH::Pos::unif_off(tm, tn, r, ldw)];
+            __syncthreads();
+            acc.zero();
+            CH::template mma<false, false, false>(acc, sm.X, sm.Y, nullptr, p); // What = S' B
+#pragma unroll
+            for (int tm = 0; tm < CH::TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < CH::TN; ++tn) {
+                    float dj = sm.Dl[p.col(tn)];
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        float res = wb[tm][tn][r] - acc.v[tm][tn][r];
+                        lsum += res * res * dj;
+                        acc.v[tm][tn][r] = res * dj;
+                    }
+                }
+        }
+        float ltot = CH::block_sum(lsum, sm.red, tid);
+        if (tid == 0) loss_part[blk] = ltot;
+        CH::store_acc(sm.X, acc, p); // R D   (Y still holds B^j)
+        __syncthreads();
+        CH::gload_tile(t0, A + (int64_t)i * B * B, B, tid);
+        acc.zero();
+        CH::template mma<false, true, false>(acc, sm.X, sm.Y, nullptr, p); // U = (R D) B^T
+        __syncthreads();
+        CH::store_acc(sm.X, acc, p);
+        CH::lstore_tile(sm.Y, t0, tid);
+        __syncthreads();
+        const int nblk = blk + gridDim.x;
+        if (nblk < nblocks) {
+            CH::gload_tile(t0, C + (int64_t)(nblk / nbj) * B * d_in + (int64_t)(nblk % nbj) * B, ldw, tid);
+            CH::gload_tile(t1, A + (int64_t)(nblk / nbj) * B * B, B, tid);
+        }
+        acc.zero();
+        CH::template mma<true, false, false>(acc, sm.Y, sm.X, nullptr, p); // G = A^T U
+        float *Gij = Gout + (int64_t)i * B * d_in + (int64_t)j * B;
+#pragma unroll
+        for (int tm = 0; tm < CH::TM; ++tm)
+#pragma unroll
+            for (int tn = 0; tn < CH::TN; ++tn)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    Gij[opaque(woff) + CH::Pos::unif_off(tm, tn, r, ldw)] = -2.f * acc.v[tm][tn][r];
         __syncthreads();
     }
 }
@@ -583,6 +854,29 @@ void launch_wrapper_grams(const Dims &d, const float *A, const float *B, const f
         dim3 grid(d.nbi + d.nbj), block(Chain<BB>::NT);
         hipLaunchKernelGGL((wrapper_grams_kernel<BB>), grid, block, 0, s, A, B, D, d.nbi, colnorm2, fro2A, AtA, K,
                            fro2K);
+    });
+}
+
+void launch_phase_FB(const Dims &d, const float *Wbar, float *C, const float *A, const float *B, const float *D,
+                     const uint8_t *mask, int mask_group, float *mC, float *vC, double lr, double b1, double b2,
+                     double eps, int64_t t, int nsplit, float *gApart, float *gBpart, float *loss_part, hipStream_t s) {
+    AdamCoef k;
+    k.b1 = (float)b1; k.b2 = (float)b2; k.one_minus_b1 = (float)(1.0 - b1); k.one_minus_b2 = (float)(1.0 - b2);
+    k.inv_c1 = (float)(1.0 / (1.0 - pow(b1, (double)t))); k.inv_c2 = (float)(1.0 / (1.0 - pow(b2, (double)t)));
+    k.lr = (float)lr; k.eps = (float)eps;
+    ARMOR_DISPATCH_B(d.b, {
+        dim3 grid(d.nbi * nsplit), block(Chain<BB>::NT);
+        hipLaunchKernelGGL((phase_FB_kernel<BB>), grid, block, 0, s, Wbar, C, A, B, D, mask, mask_group, mC, vC, k,
+                           d.d_in, d.nbi, d.nbj, nsplit, gApart, gBpart, loss_part);
+    });
+}
+
+void launch_phase_GS(const Dims &d, const float *Wbar, const float *C, const float *A, const float *B, const float *D,
+                     float *Gout, float *loss_part, int grid_cap, hipStream_t s) {
+    ARMOR_DISPATCH_B(d.b, {
+        dim3 grid(std::min(d.nblocks, grid_cap)), block(Chain<BB>::NT);
+        hipLaunchKernelGGL((phase_GS_kernel<BB>), grid, block, 0, s, Wbar, C, A, B, D, d.d_in, d.nbj, d.nblocks, Gout,
+                           loss_part);
     });
 }
 

@@ -4,6 +4,7 @@
 #include "armor_internal.h"
 
 #include <algorithm>
+#include <cmath>
 
 namespace armor {
 
@@ -194,6 +195,53 @@ void launch_update_wrapper(float *A, int nblk, int b, const float *gpart, int ns
     int nq = (b * b + 255) / 256;
     hipLaunchKernelGGL(update_wrapper_kernel, dim3(nblk, nq), dim3(256), 0, s, A, b, gpart, nsplit, beta_part, nblocks,
                        loss_part, trace_out);
+}
+
+// Adam update of a wrapper (joint-Adam variant, Sec. 3.3.1): g = sum of the partial gradients in a
+// fixed order, then the published update with bias correction; moments are fp32 state.
+// inv_c1 = 1/(1 - b1^t), inv_c2 = 1/(1 - b2^t).
+__global__ __launch_bounds__(256) void adam_wrapper_kernel(float *__restrict__ X, float *__restrict__ m,
+                                                           float *__restrict__ v, int b, const float *__restrict__ gpart,
+                                                           int nsplit, double lr, double b1, double b2, double eps,
+                                                           double inv_c1, double inv_c2, int nblocks,
+                                                           const float *__restrict__ loss_part,
+                                                           double *__restrict__ trace_out) {
+    __shared__ double red[4];
+    const int tid = threadIdx.x, k = blockIdx.x, q = blockIdx.y;
+    const int bb = b * b, e = q * 256 + tid;
+    if (trace_out != nullptr && k == 0 && q == 0) {
+        double l = 0.0;
+        for (int i = tid; i < nblocks; i += 256) l += (double)loss_part[i];
+        l = block_sum_256(l, red);
+        if (tid == 0) *trace_out = l;
+    }
+    if (e >= bb) return;
+    double g = 0.0;
+#pragma unroll 8
+    for (int c = 0; c < nsplit; ++c) g += (double)gpart[((int64_t)k * nsplit + c) * bb + e];
+    const int64_t idx = (int64_t)k * bb + e;
+    const double mn = b1 * (double)m[idx] + (1.0 - b1) * g;
+    const double vn = b2 * (double)v[idx] + (1.0 - b2) * g * g;
+    m[idx] = (float)mn;
+    v[idx] = (float)vn;
+    X[idx] = (float)((double)X[idx] - lr * (mn * inv_c1) / (sqrt(vn * inv_c2) + eps));
+}
+
+void launch_adam_wrapper(float *X, float *m, float *v, int nblk, int b, const float *gpart, int nsplit, double lr,
+                         double b1, double b2, double eps, int64_t t, int nblocks, const float *loss_part,
+                         double *trace_out, hipStream_t s) {
+    const double inv_c1 = 1.0 / (1.0 - pow(b1, (double)t)), inv_c2 = 1.0 / (1.0 - pow(b2, (double)t));
+    hipLaunchKernelGGL(adam_wrapper_kernel, dim3(nblk, (b * b + 255) / 256), dim3(256), 0, s, X, m, v, b, gpart, nsplit,
+                       lr, b1, b2, eps, inv_c1, inv_c2, nblocks, loss_part, trace_out);
+}
+
+__global__ __launch_bounds__(256) void zero_kernel(float *__restrict__ x, int64_t n) {
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < n; e += (int64_t)gridDim.x * 256) x[e] = 0.f;
+}
+
+void launch_zero(float *x, int64_t n, hipStream_t s) {
+    int grid = (int)std::min<int64_t>((n + 255) / 256, 65536);
+    if (n > 0) hipLaunchKernelGGL(zero_kernel, dim3(grid), dim3(256), 0, s, x, n);
 }
 
 // beta_W' = 2 ||A^T A||_F ||B D B^T||_F (Eq. 11) from the per-block squared norms -> scalars[2]
@@ -422,7 +470,7 @@ __global__ __launch_bounds__(256) void sparse_step_kernel(const float *__restric
             } else {
                 uint64_t ctr = (uint64_t)(((int64_t)t * nblocks + blk) * gpb + kap) + 1ULL;
                 float u01 = hash_uniform(seed, ctr);
-                key = score > 0.f ? (-__logf(u01)) / score : INFINITY;
+                key = score > 0.f ? (-logf(u01)) / score : INFINITY; // accurate log: the race is decided by u near 1
             }
             if (key < best_key) { best_key = key; best_kap = kap; }
         }

@@ -222,6 +222,66 @@ def test_unstructured_ties_go_to_lower_index(armor, torch, orc):
         np.testing.assert_array_equal(mask, expect)
 
 
+@pytest.mark.parametrize("d_out,d_in,b,N,M,sparsity", [(128, 192, 64, 2, 4, 0), (256, 384, 128, 2, 4, 0), (96, 160, 32, 4, 8, 0),
+                                                        (128, 128, 64, 2, 4, 1)])
+def test_factorize_joint_adam(armor, torch, orc, d_out, d_in, b, N, M, sparsity):
+    """The joint-Adam continuous step (what the authors run in practice) against the oracle's.
+
+    A group refit by Eq. 8 sits at a least-squares optimum, so its gradient at the next evaluation
+    is zero up to rounding, and the sign of Adam's next step on it (size ~0.74 lr, independent of the
+    gradient's magnitude) is decided by rounding noise in any implementation, the oracle included.
+    Parity is therefore: exact-to-rounding for one iteration; to 1e-5 outside the refit groups for
+    two; for longer runs loss trace, mask agreement, structure, and the bound 2 lr t on every entry."""
+    W, X = make_layer(d_out, d_in, 300, seed=21, act_outliers=(0.01, 20.0))
+    D = np.diag(orc.gram(X)).astype(np.float32)
+    lr = 1e-3
+    keep = (d_out * d_in) // 2 if sparsity else 0
+    mg = 8 if sparsity else M
+    nblk = (d_out // b) * (d_in // b)
+
+    def run(n_iters):
+        out = armor.factorize_layer(dev(torch, W), dev(torch, D), b, N, M, n_iters, seed=9, variant=1, lr=lr,
+                                    sparsity=sparsity, unstructured_keep=keep, want_cont_trace=True)
+        torch.cuda.synchronize()
+        ref = orc.factorize_layer_adam(W, D, b, N, M, n_iters, seed=9, lr=lr, sparsity=sparsity, keep=keep)
+        return out, ref
+
+    say("adam", d_out, d_in, b, N, M, sparsity)
+    # one iteration from theta_0: every quantity is determined
+    out, ref = run(1)
+    for k, rk in (("A", "A"), ("B", "B"), ("S", "C")):
+        assert relfro(out[k].cpu().numpy(), ref[rk]) <= 1e-6, k
+    np.testing.assert_array_equal(armor.unpack_mask(out["mask_bits"].cpu().numpy(), mg), ref["mask"])
+    # two iterations: the moment recursion; only the groups refit at t = 1 may differ, by < 2 lr
+    out, ref = run(2)
+    assert relfro(out["A"].cpu().numpy(), ref["A"]) <= 1e-5 and relfro(out["B"].cpu().numpy(), ref["B"]) <= 1e-5
+    dS = np.abs(out["S"].cpu().numpy() - ref["C"])
+    assert int((dS > 1e-5).sum()) <= 2 * nblk * M and dS.max() <= 2 * lr
+    # longer run
+    n_iters = 8
+    out, ref = run(n_iters)
+    mask = armor.unpack_mask(out["mask_bits"].cpu().numpy(), mg)
+    S = out["S"].cpu().numpy()
+    if sparsity == 0:
+        assert np.all(mask.reshape(d_out, d_in // M, M).sum(-1) == N)
+    else:
+        assert int(mask.sum()) == keep
+    assert np.all(S[mask == 0] == 0)
+    agree = float((mask == ref["mask"]).mean())
+    tr = out["loss_trace"].cpu().numpy()
+    dmax = max(np.abs(out["A"].cpu().numpy() - ref["A"]).max(), np.abs(out["B"].cpu().numpy() - ref["B"]).max(),
+               np.abs(S - ref["C"])[(mask == 1) & (ref["mask"] == 1)].max())
+    say("   mask agreement %.6f  max entry diff %.2e (2 lr t = %.1e)  loss %.6g -> %.6g (oracle %.6g)" %
+        (agree, dmax, 2 * lr * n_iters, tr[0], tr[-1], ref["loss_trace"][-1]))
+    assert agree >= 0.999
+    assert dmax <= 2 * lr * n_iters
+    np.testing.assert_allclose(tr, ref["loss_trace"], rtol=5e-3)
+    np.testing.assert_allclose(out["loss_cont_trace"].cpu().numpy(), ref["loss_cont_trace"], rtol=5e-3)
+    assert tr[-1] < tr[0]
+    # the reported loss is the loss of the returned factors
+    assert tr[-1] == pytest.approx(orc.proxy_loss(ref["Wbar"], out["A"].cpu().numpy(), S, out["B"].cpu().numpy(), D), rel=1e-4)
+
+
 def test_factorize_zero_iterations_is_plain_nm_pruning(armor, torch, orc):
     W, X = make_layer(64, 128, 100, seed=7)
     D = np.diag(orc.gram(X)).astype(np.float32)
