@@ -244,6 +244,19 @@ def main():
                 "algorithmic_flops_per_launch": flops, "avg_launch_ms": chain[dom]["avg_ms"]}
     for k in chain:
         kernels[k]["tflops_algorithmic"] = chain_algorithmic_flops(k, d_out, d_in, b, N, M) / (chain[k]["avg_ms"] * 1e-3) / 1e12
+    # HBM-bound kernels: algorithmic bytes (each operand read or written once) over the measured duration
+    P, wb = d_out * d_in, (2 if w_bf16 else 4)
+    hbm_bytes = {
+        "sparse_step": 4 * P,                                   # one pass over the core gradient
+        "normalize": 2 * wb * P + 4 * P,                        # W for the column norms, W again for rows + scaling, Wbar out
+        "init": 4 * P + 4 * P + P // M,                         # Wbar in, core out, one mask byte per group
+        "pack_nm": 4 * P + P // M + 2 * (P * N // M) + P * N // M // 4,  # core + mask in, bf16 values + 2-bit indices out
+    }
+    for k, nbytes in hbm_bytes.items():
+        if k in kernels:
+            kernels[k]["algorithmic_bytes"] = nbytes
+            kernels[k]["hbm_GBps"] = nbytes / (kernels[k]["avg_ms"] * 1e-3) / 1e9
+            kernels[k]["hbm_frac_of_8TBps"] = kernels[k]["hbm_GBps"] / 8000.0
     if "gram" in kernels:
         kernels["gram"]["tflops_algorithmic"] = n_tok * d_in * (d_in + 1) / (kernels["gram"]["avg_ms"] * 1e-3) / 1e12
 

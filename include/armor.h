@@ -80,7 +80,11 @@ int armor_last_hip_error(void);
 #define ARMOR_PROF_SPARSE 4
 #define ARMOR_PROF_PHASE_FB 5 /* joint-Adam forward/backward chain */
 #define ARMOR_PROF_PHASE_GS 6 /* core-gradient chain of the joint-Adam variant */
-#define ARMOR_PROF_KINDS 7
+#define ARMOR_PROF_NORMALIZE 7 /* column norms + row norms and scaling (two kernels) */
+#define ARMOR_PROF_INIT 8      /* initial mask and core (Eq. 3), N:M or unstructured */
+#define ARMOR_PROF_PACK 9      /* armor_pack_nm */
+#define ARMOR_PROF_SMALL 10    /* wrapper updates, wrapper Grams, step-size scalars */
+#define ARMOR_PROF_KINDS 11
 armor_status armor_profile_enable(int on);
 armor_status armor_profile_read(double *ms_total /*host [ARMOR_PROF_KINDS]*/, int64_t *launches /*host*/);
 
@@ -150,11 +154,18 @@ armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const flo
                                    size_t ws_bytes, void *hip_stream);
 
 /*
- * Compressed N:M storage of the core (the form an N:M sparse matmul consumes):
+ * Compressed N:M storage of the core (the form an N:M sparse matmul consumes; Sec. 3.1 stores the
+ * core as an N:M matrix):
  *   values [d_out][d_in/M*N]  the kept entries of each group in increasing column order
  *          (fp32 or bf16 per v_dtype);
- *   meta   [d_out][d_in/M*N]  one byte per kept entry: its column inside the group (0..M-1).
+ *   meta   [d_out][meta_row]  per kept entry, in the same order, its column inside the group
+ *          (0..M-1) in a field of 1, 2 or 4 bits for M = 2, 4, 8; fields fill each byte from bit 0
+ *          upwards; meta_row = ceil(d_in/M*N*field_bits / 8) bytes, so every row starts on a byte
+ *          boundary and unused bits of a row's last byte are zero.  For 2:4 one byte holds the
+ *          four 2-bit indices of two groups.
+ * S must be 16-byte aligned.  armor_pack_meta_row_bytes returns meta_row (0 on a bad shape).
  */
+int64_t armor_pack_meta_row_bytes(int64_t d_in, int N, int M);
 armor_status armor_pack_nm(const float *S, const uint8_t *mask_bits, int64_t d_out, int64_t d_in, int N, int M,
                            void *values, armor_dtype v_dtype, uint8_t *meta, void *hip_stream);
 

@@ -278,3 +278,15 @@ def pack_nm(C, mask, N, M):
     lib().oracle_pack_nm(_p(C, _f32p), _p(mask, _u8p), _i64(d_out), _i64(d_in), ctypes.c_int(N), ctypes.c_int(M),
                          _p(values, _f32p), _p(index, _u8p))
     return values, index
+
+
+def pack_index_bits(index, M):
+    """Byte-per-entry indices [d_out, entries] -> compact bit fields [d_out, ceil(entries*w/8)]."""
+    index = np.ascontiguousarray(index, dtype=np.uint8)
+    d_out, entries = index.shape
+    w = {2: 1, 4: 2, 8: 4}[M]
+    row_bytes = (entries * w + 7) // 8
+    packed = np.zeros((d_out, row_bytes), dtype=np.uint8)
+    lib().oracle_pack_index_bits(_p(index, _u8p), _i64(d_out), _i64(entries), ctypes.c_int(w), _p(packed, _u8p),
+                                 _i64(row_bytes))
+    return packed

@@ -772,7 +772,8 @@ void oracle_denormalize(float *A, float *B, const float *r1, const float *r2, in
 
 /* ------------------------------------------------------------------------------------------
  * Compressed N:M storage: for each row and group, the N kept values in increasing column order
- * and their in-group column indices (one byte each here; the product packs them tighter).
+ * and their in-group column indices: one byte each from oracle_pack_nm, the compact bit
+ * fields from oracle_pack_index_bits.
  * ------------------------------------------------------------------------------------------ */
 void oracle_pack_nm(const float *C, const uint8_t *mask, int64_t d_out, int64_t d_in, int N, int M,
                     float *values, uint8_t *index) {
@@ -786,4 +787,19 @@ void oracle_pack_nm(const float *C, const uint8_t *mask, int64_t d_out, int64_t 
                     ++x;
                 }
         }
+}
+
+/* The index stream in its compact form: entry e of a row (e counts kept entries left to right) occupies
+ * field_bits bits (1, 2 or 4 for M = 2, 4, 8) starting at bit e*field_bits of the row, bit 0 being the
+ * least significant bit of the row's first byte.  row_bytes = ceil(entries*field_bits / 8). */
+void oracle_pack_index_bits(const uint8_t *index, int64_t d_out, int64_t entries, int field_bits,
+                            uint8_t *packed, int64_t row_bytes) {
+    for (int64_t i = 0; i < d_out; ++i) {
+        for (int64_t q = 0; q < row_bytes; ++q) packed[i * row_bytes + q] = 0;
+        for (int64_t e = 0; e < entries; ++e)
+            for (int t = 0; t < field_bits; ++t) {
+                int64_t pos = e * field_bits + t;
+                if ((index[i * entries + e] >> t) & 1) packed[i * row_bytes + pos / 8] |= (uint8_t)(1u << (pos % 8));
+            }
+    }
 }

@@ -9,12 +9,14 @@ _LIB_PATH = os.path.join(_HERE, "libarmor.so")
 
 ARMOR_F32, ARMOR_BF16 = 0, 1
 
-PROF_KINDS = ["gram", "phase_A", "phase_B", "phase_WS", "sparse_step", "phase_FB", "phase_GS"]
+PROF_KINDS = ["gram", "phase_A", "phase_B", "phase_WS", "sparse_step", "phase_FB", "phase_GS", "normalize", "init",
+              "pack_nm", "small_kernels"]
 
 EXPORTED = ["armor_status_string", "armor_last_hip_error", "armor_profile_enable", "armor_profile_read",
             "armor_gram_workspace_bytes", "armor_gram", "armor_gram_diag",
             "armor_normalize_workspace_bytes", "armor_normalize", "armor_proxy_loss_workspace_bytes",
-            "armor_proxy_loss", "armor_factorize_workspace_bytes", "armor_factorize_layer", "armor_pack_nm"]
+            "armor_proxy_loss", "armor_factorize_workspace_bytes", "armor_factorize_layer", "armor_pack_nm",
+            "armor_pack_meta_row_bytes"]
 
 
 class ArmorError(RuntimeError):
@@ -60,6 +62,8 @@ def load_library():
     lib.armor_factorize_layer.argtypes = [_vp, _int, _vp, _i64, _i64, _i64, _i64, _int, _int, _int,
                                           ctypes.POINTER(ArmorOpts), _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz,
                                           _vp]
+    lib.armor_pack_meta_row_bytes.argtypes = [_i64, _int, _int]
+    lib.armor_pack_meta_row_bytes.restype = _i64
     lib.armor_pack_nm.argtypes = [_vp, _vp, _i64, _i64, _int, _int, _vp, _int, _vp, _vp]
     _lib = lib
     return lib
@@ -241,10 +245,22 @@ def pack_nm(S, mask_bits, N, M, bf16=False):
     _dev_f32(S, "S")
     d_out, d_in = S.shape
     values = torch.empty((d_out, d_in // M * N), device=S.device, dtype=torch.bfloat16 if bf16 else torch.float32)
-    meta = torch.empty((d_out, d_in // M * N), device=S.device, dtype=torch.uint8)
+    meta_row = int(lib.armor_pack_meta_row_bytes(d_in, N, M))
+    if meta_row <= 0:
+        raise ArmorError("armor_pack_nm: bad shape")
+    meta = torch.empty((d_out, meta_row), device=S.device, dtype=torch.uint8)
     _check(lib.armor_pack_nm(_ptr(S), _ptr(mask_bits), d_out, d_in, N, M, _ptr(values), ARMOR_BF16 if bf16 else ARMOR_F32,
                              _ptr(meta), _stream()))
     return values, meta
+
+
+def unpack_meta(meta, d_in, N, M):
+    """Host helper: bit-packed in-group column indices -> [d_out, d_in/M*N] bytes."""
+    mb = np.asarray(meta, dtype=np.uint8)
+    w = {2: 1, 4: 2, 8: 4}[M]
+    per = 8 // w
+    fields = (mb[..., None] >> (np.arange(per, dtype=np.uint8) * w)) & ((1 << w) - 1)
+    return fields.reshape(mb.shape[0], -1)[:, :d_in // M * N].astype(np.uint8)
 
 
 def unpack_mask(mask_bits, M):

@@ -159,7 +159,7 @@ FactorWs carve_factor(void *ws, const Dims &d, int mask_group, const armor_opts 
     f.colnorm2 = c.take<float>(d.d_out);
     f.fro2A = c.take<float>(d.nbi);
     f.fro2K = c.take<float>(d.nbj);
-    f.cn_partial = c.take<float>((size_t)f.cn_chunks * d.d_in);
+    f.cn_partial = c.take<float>(((size_t)f.cn_chunks + 1) * d.d_in); // chunk sums, then 1/r1
     f.r1 = c.take<float>(d.d_in);
     f.r2 = c.take<float>(d.d_out);
     f.scalars = c.take<double>(8);
@@ -258,7 +258,7 @@ armor_status armor_gram_diag(const float *H, int64_t d_in, int64_t ldh, float *D
 
 size_t armor_normalize_workspace_bytes(int64_t d_out, int64_t d_in) {
     if (d_out <= 0 || d_in <= 0) return 0;
-    return (size_t)colnorm_chunks(d_out) * (size_t)d_in * sizeof(float) + 256;
+    return ((size_t)colnorm_chunks(d_out) + 1) * (size_t)d_in * sizeof(float) + 256;
 }
 
 armor_status armor_normalize(const void *W, armor_dtype w_dtype, int64_t d_out, int64_t d_in, float *Wbar, float *r1,
@@ -271,9 +271,12 @@ armor_status armor_normalize(const void *W, armor_dtype w_dtype, int64_t d_out, 
     hipStream_t s = (hipStream_t)hip_stream;
     Carver c(ws);
     int chunks = colnorm_chunks(d_out);
-    float *partial = c.take<float>((size_t)chunks * d_in);
-    launch_colnorm(W, w_dtype == ARMOR_BF16, d_out, d_in, partial, chunks, r1, s);
-    launch_rownorm_scale(W, w_dtype == ARMOR_BF16, d_out, d_in, r1, r2, Wbar, s);
+    float *partial = c.take<float>(((size_t)chunks + 1) * d_in); // chunk sums, then 1/r1
+    {
+        ProfScope ps(ARMOR_PROF_NORMALIZE, s);
+        launch_colnorm(W, w_dtype == ARMOR_BF16, d_out, d_in, partial, chunks, r1, s);
+        launch_rownorm_scale(W, w_dtype == ARMOR_BF16, d_out, d_in, partial + (size_t)chunks * d_in, r2, Wbar, s);
+    }
     return check_hip();
 }
 
@@ -372,15 +375,21 @@ armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const flo
     if (ldh > 0) launch_diag(H, d_in, ldh, f.D, s);
     else if (hipMemcpyAsync(f.D, H, sizeof(float) * d_in, hipMemcpyDeviceToDevice, s) != hipSuccess) return check_hip();
     // Alg. 1: normalise, initialise
-    launch_colnorm(W, w_dtype == ARMOR_BF16, d_out, d_in, f.cn_partial, f.cn_chunks, r1p, s);
-    launch_rownorm_scale(W, w_dtype == ARMOR_BF16, d_out, d_in, r1p, r2p, f.Wbar, s);
+    {
+        ProfScope ps(ARMOR_PROF_NORMALIZE, s);
+        launch_colnorm(W, w_dtype == ARMOR_BF16, d_out, d_in, f.cn_partial, f.cn_chunks, r1p, s);
+        launch_rownorm_scale(W, w_dtype == ARMOR_BF16, d_out, d_in, f.cn_partial + (size_t)f.cn_chunks * d_in, r2p, f.Wbar, s);
+    }
     launch_init_identity(A, d.nbi, d.b, s);
     launch_init_identity(B, d.nbj, d.b, s);
-    if (unstructured)
-        launch_unstructured_init(f.Wbar, f.D, d_out, d_in, o.unstructured_keep, S, mask,
-                                 reinterpret_cast<uint32_t *>(f.G), f.unstructured, s);
-    else
-        launch_init_nm(f.Wbar, f.D, d_out, d_in, N, M, S, mask, s);
+    {
+        ProfScope ps(ARMOR_PROF_INIT, s);
+        if (unstructured)
+            launch_unstructured_init(f.Wbar, f.D, d_out, d_in, o.unstructured_keep, S, mask,
+                                     reinterpret_cast<uint32_t *>(f.G), f.unstructured, s);
+        else
+            launch_init_nm(f.Wbar, f.D, d_out, d_in, N, M, S, mask, s);
+    }
     st = check_hip();
     if (st != ARMOR_OK) return st;
 
@@ -402,13 +411,16 @@ armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const flo
                 launch_phase_FB(d, f.Wbar, S, A, B, f.D, mask, mask_group, f.mC, f.vC, lr, b1, b2, eps, t, f.nsA, f.gpart,
                                 f.gBpart, f.loss_part, s);
             }
-            launch_adam_wrapper(A, f.mA, f.vA, d.nbi, d.b, f.gpart, f.nsA, lr, b1, b2, eps, t, d.nblocks, f.loss_part,
-                                loss_trace ? loss_trace + (t - 1) : nullptr, s);
-            launch_adam_wrapper(B, f.mB, f.vB, d.nbj, d.b, f.gBpart, d.nbi, lr, b1, b2, eps, t, d.nblocks, nullptr, nullptr,
-                                s);
+            {
+                ProfScope ps(ARMOR_PROF_SMALL, s);
+                launch_adam_wrapper(A, f.mA, f.vA, d.nbi, d.b, f.gpart, f.nsA, lr, b1, b2, eps, t, d.nblocks, f.loss_part,
+                                    loss_trace ? loss_trace + (t - 1) : nullptr, s);
+                launch_adam_wrapper(B, f.mB, f.vB, d.nbj, d.b, f.gBpart, d.nbi, lr, b1, b2, eps, t, d.nblocks, nullptr,
+                                    nullptr, s);
+                if (!unstructured) launch_wrapper_grams(d, A, B, f.D, f.colnorm2, f.fro2A, f.AtA, f.K, f.fro2K, s);
+            }
             if (!unstructured) {
                 // sparse-core step (Alg. 3) at the updated point
-                launch_wrapper_grams(d, A, B, f.D, f.colnorm2, f.fro2A, f.AtA, f.K, f.fro2K, s);
                 {
                     ProfScope ps(ARMOR_PROF_PHASE_GS, s);
                     launch_phase_GS(d, f.Wbar, S, A, B, f.D, f.G, f.loss_part2, slots, s);
@@ -431,17 +443,23 @@ armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const flo
             ProfScope ps(ARMOR_PROF_PHASE_A, s);
             run_phase_A(false);
         }
-        launch_update_wrapper(A, d.nbi, d.b, f.gpart, f.nsA, f.beta_part, d.nblocks, f.loss_part,
-                              loss_trace ? loss_trace + (t - 1) : nullptr, s);
+        {
+            ProfScope ps(ARMOR_PROF_SMALL, s);
+            launch_update_wrapper(A, d.nbi, d.b, f.gpart, f.nsA, f.beta_part, d.nblocks, f.loss_part,
+                                  loss_trace ? loss_trace + (t - 1) : nullptr, s);
+        }
         {
             ProfScope ps(ARMOR_PROF_PHASE_B, s);
             if (big) launch_big_phase_B(d, f.Wbar, S, A, B, f.D, f.nsB, f.gpart, f.beta_part, slots, f.big_scratch, s);
             else launch_phase_B(d, f.Wbar, S, A, B, f.D, f.nsB, f.gpart, f.beta_part, s);
         }
-        launch_update_wrapper(B, d.nbj, d.b, f.gpart, f.nsB, f.beta_part, d.nblocks, nullptr, nullptr, s);
-        if (big) launch_big_wrapper_grams(d, A, B, f.D, f.colnorm2, f.fro2A, f.AtA, f.K, f.fro2K, s);
-        else launch_wrapper_grams(d, A, B, f.D, f.colnorm2, f.fro2A, f.AtA, f.K, f.fro2K, s);
-        launch_finalize_betaW(f.fro2A, d.nbi, f.fro2K, d.nbj, f.scalars, s);
+        {
+            ProfScope ps(ARMOR_PROF_SMALL, s);
+            launch_update_wrapper(B, d.nbj, d.b, f.gpart, f.nsB, f.beta_part, d.nblocks, nullptr, nullptr, s);
+            if (big) launch_big_wrapper_grams(d, A, B, f.D, f.colnorm2, f.fro2A, f.AtA, f.K, f.fro2K, s);
+            else launch_wrapper_grams(d, A, B, f.D, f.colnorm2, f.fro2A, f.AtA, f.K, f.fro2K, s);
+            launch_finalize_betaW(f.fro2A, d.nbi, f.fro2K, d.nbj, f.scalars, s);
+        }
         if (unstructured) {
             // Sec. 4.5: continuous step only.  W' step on the kept entries, no core-gradient follow-up.
             ProfScope ps(ARMOR_PROF_PHASE_WS, s);
@@ -479,12 +497,22 @@ armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const flo
     return check_hip();
 }
 
+int64_t armor_pack_meta_row_bytes(int64_t d_in, int N, int M) {
+    if (d_in <= 0 || (M != 2 && M != 4 && M != 8) || N < 1 || N >= M || d_in % M != 0) return 0;
+    const int field_bits = M == 2 ? 1 : (M == 4 ? 2 : 4);
+    return (d_in / M * N * field_bits + 7) / 8;
+}
+
 armor_status armor_pack_nm(const float *S, const uint8_t *mask_bits, int64_t d_out, int64_t d_in, int N, int M,
                            void *values, armor_dtype v_dtype, uint8_t *meta, void *hip_stream) {
     if (!S || !mask_bits || !values || !meta) return ARMOR_ERR_NULL;
     if (v_dtype != ARMOR_F32 && v_dtype != ARMOR_BF16) return ARMOR_ERR_DTYPE;
     if (d_out <= 0 || d_in <= 0 || (M != 2 && M != 4 && M != 8) || N < 1 || N >= M || d_in % M != 0) return ARMOR_ERR_SHAPE;
-    launch_pack_nm(S, mask_bits, d_out, d_in, N, M, values, v_dtype == ARMOR_BF16, meta, (hipStream_t)hip_stream);
+    if (!aligned16(S)) return ARMOR_ERR_ALIGN;
+    {
+        ProfScope ps(ARMOR_PROF_PACK, (hipStream_t)hip_stream);
+        launch_pack_nm(S, mask_bits, d_out, d_in, N, M, values, v_dtype == ARMOR_BF16, meta, (hipStream_t)hip_stream);
+    }
     return check_hip();
 }
 

@@ -59,9 +59,10 @@ void launch_big_wrapper_grams(const Dims &d, const float *A, const float *B, con
                               float *fro2A, float *AtA, float *K, float *fro2K, hipStream_t s);
 
 // ---- small kernels (small.hip) ----------------------------------------------------------------
+// partial: (nchunk + 1) * d_in floats; the last d_in receive 1 / r1, which launch_rownorm_scale takes
 void launch_colnorm(const void *W, int bf16, int64_t d_out, int64_t d_in, float *partial, int nchunk, float *r1,
                     hipStream_t s);
-void launch_rownorm_scale(const void *W, int bf16, int64_t d_out, int64_t d_in, const float *r1, float *r2,
+void launch_rownorm_scale(const void *W, int bf16, int64_t d_out, int64_t d_in, const float *r1_inv, float *r2,
                           float *Wbar, hipStream_t s);
 void launch_init_identity(float *A, int nblk, int b, hipStream_t s);
 void launch_init_nm(const float *Wbar, const float *D, int64_t d_out, int64_t d_in, int N, int M, float *C,

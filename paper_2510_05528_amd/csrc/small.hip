@@ -29,10 +29,67 @@ __device__ __forceinline__ double block_sum_256(double v, double *red) {
 // ------------------------------------------------------------------------------------------------
 // normalisation (Sec. 3.2)
 // ------------------------------------------------------------------------------------------------
+// A run of VEC consecutive entries of W as floats: 16 bytes per load (8 bf16 or 4 fp32).
+template <bool BF16> struct WVec {
+    static constexpr int VEC = BF16 ? 8 : 4;
+    float v[VEC];
+    __device__ __forceinline__ void load(const void *W, int64_t idx) { // idx: element index, multiple of VEC
+        if (BF16) {
+            const uint4 q = *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint16_t *>(W) + idx);
+            const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                v[2 * e] = __uint_as_float(w[e] << 16);
+                v[2 * e + 1] = __uint_as_float(w[e] & 0xffff0000u);
+            }
+        } else {
+            const float4 q = *reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(W) + idx);
+            v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+        }
+    }
+};
+
+// Column sums of squares over one chunk of rows.  Workgroup = 64 column threads (VEC columns each) x 4 row
+// lanes; the four row lanes are added in a fixed order through LDS.  Requires d_in % VEC == 0.
 template <bool BF16>
 __global__ __launch_bounds__(256) void colnorm_partial_kernel(const void *__restrict__ W, int64_t d_out,
                                                               int64_t d_in, int nchunk,
                                                               float *__restrict__ partial) {
+    constexpr int VEC = WVec<BF16>::VEC;
+    __shared__ float red[3][64][VEC + 1];
+    const int cx = threadIdx.x & 63, ry = threadIdx.x >> 6;
+    const int64_t j = ((int64_t)blockIdx.x * 64 + cx) * VEC;
+    const int c = blockIdx.y;
+    const int64_t rows = (d_out + nchunk - 1) / nchunk, r0 = c * rows, r1 = min(d_out, r0 + rows);
+    float s[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) s[e] = 0.f;
+    if (j < d_in) {
+#pragma unroll 4
+        for (int64_t i = r0 + ry; i < r1; i += 4) {
+            WVec<BF16> w;
+            w.load(W, i * d_in + j);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) s[e] += w.v[e] * w.v[e];
+        }
+    }
+    if (ry > 0) {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) red[ry - 1][cx][e] = s[e];
+    }
+    __syncthreads();
+    if (ry == 0 && j < d_in) {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e)
+            partial[(int64_t)c * d_in + j + e] = (s[e] + red[0][cx][e]) + (red[1][cx][e] + red[2][cx][e]);
+    }
+}
+
+// scalar form for widths that are not a multiple of the vector length
+template <bool BF16>
+__global__ __launch_bounds__(256) void colnorm_partial_scalar_kernel(const void *__restrict__ W, int64_t d_out,
+                                                                     int64_t d_in, int nchunk,
+                                                                     float *__restrict__ partial) {
     int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
     int c = blockIdx.y;
     int64_t rows = (d_out + nchunk - 1) / nchunk, r0 = c * rows, r1 = min(d_out, r0 + rows);
@@ -45,48 +102,129 @@ __global__ __launch_bounds__(256) void colnorm_partial_kernel(const void *__rest
     partial[(int64_t)c * d_in + j] = s;
 }
 
-__global__ __launch_bounds__(256) void colnorm_final_kernel(const float *__restrict__ partial, int64_t d_in,
-                                                            int nchunk, float *__restrict__ r1) {
-    int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
+// r1 (zero norms replaced by 1) and its reciprocal
+__global__ __launch_bounds__(64) void colnorm_final_kernel(const float *__restrict__ partial, int64_t d_in,
+                                                            int nchunk, float *__restrict__ r1,
+                                                            float *__restrict__ r1_inv) {
+    int64_t j = (int64_t)blockIdx.x * 64 + threadIdx.x;
     if (j >= d_in) return;
     double s = 0.0;
-    for (int c = 0; c < nchunk; ++c) s += (double)partial[(int64_t)c * d_in + j];
+    for (int c0 = 0; c0 < nchunk; c0 += 8) { // eight loads in flight, added in chunk order
+        float p[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) p[u] = c0 + u < nchunk ? partial[(int64_t)(c0 + u) * d_in + j] : 0.f;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += (double)p[u];
+    }
     float r = (float)sqrt(s);
-    r1[j] = r > 0.f ? r : 1.f;
+    r = r > 0.f ? r : 1.f;
+    r1[j] = r;
+    r1_inv[j] = 1.f / r;
 }
 
-template <bool BF16>
+// One workgroup per row: W1 = W / r1, r2 = its row norm, Wbar = W1 / r2.  The first KEEP vectors of
+// a thread stay in registers between the two passes; longer rows are read again (L2).
+template <bool BF16, bool VECTOR>
 __global__ __launch_bounds__(256) void rownorm_scale_kernel(const void *__restrict__ W, int64_t d_in,
-                                                            const float *__restrict__ r1, float *__restrict__ r2,
+                                                            const float *__restrict__ r1_inv, float *__restrict__ r2,
                                                             float *__restrict__ Wbar) {
     __shared__ double red[4];
     const int64_t i = blockIdx.x;
-    double s = 0.0;
-    for (int64_t j = threadIdx.x; j < d_in; j += 256) {
-        float w1 = load_w<BF16>(W, i * d_in + j) / r1[j];
-        s += (double)w1 * (double)w1;
+    const int tid = threadIdx.x;
+    if (VECTOR) {
+        constexpr int VEC = WVec<BF16>::VEC, KEEP = 4;
+        const int64_t nvec = d_in / VEC;
+        WVec<BF16> keep[KEEP];
+        double s = 0.0;
+#pragma unroll
+        for (int u = 0; u < KEEP; ++u) {
+            const int64_t v = tid + (int64_t)u * 256;
+            if (v < nvec) {
+                keep[u].load(W, i * d_in + v * VEC);
+                float part = 0.f;
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) {
+                    keep[u].v[e] *= r1_inv[v * VEC + e];
+                    part += keep[u].v[e] * keep[u].v[e];
+                }
+                s += (double)part;
+            }
+        }
+        for (int64_t v = tid + (int64_t)KEEP * 256; v < nvec; v += 256) {
+            WVec<BF16> w;
+            w.load(W, i * d_in + v * VEC);
+            float part = 0.f;
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) {
+                const float w1 = w.v[e] * r1_inv[v * VEC + e];
+                part += w1 * w1;
+            }
+            s += (double)part;
+        }
+        s = block_sum_256(s, red);
+        float r = (float)sqrt(s);
+        r = r > 0.f ? r : 1.f;
+        if (tid == 0) r2[i] = r;
+        const float rinv = 1.f / r;
+        auto store = [&](int64_t v, const float *w1) {
+            float4 *dst = reinterpret_cast<float4 *>(Wbar + i * d_in + v * VEC);
+#pragma unroll
+            for (int q = 0; q < VEC / 4; ++q)
+                dst[q] = make_float4(w1[4 * q] * rinv, w1[4 * q + 1] * rinv, w1[4 * q + 2] * rinv, w1[4 * q + 3] * rinv);
+        };
+#pragma unroll
+        for (int u = 0; u < KEEP; ++u) {
+            const int64_t v = tid + (int64_t)u * 256;
+            if (v < nvec) store(v, keep[u].v);
+        }
+        for (int64_t v = tid + (int64_t)KEEP * 256; v < nvec; v += 256) {
+            WVec<BF16> w;
+            w.load(W, i * d_in + v * VEC);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) w.v[e] *= r1_inv[v * VEC + e];
+            store(v, w.v);
+        }
+    } else {
+        double s = 0.0;
+        for (int64_t j = tid; j < d_in; j += 256) {
+            float w1 = load_w<BF16>(W, i * d_in + j) * r1_inv[j];
+            s += (double)w1 * (double)w1;
+        }
+        s = block_sum_256(s, red);
+        float r = (float)sqrt(s);
+        r = r > 0.f ? r : 1.f;
+        if (tid == 0) r2[i] = r;
+        const float rinv = 1.f / r;
+        for (int64_t j = tid; j < d_in; j += 256) Wbar[i * d_in + j] = (load_w<BF16>(W, i * d_in + j) * r1_inv[j]) * rinv;
     }
-    s = block_sum_256(s, red);
-    float r = (float)sqrt(s);
-    r = r > 0.f ? r : 1.f;
-    if (threadIdx.x == 0) r2[i] = r;
-    for (int64_t j = threadIdx.x; j < d_in; j += 256)
-        Wbar[i * d_in + j] = (load_w<BF16>(W, i * d_in + j) / r1[j]) / r;
 }
 
+// partial: [nchunk][d_in] floats followed by d_in floats for the reciprocal column norms
 void launch_colnorm(const void *W, int bf16, int64_t d_out, int64_t d_in, float *partial, int nchunk, float *r1,
                     hipStream_t s) {
-    dim3 grid((unsigned)((d_in + 255) / 256), nchunk);
-    if (bf16) hipLaunchKernelGGL(colnorm_partial_kernel<true>, grid, dim3(256), 0, s, W, d_out, d_in, nchunk, partial);
-    else      hipLaunchKernelGGL(colnorm_partial_kernel<false>, grid, dim3(256), 0, s, W, d_out, d_in, nchunk, partial);
-    hipLaunchKernelGGL(colnorm_final_kernel, dim3((unsigned)((d_in + 255) / 256)), dim3(256), 0, s, partial, d_in,
-                       nchunk, r1);
+    float *r1_inv = partial + (int64_t)nchunk * d_in;
+    const int vec = bf16 ? 8 : 4;
+    if (d_in % vec == 0) {
+        dim3 grid((unsigned)((d_in / vec + 63) / 64), nchunk);
+        if (bf16) hipLaunchKernelGGL(colnorm_partial_kernel<true>, grid, dim3(256), 0, s, W, d_out, d_in, nchunk, partial);
+        else      hipLaunchKernelGGL(colnorm_partial_kernel<false>, grid, dim3(256), 0, s, W, d_out, d_in, nchunk, partial);
+    } else {
+        dim3 grid((unsigned)((d_in + 255) / 256), nchunk);
+        if (bf16) hipLaunchKernelGGL(colnorm_partial_scalar_kernel<true>, grid, dim3(256), 0, s, W, d_out, d_in, nchunk, partial);
+        else      hipLaunchKernelGGL(colnorm_partial_scalar_kernel<false>, grid, dim3(256), 0, s, W, d_out, d_in, nchunk, partial);
+    }
+    hipLaunchKernelGGL(colnorm_final_kernel, dim3((unsigned)((d_in + 63) / 64)), dim3(64), 0, s, partial, d_in,
+                       nchunk, r1, r1_inv);
 }
 
-void launch_rownorm_scale(const void *W, int bf16, int64_t d_out, int64_t d_in, const float *r1, float *r2,
+void launch_rownorm_scale(const void *W, int bf16, int64_t d_out, int64_t d_in, const float *r1_inv, float *r2,
                           float *Wbar, hipStream_t s) {
-    if (bf16) hipLaunchKernelGGL(rownorm_scale_kernel<true>, dim3((unsigned)d_out), dim3(256), 0, s, W, d_in, r1, r2, Wbar);
-    else      hipLaunchKernelGGL(rownorm_scale_kernel<false>, dim3((unsigned)d_out), dim3(256), 0, s, W, d_in, r1, r2, Wbar);
+    const bool vec = d_in % (bf16 ? 8 : 4) == 0;
+    dim3 grid((unsigned)d_out), block(256);
+    if (bf16 && vec)       hipLaunchKernelGGL((rownorm_scale_kernel<true, true>), grid, block, 0, s, W, d_in, r1_inv, r2, Wbar);
+    else if (bf16)         hipLaunchKernelGGL((rownorm_scale_kernel<true, false>), grid, block, 0, s, W, d_in, r1_inv, r2, Wbar);
+    else if (vec)          hipLaunchKernelGGL((rownorm_scale_kernel<false, true>), grid, block, 0, s, W, d_in, r1_inv, r2, Wbar);
+    else                   hipLaunchKernelGGL((rownorm_scale_kernel<false, false>), grid, block, 0, s, W, d_in, r1_inv, r2, Wbar);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -771,38 +909,99 @@ __device__ __forceinline__ uint16_t float_to_bf16_rne(float f) {
     return (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
 }
 
-// one thread per group: the N kept values in increasing column order + their in-group columns
-template <int M, bool BF16>
+// Compressed N:M storage.  A thread packs G consecutive groups of one row, G chosen so that its index
+// fields fill whole bytes: the kept values in increasing column order, and per kept entry its column
+// inside the group in a field of W_BITS bits (1, 2 or 4 for M = 2, 4, 8), fields filling each byte
+// from bit 0 upwards; a row of meta starts on a byte boundary.
+template <int N, int M> struct PackGeom {
+    static constexpr int W_BITS = M == 2 ? 1 : (M == 4 ? 2 : 4);
+    static constexpr int NW = N * W_BITS; // index bits per group
+    static constexpr int G = (NW % 8 == 0) ? 1 : (NW % 4 == 0) ? 2 : (NW % 2 == 0) ? 4 : 8;
+    static constexpr int BYTES = G * NW / 8; // meta bytes per thread
+};
+
+template <int N, int M, bool BF16>
 __global__ __launch_bounds__(256) void pack_nm_kernel(const float *__restrict__ S, const uint8_t *__restrict__ mask,
-                                                      int64_t ngroups, int N, void *__restrict__ values,
+                                                      int64_t d_out, int64_t d_in, void *__restrict__ values,
                                                       uint8_t *__restrict__ meta) {
-    int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (g >= ngroups) return;
-    uint32_t bits = mask[g];
-    int x = 0;
+    using PG = PackGeom<N, M>;
+    constexpr int G = PG::G;
+    const int64_t gpr = d_in / M, tpr = (gpr + G - 1) / G; // groups, threads per row
+    const int64_t meta_row = (gpr * PG::NW + 7) / 8;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= d_out * tpr) return;
+    const int64_t i = idx / tpr, g0 = (idx % tpr) * G;
+    const int ng = (int)min((int64_t)G, gpr - g0);
+    float v[G][M];
+    uint32_t bits[G];
 #pragma unroll
-    for (int p = 0; p < M; ++p) {
-        if (((bits >> p) & 1u) && x < N) {
-            float v = S[g * M + p];
-            if (BF16) reinterpret_cast<uint16_t *>(values)[g * N + x] = float_to_bf16_rne(v);
-            else      reinterpret_cast<float *>(values)[g * N + x] = v;
-            meta[g * N + x] = (uint8_t)p;
-            ++x;
+    for (int g = 0; g < G; ++g) {
+        bits[g] = 0;
+        if (g < ng) {
+            bits[g] = mask[i * gpr + g0 + g];
+            const float *src = S + i * d_in + (g0 + g) * M;
+            if (M == 2) {
+                const float2 q = *reinterpret_cast<const float2 *>(src);
+                v[g][0] = q.x; v[g][1] = q.y;
+            } else {
+#pragma unroll
+                for (int q4 = 0; q4 < M / 4; ++q4) {
+                    const float4 q = reinterpret_cast<const float4 *>(src)[q4];
+                    v[g][4 * q4] = q.x; v[g][4 * q4 + 1] = q.y; v[g][4 * q4 + 2] = q.z; v[g][4 * q4 + 3] = q.w;
+                }
+            }
         }
     }
+    float kept[G][N];
+    uint64_t field = 0; // G * NW <= 56 bits
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        int x = 0;
+#pragma unroll
+        for (int e = 0; e < N; ++e) kept[g][e] = 0.f;
+#pragma unroll
+        for (int p = 0; p < M; ++p) {
+            const bool on = ((bits[g] >> p) & 1u) && x < N;
+#pragma unroll
+            for (int e = 0; e < N; ++e)
+                if (on && x == e) kept[g][e] = v[g][p];
+            if (on) {
+                field |= (uint64_t)p << (g * PG::NW + x * PG::W_BITS);
+                ++x;
+            }
+        }
+    }
+    const int64_t vbase = (i * gpr + g0) * N;
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+        if (g < ng) {
+#pragma unroll
+            for (int e = 0; e < N; ++e) {
+                if (BF16) reinterpret_cast<uint16_t *>(values)[vbase + g * N + e] = float_to_bf16_rne(kept[g][e]);
+                else      reinterpret_cast<float *>(values)[vbase + g * N + e] = kept[g][e];
+            }
+        }
+    uint8_t *mrow = meta + i * meta_row + (g0 / G) * PG::BYTES;
+    const int nbytes = (ng * PG::NW + 7) / 8;
+#pragma unroll
+    for (int q = 0; q < PG::BYTES; ++q)
+        if (q < nbytes) mrow[q] = (uint8_t)(field >> (8 * q));
 }
 
 void launch_pack_nm(const float *S, const uint8_t *mask, int64_t d_out, int64_t d_in, int N, int M, void *values,
                     int bf16, uint8_t *meta, hipStream_t s) {
-    int64_t ngroups = d_out * (d_in / M);
-    dim3 grid((unsigned)((ngroups + 255) / 256));
-#define ARMOR_PACK_CASE(m)                                                                                         \
-    if (M == m) {                                                                                                  \
-        if (bf16) hipLaunchKernelGGL((pack_nm_kernel<m, true>), grid, dim3(256), 0, s, S, mask, ngroups, N, values, meta);  \
-        else      hipLaunchKernelGGL((pack_nm_kernel<m, false>), grid, dim3(256), 0, s, S, mask, ngroups, N, values, meta); \
+#define ARMOR_PACK_CASE(n, m)                                                                                      \
+    if (N == n && M == m) {                                                                                        \
+        const int64_t gpr = d_in / m, tpr = (gpr + PackGeom<n, m>::G - 1) / PackGeom<n, m>::G;                     \
+        dim3 grid((unsigned)((d_out * tpr + 255) / 256));                                                          \
+        if (bf16) hipLaunchKernelGGL((pack_nm_kernel<n, m, true>), grid, dim3(256), 0, s, S, mask, d_out, d_in, values, meta);  \
+        else      hipLaunchKernelGGL((pack_nm_kernel<n, m, false>), grid, dim3(256), 0, s, S, mask, d_out, d_in, values, meta); \
         return;                                                                                                    \
     }
-    ARMOR_PACK_CASE(2) ARMOR_PACK_CASE(4) ARMOR_PACK_CASE(8)
+    ARMOR_PACK_CASE(1, 2)
+    ARMOR_PACK_CASE(1, 4) ARMOR_PACK_CASE(2, 4) ARMOR_PACK_CASE(3, 4)
+    ARMOR_PACK_CASE(1, 8) ARMOR_PACK_CASE(2, 8) ARMOR_PACK_CASE(3, 8) ARMOR_PACK_CASE(4, 8)
+    ARMOR_PACK_CASE(5, 8) ARMOR_PACK_CASE(6, 8) ARMOR_PACK_CASE(7, 8)
 #undef ARMOR_PACK_CASE
 }
 

@@ -312,6 +312,29 @@ def test_denormalize_and_pack(armor, torch, orc):
     mask = armor.unpack_mask(plain["mask_bits"].cpu().numpy(), 4)
     ev, ei = orc.pack_nm(plain["S"].cpu().numpy(), mask, 2, 4)
     np.testing.assert_array_equal(vals.cpu().numpy(), ev)
-    np.testing.assert_array_equal(meta.cpu().numpy(), ei)
+    np.testing.assert_array_equal(meta.cpu().numpy(), orc.pack_index_bits(ei, 4))
     vb, _ = armor.pack_nm(plain["S"], plain["mask_bits"], 2, 4, bf16=True)
     np.testing.assert_array_equal(vb.view(torch.int16).cpu().numpy().view(np.uint16), synth.to_bf16_bits(ev))
+
+
+@pytest.mark.parametrize("N,M,d_in", [(1, 2, 70), (2, 4, 136), (3, 4, 100), (1, 4, 36), (4, 8, 200), (5, 8, 72), (7, 8, 40),
+                                      (2, 8, 24), (6, 8, 1024)])
+def test_pack_nm_formats(armor, torch, orc, N, M, d_in):
+    """Every N:M the library packs, with ragged rows (groups per row not a multiple of the groups a
+    thread packs, index bits of a row not a whole number of bytes): values and bit-packed indices
+    are bit-exact against the oracle's."""
+    rng = np.random.default_rng(100 * N + M)
+    d_out = 37
+    S = rng.standard_normal((d_out, d_in)).astype(np.float32)
+    scores = rng.random((d_out, d_in // M, M))
+    keep = np.argsort(-scores, axis=-1)[..., :N]
+    mask = np.zeros((d_out, d_in // M, M), dtype=np.uint8)
+    np.put_along_axis(mask, keep, 1, axis=-1)
+    S = S * mask.reshape(d_out, d_in)
+    bits = (mask.astype(np.uint32) << np.arange(M, dtype=np.uint32)).sum(-1).astype(np.uint8)
+    say("pack", N, M, d_in)
+    vals, meta = armor.pack_nm(dev(torch, S), dev(torch, bits), N, M)
+    ev, ei = orc.pack_nm(S, mask.reshape(d_out, d_in), N, M)
+    np.testing.assert_array_equal(vals.cpu().numpy(), ev)
+    np.testing.assert_array_equal(meta.cpu().numpy(), orc.pack_index_bits(ei, M))
+    np.testing.assert_array_equal(armor.unpack_meta(meta.cpu().numpy(), d_in, N, M), ei)

@@ -541,6 +541,20 @@ def test_pack_nm_roundtrip(orc):
     assert np.all(np.diff(idx.reshape(8, 4, 2).astype(int), axis=-1) > 0)
 
 
+@pytest.mark.parametrize("M,entries", [(2, 13), (4, 16), (4, 6), (8, 5)])
+def test_pack_index_bits_is_a_little_endian_bit_stream(orc, M, entries):
+    """The compact index form read back as one integer per row: field e sits at bit e*w."""
+    rng = np.random.default_rng(54)
+    w = {2: 1, 4: 2, 8: 4}[M]
+    idx = rng.integers(0, M, (3, entries)).astype(np.uint8)
+    packed = orc.pack_index_bits(idx, M)
+    assert packed.shape == (3, (entries * w + 7) // 8)
+    for i in range(3):
+        as_int = int.from_bytes(packed[i].tobytes(), "little")
+        assert [(as_int >> (e * w)) & ((1 << w) - 1) for e in range(entries)] == idx[i].tolist()
+        assert as_int >> (entries * w) == 0
+
+
 # ---------------------------------------------------------------------------------------------
 # Gram (Sec. 2 / Eq. 2)
 # ---------------------------------------------------------------------------------------------
