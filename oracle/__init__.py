@@ -290,3 +290,17 @@ def pack_index_bits(index, M):
     lib().oracle_pack_index_bits(_p(index, _u8p), _i64(d_out), _i64(entries), ctypes.c_int(w), _p(packed, _u8p),
                                  _i64(row_bytes))
     return packed
+
+
+def apply_packed(X, A, values, index, B, N, M, round_bf16=True):
+    """y = A (S (B x)) for every row x of X, from the compressed core (Sec. 3.1 / Sec. 4.4). fp64 out."""
+    X, A, B, values = _f32(X), _f32(A), _f32(B), _f32(values)
+    index = np.ascontiguousarray(index, dtype=np.uint8)
+    n, d_in = X.shape
+    b = A.shape[-1]
+    d_out = A.shape[0] * b
+    Y = np.zeros((n, d_out), dtype=np.float64)
+    lib().oracle_apply_packed(_p(X, _f32p), _i64(n), _p(A, _f32p), _p(values, _f32p), _p(index, _u8p), _p(B, _f32p),
+                              _i64(d_out), _i64(d_in), _i64(b), ctypes.c_int(N), ctypes.c_int(M),
+                              ctypes.c_int(1 if round_bf16 else 0), Y.ctypes.data_as(ctypes.POINTER(ctypes.c_double)))
+    return Y

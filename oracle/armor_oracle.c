@@ -16,6 +16,7 @@
  *   - outer loop .................................... Alg. 1
  *   - N:M generalisation, unstructured mode ......... Sec. 4.5
  *   - denormalisation ............................... Sec. 3.2, last paragraph
+ *   - the factorized layer applied to activations ... Sec. 3.1 (y = A (S (B x))), Sec. 4.4
  *
  * Conventions: all matrices row-major; W[i*d_in + j] couples output i with input j; the sparse
  * axis is d_in (groups of M consecutive columns in a row).  A is stored [d_out/b][b][b], B is
@@ -802,4 +803,60 @@ void oracle_pack_index_bits(const uint8_t *index, int64_t d_out, int64_t entries
                 if ((index[i * entries + e] >> t) & 1) packed[i * row_bytes + pos / 8] |= (uint8_t)(1u << (pos % 8));
             }
     }
+}
+
+/* ------------------------------------------------------------------------------------------
+ * The factorized layer applied to a batch of activations (Sec. 3.1: the wrappers are applied as
+ * batched block products around the N:M core; Sec. 4.4 times exactly this on a batch of tokens):
+ *     u = B x   (block j of u from block j of x),   v = S u,   y = A v   (block i of y from block i of v)
+ * X is [n][d_in] (one token per row), Y is [n][d_out].  S comes in its compressed form: per row
+ * and group the N kept values in increasing column order and their in-group columns (one byte
+ * each, as oracle_pack_nm writes them).  All sums in fp64.  With round_bf16 != 0 the two
+ * intermediates u and v are rounded to bfloat16 (round to nearest even) before the next product,
+ * which is what a bf16 pipeline with fp32 accumulators does; with 0 nothing is rounded and the
+ * result is the exact product X (A S B)^T.
+ * ------------------------------------------------------------------------------------------ */
+static double round_to_bf16(double x) {
+    float f = (float)x;
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return x; /* NaN */
+    uint32_t lsb = (u >> 16) & 1u;
+    u += 0x7fffu + lsb;
+    u &= 0xffff0000u;
+    memcpy(&f, &u, 4);
+    return (double)f;
+}
+
+void oracle_apply_packed(const float *X, int64_t n, const float *A, const float *values, const uint8_t *index,
+                         const float *B, int64_t d_out, int64_t d_in, int64_t b, int N, int M, int round_bf16,
+                         double *Y) {
+    int64_t gpr = d_in / M;
+    double *u = dalloc(d_in), *v = dalloc(d_out);
+    for (int64_t t = 0; t < n; ++t) {
+        const float *x = X + t * d_in;
+        for (int64_t j = 0; j < d_in / b; ++j)
+            for (int64_t p = 0; p < b; ++p) {
+                double acc = 0.0;
+                for (int64_t q = 0; q < b; ++q) acc += (double)B[(j * b + p) * b + q] * (double)x[j * b + q];
+                u[j * b + p] = round_bf16 ? round_to_bf16(acc) : acc;
+            }
+        for (int64_t o = 0; o < d_out; ++o) {
+            double acc = 0.0;
+            for (int64_t g = 0; g < gpr; ++g)
+                for (int e = 0; e < N; ++e) {
+                    int64_t at = (o * gpr + g) * N + e;
+                    acc += (double)values[at] * u[g * M + index[at]];
+                }
+            v[o] = round_bf16 ? round_to_bf16(acc) : acc;
+        }
+        for (int64_t i = 0; i < d_out / b; ++i)
+            for (int64_t p = 0; p < b; ++p) {
+                double acc = 0.0;
+                for (int64_t q = 0; q < b; ++q) acc += (double)A[(i * b + p) * b + q] * v[i * b + q];
+                Y[t * d_out + i * b + p] = acc;
+            }
+    }
+    free(u);
+    free(v);
 }

@@ -556,6 +556,46 @@ def test_pack_index_bits_is_a_little_endian_bit_stream(orc, M, entries):
 
 
 # ---------------------------------------------------------------------------------------------
+# the factorized layer applied to activations (Sec. 3.1, Sec. 4.4)
+# ---------------------------------------------------------------------------------------------
+def bf16_round(a):
+    return synth.bf16_bits_to_f32(synth.to_bf16_bits(np.asarray(a, dtype=np.float32))).astype(np.float64)
+
+
+@pytest.mark.parametrize("d_out,d_in,b,N,M", [(12, 16, 4, 2, 4), (16, 24, 8, 3, 8), (8, 8, 4, 1, 2), (8, 16, 8, 5, 8)])
+def test_apply_packed_is_the_dense_product(orc, d_out, d_in, b, N, M):
+    """Without rounding, y = A(S(Bx)) from the compressed core is X (A S B)^T with dense matrices:
+    catches a transposed wrapper, a wrong block, a wrong in-group column."""
+    rng = np.random.default_rng(61)
+    _, _, A, B, C, mask = rand_state(rng, d_out, d_in, b, N=N, M=M, perturb=0.5)
+    X = rng.standard_normal((5, d_in)).astype(np.float32)
+    vals, idx = orc.pack_nm(C, mask, N, M)
+    Y = orc.apply_packed(X, A, vals, idx, B, N, M, round_bf16=False)
+    What = dense(A) @ C.astype(np.float64) @ dense(B)
+    np.testing.assert_allclose(Y, X.astype(np.float64) @ What.T, rtol=1e-12, atol=1e-13)
+    # identity wrappers: the plain N:M sparse product
+    I_A, I_B = orc.identity_blocks(d_out // b, b), orc.identity_blocks(d_in // b, b)
+    Y0 = orc.apply_packed(X, I_A, vals, idx, I_B, N, M, round_bf16=False)
+    np.testing.assert_allclose(Y0, X.astype(np.float64) @ C.astype(np.float64).T, rtol=1e-12, atol=1e-13)
+
+
+def test_apply_packed_rounds_the_two_intermediates_to_bf16(orc):
+    """With rounding on, u = Bx and v = Su pass through bfloat16 (round to nearest even, checked
+    against the input generator's own conversion); y itself is not rounded."""
+    rng = np.random.default_rng(62)
+    d_out, d_in, b = 16, 24, 8
+    _, _, A, B, C, mask = rand_state(rng, d_out, d_in, b, perturb=0.5)
+    X = bf16_round(rng.standard_normal((7, d_in))).astype(np.float32)
+    vals, idx = orc.pack_nm(C, mask, 2, 4)
+    Y = orc.apply_packed(X, A, vals, idx, B, 2, 4, round_bf16=True)
+    u = bf16_round(X.astype(np.float64) @ dense(B).T)
+    v = bf16_round(u @ C.astype(np.float64).T)
+    np.testing.assert_allclose(Y, v @ dense(A).T, rtol=1e-9, atol=1e-12)
+    exact = orc.apply_packed(X, A, vals, idx, B, 2, 4, round_bf16=False)
+    assert 0 < np.abs(Y - exact).max() < 2.0 ** -6 * np.abs(exact).max()
+
+
+# ---------------------------------------------------------------------------------------------
 # Gram (Sec. 2 / Eq. 2)
 # ---------------------------------------------------------------------------------------------
 def test_gram_is_textbook_syrk(orc):
