@@ -84,7 +84,9 @@ int armor_last_hip_error(void);
 #define ARMOR_PROF_INIT 8      /* initial mask and core (Eq. 3), N:M or unstructured */
 #define ARMOR_PROF_PACK 9      /* armor_pack_nm */
 #define ARMOR_PROF_SMALL 10    /* wrapper updates, wrapper Grams, step-size scalars */
-#define ARMOR_PROF_KINDS 11
+#define ARMOR_PROF_APPLY_PRE 11  /* armor_apply_packed: U = X B^T */
+#define ARMOR_PROF_APPLY_MAIN 12 /* armor_apply_packed: Y = (U S^T) A^T */
+#define ARMOR_PROF_KINDS 13
 armor_status armor_profile_enable(int on);
 armor_status armor_profile_read(double *ms_total /*host [ARMOR_PROF_KINDS]*/, int64_t *launches /*host*/);
 
@@ -168,6 +170,29 @@ armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const flo
 int64_t armor_pack_meta_row_bytes(int64_t d_in, int N, int M);
 armor_status armor_pack_nm(const float *S, const uint8_t *mask_bits, int64_t d_out, int64_t d_in, int N, int M,
                            void *values, armor_dtype v_dtype, uint8_t *meta, void *hip_stream);
+
+/*
+ * The factorized layer applied to a batch of activations (Sec. 3.1: the wrappers are block
+ * products around the N:M core; Sec. 4.4 times this product on a batch of tokens):
+ *     Y[t] = A (S (B X[t]))      t = 0 .. n_tokens-1
+ *   X        [n_tokens][d_in]  bf16, row-major (one token per row)
+ *   A_bf16   [d_out/d_block][d_block][d_block] bf16, B_bf16 [d_in/d_block][d_block][d_block] bf16:
+ *            the wrappers of armor_factorize_layer (with opts->denormalize = 1 when the layer is
+ *            to reproduce W rather than W-bar) converted by armor_to_bf16
+ *   values   [d_out][d_in/2] bf16 and meta [d_out][d_in/8] bytes: armor_pack_nm with ARMOR_BF16
+ *   Y        [n_tokens][d_out] bf16, row-major
+ *   ws       armor_apply_workspace_bytes(n_tokens, d_in) bytes (holds B X in bf16)
+ * Arithmetic: bf16 operands, fp32 accumulation; the two intermediates B x and S (B x) are rounded
+ * to bf16 (round to nearest even) before the next product, Y is rounded once at the end.
+ * Supported: N:M = 2:4 (the pattern the structured-sparse matrix instruction takes), d_block in
+ * {32, 64, 128}, d_in a multiple of 64; anything else returns ARMOR_ERR_UNSUPPORTED.  All pointers
+ * are device pointers, 16-byte aligned; asynchronous on the stream; n_tokens = 0 is a no-op.
+ */
+armor_status armor_to_bf16(const float *in, int64_t n, void *out_bf16, void *hip_stream);
+size_t armor_apply_workspace_bytes(int64_t n_tokens, int64_t d_in);
+armor_status armor_apply_packed(const void *X, int64_t n_tokens, const void *A_bf16, const void *values,
+                                const uint8_t *meta, const void *B_bf16, int64_t d_out, int64_t d_in,
+                                int64_t d_block, int N, int M, void *Y, void *ws, size_t ws_bytes, void *hip_stream);
 
 #ifdef __cplusplus
 }

@@ -10,13 +10,13 @@ _LIB_PATH = os.path.join(_HERE, "libarmor.so")
 ARMOR_F32, ARMOR_BF16 = 0, 1
 
 PROF_KINDS = ["gram", "phase_A", "phase_B", "phase_WS", "sparse_step", "phase_FB", "phase_GS", "normalize", "init",
-              "pack_nm", "small_kernels"]
+              "pack_nm", "small_kernels", "apply_pre", "apply_main"]
 
 EXPORTED = ["armor_status_string", "armor_last_hip_error", "armor_profile_enable", "armor_profile_read",
             "armor_gram_workspace_bytes", "armor_gram", "armor_gram_diag",
             "armor_normalize_workspace_bytes", "armor_normalize", "armor_proxy_loss_workspace_bytes",
             "armor_proxy_loss", "armor_factorize_workspace_bytes", "armor_factorize_layer", "armor_pack_nm",
-            "armor_pack_meta_row_bytes"]
+            "armor_pack_meta_row_bytes", "armor_to_bf16", "armor_apply_workspace_bytes", "armor_apply_packed"]
 
 
 class ArmorError(RuntimeError):
@@ -65,6 +65,10 @@ def load_library():
     lib.armor_pack_meta_row_bytes.argtypes = [_i64, _int, _int]
     lib.armor_pack_meta_row_bytes.restype = _i64
     lib.armor_pack_nm.argtypes = [_vp, _vp, _i64, _i64, _int, _int, _vp, _int, _vp, _vp]
+    lib.armor_to_bf16.argtypes = [_vp, _i64, _vp, _vp]
+    lib.armor_apply_workspace_bytes.restype = _sz
+    lib.armor_apply_workspace_bytes.argtypes = [_i64, _i64]
+    lib.armor_apply_packed.argtypes = [_vp, _i64, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _int, _vp, _vp, _sz, _vp]
     _lib = lib
     return lib
 
@@ -252,6 +256,41 @@ def pack_nm(S, mask_bits, N, M, bf16=False):
     _check(lib.armor_pack_nm(_ptr(S), _ptr(mask_bits), d_out, d_in, N, M, _ptr(values), ARMOR_BF16 if bf16 else ARMOR_F32,
                              _ptr(meta), _stream()))
     return values, meta
+
+
+def to_bf16(t):
+    """fp32 device tensor -> bf16 device tensor of the same shape (armor_to_bf16)."""
+    torch = _torch()
+    lib = load_library()
+    _dev_f32(t, "t")
+    out = torch.empty(t.shape, device=t.device, dtype=torch.bfloat16)
+    _check(lib.armor_to_bf16(_ptr(t), t.numel(), _ptr(out), _stream()))
+    return out
+
+
+def apply_workspace_bytes(n_tokens, d_in):
+    return int(load_library().armor_apply_workspace_bytes(n_tokens, d_in))
+
+
+def apply_packed(X, A_bf16, values, meta, B_bf16, N, M, Y=None, ws=None):
+    """Y[t] = A (S (B X[t])) from the compressed core (armor_apply_packed). X [n, d_in] bf16 -> Y [n, d_out] bf16."""
+    torch = _torch()
+    lib = load_library()
+    for name, t in (("X", X), ("A_bf16", A_bf16), ("values", values), ("B_bf16", B_bf16)):
+        if not (t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous()):
+            raise ArmorError("%s must be a contiguous bf16 device tensor" % name)
+    if not (meta.is_cuda and meta.dtype == torch.uint8 and meta.is_contiguous()):
+        raise ArmorError("meta must be a contiguous uint8 device tensor")
+    n, d_in = X.shape
+    b = A_bf16.shape[-1]
+    d_out = A_bf16.shape[0] * b
+    if Y is None:
+        Y = torch.empty((n, d_out), device=X.device, dtype=torch.bfloat16)
+    if ws is None:
+        ws = torch.empty(apply_workspace_bytes(n, d_in), device=X.device, dtype=torch.uint8)
+    _check(lib.armor_apply_packed(_ptr(X), n, _ptr(A_bf16), _ptr(values), _ptr(meta), _ptr(B_bf16), d_out, d_in, b, N, M,
+                                  _ptr(Y), _ptr(ws), ws.numel(), _stream()))
+    return Y
 
 
 def unpack_meta(meta, d_in, N, M):

@@ -516,4 +516,45 @@ armor_status armor_pack_nm(const float *S, const uint8_t *mask_bits, int64_t d_o
     return check_hip();
 }
 
+armor_status armor_to_bf16(const float *in, int64_t n, void *out_bf16, void *hip_stream) {
+    if (!in || !out_bf16) return ARMOR_ERR_NULL;
+    if (n < 0) return ARMOR_ERR_SHAPE;
+    if (n > 0) launch_to_bf16(in, n, out_bf16, (hipStream_t)hip_stream);
+    return check_hip();
+}
+
+size_t armor_apply_workspace_bytes(int64_t n_tokens, int64_t d_in) {
+    if (n_tokens < 0 || d_in <= 0) return 0;
+    return (size_t)n_tokens * (size_t)d_in * 2 + 256;
+}
+
+armor_status armor_apply_packed(const void *X, int64_t n_tokens, const void *A_bf16, const void *values,
+                                const uint8_t *meta, const void *B_bf16, int64_t d_out, int64_t d_in,
+                                int64_t d_block, int N, int M, void *Y, void *ws, size_t ws_bytes, void *hip_stream) {
+    if (!A_bf16 || !values || !meta || !B_bf16) return ARMOR_ERR_NULL;
+    if ((!X || !Y) && n_tokens != 0) return ARMOR_ERR_NULL; // an empty batch may come with null X, Y
+    if (n_tokens < 0 || d_out <= 0 || d_in <= 0 || d_block <= 0) return ARMOR_ERR_SHAPE;
+    if (d_out % d_block != 0 || d_in % d_block != 0) return ARMOR_ERR_SHAPE;
+    if (N != 2 || M != 4) return ARMOR_ERR_UNSUPPORTED;
+    if (d_block != 32 && d_block != 64 && d_block != 128) return ARMOR_ERR_UNSUPPORTED;
+    if (d_in % 64 != 0) return ARMOR_ERR_UNSUPPORTED;
+    if (n_tokens >= ((int64_t)1 << 31) / 256 * 256 || d_out >= (int64_t)1 << 31) return ARMOR_ERR_SHAPE;
+    if (n_tokens == 0) return ARMOR_OK;
+    if (!ws || ws_bytes < armor_apply_workspace_bytes(n_tokens, d_in)) return ARMOR_ERR_WORKSPACE;
+    if (!aligned16(X) || !aligned16(A_bf16) || !aligned16(values) || !aligned16(meta) || !aligned16(B_bf16) ||
+        !aligned16(Y) || !aligned16(ws))
+        return ARMOR_ERR_ALIGN;
+    hipStream_t s = (hipStream_t)hip_stream;
+    {
+        ProfScope ps(ARMOR_PROF_APPLY_PRE, s);
+        launch_apply_pre(X, n_tokens, d_in, (int)d_block, B_bf16, ws, s);
+    }
+    {
+        ProfScope ps(ARMOR_PROF_APPLY_MAIN, s);
+        if (launch_apply_main(ws, n_tokens, d_in, d_out, (int)d_block, values, meta, A_bf16, Y, s) != hipSuccess)
+            return ARMOR_ERR_DEVICE;
+    }
+    return check_hip();
+}
+
 } // extern "C"

@@ -49,6 +49,16 @@ def test_status_strings_and_host_side_validation():
     assert lib.armor_factorize_layer(p, 0, p, 0, 64, 60, 32, 2, 4, 1, None, p, p, p, None, None, None, None, None, p,
                                      1 << 30, None) == 2
     assert lib.armor_pack_nm(p, p, 4, 16, 2, 5, p, 0, p, None) == 2
+    assert lib.armor_pack_meta_row_bytes(4096, 2, 4) == 512 and lib.armor_pack_meta_row_bytes(72, 5, 8) == 23
+    assert lib.armor_pack_meta_row_bytes(70, 1, 2) == 5 and lib.armor_pack_meta_row_bytes(70, 2, 4) == 0
+    # the apply entry point: workspace = one bf16 activation matrix; unsupported patterns / shapes say so
+    assert lib.armor_apply_workspace_bytes(100, 64) >= 100 * 64 * 2
+    assert lib.armor_apply_packed(None, 1, p, p, p, p, 64, 64, 32, 2, 4, p, p, 1 << 20, None) == 1
+    assert lib.armor_apply_packed(p, 1, p, p, p, p, 64, 64, 32, 4, 8, p, p, 1 << 20, None) == 7   # only 2:4
+    assert lib.armor_apply_packed(p, 1, p, p, p, p, 64, 96, 32, 2, 4, p, p, 1 << 20, None) == 7   # d_in % 64
+    assert lib.armor_apply_packed(p, 1, p, p, p, p, 256, 256, 256, 2, 4, p, p, 1 << 20, None) == 7  # block 256
+    assert lib.armor_apply_packed(p, 1, p, p, p, p, 64, 64, 48, 2, 4, p, p, 1 << 20, None) == 2
+    assert lib.armor_apply_packed(p, 4, p, p, p, p, 64, 64, 32, 2, 4, p, p, 16, None) == 4         # workspace too small
 
 
 def test_product_package_does_not_import_the_oracle():
