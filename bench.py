@@ -47,7 +47,15 @@ BLOCK_WORKLOADS = {
         matrices=[("gate", 28672, "mlp_in"), ("up", 28672, "mlp_in"), ("down", 8192, "down_in")]),
 }
 
+# The factorized layer applied to a batch of activations (the batched product of Sec. 4.4, on the
+# gate_proj shape of a 14B model): (d_out, d_in, n_tokens, d_block).  Not the default bench line.
+APPLY_WORKLOADS = {
+    "qwen14b_gate_apply_8192tok_b128_2:4": (13824, 5120, 8192, 128),
+    "llama7b_attn_apply_8192tok_b128_2:4": (4096, 4096, 8192, 128),
+}
+
 FP32_MFMA_PEAK = 157.3e12  # MI355X dense fp32 matrix peak, FLOP/s
+BF16_MFMA_PEAK = 2.5e15    # MI355X dense bf16 matrix peak, FLOP/s
 
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by what the
 # same counter reads for a plain 256 MiB device copy (factors 2.000 and 1.000); see
@@ -148,12 +156,91 @@ def run_block_workload(args, armor, synth, torch, dev):
     }))
 
 
+def run_apply_workload(args, armor, synth, torch, dev):
+    """One step = one armor_apply_packed call (Y = A(S(BX)) for the whole batch), factors and
+    activations resident in HBM.  Factors are synthetic (random 2:4 core, near-identity wrappers):
+    the product's cost does not depend on their values."""
+    import numpy as np
+    d_out, d_in, n_tok, b = APPLY_WORKLOADS[args.workload]
+    g = torch.Generator(device=dev)
+    g.manual_seed(0)
+    S = torch.randn((d_out, d_in), device=dev, generator=g) * 0.02
+    scores = torch.rand((d_out, d_in // 4, 4), device=dev, generator=g)
+    keep = scores.argsort(dim=-1, descending=True)[..., :2]
+    mask = torch.zeros((d_out, d_in // 4, 4), device=dev, dtype=torch.uint8).scatter_(-1, keep, 1)
+    S = S * mask.reshape(d_out, d_in)
+    bits = (mask.to(torch.int32) << torch.arange(4, device=dev, dtype=torch.int32)).sum(-1).to(torch.uint8)
+    A = torch.eye(b, device=dev).repeat(d_out // b, 1, 1) + 0.02 * torch.randn((d_out // b, b, b), device=dev, generator=g)
+    Bw = torch.eye(b, device=dev).repeat(d_in // b, 1, 1) + 0.02 * torch.randn((d_in // b, b, b), device=dev, generator=g)
+    X = torch.randn((n_tok, d_in), device=dev, generator=g).to(torch.bfloat16)
+    vals, meta = armor.pack_nm(S.contiguous(), bits.contiguous(), 2, 4, bf16=True)
+    Ab, Bb = armor.to_bf16(A.contiguous()), armor.to_bf16(Bw.contiguous())
+    Y = torch.empty((n_tok, d_out), device=dev, dtype=torch.bfloat16)
+    ws = torch.empty(armor.apply_workspace_bytes(n_tok, d_in), device=dev, dtype=torch.uint8)
+    prepared = armor.apply_prepare(vals, meta, 2, 4)   # once per layer, outside the timed region
+    torch.cuda.synchronize()
+
+    def step():
+        armor.apply_packed(X, Ab, prepared, Bb, 2, 4, Y=Y, ws=ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    armor.profile_enable(True)
+    armor.profile_read()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    prof = armor.profile_read()
+    armor.profile_enable(False)
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    kernels = {k: {"launches": int(c), "avg_ms": ms / c} for k, (ms, c) in prof.items() if c > 0}
+    P = d_out * d_in
+    flops_main = 2.0 * n_tok * (P / 2 + d_out * b)          # 2:4 core product (kept entries only) + A wrapper
+    flops_pre = 2.0 * n_tok * d_in * b
+    main_ms = kernels["apply_main"]["avg_ms"]
+    achieved = flops_main / (main_ms * 1e-3) / 1e12
+    kernels["apply_main"]["tflops_algorithmic"] = achieved
+    kernels["apply_main"]["tflops_dense_equivalent"] = 2.0 * n_tok * (P + d_out * b) / (main_ms * 1e-3) / 1e12
+    pre_bytes = 2 * 2 * n_tok * d_in                           # X in, U out
+    kernels["apply_pre"]["hbm_GBps"] = pre_bytes / (kernels["apply_pre"]["avg_ms"] * 1e-3) / 1e9
+    kernels["apply_pre"]["tflops_algorithmic"] = flops_pre / (kernels["apply_pre"]["avg_ms"] * 1e-3) / 1e12
+    result = {
+        "metric": "tokens/s through one factorized layer (batched y = A(S(Bx)))", "value": n_tok / (ms_per_step * 1e-3),
+        "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": args.workload, "d_out": d_out, "d_in": d_in, "n_tokens": n_tok, "d_block": b,
+                   "pattern": "2:4", "step": "armor_apply_packed (pre-product + core product with wrapper epilogue)"},
+        "roofline": {"bound": "mfma", "kernel": "apply_main", "achieved": achieved, "peak": BF16_MFMA_PEAK / 1e12,
+                     "unit": "TFLOP/s", "frac": achieved / (BF16_MFMA_PEAK / 1e12), "traffic": None,
+                     "algorithmic_flops_per_launch": flops_main, "avg_launch_ms": main_ms},
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        oracle.build()
+        sample = 16
+        ev = vals[:, :].float().cpu().numpy()
+        idx = armor.unpack_meta(meta.cpu().numpy(), d_in, 2, 4)
+        c0 = time.perf_counter()
+        ref = oracle.apply_packed(X[:sample].float().cpu().numpy(), Ab.float().cpu().numpy(), ev, idx,
+                                  Bb.float().cpu().numpy(), 2, 4, round_bf16=True)
+        c1 = time.perf_counter()
+        got = Y[:sample].float().cpu().numpy().astype(np.float64)
+        result["cpu_baseline"] = {"value": sample / (c1 - c0), "unit": "tokens/s", "cores": 1, "kind": "oracle",
+                                  "sample": "%d of the %d tokens through the same layer; %.1f s wall" % (sample, n_tok, c1 - c0),
+                                  "rel_fro_err_vs_gpu": float(np.linalg.norm(got - ref) / np.linalg.norm(ref))}
+    print(json.dumps(result))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default=DEFAULT, choices=sorted(WORKLOADS) + sorted(BLOCK_WORKLOADS))
+    ap.add_argument("--workload", default=DEFAULT, choices=sorted(WORKLOADS) + sorted(BLOCK_WORKLOADS) + sorted(APPLY_WORKLOADS))
     ap.add_argument("--variant", default="gd", choices=["gd", "adam"],
                     help="continuous step: sequential 1/beta gradient steps (default; the monotone variant) or the "
                          "joint Adam step the authors run in practice (lr 1e-4)")
@@ -190,6 +277,9 @@ def main():
     dev = torch.device("cuda:0")
     if args.workload in BLOCK_WORKLOADS:
         run_block_workload(args, armor, synth, torch, dev)
+        return
+    if args.workload in APPLY_WORKLOADS:
+        run_apply_workload(args, armor, synth, torch, dev)
         return
     d_out, d_in, n_tok, b, N, M, n_iters, w_bf16, x_bf16, ofrac, oscale = WORKLOADS[args.workload]
     workload_name = args.workload + ("_adam" if args.variant == "adam" else "")

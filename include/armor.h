@@ -175,11 +175,18 @@ armor_status armor_pack_nm(const float *S, const uint8_t *mask_bits, int64_t d_o
  * The factorized layer applied to a batch of activations (Sec. 3.1: the wrappers are block
  * products around the N:M core; Sec. 4.4 times this product on a batch of tokens):
  *     Y[t] = A (S (B X[t]))      t = 0 .. n_tokens-1
+ *
+ * armor_apply_prepare (once per layer) re-tiles the compressed core into the order the product
+ * streams it in:
+ *   values   [d_out][d_in/2] bf16 and meta [d_out][d_in/8] bytes: armor_pack_nm with ARMOR_BF16
+ *   prepared armor_apply_prepared_bytes(d_out, d_in) bytes, device, 16-byte aligned; opaque
+ *            (per 64 input columns: the 64 B of values and the 8 B of index bits of every row,
+ *            rows padded to a multiple of 256).
+ * armor_apply_packed:
  *   X        [n_tokens][d_in]  bf16, row-major (one token per row)
  *   A_bf16   [d_out/d_block][d_block][d_block] bf16, B_bf16 [d_in/d_block][d_block][d_block] bf16:
  *            the wrappers of armor_factorize_layer (with opts->denormalize = 1 when the layer is
  *            to reproduce W rather than W-bar) converted by armor_to_bf16
- *   values   [d_out][d_in/2] bf16 and meta [d_out][d_in/8] bytes: armor_pack_nm with ARMOR_BF16
  *   Y        [n_tokens][d_out] bf16, row-major
  *   ws       armor_apply_workspace_bytes(n_tokens, d_in) bytes (holds B X in bf16)
  * Arithmetic: bf16 operands, fp32 accumulation; the two intermediates B x and S (B x) are rounded
@@ -189,10 +196,13 @@ armor_status armor_pack_nm(const float *S, const uint8_t *mask_bits, int64_t d_o
  * are device pointers, 16-byte aligned; asynchronous on the stream; n_tokens = 0 is a no-op.
  */
 armor_status armor_to_bf16(const float *in, int64_t n, void *out_bf16, void *hip_stream);
+size_t armor_apply_prepared_bytes(int64_t d_out, int64_t d_in);
+armor_status armor_apply_prepare(const void *values, const uint8_t *meta, int64_t d_out, int64_t d_in, int N, int M,
+                                 void *prepared, size_t prepared_bytes, void *hip_stream);
 size_t armor_apply_workspace_bytes(int64_t n_tokens, int64_t d_in);
-armor_status armor_apply_packed(const void *X, int64_t n_tokens, const void *A_bf16, const void *values,
-                                const uint8_t *meta, const void *B_bf16, int64_t d_out, int64_t d_in,
-                                int64_t d_block, int N, int M, void *Y, void *ws, size_t ws_bytes, void *hip_stream);
+armor_status armor_apply_packed(const void *X, int64_t n_tokens, const void *A_bf16, const void *prepared,
+                                const void *B_bf16, int64_t d_out, int64_t d_in, int64_t d_block, int N, int M,
+                                void *Y, void *ws, size_t ws_bytes, void *hip_stream);
 
 #ifdef __cplusplus
 }

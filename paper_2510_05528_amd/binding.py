@@ -16,7 +16,8 @@ EXPORTED = ["armor_status_string", "armor_last_hip_error", "armor_profile_enable
             "armor_gram_workspace_bytes", "armor_gram", "armor_gram_diag",
             "armor_normalize_workspace_bytes", "armor_normalize", "armor_proxy_loss_workspace_bytes",
             "armor_proxy_loss", "armor_factorize_workspace_bytes", "armor_factorize_layer", "armor_pack_nm",
-            "armor_pack_meta_row_bytes", "armor_to_bf16", "armor_apply_workspace_bytes", "armor_apply_packed"]
+            "armor_pack_meta_row_bytes", "armor_to_bf16", "armor_apply_prepared_bytes", "armor_apply_prepare",
+            "armor_apply_workspace_bytes", "armor_apply_packed"]
 
 
 class ArmorError(RuntimeError):
@@ -68,7 +69,10 @@ def load_library():
     lib.armor_to_bf16.argtypes = [_vp, _i64, _vp, _vp]
     lib.armor_apply_workspace_bytes.restype = _sz
     lib.armor_apply_workspace_bytes.argtypes = [_i64, _i64]
-    lib.armor_apply_packed.argtypes = [_vp, _i64, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _int, _vp, _vp, _sz, _vp]
+    lib.armor_apply_prepared_bytes.restype = _sz
+    lib.armor_apply_prepared_bytes.argtypes = [_i64, _i64]
+    lib.armor_apply_prepare.argtypes = [_vp, _vp, _i64, _i64, _int, _int, _vp, _sz, _vp]
+    lib.armor_apply_packed.argtypes = [_vp, _i64, _vp, _vp, _vp, _i64, _i64, _i64, _int, _int, _vp, _vp, _sz, _vp]
     _lib = lib
     return lib
 
@@ -272,23 +276,38 @@ def apply_workspace_bytes(n_tokens, d_in):
     return int(load_library().armor_apply_workspace_bytes(n_tokens, d_in))
 
 
-def apply_packed(X, A_bf16, values, meta, B_bf16, N, M, Y=None, ws=None):
-    """Y[t] = A (S (B X[t])) from the compressed core (armor_apply_packed). X [n, d_in] bf16 -> Y [n, d_out] bf16."""
+def apply_prepare(values, meta, N, M):
+    """Compressed core (armor_pack_nm, bf16 values) -> the streaming layout armor_apply_packed takes."""
     torch = _torch()
     lib = load_library()
-    for name, t in (("X", X), ("A_bf16", A_bf16), ("values", values), ("B_bf16", B_bf16)):
-        if not (t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous()):
-            raise ArmorError("%s must be a contiguous bf16 device tensor" % name)
+    if not (values.is_cuda and values.dtype == torch.bfloat16 and values.is_contiguous()):
+        raise ArmorError("values must be a contiguous bf16 device tensor")
     if not (meta.is_cuda and meta.dtype == torch.uint8 and meta.is_contiguous()):
         raise ArmorError("meta must be a contiguous uint8 device tensor")
+    d_out, d_in = values.shape[0], values.shape[1] * M // N
+    nbytes = int(lib.armor_apply_prepared_bytes(d_out, d_in))
+    prepared = torch.empty(max(nbytes, 16), device=values.device, dtype=torch.uint8)
+    _check(lib.armor_apply_prepare(_ptr(values), _ptr(meta), d_out, d_in, N, M, _ptr(prepared), prepared.numel(), _stream()))
+    return prepared
+
+
+def apply_packed(X, A_bf16, prepared, B_bf16, N, M, Y=None, ws=None):
+    """Y[t] = A (S (B X[t])) from the prepared core (armor_apply_packed). X [n, d_in] bf16 -> Y [n, d_out] bf16."""
+    torch = _torch()
+    lib = load_library()
+    for name, t in (("X", X), ("A_bf16", A_bf16), ("B_bf16", B_bf16)):
+        if not (t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous()):
+            raise ArmorError("%s must be a contiguous bf16 device tensor" % name)
+    if not (prepared.is_cuda and prepared.dtype == torch.uint8 and prepared.is_contiguous()):
+        raise ArmorError("prepared must be a contiguous uint8 device tensor")
     n, d_in = X.shape
     b = A_bf16.shape[-1]
     d_out = A_bf16.shape[0] * b
     if Y is None:
         Y = torch.empty((n, d_out), device=X.device, dtype=torch.bfloat16)
     if ws is None:
-        ws = torch.empty(apply_workspace_bytes(n, d_in), device=X.device, dtype=torch.uint8)
-    _check(lib.armor_apply_packed(_ptr(X), n, _ptr(A_bf16), _ptr(values), _ptr(meta), _ptr(B_bf16), d_out, d_in, b, N, M,
+        ws = torch.empty(max(apply_workspace_bytes(n, d_in), 16), device=X.device, dtype=torch.uint8)
+    _check(lib.armor_apply_packed(_ptr(X), n, _ptr(A_bf16), _ptr(prepared), _ptr(B_bf16), d_out, d_in, b, N, M,
                                   _ptr(Y), _ptr(ws), ws.numel(), _stream()))
     return Y
 

@@ -1,12 +1,22 @@
 // The factorized layer applied to a batch of activations (Sec. 3.1: y = A (S (B x)), the wrappers as
 // batched block products around the 2:4 core; Sec. 4.4 times this on a batch of tokens).
 // bf16 operands, fp32 accumulation, the two intermediates rounded to bf16.  gfx950:
+//   apply_prepare_kernel  one-off re-tiling of the compressed core (values + 2-bit in-group columns
+//                      of armor_pack_nm) into the order the product streams it in;
 //   apply_pre_kernel   U = X B^T (block-diagonal), dense v_mfma_f32_32x32x16_bf16, operands straight
 //                      from global memory (the kernel is bound by reading X and writing U once);
 //   apply_main_kernel  Y = (U S^T) A^T: the core product on the 2:4 structured-sparse matrix
 //                      instruction v_smfmac_f32_32x32x32_bf16 (the compressed values and the 2-bit
-//                      in-group columns of armor_pack_nm are exactly its sparse operand and index),
-//                      then the A wrapper as an epilogue on the accumulator tile.
+//                      in-group columns are exactly its sparse operand and index), then the A
+//                      wrapper as an epilogue on the accumulator tile.
+//
+// Streaming layout ("stage-major"): the product consumes 64 dense k per stage.  For stage s the
+// 64 B of compressed values of every row are contiguous ([s][row][64 B]), likewise the 8 B of index
+// bits ([s][row][8 B]) and the 128 B of activations of every token ([s][token][128 B]); rows and
+// tokens are padded to a multiple of 256.  A tile-stage is then one contiguous run of whole cache
+// lines (16 KB + 2 KB + 32 KB) instead of 768 separately requested lines.  Inside a row the 16-byte
+// parts are stored permuted (part p of row r sits in slot p ^ key(r)) so that the 16-byte operand
+// reads from LDS, where the rows land unpadded, are free of bank conflicts.
 #include "armor_internal.h"
 
 namespace armor {
@@ -32,15 +42,52 @@ void launch_to_bf16(const float *in, int64_t n, void *out, hipStream_t s) {
                        reinterpret_cast<uint16_t *>(out));
 }
 
+// slot permutation keys: 16 consecutive rows (8 for the narrower LDS of older parts) read 16 bytes each
+// from distinct bank groups
+__device__ __forceinline__ int key_values(int r) { return ((r >> 2) ^ (r >> 1)) & 3; }        // 4 parts of 16 B per row
+__device__ __forceinline__ int key_acts(int t) { return ((t >> 1) ^ ((t & 1) << 2)) & 7; }   // 8 parts of 16 B per row
+
+__host__ __device__ inline int64_t pad256(int64_t x) { return (x + 255) / 256 * 256; }
+
+// prepared = [stages][rows_pad][64 B] values, then [stages][rows_pad][8 B] index bits
+__global__ __launch_bounds__(256) void apply_prepare_kernel(const uint16_t *__restrict__ values,
+                                                            const uint8_t *__restrict__ meta, int64_t d_out,
+                                                            int64_t d_in, uint8_t *__restrict__ prepared) {
+    const int64_t rows_pad = pad256(d_out), stages = d_in / 64;
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; // one 16-byte slot of the values per thread
+    if (e >= stages * rows_pad * 4) return;
+    const int slot = (int)(e & 3);
+    const int64_t r = (e >> 2) % rows_pad, s = (e >> 2) / rows_pad;
+    uint4 v = make_uint4(0u, 0u, 0u, 0u);
+    if (r < d_out) v = *reinterpret_cast<const uint4 *>(values + r * (d_in / 2) + s * 32 + (slot ^ key_values((int)r)) * 8);
+    reinterpret_cast<uint4 *>(prepared)[e] = v;
+    if (slot == 0) {
+        uint2 m = make_uint2(0u, 0u);
+        if (r < d_out) m = *reinterpret_cast<const uint2 *>(meta + r * (d_in / 8) + s * 8);
+        reinterpret_cast<uint2 *>(prepared + stages * rows_pad * 64)[s * rows_pad + r] = m;
+    }
+}
+
+int64_t apply_prepared_bytes(int64_t d_out, int64_t d_in) { return (d_in / 64) * pad256(d_out) * 72; }
+int64_t apply_acts_bytes(int64_t n, int64_t d_in) { return (d_in / 64) * pad256(n) * 128; }
+
+void launch_apply_prepare(const void *values, const uint8_t *meta, int64_t d_out, int64_t d_in, void *prepared,
+                          hipStream_t s) {
+    const int64_t total = (d_in / 64) * pad256(d_out) * 4;
+    hipLaunchKernelGGL(apply_prepare_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
+                       reinterpret_cast<const uint16_t *>(values), meta, d_out, d_in, reinterpret_cast<uint8_t *>(prepared));
+}
+
 // ------------------------------------------------------------------------------------------------
 // U[t][j*b + p] = sum_q B^j[p][q] X[t][j*b + q].   One wave: 32 tokens x the b columns of block j.
 // MFMA rows = tokens (operand from X: 8 consecutive q per lane), columns = p (operand from B^j:
-// 8 consecutive q of row p per lane); a lane of the result holds one column p, so a store
-// instruction writes 32 consecutive bf16 of one token row.
+// 8 consecutive q of row p per lane); a lane of the result holds one column p.  U is written in the
+// stage-major layout described at the top: [column / 64][token][128 B], 16-byte parts permuted.
 // ------------------------------------------------------------------------------------------------
 template <int B>
 __global__ __launch_bounds__(256) void apply_pre_kernel(const uint16_t *__restrict__ X, int64_t n, int64_t d_in,
-                                                        const uint16_t *__restrict__ Bw, uint16_t *__restrict__ U) {
+                                                        const uint16_t *__restrict__ Bw, uint8_t *__restrict__ U,
+                                                        int64_t n_pad) {
     constexpr int PT = B / 32; // column tiles
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, l32 = lane & 31, half = lane >> 5;
     const int j = blockIdx.y;
@@ -68,18 +115,23 @@ __global__ __launch_bounds__(256) void apply_pre_kernel(const uint16_t *__restri
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int64_t t = t0 + 8 * (r >> 2) + 4 * half + (r & 3);
-            if (t < n) U[t * d_in + (int64_t)j * B + pt * 32 + l32] = (uint16_t)(pack_bf16x2_rne(acc[pt][r], 0.f) & 0xffffu);
+            const int64_t col = (int64_t)j * B + pt * 32 + l32;
+            const int within = (int)(col & 63), slot = (within >> 3) ^ key_acts((int)(t & 255));
+            if (t < n)
+                *reinterpret_cast<uint16_t *>(U + ((col >> 6) * n_pad + t) * 128 + slot * 16 + (within & 7) * 2) =
+                    (uint16_t)(pack_bf16x2_rne(acc[pt][r], 0.f) & 0xffffu);
         }
 }
 
 void launch_apply_pre(const void *X, int64_t n, int64_t d_in, int b, const void *Bw, void *U, hipStream_t s) {
     dim3 grid((unsigned)((n + 127) / 128), (unsigned)(d_in / b));
     const uint16_t *x = reinterpret_cast<const uint16_t *>(X), *bw = reinterpret_cast<const uint16_t *>(Bw);
-    uint16_t *u = reinterpret_cast<uint16_t *>(U);
+    uint8_t *u = reinterpret_cast<uint8_t *>(U);
+    const int64_t n_pad = pad256(n);
     switch (b) {
-    case 32: hipLaunchKernelGGL(apply_pre_kernel<32>, grid, dim3(256), 0, s, x, n, d_in, bw, u); break;
-    case 64: hipLaunchKernelGGL(apply_pre_kernel<64>, grid, dim3(256), 0, s, x, n, d_in, bw, u); break;
-    case 128: hipLaunchKernelGGL(apply_pre_kernel<128>, grid, dim3(256), 0, s, x, n, d_in, bw, u); break;
+    case 32: hipLaunchKernelGGL(apply_pre_kernel<32>, grid, dim3(256), 0, s, x, n, d_in, bw, u, n_pad); break;
+    case 64: hipLaunchKernelGGL(apply_pre_kernel<64>, grid, dim3(256), 0, s, x, n, d_in, bw, u, n_pad); break;
+    case 128: hipLaunchKernelGGL(apply_pre_kernel<128>, grid, dim3(256), 0, s, x, n, d_in, bw, u, n_pad); break;
     default: break;
     }
 }
@@ -87,29 +139,58 @@ void launch_apply_pre(const void *X, int64_t n, int64_t d_in, int b, const void 
 // ------------------------------------------------------------------------------------------------
 // Y[t][o] = sum_q A^i[p][q] V[t][i*b + q],  V[t][o] = sum_k S[o][k] U[t][k]  (V rounded to bf16).
 // Workgroup: 256 rows of S x 256 tokens, 8 waves as 2 (rows) x 4 (tokens), a wave owns 128 x 64
-// (4 x 2 accumulator tiles).  Per stage of 64 dense k: the compressed values (256 x 64 B), their
-// index bits (256 x 8 B) and the activations (256 x 128 B) go through LDS (two stages, register
-// prefetch of the next one).  Sparse operand of the instruction: lane (row, h) = the 8 kept values
-// of dense k in [16h, 16h+16) of the 32-k step and their 16 index bits; dense operand: lane
-// (token, h) = k in [8h, 8h+8) and [16+8h, 16+8h+8).
+// (4 x 2 accumulator tiles).  Per stage of 64 dense k the compressed values (256 x 64 B), their
+// index bits (256 x 8 B) and the activations (256 x 128 B) are loaded from global memory straight
+// into LDS (global_load_lds, 16 B per lane; no register staging), three LDS slots, two stages in
+// flight while one is consumed; one barrier per stage.  Both operands arrive in the stage-major
+// layout, so every load instruction copies 1 KB of consecutive bytes; the slot permutation inside a
+// row is already in the data and the reader applies the same XOR.
+// Sparse operand of the instruction: lane (row, h) = the 8 kept values of dense k in [16h, 16h+16)
+// of the 32-k step and their 16 index bits; dense operand: lane (token, h) = k in [8h, 8h+8) and
+// [16+8h, 16+8h+8).
 // Epilogue: each wave's 128 rows are whole blocks of A (b <= 128), so it needs only its own V patch:
 // written to LDS as [token][q] bf16, multiplied by A^i with the dense bf16 instruction (rows =
 // tokens, columns = p), stored like the kernel above.
 // ------------------------------------------------------------------------------------------------
 constexpr int AP_TM = 256, AP_TN = 256, AP_KT = 64;
 constexpr int AP_SUP_R = 8, AP_SUP_T = 4; // super-tile of one XCD: 8 row tiles x 4 token tiles = 32 workgroups
-constexpr int AP_SV_PITCH = 80;   // bytes per row of compressed values (64 + 16 pad)
-constexpr int AP_U_PITCH = 144;   // bytes per token row (128 + 16 pad)
-constexpr int AP_SV_BYTES = AP_TM * AP_SV_PITCH, AP_SM_BYTES = AP_TM * 8, AP_U_BYTES = AP_TN * AP_U_PITCH;
-constexpr int AP_STAGE_BYTES = AP_SV_BYTES + AP_SM_BYTES + AP_U_BYTES;
+constexpr int AP_SV_BYTES = AP_TM * 64, AP_SM_BYTES = AP_TM * 8, AP_U_BYTES = AP_TN * 128;
+constexpr int AP_SM_OFF = AP_SV_BYTES, AP_U_OFF = AP_SV_BYTES + AP_SM_BYTES;
+constexpr int AP_SLOT_BYTES = AP_SV_BYTES + AP_SM_BYTES + AP_U_BYTES; // 51200
+constexpr int AP_SLOTS = 3;
 constexpr int AP_V_PITCH = 272;   // epilogue: bytes per token row of a wave's V patch (128 bf16 + 16 pad)
 constexpr int AP_V_BYTES = 8 * 64 * AP_V_PITCH;
-constexpr int AP_LDS_BYTES = 2 * AP_STAGE_BYTES > AP_V_BYTES ? 2 * AP_STAGE_BYTES : AP_V_BYTES;
+constexpr int AP_LDS_BYTES = AP_SLOTS * AP_SLOT_BYTES > AP_V_BYTES ? AP_SLOTS * AP_SLOT_BYTES : AP_V_BYTES;
+constexpr int AP_DMA_PER_STAGE = 7; // load instructions per wave per stage: 2 (values) + 4 (activations) + 1 (index bits)
+
+typedef __attribute__((address_space(3))) void *lds_ptr_t;
+
+// One global -> LDS load instruction: every lane fetches 16 (or 4) bytes from its own global address,
+// the wave's 64 pieces land contiguously at the wave-uniform LDS byte address held in M0.  Issued as
+// inline assembly on purpose: the compiler then keeps no book on these loads, so it does not make the
+// operand reads of the stage being consumed wait for the stages still in flight; completion is waited
+// for explicitly (s_waitcnt vmcnt) before the barrier that publishes a stage.
+__device__ __forceinline__ void dma_load16(const void *g, uint32_t lds_byte_addr) {
+    asm volatile("s_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "{m0}"(lds_byte_addr) : "memory");
+}
+__device__ __forceinline__ void dma_load4(const void *g, uint32_t lds_byte_addr) {
+    asm volatile("s_nop 0\n\tglobal_load_lds_dword %0, off" ::"v"(g), "{m0}"(lds_byte_addr) : "memory");
+}
+
+// s_waitcnt vmcnt(n) alone (expcnt and lgkmcnt fields left at "no wait")
+#define AP_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0f70 | ((n) & 15) | (((n) >> 4) << 14))
+// workgroup barrier that the compiler may not move memory accesses across, without the fence of
+// __syncthreads (a fence would wait for every outstanding load, including the stages in flight)
+#define AP_BARRIER()                        \
+    {                                       \
+        asm volatile("" ::: "memory");      \
+        __builtin_amdgcn_s_barrier();       \
+        asm volatile("" ::: "memory");      \
+    }
 
 template <int B>
-__global__ __launch_bounds__(512) void apply_main_kernel(const uint16_t *__restrict__ U, int64_t n, int64_t d_in,
-                                                         int64_t d_out, const uint16_t *__restrict__ Sv,
-                                                         const uint8_t *__restrict__ Sm,
+__global__ __launch_bounds__(512) void apply_main_kernel(const uint8_t *__restrict__ U, int64_t n, int64_t d_in,
+                                                         int64_t d_out, const uint8_t *__restrict__ prepared,
                                                          const uint16_t *__restrict__ Aw, uint16_t *__restrict__ Y,
                                                          int n_row_tiles, int n_tok_tiles) {
     __shared__ __attribute__((aligned(16))) uint8_t lds[AP_LDS_BYTES];
@@ -127,43 +208,27 @@ __global__ __launch_bounds__(512) void apply_main_kernel(const uint16_t *__restr
     }
     if (row_tile >= n_row_tiles || tok_tile >= n_tok_tiles) return; // uniform for the workgroup
     const int64_t row0 = (int64_t)row_tile * AP_TM, tok0 = (int64_t)tok_tile * AP_TN;
-    const int64_t val_pitch = d_in / 2 /* bf16 per row */, meta_pitch = d_in / 8 /* bytes per row */;
+    const int64_t rows_pad = (int64_t)n_row_tiles * AP_TM, n_pad = (int64_t)n_tok_tiles * AP_TN;
+    const int64_t nst = d_in / AP_KT;
 
-    // ---- loader assignment (global -> registers -> LDS): 16-byte chunks, consecutive threads on
-    // consecutive chunks of a row ----
-    const uint16_t *sv_src0 = Sv + min(row0 + (tid >> 2), d_out - 1) * val_pitch + (tid & 3) * 8;
-    const uint16_t *sv_src1 = Sv + min(row0 + (tid >> 2) + 128, d_out - 1) * val_pitch + (tid & 3) * 8;
-    const int sv_dst = (tid >> 2) * AP_SV_PITCH + (tid & 3) * 16; // second chunk: + 128 rows
-    const uint16_t *u_src0 = U + min(tok0 + (tid >> 3), n - 1) * d_in + (tid & 7) * 8;
-    const uint16_t *u_src1 = U + min(tok0 + (tid >> 3) + 64, n - 1) * d_in + (tid & 7) * 8;
-    const uint16_t *u_src2 = U + min(tok0 + (tid >> 3) + 128, n - 1) * d_in + (tid & 7) * 8;
-    const uint16_t *u_src3 = U + min(tok0 + (tid >> 3) + 192, n - 1) * d_in + (tid & 7) * 8;
-    const int u_dst = AP_SV_BYTES + AP_SM_BYTES + (tid >> 3) * AP_U_PITCH + (tid & 7) * 16; // + 64 token rows each
-    const uint8_t *sm_src = Sm + min(row0 + (tid & 255), d_out - 1) * meta_pitch;
-    const int sm_dst = AP_SV_BYTES + (tid & 255) * 8;
+    // ---- this lane's share of a stage: 1 KB runs of the stage-major operands (padded: no edge cases) ----
+    const uint8_t *sv_src = prepared + (row0 + 32 * w) * 64 + lane * 16;                       // + stage * rows_pad * 64, + 1024
+    const uint8_t *sm_src = prepared + nst * rows_pad * 64 + (row0 + 32 * w) * 8 + lane * 4;   // + stage * rows_pad * 8
+    const uint8_t *u_src = U + (tok0 + 32 * w) * 128 + lane * 16;                              // + stage * n_pad * 128, + c * 1024
 
-    uint4 pv0, pv1, pu0, pu1, pu2, pu3;
-    uint2 pm = make_uint2(0u, 0u);
-#define AP_GLOAD(k0)                                                                            \
-    {                                                                                           \
-        pv0 = *reinterpret_cast<const uint4 *>(sv_src0 + (k0) / 2);                             \
-        pv1 = *reinterpret_cast<const uint4 *>(sv_src1 + (k0) / 2);                             \
-        pu0 = *reinterpret_cast<const uint4 *>(u_src0 + (k0));                                  \
-        pu1 = *reinterpret_cast<const uint4 *>(u_src1 + (k0));                                  \
-        pu2 = *reinterpret_cast<const uint4 *>(u_src2 + (k0));                                  \
-        pu3 = *reinterpret_cast<const uint4 *>(u_src3 + (k0));                                  \
-        if (tid < 256) pm = *reinterpret_cast<const uint2 *>(sm_src + (k0) / 8);                \
-    }
-#define AP_LSTORE(stage)                                                                        \
-    {                                                                                           \
-        uint8_t *sb = lds + (stage) * AP_STAGE_BYTES;                                           \
-        *reinterpret_cast<uint4 *>(sb + sv_dst) = pv0;                                          \
-        *reinterpret_cast<uint4 *>(sb + sv_dst + 128 * AP_SV_PITCH) = pv1;                      \
-        *reinterpret_cast<uint4 *>(sb + u_dst) = pu0;                                           \
-        *reinterpret_cast<uint4 *>(sb + u_dst + 64 * AP_U_PITCH) = pu1;                         \
-        *reinterpret_cast<uint4 *>(sb + u_dst + 128 * AP_U_PITCH) = pu2;                        \
-        *reinterpret_cast<uint4 *>(sb + u_dst + 192 * AP_U_PITCH) = pu3;                        \
-        if (tid < 256) *reinterpret_cast<uint2 *>(sb + sm_dst) = pm;                            \
+    const uint32_t lds0 = (uint32_t)(size_t)(lds_ptr_t)lds; // LDS byte address of the buffer
+#define AP_ISSUE(stage)                                                                    \
+    {                                                                                      \
+        const uint32_t sb = lds0 + ((stage) % AP_SLOTS) * AP_SLOT_BYTES;                   \
+        const uint8_t *sv = sv_src + (int64_t)(stage) * rows_pad * 64;                     \
+        const uint8_t *uu = u_src + (int64_t)(stage) * n_pad * 128;                        \
+        dma_load16(sv, sb + (2 * w) * 1024);                                               \
+        dma_load16(sv + 1024, sb + (2 * w + 1) * 1024);                                    \
+        dma_load16(uu, sb + AP_U_OFF + (4 * w) * 1024);                                    \
+        dma_load16(uu + 1024, sb + AP_U_OFF + (4 * w + 1) * 1024);                         \
+        dma_load16(uu + 2048, sb + AP_U_OFF + (4 * w + 2) * 1024);                         \
+        dma_load16(uu + 3072, sb + AP_U_OFF + (4 * w + 3) * 1024);                         \
+        dma_load4(sm_src + (int64_t)(stage) * rows_pad * 8, sb + AP_SM_OFF + w * 256);     \
     }
 
     floatx16 acc[4][2];
@@ -174,17 +239,25 @@ __global__ __launch_bounds__(512) void apply_main_kernel(const uint16_t *__restr
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[tm][tn][r] = 0.f;
 
-    const int a_off = (128 * wm + l32) * AP_SV_PITCH + half * 16;
-    const int m_off = AP_SV_BYTES + (128 * wm + l32) * 8;
-    const int b_off = AP_SV_BYTES + AP_SM_BYTES + (64 * wn + l32) * AP_U_PITCH + half * 16;
+    // reader offsets inside a slot (the keys use row bits 0..3 only and tile offsets are multiples of 32 rows)
+    int a_off[2], b_off[2][2];
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+        a_off[s] = (128 * wm + l32) * 64 + (((2 * s + half) ^ key_values(l32)) * 16);
+        b_off[s][0] = AP_U_OFF + (64 * wn + l32) * 128 + (((4 * s + half) ^ key_acts(l32)) * 16);
+        b_off[s][1] = AP_U_OFF + (64 * wn + l32) * 128 + (((4 * s + 2 + half) ^ key_acts(l32)) * 16);
+    }
+    const int m_off = AP_SM_OFF + (128 * wm + l32) * 8;
 
-    AP_GLOAD((int64_t)0);
-    AP_LSTORE(0);
-    __syncthreads();
     const int nstages = (int)(d_in / AP_KT);
+    AP_ISSUE(0);
+    if (nstages > 1) AP_ISSUE(1);
     for (int st = 0; st < nstages; ++st) {
-        const uint8_t *base = lds + (st & 1) * AP_STAGE_BYTES;
-        if (st + 1 < nstages) AP_GLOAD((int64_t)(st + 1) * AP_KT);
+        // stage st has landed once at most the loads of stage st+1 are outstanding
+        if (st + 1 < nstages) { AP_WAIT_VMCNT(AP_DMA_PER_STAGE); } else { AP_WAIT_VMCNT(0); }
+        AP_BARRIER(); // everyone's share of stage st is in LDS; everyone is done reading stage st-1
+        if (st + 2 < nstages) AP_ISSUE(st + 2); // into the slot stage st-1 occupied
+        const uint8_t *base = lds + (st % AP_SLOTS) * AP_SLOT_BYTES;
         uint2 meta[4];
 #pragma unroll
         for (int tm = 0; tm < 4; ++tm) meta[tm] = *reinterpret_cast<const uint2 *>(base + m_off + tm * 32 * 8);
@@ -195,15 +268,15 @@ __global__ __launch_bounds__(512) void apply_main_kernel(const uint16_t *__restr
             int idx[4];
 #pragma unroll
             for (int tm = 0; tm < 4; ++tm) {
-                a[tm] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(base + a_off + tm * 32 * AP_SV_PITCH + s * 32));
+                a[tm] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(base + a_off[s] + tm * 32 * 64));
                 const uint32_t word = s == 0 ? meta[tm].x : meta[tm].y; // 32 index bits of this 32-k step
                 const uint32_t f = (word >> (16 * half)) & 0xffffu;
                 idx[tm] = (int)(f | (f << 16));
             }
 #pragma unroll
             for (int tn = 0; tn < 2; ++tn) {
-                const bf16x8 lo = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(base + b_off + tn * 32 * AP_U_PITCH + s * 64));
-                const bf16x8 hi = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(base + b_off + tn * 32 * AP_U_PITCH + s * 64 + 32));
+                const bf16x8 lo = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(base + b_off[s][0] + tn * 32 * 128));
+                const bf16x8 hi = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(base + b_off[s][1] + tn * 32 * 128));
                 b[tn] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);
             }
 #pragma unroll
@@ -212,11 +285,9 @@ __global__ __launch_bounds__(512) void apply_main_kernel(const uint16_t *__restr
                 for (int tn = 0; tn < 2; ++tn)
                     acc[tm][tn] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(a[tm], b[tn], acc[tm][tn], idx[tm], 0, 0);
         }
-        if (st + 1 < nstages) AP_LSTORE((st + 1) & 1);
-        __syncthreads();
     }
-#undef AP_GLOAD
-#undef AP_LSTORE
+#undef AP_ISSUE
+    __syncthreads(); // every wave is done with the stage slots: the epilogue reuses them
 
     // ---- epilogue: V patch -> LDS [token][q] bf16, then Y = V A^T per block of A ----
     uint8_t *vbuf = lds + w * (64 * AP_V_PITCH);
@@ -266,18 +337,18 @@ __global__ __launch_bounds__(512) void apply_main_kernel(const uint16_t *__restr
     }
 }
 
-hipError_t launch_apply_main(const void *U, int64_t n, int64_t d_in, int64_t d_out, int b, const void *Sv,
-                             const uint8_t *Sm, const void *Aw, void *Y, hipStream_t s) {
+hipError_t launch_apply_main(const void *U, int64_t n, int64_t d_in, int64_t d_out, int b, const void *prepared,
+                             const void *Aw, void *Y, hipStream_t s) {
     const int n_row_tiles = (int)((d_out + AP_TM - 1) / AP_TM), n_tok_tiles = (int)((n + AP_TN - 1) / AP_TN);
     const int sups = ((n_row_tiles + AP_SUP_R - 1) / AP_SUP_R) * ((n_tok_tiles + AP_SUP_T - 1) / AP_SUP_T);
     dim3 grid((unsigned)(((sups + 7) / 8) * 8 * 32)), block(512);
-    const uint16_t *u = reinterpret_cast<const uint16_t *>(U), *sv = reinterpret_cast<const uint16_t *>(Sv),
-                   *aw = reinterpret_cast<const uint16_t *>(Aw);
+    const uint8_t *u = reinterpret_cast<const uint8_t *>(U), *pr = reinterpret_cast<const uint8_t *>(prepared);
+    const uint16_t *aw = reinterpret_cast<const uint16_t *>(Aw);
     uint16_t *y = reinterpret_cast<uint16_t *>(Y);
     switch (b) {
-    case 32: hipLaunchKernelGGL(apply_main_kernel<32>, grid, block, 0, s, u, n, d_in, d_out, sv, Sm, aw, y, n_row_tiles, n_tok_tiles); break;
-    case 64: hipLaunchKernelGGL(apply_main_kernel<64>, grid, block, 0, s, u, n, d_in, d_out, sv, Sm, aw, y, n_row_tiles, n_tok_tiles); break;
-    case 128: hipLaunchKernelGGL(apply_main_kernel<128>, grid, block, 0, s, u, n, d_in, d_out, sv, Sm, aw, y, n_row_tiles, n_tok_tiles); break;
+    case 32: hipLaunchKernelGGL(apply_main_kernel<32>, grid, block, 0, s, u, n, d_in, d_out, pr, aw, y, n_row_tiles, n_tok_tiles); break;
+    case 64: hipLaunchKernelGGL(apply_main_kernel<64>, grid, block, 0, s, u, n, d_in, d_out, pr, aw, y, n_row_tiles, n_tok_tiles); break;
+    case 128: hipLaunchKernelGGL(apply_main_kernel<128>, grid, block, 0, s, u, n, d_in, d_out, pr, aw, y, n_row_tiles, n_tok_tiles); break;
     default: return hipErrorInvalidValue;
     }
     return hipSuccess;

@@ -523,26 +523,50 @@ armor_status armor_to_bf16(const float *in, int64_t n, void *out_bf16, void *hip
     return check_hip();
 }
 
-size_t armor_apply_workspace_bytes(int64_t n_tokens, int64_t d_in) {
-    if (n_tokens < 0 || d_in <= 0) return 0;
-    return (size_t)n_tokens * (size_t)d_in * 2 + 256;
+static armor_status validate_apply(int64_t d_out, int64_t d_in, int64_t d_block, int N, int M) {
+    if (d_out <= 0 || d_in <= 0) return ARMOR_ERR_SHAPE;
+    if (d_block > 0 && (d_out % d_block != 0 || d_in % d_block != 0)) return ARMOR_ERR_SHAPE;
+    if (N != 2 || M != 4) return ARMOR_ERR_UNSUPPORTED;
+    if (d_block > 0 && d_block != 32 && d_block != 64 && d_block != 128) return ARMOR_ERR_UNSUPPORTED;
+    if (d_in % 64 != 0) return ARMOR_ERR_UNSUPPORTED;
+    if (d_out >= (int64_t)1 << 31 || d_in >= (int64_t)1 << 31) return ARMOR_ERR_SHAPE;
+    return ARMOR_OK;
 }
 
-armor_status armor_apply_packed(const void *X, int64_t n_tokens, const void *A_bf16, const void *values,
-                                const uint8_t *meta, const void *B_bf16, int64_t d_out, int64_t d_in,
-                                int64_t d_block, int N, int M, void *Y, void *ws, size_t ws_bytes, void *hip_stream) {
-    if (!A_bf16 || !values || !meta || !B_bf16) return ARMOR_ERR_NULL;
+size_t armor_apply_prepared_bytes(int64_t d_out, int64_t d_in) {
+    if (d_out <= 0 || d_in <= 0 || d_in % 64 != 0) return 0;
+    return (size_t)apply_prepared_bytes(d_out, d_in);
+}
+
+armor_status armor_apply_prepare(const void *values, const uint8_t *meta, int64_t d_out, int64_t d_in, int N, int M,
+                                 void *prepared, size_t prepared_bytes, void *hip_stream) {
+    if (!values || !meta || !prepared) return ARMOR_ERR_NULL;
+    armor_status st = validate_apply(d_out, d_in, 0, N, M);
+    if (st != ARMOR_OK) return st;
+    if (prepared_bytes < armor_apply_prepared_bytes(d_out, d_in)) return ARMOR_ERR_WORKSPACE;
+    if (!aligned16(values) || !aligned16(meta) || !aligned16(prepared)) return ARMOR_ERR_ALIGN;
+    launch_apply_prepare(values, meta, d_out, d_in, prepared, (hipStream_t)hip_stream);
+    return check_hip();
+}
+
+size_t armor_apply_workspace_bytes(int64_t n_tokens, int64_t d_in) {
+    if (n_tokens < 0 || d_in <= 0 || d_in % 64 != 0) return 0;
+    return (size_t)apply_acts_bytes(n_tokens, d_in) + 256;
+}
+
+armor_status armor_apply_packed(const void *X, int64_t n_tokens, const void *A_bf16, const void *prepared,
+                                const void *B_bf16, int64_t d_out, int64_t d_in, int64_t d_block, int N, int M,
+                                void *Y, void *ws, size_t ws_bytes, void *hip_stream) {
+    if (!A_bf16 || !prepared || !B_bf16) return ARMOR_ERR_NULL;
     if ((!X || !Y) && n_tokens != 0) return ARMOR_ERR_NULL; // an empty batch may come with null X, Y
-    if (n_tokens < 0 || d_out <= 0 || d_in <= 0 || d_block <= 0) return ARMOR_ERR_SHAPE;
-    if (d_out % d_block != 0 || d_in % d_block != 0) return ARMOR_ERR_SHAPE;
-    if (N != 2 || M != 4) return ARMOR_ERR_UNSUPPORTED;
-    if (d_block != 32 && d_block != 64 && d_block != 128) return ARMOR_ERR_UNSUPPORTED;
-    if (d_in % 64 != 0) return ARMOR_ERR_UNSUPPORTED;
-    if (n_tokens >= ((int64_t)1 << 31) / 256 * 256 || d_out >= (int64_t)1 << 31) return ARMOR_ERR_SHAPE;
+    if (n_tokens < 0 || d_block <= 0) return ARMOR_ERR_SHAPE;
+    armor_status st = validate_apply(d_out, d_in, d_block, N, M);
+    if (st != ARMOR_OK) return st;
+    if (n_tokens >= (int64_t)1 << 30) return ARMOR_ERR_SHAPE;
     if (n_tokens == 0) return ARMOR_OK;
     if (!ws || ws_bytes < armor_apply_workspace_bytes(n_tokens, d_in)) return ARMOR_ERR_WORKSPACE;
-    if (!aligned16(X) || !aligned16(A_bf16) || !aligned16(values) || !aligned16(meta) || !aligned16(B_bf16) ||
-        !aligned16(Y) || !aligned16(ws))
+    if (!aligned16(X) || !aligned16(A_bf16) || !aligned16(prepared) || !aligned16(B_bf16) || !aligned16(Y) ||
+        !aligned16(ws))
         return ARMOR_ERR_ALIGN;
     hipStream_t s = (hipStream_t)hip_stream;
     {
@@ -551,7 +575,7 @@ armor_status armor_apply_packed(const void *X, int64_t n_tokens, const void *A_b
     }
     {
         ProfScope ps(ARMOR_PROF_APPLY_MAIN, s);
-        if (launch_apply_main(ws, n_tokens, d_in, d_out, (int)d_block, values, meta, A_bf16, Y, s) != hipSuccess)
+        if (launch_apply_main(ws, n_tokens, d_in, d_out, (int)d_block, prepared, A_bf16, Y, s) != hipSuccess)
             return ARMOR_ERR_DEVICE;
     }
     return check_hip();

@@ -96,8 +96,12 @@ void launch_gram(const void *X, int bf16, int64_t n, int64_t d_in, int64_t ldx, 
 
 // ---- factorized layer applied to activations (apply.hip) ----------------------------------------
 void launch_to_bf16(const float *in, int64_t n, void *out, hipStream_t s);
+int64_t apply_prepared_bytes(int64_t d_out, int64_t d_in);
+int64_t apply_acts_bytes(int64_t n, int64_t d_in);
+void launch_apply_prepare(const void *values, const uint8_t *meta, int64_t d_out, int64_t d_in, void *prepared,
+                          hipStream_t s);
 void launch_apply_pre(const void *X, int64_t n, int64_t d_in, int b, const void *Bw, void *U, hipStream_t s);
-hipError_t launch_apply_main(const void *U, int64_t n, int64_t d_in, int64_t d_out, int b, const void *Sv,
-                             const uint8_t *Sm, const void *Aw, void *Y, hipStream_t s);
+hipError_t launch_apply_main(const void *U, int64_t n, int64_t d_in, int64_t d_out, int b, const void *prepared,
+                             const void *Aw, void *Y, hipStream_t s);
 
 } // namespace armor

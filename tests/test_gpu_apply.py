@@ -61,7 +61,8 @@ def run_case(armor, torch, orc, dev, n, d_out, d_in, b, seed):
     Ab, Bb = armor.to_bf16(torch.from_numpy(A).to(dev)), armor.to_bf16(torch.from_numpy(B).to(dev))
     Xb = torch.from_numpy(X).to(dev).to(torch.bfloat16)
     say("apply n=%d d_out=%d d_in=%d b=%d" % (n, d_out, d_in, b))
-    Y = armor.apply_packed(Xb, Ab, vals, meta, Bb, 2, 4)
+    prepared = armor.apply_prepare(vals, meta, 2, 4)
+    Y = armor.apply_packed(Xb, Ab, prepared, Bb, 2, 4)
     torch.cuda.synchronize()
     # the oracle sees exactly the bf16 operands the kernels saw
     ev, ei = orc.pack_nm(S, mask, 2, 4)
@@ -107,7 +108,7 @@ def test_apply_after_factorization(env, orc):
     vals, meta = armor.pack_nm(out["S"], out["mask_bits"], 2, 4, bf16=True)
     Ab, Bb = armor.to_bf16(out["A"]), armor.to_bf16(out["B"])
     Xb = torch.from_numpy(Xc[:n]).to(dev).to(torch.bfloat16)
-    Y = armor.apply_packed(Xb, Ab, vals, meta, Bb, 2, 4)
+    Y = armor.apply_packed(Xb, Ab, armor.apply_prepare(vals, meta, 2, 4), Bb, 2, 4)
     torch.cuda.synchronize()
     mask = armor.unpack_mask(out["mask_bits"].cpu().numpy(), 4)
     ev, ei = orc.pack_nm(out["S"].cpu().numpy(), mask, 2, 4)
@@ -127,11 +128,12 @@ def test_apply_edge_cases(env):
     Bw = torch.zeros((d_in // b, b, b), device=dev, dtype=torch.bfloat16)
     vals = torch.zeros((d_out, d_in // 2), device=dev, dtype=torch.bfloat16)
     meta = torch.zeros((d_out, d_in // 8), device=dev, dtype=torch.uint8)
+    prepared = armor.apply_prepare(vals, meta, 2, 4)
     X0 = torch.zeros((0, d_in), device=dev, dtype=torch.bfloat16)
-    assert armor.apply_packed(X0, A, vals, meta, Bw, 2, 4).shape == (0, d_out)     # no tokens: no-op
+    assert armor.apply_packed(X0, A, prepared, Bw, 2, 4).shape == (0, d_out)       # no tokens: no-op
     X = torch.ones((3, d_in), device=dev, dtype=torch.bfloat16)
     with pytest.raises(armor.ArmorError):
-        armor.apply_packed(X, A, vals, meta, Bw, 4, 8)                               # only 2:4 on this path
-    Y = armor.apply_packed(X, A, vals, meta, Bw, 2, 4)                               # all-zero factors
+        armor.apply_packed(X, A, prepared, Bw, 4, 8)                                 # only 2:4 on this path
+    Y = armor.apply_packed(X, A, prepared, Bw, 2, 4)                                 # all-zero factors
     torch.cuda.synchronize()
     assert float(Y.float().abs().max()) == 0.0

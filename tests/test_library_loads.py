@@ -52,13 +52,16 @@ def test_status_strings_and_host_side_validation():
     assert lib.armor_pack_meta_row_bytes(4096, 2, 4) == 512 and lib.armor_pack_meta_row_bytes(72, 5, 8) == 23
     assert lib.armor_pack_meta_row_bytes(70, 1, 2) == 5 and lib.armor_pack_meta_row_bytes(70, 2, 4) == 0
     # the apply entry point: workspace = one bf16 activation matrix; unsupported patterns / shapes say so
-    assert lib.armor_apply_workspace_bytes(100, 64) >= 100 * 64 * 2
-    assert lib.armor_apply_packed(None, 1, p, p, p, p, 64, 64, 32, 2, 4, p, p, 1 << 20, None) == 1
-    assert lib.armor_apply_packed(p, 1, p, p, p, p, 64, 64, 32, 4, 8, p, p, 1 << 20, None) == 7   # only 2:4
-    assert lib.armor_apply_packed(p, 1, p, p, p, p, 64, 96, 32, 2, 4, p, p, 1 << 20, None) == 7   # d_in % 64
-    assert lib.armor_apply_packed(p, 1, p, p, p, p, 256, 256, 256, 2, 4, p, p, 1 << 20, None) == 7  # block 256
-    assert lib.armor_apply_packed(p, 1, p, p, p, p, 64, 64, 48, 2, 4, p, p, 1 << 20, None) == 2
-    assert lib.armor_apply_packed(p, 4, p, p, p, p, 64, 64, 32, 2, 4, p, p, 16, None) == 4         # workspace too small
+    assert lib.armor_apply_workspace_bytes(100, 64) >= 256 * 64 * 2               # tokens padded to 256
+    assert lib.armor_apply_prepared_bytes(300, 128) == 2 * 512 * 72 and lib.armor_apply_prepared_bytes(300, 96) == 0
+    assert lib.armor_apply_prepare(p, p, 64, 64, 4, 8, p, 1 << 20, None) == 7                     # only 2:4
+    assert lib.armor_apply_prepare(p, p, 64, 64, 2, 4, p, 16, None) == 4                          # buffer too small
+    assert lib.armor_apply_packed(None, 1, p, p, p, 64, 64, 32, 2, 4, p, p, 1 << 20, None) == 1
+    assert lib.armor_apply_packed(p, 1, p, p, p, 64, 64, 32, 4, 8, p, p, 1 << 20, None) == 7      # only 2:4
+    assert lib.armor_apply_packed(p, 1, p, p, p, 64, 96, 32, 2, 4, p, p, 1 << 20, None) == 7      # d_in % 64
+    assert lib.armor_apply_packed(p, 1, p, p, p, 256, 256, 256, 2, 4, p, p, 1 << 20, None) == 7   # block 256
+    assert lib.armor_apply_packed(p, 1, p, p, p, 64, 64, 48, 2, 4, p, p, 1 << 20, None) == 2
+    assert lib.armor_apply_packed(p, 4, p, p, p, 64, 64, 32, 2, 4, p, p, 16, None) == 4            # workspace too small
 
 
 def test_product_package_does_not_import_the_oracle():
