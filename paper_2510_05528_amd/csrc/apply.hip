@@ -25,11 +25,13 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x16 __attribute__((ext_vector_type(16)));
 
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+
+// two floats -> two bf16 (round to nearest even) in one register: v_cvt_pk_bf16_f32
 __device__ __forceinline__ uint32_t pack_bf16x2_rne(float lo, float hi) {
-    uint32_t a = __float_as_uint(lo), b = __float_as_uint(hi);
-    a = (a & 0x7fffffffu) > 0x7f800000u ? (a | 0x400000u) : a + 0x7fffu + ((a >> 16) & 1u);
-    b = (b & 0x7fffffffu) > 0x7f800000u ? (b | 0x400000u) : b + 0x7fffu + ((b >> 16) & 1u);
-    return (a >> 16) | (b & 0xffff0000u);
+    const floatx2 f = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
 }
 
 __global__ __launch_bounds__(256) void to_bf16_kernel(const float *__restrict__ in, int64_t n, uint16_t *__restrict__ out) {
@@ -196,17 +198,17 @@ __global__ __launch_bounds__(512) void apply_main_kernel(const uint8_t *__restri
     __shared__ __attribute__((aligned(16))) uint8_t lds[AP_LDS_BYTES];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, l32 = lane & 31, half = lane >> 5;
     const int wm = w & 1, wn = w >> 1;
-    // Workgroups go to the 8 XCDs round-robin, each XCD with its own L2.  The 32 workgroups that are
-    // resident on one XCD together work on a super-tile of 8 row tiles x 4 token tiles, so that per
-    // stage the XCD fetches 8 + 4 operand tiles instead of 32 + 32.
-    int row_tile, tok_tile;
-    {
-        const int xcd = blockIdx.x & 7, seq = blockIdx.x >> 3, sup = (seq >> 5) * 8 + xcd, within = seq & 31;
-        const int sup_rows = (n_row_tiles + AP_SUP_R - 1) / AP_SUP_R;
-        row_tile = (sup % sup_rows) * AP_SUP_R + (within % AP_SUP_R);
-        tok_tile = (sup / sup_rows) * AP_SUP_T + (within / AP_SUP_R);
-    }
-    if (row_tile >= n_row_tiles || tok_tile >= n_tok_tiles) return; // uniform for the workgroup
+    // Workgroups go to the 8 XCDs round-robin, each XCD with its own L2.  The grid is persistent (one
+    // workgroup per CU); in round k the 32 workgroups of XCD x work on super-tile 8k + x, 8 row tiles x
+    // 4 token tiles, so that per stage the XCD fetches 8 + 4 operand tiles instead of 32 + 32.
+    const int xcd = blockIdx.x & 7, within = (blockIdx.x >> 3) & 31, wg_round0 = blockIdx.x >> 8;
+    const int sup_rows = (n_row_tiles + AP_SUP_R - 1) / AP_SUP_R, sup_cols = (n_tok_tiles + AP_SUP_T - 1) / AP_SUP_T;
+    const int rounds_stride = (int)(gridDim.x >> 8);
+    for (int round = wg_round0; round * 8 + xcd < sup_rows * sup_cols; round += rounds_stride) {
+    const int sup = round * 8 + xcd;
+    const int row_tile = (sup % sup_rows) * AP_SUP_R + (within % AP_SUP_R);
+    const int tok_tile = (sup / sup_rows) * AP_SUP_T + (within / AP_SUP_R);
+    if (row_tile >= n_row_tiles || tok_tile >= n_tok_tiles) continue; // uniform for the workgroup
     const int64_t row0 = (int64_t)row_tile * AP_TM, tok0 = (int64_t)tok_tile * AP_TN;
     const int64_t rows_pad = (int64_t)n_row_tiles * AP_TM, n_pad = (int64_t)n_tok_tiles * AP_TN;
     const int64_t nst = d_in / AP_KT;
@@ -302,14 +304,21 @@ __global__ __launch_bounds__(512) void apply_main_kernel(const uint8_t *__restri
                 pk.y = pack_bf16x2_rne(acc[tm][tn][4 * g + 2], acc[tm][tn][4 * g + 3]);
                 *reinterpret_cast<uint2 *>(vbuf + (32 * tn + l32) * AP_V_PITCH + (32 * tm + 8 * g + 4 * half) * 2) = pk;
             }
-    __syncthreads();
     const int64_t prow0 = row0 + 128 * wm; // first output column (row of S) of this wave
+    // all wrapper operands of the wave in one round of loads (the accumulators are dead by now)
+    uint4 afrag[4][B / 16];
+#pragma unroll
+    for (int pt = 0; pt < 4; ++pt) {
+        const int64_t pclamped = min(prow0 + pt * 32 + l32, d_out - 1);
+        const uint16_t *arow = Aw + pclamped * B + 8 * half; // A^i[p][q]: (i*b + p)*b + q = prow*b + (q - q0)
+#pragma unroll
+        for (int ks = 0; ks < B / 16; ++ks) afrag[pt][ks] = *reinterpret_cast<const uint4 *>(arow + 16 * ks);
+    }
+    __syncthreads();
 #pragma unroll
     for (int pt = 0; pt < 4; ++pt) {
         const int q0 = (pt * 32 / B) * B; // first q of the block of A that holds these 32 columns
         const int64_t prow = prow0 + pt * 32 + l32;
-        const int64_t pclamped = min(prow, d_out - 1);
-        const uint16_t *arow = Aw + pclamped * B + 8 * half; // A^i[p][q]: (i*b + p)*b + q = prow*b + (q - q0)
         floatx16 o[2];
 #pragma unroll
         for (int tn = 0; tn < 2; ++tn)
@@ -317,7 +326,7 @@ __global__ __launch_bounds__(512) void apply_main_kernel(const uint8_t *__restri
             for (int r = 0; r < 16; ++r) o[tn][r] = 0.f;
 #pragma unroll
         for (int ks = 0; ks < B / 16; ++ks) {
-            const bf16x8 bb = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(arow + 16 * ks));
+            const bf16x8 bb = __builtin_bit_cast(bf16x8, afrag[pt][ks]);
 #pragma unroll
             for (int tn = 0; tn < 2; ++tn) {
                 const bf16x8 a = __builtin_bit_cast(
@@ -325,23 +334,40 @@ __global__ __launch_bounds__(512) void apply_main_kernel(const uint8_t *__restri
                 o[tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bb, o[tn], 0, 0, 0);
             }
         }
-        if (prow < d_out) {
+        // A lane holds column p of 16 token rows.  Neighbouring lanes swap one value per pair of rows, so
+        // that an even lane stores (p, p+1) of the first row and the odd lane (p-1, p) of the second:
+        // 4-byte stores, 64 consecutive bytes of a token row per half-wave.
+        const bool odd = lane & 1;
+        if (prow < d_out) { // d_out is a multiple of 32: a pair of columns is inside or outside together
 #pragma unroll
-            for (int tn = 0; tn < 2; ++tn)
+            for (int tn = 0; tn < 2; ++tn) {
+                // first token row of this lane in the tile, and how many rows of the batch are left from there
+                const int64_t tl = tok0 + 64 * wn + 32 * tn + 4 * half + (odd ? 1 : 0);
+                const int left = (int)min((int64_t)64, n - tl);
+                uint16_t *ybase = Y + tl * d_out + (prow & ~(int64_t)1);
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int64_t t = tok0 + 64 * wn + 32 * tn + 8 * (r >> 2) + 4 * half + (r & 3);
-                    if (t < n) Y[t * d_out + prow] = (uint16_t)(pack_bf16x2_rne(o[tn][r], 0.f) & 0xffffu);
+                for (int r = 0; r < 16; r += 2) {
+                    const float mine = odd ? o[tn][r + 1] : o[tn][r], send = odd ? o[tn][r] : o[tn][r + 1];
+                    const float recv = __builtin_bit_cast(
+                        float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, send), 0xB1 /* quad_perm [1,0,3,2] */, 0xF, 0xF, true));
+                    const int roff = 8 * (r >> 2) + (r & 3); // row offset from tl (same for both lanes of a pair)
+                    const uint32_t pk = odd ? pack_bf16x2_rne(recv, mine) : pack_bf16x2_rne(mine, recv);
+                    if (roff < left) *reinterpret_cast<uint32_t *>(ybase + (int64_t)roff * d_out) = pk;
                 }
+            }
         }
     }
+    __syncthreads(); // the next tile's loads overwrite the patch buffers
+    } // tiles of this workgroup
 }
 
 hipError_t launch_apply_main(const void *U, int64_t n, int64_t d_in, int64_t d_out, int b, const void *prepared,
                              const void *Aw, void *Y, hipStream_t s) {
     const int n_row_tiles = (int)((d_out + AP_TM - 1) / AP_TM), n_tok_tiles = (int)((n + AP_TN - 1) / AP_TN);
     const int sups = ((n_row_tiles + AP_SUP_R - 1) / AP_SUP_R) * ((n_tok_tiles + AP_SUP_T - 1) / AP_SUP_T);
-    dim3 grid((unsigned)(((sups + 7) / 8) * 8 * 32)), block(512);
+    // persistent grid: 256 workgroups (one per CU, 32 per XCD) walk the super-tiles
+    (void)sups;
+    dim3 grid(256), block(512);
     const uint8_t *u = reinterpret_cast<const uint8_t *>(U), *pr = reinterpret_cast<const uint8_t *>(prepared);
     const uint16_t *aw = reinterpret_cast<const uint16_t *>(Aw);
     uint16_t *y = reinterpret_cast<uint16_t *>(Y);
