@@ -80,53 +80,99 @@ void launch_apply_prepare(const void *values, const uint8_t *meta, int64_t d_out
                        reinterpret_cast<const uint16_t *>(values), meta, d_out, d_in, reinterpret_cast<uint8_t *>(prepared));
 }
 
+// 4 x 4 transpose inside every quad of lanes (x[i] of lane j <-> x[j] of lane i), two rounds of
+// neighbour swaps with DPP quad permutations
+__device__ __forceinline__ void quad_transpose(float (&x)[4], int lane) {
+    const bool b0 = lane & 1, b1 = lane & 2;
+#pragma unroll
+    for (int a = 0; a < 4; a += 2) { // pairs (0,1), (2,3) with the lane whose bit 0 differs
+        const float send = b0 ? x[a] : x[a + 1];
+        const float recv = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, send), 0xB1, 0xF, 0xF, true));
+        if (b0) x[a] = recv; else x[a + 1] = recv;
+    }
+#pragma unroll
+    for (int a = 0; a < 2; ++a) { // pairs (0,2), (1,3) with the lane whose bit 1 differs
+        const float send = b1 ? x[a] : x[a + 2];
+        const float recv = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, send), 0x4E, 0xF, 0xF, true));
+        if (b1) x[a] = recv; else x[a + 2] = recv;
+    }
+}
+
 // ------------------------------------------------------------------------------------------------
-// U[t][j*b + p] = sum_q B^j[p][q] X[t][j*b + q].   One wave: 32 tokens x the b columns of block j.
-// MFMA rows = tokens (operand from X: 8 consecutive q per lane), columns = p (operand from B^j:
-// 8 consecutive q of row p per lane); a lane of the result holds one column p.  U is written in the
-// stage-major layout described at the top: [column / 64][token][128 B], 16-byte parts permuted.
+// U[t][j*b + p] = sum_q B^j[p][q] X[t][j*b + q].   Workgroup: block j x 256 tokens (4 waves x 64).
+// MFMA rows = tokens (operand from X: 8 consecutive q per lane, straight from global memory),
+// columns = p (operand from B^j, staged once per workgroup in LDS).  A lane of the result holds
+// one column p of 16 token rows; a transpose inside each quad of lanes turns that into 4
+// consecutive columns of one row, stored as 8 bytes.  U is written in the stage-major layout
+// described at the top: [column / 64][token][128 B], 16-byte parts permuted.
 // ------------------------------------------------------------------------------------------------
 template <int B>
 __global__ __launch_bounds__(256) void apply_pre_kernel(const uint16_t *__restrict__ X, int64_t n, int64_t d_in,
                                                         const uint16_t *__restrict__ Bw, uint8_t *__restrict__ U,
                                                         int64_t n_pad) {
-    constexpr int PT = B / 32; // column tiles
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, l32 = lane & 31, half = lane >> 5;
+    constexpr int PT = B / 32, KS = B / 16; // column tiles, k steps
+    constexpr int PITCH = B * 2 + 16;       // LDS bytes per row of B^j
+    __shared__ __attribute__((aligned(16))) uint8_t lb[B * PITCH];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, l32 = lane & 31, half = lane >> 5;
     const int j = blockIdx.y;
-    const int64_t t0 = ((int64_t)blockIdx.x * 4 + w) * 32;
-    if (t0 >= n) return;
-    const int64_t trow = min(t0 + l32, n - 1); // clamped: rows past the end are computed and dropped
-    const uint16_t *xrow = X + trow * d_in + (int64_t)j * B + 8 * half;
-    const uint16_t *brow = Bw + (int64_t)j * B * B + (int64_t)l32 * B + 8 * half;
-    floatx16 acc[PT];
+    const int64_t t0 = (int64_t)blockIdx.x * 256 + w * 64;
+    // X operands of this wave first (the long latency), then B^j -> LDS underneath
+    uint4 xa[2][KS];
 #pragma unroll
-    for (int pt = 0; pt < PT; ++pt)
+    for (int rt = 0; rt < 2; ++rt) {
+        const int64_t trow = min(t0 + 32 * rt + l32, n - 1); // clamped: rows past the end are computed and dropped
+        const uint16_t *xrow = X + trow * d_in + (int64_t)j * B + 8 * half;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[pt][r] = 0.f;
+        for (int ks = 0; ks < KS; ++ks) xa[rt][ks] = *reinterpret_cast<const uint4 *>(xrow + 16 * ks);
+    }
+    {
+        const uint16_t *bj = Bw + (int64_t)j * B * B;
+        constexpr int CH = B * B / 8; // 16-byte chunks
 #pragma unroll
-    for (int ks = 0; ks < B / 16; ++ks) {
-        const bf16x8 a = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(xrow + 16 * ks));
-#pragma unroll
-        for (int pt = 0; pt < PT; ++pt) {
-            const bf16x8 bb = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(brow + (int64_t)pt * 32 * B + 16 * ks));
-            acc[pt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bb, acc[pt], 0, 0, 0);
+        for (int c = tid; c < CH; c += 256) {
+            const int row = c / (B / 8), part = c % (B / 8);
+            *reinterpret_cast<uint4 *>(lb + row * PITCH + part * 16) = *reinterpret_cast<const uint4 *>(bj + row * B + part * 8);
         }
     }
+    __syncthreads();
+    floatx16 acc[2][PT];
 #pragma unroll
-    for (int pt = 0; pt < PT; ++pt)
+    for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int64_t t = t0 + 8 * (r >> 2) + 4 * half + (r & 3);
-            const int64_t col = (int64_t)j * B + pt * 32 + l32;
-            const int within = (int)(col & 63), slot = (within >> 3) ^ key_acts((int)(t & 255));
-            if (t < n)
-                *reinterpret_cast<uint16_t *>(U + ((col >> 6) * n_pad + t) * 128 + slot * 16 + (within & 7) * 2) =
-                    (uint16_t)(pack_bf16x2_rne(acc[pt][r], 0.f) & 0xffffu);
+        for (int pt = 0; pt < PT; ++pt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[rt][pt][r] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+        for (int pt = 0; pt < PT; ++pt) {
+            const bf16x8 bb = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(lb + (pt * 32 + l32) * PITCH + (16 * ks + 8 * half) * 2));
+#pragma unroll
+            for (int rt = 0; rt < 2; ++rt)
+                acc[rt][pt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, xa[rt][ks]), bb, acc[rt][pt], 0, 0, 0);
         }
+    }
+    const int q4 = lane & 3; // after the transpose this lane holds row (4g + q4) of each group of 4 rows
+#pragma unroll
+    for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+        for (int pt = 0; pt < PT; ++pt)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                float x[4] = {acc[rt][pt][4 * g], acc[rt][pt][4 * g + 1], acc[rt][pt][4 * g + 2], acc[rt][pt][4 * g + 3]};
+                quad_transpose(x, lane);
+                const int64_t t = t0 + 32 * rt + 8 * g + 4 * half + q4;
+                const int64_t col = (int64_t)j * B + pt * 32 + (l32 & ~3); // first of the 4 columns
+                const int within = (int)(col & 63), slot = (within >> 3) ^ key_acts((int)(t & 255));
+                uint2 pk;
+                pk.x = pack_bf16x2_rne(x[0], x[1]);
+                pk.y = pack_bf16x2_rne(x[2], x[3]);
+                if (t < n) *reinterpret_cast<uint2 *>(U + ((col >> 6) * n_pad + t) * 128 + slot * 16 + (within & 7) * 2) = pk;
+            }
 }
 
 void launch_apply_pre(const void *X, int64_t n, int64_t d_in, int b, const void *Bw, void *U, hipStream_t s) {
-    dim3 grid((unsigned)((n + 127) / 128), (unsigned)(d_in / b));
+    dim3 grid((unsigned)((n + 255) / 256), (unsigned)(d_in / b));
     const uint16_t *x = reinterpret_cast<const uint16_t *>(X), *bw = reinterpret_cast<const uint16_t *>(Bw);
     uint8_t *u = reinterpret_cast<uint8_t *>(U);
     const int64_t n_pad = pad256(n);
