@@ -221,7 +221,7 @@ def run_apply_workload(args, armor, synth, torch, dev):
     if not args.no_cpu_baseline:
         import oracle
         oracle.build()
-        sample = 16
+        sample = 512 if d_out * d_in > 1 << 24 else 2048   # about 10-20 s of single-thread oracle time
         ev = vals[:, :].float().cpu().numpy()
         idx = armor.unpack_meta(meta.cpu().numpy(), d_in, 2, 4)
         c0 = time.perf_counter()
