@@ -218,6 +218,212 @@ __global__ __launch_bounds__(512) void gram_bf16_kernel(const uint16_t *__restri
             }
 }
 
+// ------------------------------------------------------------------------------------------------
+// The same product with the gfx950 data path: token-major tiles go from global memory straight
+// into LDS (global_load_lds_dwordx4: 16 B per lane, 1 KB = two 512-byte token rows per
+// instruction, no register staging, no shuffles), four LDS slots of 32 tokens, up to three stages
+// in flight; the matrix-core operands (8 consecutive tokens of one channel per lane) are read with
+// the transposing LDS load ds_read_b64_tr_b16: inside each group of 16 lanes, lane j supplies 8
+// bytes and lane i receives element i % 4 of the data of lanes i/4, 4 + i/4, 8 + i/4, 12 + i/4.
+// Lane j therefore points at token row j/4 and channels 4 (j % 4) .. +3 of a 16-channel group, and
+// lane i receives channel i at four consecutive tokens.  LDS rows are unpadded (512 B); the 64-byte
+// segments of row r are stored at segment s ^ (r & 3) (applied to the global address of the loading
+// lane), so the four rows a half-wave reads together fall on distinct banks.
+// Rows past the end of the slice are read from a page of zeros.
+// ------------------------------------------------------------------------------------------------
+__device__ __attribute__((aligned(16))) uint4 g_gram_zero_row[32]; // 512 zero bytes
+
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef short short8v __attribute__((ext_vector_type(8)));
+typedef __attribute__((address_space(3))) short4v *lds_short4_ptr;
+typedef __attribute__((address_space(3))) void *lds_void_ptr;
+
+__device__ __forceinline__ void gram_dma16(const void *g, uint32_t lds_byte_addr) {
+    // issued as assembly so that the compiler keeps no book on these loads: completion is waited for
+    // explicitly (s_waitcnt vmcnt) before the barrier that publishes a stage
+    asm volatile("s_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "{m0}"(lds_byte_addr) : "memory");
+}
+
+#define GRAM_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0f70 | ((n) & 15) | (((n) >> 4) << 14))
+
+constexpr int GD_T = 256, GD_K = 32, GD_SLOTS = 4; // (a fifth slot, all of the LDS, measured slower)
+constexpr int GD_TILE_BYTES = GD_K * GD_T * 2; // 16 KB: 32 token rows of 256 channels
+constexpr int GD_SLOT_BYTES = 2 * GD_TILE_BYTES;
+
+// Tile pairs (ta <= tb) in an order that keeps neighbours close: blocks of 4 row tiles x 8 column
+// tiles, row-major over the blocks, row-major inside.  32 consecutive pairs then touch about 12
+// channel blocks instead of 17 to 33.
+__device__ __forceinline__ void gram_pair_from_index(int idx, int ntile, int &ta, int &tb) {
+    for (int bi = 0; bi * 4 < ntile; ++bi)
+        for (int bj = (bi * 4) / 8; bj * 8 < ntile; ++bj) {
+            int cnt = 0;
+            for (int r = bi * 4; r < min(bi * 4 + 4, ntile); ++r) {
+                const int c_lo = max(bj * 8, r), c_hi = min(bj * 8 + 8, ntile);
+                cnt += max(0, c_hi - c_lo);
+            }
+            if (idx >= cnt) { idx -= cnt; continue; }
+            for (int r = bi * 4; r < min(bi * 4 + 4, ntile); ++r) {
+                const int c_lo = max(bj * 8, r), c_hi = min(bj * 8 + 8, ntile);
+                const int m = max(0, c_hi - c_lo);
+                if (idx < m) { ta = r; tb = c_lo + idx; return; }
+                idx -= m;
+            }
+        }
+    ta = tb = 0; // not reached for idx < ntile (ntile + 1) / 2
+}
+
+// Work item = (token slice, tile pair).  Workgroups go to the 8 XCDs round-robin (each XCD has its
+// own L2; all share the memory-side cache).  The pairs, in the order above, are cut into 8 runs of
+// `cl`, one per XCD, and an XCD works on its run for `gs` slices at a time (gs * cl >= 32 resident
+// workgroups): the workgroups resident on one XCD share tokens and neighbouring tiles (L2), and at
+// any time the whole chip works on the same gs slices, so a row of X is fetched from HBM about once
+// and found in the memory-side cache by the other XCDs that need it.
+__global__ __launch_bounds__(512) void gram_bf16_dma_kernel(const uint16_t *__restrict__ X, int64_t ldx, int ntile,
+                                                            float *__restrict__ H, int64_t ldh, int accumulate,
+                                                            int64_t n_tokens, int64_t slice_len,
+                                                            float *__restrict__ part, int64_t d_in, int npairs,
+                                                            int nslices, int cl, int gs) {
+    constexpr int TM = 4, TN = 2;
+    const int xcd = (int)(blockIdx.x & 7), q = (int)(blockIdx.x >> 3);
+    const int grp = q / (gs * cl), in_grp = q % (gs * cl);
+    const int slice = grp * gs + in_grp / cl, pidx = xcd * cl + in_grp % cl;
+    if (slice >= nslices || pidx >= npairs) return; // uniform for the workgroup
+    const int64_t t_begin = (int64_t)slice * slice_len, t_end = min(n_tokens, t_begin + slice_len);
+    if (part != nullptr) {
+        H = part + (int64_t)slice * d_in * d_in;
+        ldh = d_in;
+        accumulate = 0;
+    }
+    __shared__ __attribute__((aligned(16))) uint8_t lds[GD_SLOTS * GD_SLOT_BYTES];
+    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, l32 = lane & 31, kh = lane >> 5;
+    int ta, tb;
+    gram_pair_from_index(pidx, ntile, ta, tb);
+    const bool diag = ta == tb;
+    const int wm = w & 1, wn = w >> 1, wm0 = wm * 128, wn0 = wn * 64;
+    const uint32_t lds0 = (uint32_t)(size_t)(lds_void_ptr)lds;
+
+    // loader role: per stage and operand this wave brings token rows 4w .. 4w+3 (two 1 KB loads);
+    // lane -> (row 2c + lane/32, stored segment (lane%32)/4, 16-byte part lane%4)
+    const int lrow = lane >> 5, lseg = (lane & 31) >> 2, lpart = lane & 3;
+    auto issue = [&](int64_t st) {
+        const uint32_t sb = lds0 + (uint32_t)(st % GD_SLOTS) * GD_SLOT_BYTES;
+#pragma unroll
+        for (int op = 0; op < 2; ++op) {
+            if (op == 1 && diag) break;
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+                const int r = 4 * w + 2 * c + lrow;                 // token row inside the stage
+                const int64_t tok = t_begin + st * GD_K + r;
+                const int sseg = lseg ^ (r & 3);                    // source segment stored at lseg
+                const uint8_t *src = tok < t_end
+                    ? reinterpret_cast<const uint8_t *>(X + tok * ldx + (int64_t)(op ? tb : ta) * GD_T) + sseg * 64 + lpart * 16
+                    : reinterpret_cast<const uint8_t *>(g_gram_zero_row) + (lane & 31) * 16;
+                gram_dma16(src, sb + op * GD_TILE_BYTES + (4 * w + 2 * c) * 512);
+            }
+        }
+    };
+
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int a = 0; a < TM; ++a)
+#pragma unroll
+        for (int c = 0; c < TN; ++c)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][c][r] = 0.f;
+
+    // reader offsets: lane j of a 16-lane group points at token row (8 kh + j/4) and channels
+    // 16 (l32/16) + 4 (j%4) .. +3 of the 32-channel segment of its accumulator tile
+    const int j16 = lane & 15, rq = j16 >> 2;
+    const int within = (16 * (l32 >> 4) + 4 * (j16 & 3)) * 2;
+    int a_off[TM], b_off[TN];
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) a_off[tm] = (8 * kh + rq) * 512 + (((4 * wm + tm) ^ rq) * 64) + within;
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) b_off[tn] = (8 * kh + rq) * 512 + (((2 * wn + tn) ^ rq) * 64) + within;
+
+    const int64_t nstages = (t_end - t_begin + GD_K - 1) / GD_K;
+    const int per = diag ? 2 : 4; // load instructions per wave per stage
+
+    // operand fragments of one 16-token step: 4 row tiles + 2 column tiles, two transposing reads each
+    struct Frags { short4v a[TM][2], b[TN][2]; };
+    auto read_frags = [&](Frags &f, int64_t st, int ks) {
+        const uint8_t *La = lds + (st % GD_SLOTS) * GD_SLOT_BYTES;
+        const uint8_t *Lb = La + (diag ? 0 : GD_TILE_BYTES);
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm) {
+            f.a[tm][0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(La + a_off[tm] + (16 * ks) * 512));
+            f.a[tm][1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(La + a_off[tm] + (16 * ks + 4) * 512));
+        }
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn) {
+            f.b[tn][0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(Lb + b_off[tn] + (16 * ks) * 512));
+            f.b[tn][1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(Lb + b_off[tn] + (16 * ks + 4) * 512));
+        }
+    };
+    auto mma = [&](const Frags &f) {
+        bf16x8 a[TM], b[TN];
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm)
+            a[tm] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(f.a[tm][0], f.a[tm][1], 0, 1, 2, 3, 4, 5, 6, 7));
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn)
+            b[tn] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(f.b[tn][0], f.b[tn][1], 0, 1, 2, 3, 4, 5, 6, 7));
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn)
+                acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[tm], b[tn], acc[tm][tn], 0, 0, 0);
+    };
+    // wait until this wave's loads of stage `st` have landed (at most the loads of `later` younger stages
+    // may still be outstanding), then meet the other waves
+    auto publish = [&](int later) {
+        if (later <= 0) { GRAM_WAIT_VMCNT(0); }
+        else if (per == 2) { if (later == 1) { GRAM_WAIT_VMCNT(2); } else if (later == 2) { GRAM_WAIT_VMCNT(4); } else { GRAM_WAIT_VMCNT(6); } }
+        else { if (later == 1) { GRAM_WAIT_VMCNT(4); } else if (later == 2) { GRAM_WAIT_VMCNT(8); } else { GRAM_WAIT_VMCNT(12); } }
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+    };
+
+    // Software pipeline over half-stages: the operand reads of a 16-token step are issued one step
+    // before its MFMAs, across stage boundaries too.  The barrier that publishes stage st+1 sits in
+    // the middle of stage st; after it every wave has finished stage st-1, whose slot then takes the
+    // loads of stage st + GD_SLOTS - 1.
+    static_assert(GD_K == 32, "two 16-token steps per stage");
+    Frags f0, f1;
+    if (nstages > 0) {
+        for (int64_t st = 0; st < GD_SLOTS - 1 && st < nstages; ++st) issue(st);
+        publish((int)min((int64_t)(GD_SLOTS - 2), nstages - 1));
+        read_frags(f0, 0, 0);
+    }
+    for (int64_t st = 0; st < nstages; ++st) {
+        read_frags(f1, st, 1);
+        mma(f0);
+        if (st + 1 < nstages) {
+            publish((int)min((int64_t)(GD_SLOTS - 3), nstages - 2 - st)); // stage st+1 landed; younger ones may be in flight
+            if (st + GD_SLOTS - 1 < nstages) issue(st + GD_SLOTS - 1);
+            read_frags(f0, st + 1, 0);
+        }
+        mma(f1);
+    }
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                int64_t row = (int64_t)ta * GD_T + wm0 + tm * 32 + (r >> 2) * 8 + kh * 4 + (r & 3);
+                int64_t col = (int64_t)tb * GD_T + wn0 + tn * 32 + l32;
+                float v = acc[tm][tn][r];
+                float *h = H + row * ldh + col;
+                *h = accumulate ? *h + v : v;
+                if (!diag && part == nullptr) {
+                    float *hm = H + col * ldh + row;
+                    *hm = accumulate ? *hm + v : v;
+                }
+            }
+}
+
 // H (+)= sum over slices, in slice order, of the upper-triangular tiles in part[]; mirror tiles are
 // written through an LDS transpose so both stores are row-contiguous.  One workgroup per 32 x 32
 // sub-block: blockIdx.x = tile pair, blockIdx.y = sub-block inside the 256 x 256 tile.
@@ -286,8 +492,16 @@ void launch_gram(const void *X, int bf16, int64_t n, int64_t d_in, int64_t ldx, 
         int S = ws ? gram_slices(n, d_in, ws_bytes) : 1;
         int64_t len = S > 1 ? ((n + S - 1) / S + 63) / 64 * 64 : n;
         float *part = S > 1 ? reinterpret_cast<float *>(ws) : nullptr;
-        hipLaunchKernelGGL(gram_bf16_kernel, dim3((unsigned)pairs, (unsigned)S), dim3(512), 0, s,
-                           reinterpret_cast<const uint16_t *>(X), ldx, nt, H, ldh, accumulate, n, len, part, d_in);
+        if ((reinterpret_cast<uintptr_t>(X) & 15) == 0) { // the LDS-direct loads want 16-byte aligned rows
+            const int cl = (pairs + 7) / 8, gs = std::min(S, std::max(1, (32 + cl - 1) / cl));
+            const int per_xcd = ((S + gs - 1) / gs) * gs * cl;
+            hipLaunchKernelGGL(gram_bf16_dma_kernel, dim3((unsigned)(per_xcd * 8)), dim3(512), 0, s,
+                               reinterpret_cast<const uint16_t *>(X), ldx, nt, H, ldh, accumulate, n, len, part, d_in,
+                               pairs, S, cl, gs);
+        }
+        else
+            hipLaunchKernelGGL(gram_bf16_kernel, dim3((unsigned)pairs, (unsigned)S), dim3(512), 0, s,
+                               reinterpret_cast<const uint16_t *>(X), ldx, nt, H, ldh, accumulate, n, len, part, d_in);
         if (S > 1)
             hipLaunchKernelGGL(gram_reduce_kernel, dim3((unsigned)pairs, 64), dim3(256), 0, s, part, S, d_in, nt, H, ldh,
                                accumulate);
