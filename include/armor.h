@@ -86,7 +86,8 @@ int armor_last_hip_error(void);
 #define ARMOR_PROF_SMALL 10    /* wrapper updates, wrapper Grams, step-size scalars */
 #define ARMOR_PROF_APPLY_PRE 11  /* armor_apply_packed: U = X B^T */
 #define ARMOR_PROF_APPLY_MAIN 12 /* armor_apply_packed: Y = (U S^T) A^T */
-#define ARMOR_PROF_KINDS 13
+#define ARMOR_PROF_DIAG_X 13     /* armor_gram_diag_x */
+#define ARMOR_PROF_KINDS 14
 armor_status armor_profile_enable(int on);
 armor_status armor_profile_read(double *ms_total /*host [ARMOR_PROF_KINDS]*/, int64_t *launches /*host*/);
 
@@ -108,6 +109,17 @@ armor_status armor_gram(const void *X, armor_dtype x_dtype, int64_t n_tokens, in
 
 /* D[j] = H[j][j]  (the weights ||X_j||^2 of Eq. 2). */
 armor_status armor_gram_diag(const float *H, int64_t d_in, int64_t ldh, float *D, void *hip_stream);
+
+/*
+ * The same weights straight from the activations, without forming H (Eq. 2 only uses diag(X X^T)):
+ *   D[j] (+)= sum_t X[t][j]^2        X [n_tokens][d_in] row-major with row pitch ldx, fp32 or bf16.
+ * accumulate as in armor_gram.  d_in must be a multiple of 8 (bf16) / 4 (fp32), X 16-byte aligned and
+ * ldx a multiple of the same count; ws of armor_gram_diag_x_workspace_bytes() bytes is required.
+ * One pass over X: 2 (bf16) or 4 bytes per element, HBM-bound.
+ */
+size_t armor_gram_diag_x_workspace_bytes(int64_t n_tokens, int64_t d_in);
+armor_status armor_gram_diag_x(const void *X, armor_dtype x_dtype, int64_t n_tokens, int64_t d_in, int64_t ldx,
+                               float *D, int accumulate, void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
  * Row/column normalisation of Sec. 3.2:  r1[j] = ||W[:,j]||,  r2[i] = ||W[i,:]/r1||,

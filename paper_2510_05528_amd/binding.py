@@ -10,10 +10,11 @@ _LIB_PATH = os.path.join(_HERE, "libarmor.so")
 ARMOR_F32, ARMOR_BF16 = 0, 1
 
 PROF_KINDS = ["gram", "phase_A", "phase_B", "phase_WS", "sparse_step", "phase_FB", "phase_GS", "normalize", "init",
-              "pack_nm", "small_kernels", "apply_pre", "apply_main"]
+              "pack_nm", "small_kernels", "apply_pre", "apply_main", "gram_diag_x"]
 
 EXPORTED = ["armor_status_string", "armor_last_hip_error", "armor_profile_enable", "armor_profile_read",
             "armor_gram_workspace_bytes", "armor_gram", "armor_gram_diag",
+            "armor_gram_diag_x_workspace_bytes", "armor_gram_diag_x",
             "armor_normalize_workspace_bytes", "armor_normalize", "armor_proxy_loss_workspace_bytes",
             "armor_proxy_loss", "armor_factorize_workspace_bytes", "armor_factorize_layer", "armor_pack_nm",
             "armor_pack_meta_row_bytes", "armor_to_bf16", "armor_apply_prepared_bytes", "armor_apply_prepare",
@@ -52,6 +53,9 @@ def load_library():
     lib.armor_gram_workspace_bytes.argtypes = [_i64, _i64, _int]
     lib.armor_gram.argtypes = [_vp, _int, _i64, _i64, _i64, _vp, _i64, _int, _vp, _sz, _vp]
     lib.armor_gram_diag.argtypes = [_vp, _i64, _i64, _vp, _vp]
+    lib.armor_gram_diag_x_workspace_bytes.restype = _sz
+    lib.armor_gram_diag_x_workspace_bytes.argtypes = [_i64, _i64]
+    lib.armor_gram_diag_x.argtypes = [_vp, _int, _i64, _i64, _i64, _vp, _int, _vp, _sz, _vp]
     lib.armor_normalize_workspace_bytes.restype = _sz
     lib.armor_normalize_workspace_bytes.argtypes = [_i64, _i64]
     lib.armor_normalize.argtypes = [_vp, _int, _i64, _i64, _vp, _vp, _vp, _vp, _sz, _vp]
@@ -158,6 +162,22 @@ def gram_diag(H):
     _dev_f32(H, "H")
     D = torch.empty(H.shape[0], device=H.device, dtype=torch.float32)
     _check(lib.armor_gram_diag(_ptr(H), H.shape[0], H.stride(0), _ptr(D), _stream()))
+    return D
+
+
+def gram_diag_x(X, D=None, accumulate=False, ws=None):
+    """D[j] (+)= sum_t X[t][j]^2 straight from the activations (armor_gram_diag_x)."""
+    torch = _torch()
+    lib = load_library()
+    if not (X.is_cuda and X.dim() == 2 and (X.numel() == 0 or X.stride(1) == 1)):
+        raise ArmorError("X must be a 2-D device tensor with unit column stride")
+    n, d_in = X.shape
+    if D is None:
+        D = torch.zeros(d_in, device=X.device, dtype=torch.float32)
+    if ws is None:
+        ws = torch.empty(int(lib.armor_gram_diag_x_workspace_bytes(n, d_in)), device=X.device, dtype=torch.uint8)
+    _check(lib.armor_gram_diag_x(_ptr(X), _dtype_code(X), n, d_in, X.stride(0) if n > 0 else d_in, _ptr(D), 1 if accumulate else 0, _ptr(ws),
+                                 ws.numel(), _stream()))
     return D
 
 

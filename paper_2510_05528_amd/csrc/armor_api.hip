@@ -256,6 +256,27 @@ armor_status armor_gram_diag(const float *H, int64_t d_in, int64_t ldh, float *D
     return check_hip();
 }
 
+size_t armor_gram_diag_x_workspace_bytes(int64_t n_tokens, int64_t d_in) {
+    if (n_tokens < 0 || d_in <= 0) return 0;
+    return (size_t)diag_x_chunks(n_tokens) * (size_t)d_in * sizeof(float) + 256;
+}
+
+armor_status armor_gram_diag_x(const void *X, armor_dtype x_dtype, int64_t n_tokens, int64_t d_in, int64_t ldx,
+                               float *D, int accumulate, void *ws, size_t ws_bytes, void *hip_stream) {
+    if (!D || (!X && n_tokens != 0)) return ARMOR_ERR_NULL; // an empty batch may come with a null X
+    if (x_dtype != ARMOR_F32 && x_dtype != ARMOR_BF16) return ARMOR_ERR_DTYPE;
+    const int vec = x_dtype == ARMOR_BF16 ? 8 : 4;
+    if (d_in <= 0 || n_tokens < 0 || ldx < d_in || d_in % vec != 0 || ldx % vec != 0) return ARMOR_ERR_SHAPE;
+    if (!ws || ws_bytes < armor_gram_diag_x_workspace_bytes(n_tokens, d_in)) return ARMOR_ERR_WORKSPACE;
+    if ((X && !aligned16(X)) || !aligned16(ws)) return ARMOR_ERR_ALIGN;
+    hipStream_t s = (hipStream_t)hip_stream;
+    {
+        ProfScope ps(ARMOR_PROF_DIAG_X, s);
+        launch_diag_x(X, x_dtype == ARMOR_BF16, n_tokens, d_in, ldx, D, accumulate, reinterpret_cast<float *>(ws), s);
+    }
+    return check_hip();
+}
+
 size_t armor_normalize_workspace_bytes(int64_t d_out, int64_t d_in) {
     if (d_out <= 0 || d_in <= 0) return 0;
     return ((size_t)colnorm_chunks(d_out) + 1) * (size_t)d_in * sizeof(float) + 256;

@@ -64,6 +64,9 @@ void launch_colnorm(const void *W, int bf16, int64_t d_out, int64_t d_in, float 
                     hipStream_t s);
 void launch_rownorm_scale(const void *W, int bf16, int64_t d_out, int64_t d_in, const float *r1_inv, float *r2,
                           float *Wbar, hipStream_t s);
+int diag_x_chunks(int64_t n);
+void launch_diag_x(const void *X, int bf16, int64_t n, int64_t d_in, int64_t ldx, float *D, int accumulate,
+                   float *partial, hipStream_t s);
 void launch_init_identity(float *A, int nblk, int b, hipStream_t s);
 void launch_init_nm(const float *Wbar, const float *D, int64_t d_out, int64_t d_in, int N, int M, float *C,
                     uint8_t *mask, hipStream_t s);

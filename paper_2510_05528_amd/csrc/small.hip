@@ -294,6 +294,73 @@ void launch_diag(const float *H, int64_t d_in, int64_t ldh, float *D, hipStream_
 }
 
 // ------------------------------------------------------------------------------------------------
+// The weights of Eq. 2 straight from the activations: D[j] (+)= sum_t X[t][j]^2, without forming H.
+// This is all the method itself needs of the calibration data (2 n d_in bytes, HBM-bound).
+// Chunk c of `rows_per_chunk` tokens -> partial[c][j] in fp32 (64 column threads x 4 row lanes per
+// workgroup, as for the column norms), then a fixed-order fp64 sum over the chunks.
+// ------------------------------------------------------------------------------------------------
+template <bool BF16>
+__global__ __launch_bounds__(256) void diag_x_partial_kernel(const void *__restrict__ X, int64_t n, int64_t d_in,
+                                                             int64_t ldx, int64_t rows_per_chunk,
+                                                             float *__restrict__ partial) {
+    constexpr int VEC = WVec<BF16>::VEC;
+    __shared__ float red[3][64][VEC + 1];
+    const int cx = threadIdx.x & 63, ry = threadIdx.x >> 6;
+    const int64_t j = ((int64_t)blockIdx.x * 64 + cx) * VEC;
+    const int64_t c = blockIdx.y, r0 = c * rows_per_chunk, r1 = min(n, r0 + rows_per_chunk);
+    float s[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) s[e] = 0.f;
+    if (j < d_in) {
+#pragma unroll 8
+        for (int64_t i = r0 + ry; i < r1; i += 4) {
+            WVec<BF16> w;
+            w.load(X, i * ldx + j);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) s[e] += w.v[e] * w.v[e];
+        }
+    }
+    if (ry > 0) {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) red[ry - 1][cx][e] = s[e];
+    }
+    __syncthreads();
+    if (ry == 0 && j < d_in) {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e)
+            partial[c * d_in + j + e] = (s[e] + red[0][cx][e]) + (red[1][cx][e] + red[2][cx][e]);
+    }
+}
+
+__global__ __launch_bounds__(64) void diag_x_final_kernel(const float *__restrict__ partial, int64_t d_in, int nchunk,
+                                                          float *__restrict__ D, int accumulate) {
+    int64_t j = (int64_t)blockIdx.x * 64 + threadIdx.x;
+    if (j >= d_in) return;
+    double s = accumulate ? (double)D[j] : 0.0;
+    for (int c0 = 0; c0 < nchunk; c0 += 8) {
+        float p[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) p[u] = c0 + u < nchunk ? partial[(int64_t)(c0 + u) * d_in + j] : 0.f;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += (double)p[u];
+    }
+    D[j] = (float)s;
+}
+
+int diag_x_chunks(int64_t n) { return (int)std::max<int64_t>(1, std::min<int64_t>(2048, (n + 255) / 256)); }
+
+void launch_diag_x(const void *X, int bf16, int64_t n, int64_t d_in, int64_t ldx, float *D, int accumulate,
+                   float *partial, hipStream_t s) {
+    const int nchunk = diag_x_chunks(n), vec = bf16 ? 8 : 4;
+    const int64_t rows_per_chunk = (n + nchunk - 1) / nchunk;
+    dim3 grid((unsigned)((d_in / vec + 63) / 64), (unsigned)nchunk);
+    if (bf16) hipLaunchKernelGGL(diag_x_partial_kernel<true>, grid, dim3(256), 0, s, X, n, d_in, ldx, rows_per_chunk, partial);
+    else      hipLaunchKernelGGL(diag_x_partial_kernel<false>, grid, dim3(256), 0, s, X, n, d_in, ldx, rows_per_chunk, partial);
+    hipLaunchKernelGGL(diag_x_final_kernel, dim3((unsigned)((d_in + 63) / 64)), dim3(64), 0, s, partial, d_in, nchunk, D,
+                       accumulate);
+}
+
+// ------------------------------------------------------------------------------------------------
 // wrapper update (Alg. 2):  X^(k) <- X^(k) - grad^(k) / beta,  beta = 2 * sum of the per-block
 // summands of Eq. 9 / Eq. 10, grad^(k) = sum of the nsplit partials the chain kernel left.
 // A zero beta leaves X unchanged.  Workgroup (k, q) updates 256 entries of block k, one per thread; every workgroup re-derives beta in the same fixed order.  Workgroup (0,0) also writes the loss of the previous
@@ -437,7 +504,8 @@ __device__ __forceinline__ float hash_uniform(uint64_t seed, uint64_t ctr) {
 }
 
 // w = G^+ q for a symmetric PSD N x N matrix (Moore-Penrose, eigenvalues <= 1e-12 * max dropped),
-// returns q^T G^+ q.  Cyclic Jacobi, fully unrolled so everything stays in registers.
+// returns q^T G^+ q.  N = 2: closed form; N >= 3: triangular solves when G is provably far from the drop
+// threshold, else cyclic Jacobi; fully unrolled so everything stays in registers.
 template <int N> __device__ double pinv_solve(double (&G)[N][N], const double (&q)[N], double (&w)[N]) {
     if (N == 1) {
         w[0] = G[0][0] > 0.0 ? q[0] / G[0][0] : 0.0;
@@ -468,6 +536,60 @@ template <int N> __device__ double pinv_solve(double (&G)[N][N], const double (&
                 gain += proj * pl;
             }
         return gain;
+    }
+    {
+        // Fast path.  With pivots d_k of G = L D L^T and rho_k = d_k / G_kk (the pivots of the unit-
+        // diagonal scaling G' of G):  lambda_min(G) >= lambda_min(G') min_k G_kk,  lambda_min(G') >=
+        // det G' / lambda_max(G')^(N-1) >= prod rho_k / N^(N-1),  lambda_max(G) <= trace G.  If that
+        // lower bound on lambda_min / lambda_max clears the drop threshold with a factor 10 to spare,
+        // no eigenvalue is dropped, G^+ = G^-1, and the triangular solves give the same w (to
+        // rounding) without the eigen-decomposition.
+        double L[N][N], d[N], dmin = G[0][0], tr = 0.0, rho = 1.0, nn = 1.0;
+        bool ok = true;
+#pragma unroll
+        for (int k = 0; k < N; ++k) {
+            dmin = fmin(dmin, G[k][k]);
+            tr += G[k][k];
+            if (k > 0) nn *= (double)N;
+        }
+#pragma unroll
+        for (int k = 0; k < N; ++k) {
+            double dk = G[k][k];
+#pragma unroll
+            for (int m = 0; m < k; ++m) dk -= L[k][m] * L[k][m] * d[m];
+            d[k] = dk;
+            ok = ok && dk > 0.0 && G[k][k] > 0.0;
+            const double inv = ok ? 1.0 / dk : 0.0;
+            rho *= ok ? dk / G[k][k] : 0.0;
+#pragma unroll
+            for (int r = k + 1; r < N; ++r) {
+                double v = G[r][k];
+#pragma unroll
+                for (int m = 0; m < k; ++m) v -= L[r][m] * L[k][m] * d[m];
+                L[r][k] = v * inv;
+            }
+        }
+        if (ok && rho * dmin >= 1e-11 * nn * tr) {
+            double y[N];
+#pragma unroll
+            for (int k = 0; k < N; ++k) { // L y = q
+                double v = q[k];
+#pragma unroll
+                for (int m = 0; m < k; ++m) v -= L[k][m] * y[m];
+                y[k] = v;
+            }
+#pragma unroll
+            for (int k = N - 1; k >= 0; --k) { // L^T w = D^-1 y
+                double v = y[k] / d[k];
+#pragma unroll
+                for (int m = k + 1; m < N; ++m) v -= L[m][k] * w[m];
+                w[k] = v;
+            }
+            double gain = 0.0;
+#pragma unroll
+            for (int k = 0; k < N; ++k) gain += q[k] * w[k];
+            return gain;
+        }
     }
     double V[N][N];
 #pragma unroll

@@ -74,6 +74,26 @@ def test_gram(armor, torch, orc, n, d_in, bf16):
     np.testing.assert_array_equal(D, np.diag(got))
 
 
+@pytest.mark.parametrize("n,d_in,bf16", [(512, 256, False), (70, 96, False), (333, 384, True), (1, 64, True), (9000, 512, True),
+                                         (0, 64, True)])
+def test_gram_diag_x(armor, torch, orc, n, d_in, bf16):
+    """The weights of Eq. 2 straight from X: against the oracle's Gram diagonal, and accumulation."""
+    say("gram_diag_x", n, d_in, bf16)
+    X = synth.make_calibration(max(n, 1), d_in, seed=4)[:n]
+    if bf16:
+        bits = synth.to_bf16_bits(X)
+        Xd = dev(torch, bits.view(np.int16)).view(torch.bfloat16)
+        Xh = synth.bf16_bits_to_f32(bits)
+    else:
+        Xd, Xh = dev(torch, X), X
+    D = armor.gram_diag_x(Xd)
+    idx = np.arange(d_in, dtype=np.int64)
+    ref = orc.gram_entries(Xh, idx, idx) if n > 0 else np.zeros(d_in)
+    np.testing.assert_allclose(D.cpu().numpy(), ref, rtol=3e-6, atol=1e-30)
+    D2 = armor.gram_diag_x(Xd, D=D.clone(), accumulate=True)
+    np.testing.assert_allclose(D2.cpu().numpy(), 2 * ref, rtol=3e-6, atol=1e-30)
+
+
 @pytest.mark.parametrize("d_out,d_in,bf16", [(256, 256, False), (96, 160, False), (384, 640, True)])
 def test_normalize(armor, torch, orc, d_out, d_in, bf16):
     say("normalize", d_out, d_in, bf16)
