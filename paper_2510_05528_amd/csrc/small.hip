@@ -296,67 +296,79 @@ void launch_diag(const float *H, int64_t d_in, int64_t ldh, float *D, hipStream_
 // ------------------------------------------------------------------------------------------------
 // The weights of Eq. 2 straight from the activations: D[j] (+)= sum_t X[t][j]^2, without forming H.
 // This is all the method itself needs of the calibration data (2 n d_in bytes, HBM-bound).
-// Chunk c of `rows_per_chunk` tokens -> partial[c][j] in fp32 (64 column threads x 4 row lanes per
-// workgroup, as for the column norms), then a fixed-order fp64 sum over the chunks.
+// Chunk c of `rows_per_chunk` tokens -> partial[c][j] in fp32, then a fixed-order fp64 sum over the
+// chunks.
 // ------------------------------------------------------------------------------------------------
 template <bool BF16>
 __global__ __launch_bounds__(256) void diag_x_partial_kernel(const void *__restrict__ X, int64_t n, int64_t d_in,
                                                              int64_t ldx, int64_t rows_per_chunk,
                                                              float *__restrict__ partial) {
+    // a workgroup reads 256 x 16 consecutive bytes of one token row per load instruction and walks
+    // down the rows of its chunk, 8 rows in flight
     constexpr int VEC = WVec<BF16>::VEC;
-    __shared__ float red[3][64][VEC + 1];
-    const int cx = threadIdx.x & 63, ry = threadIdx.x >> 6;
-    const int64_t j = ((int64_t)blockIdx.x * 64 + cx) * VEC;
+    const int64_t j = ((int64_t)blockIdx.x * 256 + threadIdx.x) * VEC;
     const int64_t c = blockIdx.y, r0 = c * rows_per_chunk, r1 = min(n, r0 + rows_per_chunk);
+    if (j >= d_in) return;
     float s[VEC];
 #pragma unroll
     for (int e = 0; e < VEC; ++e) s[e] = 0.f;
-    if (j < d_in) {
-#pragma unroll 8
-        for (int64_t i = r0 + ry; i < r1; i += 4) {
-            WVec<BF16> w;
-            w.load(X, i * ldx + j);
+    int64_t i = r0;
+    for (; i + 8 <= r1; i += 8) {
+        WVec<BF16> w[8];
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) s[e] += w.v[e] * w.v[e];
+        for (int u = 0; u < 8; ++u) w[u].load(X, (i + u) * ldx + j);
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) s[e] += w[u].v[e] * w[u].v[e];
+    }
+    for (; i < r1; ++i) {
+        WVec<BF16> w;
+        w.load(X, i * ldx + j);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) s[e] += w.v[e] * w.v[e];
+    }
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) partial[c * d_in + j + e] = s[e];
+}
+
+// 64 columns x 16 chunk lanes per workgroup: lane y adds chunks y, y+16, ... in order (fp64), the 16
+// lane sums are then added in lane order
+__global__ __launch_bounds__(1024) void diag_x_final_kernel(const float *__restrict__ partial, int64_t d_in, int nchunk,
+                                                            float *__restrict__ D, int accumulate) {
+    __shared__ double red[16][64];
+    const int cx = threadIdx.x & 63, cy = threadIdx.x >> 6;
+    const int64_t j = (int64_t)blockIdx.x * 64 + cx;
+    double s = 0.0;
+    if (j < d_in) {
+        for (int c0 = cy; c0 < nchunk; c0 += 16 * 8) { // eight loads in flight
+            float p[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) p[u] = c0 + 16 * u < nchunk ? partial[(int64_t)(c0 + 16 * u) * d_in + j] : 0.f;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) s += (double)p[u];
         }
     }
-    if (ry > 0) {
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) red[ry - 1][cx][e] = s[e];
-    }
+    red[cy][cx] = s;
     __syncthreads();
-    if (ry == 0 && j < d_in) {
+    if (cy == 0 && j < d_in) {
+        double t = accumulate ? (double)D[j] : 0.0;
 #pragma unroll
-        for (int e = 0; e < VEC; ++e)
-            partial[c * d_in + j + e] = (s[e] + red[0][cx][e]) + (red[1][cx][e] + red[2][cx][e]);
+        for (int y = 0; y < 16; ++y) t += red[y][cx];
+        D[j] = (float)t;
     }
 }
 
-__global__ __launch_bounds__(64) void diag_x_final_kernel(const float *__restrict__ partial, int64_t d_in, int nchunk,
-                                                          float *__restrict__ D, int accumulate) {
-    int64_t j = (int64_t)blockIdx.x * 64 + threadIdx.x;
-    if (j >= d_in) return;
-    double s = accumulate ? (double)D[j] : 0.0;
-    for (int c0 = 0; c0 < nchunk; c0 += 8) {
-        float p[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) p[u] = c0 + u < nchunk ? partial[(int64_t)(c0 + u) * d_in + j] : 0.f;
-#pragma unroll
-        for (int u = 0; u < 8; ++u) s += (double)p[u];
-    }
-    D[j] = (float)s;
-}
-
-int diag_x_chunks(int64_t n) { return (int)std::max<int64_t>(1, std::min<int64_t>(2048, (n + 255) / 256)); }
+int diag_x_chunks(int64_t n) { return (int)std::max<int64_t>(1, std::min<int64_t>(2048, (n + 63) / 64)); }
 
 void launch_diag_x(const void *X, int bf16, int64_t n, int64_t d_in, int64_t ldx, float *D, int accumulate,
                    float *partial, hipStream_t s) {
     const int nchunk = diag_x_chunks(n), vec = bf16 ? 8 : 4;
     const int64_t rows_per_chunk = (n + nchunk - 1) / nchunk;
-    dim3 grid((unsigned)((d_in / vec + 63) / 64), (unsigned)nchunk);
+    dim3 grid((unsigned)((d_in / vec + 255) / 256), (unsigned)nchunk);
     if (bf16) hipLaunchKernelGGL(diag_x_partial_kernel<true>, grid, dim3(256), 0, s, X, n, d_in, ldx, rows_per_chunk, partial);
     else      hipLaunchKernelGGL(diag_x_partial_kernel<false>, grid, dim3(256), 0, s, X, n, d_in, ldx, rows_per_chunk, partial);
-    hipLaunchKernelGGL(diag_x_final_kernel, dim3((unsigned)((d_in + 63) / 64)), dim3(64), 0, s, partial, d_in, nchunk, D,
+    hipLaunchKernelGGL(diag_x_final_kernel, dim3((unsigned)((d_in + 63) / 64)), dim3(1024), 0, s, partial, d_in, nchunk, D,
                        accumulate);
 }
 
