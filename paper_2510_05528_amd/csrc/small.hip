@@ -102,24 +102,28 @@ __global__ __launch_bounds__(256) void colnorm_partial_scalar_kernel(const void 
     partial[(int64_t)c * d_in + j] = s;
 }
 
-// r1 (zero norms replaced by 1) and its reciprocal
-__global__ __launch_bounds__(64) void colnorm_final_kernel(const float *__restrict__ partial, int64_t d_in,
-                                                            int nchunk, float *__restrict__ r1,
-                                                            float *__restrict__ r1_inv) {
-    int64_t j = (int64_t)blockIdx.x * 64 + threadIdx.x;
-    if (j >= d_in) return;
+// r1 (zero norms replaced by 1) and its reciprocal.  64 columns x 16 chunk lanes per workgroup: lane y adds
+// chunks y, y+16, ... in order (fp64), the 16 lane sums are then added in lane order.
+__global__ __launch_bounds__(1024) void colnorm_final_kernel(const float *__restrict__ partial, int64_t d_in,
+                                                             int nchunk, float *__restrict__ r1,
+                                                             float *__restrict__ r1_inv) {
+    __shared__ double red[16][64];
+    const int cx = threadIdx.x & 63, cy = threadIdx.x >> 6;
+    const int64_t j = (int64_t)blockIdx.x * 64 + cx;
     double s = 0.0;
-    for (int c0 = 0; c0 < nchunk; c0 += 8) { // eight loads in flight, added in chunk order
-        float p[8];
+    if (j < d_in)
+        for (int c = cy; c < nchunk; c += 16) s += (double)partial[(int64_t)c * d_in + j];
+    red[cy][cx] = s;
+    __syncthreads();
+    if (cy == 0 && j < d_in) {
+        double t = 0.0;
 #pragma unroll
-        for (int u = 0; u < 8; ++u) p[u] = c0 + u < nchunk ? partial[(int64_t)(c0 + u) * d_in + j] : 0.f;
-#pragma unroll
-        for (int u = 0; u < 8; ++u) s += (double)p[u];
+        for (int y = 0; y < 16; ++y) t += red[y][cx];
+        float r = (float)sqrt(t);
+        r = r > 0.f ? r : 1.f;
+        r1[j] = r;
+        r1_inv[j] = 1.f / r;
     }
-    float r = (float)sqrt(s);
-    r = r > 0.f ? r : 1.f;
-    r1[j] = r;
-    r1_inv[j] = 1.f / r;
 }
 
 // One workgroup per row: W1 = W / r1, r2 = its row norm, Wbar = W1 / r2.  The first KEEP vectors of
@@ -213,7 +217,7 @@ void launch_colnorm(const void *W, int bf16, int64_t d_out, int64_t d_in, float 
         if (bf16) hipLaunchKernelGGL(colnorm_partial_scalar_kernel<true>, grid, dim3(256), 0, s, W, d_out, d_in, nchunk, partial);
         else      hipLaunchKernelGGL(colnorm_partial_scalar_kernel<false>, grid, dim3(256), 0, s, W, d_out, d_in, nchunk, partial);
     }
-    hipLaunchKernelGGL(colnorm_final_kernel, dim3((unsigned)((d_in + 63) / 64)), dim3(64), 0, s, partial, d_in,
+    hipLaunchKernelGGL(colnorm_final_kernel, dim3((unsigned)((d_in + 63) / 64)), dim3(1024), 0, s, partial, d_in,
                        nchunk, r1, r1_inv);
 }
 
@@ -359,7 +363,7 @@ __global__ __launch_bounds__(1024) void diag_x_final_kernel(const float *__restr
     }
 }
 
-int diag_x_chunks(int64_t n) { return (int)std::max<int64_t>(1, std::min<int64_t>(2048, (n + 63) / 64)); }
+int diag_x_chunks(int64_t n) { return (int)std::max<int64_t>(1, std::min<int64_t>(512, (n + 63) / 64)); }
 
 void launch_diag_x(const void *X, int bf16, int64_t n, int64_t d_in, int64_t ldx, float *D, int accumulate,
                    float *partial, hipStream_t s) {
