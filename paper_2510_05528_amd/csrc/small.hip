@@ -519,6 +519,25 @@ __device__ __forceinline__ float hash_uniform(uint64_t seed, uint64_t ctr) {
     return (float)((z >> 40) + 1ULL) * (1.0f / 16777216.0f);
 }
 
+// -ln(u) for u = m * 2^-24, m = (z >> 40) + 1, to about 2 ulp without the library logarithm.  The race
+// is decided by u near 1, where -ln(u) is small: there x = 1 - u is exact in fp32 and the series of
+// -ln(1 - x) is used (x < 1/16, 7 terms, truncation below 1e-9 relative); elsewhere the hardware log2
+// is accurate relative to a result that is at least 0.06.
+__device__ __forceinline__ float neg_log_uniform(uint64_t z) {
+    const uint32_t m = (uint32_t)(z >> 40) + 1u;
+    const float u = (float)m * (1.0f / 16777216.0f);
+    const float x = (float)(16777216u - m) * (1.0f / 16777216.0f);
+    float poly = fmaf(x, 1.0f / 7.0f, 1.0f / 6.0f);
+    poly = fmaf(x, poly, 0.2f);
+    poly = fmaf(x, poly, 0.25f);
+    poly = fmaf(x, poly, 1.0f / 3.0f);
+    poly = fmaf(x, poly, 0.5f);
+    poly = fmaf(x, poly, 1.0f);
+    poly *= x;
+    const float big = -0.69314718056f * __log2f(u);
+    return x < 0.0625f ? poly : big;
+}
+
 // w = G^+ q for a symmetric PSD N x N matrix (Moore-Penrose, eigenvalues <= 1e-12 * max dropped),
 // returns q^T G^+ q.  N = 2: closed form; N >= 3: triangular solves when G is provably far from the drop
 // threshold, else cyclic Jacobi; fully unrolled so everything stays in registers.
@@ -703,7 +722,11 @@ __global__ __launch_bounds__(256) void sparse_step_kernel(const float *__restric
     float best_key = INFINITY;
     int best_kap = 0x7fffffff;
     const float *Gij = G + (int64_t)i * b * d_in + (int64_t)j * b;
-    constexpr int U = 4; // groups per thread whose loads are in flight together
+    constexpr int U = 4; // groups per thread whose loads are in flight together (more in flight measured slower)
+    // counter hash input of this thread's first group; consecutive groups of a thread are 256 apart,
+    // so the 64-bit product by the odd constant is replaced by a running sum
+    constexpr uint64_t PHI = 0x9E3779B97F4A7C15ULL;
+    uint64_t zin = seed + PHI * ((uint64_t)(((int64_t)t * nblocks + blk) * gpb + tid) + 1ULL);
     for (int kap0 = tid; kap0 < gpb; kap0 += 256 * U) {
         float v[U][M];
 #pragma unroll
@@ -726,7 +749,9 @@ __global__ __launch_bounds__(256) void sparse_step_kernel(const float *__restric
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int kap = kap0 + u * 256;
-            if (kap >= gpb) break;
+            const uint64_t z = mix64(zin);
+            zin += PHI * 256ULL;
+            if (kap >= gpb) continue;
             float score;
             if (selection == 2) {
                 float a = 0.f;
@@ -741,13 +766,8 @@ __global__ __launch_bounds__(256) void sparse_step_kernel(const float *__restric
             }
             if (selection == 3) score = 1.f;
             float key;
-            if (selection == 1) {
-                key = -score;
-            } else {
-                uint64_t ctr = (uint64_t)(((int64_t)t * nblocks + blk) * gpb + kap) + 1ULL;
-                float u01 = hash_uniform(seed, ctr);
-                key = score > 0.f ? (-logf(u01)) / score : INFINITY; // accurate log: the race is decided by u near 1
-            }
+            if (selection == 1) key = -score;
+            else key = score > 0.f ? __fdividef(neg_log_uniform(z), score) : INFINITY;
             if (key < best_key) { best_key = key; best_kap = kap; }
         }
     }
