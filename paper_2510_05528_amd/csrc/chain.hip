@@ -113,15 +113,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_A_kernel(
         }
         if (!LOSS_ONLY) {
             CH::template mma<false, true, false>(gacc, sm.Y, sm.X, nullptr, p); // += (R D) S^T
-            acc.zero();
-            CH::template mma<false, true, false>(acc, sm.X, sm.X, nullptr, p); // S D S^T
-            float f2 = 0.f;
-#pragma unroll
-            for (int tm = 0; tm < CH::TM; ++tm)
-#pragma unroll
-                for (int tn = 0; tn < CH::TN; ++tn)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) f2 += acc.v[tm][tn][r] * acc.v[tm][tn][r];
+            const float f2 = CH::template sym_frob2<false>(sm.X, p, tid); // ||S D S^T||_F^2 (symmetric: upper tiles)
             float ftot = CH::block_sum(f2, sm.red, tid);
             if (tid == 0) beta_part[i * nbj + j] = sqrtf(ftot);
         }
@@ -207,14 +199,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_B_kernel(
         }
         CH::template mma<true, false, false>(gacc, sm.X, sm.Y, nullptr, p); // += S'^T (R D)
         acc.zero();
-        CH::template mma<true, false, false>(acc, sm.X, sm.X, nullptr, p); // S'^T S'
-        float f2 = 0.f;
-#pragma unroll
-        for (int tm = 0; tm < CH::TM; ++tm)
-#pragma unroll
-            for (int tn = 0; tn < CH::TN; ++tn)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) f2 += acc.v[tm][tn][r] * acc.v[tm][tn][r];
+        const float f2 = CH::template sym_frob2<true>(sm.X, p, tid); // ||S'^T S'||_F^2 (symmetric: upper tiles)
         float ftot = CH::block_sum(f2, sm.red, tid);
         if (tid == 0) beta_part[i * nbj + j] = sqrtf(ftot) * sqrtf(dn2);
         __syncthreads();

@@ -165,6 +165,59 @@ template <int B> struct Chain {
         }
     }
 
+    // Squared Frobenius norm of the symmetric product X X^T (XT = false; rows of the tile) or X^T X
+    // (XT = true), as this lane's share of the sum.  At b = 128 only the 10 upper-triangular 32 x 32
+    // tiles of the 4 x 4 grid are formed, off-diagonal ones counted twice; the two SIMDs that carry
+    // a two-tile wave and a one-tile wave set the time, 3 tile-products instead of the 4 every SIMD
+    // does for the full product.  Wave -> tiles: w0 (0,0)(0,1), w1 (1,1)(1,2), w2 (2,2), w3 (3,3),
+    // w4 (0,2), w5 (0,3), w6 (1,3), w7 (2,3).
+    template <bool XT> __device__ static float sym_frob2(const float *__restrict__ X, const Pos &p, int tid) {
+        if constexpr (B != 128) {
+            Acc acc;
+            acc.zero();
+            mma<XT, !XT, false>(acc, X, X, nullptr, p);
+            float f2 = 0.f;
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) f2 += acc.v[tm][tn][r] * acc.v[tm][tn][r];
+            return f2;
+        } else {
+            const int w = tid >> 6;
+            const int rt = w < 4 ? w : (w < 6 ? 0 : w - 5);
+            const int ct = w < 4 ? w : (w == 4 ? 2 : 3);
+            const bool two = w < 2;
+            const int ra = XT ? 32 * rt + p.l32 : (32 * rt + p.l32) * P;
+            const int cb = XT ? 32 * ct + p.l32 : (32 * ct + p.l32) * P;
+            const int cstep = XT ? 32 : 32 * P;     // to the next column tile
+            const int kstride = XT ? P : 1;         // one k step
+            const float *xa = X + ra + p.kh * kstride, *xb = X + cb + p.kh * kstride;
+            floatx16 a0, a1;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) { a0[r] = 0.f; a1[r] = 0.f; }
+            if (two) {
+#pragma unroll 8
+                for (int k = 0; k < B; k += 2) {
+                    const float fa = xa[k * kstride], fb0 = xb[k * kstride], fb1 = xb[k * kstride + cstep];
+                    a0 = __builtin_amdgcn_mfma_f32_32x32x2f32(fa, fb0, a0, 0, 0, 0);
+                    a1 = __builtin_amdgcn_mfma_f32_32x32x2f32(fa, fb1, a1, 0, 0, 0);
+                }
+            } else {
+#pragma unroll 8
+                for (int k = 0; k < B; k += 2) {
+                    const float fa = xa[k * kstride], fb0 = xb[k * kstride];
+                    a0 = __builtin_amdgcn_mfma_f32_32x32x2f32(fa, fb0, a0, 0, 0, 0);
+                }
+            }
+            float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) { s0 += a0[r] * a0[r]; s1 += a1[r] * a1[r]; }
+            return (rt == ct ? s0 : 2.f * s0) + 2.f * s1;
+        }
+    }
+
     // deterministic block-wide sum; result valid in thread 0.  red: NW floats of LDS.
     __device__ static float block_sum(float v, float *red, int tid) {
 #pragma unroll
