@@ -77,7 +77,10 @@ def chain_algorithmic_flops(kind, d_out, d_in, b, N, M):
         return sparse + unit + unit + 0.5 * unit
     if kind == "phase_GS":  # S' = A C (core operand), What, U, G
         return sparse + 3 * unit
-    # phase_WS: S' = A C (core operand), What, U, G, V = (G.M) K (N:M-sparse operand), Z = (A^T A) V
+    if kind == "phase_WS" and b <= 128:
+        # What, U, G, V = (G.M) K (N:M-sparse operand), Z = (A^T A) V; S' = A C comes from the B step
+        return 3 * unit + sparse + unit
+    # phase_WS at d_block 256: S' = A C (core operand) is formed here as well
     # phase_FB: S = C B (core operand), What, grad_A, T, C^T T (core operand), T B^T
     return sparse + 3 * unit + sparse + unit
 

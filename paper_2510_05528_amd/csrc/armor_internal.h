@@ -20,7 +20,7 @@ void launch_phase_A(const Dims &d, const float *Wbar, const float *C, const floa
                     bool loss_only, hipStream_t s);
 // B-phase: S' = A C, R = Wbar - S' B, partial grad_B, ||S'^T S'||_F ||D^j||_F.
 void launch_phase_B(const Dims &d, const float *Wbar, const float *C, const float *A, const float *B,
-                    const float *D, int nsplit, float *gpart, float *beta_part, hipStream_t s);
+                    const float *D, int nsplit, float *gpart, float *beta_part, float *Sp, hipStream_t s);
 // W' step of Alg. 2 alone (unstructured mode): C += (2/beta_W) (A^T ((Wbar - A C B) D) B^T) (.) M, beta_W
 // read from scalars[2].  grid_cap workgroups at most, each walking blocks w, w + grid, ...
 void launch_phase_W(const Dims &d, const float *Wbar, float *C, const float *A, const float *B, const float *D,
@@ -32,7 +32,7 @@ void launch_wrapper_grams(const Dims &d, const float *A, const float *B, const f
 // Gout = -2 (G - (2/beta_W) (A^T A)(G (.) M) K), block loss after the continuous step to loss_part.
 void launch_phase_WS(const Dims &d, const float *Wbar, float *C, const float *A, const float *B, const float *D,
                      const float *AtA, const float *K, const uint8_t *mask, int mask_group, const double *scalars,
-                     float *Gout, float *loss_part, int grid_cap, hipStream_t s);
+                     float *Gout, float *loss_part, const float *Sp, int grid_cap, hipStream_t s);
 int chain_max_nsplit();
 // Joint-Adam forward/backward pass: gradients of A (gApart, nsplit chunks per row block), B (gBpart,
 // one partial per block, laid out [j][i]) and the Adam update of the core and its moments in place.

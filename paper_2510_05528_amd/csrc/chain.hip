@@ -140,7 +140,7 @@ template <int B>
 __global__ __launch_bounds__(Chain<B>::NT) void phase_B_kernel(
     const float *__restrict__ Wbar, const float *__restrict__ C, const float *__restrict__ A,
     const float *__restrict__ Bw, const float *__restrict__ D, int64_t d_in, int nbi, int nbj, int nsplit,
-    float *__restrict__ gpart, float *__restrict__ beta_part) {
+    float *__restrict__ gpart, float *__restrict__ beta_part, float *__restrict__ Sp) {
     using CH = Chain<B>;
     __shared__ Smem<B> sm;
     const int tid = threadIdx.x;
@@ -171,6 +171,15 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_B_kernel(
         CH::template mma<false, false, false>(acc, sm.Y, sm.X, nullptr, p); // S' = A C
         __syncthreads();
         CH::store_acc(sm.X, acc, p);
+        if (Sp != nullptr) { // A and C do not change until the W' step: that step takes S' from here
+            float *Sij = Sp + (int64_t)i * B * d_in + (int64_t)j * B;
+#pragma unroll
+            for (int tm = 0; tm < CH::TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < CH::TN; ++tn)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) Sij[opaque(woff) + CH::Pos::unif_off(tm, tn, r, ldw)] = acc.v[tm][tn][r];
+        }
         CH::lstore_tile(sm.Y, t0, tid);
         float wb[CH::TM][CH::TN][16];
 #pragma unroll
@@ -339,34 +348,43 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_WS_kernel(
     const float *__restrict__ Bw, const float *__restrict__ D, const float *__restrict__ AtA,
     const float *__restrict__ K, const uint8_t *__restrict__ mask, int mask_group,
     const double *__restrict__ scalars, int64_t d_in, int nbj, int nblocks, float *__restrict__ Gout,
-    float *__restrict__ loss_part) {
+    float *__restrict__ loss_part, const float *__restrict__ Sp) {
     using CH = Chain<B>;
     __shared__ Smem<B> sm;
     const int tid = threadIdx.x;
     const typename CH::Pos p(tid);
     const int ldw = (int)d_in, woff = p.lane_off(ldw);
     typename CH::Acc acc, acc2;
-    typename CH::TileRegs t0;
+    typename CH::TileRegs t0, t1;
     const double bw = scalars[2];
     const float eta2 = bw > 0.0 ? (float)(2.0 / bw) : 0.f; // eta of the comment above
     const int64_t mrow = d_in / mask_group;
+    // S' = A C either comes from the B step, which formed it at the same A and C (Sp), or is formed here
+    const float *first = Sp != nullptr ? Sp : C;
     int blk = blockIdx.x;
-    if (blk < nblocks) CH::gload_tile(t0, C + (int64_t)(blk / nbj) * B * d_in + (int64_t)(blk % nbj) * B, ldw, tid);
+    if (blk < nblocks) {
+        CH::gload_tile(t0, first + (int64_t)(blk / nbj) * B * d_in + (int64_t)(blk % nbj) * B, ldw, tid);
+        if (Sp != nullptr) CH::gload_tile(t1, Bw + (int64_t)(blk % nbj) * B * B, B, tid);
+    }
     for (; blk < nblocks; blk += gridDim.x) {
         const int i = blk / nbj, j = blk % nbj;
         float *Cij = C + (int64_t)i * B * d_in + (int64_t)j * B;
         const float *Wij = Wbar + (int64_t)i * B * d_in + (int64_t)j * B;
         CH::lstore_tile(sm.X, t0, tid);
-        CH::gload_tile(t0, A + (int64_t)i * B * B, B, tid);
         if (tid < B) sm.Dl[tid] = D[(int64_t)j * B + tid];
-        CH::lstore_tile(sm.Y, t0, tid);
-        __syncthreads();
-        CH::gload_tile(t0, Bw + (int64_t)j * B * B, B, tid);
-        acc.zero();
-        CH::template mma<false, false, false>(acc, sm.Y, sm.X, nullptr, p); // S' = A C
-        __syncthreads();
-        CH::store_acc(sm.X, acc, p);
-        CH::lstore_tile(sm.Y, t0, tid);
+        if (Sp != nullptr) {
+            CH::lstore_tile(sm.Y, t1, tid); // X = S', Y = B^j
+        } else {
+            CH::gload_tile(t0, A + (int64_t)i * B * B, B, tid);
+            CH::lstore_tile(sm.Y, t0, tid);
+            __syncthreads();
+            CH::gload_tile(t0, Bw + (int64_t)j * B * B, B, tid);
+            acc.zero();
+            CH::template mma<false, false, false>(acc, sm.Y, sm.X, nullptr, p); // S' = A C
+            __syncthreads();
+            CH::store_acc(sm.X, acc, p);
+            CH::lstore_tile(sm.Y, t0, tid);
+        }
         float lsum = 0.f;
         {
             float wb[CH::TM][CH::TN][16];
@@ -453,8 +471,10 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_WS_kernel(
         CH::lstore_tile(sm.Y, t0, tid); // A^T A (symmetric)
         __syncthreads();
         const int nblk = blk + gridDim.x;
-        if (nblk < nblocks)
-            CH::gload_tile(t0, C + (int64_t)(nblk / nbj) * B * d_in + (int64_t)(nblk % nbj) * B, ldw, tid);
+        if (nblk < nblocks) {
+            CH::gload_tile(t0, first + (int64_t)(nblk / nbj) * B * d_in + (int64_t)(nblk % nbj) * B, ldw, tid);
+            if (Sp != nullptr) CH::gload_tile(t1, Bw + (int64_t)(nblk % nbj) * B * B, B, tid);
+        }
         acc2.zero();
         CH::template mma<false, false, false>(acc2, sm.Y, sm.X, nullptr, p); // Z = (A^T A) V
         float dz = 0.f;
@@ -816,11 +836,11 @@ void launch_phase_A(const Dims &d, const float *Wbar, const float *C, const floa
 }
 
 void launch_phase_B(const Dims &d, const float *Wbar, const float *C, const float *A, const float *B,
-                    const float *D, int nsplit, float *gpart, float *beta_part, hipStream_t s) {
+                    const float *D, int nsplit, float *gpart, float *beta_part, float *Sp, hipStream_t s) {
     ARMOR_DISPATCH_B(d.b, {
         dim3 grid(d.nbj * nsplit), block(Chain<BB>::NT);
         hipLaunchKernelGGL((phase_B_kernel<BB>), grid, block, 0, s, Wbar, C, A, B, D, d.d_in, d.nbi, d.nbj, nsplit,
-                           gpart, beta_part);
+                           gpart, beta_part, Sp);
     });
 }
 
@@ -867,11 +887,11 @@ void launch_phase_GS(const Dims &d, const float *Wbar, const float *C, const flo
 
 void launch_phase_WS(const Dims &d, const float *Wbar, float *C, const float *A, const float *B, const float *D,
                      const float *AtA, const float *K, const uint8_t *mask, int mask_group, const double *scalars,
-                     float *Gout, float *loss_part, int grid_cap, hipStream_t s) {
+                     float *Gout, float *loss_part, const float *Sp, int grid_cap, hipStream_t s) {
     ARMOR_DISPATCH_B(d.b, {
         dim3 grid(std::min(d.nblocks, grid_cap)), block(Chain<BB>::NT);
         hipLaunchKernelGGL((phase_WS_kernel<BB>), grid, block, 0, s, Wbar, C, A, B, D, AtA, K, mask, mask_group,
-                           scalars, d.d_in, d.nbj, d.nblocks, Gout, loss_part);
+                           scalars, d.d_in, d.nbj, d.nblocks, Gout, loss_part, Sp);
     });
 }
 
