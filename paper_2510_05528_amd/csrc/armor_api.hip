@@ -25,41 +25,55 @@ armor_status check_hip() {
 }
 
 // Optional per-kernel timing with HIP events recorded on the caller's stream around each
-// instrumented launch (host-side bookkeeping only; off by default).
+// instrumented launch (host-side bookkeeping only; off by default).  A scope that directly follows
+// another scope on the same stream (nothing enqueued in between) may take that scope's closing
+// event as its opening one: half as many event packets between the kernels of the iteration loop,
+// and a launch's time then runs from the end of its predecessor to its own end.
 struct Profiler {
     bool on = false;
     std::vector<hipEvent_t> pool;
     size_t used = 0;
-    struct Rec { int kind; size_t e0; };
+    struct Rec { int kind; size_t e0, e1; };
     std::vector<Rec> recs;
     static constexpr size_t kMaxEvents = 1 << 15;
-    int begin(int kind, hipStream_t s) {
-        if (!on) return -1;
-        if (used + 2 > pool.size()) {
-            if (pool.size() + 2 > kMaxEvents) return -1;
-            hipEvent_t a, b;
-            if (hipEventCreate(&a) != hipSuccess) return -1;
-            if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); return -1; }
+    long last_end = -1;            // closing event of the most recent scope
+    hipStream_t last_stream = nullptr;
+    long take(hipStream_t s) {
+        if (used >= pool.size()) {
+            if (pool.size() >= kMaxEvents) return -1;
+            hipEvent_t a;
+            // timing-only events: no system-scope fence (cache write-back + invalidate) when they
+            // complete, which would otherwise sit between every two instrumented kernels
+            if (hipEventCreateWithFlags(&a, hipEventDisableSystemFence) != hipSuccess) return -1;
             pool.push_back(a);
-            pool.push_back(b);
         }
-        size_t e0 = used;
-        used += 2;
-        (void)hipEventRecord(pool[e0], s);
-        recs.push_back({kind, e0});
-        return (int)e0;
+        size_t e = used++;
+        (void)hipEventRecord(pool[e], s);
+        return (long)e;
     }
-    void end(int tok, hipStream_t s) {
-        if (tok >= 0) (void)hipEventRecord(pool[(size_t)tok + 1], s);
+    long begin(hipStream_t s, bool follows) {
+        if (!on) return -1;
+        if (follows && last_end >= 0 && last_stream == s) return last_end;
+        return take(s);
     }
+    void end(int kind, long e0, hipStream_t s) {
+        if (e0 < 0) return;
+        long e1 = take(s);
+        if (e1 < 0) return;
+        recs.push_back({kind, (size_t)e0, (size_t)e1});
+        last_end = e1;
+        last_stream = s;
+    }
+    void reset() { recs.clear(); used = 0; last_end = -1; }
 };
 Profiler g_prof;
 
 struct ProfScope {
-    int tok;
+    int kind;
+    long e0;
     hipStream_t s;
-    ProfScope(int kind, hipStream_t st) : tok(g_prof.begin(kind, st)), s(st) {}
-    ~ProfScope() { g_prof.end(tok, s); }
+    ProfScope(int k, hipStream_t st, bool follows = false) : kind(k), e0(g_prof.begin(st, follows)), s(st) {}
+    ~ProfScope() { g_prof.end(kind, e0, s); }
 };
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -209,6 +223,7 @@ int armor_last_hip_error(void) { return g_last_hip_error; }
 
 armor_status armor_profile_enable(int on) {
     g_prof.on = on != 0;
+    g_prof.last_end = -1;
     return ARMOR_OK;
 }
 
@@ -218,8 +233,8 @@ armor_status armor_profile_read(double *ms_total, int64_t *launches) {
     armor_status st = ARMOR_OK;
     for (const auto &r : g_prof.recs) {
         float ms = 0.f;
-        if (hipEventSynchronize(g_prof.pool[r.e0 + 1]) != hipSuccess ||
-            hipEventElapsedTime(&ms, g_prof.pool[r.e0], g_prof.pool[r.e0 + 1]) != hipSuccess) {
+        if (hipEventSynchronize(g_prof.pool[r.e1]) != hipSuccess ||
+            hipEventElapsedTime(&ms, g_prof.pool[r.e0], g_prof.pool[r.e1]) != hipSuccess) {
             st = check_hip();
             if (st == ARMOR_OK) st = ARMOR_ERR_DEVICE;
             break;
@@ -227,8 +242,7 @@ armor_status armor_profile_read(double *ms_total, int64_t *launches) {
         ms_total[r.kind] += (double)ms;
         launches[r.kind] += 1;
     }
-    g_prof.recs.clear();
-    g_prof.used = 0;
+    g_prof.reset();
     return st;
 }
 
@@ -430,12 +444,12 @@ armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const flo
         for (int t = 1; t <= n_iters; ++t) {
             // joint Adam continuous step (Sec. 3.3.1): all three gradients at theta_{t-1}
             {
-                ProfScope ps(ARMOR_PROF_PHASE_FB, s);
+                ProfScope ps(ARMOR_PROF_PHASE_FB, s, t > 1);
                 launch_phase_FB(d, f.Wbar, S, A, B, f.D, mask, mask_group, f.mC, f.vC, lr, b1, b2, eps, t, f.nsA, f.gpart,
                                 f.gBpart, f.loss_part, s);
             }
             {
-                ProfScope ps(ARMOR_PROF_SMALL, s);
+                ProfScope ps(ARMOR_PROF_SMALL, s, true);
                 launch_adam_wrapper(A, f.mA, f.vA, d.nbi, d.b, f.gpart, f.nsA, lr, b1, b2, eps, t, d.nblocks, f.loss_part,
                                     loss_trace ? loss_trace + (t - 1) : nullptr, s);
                 launch_adam_wrapper(B, f.mB, f.vB, d.nbj, d.b, f.gBpart, d.nbi, lr, b1, b2, eps, t, d.nblocks, nullptr,
@@ -445,11 +459,11 @@ armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const flo
             if (!unstructured) {
                 // sparse-core step (Alg. 3) at the updated point
                 {
-                    ProfScope ps(ARMOR_PROF_PHASE_GS, s);
+                    ProfScope ps(ARMOR_PROF_PHASE_GS, s, true);
                     launch_phase_GS(d, f.Wbar, S, A, B, f.D, f.G, f.loss_part2, slots, s);
                 }
                 {
-                    ProfScope ps(ARMOR_PROF_SPARSE, s);
+                    ProfScope ps(ARMOR_PROF_SPARSE, s, true);
                     launch_sparse_step(d, f.G, S, mask, f.K, f.colnorm2, N, M, o.selection, o.seed, t, f.loss_part2,
                                        loss_cont_trace ? loss_cont_trace + (t - 1) : nullptr, s);
                 }
@@ -463,21 +477,21 @@ armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const flo
     for (int t = 1; o.variant == 0 && t <= n_iters; ++t) {
         // continuous step (Alg. 2), each gradient at the already-updated parameters (Lemma 1)
         {
-            ProfScope ps(ARMOR_PROF_PHASE_A, s);
+            ProfScope ps(ARMOR_PROF_PHASE_A, s, t > 1);
             run_phase_A(false);
         }
         {
-            ProfScope ps(ARMOR_PROF_SMALL, s);
+            ProfScope ps(ARMOR_PROF_SMALL, s, true);
             launch_update_wrapper(A, d.nbi, d.b, f.gpart, f.nsA, f.beta_part, d.nblocks, f.loss_part,
                                   loss_trace ? loss_trace + (t - 1) : nullptr, s);
         }
         {
-            ProfScope ps(ARMOR_PROF_PHASE_B, s);
+            ProfScope ps(ARMOR_PROF_PHASE_B, s, true);
             if (big) launch_big_phase_B(d, f.Wbar, S, A, B, f.D, f.nsB, f.gpart, f.beta_part, slots, f.big_scratch, s);
             else launch_phase_B(d, f.Wbar, S, A, B, f.D, f.nsB, f.gpart, f.beta_part, unstructured ? nullptr : f.Sp, s);
         }
         {
-            ProfScope ps(ARMOR_PROF_SMALL, s);
+            ProfScope ps(ARMOR_PROF_SMALL, s, true);
             launch_update_wrapper(B, d.nbj, d.b, f.gpart, f.nsB, f.beta_part, d.nblocks, nullptr, nullptr, s);
             if (big) launch_big_wrapper_grams(d, A, B, f.D, f.colnorm2, f.fro2A, f.AtA, f.K, f.fro2K, s);
             else launch_wrapper_grams(d, A, B, f.D, f.colnorm2, f.fro2A, f.AtA, f.K, f.fro2K, s);
@@ -485,21 +499,21 @@ armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const flo
         }
         if (unstructured) {
             // Sec. 4.5: continuous step only.  W' step on the kept entries, no core-gradient follow-up.
-            ProfScope ps(ARMOR_PROF_PHASE_WS, s);
+            ProfScope ps(ARMOR_PROF_PHASE_WS, s, true);
             if (big) launch_big_phase_WS(d, f.Wbar, S, A, B, f.D, f.AtA, f.K, mask, mask_group, f.scalars, nullptr,
                                          nullptr, false, slots, f.big_scratch, s);
             else launch_phase_W(d, f.Wbar, S, A, B, f.D, mask, mask_group, f.scalars, slots, s);
         } else {
             // W' step fused with the core gradient at the updated core; then the sparse-core step (Alg. 3)
             {
-                ProfScope ps(ARMOR_PROF_PHASE_WS, s);
+                ProfScope ps(ARMOR_PROF_PHASE_WS, s, true);
                 if (big) launch_big_phase_WS(d, f.Wbar, S, A, B, f.D, f.AtA, f.K, mask, mask_group, f.scalars, f.G,
                                              f.loss_part2, true, slots, f.big_scratch, s);
                 else launch_phase_WS(d, f.Wbar, S, A, B, f.D, f.AtA, f.K, mask, mask_group, f.scalars, f.G,
                                      f.loss_part2, f.Sp, slots, s);
             }
             {
-                ProfScope ps(ARMOR_PROF_SPARSE, s);
+                ProfScope ps(ARMOR_PROF_SPARSE, s, true);
                 launch_sparse_step(d, f.G, S, mask, f.K, f.colnorm2, N, M, o.selection, o.seed, t, f.loss_part2,
                                    loss_cont_trace ? loss_cont_trace + (t - 1) : nullptr, s);
             }
@@ -597,7 +611,7 @@ armor_status armor_apply_packed(const void *X, int64_t n_tokens, const void *A_b
         launch_apply_pre(X, n_tokens, d_in, (int)d_block, B_bf16, ws, s);
     }
     {
-        ProfScope ps(ARMOR_PROF_APPLY_MAIN, s);
+        ProfScope ps(ARMOR_PROF_APPLY_MAIN, s, true);
         if (launch_apply_main(ws, n_tokens, d_in, d_out, (int)d_block, prepared, A_bf16, Y, s) != hipSuccess)
             return ARMOR_ERR_DEVICE;
     }
