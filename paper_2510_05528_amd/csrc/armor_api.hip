@@ -126,7 +126,7 @@ struct Carver {
 };
 
 struct FactorWs {
-    float *Sp; // S' = A C handed from the B step to the W' step (sequential variant, d_block <= 128, N:M)
+    float *Sp; // S' = A C handed from the B step to the W' step (sequential variant; at d_block <= 128 in N:M mode only)
     float *Wbar, *G, *D, *gpart, *beta_part, *loss_part, *loss_part2, *K, *AtA, *colnorm2, *fro2A, *fro2K, *cn_partial,
         *r1, *r2;
     double *scalars;
@@ -164,7 +164,8 @@ FactorWs carve_factor(void *ws, const Dims &d, int mask_group, const armor_opts 
     f.cn_chunks = colnorm_chunks(d.d_out);
     f.Wbar = c.take<float>(P);
     f.G = c.take<float>(P);
-    f.Sp = (d.b <= 128 && !(opts && (opts->sparsity == 1 || opts->variant == 1))) ? c.take<float>(P) : nullptr;
+    const bool adam = opts && opts->variant == 1, unstr = opts && opts->sparsity == 1;
+    f.Sp = (!adam && (d.b > 128 || !unstr)) ? c.take<float>(P) : nullptr;
     f.D = c.take<float>(d.d_in);
     f.gpart = c.take<float>(std::max((size_t)d.nbi * f.nsA, (size_t)d.nbj * f.nsB) * bb);
     f.beta_part = c.take<float>(d.nblocks);
@@ -487,7 +488,7 @@ armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const flo
         }
         {
             ProfScope ps(ARMOR_PROF_PHASE_B, s, true);
-            if (big) launch_big_phase_B(d, f.Wbar, S, A, B, f.D, f.nsB, f.gpart, f.beta_part, slots, f.big_scratch, s);
+            if (big) launch_big_phase_B(d, f.Wbar, S, A, B, f.D, f.nsB, f.gpart, f.beta_part, f.Sp, slots, f.big_scratch, s);
             else launch_phase_B(d, f.Wbar, S, A, B, f.D, f.nsB, f.gpart, f.beta_part, unstructured ? nullptr : f.Sp, s);
         }
         {
@@ -501,14 +502,14 @@ armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const flo
             // Sec. 4.5: continuous step only.  W' step on the kept entries, no core-gradient follow-up.
             ProfScope ps(ARMOR_PROF_PHASE_WS, s, true);
             if (big) launch_big_phase_WS(d, f.Wbar, S, A, B, f.D, f.AtA, f.K, mask, mask_group, f.scalars, nullptr,
-                                         nullptr, false, slots, f.big_scratch, s);
+                                         nullptr, f.Sp, false, slots, f.big_scratch, s);
             else launch_phase_W(d, f.Wbar, S, A, B, f.D, mask, mask_group, f.scalars, slots, s);
         } else {
             // W' step fused with the core gradient at the updated core; then the sparse-core step (Alg. 3)
             {
                 ProfScope ps(ARMOR_PROF_PHASE_WS, s, true);
                 if (big) launch_big_phase_WS(d, f.Wbar, S, A, B, f.D, f.AtA, f.K, mask, mask_group, f.scalars, f.G,
-                                             f.loss_part2, true, slots, f.big_scratch, s);
+                                             f.loss_part2, f.Sp, true, slots, f.big_scratch, s);
                 else launch_phase_WS(d, f.Wbar, S, A, B, f.D, f.AtA, f.K, mask, mask_group, f.scalars, f.G,
                                      f.loss_part2, f.Sp, slots, s);
             }

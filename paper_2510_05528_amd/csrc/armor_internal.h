@@ -50,11 +50,12 @@ void launch_big_phase_A(const Dims &d, const float *Wbar, const float *C, const 
                         const float *D, int nsplit, float *gpart, float *beta_part, float *loss_part, bool loss_only,
                         int grid_cap, float *scratch, hipStream_t s);
 void launch_big_phase_B(const Dims &d, const float *Wbar, const float *C, const float *A, const float *B,
-                        const float *D, int nsplit, float *gpart, float *beta_part, int grid_cap, float *scratch,
-                        hipStream_t s);
+                        const float *D, int nsplit, float *gpart, float *beta_part, float *Sp, int grid_cap,
+                        float *scratch, hipStream_t s);
 void launch_big_phase_WS(const Dims &d, const float *Wbar, float *C, const float *A, const float *B, const float *D,
                          const float *AtA, const float *K, const uint8_t *mask, int mask_group, const double *scalars,
-                         float *Gout, float *loss_part, bool fused, int grid_cap, float *scratch, hipStream_t s);
+                         float *Gout, float *loss_part, const float *Sp, bool fused, int grid_cap, float *scratch,
+                         hipStream_t s);
 void launch_big_wrapper_grams(const Dims &d, const float *A, const float *B, const float *D, float *colnorm2,
                               float *fro2A, float *AtA, float *K, float *fro2K, hipStream_t s);
 

@@ -18,24 +18,53 @@ using CH = Chain<TB>;
 
 // acc over the NS inner sub-tiles of  op(L) (pt, :) * op(R) (:, qt)  for every output sub-tile,
 // then epi(pt, qt, acc).  L, R: b x b row-major with leading dimensions ldl, ldr (global memory;
-// may be this workgroup's scratch: the leading barrier orders its earlier stores before the loads).
-template <int NS, bool LT, bool RT, bool SCALE, class Epi>
+// may be this workgroup's scratch: the leading barrier orders its earlier stores before the loads;
+// no product writes one of its own operands).  The two operand sub-tiles of the next step are
+// requested into registers before the matrix work of the current one and go to LDS after it, so
+// the L2 round trip is hidden.  SYM: the product is symmetric and only its Frobenius norm is
+// wanted, so output sub-tiles below the diagonal are skipped (the caller counts the others twice).
+// pre(pt, qt) runs before the last matrix step of an output sub-tile: the place to request what
+// the epilogue reads from global memory, so that its latency is covered by that step.
+template <int NS, bool LT, bool RT, bool SCALE, bool SYM, class Pre, class Epi>
 __device__ __forceinline__ void big_mma(Smem<TB> &sm, int tid, const CH::Pos &p, const float *__restrict__ L, int ldl,
                                         const float *__restrict__ R, int ldr, const float *__restrict__ Dk,
-                                        Epi &&epi) {
+                                        Pre &&pre, Epi &&epi) {
+    auto lsub = [&](int pt, int rt) { return LT ? L + (rt * TB) * ldl + pt * TB : L + (pt * TB) * ldl + rt * TB; };
+    auto rsub = [&](int qt, int rt) { return RT ? R + (qt * TB) * ldr + rt * TB : R + (rt * TB) * ldr + qt * TB; };
+    CH::TileRegs tx, ty;
+    float dnext = 0.f;
+    __syncthreads();
+    CH::gload_tile(tx, lsub(0, 0), ldl, tid);
+    CH::gload_tile(ty, rsub(0, 0), ldr, tid);
+    if (SCALE && tid < TB) dnext = Dk[tid];
+    CH::lstore_tile(sm.X, tx, tid);
+    CH::lstore_tile(sm.Y, ty, tid);
+    if (SCALE && tid < TB) sm.Dl[tid] = dnext;
+    __syncthreads();
     for (int pt = 0; pt < NS; ++pt)
-        for (int qt = 0; qt < NS; ++qt) {
+        for (int qt = SYM ? pt : 0; qt < NS; ++qt) {
             CH::Acc acc;
             acc.zero();
             for (int rt = 0; rt < NS; ++rt) {
-                const float *Ls = LT ? L + (rt * TB) * ldl + pt * TB : L + (pt * TB) * ldl + rt * TB;
-                const float *Rs = RT ? R + (qt * TB) * ldr + rt * TB : R + (rt * TB) * ldr + qt * TB;
-                __syncthreads();
-                CH::load_tile(sm.X, Ls, ldl, tid);
-                CH::load_tile(sm.Y, Rs, ldr, tid);
-                if (SCALE && tid < TB) sm.Dl[tid] = Dk[rt * TB + tid];
-                __syncthreads();
+                // the step after this one
+                int nr = rt + 1, nq = qt, np = pt;
+                if (nr == NS) { nr = 0; ++nq; }
+                if (nq == NS) { ++np; nq = SYM ? np : 0; }
+                const bool more = np < NS;
+                if (more) {
+                    CH::gload_tile(tx, lsub(np, nr), ldl, tid);
+                    CH::gload_tile(ty, rsub(nq, nr), ldr, tid);
+                    if (SCALE && tid < TB) dnext = Dk[nr * TB + tid];
+                }
+                if (rt == NS - 1) pre(pt, qt);
                 CH::template mma<LT, RT, SCALE>(acc, sm.X, sm.Y, sm.Dl, p);
+                __syncthreads();
+                if (more) {
+                    CH::lstore_tile(sm.X, tx, tid);
+                    CH::lstore_tile(sm.Y, ty, tid);
+                    if (SCALE && tid < TB) sm.Dl[tid] = dnext;
+                }
+                __syncthreads();
             }
             epi(pt, qt, acc);
         }
@@ -43,6 +72,25 @@ __device__ __forceinline__ void big_mma(Smem<TB> &sm, int tid, const CH::Pos &p,
 
 // visit every accumulator element of output sub-tile (pt, qt): f(off, value&) with off the element
 // offset in a row-major matrix of leading dimension ld
+struct NoPre {
+    __device__ void operator()(int, int) const {}
+};
+
+// this lane's 32 elements of output sub-tile (pt, qt) of a row-major matrix: load / visit
+struct Patch {
+    float v[CH::TM][CH::TN][16];
+};
+__device__ __forceinline__ void load_patch(Patch &w, const float *__restrict__ g, const CH::Pos &p, int pt, int qt,
+                                           int ld) {
+    const int base = opaque((pt * TB + p.wm0 + p.kh * 4) * ld + qt * TB + p.wn0 + p.l32);
+#pragma unroll
+    for (int tm = 0; tm < CH::TM; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < CH::TN; ++tn)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) w.v[tm][tn][r] = g[base + CH::Pos::unif_off(tm, tn, r, ld)];
+}
+
 template <class F>
 __device__ __forceinline__ void for_acc(CH::Acc &acc, const CH::Pos &p, int pt, int qt, int ld, F &&f) {
     const int base = opaque((pt * TB + p.wm0 + p.kh * 4) * ld + qt * TB + p.wn0 + p.l32);
@@ -77,12 +125,14 @@ __global__ __launch_bounds__(CH::NT) void big_phase_A_kernel(
         const float *Cij = C + (int64_t)i * b * d_in + (int64_t)j * b;
         const float *Wij = Wbar + (int64_t)i * b * d_in + (int64_t)j * b;
         const float *Bj = Bw + (int64_t)j * b * b, *Dj = D + (int64_t)j * b;
-        big_mma<NS, false, false, false>(sm, tid, p, Cij, ldw, Bj, b, nullptr, [&](int pt, int qt, CH::Acc &acc) {
+        big_mma<NS, false, false, false, false>(sm, tid, p, Cij, ldw, Bj, b, nullptr, NoPre(), [&](int pt, int qt, CH::Acc &acc) {
             for_acc(acc, p, pt, qt, b, [&](int off, float v, int, int, int) { s0[off] = v; }); // S = C B
         });
         float lsum = 0.f;
-        big_mma<NS, false, false, false>(sm, tid, p, Ai, b, s0, b, nullptr, [&](int pt, int qt, CH::Acc &acc) {
-            const int wbase = opaque((pt * TB + p.wm0 + p.kh * 4) * ldw + qt * TB + p.wn0 + p.l32);
+        Patch wp;
+        big_mma<NS, false, false, false, false>(sm, tid, p, Ai, b, s0, b, nullptr,
+                                                [&](int pt, int qt) { load_patch(wp, Wij, p, pt, qt, ldw); },
+                                                [&](int pt, int qt, CH::Acc &acc) {
 #pragma unroll
             for (int tm = 0; tm < CH::TM; ++tm)
 #pragma unroll
@@ -90,7 +140,7 @@ __global__ __launch_bounds__(CH::NT) void big_phase_A_kernel(
                     const float dj = Dj[qt * TB + p.col(tn)];
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
-                        float res = Wij[wbase + CH::Pos::unif_off(tm, tn, r, ldw)] - acc.v[tm][tn][r];
+                        float res = wp.v[tm][tn][r] - acc.v[tm][tn][r];
                         lsum += res * res * dj;
                         acc.v[tm][tn][r] = res * dj;
                     }
@@ -101,19 +151,23 @@ __global__ __launch_bounds__(CH::NT) void big_phase_A_kernel(
         if (tid == 0) loss_part[i * nbj + j] = ltot;
         if (!LOSS_ONLY) {
             const bool first = j == j0;
-            big_mma<NS, false, true, false>(sm, tid, p, s1, b, s0, b, nullptr, [&](int pt, int qt, CH::Acc &acc) {
-                for_acc(acc, p, pt, qt, b, [&](int off, float v, int, int, int) {
-                    gp[off] = (first ? 0.f : gp[off]) - 2.f * v; // += -2 (R D) S^T, same workgroup, fixed order
+            big_mma<NS, false, true, false, false>(sm, tid, p, s1, b, s0, b, nullptr,
+                                                   [&](int pt, int qt) { if (!first) load_patch(wp, gp, p, pt, qt, b); },
+                                                   [&](int pt, int qt, CH::Acc &acc) {
+                for_acc(acc, p, pt, qt, b, [&](int off, float v, int tm, int tn, int r) {
+                    gp[off] = (first ? 0.f : wp.v[tm][tn][r]) - 2.f * v; // += -2 (R D) S^T, same workgroup, fixed order
                 });
             });
             float f2 = 0.f;
-            big_mma<NS, false, true, true>(sm, tid, p, s0, b, s0, b, Dj, [&](int, int, CH::Acc &acc) {
+            big_mma<NS, false, true, true, true>(sm, tid, p, s0, b, s0, b, Dj, NoPre(), [&](int pt, int qt, CH::Acc &acc) {
+                float t2 = 0.f; // S D S^T is symmetric: upper sub-tiles only, off-diagonal ones twice
 #pragma unroll
                 for (int tm = 0; tm < CH::TM; ++tm)
 #pragma unroll
                     for (int tn = 0; tn < CH::TN; ++tn)
 #pragma unroll
-                        for (int r = 0; r < 16; ++r) f2 += acc.v[tm][tn][r] * acc.v[tm][tn][r];
+                        for (int r = 0; r < 16; ++r) t2 += acc.v[tm][tn][r] * acc.v[tm][tn][r];
+                f2 += pt == qt ? t2 : 2.f * t2;
             });
             float ftot = CH::block_sum(f2, sm.red, tid);
             if (tid == 0) beta_part[i * nbj + j] = sqrtf(ftot);
@@ -127,7 +181,8 @@ template <int NS>
 __global__ __launch_bounds__(CH::NT) void big_phase_B_kernel(
     const float *__restrict__ Wbar, const float *__restrict__ C, const float *__restrict__ A,
     const float *__restrict__ Bw, const float *__restrict__ D, int64_t d_in, int nbi, int nbj, int nsplit,
-    int nitems, float *__restrict__ gpart, float *__restrict__ beta_part, float *__restrict__ scratch) {
+    int nitems, float *__restrict__ gpart, float *__restrict__ beta_part, float *__restrict__ Sp,
+    float *__restrict__ scratch) {
     constexpr int b = NS * TB;
     __shared__ Smem<TB> sm;
     const int tid = threadIdx.x;
@@ -147,36 +202,44 @@ __global__ __launch_bounds__(CH::NT) void big_phase_B_kernel(
         const float *Cij = C + (int64_t)i * b * d_in + (int64_t)j * b;
         const float *Wij = Wbar + (int64_t)i * b * d_in + (int64_t)j * b;
         const float *Ai = A + (int64_t)i * b * b;
-        big_mma<NS, false, false, false>(sm, tid, p, Ai, b, Cij, ldw, nullptr, [&](int pt, int qt, CH::Acc &acc) {
+        float *Spij = Sp ? Sp + (int64_t)i * b * d_in + (int64_t)j * b : nullptr;
+        big_mma<NS, false, false, false, false>(sm, tid, p, Ai, b, Cij, ldw, nullptr, NoPre(), [&](int pt, int qt, CH::Acc &acc) {
             for_acc(acc, p, pt, qt, b, [&](int off, float v, int, int, int) { s0[off] = v; }); // S' = A C
+            // the W' step sees the same A and C: hand S' over instead of forming it again there
+            if (Spij) for_acc(acc, p, pt, qt, ldw, [&](int off, float v, int, int, int) { Spij[off] = v; });
         });
-        big_mma<NS, false, false, false>(sm, tid, p, s0, b, Bj, b, nullptr, [&](int pt, int qt, CH::Acc &acc) {
-            const int wbase = opaque((pt * TB + p.wm0 + p.kh * 4) * ldw + qt * TB + p.wn0 + p.l32);
+        Patch wp;
+        big_mma<NS, false, false, false, false>(sm, tid, p, s0, b, Bj, b, nullptr,
+                                                [&](int pt, int qt) { load_patch(wp, Wij, p, pt, qt, ldw); },
+                                                [&](int pt, int qt, CH::Acc &acc) {
 #pragma unroll
             for (int tm = 0; tm < CH::TM; ++tm)
 #pragma unroll
                 for (int tn = 0; tn < CH::TN; ++tn) {
                     const float dj = Dj[qt * TB + p.col(tn)];
 #pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        acc.v[tm][tn][r] = (Wij[wbase + CH::Pos::unif_off(tm, tn, r, ldw)] - acc.v[tm][tn][r]) * dj;
+                    for (int r = 0; r < 16; ++r) acc.v[tm][tn][r] = (wp.v[tm][tn][r] - acc.v[tm][tn][r]) * dj;
                 }
             for_acc(acc, p, pt, qt, b, [&](int off, float v, int, int, int) { s1[off] = v; }); // R D
         });
         const bool first = i == i0;
-        big_mma<NS, true, false, false>(sm, tid, p, s0, b, s1, b, nullptr, [&](int pt, int qt, CH::Acc &acc) {
-            for_acc(acc, p, pt, qt, b, [&](int off, float v, int, int, int) {
-                gp[off] = (first ? 0.f : gp[off]) - 2.f * v; // += -2 S'^T (R D)
+        big_mma<NS, true, false, false, false>(sm, tid, p, s0, b, s1, b, nullptr,
+                                               [&](int pt, int qt) { if (!first) load_patch(wp, gp, p, pt, qt, b); },
+                                               [&](int pt, int qt, CH::Acc &acc) {
+            for_acc(acc, p, pt, qt, b, [&](int off, float v, int tm, int tn, int r) {
+                gp[off] = (first ? 0.f : wp.v[tm][tn][r]) - 2.f * v; // += -2 S'^T (R D)
             });
         });
         float f2 = 0.f;
-        big_mma<NS, true, false, false>(sm, tid, p, s0, b, s0, b, nullptr, [&](int, int, CH::Acc &acc) {
+        big_mma<NS, true, false, false, true>(sm, tid, p, s0, b, s0, b, nullptr, NoPre(), [&](int pt, int qt, CH::Acc &acc) {
+            float t2 = 0.f; // S'^T S' is symmetric: upper sub-tiles only, off-diagonal ones twice
 #pragma unroll
             for (int tm = 0; tm < CH::TM; ++tm)
 #pragma unroll
                 for (int tn = 0; tn < CH::TN; ++tn)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) f2 += acc.v[tm][tn][r] * acc.v[tm][tn][r];
+                    for (int r = 0; r < 16; ++r) t2 += acc.v[tm][tn][r] * acc.v[tm][tn][r];
+            f2 += pt == qt ? t2 : 2.f * t2;
         });
         float ftot = CH::block_sum(f2, sm.red, tid);
         if (tid == 0) beta_part[i * nbj + j] = sqrtf(ftot) * sqrtf(dn2);
@@ -191,7 +254,7 @@ __global__ __launch_bounds__(CH::NT) void big_phase_WS_kernel(
     const float *__restrict__ Bw, const float *__restrict__ D, const float *__restrict__ AtA,
     const float *__restrict__ K, const uint8_t *__restrict__ mask, int mask_group,
     const double *__restrict__ scalars, int64_t d_in, int nbj, int nblocks, float *__restrict__ Gout,
-    float *__restrict__ loss_part, float *__restrict__ scratch) {
+    float *__restrict__ loss_part, const float *__restrict__ Sp, float *__restrict__ scratch) {
     constexpr int b = NS * TB;
     __shared__ Smem<TB> sm;
     const int tid = threadIdx.x;
@@ -207,12 +270,21 @@ __global__ __launch_bounds__(CH::NT) void big_phase_WS_kernel(
         const float *Wij = Wbar + (int64_t)i * b * d_in + (int64_t)j * b;
         const float *Ai = A + (int64_t)i * b * b, *Bj = Bw + (int64_t)j * b * b, *Dj = D + (int64_t)j * b;
         float *Gij = FUSED ? Gout + (int64_t)i * b * d_in + (int64_t)j * b : nullptr;
-        big_mma<NS, false, false, false>(sm, tid, p, Ai, b, Cij, ldw, nullptr, [&](int pt, int qt, CH::Acc &acc) {
-            for_acc(acc, p, pt, qt, b, [&](int off, float v, int, int, int) { s0[off] = v; }); // S' = A C
-        });
+        const float *Sl = s0; // S' = A C: from the B step when it left it, else formed here
+        int lds = b;
+        if (Sp) {
+            Sl = Sp + (int64_t)i * b * d_in + (int64_t)j * b;
+            lds = ldw;
+        } else {
+            big_mma<NS, false, false, false, false>(sm, tid, p, Ai, b, Cij, ldw, nullptr, NoPre(), [&](int pt, int qt, CH::Acc &acc) {
+                for_acc(acc, p, pt, qt, b, [&](int off, float v, int, int, int) { s0[off] = v; });
+            });
+        }
         float lsum = 0.f;
-        big_mma<NS, false, false, false>(sm, tid, p, s0, b, Bj, b, nullptr, [&](int pt, int qt, CH::Acc &acc) {
-            const int wbase = opaque((pt * TB + p.wm0 + p.kh * 4) * ldw + qt * TB + p.wn0 + p.l32);
+        Patch wp;
+        big_mma<NS, false, false, false, false>(sm, tid, p, Sl, lds, Bj, b, nullptr,
+                                                [&](int pt, int qt) { load_patch(wp, Wij, p, pt, qt, ldw); },
+                                                [&](int pt, int qt, CH::Acc &acc) {
 #pragma unroll
             for (int tm = 0; tm < CH::TM; ++tm)
 #pragma unroll
@@ -220,18 +292,31 @@ __global__ __launch_bounds__(CH::NT) void big_phase_WS_kernel(
                     const float dj = Dj[qt * TB + p.col(tn)];
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
-                        float res = Wij[wbase + CH::Pos::unif_off(tm, tn, r, ldw)] - acc.v[tm][tn][r];
+                        float res = wp.v[tm][tn][r] - acc.v[tm][tn][r];
                         lsum += res * res * dj;
                         acc.v[tm][tn][r] = res * dj;
                     }
                 }
             for_acc(acc, p, pt, qt, b, [&](int off, float v, int, int, int) { s1[off] = v; }); // R D
         });
-        big_mma<NS, false, true, false>(sm, tid, p, s1, b, Bj, b, nullptr, [&](int pt, int qt, CH::Acc &acc) {
+        big_mma<NS, false, true, false, false>(sm, tid, p, s1, b, Bj, b, nullptr, NoPre(), [&](int pt, int qt, CH::Acc &acc) {
             for_acc(acc, p, pt, qt, b, [&](int off, float v, int, int, int) { s0[off] = v; }); // U = (R D) B^T
         });
         float dd = 0.f;
-        big_mma<NS, true, false, false>(sm, tid, p, Ai, b, s0, b, nullptr, [&](int pt, int qt, CH::Acc &acc) {
+        uint32_t mb[CH::TM][CH::TN][16]; // mask bytes of this lane's elements, requested under the last matrix step
+        auto pre_G = [&](int pt, int qt) {
+            load_patch(wp, Cij, p, pt, qt, ldw);
+#pragma unroll
+            for (int tm = 0; tm < CH::TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < CH::TN; ++tn) {
+                    const int64_t gcol = (int64_t)j * b + qt * TB + p.col(tn);
+                    const uint8_t *mp = mask + ((int64_t)i * b + pt * TB + p.wm0 + p.kh * 4) * mrow + gcol / mask_group;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) mb[tm][tn][r] = mp[(int64_t)(tm * 32 + (r >> 2) * 8 + (r & 3)) * mrow];
+                }
+        };
+        big_mma<NS, true, false, false, false>(sm, tid, p, Ai, b, s0, b, nullptr, pre_G, [&](int pt, int qt, CH::Acc &acc) {
             // G = A^T U: W' step on kept entries; Delta -> s1, raw G -> Gout (fused mode)
             const int cbase = opaque((pt * TB + p.wm0 + p.kh * 4) * ldw + qt * TB + p.wn0 + p.l32);
             const int sbase = opaque((pt * TB + p.wm0 + p.kh * 4) * b + qt * TB + p.wn0 + p.l32);
@@ -241,17 +326,12 @@ __global__ __launch_bounds__(CH::NT) void big_phase_WS_kernel(
                 for (int tn = 0; tn < CH::TN; ++tn) {
                     const int64_t gcol = (int64_t)j * b + qt * TB + p.col(tn);
                     const int sh = (int)(gcol % mask_group);
-                    const uint8_t *mp = mask + ((int64_t)i * b + pt * TB + p.wm0 + p.kh * 4) * mrow + gcol / mask_group;
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
-                        const uint32_t mb = mp[(int64_t)(tm * 32 + (r >> 2) * 8 + (r & 3)) * mrow];
-                        const bool kp = (mb >> sh) & 1u;
+                        const bool kp = (mb[tm][tn][r] >> sh) & 1u;
                         const float g = acc.v[tm][tn][r], dl = kp ? g : 0.f;
                         dd += dl * dl;
-                        if (kp) {
-                            float *cp = Cij + cbase + CH::Pos::unif_off(tm, tn, r, ldw);
-                            *cp = *cp + eta2 * dl;
-                        }
+                        if (kp) Cij[cbase + CH::Pos::unif_off(tm, tn, r, ldw)] = wp.v[tm][tn][r] + eta2 * dl;
                         if (FUSED) {
                             s1[sbase + CH::Pos::unif_off(tm, tn, r, b)] = dl;
                             Gij[cbase + CH::Pos::unif_off(tm, tn, r, ldw)] = g;
@@ -260,26 +340,29 @@ __global__ __launch_bounds__(CH::NT) void big_phase_WS_kernel(
                 }
         });
         if (FUSED) {
-            big_mma<NS, false, false, false>(sm, tid, p, s1, b, K + (int64_t)j * b * b, b, nullptr,
+            big_mma<NS, false, false, false, false>(sm, tid, p, s1, b, K + (int64_t)j * b * b, b, nullptr, NoPre(),
                                              [&](int pt, int qt, CH::Acc &acc) {
                 for_acc(acc, p, pt, qt, b, [&](int off, float v, int, int, int) { s0[off] = v; }); // V = Delta K
             });
             float dz = 0.f;
-            big_mma<NS, false, false, false>(sm, tid, p, AtA + (int64_t)i * b * b, b, s0, b, nullptr,
+            Patch dp; // Delta and the raw G of this lane's elements (both written by this lane above)
+            big_mma<NS, false, false, false, false>(sm, tid, p, AtA + (int64_t)i * b * b, b, s0, b, nullptr,
+                                             [&](int pt, int qt) {
+                                                 load_patch(wp, Gij, p, pt, qt, ldw);
+                                                 load_patch(dp, s1, p, pt, qt, b);
+                                             },
                                              [&](int pt, int qt, CH::Acc &acc) {
                 // Z = (A^T A) V:  G_new = G - eta Z;  <Delta, Z>
                 const int cbase = opaque((pt * TB + p.wm0 + p.kh * 4) * ldw + qt * TB + p.wn0 + p.l32);
-                const int sbase = opaque((pt * TB + p.wm0 + p.kh * 4) * b + qt * TB + p.wn0 + p.l32);
 #pragma unroll
                 for (int tm = 0; tm < CH::TM; ++tm)
 #pragma unroll
                     for (int tn = 0; tn < CH::TN; ++tn)
 #pragma unroll
                         for (int r = 0; r < 16; ++r) {
-                            float *gp = Gij + cbase + CH::Pos::unif_off(tm, tn, r, ldw);
                             const float z = acc.v[tm][tn][r];
-                            dz += s1[sbase + CH::Pos::unif_off(tm, tn, r, b)] * z;
-                            *gp = -2.f * (*gp - eta2 * z);
+                            dz += dp.v[tm][tn][r] * z;
+                            Gij[cbase + CH::Pos::unif_off(tm, tn, r, ldw)] = -2.f * (wp.v[tm][tn][r] - eta2 * z);
                         }
             });
             float ltot = CH::block_sum(lsum - 2.f * eta2 * dd + eta2 * eta2 * dz, sm.red, tid);
@@ -310,8 +393,8 @@ __global__ __launch_bounds__(CH::NT) void big_wrapper_grams_kernel(
             if (isA && off / b == off % b) colnorm2[(int64_t)idx * b + off / b] = v;
         });
     };
-    if (isA) big_mma<NS, true, false, false>(sm, tid, p, src, b, src, b, nullptr, epi);          // A^T A
-    else     big_mma<NS, false, true, true>(sm, tid, p, src, b, src, b, D + (int64_t)idx * b, epi); // (B D) B^T
+    if (isA) big_mma<NS, true, false, false, false>(sm, tid, p, src, b, src, b, nullptr, NoPre(), epi);          // A^T A
+    else     big_mma<NS, false, true, true, false>(sm, tid, p, src, b, src, b, D + (int64_t)idx * b, NoPre(), epi); // (B D) B^T
     float ftot = CH::block_sum(f2, sm.red, tid);
     if (tid == 0) (isA ? fro2A : fro2K)[idx] = ftot;
 }
@@ -334,23 +417,24 @@ void launch_big_phase_A(const Dims &d, const float *Wbar, const float *C, const 
 }
 
 void launch_big_phase_B(const Dims &d, const float *Wbar, const float *C, const float *A, const float *B,
-                        const float *D, int nsplit, float *gpart, float *beta_part, int grid_cap, float *scratch,
-                        hipStream_t s) {
+                        const float *D, int nsplit, float *gpart, float *beta_part, float *Sp, int grid_cap,
+                        float *scratch, hipStream_t s) {
     const int nitems = d.nbj * nsplit;
     hipLaunchKernelGGL((big_phase_B_kernel<2>), dim3(std::min(nitems, grid_cap)), dim3(CH::NT), 0, s, Wbar, C, A, B, D,
-                       d.d_in, d.nbi, d.nbj, nsplit, nitems, gpart, beta_part, scratch);
+                       d.d_in, d.nbi, d.nbj, nsplit, nitems, gpart, beta_part, Sp, scratch);
 }
 
 void launch_big_phase_WS(const Dims &d, const float *Wbar, float *C, const float *A, const float *B, const float *D,
                          const float *AtA, const float *K, const uint8_t *mask, int mask_group, const double *scalars,
-                         float *Gout, float *loss_part, bool fused, int grid_cap, float *scratch, hipStream_t s) {
+                         float *Gout, float *loss_part, const float *Sp, bool fused, int grid_cap, float *scratch,
+                         hipStream_t s) {
     dim3 grid(std::min(d.nblocks, grid_cap)), block(CH::NT);
     if (fused)
         hipLaunchKernelGGL((big_phase_WS_kernel<2, true>), grid, block, 0, s, Wbar, C, A, B, D, AtA, K, mask,
-                           mask_group, scalars, d.d_in, d.nbj, d.nblocks, Gout, loss_part, scratch);
+                           mask_group, scalars, d.d_in, d.nbj, d.nblocks, Gout, loss_part, Sp, scratch);
     else
         hipLaunchKernelGGL((big_phase_WS_kernel<2, false>), grid, block, 0, s, Wbar, C, A, B, D, AtA, K, mask,
-                           mask_group, scalars, d.d_in, d.nbj, d.nblocks, Gout, loss_part, scratch);
+                           mask_group, scalars, d.d_in, d.nbj, d.nblocks, Gout, loss_part, Sp, scratch);
 }
 
 void launch_big_wrapper_grams(const Dims &d, const float *A, const float *B, const float *D, float *colnorm2,
