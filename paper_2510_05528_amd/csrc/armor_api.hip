@@ -129,7 +129,6 @@ struct FactorWs {
     float *Sp; // S' = A C handed from the B step to the W' step (sequential variant; at d_block <= 128 in N:M mode only)
     float *Wbar, *G, *D, *gpart, *beta_part, *loss_part, *loss_part2, *K, *AtA, *colnorm2, *fro2A, *fro2K, *cn_partial,
         *r1, *r2;
-    double *scalars;
     uint8_t *mask;
     void *unstructured;
     float *big_scratch;
@@ -174,12 +173,11 @@ FactorWs carve_factor(void *ws, const Dims &d, int mask_group, const armor_opts 
     f.K = c.take<float>((size_t)d.nbj * bb);
     f.AtA = c.take<float>((size_t)d.nbi * bb);
     f.colnorm2 = c.take<float>(d.d_out);
-    f.fro2A = c.take<float>(d.nbi);
-    f.fro2K = c.take<float>(d.nbj);
+    f.fro2A = c.take<float>((size_t)d.nbi * gram_parts(d.b));
+    f.fro2K = c.take<float>((size_t)d.nbj * gram_parts(d.b));
     f.cn_partial = c.take<float>(((size_t)f.cn_chunks + 1) * d.d_in); // chunk sums, then 1/r1
     f.r1 = c.take<float>(d.d_in);
     f.r2 = c.take<float>(d.d_out);
-    f.scalars = c.take<double>(8);
     f.mask = c.take<uint8_t>((size_t)d.d_out * (d.d_in / mask_group));
     f.unstructured = (opts && opts->sparsity == 1)
                          ? c.take<char>(unstructured_init_ws_bytes(d.d_out, d.d_in)) : nullptr;
@@ -496,21 +494,20 @@ armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const flo
             launch_update_wrapper(B, d.nbj, d.b, f.gpart, f.nsB, f.beta_part, d.nblocks, nullptr, nullptr, s);
             if (big) launch_big_wrapper_grams(d, A, B, f.D, f.colnorm2, f.fro2A, f.AtA, f.K, f.fro2K, s);
             else launch_wrapper_grams(d, A, B, f.D, f.colnorm2, f.fro2A, f.AtA, f.K, f.fro2K, s);
-            launch_finalize_betaW(f.fro2A, d.nbi, f.fro2K, d.nbj, f.scalars, s);
         }
         if (unstructured) {
             // Sec. 4.5: continuous step only.  W' step on the kept entries, no core-gradient follow-up.
             ProfScope ps(ARMOR_PROF_PHASE_WS, s, true);
-            if (big) launch_big_phase_WS(d, f.Wbar, S, A, B, f.D, f.AtA, f.K, mask, mask_group, f.scalars, nullptr,
+            if (big) launch_big_phase_WS(d, f.Wbar, S, A, B, f.D, f.AtA, f.K, mask, mask_group, f.fro2A, f.fro2K, nullptr,
                                          nullptr, f.Sp, false, slots, f.big_scratch, s);
-            else launch_phase_W(d, f.Wbar, S, A, B, f.D, mask, mask_group, f.scalars, slots, s);
+            else launch_phase_W(d, f.Wbar, S, A, B, f.D, mask, mask_group, f.fro2A, f.fro2K, slots, s);
         } else {
             // W' step fused with the core gradient at the updated core; then the sparse-core step (Alg. 3)
             {
                 ProfScope ps(ARMOR_PROF_PHASE_WS, s, true);
-                if (big) launch_big_phase_WS(d, f.Wbar, S, A, B, f.D, f.AtA, f.K, mask, mask_group, f.scalars, f.G,
+                if (big) launch_big_phase_WS(d, f.Wbar, S, A, B, f.D, f.AtA, f.K, mask, mask_group, f.fro2A, f.fro2K, f.G,
                                              f.loss_part2, f.Sp, true, slots, f.big_scratch, s);
-                else launch_phase_WS(d, f.Wbar, S, A, B, f.D, f.AtA, f.K, mask, mask_group, f.scalars, f.G,
+                else launch_phase_WS(d, f.Wbar, S, A, B, f.D, f.AtA, f.K, mask, mask_group, f.fro2A, f.fro2K, f.G,
                                      f.loss_part2, f.Sp, slots, s);
             }
             {

@@ -24,15 +24,16 @@ void launch_phase_B(const Dims &d, const float *Wbar, const float *C, const floa
 // W' step of Alg. 2 alone (unstructured mode): C += (2/beta_W) (A^T ((Wbar - A C B) D) B^T) (.) M, beta_W
 // read from scalars[2].  grid_cap workgroups at most, each walking blocks w, w + grid, ...
 void launch_phase_W(const Dims &d, const float *Wbar, float *C, const float *A, const float *B, const float *D,
-                    const uint8_t *mask, int mask_group, const double *scalars, int grid_cap, hipStream_t s);
+                    const uint8_t *mask, int mask_group, const float *fro2A, const float *fro2K, int grid_cap,
+                    hipStream_t s);
 // Per wrapper block: A^iT A^i, its diagonal ||A^i[:,p]||^2 and ||A^iT A^i||_F^2; K^j = B^j D^j B^jT, ||K^j||_F^2.
 void launch_wrapper_grams(const Dims &d, const float *A, const float *B, const float *D, float *colnorm2,
                           float *fro2A, float *AtA, float *K, float *fro2K, hipStream_t s);
 // W' step fused with the core gradient at the updated core (N:M mode): C += (2/beta_W) G (.) M,
 // Gout = -2 (G - (2/beta_W) (A^T A)(G (.) M) K), block loss after the continuous step to loss_part.
 void launch_phase_WS(const Dims &d, const float *Wbar, float *C, const float *A, const float *B, const float *D,
-                     const float *AtA, const float *K, const uint8_t *mask, int mask_group, const double *scalars,
-                     float *Gout, float *loss_part, const float *Sp, int grid_cap, hipStream_t s);
+                     const float *AtA, const float *K, const uint8_t *mask, int mask_group, const float *fro2A,
+                     const float *fro2K, float *Gout, float *loss_part, const float *Sp, int grid_cap, hipStream_t s);
 int chain_max_nsplit();
 // Joint-Adam forward/backward pass: gradients of A (gApart, nsplit chunks per row block), B (gBpart,
 // one partial per block, laid out [j][i]) and the Adam update of the core and its moments in place.
@@ -53,8 +54,8 @@ void launch_big_phase_B(const Dims &d, const float *Wbar, const float *C, const 
                         const float *D, int nsplit, float *gpart, float *beta_part, float *Sp, int grid_cap,
                         float *scratch, hipStream_t s);
 void launch_big_phase_WS(const Dims &d, const float *Wbar, float *C, const float *A, const float *B, const float *D,
-                         const float *AtA, const float *K, const uint8_t *mask, int mask_group, const double *scalars,
-                         float *Gout, float *loss_part, const float *Sp, bool fused, int grid_cap, float *scratch,
+                         const float *AtA, const float *K, const uint8_t *mask, int mask_group, const float *fro2A,
+                         const float *fro2K, float *Gout, float *loss_part, const float *Sp, bool fused, int grid_cap, float *scratch,
                          hipStream_t s);
 void launch_big_wrapper_grams(const Dims &d, const float *A, const float *B, const float *D, float *colnorm2,
                               float *fro2A, float *AtA, float *K, float *fro2K, hipStream_t s);
@@ -79,7 +80,7 @@ void launch_adam_wrapper(float *X, float *m, float *v, int nblk, int b, const fl
                          double b1, double b2, double eps, int64_t t, int nblocks, const float *loss_part,
                          double *trace_out, hipStream_t s);
 void launch_zero(float *x, int64_t n, hipStream_t s);
-void launch_finalize_betaW(const float *fro2A, int nbi, const float *fro2K, int nbj, double *scalars, hipStream_t s);
+int gram_parts(int b);
 void launch_sum_to_double(const float *part, int n, double *out, hipStream_t s);
 void launch_sparse_step(const Dims &d, const float *G, float *C, uint8_t *mask, const float *K,
                         const float *colnorm2, int N, int M, int selection, uint64_t seed, int64_t t,

@@ -231,7 +231,8 @@ template <int B>
 __global__ __launch_bounds__(Chain<B>::NT) void phase_W_kernel(
     const float *__restrict__ Wbar, float *__restrict__ C, const float *__restrict__ A,
     const float *__restrict__ Bw, const float *__restrict__ D, const uint8_t *__restrict__ mask, int mask_group,
-    const double *__restrict__ scalars, int64_t d_in, int nbj, int nblocks) {
+    const float *__restrict__ fro2A, int nA, const float *__restrict__ fro2K, int nK, int64_t d_in, int nbj,
+    int nblocks) {
     using CH = Chain<B>;
     __shared__ Smem<B> sm;
     const int tid = threadIdx.x;
@@ -239,11 +240,10 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_W_kernel(
     const int ldw = (int)d_in, woff = p.lane_off(ldw);
     typename CH::Acc acc;
     typename CH::TileRegs t0, tc;
-    const double bw = scalars[2];
-    const float eta2 = bw > 0.0 ? (float)(2.0 / bw) : 0.f;
     const int64_t mrow = d_in / mask_group;
     int blk = blockIdx.x;
     if (blk < nblocks) CH::gload_tile(t0, C + (int64_t)(blk / nbj) * B * d_in + (int64_t)(blk % nbj) * B, ldw, tid);
+    publish_eta_W(sm, tid, fro2A, nA, fro2K, nK); // its loads travel with the first tile's
     for (; blk < nblocks; blk += gridDim.x) {
         const int i = blk / nbj, j = blk % nbj;
         float *Cij = C + (int64_t)i * B * d_in + (int64_t)j * B;
@@ -307,6 +307,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_W_kernel(
         CH::template mma<true, false, false>(acc, sm.Y, sm.X, nullptr, p); // G = A^T U
         {
             // C <- C + (2/beta) G on kept entries, as one coalesced float4 pass: G goes through LDS
+            const float eta2 = read_eta_W(sm);
             __syncthreads();
             CH::store_acc(sm.X, acc, p);
             __syncthreads();
@@ -347,8 +348,8 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_WS_kernel(
     const float *__restrict__ Wbar, float *__restrict__ C, const float *__restrict__ A,
     const float *__restrict__ Bw, const float *__restrict__ D, const float *__restrict__ AtA,
     const float *__restrict__ K, const uint8_t *__restrict__ mask, int mask_group,
-    const double *__restrict__ scalars, int64_t d_in, int nbj, int nblocks, float *__restrict__ Gout,
-    float *__restrict__ loss_part, const float *__restrict__ Sp) {
+    const float *__restrict__ fro2A, int nA, const float *__restrict__ fro2K, int nK, int64_t d_in, int nbj,
+    int nblocks, float *__restrict__ Gout, float *__restrict__ loss_part, const float *__restrict__ Sp) {
     using CH = Chain<B>;
     __shared__ Smem<B> sm;
     const int tid = threadIdx.x;
@@ -356,8 +357,6 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_WS_kernel(
     const int ldw = (int)d_in, woff = p.lane_off(ldw);
     typename CH::Acc acc, acc2;
     typename CH::TileRegs t0, t1;
-    const double bw = scalars[2];
-    const float eta2 = bw > 0.0 ? (float)(2.0 / bw) : 0.f; // eta of the comment above
     const int64_t mrow = d_in / mask_group;
     // S' = A C either comes from the B step, which formed it at the same A and C (Sp), or is formed here
     const float *first = Sp != nullptr ? Sp : C;
@@ -366,6 +365,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_WS_kernel(
         CH::gload_tile(t0, first + (int64_t)(blk / nbj) * B * d_in + (int64_t)(blk % nbj) * B, ldw, tid);
         if (Sp != nullptr) CH::gload_tile(t1, Bw + (int64_t)(blk % nbj) * B * B, B, tid);
     }
+    publish_eta_W(sm, tid, fro2A, nA, fro2K, nK); // eta of the comment above; its loads travel with the first tiles'
     for (; blk < nblocks; blk += gridDim.x) {
         const int i = blk / nbj, j = blk % nbj;
         float *Cij = C + (int64_t)i * B * d_in + (int64_t)j * B;
@@ -438,6 +438,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_WS_kernel(
         __syncthreads();
         acc.zero();
         CH::template mma<true, false, false>(acc, sm.Y, sm.X, nullptr, p); // G = A^T U   (stays in acc)
+        const float eta2 = read_eta_W(sm);
         // W' step on kept entries; Delta = G (.) M goes to LDS for the two extra products
         uint32_t keep[CH::TM][CH::TN];
         float dd = 0.f;
@@ -769,49 +770,83 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_GS_kernel(
 
 // ------------------------------------------------------------------------------------------------
 // Small Gram-type products of the wrappers themselves (Eq. 11 and the shortcuts of Alg. 3):
-//   blockIdx <  nbi : AtA^(i) = A^(i)T A^(i), colnorm2[i*b+p] = its diagonal = ||A^(i)[:,p]||^2 (the ||a||^2 of
-//                     Eq. 7), fro2A[i] = ||A^iT A^i||_F^2
-//   blockIdx >= nbi : K^(j) = B^(j) D^(j) B^(j)T (holds every B' D B'^T of Eq. 7), fro2K[j] = ||K^j||_F^2
+//   block <  nbi : AtA^(i) = A^(i)T A^(i), colnorm2[i*b+p] = its diagonal = ||A^(i)[:,p]||^2 (the ||a||^2 of
+//                  Eq. 7), fro2A[i*b/32 + slab] = squared Frobenius norm of one 32-column slab of it
+//   block >= nbi : K^(j) = B^(j) D^(j) B^(j)T (holds every B' D B'^T of Eq. 7), fro2K likewise
 // ------------------------------------------------------------------------------------------------
 template <int B>
-__global__ __launch_bounds__(Chain<B>::NT) void wrapper_grams_kernel(
+__global__ __launch_bounds__((B / 32) * 64) void wrapper_grams_kernel(
     const float *__restrict__ A, const float *__restrict__ Bw, const float *__restrict__ D, int nbi,
     float *__restrict__ colnorm2, float *__restrict__ fro2A, float *__restrict__ AtA, float *__restrict__ K,
     float *__restrict__ fro2K) {
+    // One workgroup per (block, 32-column slab of the result), one wave per 32 x 32 tile of the slab:
+    // the b x b products are few (d_out/b + d_in/b), so each is spread over b/32 compute units.
     using CH = Chain<B>;
-    __shared__ Smem<B> sm;
-    const int tid = threadIdx.x;
-    const typename CH::Pos p(tid);
-    typename CH::Acc acc;
-    acc.zero();
-    const bool isA = (int)blockIdx.x < nbi;
-    const int idx = isA ? blockIdx.x : blockIdx.x - nbi;
-    CH::load_tile(sm.X, (isA ? A : Bw) + (int64_t)idx * B * B, B, tid);
-    if (!isA && tid < B) sm.Dl[tid] = D[(int64_t)idx * B + tid];
+    constexpr int NS = B / 32, NTH = NS * 64, P = CH::P;
+    __shared__ float X[CH::TILE_FLOATS];
+    __shared__ float Dl[B];
+    __shared__ float red[NS];
+    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, l32 = lane & 31, kh = lane >> 5;
+    const int blk = blockIdx.x / NS, ct = blockIdx.x % NS, rt = w;
+    const bool isA = blk < nbi;
+    const int idx = isA ? blk : blk - nbi;
+    const float *src = (isA ? A : Bw) + (int64_t)idx * B * B;
+    {   // whole block -> LDS (loader lane mapping of Chain, for this workgroup size)
+        constexpr int ROWS_PER_IT = NTH / (B / 4), PER = B * B / 4 / NTH;
+        const int lrow = ((tid >> 5) / (B / 32)) * 4 + ((tid & 31) >> 3), c4 = ((tid >> 5) % (B / 32)) * 8 + (tid & 7);
+        float4 v[PER];
+#pragma unroll
+        for (int it = 0; it < PER; ++it)
+            v[it] = *reinterpret_cast<const float4 *>(src + (lrow + it * ROWS_PER_IT) * B + c4 * 4);
+#pragma unroll
+        for (int it = 0; it < PER; ++it) {
+            float *d = X + (lrow + it * ROWS_PER_IT) * P + c4 * 4;
+            d[0] = v[it].x; d[1] = v[it].y; d[2] = v[it].z; d[3] = v[it].w;
+        }
+        if (!isA && tid < B) Dl[tid] = D[(int64_t)idx * B + tid];
+    }
     __syncthreads();
-    if (isA) CH::template mma<true, false, false>(acc, sm.X, sm.X, nullptr, p); // A^T A
-    else     CH::template mma<false, true, true>(acc, sm.X, sm.X, sm.Dl, p);    // (B D) B^T
+    floatx16 acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+    if (isA) { // (A^T A)[m][n] = sum_k A[k][m] A[k][n]
+        const float *xa = X + kh * P + 32 * rt + l32, *xb = X + kh * P + 32 * ct + l32;
+#pragma unroll 8
+        for (int k = 0; k < B; k += 2) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(xa[k * P], xb[k * P], acc, 0, 0, 0);
+    } else {   // K[m][n] = sum_k B[m][k] D[k] B[n][k]
+        const float *xa = X + (32 * rt + l32) * P + kh, *xb = X + (32 * ct + l32) * P + kh;
+#pragma unroll 8
+        for (int k = 0; k < B; k += 2)
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(xa[k] * Dl[k + kh], xb[k], acc, 0, 0, 0);
+    }
     float f2 = 0.f;
+    float *dst = (isA ? AtA : K) + (int64_t)idx * B * B;
 #pragma unroll
-    for (int tm = 0; tm < CH::TM; ++tm)
+    for (int r = 0; r < 16; ++r) {
+        const float v = acc[r];
+        const int row = 32 * rt + (r >> 2) * 8 + kh * 4 + (r & 3), col = 32 * ct + l32;
+        f2 += v * v;
+        if (isA && row == col) colnorm2[(int64_t)idx * B + row] = v;
+        dst[row * B + col] = v;
+    }
 #pragma unroll
-        for (int tn = 0; tn < CH::TN; ++tn)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                float v = acc.v[tm][tn][r];
-                f2 += v * v;
-                int row = p.row(tm, r), col = p.col(tn);
-                if (isA && row == col) colnorm2[(int64_t)idx * B + row] = v;
-                (isA ? AtA : K)[(int64_t)idx * B * B + row * B + col] = v;
-            }
-    float ftot = CH::block_sum(f2, sm.red, tid);
-    if (tid == 0) (isA ? fro2A : fro2K)[idx] = ftot;
+    for (int off = 32; off > 0; off >>= 1) f2 += __shfl_xor(f2, off, 64);
+    if (lane == 0) red[w] = f2;
+    __syncthreads();
+    if (tid == 0) {
+        float s = 0.f;
+        for (int q = 0; q < NS; ++q) s += red[q];
+        (isA ? fro2A : fro2K)[idx * NS + ct] = s;
+    }
 }
 
 // ------------------------------------------------------------------------------------------------
 // host launchers
 // ------------------------------------------------------------------------------------------------
 int chain_max_nsplit() { return 64; }
+
+// partial squared norms the wrapper-Gram kernels leave per block (one per 32-column slab up to b = 128)
+int gram_parts(int b) { return b <= 128 ? b / 32 : 1; }
 
 #define ARMOR_DISPATCH_B(bval, ...)                      \
     switch (bval) {                                      \
@@ -845,18 +880,19 @@ void launch_phase_B(const Dims &d, const float *Wbar, const float *C, const floa
 }
 
 void launch_phase_W(const Dims &d, const float *Wbar, float *C, const float *A, const float *B, const float *D,
-                    const uint8_t *mask, int mask_group, const double *scalars, int grid_cap, hipStream_t s) {
+                    const uint8_t *mask, int mask_group, const float *fro2A, const float *fro2K, int grid_cap,
+                    hipStream_t s) {
     ARMOR_DISPATCH_B(d.b, {
         dim3 grid(std::min(d.nblocks, grid_cap)), block(Chain<BB>::NT);
-        hipLaunchKernelGGL((phase_W_kernel<BB>), grid, block, 0, s, Wbar, C, A, B, D, mask, mask_group, scalars,
-                           d.d_in, d.nbj, d.nblocks);
+        hipLaunchKernelGGL((phase_W_kernel<BB>), grid, block, 0, s, Wbar, C, A, B, D, mask, mask_group, fro2A,
+                           d.nbi * gram_parts(d.b), fro2K, d.nbj * gram_parts(d.b), d.d_in, d.nbj, d.nblocks);
     });
 }
 
 void launch_wrapper_grams(const Dims &d, const float *A, const float *B, const float *D, float *colnorm2,
                           float *fro2A, float *AtA, float *K, float *fro2K, hipStream_t s) {
     ARMOR_DISPATCH_B(d.b, {
-        dim3 grid(d.nbi + d.nbj), block(Chain<BB>::NT);
+        dim3 grid((d.nbi + d.nbj) * (BB / 32)), block((BB / 32) * 64);
         hipLaunchKernelGGL((wrapper_grams_kernel<BB>), grid, block, 0, s, A, B, D, d.nbi, colnorm2, fro2A, AtA, K,
                            fro2K);
     });
@@ -886,12 +922,13 @@ void launch_phase_GS(const Dims &d, const float *Wbar, const float *C, const flo
 }
 
 void launch_phase_WS(const Dims &d, const float *Wbar, float *C, const float *A, const float *B, const float *D,
-                     const float *AtA, const float *K, const uint8_t *mask, int mask_group, const double *scalars,
-                     float *Gout, float *loss_part, const float *Sp, int grid_cap, hipStream_t s) {
+                     const float *AtA, const float *K, const uint8_t *mask, int mask_group, const float *fro2A,
+                     const float *fro2K, float *Gout, float *loss_part, const float *Sp, int grid_cap, hipStream_t s) {
     ARMOR_DISPATCH_B(d.b, {
         dim3 grid(std::min(d.nblocks, grid_cap)), block(Chain<BB>::NT);
         hipLaunchKernelGGL((phase_WS_kernel<BB>), grid, block, 0, s, Wbar, C, A, B, D, AtA, K, mask, mask_group,
-                           scalars, d.d_in, d.nbj, d.nblocks, Gout, loss_part, Sp);
+                           fro2A, d.nbi * gram_parts(d.b), fro2K, d.nbj * gram_parts(d.b), d.d_in, d.nbj, d.nblocks, Gout,
+                           loss_part, Sp);
     });
 }
 

@@ -253,15 +253,17 @@ __global__ __launch_bounds__(CH::NT) void big_phase_WS_kernel(
     const float *__restrict__ Wbar, float *__restrict__ C, const float *__restrict__ A,
     const float *__restrict__ Bw, const float *__restrict__ D, const float *__restrict__ AtA,
     const float *__restrict__ K, const uint8_t *__restrict__ mask, int mask_group,
-    const double *__restrict__ scalars, int64_t d_in, int nbj, int nblocks, float *__restrict__ Gout,
-    float *__restrict__ loss_part, const float *__restrict__ Sp, float *__restrict__ scratch) {
+    const float *__restrict__ fro2A, int nA, const float *__restrict__ fro2K, int nK, int64_t d_in, int nbj,
+    int nblocks, float *__restrict__ Gout, float *__restrict__ loss_part, const float *__restrict__ Sp,
+    float *__restrict__ scratch) {
     constexpr int b = NS * TB;
     __shared__ Smem<TB> sm;
     const int tid = threadIdx.x;
     const CH::Pos p(tid);
     const int ldw = (int)d_in;
-    const double bw = scalars[2];
-    const float eta2 = bw > 0.0 ? (float)(2.0 / bw) : 0.f;
+    publish_eta_W(sm, tid, fro2A, nA, fro2K, nK);
+    __syncthreads();
+    const float eta2 = read_eta_W(sm);
     const int64_t mrow = d_in / mask_group;
     float *s0 = scratch + (int64_t)blockIdx.x * 2 * b * b, *s1 = s0 + b * b;
     for (int blk = blockIdx.x; blk < nblocks; blk += gridDim.x) {
@@ -425,16 +427,16 @@ void launch_big_phase_B(const Dims &d, const float *Wbar, const float *C, const 
 }
 
 void launch_big_phase_WS(const Dims &d, const float *Wbar, float *C, const float *A, const float *B, const float *D,
-                         const float *AtA, const float *K, const uint8_t *mask, int mask_group, const double *scalars,
-                         float *Gout, float *loss_part, const float *Sp, bool fused, int grid_cap, float *scratch,
+                         const float *AtA, const float *K, const uint8_t *mask, int mask_group, const float *fro2A,
+                         const float *fro2K, float *Gout, float *loss_part, const float *Sp, bool fused, int grid_cap, float *scratch,
                          hipStream_t s) {
     dim3 grid(std::min(d.nblocks, grid_cap)), block(CH::NT);
     if (fused)
         hipLaunchKernelGGL((big_phase_WS_kernel<2, true>), grid, block, 0, s, Wbar, C, A, B, D, AtA, K, mask,
-                           mask_group, scalars, d.d_in, d.nbj, d.nblocks, Gout, loss_part, Sp, scratch);
+                           mask_group, fro2A, d.nbi, fro2K, d.nbj, d.d_in, d.nbj, d.nblocks, Gout, loss_part, Sp, scratch);
     else
         hipLaunchKernelGGL((big_phase_WS_kernel<2, false>), grid, block, 0, s, Wbar, C, A, B, D, AtA, K, mask,
-                           mask_group, scalars, d.d_in, d.nbj, d.nblocks, Gout, loss_part, Sp, scratch);
+                           mask_group, fro2A, d.nbi, fro2K, d.nbj, d.d_in, d.nbj, d.nblocks, Gout, loss_part, Sp, scratch);
 }
 
 void launch_big_wrapper_grams(const Dims &d, const float *A, const float *B, const float *D, float *colnorm2,

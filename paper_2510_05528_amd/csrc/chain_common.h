@@ -232,11 +232,64 @@ template <int B> struct Chain {
     }
 };
 
+// eta = 2 / beta_W' with beta_W' = 2 ||A^T A||_F ||B D B^T||_F (Eq. 11), from the squared Frobenius
+// norms of the parts of the two block-diagonal matrices (nA and nK partial sums).  One wave per
+// workgroup evaluates the sums, every workgroup in the same fixed order (fp64), so all take the
+// same step and no separate reduction launch is needed (one wave only: thousands of waves reading
+// the same few cache lines at kernel start queue up on one L2 channel).  Call with a whole wave;
+// publish_eta_W / read_eta_W move the value through LDS to the rest of the workgroup.
+__device__ __forceinline__ float wave_eta_W(const float *__restrict__ fro2A, int nA, const float *__restrict__ fro2K,
+                                            int nK) {
+    const int lane = threadIdx.x & 63;
+    // the first 256 values of each array are requested together: one memory round trip, not one per value
+    float va[4], vk[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int e = lane + 64 * q; // clamped, unconditional loads: a lane-predicated load would wait for its own data
+        va[q] = 0.f;
+        vk[q] = 0.f;
+        if (64 * q < nA) va[q] = fro2A[min(e, nA - 1)];
+        if (64 * q < nK) vk[q] = fro2K[min(e, nK - 1)];
+        if (e >= nA) va[q] = 0.f;
+        if (e >= nK) vk[q] = 0.f;
+    }
+    double a = 0.0, k = 0.0;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        a += (double)va[q];
+        k += (double)vk[q];
+    }
+    for (int e = lane + 256; e < nA; e += 64) a += (double)fro2A[e];
+    for (int e = lane + 256; e < nK; e += 64) k += (double)fro2K[e];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        a += __shfl_xor(a, off, 64);
+        k += __shfl_xor(k, off, 64);
+    }
+    const double bw = 2.0 * sqrt(a) * sqrt(k);
+    const float eta = bw > 0.0 ? (float)(2.0 / bw) : 0.f;
+    // every lane holds the same value: keep it in a scalar register like any other uniform
+    return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(eta)));
+}
+
 template <int B> struct Smem {
     float X[Chain<B>::TILE_FLOATS];
     float Y[Chain<B>::TILE_FLOATS];
     float Dl[B];
     float red[16];
+    float eta;
 };
+
+template <int B>
+__device__ __forceinline__ void publish_eta_W(Smem<B> &sm, int tid, const float *__restrict__ fro2A, int nA,
+                                              const float *__restrict__ fro2K, int nK) {
+    if (tid < 64) { // wave 0; visible to the others after the next barrier
+        const float e = wave_eta_W(fro2A, nA, fro2K, nK);
+        if (tid == 0) sm.eta = e;
+    }
+}
+template <int B> __device__ __forceinline__ float read_eta_W(const Smem<B> &sm) {
+    return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(sm.eta))); // uniform: scalar register
+}
 
 } // namespace armor

@@ -465,23 +465,6 @@ void launch_zero(float *x, int64_t n, hipStream_t s) {
     if (n > 0) hipLaunchKernelGGL(zero_kernel, dim3(grid), dim3(256), 0, s, x, n);
 }
 
-// beta_W' = 2 ||A^T A||_F ||B D B^T||_F (Eq. 11) from the per-block squared norms -> scalars[2]
-__global__ __launch_bounds__(256) void finalize_betaW_kernel(const float *__restrict__ fro2A, int nbi,
-                                                             const float *__restrict__ fro2K, int nbj,
-                                                             double *__restrict__ scalars) {
-    __shared__ double red[4];
-    double a = 0.0, k = 0.0;
-    for (int e = threadIdx.x; e < nbi; e += 256) a += (double)fro2A[e];
-    for (int e = threadIdx.x; e < nbj; e += 256) k += (double)fro2K[e];
-    a = block_sum_256(a, red);
-    k = block_sum_256(k, red);
-    if (threadIdx.x == 0) scalars[2] = 2.0 * sqrt(a) * sqrt(k);
-}
-
-void launch_finalize_betaW(const float *fro2A, int nbi, const float *fro2K, int nbj, double *scalars, hipStream_t s) {
-    hipLaunchKernelGGL(finalize_betaW_kernel, dim3(1), dim3(256), 0, s, fro2A, nbi, fro2K, nbj, scalars);
-}
-
 __global__ __launch_bounds__(256) void sum_to_double_kernel(const float *__restrict__ part, int n,
                                                             double *__restrict__ out) {
     __shared__ double red[4];
