@@ -384,7 +384,6 @@ armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const flo
     const bool unstructured = o.sparsity == 1;
     if (o.sparsity != 0 && o.sparsity != 1) return ARMOR_ERR_SHAPE;
     if (o.selection < 0 || o.selection > 3 || o.variant < 0 || o.variant > 1) return ARMOR_ERR_SHAPE;
-    if (o.variant == 1 && d_block > 128) return ARMOR_ERR_UNSUPPORTED;
     if (o.lr < 0 || o.adam_beta1 < 0 || o.adam_beta1 >= 1 || o.adam_beta2 < 0 || o.adam_beta2 >= 1 || o.adam_eps < 0)
         return ARMOR_ERR_SHAPE;
     if (!unstructured) {
@@ -444,8 +443,10 @@ armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const flo
             // joint Adam continuous step (Sec. 3.3.1): all three gradients at theta_{t-1}
             {
                 ProfScope ps(ARMOR_PROF_PHASE_FB, s, t > 1);
-                launch_phase_FB(d, f.Wbar, S, A, B, f.D, mask, mask_group, f.mC, f.vC, lr, b1, b2, eps, t, f.nsA, f.gpart,
-                                f.gBpart, f.loss_part, s);
+                if (big) launch_big_phase_FB(d, f.Wbar, S, A, B, f.D, mask, mask_group, f.mC, f.vC, lr, b1, b2, eps, t, f.nsA,
+                                             f.gpart, f.gBpart, f.loss_part, slots, f.big_scratch, s);
+                else launch_phase_FB(d, f.Wbar, S, A, B, f.D, mask, mask_group, f.mC, f.vC, lr, b1, b2, eps, t, f.nsA,
+                                     f.gpart, f.gBpart, f.loss_part, s);
             }
             {
                 ProfScope ps(ARMOR_PROF_SMALL, s, true);
@@ -453,13 +454,17 @@ armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const flo
                                     loss_trace ? loss_trace + (t - 1) : nullptr, s);
                 launch_adam_wrapper(B, f.mB, f.vB, d.nbj, d.b, f.gBpart, d.nbi, lr, b1, b2, eps, t, d.nblocks, nullptr,
                                     nullptr, s);
-                if (!unstructured) launch_wrapper_grams(d, A, B, f.D, f.colnorm2, f.fro2A, f.AtA, f.K, f.fro2K, s);
+                if (!unstructured) {
+                    if (big) launch_big_wrapper_grams(d, A, B, f.D, f.colnorm2, f.fro2A, f.AtA, f.K, f.fro2K, s);
+                    else launch_wrapper_grams(d, A, B, f.D, f.colnorm2, f.fro2A, f.AtA, f.K, f.fro2K, s);
+                }
             }
             if (!unstructured) {
                 // sparse-core step (Alg. 3) at the updated point
                 {
                     ProfScope ps(ARMOR_PROF_PHASE_GS, s, true);
-                    launch_phase_GS(d, f.Wbar, S, A, B, f.D, f.G, f.loss_part2, slots, s);
+                    if (big) launch_big_phase_GS(d, f.Wbar, S, A, B, f.D, f.G, f.loss_part2, slots, f.big_scratch, s);
+                    else launch_phase_GS(d, f.Wbar, S, A, B, f.D, f.G, f.loss_part2, slots, s);
                 }
                 {
                     ProfScope ps(ARMOR_PROF_SPARSE, s, true);

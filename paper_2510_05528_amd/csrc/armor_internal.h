@@ -57,6 +57,12 @@ void launch_big_phase_WS(const Dims &d, const float *Wbar, float *C, const float
                          const float *AtA, const float *K, const uint8_t *mask, int mask_group, const float *fro2A,
                          const float *fro2K, float *Gout, float *loss_part, const float *Sp, bool fused, int grid_cap, float *scratch,
                          hipStream_t s);
+void launch_big_phase_FB(const Dims &d, const float *Wbar, float *C, const float *A, const float *B, const float *D,
+                         const uint8_t *mask, int mask_group, float *mC, float *vC, double lr, double b1, double b2,
+                         double eps, int64_t t, int nsplit, float *gApart, float *gBpart, float *loss_part, int grid_cap,
+                         float *scratch, hipStream_t s);
+void launch_big_phase_GS(const Dims &d, const float *Wbar, const float *C, const float *A, const float *B,
+                         const float *D, float *Gout, float *loss_part, int grid_cap, float *scratch, hipStream_t s);
 void launch_big_wrapper_grams(const Dims &d, const float *A, const float *B, const float *D, float *colnorm2,
                               float *fro2A, float *AtA, float *K, float *fro2K, hipStream_t s);
 

@@ -507,10 +507,6 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_WS_kernel(
 //                                         moments happens here, moments also decay on pruned entries)
 // Workgroup (i, c) walks the column blocks j of its chunk.  loss_part = block loss at the old point.
 // ------------------------------------------------------------------------------------------------
-struct AdamCoef {
-    float b1, b2, one_minus_b1, one_minus_b2, inv_c1, inv_c2, lr, eps; // inv_c = 1 / (1 - beta^t)
-};
-
 template <int B>
 __global__ __launch_bounds__(Chain<B>::NT) void phase_FB_kernel(
     const float *__restrict__ Wbar, float *__restrict__ C, const float *__restrict__ A,
@@ -901,10 +897,7 @@ void launch_wrapper_grams(const Dims &d, const float *A, const float *B, const f
 void launch_phase_FB(const Dims &d, const float *Wbar, float *C, const float *A, const float *B, const float *D,
                      const uint8_t *mask, int mask_group, float *mC, float *vC, double lr, double b1, double b2,
                      double eps, int64_t t, int nsplit, float *gApart, float *gBpart, float *loss_part, hipStream_t s) {
-    AdamCoef k;
-    k.b1 = (float)b1; k.b2 = (float)b2; k.one_minus_b1 = (float)(1.0 - b1); k.one_minus_b2 = (float)(1.0 - b2);
-    k.inv_c1 = (float)(1.0 / (1.0 - pow(b1, (double)t))); k.inv_c2 = (float)(1.0 / (1.0 - pow(b2, (double)t)));
-    k.lr = (float)lr; k.eps = (float)eps;
+    const AdamCoef k = make_adam_coef(lr, b1, b2, eps, t);
     ARMOR_DISPATCH_B(d.b, {
         dim3 grid(d.nbi * nsplit), block(Chain<BB>::NT);
         hipLaunchKernelGGL((phase_FB_kernel<BB>), grid, block, 0, s, Wbar, C, A, B, D, mask, mask_group, mC, vC, k,

@@ -373,6 +373,166 @@ __global__ __launch_bounds__(CH::NT) void big_phase_WS_kernel(
     }
 }
 
+// ---- joint-Adam forward/backward (see phase_FB_kernel in chain.hip) ----------------------------------
+// Per block: S = C B -> s0, R D -> s1, grad_A partial += -2 (R D) S^T, T = A^T (R D) -> s0 (S is dead),
+// grad_B partial = -2 C^T T (old core), then T B^T with the Adam update of the core in its epilogue.
+template <int NS>
+__global__ __launch_bounds__(CH::NT) void big_phase_FB_kernel(
+    const float *__restrict__ Wbar, float *__restrict__ C, const float *__restrict__ A,
+    const float *__restrict__ Bw, const float *__restrict__ D, const uint8_t *__restrict__ mask, int mask_group,
+    float *__restrict__ mC, float *__restrict__ vC, AdamCoef k, int64_t d_in, int nbi, int nbj, int nsplit, int nitems,
+    float *__restrict__ gApart, float *__restrict__ gBpart, float *__restrict__ loss_part,
+    float *__restrict__ scratch) {
+    constexpr int b = NS * TB;
+    __shared__ Smem<TB> sm;
+    const int tid = threadIdx.x;
+    const CH::Pos p(tid);
+    const int ldw = (int)d_in;
+    const int64_t mrow = d_in / mask_group;
+    float *s0 = scratch + (int64_t)blockIdx.x * 2 * b * b, *s1 = s0 + b * b;
+    const int chunk = (nbj + nsplit - 1) / nsplit;
+    for (int item = blockIdx.x; item < nitems; item += gridDim.x) { // item = (row block i, chunk c)
+    const int i = item / nsplit, c = item % nsplit;
+    const int j0 = c * chunk, j1 = min(nbj, j0 + chunk);
+    float *gp = gApart + (int64_t)item * b * b;
+    const float *Ai = A + (int64_t)i * b * b;
+    if (j0 >= j1) { // empty chunk: its partial is still summed by the wrapper update
+        for (int e = tid; e < b * b; e += CH::NT) gp[e] = 0.f;
+        continue;
+    }
+    for (int j = j0; j < j1; ++j) {
+        float *Cij = C + (int64_t)i * b * d_in + (int64_t)j * b;
+        const float *Wij = Wbar + (int64_t)i * b * d_in + (int64_t)j * b;
+        const float *Bj = Bw + (int64_t)j * b * b, *Dj = D + (int64_t)j * b;
+        big_mma<NS, false, false, false, false>(sm, tid, p, Cij, ldw, Bj, b, nullptr, NoPre(), [&](int pt, int qt, CH::Acc &acc) {
+            for_acc(acc, p, pt, qt, b, [&](int off, float v, int, int, int) { s0[off] = v; }); // S = C B
+        });
+        float lsum = 0.f;
+        Patch wp;
+        big_mma<NS, false, false, false, false>(sm, tid, p, Ai, b, s0, b, nullptr,
+                                                [&](int pt, int qt) { load_patch(wp, Wij, p, pt, qt, ldw); },
+                                                [&](int pt, int qt, CH::Acc &acc) {
+#pragma unroll
+            for (int tm = 0; tm < CH::TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < CH::TN; ++tn) {
+                    const float dj = Dj[qt * TB + p.col(tn)];
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        float res = wp.v[tm][tn][r] - acc.v[tm][tn][r];
+                        lsum += res * res * dj;
+                        acc.v[tm][tn][r] = res * dj;
+                    }
+                }
+            for_acc(acc, p, pt, qt, b, [&](int off, float v, int, int, int) { s1[off] = v; }); // R D
+        });
+        float ltot = CH::block_sum(lsum, sm.red, tid);
+        if (tid == 0) loss_part[i * nbj + j] = ltot;
+        const bool first = j == j0;
+        big_mma<NS, false, true, false, false>(sm, tid, p, s1, b, s0, b, nullptr,
+                                               [&](int pt, int qt) { if (!first) load_patch(wp, gp, p, pt, qt, b); },
+                                               [&](int pt, int qt, CH::Acc &acc) {
+            for_acc(acc, p, pt, qt, b, [&](int off, float v, int tm, int tn, int r) {
+                gp[off] = (first ? 0.f : wp.v[tm][tn][r]) - 2.f * v; // += -2 (R D) S^T, same workgroup, fixed order
+            });
+        });
+        big_mma<NS, true, false, false, false>(sm, tid, p, Ai, b, s1, b, nullptr, NoPre(), [&](int pt, int qt, CH::Acc &acc) {
+            for_acc(acc, p, pt, qt, b, [&](int off, float v, int, int, int) { s0[off] = v; }); // T = A^T (R D)
+        });
+        float *gb = gBpart + ((int64_t)j * nbi + i) * b * b;
+        big_mma<NS, true, false, false, false>(sm, tid, p, Cij, ldw, s0, b, nullptr, NoPre(), [&](int pt, int qt, CH::Acc &acc) {
+            for_acc(acc, p, pt, qt, b, [&](int off, float v, int, int, int) { gb[off] = -2.f * v; }); // C^T T, old core
+        });
+        float *mij = mC + (int64_t)i * b * d_in + (int64_t)j * b, *vij = vC + (int64_t)i * b * d_in + (int64_t)j * b;
+        uint32_t mb[CH::TM][CH::TN][16];
+        auto pre_C = [&](int pt, int qt) {
+            load_patch(wp, Cij, p, pt, qt, ldw);
+#pragma unroll
+            for (int tm = 0; tm < CH::TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < CH::TN; ++tn) {
+                    const int64_t gcol = (int64_t)j * b + qt * TB + p.col(tn);
+                    const uint8_t *mp = mask + ((int64_t)i * b + pt * TB + p.wm0 + p.kh * 4) * mrow + gcol / mask_group;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) mb[tm][tn][r] = mp[(int64_t)(tm * 32 + (r >> 2) * 8 + (r & 3)) * mrow];
+                }
+        };
+        big_mma<NS, false, true, false, false>(sm, tid, p, s0, b, Bj, b, nullptr, pre_C, [&](int pt, int qt, CH::Acc &acc) {
+            // T B^T: Adam on the core, g = -2 (T B^T) (.) M; the moments decay on pruned entries too
+            const int cbase = opaque((pt * TB + p.wm0 + p.kh * 4) * ldw + qt * TB + p.wn0 + p.l32);
+#pragma unroll
+            for (int tm = 0; tm < CH::TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < CH::TN; ++tn) {
+                    const int sh = (int)(((int64_t)j * b + qt * TB + p.col(tn)) % mask_group);
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int off = cbase + CH::Pos::unif_off(tm, tn, r, ldw);
+                        const bool kp = (mb[tm][tn][r] >> sh) & 1u;
+                        const float g = kp ? -2.f * acc.v[tm][tn][r] : 0.f;
+                        const float mn = k.b1 * mij[off] + k.one_minus_b1 * g;
+                        const float vn = k.b2 * vij[off] + k.one_minus_b2 * g * g;
+                        mij[off] = mn;
+                        vij[off] = vn;
+                        if (kp) Cij[off] = wp.v[tm][tn][r] - k.lr * (mn * k.inv_c1) / (sqrtf(vn * k.inv_c2) + k.eps);
+                    }
+                }
+        });
+    }
+    }
+}
+
+// ---- core gradient at the current point (see phase_GS_kernel in chain.hip) ------------------------------
+template <int NS>
+__global__ __launch_bounds__(CH::NT) void big_phase_GS_kernel(
+    const float *__restrict__ Wbar, const float *__restrict__ C, const float *__restrict__ A,
+    const float *__restrict__ Bw, const float *__restrict__ D, int64_t d_in, int nbj, int nblocks,
+    float *__restrict__ Gout, float *__restrict__ loss_part, float *__restrict__ scratch) {
+    constexpr int b = NS * TB;
+    __shared__ Smem<TB> sm;
+    const int tid = threadIdx.x;
+    const CH::Pos p(tid);
+    const int ldw = (int)d_in;
+    float *s0 = scratch + (int64_t)blockIdx.x * 2 * b * b, *s1 = s0 + b * b;
+    for (int blk = blockIdx.x; blk < nblocks; blk += gridDim.x) {
+        const int i = blk / nbj, j = blk % nbj;
+        const float *Cij = C + (int64_t)i * b * d_in + (int64_t)j * b;
+        const float *Wij = Wbar + (int64_t)i * b * d_in + (int64_t)j * b;
+        const float *Ai = A + (int64_t)i * b * b, *Bj = Bw + (int64_t)j * b * b, *Dj = D + (int64_t)j * b;
+        float *Gij = Gout + (int64_t)i * b * d_in + (int64_t)j * b;
+        big_mma<NS, false, false, false, false>(sm, tid, p, Ai, b, Cij, ldw, nullptr, NoPre(), [&](int pt, int qt, CH::Acc &acc) {
+            for_acc(acc, p, pt, qt, b, [&](int off, float v, int, int, int) { s0[off] = v; }); // S' = A C
+        });
+        float lsum = 0.f;
+        Patch wp;
+        big_mma<NS, false, false, false, false>(sm, tid, p, s0, b, Bj, b, nullptr,
+                                                [&](int pt, int qt) { load_patch(wp, Wij, p, pt, qt, ldw); },
+                                                [&](int pt, int qt, CH::Acc &acc) {
+#pragma unroll
+            for (int tm = 0; tm < CH::TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < CH::TN; ++tn) {
+                    const float dj = Dj[qt * TB + p.col(tn)];
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        float res = wp.v[tm][tn][r] - acc.v[tm][tn][r];
+                        lsum += res * res * dj;
+                        acc.v[tm][tn][r] = res * dj;
+                    }
+                }
+            for_acc(acc, p, pt, qt, b, [&](int off, float v, int, int, int) { s1[off] = v; }); // R D
+        });
+        big_mma<NS, false, true, false, false>(sm, tid, p, s1, b, Bj, b, nullptr, NoPre(), [&](int pt, int qt, CH::Acc &acc) {
+            for_acc(acc, p, pt, qt, b, [&](int off, float v, int, int, int) { s0[off] = v; }); // U = (R D) B^T
+        });
+        big_mma<NS, true, false, false, false>(sm, tid, p, Ai, b, s0, b, nullptr, NoPre(), [&](int pt, int qt, CH::Acc &acc) {
+            for_acc(acc, p, pt, qt, ldw, [&](int off, float v, int, int, int) { Gij[off] = -2.f * v; }); // -2 A^T U
+        });
+        float ltot = CH::block_sum(lsum, sm.red, tid);
+        if (tid == 0) loss_part[blk] = ltot;
+    }
+}
+
 // ---- wrapper Grams -----------------------------------------------------------------------------
 template <int NS>
 __global__ __launch_bounds__(CH::NT) void big_wrapper_grams_kernel(
@@ -437,6 +597,23 @@ void launch_big_phase_WS(const Dims &d, const float *Wbar, float *C, const float
     else
         hipLaunchKernelGGL((big_phase_WS_kernel<2, false>), grid, block, 0, s, Wbar, C, A, B, D, AtA, K, mask,
                            mask_group, fro2A, d.nbi, fro2K, d.nbj, d.d_in, d.nbj, d.nblocks, Gout, loss_part, Sp, scratch);
+}
+
+void launch_big_phase_FB(const Dims &d, const float *Wbar, float *C, const float *A, const float *B, const float *D,
+                         const uint8_t *mask, int mask_group, float *mC, float *vC, double lr, double b1, double b2,
+                         double eps, int64_t t, int nsplit, float *gApart, float *gBpart, float *loss_part, int grid_cap,
+                         float *scratch, hipStream_t s) {
+    const AdamCoef k = make_adam_coef(lr, b1, b2, eps, t);
+    const int nitems = d.nbi * nsplit;
+    hipLaunchKernelGGL((big_phase_FB_kernel<2>), dim3(std::min(nitems, grid_cap)), dim3(CH::NT), 0, s, Wbar, C, A, B, D,
+                       mask, mask_group, mC, vC, k, d.d_in, d.nbi, d.nbj, nsplit, nitems, gApart, gBpart, loss_part,
+                       scratch);
+}
+
+void launch_big_phase_GS(const Dims &d, const float *Wbar, const float *C, const float *A, const float *B,
+                         const float *D, float *Gout, float *loss_part, int grid_cap, float *scratch, hipStream_t s) {
+    hipLaunchKernelGGL((big_phase_GS_kernel<2>), dim3(std::min(d.nblocks, grid_cap)), dim3(CH::NT), 0, s, Wbar, C, A, B,
+                       D, d.d_in, d.nbj, d.nblocks, Gout, loss_part, scratch);
 }
 
 void launch_big_wrapper_grams(const Dims &d, const float *A, const float *B, const float *D, float *colnorm2,

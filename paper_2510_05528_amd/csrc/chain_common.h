@@ -7,6 +7,18 @@ namespace armor {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
+// Adam coefficients of iteration t as the kernels use them (Sec. 3.3.1); inv_c = 1 / (1 - beta^t).
+struct AdamCoef {
+    float b1, b2, one_minus_b1, one_minus_b2, inv_c1, inv_c2, lr, eps;
+};
+inline AdamCoef make_adam_coef(double lr, double b1, double b2, double eps, int64_t t) {
+    AdamCoef k;
+    k.b1 = (float)b1; k.b2 = (float)b2; k.one_minus_b1 = (float)(1.0 - b1); k.one_minus_b2 = (float)(1.0 - b2);
+    k.inv_c1 = (float)(1.0 / (1.0 - pow(b1, (double)t))); k.inv_c2 = (float)(1.0 / (1.0 - pow(b2, (double)t)));
+    k.lr = (float)lr; k.eps = (float)eps;
+    return k;
+}
+
 // Hides a per-lane offset from loop-invariant code motion: without it the compiler hoists every
 // unrolled address of the epilogues out of the block loop and keeps hundreds of them live across
 // the matrix products (spilling accumulators), instead of re-deriving each with one add.

@@ -243,7 +243,8 @@ def test_unstructured_ties_go_to_lower_index(armor, torch, orc):
 
 
 @pytest.mark.parametrize("d_out,d_in,b,N,M,sparsity", [(128, 192, 64, 2, 4, 0), (256, 384, 128, 2, 4, 0), (96, 160, 32, 4, 8, 0),
-                                                        (128, 128, 64, 2, 4, 1)])
+                                                        (128, 128, 64, 2, 4, 1), (512, 768, 256, 2, 4, 0),
+                                                        (512, 512, 256, 2, 4, 1)])
 def test_factorize_joint_adam(armor, torch, orc, d_out, d_in, b, N, M, sparsity):
     """The joint-Adam continuous step (what the authors run in practice) against the oracle's.
 
