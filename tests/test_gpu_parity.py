@@ -359,3 +359,34 @@ def test_pack_nm_formats(armor, torch, orc, N, M, d_in):
     np.testing.assert_array_equal(vals.cpu().numpy(), ev)
     np.testing.assert_array_equal(meta.cpu().numpy(), orc.pack_index_bits(ei, M))
     np.testing.assert_array_equal(armor.unpack_meta(meta.cpu().numpy(), d_in, N, M), ei)
+
+
+def test_kernel_timing_counts_every_launch(armor, torch):
+    """The library's own HIP-event timing: one record per instrumented launch, positive times that add up
+    to no more than the wall time, nothing recorded when switched off."""
+    import time
+    W, X = make_layer(256, 256, 100, seed=3)
+    D = (X.astype(np.float64) ** 2).sum(0).astype(np.float32)
+    Wd, Dd = dev(torch, W), dev(torch, D)
+    armor.factorize_layer(Wd, Dd, 64, 2, 4, 1, seed=1)
+    torch.cuda.synchronize()
+    armor.profile_enable(True)
+    armor.profile_read()
+    try:
+        t0 = time.perf_counter()
+        armor.factorize_layer(Wd, Dd, 64, 2, 4, 3, seed=1)
+        armor.factorize_layer(Wd, Dd, 64, 2, 4, 2, seed=1, variant=1)
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3
+        prof = armor.profile_read()
+    finally:
+        armor.profile_enable(False)
+    expect = {"phase_A": 3, "phase_B": 3, "phase_WS": 3, "sparse_step": 5, "phase_FB": 2, "phase_GS": 2,
+              "small_kernels": 2 * 3 + 2, "normalize": 2, "init": 2, "gram": 0, "pack_nm": 0}
+    for k, n in expect.items():
+        assert prof[k][1] == n, (k, prof[k])
+        assert (prof[k][0] > 0) == (n > 0), (k, prof[k])
+    assert sum(ms for ms, _ in prof.values()) <= wall_ms
+    armor.factorize_layer(Wd, Dd, 64, 2, 4, 1, seed=1)
+    torch.cuda.synchronize()
+    assert all(n == 0 for _, n in armor.profile_read().values())

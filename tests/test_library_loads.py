@@ -72,3 +72,15 @@ def test_product_package_does_not_import_the_oracle():
             if f.endswith((".py", ".hip", ".h", ".cpp")):
                 src = open(os.path.join(dirpath, f)).read()
                 assert "import oracle" not in src and "from oracle" not in src and "liboracle" not in src, f
+
+
+def test_profiler_host_side():
+    """Switching the per-kernel timing on and off and reading it with nothing recorded touch no device."""
+    from paper_2510_05528_amd import binding
+    lib = binding.load_library()
+    assert lib.armor_profile_read(None, None) == 1
+    assert lib.armor_profile_enable(0) == 0
+    ms = (ctypes.c_double * len(binding.PROF_KINDS))(*([7.0] * len(binding.PROF_KINDS)))
+    cnt = (ctypes.c_int64 * len(binding.PROF_KINDS))(*([7] * len(binding.PROF_KINDS)))
+    assert lib.armor_profile_read(ms, cnt) == 0
+    assert list(ms) == [0.0] * len(binding.PROF_KINDS) and list(cnt) == [0] * len(binding.PROF_KINDS)
