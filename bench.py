@@ -61,7 +61,7 @@ BF16_MFMA_PEAK = 2.5e15    # MI355X dense bf16 matrix peak, FLOP/s
 # same counter reads for a plain 256 MiB device copy (factors 2.000 and 1.000); see
 # profiles/chain_kernels_llama7b_attn_pmc.txt.  Keyed by (workload, kernel); other workloads: null.
 MEASURED_TRAFFIC_BYTES = {
-    ("llama7b_attn_4096x4096_b128_2:4_50it", "phase_WS"): (273.9 + 135.0) * 2 ** 20,
+    ("llama7b_attn_4096x4096_b128_2:4_50it", "phase_WS"): (269.7 + 134.0) * 2 ** 20,
     ("llama7b_attn_4096x4096_b128_2:4_50it", "phase_A"): (186.2 + 16.1) * 2 ** 20,
     ("llama7b_attn_4096x4096_b128_2:4_50it", "phase_B"): (194.3 + 80.0) * 2 ** 20,
 }
@@ -241,8 +241,8 @@ def run_apply_workload(args, armor, synth, torch, dev):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=3)
-    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None, help="timed steps (default 3; 100 for the ~1 ms apply workloads)")
+    ap.add_argument("--warmup", type=int, default=None, help="untimed steps first (default 1; 20 for the apply workloads)")
     ap.add_argument("--workload", default=DEFAULT, choices=sorted(WORKLOADS) + sorted(BLOCK_WORKLOADS) + sorted(APPLY_WORKLOADS))
     ap.add_argument("--variant", default="gd", choices=["gd", "adam"],
                     help="continuous step: sequential 1/beta gradient steps (default; the monotone variant) or the "
@@ -257,6 +257,11 @@ def main():
                     help="only run a plain device copy of known size (256 MiB read + 256 MiB written, 3 times) "
                          "so that rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings can be scaled")
     args = ap.parse_args()
+    short = args.workload in APPLY_WORKLOADS  # a step of ~1 ms: a few of them would time the clock ramp
+    if args.steps is None:
+        args.steps = 100 if short else 3
+    if args.warmup is None:
+        args.warmup = 20 if short else 1
     if args.copy_calibration:
         import torch
         src = torch.ones(64 * 1024 * 1024, device="cuda:0", dtype=torch.float32)
