@@ -53,7 +53,7 @@ typedef struct {
     int32_t denormalize;        /* 1: fold r2 into the rows of A and r1 into the columns of B (Sec. 3.2) */
     int32_t variant;            /* continuous step (Sec. 3.3.1): 0 = sequential gradient steps with 1/beta step
                                    sizes (Alg. 2; monotone, default), 1 = joint Adam on A, B, W' (what the authors
-                                   run in practice; one forward/backward pass per iteration; d_block <= 128) */
+                                   run in practice; one forward/backward pass per iteration) */
     double lr;                  /* Adam learning rate; 0 = 1e-4 (App. F) */
     double adam_beta1;          /* 0 = 0.9   (the optimiser's published default; the paper gives none) */
     double adam_beta2;          /* 0 = 0.999 */
@@ -66,8 +66,11 @@ int armor_last_hip_error(void);
 
 /*
  * Optional per-kernel timing (host-side; not thread-safe; off by default).  While enabled, the
- * library brackets each instrumented kernel launch with two HIP events recorded on the caller's
- * stream (events are host resources created on first use and kept; no device memory).
+ * library brackets each instrumented kernel launch with HIP events recorded on the caller's
+ * stream (timing-only events, host resources created on first use and kept; no device memory).
+ * Inside the iteration loop of armor_factorize_layer and inside armor_apply_packed, consecutive
+ * launches share their boundary event: a launch is then timed from the end of its predecessor
+ * to its own end.
  * armor_profile_read() waits for the recorded events, returns per kind the summed elapsed
  * milliseconds and the number of launches into two HOST arrays of ARMOR_PROF_KINDS entries, and
  * resets the record.  Kinds: the Gram kernel (Sec. 2), the A-step and B-step chains of Alg. 2,
