@@ -255,7 +255,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_W_kernel(
         __syncthreads();
         CH::gload_tile(t0, Bw + (int64_t)j * B * B, B, tid);
         acc.zero();
-        CH::template mma<false, false, false>(acc, sm.Y, sm.X, nullptr, p); // S' = A C
+        CH::template mma<false, false, false, false>(acc, sm.Y, sm.X, nullptr, p); // S' = A C
         __syncthreads();
         CH::store_acc(sm.X, acc, p);
         CH::lstore_tile(sm.Y, t0, tid);
@@ -269,7 +269,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_W_kernel(
                     for (int r = 0; r < 16; ++r) wb[tm][tn][r] = Wij[opaque(woff) + CH::Pos::unif_off(tm, tn, r, ldw)];
             __syncthreads();
             acc.zero();
-            CH::template mma<false, false, false>(acc, sm.X, sm.Y, nullptr, p); // What = S' B
+            CH::template mma<false, false, false, false>(acc, sm.X, sm.Y, nullptr, p); // What = S' B
 #pragma unroll
             for (int tm = 0; tm < CH::TM; ++tm)
 #pragma unroll
@@ -284,7 +284,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_W_kernel(
         __syncthreads();
         CH::gload_tile(t0, A + (int64_t)i * B * B, B, tid);
         acc.zero();
-        CH::template mma<false, true, false>(acc, sm.X, sm.Y, nullptr, p); // U = (R D) B^T
+        CH::template mma<false, true, false, false>(acc, sm.X, sm.Y, nullptr, p); // U = (R D) B^T
         __syncthreads();
         CH::store_acc(sm.X, acc, p);
         CH::lstore_tile(sm.Y, t0, tid);
@@ -304,7 +304,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_W_kernel(
             CH::gload_tile(t0, C + (int64_t)(nblk / nbj) * B * d_in + (int64_t)(nblk % nbj) * B, ldw, tid);
         __syncthreads();
         acc.zero();
-        CH::template mma<true, false, false>(acc, sm.Y, sm.X, nullptr, p); // G = A^T U
+        CH::template mma<true, false, false, false>(acc, sm.Y, sm.X, nullptr, p); // G = A^T U
         {
             // C <- C + (2/beta) G on kept entries, as one coalesced float4 pass: G goes through LDS
             const float eta2 = read_eta_W(sm);
@@ -380,7 +380,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_WS_kernel(
             __syncthreads();
             CH::gload_tile(t0, Bw + (int64_t)j * B * B, B, tid);
             acc.zero();
-            CH::template mma<false, false, false>(acc, sm.Y, sm.X, nullptr, p); // S' = A C
+            CH::template mma<false, false, false, false>(acc, sm.Y, sm.X, nullptr, p); // S' = A C
             __syncthreads();
             CH::store_acc(sm.X, acc, p);
             CH::lstore_tile(sm.Y, t0, tid);
@@ -396,7 +396,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_WS_kernel(
                     for (int r = 0; r < 16; ++r) wb[tm][tn][r] = Wij[opaque(woff) + CH::Pos::unif_off(tm, tn, r, ldw)];
             __syncthreads();
             acc.zero();
-            CH::template mma<false, false, false>(acc, sm.X, sm.Y, nullptr, p); // What = S' B
+            CH::template mma<false, false, false, false>(acc, sm.X, sm.Y, nullptr, p); // What = S' B
 #pragma unroll
             for (int tm = 0; tm < CH::TM; ++tm)
 #pragma unroll
@@ -415,7 +415,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_WS_kernel(
         __syncthreads();
         CH::gload_tile(t0, A + (int64_t)i * B * B, B, tid);
         acc.zero();
-        CH::template mma<false, true, false>(acc, sm.X, sm.Y, nullptr, p); // U = (R D) B^T
+        CH::template mma<false, true, false, false>(acc, sm.X, sm.Y, nullptr, p); // U = (R D) B^T
         __syncthreads();
         CH::store_acc(sm.X, acc, p);
         CH::lstore_tile(sm.Y, t0, tid);
@@ -437,7 +437,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_WS_kernel(
         CH::gload_tile(t0, K + (int64_t)j * B * B, B, tid);
         __syncthreads();
         acc.zero();
-        CH::template mma<true, false, false>(acc, sm.Y, sm.X, nullptr, p); // G = A^T U   (stays in acc)
+        CH::template mma<true, false, false, false>(acc, sm.Y, sm.X, nullptr, p); // G = A^T U   (stays in acc)
         const float eta2 = read_eta_W(sm);
         // W' step on kept entries; Delta = G (.) M goes to LDS for the two extra products
         uint32_t keep[CH::TM][CH::TN];
@@ -466,7 +466,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_WS_kernel(
         __syncthreads();
         CH::gload_tile(t0, AtA + (int64_t)i * B * B, B, tid);
         acc2.zero();
-        CH::template mma<false, false, false>(acc2, sm.X, sm.Y, nullptr, p); // V = Delta K
+        CH::template mma<false, false, false, false>(acc2, sm.X, sm.Y, nullptr, p); // V = Delta K
         __syncthreads();
         CH::store_acc(sm.X, acc2, p);
         CH::lstore_tile(sm.Y, t0, tid); // A^T A (symmetric)
@@ -477,7 +477,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_WS_kernel(
             if (Sp != nullptr) CH::gload_tile(t1, Bw + (int64_t)(nblk % nbj) * B * B, B, tid);
         }
         acc2.zero();
-        CH::template mma<false, false, false>(acc2, sm.Y, sm.X, nullptr, p); // Z = (A^T A) V
+        CH::template mma<false, false, false, false>(acc2, sm.Y, sm.X, nullptr, p); // Z = (A^T A) V
         float dz = 0.f;
         {
             float *Gij = Gout + (int64_t)i * B * d_in + (int64_t)j * B;
@@ -538,7 +538,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_FB_kernel(
         __syncthreads();
         CH::gload_tile(t0, A + (int64_t)i * B * B, B, tid);
         acc.zero();
-        CH::template mma<false, false, false>(acc, sm.X, sm.Y, nullptr, p); // S = C B
+        CH::template mma<false, false, false, false>(acc, sm.X, sm.Y, nullptr, p); // S = C B
         __syncthreads();
         CH::store_acc(sm.X, acc, p);
         CH::lstore_tile(sm.Y, t0, tid);
@@ -553,7 +553,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_FB_kernel(
                     for (int r = 0; r < 16; ++r) wb[tm][tn][r] = Wij[opaque(woff) + CH::Pos::unif_off(tm, tn, r, ldw)];
             __syncthreads();
             acc.zero();
-            CH::template mma<false, false, false>(acc, sm.Y, sm.X, nullptr, p); // What = A S
+            CH::template mma<false, false, false, false>(acc, sm.Y, sm.X, nullptr, p); // What = A S
 #pragma unroll
             for (int tm = 0; tm < CH::TM; ++tm)
 #pragma unroll
@@ -572,13 +572,13 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_FB_kernel(
         CH::store_acc(sm.Y, acc, p); // R D          [X = S, Y = R D]
         __syncthreads();
         CH::gload_tile(t0, A + (int64_t)i * B * B, B, tid);
-        CH::template mma<false, true, false>(gacc, sm.Y, sm.X, nullptr, p); // grad_A += (R D) S^T
+        CH::template mma<false, true, false, false>(gacc, sm.Y, sm.X, nullptr, p); // grad_A += (R D) S^T
         __syncthreads();
         CH::lstore_tile(sm.X, t0, tid); //            [X = A, Y = R D]
         __syncthreads();
         CH::gload_tile(t0, Bw + (int64_t)j * B * B, B, tid);
         acc.zero();
-        CH::template mma<true, false, false>(acc, sm.X, sm.Y, nullptr, p); // T = A^T (R D)
+        CH::template mma<true, false, false, false>(acc, sm.X, sm.Y, nullptr, p); // T = A^T (R D)
         __syncthreads();
         CH::store_acc(sm.Y, acc, p);
         CH::lstore_tile(sm.X, t0, tid); //            [X = B, Y = T]
@@ -598,7 +598,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_FB_kernel(
                     for (int r = 0; r < 16; ++r) mraw[tm][tn][r] = mb[mlane + (tm * 32 + (r >> 2) * 8 + (r & 3)) * (int)mrow];
                 }
             acc.zero();
-            CH::template mma<false, true, false>(acc, sm.Y, sm.X, nullptr, p); // T B^T  (stays in acc for the core update)
+            CH::template mma<false, true, false, false>(acc, sm.Y, sm.X, nullptr, p); // T B^T  (stays in acc for the core update)
 #pragma unroll
             for (int tm = 0; tm < CH::TM; ++tm)
 #pragma unroll
@@ -615,7 +615,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_FB_kernel(
         __syncthreads();
         typename CH::Acc acc2;
         acc2.zero();
-        CH::template mma<true, false, false>(acc2, sm.X, sm.Y, nullptr, p); // C^T T
+        CH::template mma<true, false, false, false>(acc2, sm.X, sm.Y, nullptr, p); // C^T T
         {
             float *gb = gBpart + ((int64_t)j * nbi + i) * B * B;
 #pragma unroll

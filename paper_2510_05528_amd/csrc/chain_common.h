@@ -162,18 +162,36 @@ template <int B> struct Chain {
                     acc.v[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a[g][tm], f.b[g][tn], acc.v[tm][tn], 0, 0, 0);
     }
 
-    template <bool LT, bool RT, bool SCALE>
+    // PEEL: the last trip is peeled off the loop.  A fetch under a condition inside the loop splits it
+    // into blocks, and the wait in front of the next matrix instructions then has to cover the path
+    // without the fetch, i.e. it also waits for operands requested a moment ago (LDS-fed loop alone:
+    // 83 % of the fp32 matrix peak with the condition, 91 % peeled).  Inside a kernel the better form
+    // depends on what else is live around the product, so call sites choose by measurement.
+    template <bool LT, bool RT, bool SCALE, bool PEEL = true>
     __device__ static void mma(Acc &acc, const float *__restrict__ L, const float *__restrict__ R,
                                const float *__restrict__ Dk, const Pos &p) {
         static_assert(B % (4 * G) == 0, "two groups per trip");
         Frag f0, f1;
         fetch<LT, RT, SCALE>(f0, 0, L, R, Dk, p);
+        if constexpr (PEEL) {
 #pragma unroll 1
-        for (int k = 0; k < B; k += 4 * G) {
-            fetch<LT, RT, SCALE>(f1, k + 2 * G, L, R, Dk, p);
+            for (int k = 0; k < B - 4 * G; k += 4 * G) {
+                fetch<LT, RT, SCALE>(f1, k + 2 * G, L, R, Dk, p);
+                issue(acc, f0);
+                fetch<LT, RT, SCALE>(f0, k + 4 * G, L, R, Dk, p);
+                issue(acc, f1);
+            }
+            fetch<LT, RT, SCALE>(f1, B - 2 * G, L, R, Dk, p);
             issue(acc, f0);
-            if (k + 4 * G < B) fetch<LT, RT, SCALE>(f0, k + 4 * G, L, R, Dk, p);
             issue(acc, f1);
+        } else {
+#pragma unroll 1
+            for (int k = 0; k < B; k += 4 * G) {
+                fetch<LT, RT, SCALE>(f1, k + 2 * G, L, R, Dk, p);
+                issue(acc, f0);
+                if (k + 4 * G < B) fetch<LT, RT, SCALE>(f0, k + 4 * G, L, R, Dk, p);
+                issue(acc, f1);
+            }
         }
     }
 
