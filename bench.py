@@ -52,6 +52,7 @@ BLOCK_WORKLOADS = {
 APPLY_WORKLOADS = {
     "qwen14b_gate_apply_8192tok_b128_2:4": (13824, 5120, 8192, 128),
     "llama7b_attn_apply_8192tok_b128_2:4": (4096, 4096, 8192, 128),
+    "llama70b_gate_apply_8192tok_b256_2:4": (28672, 8192, 8192, 256),
 }
 
 FP32_MFMA_PEAK = 157.3e12  # MI355X dense fp32 matrix peak, FLOP/s
@@ -224,7 +225,8 @@ def run_apply_workload(args, armor, synth, torch, dev):
     if not args.no_cpu_baseline:
         import oracle
         oracle.build()
-        sample = 512 if d_out * d_in > 1 << 24 else 2048   # about 10-20 s of single-thread oracle time
+        # about 10-20 s of single-thread oracle time (44 tokens/s on the 13824 x 5120 layer)
+        sample = 2048 if d_out * d_in <= 1 << 24 else (512 if d_out * d_in <= 1 << 27 else 128)
         ev = vals[:, :].float().cpu().numpy()
         idx = armor.unpack_meta(meta.cpu().numpy(), d_in, 2, 4)
         c0 = time.perf_counter()

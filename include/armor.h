@@ -206,8 +206,9 @@ armor_status armor_pack_nm(const float *S, const uint8_t *mask_bits, int64_t d_o
  *   ws       armor_apply_workspace_bytes(n_tokens, d_in) bytes (holds B X in bf16)
  * Arithmetic: bf16 operands, fp32 accumulation; the two intermediates B x and S (B x) are rounded
  * to bf16 (round to nearest even) before the next product, Y is rounded once at the end.
- * Supported: N:M = 2:4 (the pattern the structured-sparse matrix instruction takes), d_block in
- * {32, 64, 128}, d_in a multiple of 64; anything else returns ARMOR_ERR_UNSUPPORTED.  All pointers
+ * Supported: N:M = 2:4 (the pattern the structured-sparse matrix instruction takes), d_in a multiple
+ * of 64; anything else returns ARMOR_ERR_UNSUPPORTED (d_block outside {32, 64, 128, 256}:
+ * ARMOR_ERR_SHAPE, as everywhere).  All pointers
  * are device pointers, 16-byte aligned; asynchronous on the stream; n_tokens = 0 is a no-op.
  */
 armor_status armor_to_bf16(const float *in, int64_t n, void *out_bf16, void *hip_stream);

@@ -116,15 +116,21 @@ __global__ __launch_bounds__(256) void apply_pre_kernel(const uint16_t *__restri
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, l32 = lane & 31, half = lane >> 5;
     const int j = blockIdx.y;
     const int64_t t0 = (int64_t)blockIdx.x * 256 + w * 64;
+    // The wave's two 32-token row tiles are processed together while operands and accumulators fit in
+    // the register file (b <= 128), one after the other at b = 256.
+    constexpr int RT = B <= 128 ? 2 : 1;
     // X operands of this wave first (the long latency), then B^j -> LDS underneath
-    uint4 xa[2][KS];
+    uint4 xa[RT][KS];
+    auto load_x = [&](int rt0) {
 #pragma unroll
-    for (int rt = 0; rt < 2; ++rt) {
-        const int64_t trow = min(t0 + 32 * rt + l32, n - 1); // clamped: rows past the end are computed and dropped
-        const uint16_t *xrow = X + trow * d_in + (int64_t)j * B + 8 * half;
+        for (int rt = 0; rt < RT; ++rt) {
+            const int64_t trow = min(t0 + 32 * (rt0 + rt) + l32, n - 1); // clamped: rows past the end are computed and dropped
+            const uint16_t *xrow = X + trow * d_in + (int64_t)j * B + 8 * half;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) xa[rt][ks] = *reinterpret_cast<const uint4 *>(xrow + 16 * ks);
-    }
+            for (int ks = 0; ks < KS; ++ks) xa[rt][ks] = *reinterpret_cast<const uint4 *>(xrow + 16 * ks);
+        }
+    };
+    load_x(0);
     {
         const uint16_t *bj = Bw + (int64_t)j * B * B;
         constexpr int CH = B * B / 8; // 16-byte chunks
@@ -135,40 +141,46 @@ __global__ __launch_bounds__(256) void apply_pre_kernel(const uint16_t *__restri
         }
     }
     __syncthreads();
-    floatx16 acc[2][PT];
-#pragma unroll
-    for (int rt = 0; rt < 2; ++rt)
-#pragma unroll
-        for (int pt = 0; pt < PT; ++pt)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[rt][pt][r] = 0.f;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-#pragma unroll
-        for (int pt = 0; pt < PT; ++pt) {
-            const bf16x8 bb = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(lb + (pt * 32 + l32) * PITCH + (16 * ks + 8 * half) * 2));
-#pragma unroll
-            for (int rt = 0; rt < 2; ++rt)
-                acc[rt][pt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, xa[rt][ks]), bb, acc[rt][pt], 0, 0, 0);
-        }
-    }
     const int q4 = lane & 3; // after the transpose this lane holds row (4g + q4) of each group of 4 rows
+#pragma unroll 1
+    for (int rt0 = 0; rt0 < 2; rt0 += RT) {
+        if (rt0 > 0) load_x(rt0);
+        floatx16 acc[RT][PT];
 #pragma unroll
-    for (int rt = 0; rt < 2; ++rt)
+        for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
-        for (int pt = 0; pt < PT; ++pt)
+            for (int pt = 0; pt < PT; ++pt)
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                float x[4] = {acc[rt][pt][4 * g], acc[rt][pt][4 * g + 1], acc[rt][pt][4 * g + 2], acc[rt][pt][4 * g + 3]};
-                quad_transpose(x, lane);
-                const int64_t t = t0 + 32 * rt + 8 * g + 4 * half + q4;
-                const int64_t col = (int64_t)j * B + pt * 32 + (l32 & ~3); // first of the 4 columns
-                const int within = (int)(col & 63), slot = (within >> 3) ^ key_acts((int)(t & 255));
-                uint2 pk;
-                pk.x = pack_bf16x2_rne(x[0], x[1]);
-                pk.y = pack_bf16x2_rne(x[2], x[3]);
-                if (t < n) *reinterpret_cast<uint2 *>(U + ((col >> 6) * n_pad + t) * 128 + slot * 16 + (within & 7) * 2) = pk;
+                for (int r = 0; r < 16; ++r) acc[rt][pt][r] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+            for (int pt = 0; pt < PT; ++pt) {
+                const bf16x8 bb = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(lb + (pt * 32 + l32) * PITCH + (16 * ks + 8 * half) * 2));
+#pragma unroll
+                for (int rt = 0; rt < RT; ++rt)
+                    acc[rt][pt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, xa[rt][ks]), bb, acc[rt][pt], 0, 0, 0);
             }
+            // b = 256: keep the scheduler from hoisting all 128 operand reads above the matrix work
+            if (B > 128 && (ks & 1)) __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+            for (int pt = 0; pt < PT; ++pt)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    float x[4] = {acc[rt][pt][4 * g], acc[rt][pt][4 * g + 1], acc[rt][pt][4 * g + 2], acc[rt][pt][4 * g + 3]};
+                    quad_transpose(x, lane);
+                    const int64_t t = t0 + 32 * (rt0 + rt) + 8 * g + 4 * half + q4;
+                    const int64_t col = (int64_t)j * B + pt * 32 + (l32 & ~3); // first of the 4 columns
+                    const int within = (int)(col & 63), slot = (within >> 3) ^ key_acts((int)(t & 255));
+                    uint2 pk;
+                    pk.x = pack_bf16x2_rne(x[0], x[1]);
+                    pk.y = pack_bf16x2_rne(x[2], x[3]);
+                    if (t < n) *reinterpret_cast<uint2 *>(U + ((col >> 6) * n_pad + t) * 128 + slot * 16 + (within & 7) * 2) = pk;
+                }
+    }
 }
 
 void launch_apply_pre(const void *X, int64_t n, int64_t d_in, int b, const void *Bw, void *U, hipStream_t s) {
@@ -180,6 +192,7 @@ void launch_apply_pre(const void *X, int64_t n, int64_t d_in, int b, const void 
     case 32: hipLaunchKernelGGL(apply_pre_kernel<32>, grid, dim3(256), 0, s, x, n, d_in, bw, u, n_pad); break;
     case 64: hipLaunchKernelGGL(apply_pre_kernel<64>, grid, dim3(256), 0, s, x, n, d_in, bw, u, n_pad); break;
     case 128: hipLaunchKernelGGL(apply_pre_kernel<128>, grid, dim3(256), 0, s, x, n, d_in, bw, u, n_pad); break;
+    case 256: hipLaunchKernelGGL(apply_pre_kernel<256>, grid, dim3(256), 0, s, x, n, d_in, bw, u, n_pad); break;
     default: break;
     }
 }
@@ -196,9 +209,11 @@ void launch_apply_pre(const void *X, int64_t n, int64_t d_in, int b, const void 
 // Sparse operand of the instruction: lane (row, h) = the 8 kept values of dense k in [16h, 16h+16)
 // of the 32-k step and their 16 index bits; dense operand: lane (token, h) = k in [8h, 8h+8) and
 // [16+8h, 16+8h+8).
-// Epilogue: each wave's 128 rows are whole blocks of A (b <= 128), so it needs only its own V patch:
-// written to LDS as [token][q] bf16, multiplied by A^i with the dense bf16 instruction (rows =
-// tokens, columns = p), stored like the kernel above.
+// Epilogue: each wave's V patch is written to LDS as [token][q] bf16 and multiplied by A^i with the
+// dense bf16 instruction (rows = tokens, columns = p), stored like the kernel above.  Up to b = 128
+// a wave's 128 rows are whole blocks of A and it needs only its own patch; at b = 256 the tile is
+// one block of A and a wave also reads the patch of the wave that holds the other 128 rows of the
+// same tokens.
 // ------------------------------------------------------------------------------------------------
 constexpr int AP_TM = 256, AP_TN = 256, AP_KT = 64;
 constexpr int AP_SUP_R = 8, AP_SUP_T = 4; // super-tile of one XCD: 8 row tiles x 4 token tiles = 32 workgroups
@@ -351,19 +366,28 @@ __global__ __launch_bounds__(512) void apply_main_kernel(const uint8_t *__restri
                 *reinterpret_cast<uint2 *>(vbuf + (32 * tn + l32) * AP_V_PITCH + (32 * tm + 8 * g + 4 * half) * 2) = pk;
             }
     const int64_t prow0 = row0 + 128 * wm; // first output column (row of S) of this wave
-    // all wrapper operands of the wave in one round of loads (the accumulators are dead by now)
-    uint4 afrag[4][B / 16];
+    // wrapper operands: all of the wave's in one round of loads up to b = 128 (the accumulators are dead
+    // by now), one 32-column tile at a time at b = 256 (64 registers each)
+    constexpr int APT = B <= 128 ? 4 : 1, AKS = B / 16;
+    uint4 afrag[APT][AKS];
+    auto load_afrag = [&](int pt0) {
 #pragma unroll
-    for (int pt = 0; pt < 4; ++pt) {
-        const int64_t pclamped = min(prow0 + pt * 32 + l32, d_out - 1);
-        const uint16_t *arow = Aw + pclamped * B + 8 * half; // A^i[p][q]: (i*b + p)*b + q = prow*b + (q - q0)
+        for (int pt = 0; pt < APT; ++pt) {
+            const int64_t pclamped = min(prow0 + (pt0 + pt) * 32 + l32, d_out - 1);
+            // A^i[p][q] sits at (i*b + p)*b + q = prow*b + q, q counted from the block's first column
+            const uint16_t *arow = Aw + pclamped * B + 8 * half;
 #pragma unroll
-        for (int ks = 0; ks < B / 16; ++ks) afrag[pt][ks] = *reinterpret_cast<const uint4 *>(arow + 16 * ks);
-    }
+            for (int ks = 0; ks < AKS; ++ks) afrag[pt][ks] = *reinterpret_cast<const uint4 *>(arow + 16 * ks);
+        }
+    };
+    load_afrag(0);
     __syncthreads();
+    // V patches by 128-row half of the tile: this wave's own and, at b = 256, its partner's (same tokens)
+    const uint8_t *vhalf[2] = {lds + (0 + 2 * wn) * (64 * AP_V_PITCH), lds + (1 + 2 * wn) * (64 * AP_V_PITCH)};
 #pragma unroll
     for (int pt = 0; pt < 4; ++pt) {
-        const int q0 = (pt * 32 / B) * B; // first q of the block of A that holds these 32 columns
+        if (APT == 1 && pt > 0) load_afrag(pt);
+        const int q0 = B <= 128 ? (pt * 32 / B) * B : 0; // first q (in this wave's patch) of the block of A that holds these 32 columns
         const int64_t prow = prow0 + pt * 32 + l32;
         floatx16 o[2];
 #pragma unroll
@@ -371,12 +395,15 @@ __global__ __launch_bounds__(512) void apply_main_kernel(const uint8_t *__restri
 #pragma unroll
             for (int r = 0; r < 16; ++r) o[tn][r] = 0.f;
 #pragma unroll
-        for (int ks = 0; ks < B / 16; ++ks) {
-            const bf16x8 bb = __builtin_bit_cast(bf16x8, afrag[pt][ks]);
+        for (int ks = 0; ks < AKS; ++ks) {
+            const bf16x8 bb = __builtin_bit_cast(bf16x8, afrag[APT == 1 ? 0 : pt][ks]);
+            // b <= 128: q0 + 16 ks lies in this wave's patch; b = 256: k steps 0..7 in the patch of rows 0..127, 8..15 in the other
+            const uint8_t *vsrc = B <= 128 ? vbuf : vhalf[ks / 8];
+            const int qoff = B <= 128 ? q0 + 16 * ks : 16 * (ks % 8);
 #pragma unroll
             for (int tn = 0; tn < 2; ++tn) {
                 const bf16x8 a = __builtin_bit_cast(
-                    bf16x8, *reinterpret_cast<const uint4 *>(vbuf + (32 * tn + l32) * AP_V_PITCH + (q0 + 16 * ks + 8 * half) * 2));
+                    bf16x8, *reinterpret_cast<const uint4 *>(vsrc + (32 * tn + l32) * AP_V_PITCH + (qoff + 8 * half) * 2));
                 o[tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bb, o[tn], 0, 0, 0);
             }
         }
@@ -421,6 +448,7 @@ hipError_t launch_apply_main(const void *U, int64_t n, int64_t d_in, int64_t d_o
     case 32: hipLaunchKernelGGL(apply_main_kernel<32>, grid, block, 0, s, u, n, d_in, d_out, pr, aw, y, n_row_tiles, n_tok_tiles); break;
     case 64: hipLaunchKernelGGL(apply_main_kernel<64>, grid, block, 0, s, u, n, d_in, d_out, pr, aw, y, n_row_tiles, n_tok_tiles); break;
     case 128: hipLaunchKernelGGL(apply_main_kernel<128>, grid, block, 0, s, u, n, d_in, d_out, pr, aw, y, n_row_tiles, n_tok_tiles); break;
+    case 256: hipLaunchKernelGGL(apply_main_kernel<256>, grid, block, 0, s, u, n, d_in, d_out, pr, aw, y, n_row_tiles, n_tok_tiles); break;
     default: return hipErrorInvalidValue;
     }
     return hipSuccess;

@@ -567,7 +567,7 @@ static armor_status validate_apply(int64_t d_out, int64_t d_in, int64_t d_block,
     if (d_out <= 0 || d_in <= 0) return ARMOR_ERR_SHAPE;
     if (d_block > 0 && (d_out % d_block != 0 || d_in % d_block != 0)) return ARMOR_ERR_SHAPE;
     if (N != 2 || M != 4) return ARMOR_ERR_UNSUPPORTED;
-    if (d_block > 0 && d_block != 32 && d_block != 64 && d_block != 128) return ARMOR_ERR_UNSUPPORTED;
+    if (d_block > 0 && d_block != 32 && d_block != 64 && d_block != 128 && d_block != 256) return ARMOR_ERR_SHAPE;
     if (d_in % 64 != 0) return ARMOR_ERR_UNSUPPORTED;
     if (d_out >= (int64_t)1 << 31 || d_in >= (int64_t)1 << 31) return ARMOR_ERR_SHAPE;
     return ARMOR_OK;

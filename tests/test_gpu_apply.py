@@ -89,7 +89,8 @@ def run_case(armor, torch, orc, dev, n, d_out, d_in, b, seed):
 
 
 @pytest.mark.parametrize("n,d_out,d_in,b", [(300, 512, 768, 128), (1000, 384, 640, 64), (64, 96, 128, 32),
-                                            (257, 256, 64, 32), (5, 128, 192, 64), (513, 640, 256, 128)])
+                                            (257, 256, 64, 32), (5, 128, 192, 64), (513, 640, 256, 128),
+                                            (300, 512, 768, 256), (700, 768, 256, 256)])
 def test_apply_packed_matches_oracle(env, orc, n, d_out, d_in, b):
     """Several row tiles and token tiles, ragged tails in both, every wrapper block size, one-stage K."""
     armor, torch, dev = env

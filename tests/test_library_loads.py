@@ -59,7 +59,7 @@ def test_status_strings_and_host_side_validation():
     assert lib.armor_apply_packed(None, 1, p, p, p, 64, 64, 32, 2, 4, p, p, 1 << 20, None) == 1
     assert lib.armor_apply_packed(p, 1, p, p, p, 64, 64, 32, 4, 8, p, p, 1 << 20, None) == 7      # only 2:4
     assert lib.armor_apply_packed(p, 1, p, p, p, 64, 96, 32, 2, 4, p, p, 1 << 20, None) == 7      # d_in % 64
-    assert lib.armor_apply_packed(p, 1, p, p, p, 256, 256, 256, 2, 4, p, p, 1 << 20, None) == 7   # block 256
+    assert lib.armor_apply_packed(p, 1, p, p, p, 192, 192, 96, 2, 4, p, p, 1 << 20, None) == 2     # block size
     assert lib.armor_apply_packed(p, 1, p, p, p, 64, 64, 48, 2, 4, p, p, 1 << 20, None) == 2
     assert lib.armor_apply_packed(p, 4, p, p, p, 64, 64, 32, 2, 4, p, p, 16, None) == 4            # workspace too small
 
