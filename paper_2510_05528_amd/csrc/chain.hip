@@ -42,7 +42,8 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_A_kernel(
     __shared__ Smem<B> sm;
     const int tid = threadIdx.x;
     const typename CH::Pos p(tid);
-    const int ldw = (int)d_in, woff = p.lane_off(ldw);
+    const int ldw = (int)d_in;
+    const uint32_t wboff = p.lane_boff(ldw);
     const int i = blockIdx.x / nsplit, c = blockIdx.x % nsplit;
     const int chunk = (nbj + nsplit - 1) / nsplit;
     const int j0 = c * chunk, j1 = min(nbj, j0 + chunk);
@@ -85,7 +86,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_A_kernel(
 #pragma unroll
             for (int tn = 0; tn < CH::TN; ++tn)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) wb[tm][tn][r] = Wij[opaque(woff) + CH::Pos::unif_off(tm, tn, r, ldw)];
+                for (int r = 0; r < 16; ++r) wb[tm][tn][r] = gld(Wij, opaque_u(wboff) + CH::Pos::unif_boff(tm, tn, r, ldw));
         __syncthreads();
         acc.zero();
         CH::template mma<false, false, false>(acc, sm.Y, sm.X, nullptr, p); // A (S sqrt D)
@@ -126,7 +127,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_A_kernel(
 #pragma unroll
             for (int tn = 0; tn < CH::TN; ++tn)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) gp[opaque(p.lane_off(B)) + CH::Pos::unif_off(tm, tn, r, B)] = -2.f * gacc.v[tm][tn][r];
+                for (int r = 0; r < 16; ++r) gst(gp, opaque_u(p.lane_boff(B)) + CH::Pos::unif_boff(tm, tn, r, B), -2.f * gacc.v[tm][tn][r]);
     }
 }
 
@@ -145,7 +146,8 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_B_kernel(
     __shared__ Smem<B> sm;
     const int tid = threadIdx.x;
     const typename CH::Pos p(tid);
-    const int ldw = (int)d_in, woff = p.lane_off(ldw);
+    const int ldw = (int)d_in;
+    const uint32_t wboff = p.lane_boff(ldw);
     const int j = blockIdx.x / nsplit, c = blockIdx.x % nsplit;
     const int chunk = (nbi + nsplit - 1) / nsplit;
     const int i0 = c * chunk, i1 = min(nbi, i0 + chunk);
@@ -178,7 +180,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_B_kernel(
 #pragma unroll
                 for (int tn = 0; tn < CH::TN; ++tn)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) Sij[opaque(woff) + CH::Pos::unif_off(tm, tn, r, ldw)] = acc.v[tm][tn][r];
+                    for (int r = 0; r < 16; ++r) gst(Sij, opaque_u(wboff) + CH::Pos::unif_boff(tm, tn, r, ldw), acc.v[tm][tn][r]);
         }
         CH::lstore_tile(sm.Y, t0, tid);
         float wb[CH::TM][CH::TN][16];
@@ -187,7 +189,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_B_kernel(
 #pragma unroll
             for (int tn = 0; tn < CH::TN; ++tn)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) wb[tm][tn][r] = Wij[opaque(woff) + CH::Pos::unif_off(tm, tn, r, ldw)];
+                for (int r = 0; r < 16; ++r) wb[tm][tn][r] = gld(Wij, opaque_u(wboff) + CH::Pos::unif_boff(tm, tn, r, ldw));
         __syncthreads();
         acc.zero();
         CH::template mma<false, false, false>(acc, sm.X, sm.Y, nullptr, p); // What = S' B
@@ -219,7 +221,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_B_kernel(
 #pragma unroll
         for (int tn = 0; tn < CH::TN; ++tn)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) gp[opaque(p.lane_off(B)) + CH::Pos::unif_off(tm, tn, r, B)] = -2.f * gacc.v[tm][tn][r];
+            for (int r = 0; r < 16; ++r) gst(gp, opaque_u(p.lane_boff(B)) + CH::Pos::unif_boff(tm, tn, r, B), -2.f * gacc.v[tm][tn][r]);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -237,7 +239,8 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_W_kernel(
     __shared__ Smem<B> sm;
     const int tid = threadIdx.x;
     const typename CH::Pos p(tid);
-    const int ldw = (int)d_in, woff = p.lane_off(ldw);
+    const int ldw = (int)d_in;
+    const uint32_t wboff = p.lane_boff(ldw);
     typename CH::Acc acc;
     typename CH::TileRegs t0, tc;
     const int64_t mrow = d_in / mask_group;
@@ -266,7 +269,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_W_kernel(
 #pragma unroll
                 for (int tn = 0; tn < CH::TN; ++tn)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) wb[tm][tn][r] = Wij[opaque(woff) + CH::Pos::unif_off(tm, tn, r, ldw)];
+                    for (int r = 0; r < 16; ++r) wb[tm][tn][r] = gld(Wij, opaque_u(wboff) + CH::Pos::unif_boff(tm, tn, r, ldw));
             __syncthreads();
             acc.zero();
             CH::template mma<false, false, false, false>(acc, sm.X, sm.Y, nullptr, p); // What = S' B
@@ -354,7 +357,8 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_WS_kernel(
     __shared__ Smem<B> sm;
     const int tid = threadIdx.x;
     const typename CH::Pos p(tid);
-    const int ldw = (int)d_in, woff = p.lane_off(ldw);
+    const int ldw = (int)d_in;
+    const uint32_t wboff = p.lane_boff(ldw);
     typename CH::Acc acc, acc2;
     typename CH::TileRegs t0, t1;
     const int64_t mrow = d_in / mask_group;
@@ -388,12 +392,13 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_WS_kernel(
         float lsum = 0.f;
         {
             float wb[CH::TM][CH::TN][16];
+            const uint32_t lb = opaque_u(wboff);
 #pragma unroll
             for (int tm = 0; tm < CH::TM; ++tm)
 #pragma unroll
                 for (int tn = 0; tn < CH::TN; ++tn)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) wb[tm][tn][r] = Wij[opaque(woff) + CH::Pos::unif_off(tm, tn, r, ldw)];
+                    for (int r = 0; r < 16; ++r) wb[tm][tn][r] = gld(Wij, lb + CH::Pos::unif_boff(tm, tn, r, ldw));
             __syncthreads();
             acc.zero();
             CH::template mma<false, false, false, false>(acc, sm.X, sm.Y, nullptr, p); // What = S' B
@@ -422,18 +427,22 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_WS_kernel(
         // current core values and mask bytes in the accumulator layout, underneath the next product
         float cv[CH::TM][CH::TN][16];
         uint32_t mraw[CH::TM][CH::TN][16];
+        {
+            const uint32_t lb = opaque_u(wboff);
+            // mask bytes: uniform block base + 32-bit lane offset (b is a multiple of the group size)
+            const uint8_t *mb = mask + (int64_t)i * B * mrow + (int64_t)j * B / mask_group;
 #pragma unroll
-        for (int tm = 0; tm < CH::TM; ++tm)
+            for (int tm = 0; tm < CH::TM; ++tm)
 #pragma unroll
-            for (int tn = 0; tn < CH::TN; ++tn) {
-                const int64_t gcol = (int64_t)j * B + p.col(tn);
-                const uint8_t *mp = mask + ((int64_t)i * B + opaque(p.wm0 + p.kh * 4)) * mrow + gcol / mask_group;
+                for (int tn = 0; tn < CH::TN; ++tn) {
+                    const uint32_t ml = opaque_u((uint32_t)((p.wm0 + p.kh * 4) * (int)mrow + p.col(tn) / mask_group));
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    cv[tm][tn][r] = Cij[opaque(woff) + CH::Pos::unif_off(tm, tn, r, ldw)];
-                    mraw[tm][tn][r] = mp[(int64_t)(tm * 32 + (r >> 2) * 8 + (r & 3)) * mrow];
+                    for (int r = 0; r < 16; ++r) {
+                        cv[tm][tn][r] = gld(Cij, lb + CH::Pos::unif_boff(tm, tn, r, ldw));
+                        mraw[tm][tn][r] = gld(mb, ml + (uint32_t)((tm * 32 + (r >> 2) * 8 + (r & 3)) * (int)mrow));
+                    }
                 }
-            }
+        }
         CH::gload_tile(t0, K + (int64_t)j * B * B, B, tid);
         __syncthreads();
         acc.zero();
@@ -445,6 +454,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_WS_kernel(
         __syncthreads();
         {
             float *d0 = sm.X + opaque(p.lane_off(CH::P));
+            const uint32_t lb = opaque_u(wboff);
 #pragma unroll
             for (int tm = 0; tm < CH::TM; ++tm)
 #pragma unroll
@@ -458,7 +468,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_WS_kernel(
                         const float dl = kp ? acc.v[tm][tn][r] : 0.f;
                         dd += dl * dl;
                         d0[CH::Pos::unif_off(tm, tn, r, CH::P)] = dl;
-                        if (kp) Cij[opaque(woff) + CH::Pos::unif_off(tm, tn, r, ldw)] = cv[tm][tn][r] + eta2 * dl;
+                        if (kp) gst(Cij, lb + CH::Pos::unif_boff(tm, tn, r, ldw), cv[tm][tn][r] + eta2 * dl);
                     }
                 }
         }
@@ -481,6 +491,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_WS_kernel(
         float dz = 0.f;
         {
             float *Gij = Gout + (int64_t)i * B * d_in + (int64_t)j * B;
+            const uint32_t lb = opaque_u(wboff);
 #pragma unroll
             for (int tm = 0; tm < CH::TM; ++tm)
 #pragma unroll
@@ -489,7 +500,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_WS_kernel(
                     for (int r = 0; r < 16; ++r) {
                         const float g = acc.v[tm][tn][r], z = acc2.v[tm][tn][r];
                         if ((keep[tm][tn] >> r) & 1u) dz += g * z;
-                        Gij[opaque(woff) + CH::Pos::unif_off(tm, tn, r, ldw)] = -2.f * (g - eta2 * z);
+                        gst(Gij, lb + CH::Pos::unif_boff(tm, tn, r, ldw), -2.f * (g - eta2 * z));
                     }
         }
         float ltot = CH::block_sum(lsum - 2.f * eta2 * dd + eta2 * eta2 * dz, sm.red, tid);
@@ -517,7 +528,8 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_FB_kernel(
     __shared__ Smem<B> sm;
     const int tid = threadIdx.x;
     const typename CH::Pos p(tid);
-    const int ldw = (int)d_in, woff = p.lane_off(ldw);
+    const int ldw = (int)d_in;
+    const uint32_t wboff = p.lane_boff(ldw);
     const int i = blockIdx.x / nsplit, c = blockIdx.x % nsplit;
     const int chunk = (nbj + nsplit - 1) / nsplit;
     const int j0 = c * chunk, j1 = min(nbj, j0 + chunk);
@@ -550,7 +562,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_FB_kernel(
 #pragma unroll
                 for (int tn = 0; tn < CH::TN; ++tn)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) wb[tm][tn][r] = Wij[opaque(woff) + CH::Pos::unif_off(tm, tn, r, ldw)];
+                    for (int r = 0; r < 16; ++r) wb[tm][tn][r] = gld(Wij, opaque_u(wboff) + CH::Pos::unif_boff(tm, tn, r, ldw));
             __syncthreads();
             acc.zero();
             CH::template mma<false, false, false, false>(acc, sm.Y, sm.X, nullptr, p); // What = A S
@@ -593,9 +605,10 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_FB_kernel(
                 for (int tn = 0; tn < CH::TN; ++tn) {
                     // uniform block base + 32-bit lane offset (B is a multiple of the group size)
                     const uint8_t *mb = mask + (int64_t)i * B * mrow + (int64_t)j * B / mask_group;
-                    const int mlane = opaque((p.wm0 + p.kh * 4) * (int)mrow + p.col(tn) / mask_group);
+                    const uint32_t mlane = opaque_u((uint32_t)((p.wm0 + p.kh * 4) * (int)mrow + p.col(tn) / mask_group));
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) mraw[tm][tn][r] = mb[mlane + (tm * 32 + (r >> 2) * 8 + (r & 3)) * (int)mrow];
+                    for (int r = 0; r < 16; ++r)
+                        mraw[tm][tn][r] = gld(mb, mlane + (uint32_t)((tm * 32 + (r >> 2) * 8 + (r & 3)) * (int)mrow));
                 }
             acc.zero();
             CH::template mma<false, true, false, false>(acc, sm.Y, sm.X, nullptr, p); // T B^T  (stays in acc for the core update)
@@ -624,7 +637,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_FB_kernel(
                 for (int tn = 0; tn < CH::TN; ++tn)
 #pragma unroll
                     for (int r = 0; r < 16; ++r)
-                        gb[opaque(p.lane_off(B)) + CH::Pos::unif_off(tm, tn, r, B)] = -2.f * acc2.v[tm][tn][r];
+                        gst(gb, opaque_u(p.lane_boff(B)) + CH::Pos::unif_boff(tm, tn, r, B), -2.f * acc2.v[tm][tn][r]);
         }
         __builtin_amdgcn_sched_barrier(0); // keep the moment loads below the product: they would not fit beside it
         float mo[CH::TM][CH::TN][16], vo[CH::TM][CH::TN][16];
@@ -634,9 +647,9 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_FB_kernel(
             for (int tn = 0; tn < CH::TN; ++tn)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    const int off = opaque(woff) + CH::Pos::unif_off(tm, tn, r, ldw);
-                    mo[tm][tn][r] = mij[off];
-                    vo[tm][tn][r] = vij[off];
+                    const uint32_t off = opaque_u(wboff) + CH::Pos::unif_boff(tm, tn, r, ldw);
+                    mo[tm][tn][r] = gld(mij, off);
+                    vo[tm][tn][r] = gld(vij, off);
                 }
         if (j + 1 < j1) // next block's core tile, underneath the core update below
             CH::gload_tile(t0, C + (int64_t)i * B * d_in + (int64_t)(j + 1) * B, ldw, tid);
@@ -648,16 +661,16 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_FB_kernel(
                 for (int tn = 0; tn < CH::TN; ++tn) {
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
-                        const int off = opaque(woff) + CH::Pos::unif_off(tm, tn, r, ldw);
+                        const uint32_t off = opaque_u(wboff) + CH::Pos::unif_boff(tm, tn, r, ldw);
                         const bool kp = (keep[tm][tn] >> r) & 1u;
                         const float g = kp ? -2.f * acc.v[tm][tn][r] : 0.f;
                         const float mn = k.b1 * mo[tm][tn][r] + k.one_minus_b1 * g;
                         const float vn = k.b2 * vo[tm][tn][r] + k.one_minus_b2 * g * g;
-                        mij[off] = mn;
-                        vij[off] = vn;
+                        gst(mij, off, mn);
+                        gst(vij, off, vn);
                         if (kp)
-                            Cij[off] = c0[CH::Pos::unif_off(tm, tn, r, CH::P)] -
-                                       k.lr * (mn * k.inv_c1) / (sqrtf(vn * k.inv_c2) + k.eps);
+                            gst(Cij, off, c0[CH::Pos::unif_off(tm, tn, r, CH::P)] -
+                                              k.lr * (mn * k.inv_c1) / (sqrtf(vn * k.inv_c2) + k.eps));
                     }
                 }
         }
@@ -671,7 +684,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_FB_kernel(
 #pragma unroll
         for (int tn = 0; tn < CH::TN; ++tn)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) gp[opaque(p.lane_off(B)) + CH::Pos::unif_off(tm, tn, r, B)] = -2.f * gacc.v[tm][tn][r];
+            for (int r = 0; r < 16; ++r) gst(gp, opaque_u(p.lane_boff(B)) + CH::Pos::unif_boff(tm, tn, r, B), -2.f * gacc.v[tm][tn][r]);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -688,7 +701,8 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_GS_kernel(
     __shared__ Smem<B> sm;
     const int tid = threadIdx.x;
     const typename CH::Pos p(tid);
-    const int ldw = (int)d_in, woff = p.lane_off(ldw);
+    const int ldw = (int)d_in;
+    const uint32_t wboff = p.lane_boff(ldw);
     typename CH::Acc acc;
     typename CH::TileRegs t0, t1;
     int blk = blockIdx.x;
@@ -717,7 +731,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_GS_kernel(
 #pragma unroll
                 for (int tn = 0; tn < CH::TN; ++tn)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) wb[tm][tn][r] = Wij[opaque(woff) + CH::Pos::unif_off(tm, tn, r, ldw)];
+                    for (int r = 0; r < 16; ++r) wb[tm][tn][r] = gld(Wij, opaque_u(wboff) + CH::Pos::unif_boff(tm, tn, r, ldw));
             __syncthreads();
             acc.zero();
             CH::template mma<false, false, false>(acc, sm.X, sm.Y, nullptr, p); // What = S' B
@@ -759,7 +773,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_GS_kernel(
             for (int tn = 0; tn < CH::TN; ++tn)
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
-                    Gij[opaque(woff) + CH::Pos::unif_off(tm, tn, r, ldw)] = -2.f * acc.v[tm][tn][r];
+                    gst(Gij, opaque_u(wboff) + CH::Pos::unif_boff(tm, tn, r, ldw), -2.f * acc.v[tm][tn][r]);
         __syncthreads();
     }
 }

@@ -70,8 +70,8 @@ __device__ __forceinline__ void big_mma(Smem<TB> &sm, int tid, const CH::Pos &p,
         }
 }
 
-// visit every accumulator element of output sub-tile (pt, qt): f(off, value&) with off the element
-// offset in a row-major matrix of leading dimension ld
+// visit every accumulator element of output sub-tile (pt, qt): f(off, value, ...) with off the byte
+// offset (for gld / gst) in a row-major fp32 matrix of leading dimension ld
 struct NoPre {
     __device__ void operator()(int, int) const {}
 };
@@ -82,24 +82,24 @@ struct Patch {
 };
 __device__ __forceinline__ void load_patch(Patch &w, const float *__restrict__ g, const CH::Pos &p, int pt, int qt,
                                            int ld) {
-    const int base = opaque((pt * TB + p.wm0 + p.kh * 4) * ld + qt * TB + p.wn0 + p.l32);
+    const uint32_t base = opaque_u(4u * (uint32_t)((pt * TB + p.wm0 + p.kh * 4) * ld + qt * TB + p.wn0 + p.l32));
 #pragma unroll
     for (int tm = 0; tm < CH::TM; ++tm)
 #pragma unroll
         for (int tn = 0; tn < CH::TN; ++tn)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) w.v[tm][tn][r] = g[base + CH::Pos::unif_off(tm, tn, r, ld)];
+            for (int r = 0; r < 16; ++r) w.v[tm][tn][r] = gld(g, base + CH::Pos::unif_boff(tm, tn, r, ld));
 }
 
 template <class F>
 __device__ __forceinline__ void for_acc(CH::Acc &acc, const CH::Pos &p, int pt, int qt, int ld, F &&f) {
-    const int base = opaque((pt * TB + p.wm0 + p.kh * 4) * ld + qt * TB + p.wn0 + p.l32);
+    const uint32_t base = opaque_u(4u * (uint32_t)((pt * TB + p.wm0 + p.kh * 4) * ld + qt * TB + p.wn0 + p.l32));
 #pragma unroll
     for (int tm = 0; tm < CH::TM; ++tm)
 #pragma unroll
         for (int tn = 0; tn < CH::TN; ++tn)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) f(base + CH::Pos::unif_off(tm, tn, r, ld), acc.v[tm][tn][r], tm, tn, r);
+            for (int r = 0; r < 16; ++r) f(base + CH::Pos::unif_boff(tm, tn, r, ld), acc.v[tm][tn][r], tm, tn, r);
 }
 
 // ---- A-phase (see chain.hip) -------------------------------------------------------------------
@@ -126,7 +126,7 @@ __global__ __launch_bounds__(CH::NT) void big_phase_A_kernel(
         const float *Wij = Wbar + (int64_t)i * b * d_in + (int64_t)j * b;
         const float *Bj = Bw + (int64_t)j * b * b, *Dj = D + (int64_t)j * b;
         big_mma<NS, false, false, false, false>(sm, tid, p, Cij, ldw, Bj, b, nullptr, NoPre(), [&](int pt, int qt, CH::Acc &acc) {
-            for_acc(acc, p, pt, qt, b, [&](int off, float v, int, int, int) { s0[off] = v; }); // S = C B
+            for_acc(acc, p, pt, qt, b, [&](uint32_t off, float v, int, int, int) { gst(s0, off, v); }); // S = C B
         });
         float lsum = 0.f;
         Patch wp;
@@ -145,7 +145,7 @@ __global__ __launch_bounds__(CH::NT) void big_phase_A_kernel(
                         acc.v[tm][tn][r] = res * dj;
                     }
                 }
-            if (!LOSS_ONLY) for_acc(acc, p, pt, qt, b, [&](int off, float v, int, int, int) { s1[off] = v; });
+            if (!LOSS_ONLY) for_acc(acc, p, pt, qt, b, [&](uint32_t off, float v, int, int, int) { gst(s1, off, v); });
         });
         float ltot = CH::block_sum(lsum, sm.red, tid);
         if (tid == 0) loss_part[i * nbj + j] = ltot;
@@ -154,8 +154,8 @@ __global__ __launch_bounds__(CH::NT) void big_phase_A_kernel(
             big_mma<NS, false, true, false, false>(sm, tid, p, s1, b, s0, b, nullptr,
                                                    [&](int pt, int qt) { if (!first) load_patch(wp, gp, p, pt, qt, b); },
                                                    [&](int pt, int qt, CH::Acc &acc) {
-                for_acc(acc, p, pt, qt, b, [&](int off, float v, int tm, int tn, int r) {
-                    gp[off] = (first ? 0.f : wp.v[tm][tn][r]) - 2.f * v; // += -2 (R D) S^T, same workgroup, fixed order
+                for_acc(acc, p, pt, qt, b, [&](uint32_t off, float v, int tm, int tn, int r) {
+                    gst(gp, off, (first ? 0.f : wp.v[tm][tn][r]) - 2.f * v); // += -2 (R D) S^T, same workgroup, fixed order
                 });
             });
             float f2 = 0.f;
@@ -204,9 +204,9 @@ __global__ __launch_bounds__(CH::NT) void big_phase_B_kernel(
         const float *Ai = A + (int64_t)i * b * b;
         float *Spij = Sp ? Sp + (int64_t)i * b * d_in + (int64_t)j * b : nullptr;
         big_mma<NS, false, false, false, false>(sm, tid, p, Ai, b, Cij, ldw, nullptr, NoPre(), [&](int pt, int qt, CH::Acc &acc) {
-            for_acc(acc, p, pt, qt, b, [&](int off, float v, int, int, int) { s0[off] = v; }); // S' = A C
+            for_acc(acc, p, pt, qt, b, [&](uint32_t off, float v, int, int, int) { gst(s0, off, v); }); // S' = A C
             // the W' step sees the same A and C: hand S' over instead of forming it again there
-            if (Spij) for_acc(acc, p, pt, qt, ldw, [&](int off, float v, int, int, int) { Spij[off] = v; });
+            if (Spij) for_acc(acc, p, pt, qt, ldw, [&](uint32_t off, float v, int, int, int) { gst(Spij, off, v); });
         });
         Patch wp;
         big_mma<NS, false, false, false, false>(sm, tid, p, s0, b, Bj, b, nullptr,
@@ -220,14 +220,14 @@ __global__ __launch_bounds__(CH::NT) void big_phase_B_kernel(
 #pragma unroll
                     for (int r = 0; r < 16; ++r) acc.v[tm][tn][r] = (wp.v[tm][tn][r] - acc.v[tm][tn][r]) * dj;
                 }
-            for_acc(acc, p, pt, qt, b, [&](int off, float v, int, int, int) { s1[off] = v; }); // R D
+            for_acc(acc, p, pt, qt, b, [&](uint32_t off, float v, int, int, int) { gst(s1, off, v); }); // R D
         });
         const bool first = i == i0;
         big_mma<NS, true, false, false, false>(sm, tid, p, s0, b, s1, b, nullptr,
                                                [&](int pt, int qt) { if (!first) load_patch(wp, gp, p, pt, qt, b); },
                                                [&](int pt, int qt, CH::Acc &acc) {
-            for_acc(acc, p, pt, qt, b, [&](int off, float v, int tm, int tn, int r) {
-                gp[off] = (first ? 0.f : wp.v[tm][tn][r]) - 2.f * v; // += -2 S'^T (R D)
+            for_acc(acc, p, pt, qt, b, [&](uint32_t off, float v, int tm, int tn, int r) {
+                gst(gp, off, (first ? 0.f : wp.v[tm][tn][r]) - 2.f * v); // += -2 S'^T (R D)
             });
         });
         float f2 = 0.f;
@@ -279,7 +279,7 @@ __global__ __launch_bounds__(CH::NT) void big_phase_WS_kernel(
             lds = ldw;
         } else {
             big_mma<NS, false, false, false, false>(sm, tid, p, Ai, b, Cij, ldw, nullptr, NoPre(), [&](int pt, int qt, CH::Acc &acc) {
-                for_acc(acc, p, pt, qt, b, [&](int off, float v, int, int, int) { s0[off] = v; });
+                for_acc(acc, p, pt, qt, b, [&](uint32_t off, float v, int, int, int) { gst(s0, off, v); });
             });
         }
         float lsum = 0.f;
@@ -299,10 +299,10 @@ __global__ __launch_bounds__(CH::NT) void big_phase_WS_kernel(
                         acc.v[tm][tn][r] = res * dj;
                     }
                 }
-            for_acc(acc, p, pt, qt, b, [&](int off, float v, int, int, int) { s1[off] = v; }); // R D
+            for_acc(acc, p, pt, qt, b, [&](uint32_t off, float v, int, int, int) { gst(s1, off, v); }); // R D
         });
         big_mma<NS, false, true, false, false>(sm, tid, p, s1, b, Bj, b, nullptr, NoPre(), [&](int pt, int qt, CH::Acc &acc) {
-            for_acc(acc, p, pt, qt, b, [&](int off, float v, int, int, int) { s0[off] = v; }); // U = (R D) B^T
+            for_acc(acc, p, pt, qt, b, [&](uint32_t off, float v, int, int, int) { gst(s0, off, v); }); // U = (R D) B^T
         });
         float dd = 0.f;
         uint32_t mb[CH::TM][CH::TN][16]; // mask bytes of this lane's elements, requested under the last matrix step
@@ -320,8 +320,8 @@ __global__ __launch_bounds__(CH::NT) void big_phase_WS_kernel(
         };
         big_mma<NS, true, false, false, false>(sm, tid, p, Ai, b, s0, b, nullptr, pre_G, [&](int pt, int qt, CH::Acc &acc) {
             // G = A^T U: W' step on kept entries; Delta -> s1, raw G -> Gout (fused mode)
-            const int cbase = opaque((pt * TB + p.wm0 + p.kh * 4) * ldw + qt * TB + p.wn0 + p.l32);
-            const int sbase = opaque((pt * TB + p.wm0 + p.kh * 4) * b + qt * TB + p.wn0 + p.l32);
+            const uint32_t cbase = opaque_u(4u * (uint32_t)((pt * TB + p.wm0 + p.kh * 4) * ldw + qt * TB + p.wn0 + p.l32));
+            const uint32_t sbase = opaque_u(4u * (uint32_t)((pt * TB + p.wm0 + p.kh * 4) * b + qt * TB + p.wn0 + p.l32));
 #pragma unroll
             for (int tm = 0; tm < CH::TM; ++tm)
 #pragma unroll
@@ -333,10 +333,10 @@ __global__ __launch_bounds__(CH::NT) void big_phase_WS_kernel(
                         const bool kp = (mb[tm][tn][r] >> sh) & 1u;
                         const float g = acc.v[tm][tn][r], dl = kp ? g : 0.f;
                         dd += dl * dl;
-                        if (kp) Cij[cbase + CH::Pos::unif_off(tm, tn, r, ldw)] = wp.v[tm][tn][r] + eta2 * dl;
+                        if (kp) gst(Cij, cbase + CH::Pos::unif_boff(tm, tn, r, ldw), wp.v[tm][tn][r] + eta2 * dl);
                         if (FUSED) {
-                            s1[sbase + CH::Pos::unif_off(tm, tn, r, b)] = dl;
-                            Gij[cbase + CH::Pos::unif_off(tm, tn, r, ldw)] = g;
+                            gst(s1, sbase + CH::Pos::unif_boff(tm, tn, r, b), dl);
+                            gst(Gij, cbase + CH::Pos::unif_boff(tm, tn, r, ldw), g);
                         }
                     }
                 }
@@ -344,7 +344,7 @@ __global__ __launch_bounds__(CH::NT) void big_phase_WS_kernel(
         if (FUSED) {
             big_mma<NS, false, false, false, false>(sm, tid, p, s1, b, K + (int64_t)j * b * b, b, nullptr, NoPre(),
                                              [&](int pt, int qt, CH::Acc &acc) {
-                for_acc(acc, p, pt, qt, b, [&](int off, float v, int, int, int) { s0[off] = v; }); // V = Delta K
+                for_acc(acc, p, pt, qt, b, [&](uint32_t off, float v, int, int, int) { gst(s0, off, v); }); // V = Delta K
             });
             float dz = 0.f;
             Patch dp; // Delta and the raw G of this lane's elements (both written by this lane above)
@@ -355,7 +355,7 @@ __global__ __launch_bounds__(CH::NT) void big_phase_WS_kernel(
                                              },
                                              [&](int pt, int qt, CH::Acc &acc) {
                 // Z = (A^T A) V:  G_new = G - eta Z;  <Delta, Z>
-                const int cbase = opaque((pt * TB + p.wm0 + p.kh * 4) * ldw + qt * TB + p.wn0 + p.l32);
+                const uint32_t cbase = opaque_u(4u * (uint32_t)((pt * TB + p.wm0 + p.kh * 4) * ldw + qt * TB + p.wn0 + p.l32));
 #pragma unroll
                 for (int tm = 0; tm < CH::TM; ++tm)
 #pragma unroll
@@ -364,7 +364,7 @@ __global__ __launch_bounds__(CH::NT) void big_phase_WS_kernel(
                         for (int r = 0; r < 16; ++r) {
                             const float z = acc.v[tm][tn][r];
                             dz += dp.v[tm][tn][r] * z;
-                            Gij[cbase + CH::Pos::unif_off(tm, tn, r, ldw)] = -2.f * (wp.v[tm][tn][r] - eta2 * z);
+                            gst(Gij, cbase + CH::Pos::unif_boff(tm, tn, r, ldw), -2.f * (wp.v[tm][tn][r] - eta2 * z));
                         }
             });
             float ltot = CH::block_sum(lsum - 2.f * eta2 * dd + eta2 * eta2 * dz, sm.red, tid);
@@ -405,7 +405,7 @@ __global__ __launch_bounds__(CH::NT) void big_phase_FB_kernel(
         const float *Wij = Wbar + (int64_t)i * b * d_in + (int64_t)j * b;
         const float *Bj = Bw + (int64_t)j * b * b, *Dj = D + (int64_t)j * b;
         big_mma<NS, false, false, false, false>(sm, tid, p, Cij, ldw, Bj, b, nullptr, NoPre(), [&](int pt, int qt, CH::Acc &acc) {
-            for_acc(acc, p, pt, qt, b, [&](int off, float v, int, int, int) { s0[off] = v; }); // S = C B
+            for_acc(acc, p, pt, qt, b, [&](uint32_t off, float v, int, int, int) { gst(s0, off, v); }); // S = C B
         });
         float lsum = 0.f;
         Patch wp;
@@ -424,7 +424,7 @@ __global__ __launch_bounds__(CH::NT) void big_phase_FB_kernel(
                         acc.v[tm][tn][r] = res * dj;
                     }
                 }
-            for_acc(acc, p, pt, qt, b, [&](int off, float v, int, int, int) { s1[off] = v; }); // R D
+            for_acc(acc, p, pt, qt, b, [&](uint32_t off, float v, int, int, int) { gst(s1, off, v); }); // R D
         });
         float ltot = CH::block_sum(lsum, sm.red, tid);
         if (tid == 0) loss_part[i * nbj + j] = ltot;
@@ -432,16 +432,16 @@ __global__ __launch_bounds__(CH::NT) void big_phase_FB_kernel(
         big_mma<NS, false, true, false, false>(sm, tid, p, s1, b, s0, b, nullptr,
                                                [&](int pt, int qt) { if (!first) load_patch(wp, gp, p, pt, qt, b); },
                                                [&](int pt, int qt, CH::Acc &acc) {
-            for_acc(acc, p, pt, qt, b, [&](int off, float v, int tm, int tn, int r) {
-                gp[off] = (first ? 0.f : wp.v[tm][tn][r]) - 2.f * v; // += -2 (R D) S^T, same workgroup, fixed order
+            for_acc(acc, p, pt, qt, b, [&](uint32_t off, float v, int tm, int tn, int r) {
+                gst(gp, off, (first ? 0.f : wp.v[tm][tn][r]) - 2.f * v); // += -2 (R D) S^T, same workgroup, fixed order
             });
         });
         big_mma<NS, true, false, false, false>(sm, tid, p, Ai, b, s1, b, nullptr, NoPre(), [&](int pt, int qt, CH::Acc &acc) {
-            for_acc(acc, p, pt, qt, b, [&](int off, float v, int, int, int) { s0[off] = v; }); // T = A^T (R D)
+            for_acc(acc, p, pt, qt, b, [&](uint32_t off, float v, int, int, int) { gst(s0, off, v); }); // T = A^T (R D)
         });
         float *gb = gBpart + ((int64_t)j * nbi + i) * b * b;
         big_mma<NS, true, false, false, false>(sm, tid, p, Cij, ldw, s0, b, nullptr, NoPre(), [&](int pt, int qt, CH::Acc &acc) {
-            for_acc(acc, p, pt, qt, b, [&](int off, float v, int, int, int) { gb[off] = -2.f * v; }); // C^T T, old core
+            for_acc(acc, p, pt, qt, b, [&](uint32_t off, float v, int, int, int) { gst(gb, off, -2.f * v); }); // C^T T, old core
         });
         float *mij = mC + (int64_t)i * b * d_in + (int64_t)j * b, *vij = vC + (int64_t)i * b * d_in + (int64_t)j * b;
         uint32_t mb[CH::TM][CH::TN][16];
@@ -459,7 +459,7 @@ __global__ __launch_bounds__(CH::NT) void big_phase_FB_kernel(
         };
         big_mma<NS, false, true, false, false>(sm, tid, p, s0, b, Bj, b, nullptr, pre_C, [&](int pt, int qt, CH::Acc &acc) {
             // T B^T: Adam on the core, g = -2 (T B^T) (.) M; the moments decay on pruned entries too
-            const int cbase = opaque((pt * TB + p.wm0 + p.kh * 4) * ldw + qt * TB + p.wn0 + p.l32);
+            const uint32_t cbase = opaque_u(4u * (uint32_t)((pt * TB + p.wm0 + p.kh * 4) * ldw + qt * TB + p.wn0 + p.l32));
 #pragma unroll
             for (int tm = 0; tm < CH::TM; ++tm)
 #pragma unroll
@@ -467,14 +467,14 @@ __global__ __launch_bounds__(CH::NT) void big_phase_FB_kernel(
                     const int sh = (int)(((int64_t)j * b + qt * TB + p.col(tn)) % mask_group);
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
-                        const int off = cbase + CH::Pos::unif_off(tm, tn, r, ldw);
+                        const uint32_t off = cbase + CH::Pos::unif_boff(tm, tn, r, ldw);
                         const bool kp = (mb[tm][tn][r] >> sh) & 1u;
                         const float g = kp ? -2.f * acc.v[tm][tn][r] : 0.f;
-                        const float mn = k.b1 * mij[off] + k.one_minus_b1 * g;
-                        const float vn = k.b2 * vij[off] + k.one_minus_b2 * g * g;
-                        mij[off] = mn;
-                        vij[off] = vn;
-                        if (kp) Cij[off] = wp.v[tm][tn][r] - k.lr * (mn * k.inv_c1) / (sqrtf(vn * k.inv_c2) + k.eps);
+                        const float mn = k.b1 * gld(mij, off) + k.one_minus_b1 * g;
+                        const float vn = k.b2 * gld(vij, off) + k.one_minus_b2 * g * g;
+                        gst(mij, off, mn);
+                        gst(vij, off, vn);
+                        if (kp) gst(Cij, off, wp.v[tm][tn][r] - k.lr * (mn * k.inv_c1) / (sqrtf(vn * k.inv_c2) + k.eps));
                     }
                 }
         });
@@ -501,7 +501,7 @@ __global__ __launch_bounds__(CH::NT) void big_phase_GS_kernel(
         const float *Ai = A + (int64_t)i * b * b, *Bj = Bw + (int64_t)j * b * b, *Dj = D + (int64_t)j * b;
         float *Gij = Gout + (int64_t)i * b * d_in + (int64_t)j * b;
         big_mma<NS, false, false, false, false>(sm, tid, p, Ai, b, Cij, ldw, nullptr, NoPre(), [&](int pt, int qt, CH::Acc &acc) {
-            for_acc(acc, p, pt, qt, b, [&](int off, float v, int, int, int) { s0[off] = v; }); // S' = A C
+            for_acc(acc, p, pt, qt, b, [&](uint32_t off, float v, int, int, int) { gst(s0, off, v); }); // S' = A C
         });
         float lsum = 0.f;
         Patch wp;
@@ -520,13 +520,13 @@ __global__ __launch_bounds__(CH::NT) void big_phase_GS_kernel(
                         acc.v[tm][tn][r] = res * dj;
                     }
                 }
-            for_acc(acc, p, pt, qt, b, [&](int off, float v, int, int, int) { s1[off] = v; }); // R D
+            for_acc(acc, p, pt, qt, b, [&](uint32_t off, float v, int, int, int) { gst(s1, off, v); }); // R D
         });
         big_mma<NS, false, true, false, false>(sm, tid, p, s1, b, Bj, b, nullptr, NoPre(), [&](int pt, int qt, CH::Acc &acc) {
-            for_acc(acc, p, pt, qt, b, [&](int off, float v, int, int, int) { s0[off] = v; }); // U = (R D) B^T
+            for_acc(acc, p, pt, qt, b, [&](uint32_t off, float v, int, int, int) { gst(s0, off, v); }); // U = (R D) B^T
         });
         big_mma<NS, true, false, false, false>(sm, tid, p, Ai, b, s0, b, nullptr, NoPre(), [&](int pt, int qt, CH::Acc &acc) {
-            for_acc(acc, p, pt, qt, ldw, [&](int off, float v, int, int, int) { Gij[off] = -2.f * v; }); // -2 A^T U
+            for_acc(acc, p, pt, qt, ldw, [&](uint32_t off, float v, int, int, int) { gst(Gij, off, -2.f * v); }); // -2 A^T U
         });
         float ltot = CH::block_sum(lsum, sm.red, tid);
         if (tid == 0) loss_part[blk] = ltot;
@@ -549,10 +549,11 @@ __global__ __launch_bounds__(CH::NT) void big_wrapper_grams_kernel(
     float *dst = (isA ? AtA : K) + (int64_t)idx * b * b;
     float f2 = 0.f;
     auto epi = [&](int pt, int qt, CH::Acc &acc) {
-        for_acc(acc, p, pt, qt, b, [&](int off, float v, int, int, int) {
+        for_acc(acc, p, pt, qt, b, [&](uint32_t off, float v, int, int, int) {
+            const int e = (int)(off / 4u); // element index in the b x b result
             f2 += v * v;
-            dst[off] = v;
-            if (isA && off / b == off % b) colnorm2[(int64_t)idx * b + off / b] = v;
+            gst(dst, off, v);
+            if (isA && e / b == e % b) colnorm2[(int64_t)idx * b + e / b] = v;
         });
     };
     if (isA) big_mma<NS, true, false, false, false>(sm, tid, p, src, b, src, b, nullptr, NoPre(), epi);          // A^T A

@@ -27,6 +27,23 @@ __device__ __forceinline__ int opaque(int x) {
     return x;
 }
 
+__device__ __forceinline__ uint32_t opaque_u(uint32_t x) {
+    asm volatile("" : "+v"(x));
+    return x;
+}
+
+// Global access at a wave-uniform base pointer plus a 32-bit unsigned byte offset.  This is the form
+// that maps onto the scalar-base addressing mode of the global instructions (one vector add per
+// access); a signed element index instead costs a sign extension and a 64-bit pointer sum each time,
+// which made address arithmetic the bulk of the epilogues' vector instructions.  The offsets stay
+// inside one b x b block of a matrix, far below 4 GB.
+template <class T> __device__ __forceinline__ T gld(const T *base, uint32_t boff) {
+    return *reinterpret_cast<const T *>(reinterpret_cast<const char *>(base) + boff);
+}
+template <class T> __device__ __forceinline__ void gst(T *base, uint32_t boff, T v) {
+    *reinterpret_cast<T *>(reinterpret_cast<char *>(base) + boff) = v;
+}
+
 template <int B> struct Cfg;
 template <> struct Cfg<32>  { static constexpr int WM = 1, WN = 1, TM = 1, TN = 1; };
 template <> struct Cfg<64>  { static constexpr int WM = 2, WN = 2, TM = 1, TN = 1; };
@@ -72,6 +89,9 @@ template <int B> struct Chain {
         __device__ static int unif_off(int tm, int tn, int r, int ld) {
             return (tm * 32 + (r >> 2) * 8 + (r & 3)) * ld + tn * 32;
         }
+        // the same as byte offsets of fp32 elements, for gld / gst
+        __device__ uint32_t lane_boff(int ld) const { return 4u * (uint32_t)lane_off(ld); }
+        __device__ static uint32_t unif_boff(int tm, int tn, int r, int ld) { return 4u * (uint32_t)unif_off(tm, tn, r, ld); }
     };
 
     // global (row-major, leading dimension ld) -> registers -> LDS tile, in two halves so that the
