@@ -420,7 +420,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_WS_kernel(
         __syncthreads();
         CH::gload_tile(t0, A + (int64_t)i * B * B, B, tid);
         acc.zero();
-        CH::template mma<false, true, false, false>(acc, sm.X, sm.Y, nullptr, p); // U = (R D) B^T
+        CH::template mma<false, true, false>(acc, sm.X, sm.Y, nullptr, p); // U = (R D) B^T
         __syncthreads();
         CH::store_acc(sm.X, acc, p);
         CH::lstore_tile(sm.Y, t0, tid);
