@@ -692,7 +692,9 @@ __global__ __launch_bounds__(256) void sparse_step_kernel(const float *__restric
     __shared__ double s_q[M], s_K[M][M], s_red[4];
     __shared__ int s_best;
     const int tid = threadIdx.x, blk = blockIdx.x, i = blk / nbj, j = blk % nbj;
-    const int gpr = b / M, gpb = b * gpr;
+    // groups per block row: b and M are powers of two, so rows and columns of a group index come from
+    // a shift and a mask (an integer division per group was a quarter of the selection pass)
+    const int gpr = b / M, gpb = b * gpr, gsh = 31 - __clz(gpr);
 
     if (blk == 0 && loss_cont_out != nullptr) { // loss after the continuous step = sum of block losses
         double l = 0.0;
@@ -716,7 +718,7 @@ __global__ __launch_bounds__(256) void sparse_step_kernel(const float *__restric
         for (int u = 0; u < U; ++u) {
             const int kap = kap0 + u * 256;
             if (kap < gpb) {
-                const float *g = Gij + (int64_t)(kap / gpr) * d_in + (kap % gpr) * M;
+                const float *g = Gij + (int64_t)(kap >> gsh) * d_in + (kap & (gpr - 1)) * M;
                 if (M == 4) {
                     float4 x = *reinterpret_cast<const float4 *>(g);
                     v[u][0] = x.x; v[u][1] = x.y; v[u][2] = x.z; v[u][3] = x.w;
@@ -767,7 +769,7 @@ __global__ __launch_bounds__(256) void sparse_step_kernel(const float *__restric
     for (int w = 1; w < 4; ++w)
         if (s_key[w] < best_key || (s_key[w] == best_key && s_kap[w] < best_kap)) { best_key = s_key[w]; best_kap = s_kap[w]; }
     if (best_kap == 0x7fffffff) best_kap = 0; // every key was +inf (or NaN): the first group
-    const int ip = best_kap / gpr, k0 = (best_kap % gpr) * M;
+    const int ip = best_kap >> gsh, k0 = (best_kap & (gpr - 1)) * M;
 
     // ---- 2. operands of Eq. 7 for the drawn group: one round of independent loads ----
     float *crow = C + ((int64_t)i * b + ip) * d_in + (int64_t)j * b + k0;
