@@ -81,12 +81,13 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_A_kernel(
         CH::store_acc(sm.X, acc, p);
         CH::lstore_tile(sm.Y, t0, tid);
         float wb[CH::TM][CH::TN][16];
+        const uint32_t lb = opaque_u(wboff);
 #pragma unroll
         for (int tm = 0; tm < CH::TM; ++tm)
 #pragma unroll
             for (int tn = 0; tn < CH::TN; ++tn)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) wb[tm][tn][r] = gld(Wij, opaque_u(wboff) + CH::Pos::unif_boff(tm, tn, r, ldw));
+                for (int r = 0; r < 16; ++r) wb[tm][tn][r] = gld(Wij, lb + CH::Pos::unif_boff(tm, tn, r, ldw));
         __syncthreads();
         acc.zero();
         CH::template mma<false, false, false>(acc, sm.Y, sm.X, nullptr, p); // A (S sqrt D)
@@ -122,12 +123,13 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_A_kernel(
     }
     if (!LOSS_ONLY) {
         float *gp = gpart + (int64_t)blockIdx.x * B * B;
+        const uint32_t lb = opaque_u(p.lane_boff(B));
 #pragma unroll
         for (int tm = 0; tm < CH::TM; ++tm)
 #pragma unroll
             for (int tn = 0; tn < CH::TN; ++tn)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) gst(gp, opaque_u(p.lane_boff(B)) + CH::Pos::unif_boff(tm, tn, r, B), -2.f * gacc.v[tm][tn][r]);
+                for (int r = 0; r < 16; ++r) gst(gp, lb + CH::Pos::unif_boff(tm, tn, r, B), -2.f * gacc.v[tm][tn][r]);
     }
 }
 
@@ -175,21 +177,23 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_B_kernel(
         CH::store_acc(sm.X, acc, p);
         if (Sp != nullptr) { // A and C do not change until the W' step: that step takes S' from here
             float *Sij = Sp + (int64_t)i * B * d_in + (int64_t)j * B;
+            const uint32_t lb = opaque_u(wboff);
 #pragma unroll
             for (int tm = 0; tm < CH::TM; ++tm)
 #pragma unroll
                 for (int tn = 0; tn < CH::TN; ++tn)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) gst(Sij, opaque_u(wboff) + CH::Pos::unif_boff(tm, tn, r, ldw), acc.v[tm][tn][r]);
+                    for (int r = 0; r < 16; ++r) gst(Sij, lb + CH::Pos::unif_boff(tm, tn, r, ldw), acc.v[tm][tn][r]);
         }
         CH::lstore_tile(sm.Y, t0, tid);
         float wb[CH::TM][CH::TN][16];
+        const uint32_t lb = opaque_u(wboff);
 #pragma unroll
         for (int tm = 0; tm < CH::TM; ++tm)
 #pragma unroll
             for (int tn = 0; tn < CH::TN; ++tn)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) wb[tm][tn][r] = gld(Wij, opaque_u(wboff) + CH::Pos::unif_boff(tm, tn, r, ldw));
+                for (int r = 0; r < 16; ++r) wb[tm][tn][r] = gld(Wij, lb + CH::Pos::unif_boff(tm, tn, r, ldw));
         __syncthreads();
         acc.zero();
         CH::template mma<false, false, false>(acc, sm.X, sm.Y, nullptr, p); // What = S' B
@@ -216,12 +220,13 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_B_kernel(
         __syncthreads();
     }
     float *gp = gpart + (int64_t)blockIdx.x * B * B;
+    const uint32_t lb = opaque_u(p.lane_boff(B));
 #pragma unroll
     for (int tm = 0; tm < CH::TM; ++tm)
 #pragma unroll
         for (int tn = 0; tn < CH::TN; ++tn)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) gst(gp, opaque_u(p.lane_boff(B)) + CH::Pos::unif_boff(tm, tn, r, B), -2.f * gacc.v[tm][tn][r]);
+            for (int r = 0; r < 16; ++r) gst(gp, lb + CH::Pos::unif_boff(tm, tn, r, B), -2.f * gacc.v[tm][tn][r]);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -264,12 +269,13 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_W_kernel(
         CH::lstore_tile(sm.Y, t0, tid);
         {
             float wb[CH::TM][CH::TN][16];
+            const uint32_t lb = opaque_u(wboff);
 #pragma unroll
             for (int tm = 0; tm < CH::TM; ++tm)
 #pragma unroll
                 for (int tn = 0; tn < CH::TN; ++tn)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) wb[tm][tn][r] = gld(Wij, opaque_u(wboff) + CH::Pos::unif_boff(tm, tn, r, ldw));
+                    for (int r = 0; r < 16; ++r) wb[tm][tn][r] = gld(Wij, lb + CH::Pos::unif_boff(tm, tn, r, ldw));
             __syncthreads();
             acc.zero();
             CH::template mma<false, false, false, false>(acc, sm.X, sm.Y, nullptr, p); // What = S' B
@@ -557,12 +563,13 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_FB_kernel(
         float lsum = 0.f;
         {
             float wb[CH::TM][CH::TN][16];
+            const uint32_t lb = opaque_u(wboff);
 #pragma unroll
             for (int tm = 0; tm < CH::TM; ++tm)
 #pragma unroll
                 for (int tn = 0; tn < CH::TN; ++tn)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) wb[tm][tn][r] = gld(Wij, opaque_u(wboff) + CH::Pos::unif_boff(tm, tn, r, ldw));
+                    for (int r = 0; r < 16; ++r) wb[tm][tn][r] = gld(Wij, lb + CH::Pos::unif_boff(tm, tn, r, ldw));
             __syncthreads();
             acc.zero();
             CH::template mma<false, false, false, false>(acc, sm.Y, sm.X, nullptr, p); // What = A S
@@ -631,23 +638,25 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_FB_kernel(
         CH::template mma<true, false, false, false>(acc2, sm.X, sm.Y, nullptr, p); // C^T T
         {
             float *gb = gBpart + ((int64_t)j * nbi + i) * B * B;
+            const uint32_t lb = opaque_u(p.lane_boff(B));
 #pragma unroll
             for (int tm = 0; tm < CH::TM; ++tm)
 #pragma unroll
                 for (int tn = 0; tn < CH::TN; ++tn)
 #pragma unroll
                     for (int r = 0; r < 16; ++r)
-                        gst(gb, opaque_u(p.lane_boff(B)) + CH::Pos::unif_boff(tm, tn, r, B), -2.f * acc2.v[tm][tn][r]);
+                        gst(gb, lb + CH::Pos::unif_boff(tm, tn, r, B), -2.f * acc2.v[tm][tn][r]);
         }
         __builtin_amdgcn_sched_barrier(0); // keep the moment loads below the product: they would not fit beside it
         float mo[CH::TM][CH::TN][16], vo[CH::TM][CH::TN][16];
+        const uint32_t lb = opaque_u(wboff);
 #pragma unroll
         for (int tm = 0; tm < CH::TM; ++tm)
 #pragma unroll
             for (int tn = 0; tn < CH::TN; ++tn)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    const uint32_t off = opaque_u(wboff) + CH::Pos::unif_boff(tm, tn, r, ldw);
+                    const uint32_t off = lb + CH::Pos::unif_boff(tm, tn, r, ldw);
                     mo[tm][tn][r] = gld(mij, off);
                     vo[tm][tn][r] = gld(vij, off);
                 }
@@ -655,13 +664,14 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_FB_kernel(
             CH::gload_tile(t0, C + (int64_t)i * B * d_in + (int64_t)(j + 1) * B, ldw, tid);
         {   // Adam on the core: g = -2 (T B^T) (.) M; the current values are still in LDS (X = C)
             const float *c0 = sm.X + opaque(p.lane_off(CH::P));
+            const uint32_t lb = opaque_u(wboff);
 #pragma unroll
             for (int tm = 0; tm < CH::TM; ++tm)
 #pragma unroll
                 for (int tn = 0; tn < CH::TN; ++tn) {
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
-                        const uint32_t off = opaque_u(wboff) + CH::Pos::unif_boff(tm, tn, r, ldw);
+                        const uint32_t off = lb + CH::Pos::unif_boff(tm, tn, r, ldw);
                         const bool kp = (keep[tm][tn] >> r) & 1u;
                         const float g = kp ? -2.f * acc.v[tm][tn][r] : 0.f;
                         const float mn = k.b1 * mo[tm][tn][r] + k.one_minus_b1 * g;
@@ -679,12 +689,13 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_FB_kernel(
         __syncthreads();
     }
     float *gp = gApart + (int64_t)blockIdx.x * B * B;
+    const uint32_t lb = opaque_u(p.lane_boff(B));
 #pragma unroll
     for (int tm = 0; tm < CH::TM; ++tm)
 #pragma unroll
         for (int tn = 0; tn < CH::TN; ++tn)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) gst(gp, opaque_u(p.lane_boff(B)) + CH::Pos::unif_boff(tm, tn, r, B), -2.f * gacc.v[tm][tn][r]);
+            for (int r = 0; r < 16; ++r) gst(gp, lb + CH::Pos::unif_boff(tm, tn, r, B), -2.f * gacc.v[tm][tn][r]);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -726,12 +737,13 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_GS_kernel(
         float lsum = 0.f;
         {
             float wb[CH::TM][CH::TN][16];
+            const uint32_t lb = opaque_u(wboff);
 #pragma unroll
             for (int tm = 0; tm < CH::TM; ++tm)
 #pragma unroll
                 for (int tn = 0; tn < CH::TN; ++tn)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) wb[tm][tn][r] = gld(Wij, opaque_u(wboff) + CH::Pos::unif_boff(tm, tn, r, ldw));
+                    for (int r = 0; r < 16; ++r) wb[tm][tn][r] = gld(Wij, lb + CH::Pos::unif_boff(tm, tn, r, ldw));
             __syncthreads();
             acc.zero();
             CH::template mma<false, false, false>(acc, sm.X, sm.Y, nullptr, p); // What = S' B
@@ -767,13 +779,14 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_GS_kernel(
         acc.zero();
         CH::template mma<true, false, false>(acc, sm.Y, sm.X, nullptr, p); // G = A^T U
         float *Gij = Gout + (int64_t)i * B * d_in + (int64_t)j * B;
+        const uint32_t lb = opaque_u(wboff);
 #pragma unroll
         for (int tm = 0; tm < CH::TM; ++tm)
 #pragma unroll
             for (int tn = 0; tn < CH::TN; ++tn)
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
-                    gst(Gij, opaque_u(wboff) + CH::Pos::unif_boff(tm, tn, r, ldw), -2.f * acc.v[tm][tn][r]);
+                    gst(Gij, lb + CH::Pos::unif_boff(tm, tn, r, ldw), -2.f * acc.v[tm][tn][r]);
         __syncthreads();
     }
 }
