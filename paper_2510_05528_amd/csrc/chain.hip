@@ -61,8 +61,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_A_kernel(
         if (tid < B) sm.Dl[tid] = D[(int64_t)j * B + tid];
         __syncthreads();
         CH::gload_tile(t0, A + (int64_t)i * B * B, B, tid);
-        acc.zero();
-        CH::template mma<false, false, false>(acc, sm.X, sm.Y, nullptr, p); // S = C B
+        CH::template mma<false, false, false, true, true>(acc, sm.X, sm.Y, nullptr, p); // S = C B
         // Everything downstream needs S only as S sqrt(D) (columns scaled): (R D) S^T = (R sqrt D)(S sqrt D)^T,
         // S D S^T = (S sqrt D)(S sqrt D)^T, and A S = (A S sqrt D) / sqrt D column by column.  Scaling here
         // once keeps the per-k multiply out of the product loops.  A zero weight gives a zero column.
@@ -89,8 +88,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_A_kernel(
 #pragma unroll
                 for (int r = 0; r < 16; ++r) wb[tm][tn][r] = gld(Wij, lb + CH::Pos::unif_boff(tm, tn, r, ldw));
         __syncthreads();
-        acc.zero();
-        CH::template mma<false, false, false>(acc, sm.Y, sm.X, nullptr, p); // A (S sqrt D)
+        CH::template mma<false, false, false, true, true>(acc, sm.Y, sm.X, nullptr, p); // A (S sqrt D)
         float lsum = 0.f;
 #pragma unroll
         for (int tm = 0; tm < CH::TM; ++tm)
@@ -171,8 +169,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_B_kernel(
         CH::lstore_tile(sm.Y, t1, tid);
         __syncthreads();
         CH::gload_tile(t0, Bw + (int64_t)j * B * B, B, tid);
-        acc.zero();
-        CH::template mma<false, false, false>(acc, sm.Y, sm.X, nullptr, p); // S' = A C
+        CH::template mma<false, false, false, true, true>(acc, sm.Y, sm.X, nullptr, p); // S' = A C
         __syncthreads();
         CH::store_acc(sm.X, acc, p);
         if (Sp != nullptr) { // A and C do not change until the W' step: that step takes S' from here
@@ -195,8 +192,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_B_kernel(
 #pragma unroll
                 for (int r = 0; r < 16; ++r) wb[tm][tn][r] = gld(Wij, lb + CH::Pos::unif_boff(tm, tn, r, ldw));
         __syncthreads();
-        acc.zero();
-        CH::template mma<false, false, false>(acc, sm.X, sm.Y, nullptr, p); // What = S' B
+        CH::template mma<false, false, false, true, true>(acc, sm.X, sm.Y, nullptr, p); // What = S' B
 #pragma unroll
         for (int tm = 0; tm < CH::TM; ++tm)
 #pragma unroll
@@ -213,7 +209,6 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_B_kernel(
             CH::gload_tile(t1, A + (int64_t)(i + 1) * B * B, B, tid);
         }
         CH::template mma<true, false, false>(gacc, sm.X, sm.Y, nullptr, p); // += S'^T (R D)
-        acc.zero();
         const float f2 = CH::template sym_frob2<true>(sm.X, p, tid); // ||S'^T S'||_F^2 (symmetric: upper tiles)
         float ftot = CH::block_sum(f2, sm.red, tid);
         if (tid == 0) beta_part[i * nbj + j] = sqrtf(ftot) * sqrtf(dn2);
@@ -729,8 +724,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_GS_kernel(
         if (tid < B) sm.Dl[tid] = D[(int64_t)j * B + tid];
         __syncthreads();
         CH::gload_tile(t0, Bw + (int64_t)j * B * B, B, tid);
-        acc.zero();
-        CH::template mma<false, false, false>(acc, sm.Y, sm.X, nullptr, p); // S' = A C
+        CH::template mma<false, false, false, true, true>(acc, sm.Y, sm.X, nullptr, p); // S' = A C
         __syncthreads();
         CH::store_acc(sm.X, acc, p);
         CH::lstore_tile(sm.Y, t0, tid);
@@ -745,8 +739,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_GS_kernel(
 #pragma unroll
                     for (int r = 0; r < 16; ++r) wb[tm][tn][r] = gld(Wij, lb + CH::Pos::unif_boff(tm, tn, r, ldw));
             __syncthreads();
-            acc.zero();
-            CH::template mma<false, false, false>(acc, sm.X, sm.Y, nullptr, p); // What = S' B
+            CH::template mma<false, false, false, true, true>(acc, sm.X, sm.Y, nullptr, p); // What = S' B
 #pragma unroll
             for (int tm = 0; tm < CH::TM; ++tm)
 #pragma unroll
@@ -765,8 +758,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_GS_kernel(
         CH::store_acc(sm.X, acc, p); // R D   (Y still holds B^j)
         __syncthreads();
         CH::gload_tile(t0, A + (int64_t)i * B * B, B, tid);
-        acc.zero();
-        CH::template mma<false, true, false>(acc, sm.X, sm.Y, nullptr, p); // U = (R D) B^T
+        CH::template mma<false, true, false, true, true>(acc, sm.X, sm.Y, nullptr, p); // U = (R D) B^T
         __syncthreads();
         CH::store_acc(sm.X, acc, p);
         CH::lstore_tile(sm.Y, t0, tid);
@@ -776,8 +768,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_GS_kernel(
             CH::gload_tile(t0, C + (int64_t)(nblk / nbj) * B * d_in + (int64_t)(nblk % nbj) * B, ldw, tid);
             CH::gload_tile(t1, A + (int64_t)(nblk / nbj) * B * B, B, tid);
         }
-        acc.zero();
-        CH::template mma<true, false, false>(acc, sm.Y, sm.X, nullptr, p); // G = A^T U
+        CH::template mma<true, false, false, true, true>(acc, sm.Y, sm.X, nullptr, p); // G = A^T U
         float *Gij = Gout + (int64_t)i * B * d_in + (int64_t)j * B;
         const uint32_t lb = opaque_u(wboff);
 #pragma unroll

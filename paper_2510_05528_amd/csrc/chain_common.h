@@ -172,30 +172,47 @@ template <int B> struct Chain {
         }
     }
 
-    __device__ static __forceinline__ void issue(Acc &acc, const Frag &f) {
+    // FIRST: the first matrix instruction of every accumulator tile takes a zero C operand, i.e. the
+    // product overwrites acc and nobody has to clear 16 registers per tile beforehand.
+    template <bool FIRST = false> __device__ static __forceinline__ void issue(Acc &acc, const Frag &f) {
 #pragma unroll
         for (int g = 0; g < G; ++g)
 #pragma unroll
             for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
-                for (int tn = 0; tn < TN; ++tn)
-                    acc.v[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a[g][tm], f.b[g][tn], acc.v[tm][tn], 0, 0, 0);
+                for (int tn = 0; tn < TN; ++tn) {
+                    if (FIRST && g == 0) {
+                        const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                        acc.v[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a[g][tm], f.b[g][tn], zero, 0, 0, 0);
+                    } else {
+                        acc.v[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a[g][tm], f.b[g][tn], acc.v[tm][tn], 0, 0, 0);
+                    }
+                }
     }
 
+    // acc (+)= op(L) * op(R); ZERO: acc = op(L) * op(R) (see issue).
     // PEEL: the last trip is peeled off the loop.  A fetch under a condition inside the loop splits it
     // into blocks, and the wait in front of the next matrix instructions then has to cover the path
     // without the fetch, i.e. it also waits for operands requested a moment ago (LDS-fed loop alone:
     // 83 % of the fp32 matrix peak with the condition, 91 % peeled).  Inside a kernel the better form
     // depends on what else is live around the product, so call sites choose by measurement.
-    template <bool LT, bool RT, bool SCALE, bool PEEL = true>
+    template <bool LT, bool RT, bool SCALE, bool PEEL = true, bool ZERO = false>
     __device__ static void mma(Acc &acc, const float *__restrict__ L, const float *__restrict__ R,
                                const float *__restrict__ Dk, const Pos &p) {
-        static_assert(B % (4 * G) == 0, "two groups per trip");
+        static_assert(B % (4 * G) == 0 && B >= 12 * G, "two groups per trip; head, loop and tail trips");
         Frag f0, f1;
         fetch<LT, RT, SCALE>(f0, 0, L, R, Dk, p);
+        int k = 0;
+        if constexpr (ZERO) { // head trip
+            fetch<LT, RT, SCALE>(f1, 2 * G, L, R, Dk, p);
+            issue<true>(acc, f0);
+            fetch<LT, RT, SCALE>(f0, 4 * G, L, R, Dk, p);
+            issue(acc, f1);
+            k = 4 * G;
+        }
         if constexpr (PEEL) {
 #pragma unroll 1
-            for (int k = 0; k < B - 4 * G; k += 4 * G) {
+            for (; k < B - 4 * G; k += 4 * G) {
                 fetch<LT, RT, SCALE>(f1, k + 2 * G, L, R, Dk, p);
                 issue(acc, f0);
                 fetch<LT, RT, SCALE>(f0, k + 4 * G, L, R, Dk, p);
@@ -206,7 +223,7 @@ template <int B> struct Chain {
             issue(acc, f1);
         } else {
 #pragma unroll 1
-            for (int k = 0; k < B; k += 4 * G) {
+            for (; k < B; k += 4 * G) {
                 fetch<LT, RT, SCALE>(f1, k + 2 * G, L, R, Dk, p);
                 issue(acc, f0);
                 if (k + 4 * G < B) fetch<LT, RT, SCALE>(f0, k + 4 * G, L, R, Dk, p);
