@@ -86,7 +86,7 @@ int armor_last_hip_error(void);
 #define ARMOR_PROF_NORMALIZE 7 /* column norms + row norms and scaling (two kernels) */
 #define ARMOR_PROF_INIT 8      /* initial mask and core (Eq. 3), N:M or unstructured */
 #define ARMOR_PROF_PACK 9      /* armor_pack_nm */
-#define ARMOR_PROF_SMALL 10    /* wrapper updates, wrapper Grams, step-size scalars */
+#define ARMOR_PROF_SMALL 10    /* wrapper updates, wrapper Grams */
 #define ARMOR_PROF_APPLY_PRE 11  /* armor_apply_packed: U = X B^T */
 #define ARMOR_PROF_APPLY_MAIN 12 /* armor_apply_packed: Y = (U S^T) A^T */
 #define ARMOR_PROF_DIAG_X 13     /* armor_gram_diag_x */
