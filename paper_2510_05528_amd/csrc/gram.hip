@@ -396,14 +396,20 @@ __global__ __launch_bounds__(512) void gram_bf16_dma_kernel(const uint16_t *__re
         publish((int)min((int64_t)(GD_SLOTS - 2), nstages - 1));
         read_frags(f0, 0, 0);
     }
-    for (int64_t st = 0; st < nstages; ++st) {
+    // (the last stage is peeled: with the second half under a condition, the paths that meet in front
+    // of mma(f1) differ in their outstanding LDS reads and the compiler makes that product wait for
+    // the reads of f0 that were issued a moment ago)
+    for (int64_t st = 0; st + 1 < nstages; ++st) {
         read_frags(f1, st, 1);
         mma(f0);
-        if (st + 1 < nstages) {
-            publish((int)min((int64_t)(GD_SLOTS - 3), nstages - 2 - st)); // stage st+1 landed; younger ones may be in flight
-            if (st + GD_SLOTS - 1 < nstages) issue(st + GD_SLOTS - 1);
-            read_frags(f0, st + 1, 0);
-        }
+        publish((int)min((int64_t)(GD_SLOTS - 3), nstages - 2 - st)); // stage st+1 landed; younger ones may be in flight
+        if (st + GD_SLOTS - 1 < nstages) issue(st + GD_SLOTS - 1);
+        read_frags(f0, st + 1, 0);
+        mma(f1);
+    }
+    if (nstages > 0) {
+        read_frags(f1, nstages - 1, 1);
+        mma(f0);
         mma(f1);
     }
 #pragma unroll
