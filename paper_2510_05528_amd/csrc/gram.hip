@@ -399,11 +399,39 @@ __global__ __launch_bounds__(512) void gram_bf16_dma_kernel(const uint16_t *__re
     // (the last stage is peeled: with the second half under a condition, the paths that meet in front
     // of mma(f1) differ in their outstanding LDS reads and the compiler makes that product wait for
     // the reads of f0 that were issued a moment ago)
-    for (int64_t st = 0; st + 1 < nstages; ++st) {
+    int64_t st = 0;
+    // steady state: a new stage is issued every trip and exactly one younger stage is in flight at the
+    // barrier, so the wait is a constant and the trip has no branches
+    static_assert(GD_SLOTS == 4, "one younger stage in flight in the steady state");
+    if (diag) {
+        for (; st + GD_SLOTS - 1 < nstages; ++st) {
+            read_frags(f1, st, 1);
+            mma(f0);
+            GRAM_WAIT_VMCNT(2);
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            issue(st + GD_SLOTS - 1);
+            read_frags(f0, st + 1, 0);
+            mma(f1);
+        }
+    } else {
+        for (; st + GD_SLOTS - 1 < nstages; ++st) {
+            read_frags(f1, st, 1);
+            mma(f0);
+            GRAM_WAIT_VMCNT(4);
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            issue(st + GD_SLOTS - 1);
+            read_frags(f0, st + 1, 0);
+            mma(f1);
+        }
+    }
+    for (; st + 1 < nstages; ++st) { // the last stages: nothing left to issue
         read_frags(f1, st, 1);
         mma(f0);
         publish((int)min((int64_t)(GD_SLOTS - 3), nstages - 2 - st)); // stage st+1 landed; younger ones may be in flight
-        if (st + GD_SLOTS - 1 < nstages) issue(st + GD_SLOTS - 1);
         read_frags(f0, st + 1, 0);
         mma(f1);
     }
