@@ -312,43 +312,57 @@ __global__ __launch_bounds__(512) void apply_main_kernel(const uint8_t *__restri
     }
     const int m_off = AP_SM_OFF + (128 * wm + l32) * 8;
 
+    // one stage of matrix work; meta words: 32 index bits per 32-k step (x: first step, y: second)
+#define AP_COMPUTE(st)                                                                   \
+    {                                                                                    \
+        const uint8_t *base = lds + ((st) % AP_SLOTS) * AP_SLOT_BYTES;                               \
+        uint2 meta[4];                                                                               \
+_Pragma("unroll")                                                                                    \
+        for (int tm = 0; tm < 4; ++tm) meta[tm] = *reinterpret_cast<const uint2 *>(base + m_off + tm * 32 * 8); \
+_Pragma("unroll")                                                                                    \
+        for (int s = 0; s < 2; ++s) {                                                                \
+            bf16x8 a[4];                                                                             \
+            bf16x16 b[2];                                                                            \
+            int idx[4];                                                                              \
+_Pragma("unroll")                                                                                    \
+            for (int tm = 0; tm < 4; ++tm) {                                                         \
+                a[tm] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(base + a_off[s] + tm * 32 * 64)); \
+                const uint32_t word = s == 0 ? meta[tm].x : meta[tm].y;                              \
+                const uint32_t f = (word >> (16 * half)) & 0xffffu;                                  \
+                idx[tm] = (int)(f | (f << 16));                                                      \
+            }                                                                                        \
+_Pragma("unroll")                                                                                    \
+            for (int tn = 0; tn < 2; ++tn) {                                                         \
+                const bf16x8 lo = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(base + b_off[s][0] + tn * 32 * 128)); \
+                const bf16x8 hi = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(base + b_off[s][1] + tn * 32 * 128)); \
+                b[tn] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15); \
+            }                                                                                        \
+_Pragma("unroll")                                                                                    \
+            for (int tm = 0; tm < 4; ++tm)                                                           \
+_Pragma("unroll")                                                                                    \
+                for (int tn = 0; tn < 2; ++tn)                                                       \
+                    acc[tm][tn] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(a[tm], b[tn], acc[tm][tn], idx[tm], 0, 0); \
+        }                                                                                            \
+    }
+
     const int nstages = (int)(d_in / AP_KT);
     AP_ISSUE(0);
     if (nstages > 1) AP_ISSUE(1);
-    for (int st = 0; st < nstages; ++st) {
-        // stage st has landed once at most the loads of stage st+1 are outstanding
-        if (st + 1 < nstages) { AP_WAIT_VMCNT(AP_DMA_PER_STAGE); } else { AP_WAIT_VMCNT(0); }
-        AP_BARRIER(); // everyone's share of stage st is in LDS; everyone is done reading stage st-1
-        if (st + 2 < nstages) AP_ISSUE(st + 2); // into the slot stage st-1 occupied
-        const uint8_t *base = lds + (st % AP_SLOTS) * AP_SLOT_BYTES;
-        uint2 meta[4];
-#pragma unroll
-        for (int tm = 0; tm < 4; ++tm) meta[tm] = *reinterpret_cast<const uint2 *>(base + m_off + tm * 32 * 8);
-#pragma unroll
-        for (int s = 0; s < 2; ++s) {
-            bf16x8 a[4];
-            bf16x16 b[2];
-            int idx[4];
-#pragma unroll
-            for (int tm = 0; tm < 4; ++tm) {
-                a[tm] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(base + a_off[s] + tm * 32 * 64));
-                const uint32_t word = s == 0 ? meta[tm].x : meta[tm].y; // 32 index bits of this 32-k step
-                const uint32_t f = (word >> (16 * half)) & 0xffffu;
-                idx[tm] = (int)(f | (f << 16));
-            }
-#pragma unroll
-            for (int tn = 0; tn < 2; ++tn) {
-                const bf16x8 lo = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(base + b_off[s][0] + tn * 32 * 128));
-                const bf16x8 hi = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(base + b_off[s][1] + tn * 32 * 128));
-                b[tn] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);
-            }
-#pragma unroll
-            for (int tm = 0; tm < 4; ++tm)
-#pragma unroll
-                for (int tn = 0; tn < 2; ++tn)
-                    acc[tm][tn] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(a[tm], b[tn], acc[tm][tn], idx[tm], 0, 0);
-        }
+    int st = 0;
+    // steady state: stage st has landed once at most the loads of stage st+1 are outstanding; after the
+    // barrier everyone is done reading stage st-1, whose slot takes stage st+2.  No branches in the trip.
+    for (; st + 2 < nstages; ++st) {
+        AP_WAIT_VMCNT(AP_DMA_PER_STAGE);
+        AP_BARRIER();
+        AP_ISSUE(st + 2);
+        AP_COMPUTE(st);
     }
+    for (; st < nstages; ++st) { // the last two stages: nothing left to issue
+        if (st + 1 < nstages) { AP_WAIT_VMCNT(AP_DMA_PER_STAGE); } else { AP_WAIT_VMCNT(0); }
+        AP_BARRIER();
+        AP_COMPUTE(st);
+    }
+#undef AP_COMPUTE
 #undef AP_ISSUE
     __syncthreads(); // every wave is done with the stage slots: the epilogue reuses them
 
