@@ -304,8 +304,11 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_W_kernel(
             mraw[it][1] = mask_group == 2 ? mp[1] : 0u;
         }
         const int nblk = blk + gridDim.x;
-        if (nblk < nblocks)
-            CH::gload_tile(t0, C + (int64_t)(nblk / nbj) * B * d_in + (int64_t)(nblk % nbj) * B, ldw, tid);
+        {   // unconditional (the last block asks for its own tile again): a request under a condition makes
+            // the wait for the epilogue's operands cover it too
+            const int nb = nblk < nblocks ? nblk : blk;
+            CH::gload_tile(t0, C + (int64_t)(nb / nbj) * B * d_in + (int64_t)(nb % nbj) * B, ldw, tid);
+        }
         __syncthreads();
         acc.zero();
         CH::template mma<true, false, false, false>(acc, sm.Y, sm.X, nullptr, p); // G = A^T U
@@ -655,8 +658,11 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_FB_kernel(
                     mo[tm][tn][r] = gld(mij, off);
                     vo[tm][tn][r] = gld(vij, off);
                 }
-        if (j + 1 < j1) // next block's core tile, underneath the core update below
-            CH::gload_tile(t0, C + (int64_t)i * B * d_in + (int64_t)(j + 1) * B, ldw, tid);
+        // next block's core tile, underneath the core update below.  Unconditional (the last block asks
+        // for its own tile again): under a condition, the paths that meet in front of the update differ
+        // in their outstanding loads and the wait for the moments would cover this request as well.
+        const int jn = min(j + 1, j1 - 1);
+        CH::gload_tile(t0, C + (int64_t)i * B * d_in + (int64_t)jn * B, ldw, tid);
         {   // Adam on the core: g = -2 (T B^T) (.) M; the current values are still in LDS (X = C)
             const float *c0 = sm.X + opaque(p.lane_off(CH::P));
             const uint32_t lb = opaque_u(wboff);
@@ -680,7 +686,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_FB_kernel(
                 }
         }
         __builtin_amdgcn_sched_barrier(0); // the wrapper tile only once the moments have left their registers
-        if (j + 1 < j1) CH::gload_tile(t1, Bw + (int64_t)(j + 1) * B * B, B, tid);
+        CH::gload_tile(t1, Bw + (int64_t)jn * B * B, B, tid);
         __syncthreads();
     }
     float *gp = gApart + (int64_t)blockIdx.x * B * B;
