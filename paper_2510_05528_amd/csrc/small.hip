@@ -678,11 +678,12 @@ template <int N> __device__ double pinv_solve(double (&G)[N][N], const double (&
 
 constexpr int binom(int n, int k) { return (k == 0 || k == n) ? 1 : binom(n - 1, k - 1) + binom(n - 1, k); }
 
-template <int N, int M>
+// SEL = the selection heuristic (a template argument: the pass over the groups then has no branches)
+template <int N, int M, int SEL>
 __global__ __launch_bounds__(256) void sparse_step_kernel(const float *__restrict__ G, float *__restrict__ C,
                                                           uint8_t *__restrict__ mask, const float *__restrict__ K,
                                                           const float *__restrict__ colnorm2, int64_t d_in, int b,
-                                                          int nbj, int nblocks, int selection, uint64_t seed,
+                                                          int nbj, int nblocks, uint64_t seed,
                                                           int64_t t, const float *__restrict__ loss_part,
                                                           double *__restrict__ loss_cont_out) {
     constexpr int NPAT = binom(M, N);
@@ -715,20 +716,15 @@ __global__ __launch_bounds__(256) void sparse_step_kernel(const float *__restric
     for (int kap0 = tid; kap0 < gpb; kap0 += 256 * U) {
         float v[U][M];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int kap = kap0 + u * 256;
-            if (kap < gpb) {
-                const float *g = Gij + (int64_t)(kap >> gsh) * d_in + (kap & (gpr - 1)) * M;
-                if (M == 4) {
-                    float4 x = *reinterpret_cast<const float4 *>(g);
-                    v[u][0] = x.x; v[u][1] = x.y; v[u][2] = x.z; v[u][3] = x.w;
-                } else {
-#pragma unroll
-                    for (int p = 0; p < M; ++p) v[u][p] = g[p];
-                }
+        for (int u = 0; u < U; ++u) { // unconditional loads (index clamped): a group past the end is dropped below
+            const int kap = min(kap0 + u * 256, gpb - 1);
+            const float *g = Gij + (int64_t)(kap >> gsh) * d_in + (kap & (gpr - 1)) * M;
+            if (M == 4) {
+                float4 x = *reinterpret_cast<const float4 *>(g);
+                v[u][0] = x.x; v[u][1] = x.y; v[u][2] = x.z; v[u][3] = x.w;
             } else {
 #pragma unroll
-                for (int p = 0; p < M; ++p) v[u][p] = 0.f;
+                for (int p = 0; p < M; ++p) v[u][p] = g[p];
             }
         }
 #pragma unroll
@@ -736,23 +732,21 @@ __global__ __launch_bounds__(256) void sparse_step_kernel(const float *__restric
             const int kap = kap0 + u * 256;
             const uint64_t z = mix64(zin);
             zin += PHI * 256ULL;
-            if (kap >= gpb) continue;
-            float score;
-            if (selection == 2) {
-                float a = 0.f;
+            float score = 0.f;
+            if (SEL == 2) {
 #pragma unroll
-                for (int p = 0; p < M; ++p) a = fmaf(v[u][p], v[u][p], a);
-                score = sqrtf(a);
+                for (int p = 0; p < M; ++p) score = fmaf(v[u][p], v[u][p], score);
+                score = sqrtf(score);
+            } else if (SEL == 3) {
+                score = 1.f;
             } else {
-                float a = 0.f;
 #pragma unroll
-                for (int p = 0; p < M; ++p) a += fabsf(v[u][p]);
-                score = a;
+                for (int p = 0; p < M; ++p) score += fabsf(v[u][p]);
             }
-            if (selection == 3) score = 1.f;
             float key;
-            if (selection == 1) key = -score;
+            if (SEL == 1) key = -score;
             else key = score > 0.f ? __fdividef(neg_log_uniform(z), score) : INFINITY;
+            if (kap >= gpb) key = INFINITY; // (a NaN key never wins either: the comparison below is false)
             if (key < best_key) { best_key = key; best_kap = kap; }
         }
     }
@@ -846,10 +840,17 @@ __global__ __launch_bounds__(256) void sparse_step_kernel(const float *__restric
 void launch_sparse_step(const Dims &d, const float *G, float *C, uint8_t *mask, const float *K,
                         const float *colnorm2, int N, int M, int selection, uint64_t seed, int64_t t,
                         const float *loss_part, double *loss_cont_out, hipStream_t s) {
+#define ARMOR_SPARSE_LAUNCH(n, m, sel)                                                                        \
+    hipLaunchKernelGGL((sparse_step_kernel<n, m, sel>), dim3(d.nblocks), dim3(256), 0, s, G, C, mask, K, colnorm2,  \
+                       d.d_in, d.b, d.nbj, d.nblocks, seed, t, loss_part, loss_cont_out)
 #define ARMOR_SPARSE_CASE(n, m)                                                                               \
     if (N == n && M == m) {                                                                                   \
-        hipLaunchKernelGGL((sparse_step_kernel<n, m>), dim3(d.nblocks), dim3(256), 0, s, G, C, mask, K, colnorm2, \
-                           d.d_in, d.b, d.nbj, d.nblocks, selection, seed, t, loss_part, loss_cont_out);     \
+        switch (selection) {                                                                                  \
+        case 1: ARMOR_SPARSE_LAUNCH(n, m, 1); break;                                                          \
+        case 2: ARMOR_SPARSE_LAUNCH(n, m, 2); break;                                                          \
+        case 3: ARMOR_SPARSE_LAUNCH(n, m, 3); break;                                                          \
+        default: ARMOR_SPARSE_LAUNCH(n, m, 0); break;                                                         \
+        }                                                                                                     \
         return;                                                                                               \
     }
     ARMOR_SPARSE_CASE(1, 2)
@@ -857,6 +858,7 @@ void launch_sparse_step(const Dims &d, const float *G, float *C, uint8_t *mask, 
     ARMOR_SPARSE_CASE(1, 8) ARMOR_SPARSE_CASE(2, 8) ARMOR_SPARSE_CASE(3, 8) ARMOR_SPARSE_CASE(4, 8)
     ARMOR_SPARSE_CASE(5, 8) ARMOR_SPARSE_CASE(6, 8) ARMOR_SPARSE_CASE(7, 8)
 #undef ARMOR_SPARSE_CASE
+#undef ARMOR_SPARSE_LAUNCH
 }
 
 // ------------------------------------------------------------------------------------------------
