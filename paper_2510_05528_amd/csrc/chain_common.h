@@ -203,33 +203,51 @@ template <int B> struct Chain {
         Frag f0, f1;
         fetch<LT, RT, SCALE>(f0, 0, L, R, Dk, p);
         int k = 0;
+        // The scheduling fences keep the order "request the next group, then the matrix instructions of
+        // the current one": left alone, the scheduler sinks the LDS reads to just in front of their
+        // first use inside the kernels, and every group then waits for its own operands.
+#define ARMOR_MMA_FENCE() __builtin_amdgcn_sched_barrier(0)
         if constexpr (ZERO) { // head trip
             fetch<LT, RT, SCALE>(f1, 2 * G, L, R, Dk, p);
+            ARMOR_MMA_FENCE();
             issue<true>(acc, f0);
+            ARMOR_MMA_FENCE();
             fetch<LT, RT, SCALE>(f0, 4 * G, L, R, Dk, p);
+            ARMOR_MMA_FENCE();
             issue(acc, f1);
+            ARMOR_MMA_FENCE();
             k = 4 * G;
         }
         if constexpr (PEEL) {
 #pragma unroll 1
             for (; k < B - 4 * G; k += 4 * G) {
                 fetch<LT, RT, SCALE>(f1, k + 2 * G, L, R, Dk, p);
+                ARMOR_MMA_FENCE();
                 issue(acc, f0);
+                ARMOR_MMA_FENCE();
                 fetch<LT, RT, SCALE>(f0, k + 4 * G, L, R, Dk, p);
+                ARMOR_MMA_FENCE();
                 issue(acc, f1);
+                ARMOR_MMA_FENCE();
             }
             fetch<LT, RT, SCALE>(f1, B - 2 * G, L, R, Dk, p);
+            ARMOR_MMA_FENCE();
             issue(acc, f0);
             issue(acc, f1);
         } else {
 #pragma unroll 1
             for (; k < B; k += 4 * G) {
                 fetch<LT, RT, SCALE>(f1, k + 2 * G, L, R, Dk, p);
+                ARMOR_MMA_FENCE();
                 issue(acc, f0);
+                ARMOR_MMA_FENCE();
                 if (k + 4 * G < B) fetch<LT, RT, SCALE>(f0, k + 4 * G, L, R, Dk, p);
+                ARMOR_MMA_FENCE();
                 issue(acc, f1);
+                ARMOR_MMA_FENCE();
             }
         }
+#undef ARMOR_MMA_FENCE
     }
 
     // Squared Frobenius norm of the symmetric product X X^T (XT = false; rows of the tile) or X^T X
