@@ -554,7 +554,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_FB_kernel(
         __syncthreads();
         CH::gload_tile(t0, A + (int64_t)i * B * B, B, tid);
         acc.zero();
-        CH::template mma<false, false, false, false>(acc, sm.X, sm.Y, nullptr, p); // S = C B
+        CH::template mma<false, false, false>(acc, sm.X, sm.Y, nullptr, p); // S = C B
         __syncthreads();
         CH::store_acc(sm.X, acc, p);
         CH::lstore_tile(sm.Y, t0, tid);
@@ -570,7 +570,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_FB_kernel(
                     for (int r = 0; r < 16; ++r) wb[tm][tn][r] = gld(Wij, lb + CH::Pos::unif_boff(tm, tn, r, ldw));
             __syncthreads();
             acc.zero();
-            CH::template mma<false, false, false, false>(acc, sm.Y, sm.X, nullptr, p); // What = A S
+            CH::template mma<false, false, false>(acc, sm.Y, sm.X, nullptr, p); // What = A S
 #pragma unroll
             for (int tm = 0; tm < CH::TM; ++tm)
 #pragma unroll
@@ -589,13 +589,13 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_FB_kernel(
         CH::store_acc(sm.Y, acc, p); // R D          [X = S, Y = R D]
         __syncthreads();
         CH::gload_tile(t0, A + (int64_t)i * B * B, B, tid);
-        CH::template mma<false, true, false, false>(gacc, sm.Y, sm.X, nullptr, p); // grad_A += (R D) S^T
+        CH::template mma<false, true, false>(gacc, sm.Y, sm.X, nullptr, p); // grad_A += (R D) S^T
         __syncthreads();
         CH::lstore_tile(sm.X, t0, tid); //            [X = A, Y = R D]
         __syncthreads();
         CH::gload_tile(t0, Bw + (int64_t)j * B * B, B, tid);
         acc.zero();
-        CH::template mma<true, false, false, false>(acc, sm.X, sm.Y, nullptr, p); // T = A^T (R D)
+        CH::template mma<true, false, false>(acc, sm.X, sm.Y, nullptr, p); // T = A^T (R D)
         __syncthreads();
         CH::store_acc(sm.Y, acc, p);
         CH::lstore_tile(sm.X, t0, tid); //            [X = B, Y = T]
@@ -616,7 +616,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_FB_kernel(
                         mraw[tm][tn][r] = gld(mb, mlane + (uint32_t)((tm * 32 + (r >> 2) * 8 + (r & 3)) * (int)mrow));
                 }
             acc.zero();
-            CH::template mma<false, true, false, false>(acc, sm.Y, sm.X, nullptr, p); // T B^T  (stays in acc for the core update)
+            CH::template mma<false, true, false>(acc, sm.Y, sm.X, nullptr, p); // T B^T  (stays in acc for the core update)
 #pragma unroll
             for (int tm = 0; tm < CH::TM; ++tm)
 #pragma unroll
@@ -633,7 +633,7 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_FB_kernel(
         __syncthreads();
         typename CH::Acc acc2;
         acc2.zero();
-        CH::template mma<true, false, false, false>(acc2, sm.X, sm.Y, nullptr, p); // C^T T
+        CH::template mma<true, false, false>(acc2, sm.X, sm.Y, nullptr, p); // C^T T
         {
             float *gb = gBpart + ((int64_t)j * nbi + i) * B * B;
             const uint32_t lb = opaque_u(p.lane_boff(B));
