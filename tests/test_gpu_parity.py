@@ -189,7 +189,7 @@ def test_factorize_selection_modes(armor, torch, orc, sel):
     check_factorization(armor, torch, orc, W, D, 32, 2, 4, 6, seed=2, selection=sel)
 
 
-@pytest.mark.parametrize("N,M", [(4, 8), (1, 4), (3, 4), (5, 8), (6, 8), (1, 2)])
+@pytest.mark.parametrize("N,M", [(4, 8), (1, 4), (3, 4), (5, 8), (6, 8), (1, 2), (2, 8), (3, 8), (7, 8), (1, 8)])
 def test_factorize_general_nm(armor, torch, orc, N, M):
     W, X = make_layer(128, 192, 200, seed=6)
     D = np.diag(orc.gram(X)).astype(np.float32)
