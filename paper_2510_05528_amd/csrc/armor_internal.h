@@ -34,6 +34,9 @@ void launch_wrapper_grams(const Dims &d, const float *A, const float *B, const f
 void launch_phase_WS(const Dims &d, const float *Wbar, float *C, const float *A, const float *B, const float *D,
                      const float *AtA, const float *K, const uint8_t *mask, int mask_group, const float *fro2A,
                      const float *fro2K, float *Gout, float *loss_part, const float *Sp, int grid_cap, hipStream_t s);
+void launch_phase_WS_stream(const Dims &d, const float *Wbar, float *C, const float *A, const float *B, const float *D,
+                     const float *AtA, const float *K, const uint8_t *mask, int mask_group, const float *fro2A,
+                     const float *fro2K, float *Gout, float *loss_part, const float *Sp, int grid_cap, hipStream_t s);
 int chain_max_nsplit();
 // Joint-Adam forward/backward pass: gradients of A (gApart, nsplit chunks per row block), B (gBpart,
 // one partial per block, laid out [j][i]) and the Adam update of the core and its moments in place.

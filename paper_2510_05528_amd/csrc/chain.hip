@@ -941,6 +941,11 @@ void launch_phase_GS(const Dims &d, const float *Wbar, const float *C, const flo
 void launch_phase_WS(const Dims &d, const float *Wbar, float *C, const float *A, const float *B, const float *D,
                      const float *AtA, const float *K, const uint8_t *mask, int mask_group, const float *fro2A,
                      const float *fro2K, float *Gout, float *loss_part, const float *Sp, int grid_cap, hipStream_t s) {
+    if (d.b == 128 && Sp != nullptr) { // the form with two workgroups per CU (chain_stream.hip)
+        launch_phase_WS_stream(d, Wbar, C, A, B, D, AtA, K, mask, mask_group, fro2A, fro2K, Gout, loss_part, Sp,
+                               2 * grid_cap, s);
+        return;
+    }
     ARMOR_DISPATCH_B(d.b, {
         dim3 grid(std::min(d.nblocks, grid_cap)), block(Chain<BB>::NT);
         hipLaunchKernelGGL((phase_WS_kernel<BB>), grid, block, 0, s, Wbar, C, A, B, D, AtA, K, mask, mask_group,

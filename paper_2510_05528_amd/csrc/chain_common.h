@@ -52,8 +52,8 @@ template <> struct Cfg<64>  { static constexpr int WM = 2, WN = 2, TM = 1, TN = 
 // 64 x 64 or 16 waves of 32 x 32, but the only shape that leaves registers for operand prefetch).
 template <> struct Cfg<128> { static constexpr int WM = 2, WN = 4, TM = 2, TN = 1; };
 
-template <int B> struct Chain {
-    static constexpr int WM = Cfg<B>::WM, WN = Cfg<B>::WN, TM = Cfg<B>::TM, TN = Cfg<B>::TN;
+template <int B, class C = Cfg<B>> struct Chain {
+    static constexpr int WM = C::WM, WN = C::WN, TM = C::TM, TN = C::TN;
     static constexpr int NW = WM * WN, NT = NW * 64, P = B + 1;
     static constexpr int TILE_FLOATS = B * P;
     static_assert(WM * TM * 32 == B && WN * TN * 32 == B, "wave tiling must cover the block");
@@ -365,15 +365,15 @@ template <int B> struct Smem {
     float eta;
 };
 
-template <int B>
-__device__ __forceinline__ void publish_eta_W(Smem<B> &sm, int tid, const float *__restrict__ fro2A, int nA,
+template <class SM>
+__device__ __forceinline__ void publish_eta_W(SM &sm, int tid, const float *__restrict__ fro2A, int nA,
                                               const float *__restrict__ fro2K, int nK) {
     if (tid < 64) { // wave 0; visible to the others after the next barrier
         const float e = wave_eta_W(fro2A, nA, fro2K, nK);
         if (tid == 0) sm.eta = e;
     }
 }
-template <int B> __device__ __forceinline__ float read_eta_W(const Smem<B> &sm) {
+template <class SM> __device__ __forceinline__ float read_eta_W(const SM &sm) {
     return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(sm.eta))); // uniform: scalar register
 }
 

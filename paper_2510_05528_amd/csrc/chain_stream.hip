@@ -1,0 +1,307 @@
+// Per-block contraction chains at b = 128 with one operand resident in LDS and the other streamed
+// from global memory straight into matrix-instruction fragments (same mathematics as chain.hip:
+// Alg. 2 / App. D, Alg. 3's gradient; that file states what each phase computes).
+//
+// Why a second form.  With both operand tiles of a product staged in LDS (chain.hip) a workgroup
+// holds 2 x 66 KB, so one workgroup owns a CU, and everything that is not a matrix instruction
+// (LDS hand-over of a result, tile staging, barriers, the epilogue arithmetic, waiting for Wbar)
+// leaves the matrix pipes idle.  Here only the operand that was just computed on the CU sits in LDS
+// (66 KB); the other one comes from L2 / HBM as fragments: a lane asks for exactly the elements the
+// matrix instruction wants from it, a few k-groups ahead of their use.  Two 256-thread workgroups
+// then share a CU (2 x 75 KB of LDS, at most 256 VGPRs per wave), and one's epilogue runs
+// underneath the other's products.  Nothing is staged, so a product has no barrier inside it.
+//
+// k-slot map.  v_mfma_f32_32x32x2_f32 takes from lane (x = lane % 32, h = lane / 32) the operand
+// element (x, k-slot h) of the step.  Which k of the inner dimension a slot stands for is free as
+// long as both operands agree.  Steps come in groups of four (8 inner indices); step i of group q
+// gives lane half h the index k = 8 q + 4 h + i.  A lane of a k-contiguous operand then needs four
+// consecutive floats per group: one 16-byte load.
+#include "chain_common.h"
+
+#include <algorithm>
+
+namespace armor {
+
+namespace {
+
+struct CfgStream { static constexpr int WM = 2, WN = 2, TM = 2, TN = 2; };
+constexpr int SB = 128;
+using CS = Chain<SB, CfgStream>;
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+struct SmemStream {
+    float X[CS::TILE_FLOATS];
+    float red[16];
+    float eta;
+    uint2 M[SB * 64 / 8]; // the block's mask bytes, rows of 64 bytes (at most one byte per two columns)
+};
+
+// Where an operand op(x, k) of a product lives (x: its row index for the left operand, its column
+// index for the right one; k: the inner index):
+enum class Src {
+    GK, // global memory, k contiguous: g[x * ld + k]
+    GX, // global memory, x contiguous: g[k * ld + x]
+    LK, // LDS tile of pitch P, k contiguous: T[x * P + k]
+    LX, // LDS tile of pitch P, x contiguous: T[k * P + x]
+};
+constexpr bool is_global(Src s) { return s == Src::GK || s == Src::GX; }
+
+constexpr int NGROUP = SB / 8;
+
+// One operand's fragments: f[q][i][t] for group q, step i, 32-wide tile t of this wave.  Indices are
+// compile-time everywhere (the product is fully unrolled), so only the groups in flight hold registers.
+template <Src S> struct Operand {
+    const float *base;
+    uint32_t lane; // byte offset (global) or float index (LDS) of this lane's element (x0, k = 4 h)
+    uint32_t tile; // the same kind of offset from tile 0 to tile 1
+    uint32_t ld4;  // bytes per k step (GX)
+    float f[NGROUP][4][2];
+
+    __device__ __forceinline__ Operand(const float *b, int ld, int x0, int kh) : base(b) {
+        if constexpr (S == Src::GK) { lane = opaque_u(4u * (uint32_t)(x0 * ld + 4 * kh)); tile = 4u * 32u * (uint32_t)ld; ld4 = 0; }
+        if constexpr (S == Src::GX) { lane = opaque_u(4u * (uint32_t)(4 * kh * ld + x0)); tile = 4u * 32u; ld4 = 4u * (uint32_t)ld; }
+        if constexpr (S == Src::LK) { lane = opaque_u((uint32_t)(x0 * CS::P + 4 * kh)); tile = 32u * CS::P; ld4 = 0; }
+        if constexpr (S == Src::LX) { lane = opaque_u((uint32_t)(4 * kh * CS::P + x0)); tile = 32u; ld4 = 0; }
+    }
+    __device__ __forceinline__ void request(int q) {
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            if constexpr (S == Src::GK) {
+                const floatx4 v = gld(reinterpret_cast<const floatx4 *>(base), lane + t * tile + 32u * q);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) f[q][i][t] = v[i];
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    if constexpr (S == Src::GX) f[q][i][t] = gld(base, lane + t * tile + (uint32_t)(8 * q + i) * ld4);
+                    if constexpr (S == Src::LK) f[q][i][t] = base[lane + t * tile + 8 * q + i];
+                    if constexpr (S == Src::LX) f[q][i][t] = base[lane + t * tile + (8 * q + i) * CS::P];
+                }
+            }
+        }
+    }
+};
+
+// acc (+)= opL * opR over the 128 inner indices; ZERO: acc = opL * opR (the first matrix instruction
+// of every tile takes a zero C operand); NEGR: opR enters negated.  Global operands are requested
+// DEPTH groups ahead (a group's matrix instructions take ~0.43 us per wave: 3 groups cover an L2
+// hit; measured 2 and 3 alike, 4 and 5 slower), LDS operands one group ahead.
+// tail() runs once, behind the product's last global request.  Loads return in issue order, so a
+// request that goes to HBM holds up every later one: what the caller wants from HBM next is asked
+// for there and travels underneath the remaining matrix instructions and the hand-over that follows.
+constexpr int STREAM_DEPTH = 3;
+struct NoTail {
+    __device__ void operator()() const {}
+};
+template <Src LS, Src RS, bool ZERO, bool NEGR = false, class Tail = NoTail>
+__device__ __forceinline__ void mma_stream(CS::Acc &acc, const float *L, int ldl, const float *R, int ldr,
+                                           const CS::Pos &p, Tail &&tail = Tail()) {
+    constexpr int DEPTH = STREAM_DEPTH;
+    Operand<LS> l(L, ldl, p.wm0 + p.l32, p.kh);
+    Operand<RS> r(R, ldr, p.wn0 + p.l32, p.kh);
+#pragma unroll
+    for (int q = 0; q < DEPTH; ++q) {
+        if constexpr (is_global(LS)) l.request(q);
+        if constexpr (is_global(RS)) r.request(q);
+    }
+    if constexpr (!is_global(LS)) l.request(0);
+    if constexpr (!is_global(RS)) r.request(0);
+#pragma unroll
+    for (int q = 0; q < NGROUP; ++q) {
+        if (q + DEPTH < NGROUP) {
+            if constexpr (is_global(LS)) l.request(q + DEPTH);
+            if constexpr (is_global(RS)) r.request(q + DEPTH);
+        }
+        if (q == NGROUP - 1 - DEPTH) tail();
+        if (q + 1 < NGROUP) {
+            if constexpr (!is_global(LS)) l.request(q + 1);
+            if constexpr (!is_global(RS)) r.request(q + 1);
+        }
+        // requests first, then the group's matrix instructions: left alone, the scheduler sinks the
+        // requests to just in front of their first use
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < 2; ++tn) {
+                    const float rv = NEGR ? -r.f[q][i][tn] : r.f[q][i][tn];
+                    if (ZERO && q == 0 && i == 0) {
+                        const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                        acc.v[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x2f32(l.f[q][i][tm], rv, zero, 0, 0, 0);
+                    } else {
+                        acc.v[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x2f32(l.f[q][i][tm], rv, acc.v[tm][tn], 0, 0, 0);
+                    }
+                }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+// A reduction variable is evaluated where this stands.  Without it the compiler is free to form the
+// sum where it is used, after later products, and keeps every addend in a register until then.
+__device__ __forceinline__ void settle(float &v) { asm volatile("" : "+v"(v)); }
+
+// ------------------------------------------------------------------------------------------------
+// W' step fused with the core gradient at the updated core (see phase_WS_kernel in chain.hip for the
+// identities).  Per block, with S' = A C handed over by the B step:
+//   R = Wbar - S' B      both operands streamed (S' k-contiguous, B^j column-contiguous); Wbar is
+//                        loaded into the accumulator and the product runs as Wbar + S' (-B)
+//   U = (R D) B^T        R D resident, B^j streamed k-contiguous
+//   G = A^T U            U resident, A^i streamed row-contiguous
+//   V = Delta K          Delta = G (.) M resident, K^j streamed
+//   Z = (A^T A) V        V resident, A^T A streamed
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(CS::NT, 2) void phase_WS_stream_kernel(
+    const float *__restrict__ Wbar, float *__restrict__ C, const float *__restrict__ A,
+    const float *__restrict__ Bw, const float *__restrict__ D, const float *__restrict__ AtA,
+    const float *__restrict__ K, const uint8_t *__restrict__ mask, int mask_group,
+    const float *__restrict__ fro2A, int nA, const float *__restrict__ fro2K, int nK, int64_t d_in, int nbj,
+    int nblocks, float *__restrict__ Gout, float *__restrict__ loss_part, const float *__restrict__ Sp) {
+    constexpr int B = SB;
+    __shared__ SmemStream sm;
+    const int tid = threadIdx.x;
+    const CS::Pos p(tid);
+    const int ldw = (int)d_in;
+    const uint32_t wboff = p.lane_boff(ldw);
+    const int64_t mrow = d_in / mask_group;
+    CS::Acc acc, acc2;
+    publish_eta_W(sm, tid, fro2A, nA, fro2K, nK);
+    __syncthreads();
+    const float eta2 = read_eta_W(sm);
+    const int nb = B / mask_group; // mask bytes per block row: 16, 32 or 64
+    const uint32_t mhalf = (uint32_t)((tid >> 1) * 64 + (tid & 1) * (nb >> 1));
+    // Wbar of a block and its mask bytes (thread t: half of row t / 2, 8 bytes at a time) are requested
+    // at the end of the block before.  Wbar lands in the accumulator of the block's first product: no
+    // second set of registers holds it.  The mask bytes wait in LDS for the W' step.
+    CS::Acc accw;
+    uint2 mreg[4];
+    auto request_block = [&](int blk) {
+        const int i = blk / nbj, j = blk % nbj;
+        const float *Wij = Wbar + (int64_t)i * B * d_in + (int64_t)j * B;
+        const uint8_t *mb = mask + (int64_t)i * B * mrow + (int64_t)j * nb;
+        const uint32_t mo = (uint32_t)((tid >> 1) * (int)mrow + (tid & 1) * (nb >> 1));
+        const uint32_t lb = opaque_u(wboff);
+#pragma unroll
+        for (int it = 0; it < 4; ++it)
+            if (it * 16 < nb) mreg[it] = gld(reinterpret_cast<const uint2 *>(mb), mo + 8u * it);
+#pragma unroll
+        for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+            for (int tn = 0; tn < 2; ++tn)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) accw.v[tm][tn][r] = gld(Wij, lb + CS::Pos::unif_boff(tm, tn, r, ldw));
+    };
+    if ((int)blockIdx.x < nblocks) request_block(blockIdx.x);
+    for (int blk = blockIdx.x; blk < nblocks; blk += gridDim.x) {
+        const int i = blk / nbj, j = blk % nbj;
+        float *Cij = C + (int64_t)i * B * d_in + (int64_t)j * B;
+        const float *Sij = Sp + (int64_t)i * B * d_in + (int64_t)j * B;
+        const float *Ai = A + (int64_t)i * B * B, *Bj = Bw + (int64_t)j * B * B;
+        const float *Dj = D + (int64_t)j * B;
+        float lsum = 0.f;
+        mma_stream<Src::GK, Src::GX, false, true>(accw, Sij, ldw, Bj, B, p); // R = Wbar - S' B
+#pragma unroll
+        for (int tn = 0; tn < 2; ++tn) {
+            const float dj = Dj[p.col(tn)];
+#pragma unroll
+            for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float res = accw.v[tm][tn][r];
+                    lsum += res * res * dj;
+                    accw.v[tm][tn][r] = res * dj;
+                }
+        }
+        settle(lsum);
+        CS::store_acc(sm.X, accw, p); // R D   (the previous block is done with X and M: barriers at its end)
+#pragma unroll
+        for (int it = 0; it < 4; ++it)
+            if (it * 16 < nb) *reinterpret_cast<uint2 *>(reinterpret_cast<char *>(sm.M) + mhalf + 8u * it) = mreg[it];
+        __syncthreads();
+        mma_stream<Src::LK, Src::GK, true>(acc, sm.X, 0, Bj, B, p); // U = (R D) B^T
+        __syncthreads();
+        CS::store_acc(sm.X, acc, p);
+        __syncthreads();
+        // current core values in the accumulator layout, requested behind the product's last operands
+        float cv[2][2][16];
+        mma_stream<Src::GX, Src::LX, true>(acc, Ai, B, sm.X, 0, p, [&]() { // G = A^T U   (stays in acc)
+            const uint32_t lb = opaque_u(wboff);
+#pragma unroll
+            for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < 2; ++tn)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) cv[tm][tn][r] = gld(Cij, lb + CS::Pos::unif_boff(tm, tn, r, ldw));
+        });
+        __syncthreads();
+        // W' step on kept entries; Delta = G (.) M goes to LDS for the two extra products
+        uint32_t keep[2][2];
+        float dd = 0.f;
+        {
+            float *d0 = sm.X + opaque(p.lane_off(CS::P));
+            const uint32_t lb = opaque_u(wboff);
+            const uint8_t *ml = reinterpret_cast<const uint8_t *>(sm.M);
+#pragma unroll
+            for (int tn = 0; tn < 2; ++tn) {
+                const uint32_t mo = opaque_u((uint32_t)((p.wm0 + p.kh * 4) * 64 + p.col(tn) / mask_group));
+                const int sh = p.col(tn) % mask_group;
+#pragma unroll
+                for (int tm = 0; tm < 2; ++tm) {
+                    keep[tm][tn] = 0u;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const uint32_t mbyte = ml[mo + (uint32_t)((tm * 32 + (r >> 2) * 8 + (r & 3)) * 64)];
+                        const bool kp = (mbyte >> sh) & 1u;
+                        keep[tm][tn] |= (kp ? 1u : 0u) << r;
+                        const float dl = kp ? acc.v[tm][tn][r] : 0.f;
+                        dd += dl * dl;
+                        d0[CS::Pos::unif_off(tm, tn, r, CS::P)] = dl;
+                        // (pruned entries are written back as they were: no branch around the store, same lines)
+                        gst(Cij, lb + CS::Pos::unif_boff(tm, tn, r, ldw), cv[tm][tn][r] + eta2 * dl);
+                    }
+                    keep[tm][tn] = opaque_u(keep[tm][tn]); // the masked values themselves are not kept in registers
+                }
+            }
+        }
+        settle(dd);
+        __syncthreads();
+        mma_stream<Src::LK, Src::GX, true>(acc2, sm.X, 0, K + (int64_t)j * B * B, B, p); // V = Delta K
+        __syncthreads();
+        CS::store_acc(sm.X, acc2, p);
+        __syncthreads();
+        mma_stream<Src::GK, Src::LX, true>(acc2, AtA + (int64_t)i * B * B, B, sm.X, 0, p); // Z = (A^T A) V
+        request_block(min(blk + (int)gridDim.x, nblocks - 1)); // (the last block asks for itself again: harmless)
+        float dz = 0.f;
+        {
+            float *Gij = Gout + (int64_t)i * B * d_in + (int64_t)j * B;
+            const uint32_t lb = opaque_u(wboff);
+#pragma unroll
+            for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < 2; ++tn)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const float g = acc.v[tm][tn][r], z = acc2.v[tm][tn][r];
+                        if ((keep[tm][tn] >> r) & 1u) dz += g * z;
+                        gst(Gij, lb + CS::Pos::unif_boff(tm, tn, r, ldw), -2.f * (g - eta2 * z));
+                    }
+        }
+        float ltot = CS::block_sum(lsum - 2.f * eta2 * dd + eta2 * eta2 * dz, sm.red, tid); // (barriers: X is free again)
+        if (tid == 0) loss_part[blk] = ltot;
+    }
+}
+
+} // namespace
+
+void launch_phase_WS_stream(const Dims &d, const float *Wbar, float *C, const float *A, const float *B,
+                            const float *D, const float *AtA, const float *K, const uint8_t *mask, int mask_group,
+                            const float *fro2A, const float *fro2K, float *Gout, float *loss_part, const float *Sp,
+                            int grid_cap, hipStream_t s) {
+    dim3 grid(std::min(d.nblocks, grid_cap)), block(CS::NT);
+    hipLaunchKernelGGL(phase_WS_stream_kernel, grid, block, 0, s, Wbar, C, A, B, D, AtA, K, mask, mask_group, fro2A,
+                       d.nbi * gram_parts(d.b), fro2K, d.nbj * gram_parts(d.b), d.d_in, d.nbj, d.nblocks, Gout,
+                       loss_part, Sp);
+}
+
+} // namespace armor
