@@ -97,8 +97,8 @@ int chain_slots(int b) { return device_cus() * (b >= 128 ? 1 : 2); }
 // How many chunks to split the accumulation axis of a gradient phase into: workgroup (k, c) walks
 // `chunk` blocks and leaves one b x b partial.  Cost model in units of one block's chain time:
 // rounds * (chunk + a small charge for writing the partial); finer splits balance the tail.
-int choose_nsplit(int n_outer, int n_inner, int b) {
-    const int slots = chain_slots(b);
+int choose_nsplit(int n_outer, int n_inner, int b, int slots = 0) {
+    if (slots == 0) slots = chain_slots(b);
     int best = 1;
     double best_cost = 1e300;
     for (int ns = 1; ns <= n_inner && ns <= chain_max_nsplit(); ++ns) {
@@ -132,6 +132,7 @@ struct FactorWs {
     uint8_t *mask;
     void *unstructured;
     float *big_scratch;
+    float *stream_scratch; // one b x b tile per workgroup of a gradient phase (streamed-operand form, d_block 128)
     float *mA, *vA, *mB, *vB, *mC, *vC, *gBpart;
     int nsA, nsB, cn_chunks;
     size_t bytes;
@@ -158,15 +159,19 @@ FactorWs carve_factor(void *ws, const Dims &d, int mask_group, const armor_opts 
     FactorWs f;
     Carver c(ws);
     const size_t P = (size_t)d.d_out * d.d_in, bb = (size_t)d.b * d.b;
-    f.nsA = choose_nsplit(d.nbi, d.nbj, d.b);
-    f.nsB = choose_nsplit(d.nbj, d.nbi, d.b);
+    const bool adam = opts && opts->variant == 1, unstr = opts && opts->sparsity == 1;
+    // the sequential variant at d_block 128 runs its gradient phases with two workgroups per CU
+    const bool stream = !adam && d.b == 128;
+    const int slots = chain_slots(d.b) * (stream ? 2 : 1);
+    f.nsA = choose_nsplit(d.nbi, d.nbj, d.b, slots);
+    f.nsB = choose_nsplit(d.nbj, d.nbi, d.b, slots);
     f.cn_chunks = colnorm_chunks(d.d_out);
     f.Wbar = c.take<float>(P);
     f.G = c.take<float>(P);
-    const bool adam = opts && opts->variant == 1, unstr = opts && opts->sparsity == 1;
     f.Sp = (!adam && (d.b > 128 || !unstr)) ? c.take<float>(P) : nullptr;
     f.D = c.take<float>(d.d_in);
     f.gpart = c.take<float>(std::max((size_t)d.nbi * f.nsA, (size_t)d.nbj * f.nsB) * bb);
+    f.stream_scratch = stream ? c.take<float>(std::max((size_t)d.nbi * f.nsA, (size_t)d.nbj * f.nsB) * bb) : nullptr;
     f.beta_part = c.take<float>(d.nblocks);
     f.loss_part = c.take<float>(d.nblocks);
     f.loss_part2 = c.take<float>(d.nblocks);
@@ -354,7 +359,7 @@ armor_status armor_proxy_loss(const float *Wbar, const float *A, const float *S,
         launch_big_phase_A(d, Wbar, S, A, B, D, choose_nsplit(d.nbi, d.nbj, d.b), nullptr, nullptr, loss_part, true,
                            chain_slots(d.b), big, s);
     else
-        launch_phase_A(d, Wbar, S, A, B, D, choose_nsplit(d.nbi, d.nbj, d.b), nullptr, nullptr, loss_part, true, s);
+        launch_phase_A(d, Wbar, S, A, B, D, choose_nsplit(d.nbi, d.nbj, d.b), nullptr, nullptr, loss_part, true, nullptr, s);
     launch_sum_to_double(loss_part, d.nblocks, loss_out, s);
     return check_hip();
 }
@@ -433,7 +438,7 @@ armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const flo
     auto run_phase_A = [&](bool loss_only) {
         if (big) launch_big_phase_A(d, f.Wbar, S, A, B, f.D, f.nsA, f.gpart, f.beta_part, f.loss_part, loss_only, slots,
                                     f.big_scratch, s);
-        else launch_phase_A(d, f.Wbar, S, A, B, f.D, f.nsA, f.gpart, f.beta_part, f.loss_part, loss_only, s);
+        else launch_phase_A(d, f.Wbar, S, A, B, f.D, f.nsA, f.gpart, f.beta_part, f.loss_part, loss_only, f.stream_scratch, s);
     };
     if (o.variant == 1) {
         const double lr = o.lr > 0 ? o.lr : 1e-4, b1 = o.adam_beta1 > 0 ? o.adam_beta1 : 0.9,
@@ -492,7 +497,7 @@ armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const flo
         {
             ProfScope ps(ARMOR_PROF_PHASE_B, s, true);
             if (big) launch_big_phase_B(d, f.Wbar, S, A, B, f.D, f.nsB, f.gpart, f.beta_part, f.Sp, slots, f.big_scratch, s);
-            else launch_phase_B(d, f.Wbar, S, A, B, f.D, f.nsB, f.gpart, f.beta_part, unstructured ? nullptr : f.Sp, s);
+            else launch_phase_B(d, f.Wbar, S, A, B, f.D, f.nsB, f.gpart, f.beta_part, unstructured ? nullptr : f.Sp, f.stream_scratch, s);
         }
         {
             ProfScope ps(ARMOR_PROF_SMALL, s, true);

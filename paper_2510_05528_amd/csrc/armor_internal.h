@@ -17,10 +17,20 @@ struct Dims {
 // A-phase of Alg. 2: per block S = C B, R = Wbar - A S, partial grad_A, ||S D S^T||_F, block loss.
 void launch_phase_A(const Dims &d, const float *Wbar, const float *C, const float *A, const float *B,
                     const float *D, int nsplit, float *gpart, float *beta_part, float *loss_part,
-                    bool loss_only, hipStream_t s);
+                    bool loss_only, float *stream_scratch, hipStream_t s);
 // B-phase: S' = A C, R = Wbar - S' B, partial grad_B, ||S'^T S'||_F ||D^j||_F.
 void launch_phase_B(const Dims &d, const float *Wbar, const float *C, const float *A, const float *B,
-                    const float *D, int nsplit, float *gpart, float *beta_part, float *Sp, hipStream_t s);
+                    const float *D, int nsplit, float *gpart, float *beta_part, float *Sp, float *stream_scratch,
+                    hipStream_t s);
+// The same phases at d_block 128 with one operand streamed from global memory and two workgroups
+// per CU (chain_stream.hip); launch_phase_A / _B / _WS go there when given the scratch (A, B: one
+// b x b tile per workgroup) or S' (W' step).
+void launch_phase_A_stream(const Dims &d, const float *Wbar, const float *C, const float *A, const float *B,
+                           const float *D, int nsplit, float *gpart, float *beta_part, float *loss_part,
+                           float *scratch, hipStream_t s);
+void launch_phase_B_stream(const Dims &d, const float *Wbar, const float *C, const float *A, const float *B,
+                           const float *D, int nsplit, float *gpart, float *beta_part, float *Sp, float *scratch,
+                           hipStream_t s);
 // W' step of Alg. 2 alone (unstructured mode): C += (2/beta_W) (A^T ((Wbar - A C B) D) B^T) (.) M, beta_W
 // read from scalars[2].  grid_cap workgroups at most, each walking blocks w, w + grid, ...
 void launch_phase_W(const Dims &d, const float *Wbar, float *C, const float *A, const float *B, const float *D,

@@ -878,7 +878,11 @@ int gram_parts(int b) { return b <= 128 ? b / 32 : 1; }
 
 void launch_phase_A(const Dims &d, const float *Wbar, const float *C, const float *A, const float *B,
                     const float *D, int nsplit, float *gpart, float *beta_part, float *loss_part,
-                    bool loss_only, hipStream_t s) {
+                    bool loss_only, float *stream_scratch, hipStream_t s) {
+    if (d.b == 128 && !loss_only && stream_scratch != nullptr) { // the form with two workgroups per CU (chain_stream.hip)
+        launch_phase_A_stream(d, Wbar, C, A, B, D, nsplit, gpart, beta_part, loss_part, stream_scratch, s);
+        return;
+    }
     ARMOR_DISPATCH_B(d.b, {
         dim3 grid(d.nbi * nsplit), block(Chain<BB>::NT);
         if (loss_only)
@@ -891,7 +895,12 @@ void launch_phase_A(const Dims &d, const float *Wbar, const float *C, const floa
 }
 
 void launch_phase_B(const Dims &d, const float *Wbar, const float *C, const float *A, const float *B,
-                    const float *D, int nsplit, float *gpart, float *beta_part, float *Sp, hipStream_t s) {
+                    const float *D, int nsplit, float *gpart, float *beta_part, float *Sp, float *stream_scratch,
+                    hipStream_t s) {
+    if (d.b == 128 && stream_scratch != nullptr) {
+        launch_phase_B_stream(d, Wbar, C, A, B, D, nsplit, gpart, beta_part, Sp, stream_scratch, s);
+        return;
+    }
     ARMOR_DISPATCH_B(d.b, {
         dim3 grid(d.nbj * nsplit), block(Chain<BB>::NT);
         hipLaunchKernelGGL((phase_B_kernel<BB>), grid, block, 0, s, Wbar, C, A, B, D, d.d_in, d.nbi, d.nbj, nsplit,

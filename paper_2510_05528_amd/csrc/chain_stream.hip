@@ -86,14 +86,17 @@ template <Src S> struct Operand {
 // of every tile takes a zero C operand); NEGR: opR enters negated.  Global operands are requested
 // DEPTH groups ahead (a group's matrix instructions take ~0.43 us per wave: 3 groups cover an L2
 // hit; measured 2 and 3 alike, 4 and 5 slower), LDS operands one group ahead.
-// tail() runs once, behind the product's last global request.  Loads return in issue order, so a
-// request that goes to HBM holds up every later one: what the caller wants from HBM next is asked
-// for there and travels underneath the remaining matrix instructions and the hand-over that follows.
+// tail() runs once, TAIL_BACK groups before the end: at or behind the product's last global request.
+// Loads return in issue order, so a request that goes to HBM holds up every later one: what the
+// caller wants from HBM next is asked for there and travels underneath the remaining matrix
+// instructions and the hand-over that follows (a smaller TAIL_BACK when registers are short: fewer
+// operand groups are still held).
 constexpr int STREAM_DEPTH = 3;
+
 struct NoTail {
     __device__ void operator()() const {}
 };
-template <Src LS, Src RS, bool ZERO, bool NEGR = false, class Tail = NoTail>
+template <Src LS, Src RS, bool ZERO, bool NEGR = false, int TAIL_BACK = STREAM_DEPTH, class Tail = NoTail>
 __device__ __forceinline__ void mma_stream(CS::Acc &acc, const float *L, int ldl, const float *R, int ldr,
                                            const CS::Pos &p, Tail &&tail = Tail()) {
     constexpr int DEPTH = STREAM_DEPTH;
@@ -112,7 +115,7 @@ __device__ __forceinline__ void mma_stream(CS::Acc &acc, const float *L, int ldl
             if constexpr (is_global(LS)) l.request(q + DEPTH);
             if constexpr (is_global(RS)) r.request(q + DEPTH);
         }
-        if (q == NGROUP - 1 - DEPTH) tail();
+        if (q == NGROUP - 1 - TAIL_BACK) tail();
         if (q + 1 < NGROUP) {
             if constexpr (!is_global(LS)) l.request(q + 1);
             if constexpr (!is_global(RS)) r.request(q + 1);
@@ -225,7 +228,7 @@ __global__ __launch_bounds__(CS::NT, 2) void phase_WS_stream_kernel(
         __syncthreads();
         // current core values in the accumulator layout, requested behind the product's last operands
         float cv[2][2][16];
-        mma_stream<Src::GX, Src::LX, true>(acc, Ai, B, sm.X, 0, p, [&]() { // G = A^T U   (stays in acc)
+        mma_stream<Src::GX, Src::LX, true, false, STREAM_DEPTH>(acc, Ai, B, sm.X, 0, p, [&]() { // G = A^T U   (stays in acc)
             const uint32_t lb = opaque_u(wboff);
 #pragma unroll
             for (int tm = 0; tm < 2; ++tm)
@@ -292,7 +295,271 @@ __global__ __launch_bounds__(CS::NT, 2) void phase_WS_stream_kernel(
     }
 }
 
+// deterministic workgroup-wide sums of two values at once; results valid in thread 0
+__device__ __forceinline__ void block_sum2(float &a, float &b, float *red, int tid) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        a += __shfl_xor(a, off, 64);
+        b += __shfl_xor(b, off, 64);
+    }
+    __syncthreads();
+    if ((tid & 63) == 0) { red[tid >> 6] = a; red[8 + (tid >> 6)] = b; }
+    __syncthreads();
+    if (tid == 0) {
+        a = 0.f; b = 0.f;
+        for (int w = 0; w < CS::NW; ++w) { a += red[w]; b += red[8 + w]; }
+    }
+}
+
+__device__ __forceinline__ float frob2(const CS::Acc &acc) {
+    float f2 = 0.f;
+#pragma unroll
+    for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < 2; ++tn)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) f2 += acc.v[tm][tn][r] * acc.v[tm][tn][r];
+    return f2;
+}
+
+// Squared Frobenius norm of the symmetric product X X^T (XT = false) or X^T X (XT = true) of the
+// resident tile, as this lane's share of the sum: only the 10 upper-triangular 32 x 32 tiles of the
+// 4 x 4 grid are formed, off-diagonal ones counted twice.  Two waves take three tiles and two take
+// two; `flip` swaps the two kinds (callers pass it for the second half of the grid, which is what
+// lands in the CUs' second slots), so that the two workgroups of a CU put their heavy waves on
+// different SIMDs.  Both operands come from LDS: no global request is outstanding behind this.
+template <bool XT> __device__ __forceinline__ float sym_frob2_stream(const float *X, const CS::Pos &p, int tid, bool flip) {
+    const int w = (tid >> 6) ^ (flip ? 2 : 0);
+    // wave -> tiles (row tile, column tile): w0 (0,0)(0,1)(1,1), w1 (0,2)(0,3)(1,2), w2 (1,3)(2,3), w3 (2,2)(3,3)
+    const int r0 = w == 0 ? 0 : w == 1 ? 0 : w == 2 ? 1 : 2, c0 = w == 0 ? 0 : w == 1 ? 2 : w == 2 ? 3 : 2;
+    const int r1 = w == 0 ? 0 : w == 1 ? 0 : w == 2 ? 2 : 3, c1 = w == 0 ? 1 : w == 1 ? 3 : 3;
+    const int r2 = 1, c2 = w == 0 ? 1 : 2;
+    const bool three = w < 2;
+    const int xs = XT ? 1 : CS::P, ks = XT ? CS::P : 1; // strides of the tile index and of k
+    const float *base = X + p.l32 * xs + p.kh * ks;
+    const float *a0 = base + 32 * r0 * xs, *b0 = base + 32 * c0 * xs;
+    const float *a1 = base + 32 * r1 * xs, *b1 = base + 32 * c1 * xs;
+    const float *a2 = base + 32 * r2 * xs, *b2 = base + 32 * c2 * xs;
+    floatx16 t0, t1, t2;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { t0[r] = 0.f; t1[r] = 0.f; t2[r] = 0.f; }
+    if (three) {
+#pragma unroll 8
+        for (int k = 0; k < SB; k += 2) {
+            t0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[k * ks], b0[k * ks], t0, 0, 0, 0);
+            t1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[k * ks], b1[k * ks], t1, 0, 0, 0);
+            t2 = __builtin_amdgcn_mfma_f32_32x32x2f32(a2[k * ks], b2[k * ks], t2, 0, 0, 0);
+        }
+    } else {
+#pragma unroll 8
+        for (int k = 0; k < SB; k += 2) {
+            t0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[k * ks], b0[k * ks], t0, 0, 0, 0);
+            t1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[k * ks], b1[k * ks], t1, 0, 0, 0);
+        }
+    }
+    float s0 = 0.f, s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { s0 += t0[r] * t0[r]; s1 += t1[r] * t1[r]; s2 += t2[r] * t2[r]; }
+    return (r0 == c0 ? s0 : 2.f * s0) + (r1 == c1 ? s1 : 2.f * s1) + (r2 == c2 ? s2 : 2.f * s2);
+}
+
+struct SmemGrad {
+    float X[CS::TILE_FLOATS];
+    float red[16];
+};
+
+// ------------------------------------------------------------------------------------------------
+// A-phase (see phase_A_kernel in chain.hip).  Per block:
+//   S sqrt(D) = (C B) sqrt(D)        both operands streamed; result resident
+//   R sqrt(D) = Wbar sqrt(D) - A (S sqrt D)    A^i streamed; Wbar, scaled, is the accumulator's start
+//   gacc += (R sqrt D)(S sqrt D)^T   R sqrt(D) goes through the workgroup's 64 KB of global scratch
+//                                    (it stays in L2) and comes back as the streamed operand
+//   || (S sqrt D)(S sqrt D)^T ||_F   both operands resident
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(CS::NT, 2) void phase_A_stream_kernel(
+    const float *__restrict__ Wbar, const float *__restrict__ C, const float *__restrict__ A,
+    const float *__restrict__ Bw, const float *__restrict__ D, int64_t d_in, int nbj, int nsplit,
+    float *__restrict__ gpart, float *__restrict__ beta_part, float *__restrict__ loss_part,
+    float *__restrict__ scratch) {
+    constexpr int B = SB;
+    __shared__ SmemGrad sm;
+    const int tid = threadIdx.x;
+    const CS::Pos p(tid);
+    const int ldw = (int)d_in;
+    const uint32_t wboff = p.lane_boff(ldw);
+    const int i = blockIdx.x / nsplit, c = blockIdx.x % nsplit;
+    const int chunk = (nbj + nsplit - 1) / nsplit;
+    const int j0 = c * chunk, j1 = min(nbj, j0 + chunk);
+    float *sc = scratch + (int64_t)blockIdx.x * B * B;
+    const float *Ai = A + (int64_t)i * B * B;
+    CS::Acc gacc, acc, accw;
+    gacc.zero();
+    float *gp = gpart + (int64_t)blockIdx.x * B * B;
+    const uint32_t gb = p.lane_boff(B);
+    for (int j = j0; j < j1; ++j) {
+        const float *Cij = C + (int64_t)i * B * d_in + (int64_t)j * B;
+        const float *Wij = Wbar + (int64_t)i * B * d_in + (int64_t)j * B;
+        const float *Bj = Bw + (int64_t)j * B * B;
+        const bool first = j == j0;
+        auto reqW = [&]() {
+            const uint32_t lb = opaque_u(wboff);
+#pragma unroll
+            for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < 2; ++tn)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) accw.v[tm][tn][r] = gld(Wij, lb + CS::Pos::unif_boff(tm, tn, r, ldw));
+        };
+        mma_stream<Src::GK, Src::GX, true, false, 1>(acc, Cij, ldw, Bj, B, p, reqW); // S = C B; Wbar requested behind it
+        float sq[2];
+#pragma unroll
+        for (int tn = 0; tn < 2; ++tn) {
+            sq[tn] = sqrtf(D[(int64_t)j * B + p.col(tn)]);
+#pragma unroll
+            for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc.v[tm][tn][r] *= sq[tn];
+        }
+        CS::store_acc(sm.X, acc, p); // S sqrt(D)   (the previous block is done with X: barriers at its end)
+        __syncthreads();
+#pragma unroll
+        for (int tn = 0; tn < 2; ++tn)
+#pragma unroll
+            for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) accw.v[tm][tn][r] *= sq[tn];
+        mma_stream<Src::GK, Src::LX, false, true>(accw, Ai, B, sm.X, 0, p); // R sqrt(D)
+        float lsum = frob2(accw);
+        settle(lsum);
+        {
+            const uint32_t lb = opaque_u(gb);
+#pragma unroll
+            for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < 2; ++tn)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) gst(sc, lb + CS::Pos::unif_boff(tm, tn, r, B), accw.v[tm][tn][r]);
+        }
+        __syncthreads(); // scratch written by the whole workgroup (same CU, same L1: in order)
+        mma_stream<Src::GK, Src::LK, false>(gacc, sc, B, sm.X, 0, p); // += (R sqrt D)(S sqrt D)^T
+        float f2 = sym_frob2_stream<false>(sm.X, p, tid, 2 * blockIdx.x >= gridDim.x); // || (S sqrt D)(S sqrt D)^T ||_F^2
+        block_sum2(lsum, f2, sm.red, tid); // (barriers: X and the scratch are free again)
+        if (tid == 0) {
+            loss_part[i * nbj + j] = lsum;
+            beta_part[i * nbj + j] = sqrtf(f2);
+        }
+    }
+    const uint32_t lb = opaque_u(gb);
+#pragma unroll
+    for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < 2; ++tn)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) gst(gp, lb + CS::Pos::unif_boff(tm, tn, r, B), -2.f * gacc.v[tm][tn][r]);
+}
+
+// ------------------------------------------------------------------------------------------------
+// B-phase (see phase_B_kernel in chain.hip).  Per block:
+//   S' = A C                     both operands streamed; result resident, and written out for the W' step
+//   R D = (Wbar - S' B) D        B^j streamed; Wbar is the accumulator's start
+//   gacc += S'^T (R D)           R D through the workgroup's global scratch
+//   || S'^T S' ||_F              both operands resident
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(CS::NT, 2) void phase_B_stream_kernel(
+    const float *__restrict__ Wbar, const float *__restrict__ C, const float *__restrict__ A,
+    const float *__restrict__ Bw, const float *__restrict__ D, int64_t d_in, int nbi, int nbj, int nsplit,
+    float *__restrict__ gpart, float *__restrict__ beta_part, float *__restrict__ Sp,
+    float *__restrict__ scratch) {
+    constexpr int B = SB;
+    __shared__ SmemGrad sm;
+    const int tid = threadIdx.x;
+    const CS::Pos p(tid);
+    const int ldw = (int)d_in;
+    const uint32_t wboff = p.lane_boff(ldw);
+    const int j = blockIdx.x / nsplit, c = blockIdx.x % nsplit;
+    const int chunk = (nbi + nsplit - 1) / nsplit;
+    const int i0 = c * chunk, i1 = min(nbi, i0 + chunk);
+    float *sc = scratch + (int64_t)blockIdx.x * B * B;
+    const float *Bj = Bw + (int64_t)j * B * B, *Dj = D + (int64_t)j * B;
+    float dj[2];
+#pragma unroll
+    for (int tn = 0; tn < 2; ++tn) dj[tn] = Dj[p.col(tn)];
+    float dn2 = 0.f;
+    if (tid == 0)
+        for (int q = 0; q < B; ++q) dn2 += Dj[q] * Dj[q];
+    CS::Acc gacc, acc, accw;
+    gacc.zero();
+    float *gp = gpart + (int64_t)blockIdx.x * B * B;
+    const uint32_t gb = p.lane_boff(B);
+    for (int i = i0; i < i1; ++i) {
+        const float *Cij = C + (int64_t)i * B * d_in + (int64_t)j * B;
+        const float *Wij = Wbar + (int64_t)i * B * d_in + (int64_t)j * B;
+        const float *Ai = A + (int64_t)i * B * B;
+        const bool first = i == i0;
+        auto reqW = [&]() {
+            const uint32_t lb = opaque_u(wboff);
+#pragma unroll
+            for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < 2; ++tn)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) accw.v[tm][tn][r] = gld(Wij, lb + CS::Pos::unif_boff(tm, tn, r, ldw));
+        };
+        mma_stream<Src::GK, Src::GX, true, false, 1>(acc, Ai, B, Cij, ldw, p, reqW); // S' = A C; Wbar requested behind it
+        CS::store_acc(sm.X, acc, p); // (the previous block is done with X: barriers at its end)
+        if (Sp != nullptr) { // A and C do not change until the W' step: that step takes S' from here
+            float *Sij = Sp + (int64_t)i * B * d_in + (int64_t)j * B;
+            const uint32_t lb = opaque_u(wboff);
+#pragma unroll
+            for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < 2; ++tn)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) gst(Sij, lb + CS::Pos::unif_boff(tm, tn, r, ldw), acc.v[tm][tn][r]);
+        }
+        __syncthreads();
+        mma_stream<Src::LK, Src::GX, false, true>(accw, sm.X, 0, Bj, B, p); // R = Wbar - S' B
+        {
+            const uint32_t lb = opaque_u(gb);
+#pragma unroll
+            for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < 2; ++tn)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) gst(sc, lb + CS::Pos::unif_boff(tm, tn, r, B), accw.v[tm][tn][r] * dj[tn]); // R D
+        }
+        __syncthreads(); // scratch written by the whole workgroup (same CU, same L1: in order)
+        mma_stream<Src::LX, Src::GX, false>(gacc, sm.X, 0, sc, B, p); // += S'^T (R D)
+        float f2 = sym_frob2_stream<true>(sm.X, p, tid, 2 * blockIdx.x >= gridDim.x), unused = 0.f; // || S'^T S' ||_F^2
+        block_sum2(f2, unused, sm.red, tid); // (barriers: X and the scratch are free again)
+        if (tid == 0) beta_part[i * nbj + j] = sqrtf(f2) * sqrtf(dn2);
+    }
+    const uint32_t lb = opaque_u(gb);
+#pragma unroll
+    for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < 2; ++tn)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) gst(gp, lb + CS::Pos::unif_boff(tm, tn, r, B), -2.f * gacc.v[tm][tn][r]);
+}
+
 } // namespace
+
+void launch_phase_A_stream(const Dims &d, const float *Wbar, const float *C, const float *A, const float *B,
+                           const float *D, int nsplit, float *gpart, float *beta_part, float *loss_part,
+                           float *scratch, hipStream_t s) {
+    dim3 grid(d.nbi * nsplit), block(CS::NT);
+    hipLaunchKernelGGL(phase_A_stream_kernel, grid, block, 0, s, Wbar, C, A, B, D, d.d_in, d.nbj, nsplit, gpart,
+                       beta_part, loss_part, scratch);
+}
+
+void launch_phase_B_stream(const Dims &d, const float *Wbar, const float *C, const float *A, const float *B,
+                           const float *D, int nsplit, float *gpart, float *beta_part, float *Sp, float *scratch,
+                           hipStream_t s) {
+    dim3 grid(d.nbj * nsplit), block(CS::NT);
+    hipLaunchKernelGGL(phase_B_stream_kernel, grid, block, 0, s, Wbar, C, A, B, D, d.d_in, d.nbi, d.nbj, nsplit, gpart,
+                       beta_part, Sp, scratch);
+}
 
 void launch_phase_WS_stream(const Dims &d, const float *Wbar, float *C, const float *A, const float *B,
                             const float *D, const float *AtA, const float *K, const uint8_t *mask, int mask_group,
