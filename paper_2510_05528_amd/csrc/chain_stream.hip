@@ -63,16 +63,19 @@ template <Src S> struct Operand {
         if constexpr (S == Src::LK) { lane = opaque_u((uint32_t)(x0 * CS::P + 4 * kh)); tile = 32u * CS::P; ld4 = 0; }
         if constexpr (S == Src::LX) { lane = opaque_u((uint32_t)(4 * kh * CS::P + x0)); tile = 32u; ld4 = 0; }
     }
-    __device__ __forceinline__ void request(int q) {
+    // a quarter of group q's requests (part 0..3), or all of them (part < 0)
+    __device__ __forceinline__ void request(int q, int part = -1) {
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
             if constexpr (S == Src::GK) {
+                if (part >= 0 && part != t) continue;
                 const floatx4 v = gld(reinterpret_cast<const floatx4 *>(base), lane + t * tile + 32u * q);
 #pragma unroll
                 for (int i = 0; i < 4; ++i) f[q][i][t] = v[i];
             } else {
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
+                    if (part >= 0 && part != i) continue;
                     if constexpr (S == Src::GX) f[q][i][t] = gld(base, lane + t * tile + (uint32_t)(8 * q + i) * ld4);
                     if constexpr (S == Src::LK) f[q][i][t] = base[lane + t * tile + 8 * q + i];
                     if constexpr (S == Src::LX) f[q][i][t] = base[lane + t * tile + (8 * q + i) * CS::P];
@@ -85,60 +88,79 @@ template <Src S> struct Operand {
 // acc (+)= opL * opR over the 128 inner indices; ZERO: acc = opL * opR (the first matrix instruction
 // of every tile takes a zero C operand); NEGR: opR enters negated.  Global operands are requested
 // DEPTH groups ahead (a group's matrix instructions take ~0.43 us per wave: 3 groups cover an L2
-// hit; measured 2 and 3 alike, 4 and 5 slower), LDS operands one group ahead.
+// hit; measured 2 and 3 alike, 4 and 5 slower; 2 leaves more registers), LDS operands one group ahead.
 // tail() runs once, TAIL_BACK groups before the end: at or behind the product's last global request.
 // Loads return in issue order, so a request that goes to HBM holds up every later one: what the
 // caller wants from HBM next is asked for there and travels underneath the remaining matrix
 // instructions and the hand-over that follows (a smaller TAIL_BACK when registers are short: fewer
 // operand groups are still held).
-constexpr int STREAM_DEPTH = 3;
+constexpr int STREAM_DEPTH = 2;
 
 struct NoTail {
     __device__ void operator()() const {}
 };
+// A product: begin() asks for the global operands' first groups, run() does the rest.  (Starting the
+// requests of the next product in front of an epilogue's stores was measured: no gain.)
+template <Src LS, Src RS> struct Product {
+    static constexpr int DEPTH = STREAM_DEPTH;
+    Operand<LS> l;
+    Operand<RS> r;
+    __device__ __forceinline__ Product(const float *L, int ldl, const float *R, int ldr, const CS::Pos &p)
+        : l(L, ldl, p.wm0 + p.l32, p.kh), r(R, ldr, p.wn0 + p.l32, p.kh) {}
+    // the global operands' first DEPTH groups
+    __device__ __forceinline__ void begin() {
+#pragma unroll
+        for (int q = 0; q < DEPTH; ++q) {
+            if constexpr (is_global(LS)) l.request(q);
+            if constexpr (is_global(RS)) r.request(q);
+        }
+    }
+    template <bool ZERO, bool NEGR = false, int TAIL_BACK = STREAM_DEPTH, class Tail = NoTail>
+    __device__ __forceinline__ void run(CS::Acc &acc, Tail &&tail = Tail()) {
+        if constexpr (!is_global(LS)) l.request(0);
+        if constexpr (!is_global(RS)) r.request(0);
+#pragma unroll
+        for (int q = 0; q < NGROUP; ++q) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if (q + DEPTH < NGROUP) {
+                    if constexpr (is_global(LS)) l.request(q + DEPTH, i);
+                    if constexpr (is_global(RS)) r.request(q + DEPTH, i);
+                }
+                if (i == 3 && q == NGROUP - 1 - TAIL_BACK) tail();
+                if (q + 1 < NGROUP) {
+                    if constexpr (!is_global(LS)) l.request(q + 1, i);
+                    if constexpr (!is_global(RS)) r.request(q + 1, i);
+                }
+                // A quarter of a later group's requests, then one step's matrix instructions: the requests
+                // issue while the matrix pipe works off the step before (measured 3 % faster than whole groups
+                // of requests in front of whole groups of matrix instructions).  The fences keep that order:
+                // left alone, the scheduler sinks the requests to just in front of their first use.
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+                    for (int tn = 0; tn < 2; ++tn) {
+                        const float rv = NEGR ? -r.f[q][i][tn] : r.f[q][i][tn];
+                        if (ZERO && q == 0 && i == 0) {
+                            const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                            acc.v[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x2f32(l.f[q][i][tm], rv, zero, 0, 0, 0);
+                        } else {
+                            acc.v[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x2f32(l.f[q][i][tm], rv, acc.v[tm][tn], 0, 0, 0);
+                        }
+                    }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    }
+};
+
 template <Src LS, Src RS, bool ZERO, bool NEGR = false, int TAIL_BACK = STREAM_DEPTH, class Tail = NoTail>
 __device__ __forceinline__ void mma_stream(CS::Acc &acc, const float *L, int ldl, const float *R, int ldr,
                                            const CS::Pos &p, Tail &&tail = Tail()) {
-    constexpr int DEPTH = STREAM_DEPTH;
-    Operand<LS> l(L, ldl, p.wm0 + p.l32, p.kh);
-    Operand<RS> r(R, ldr, p.wn0 + p.l32, p.kh);
-#pragma unroll
-    for (int q = 0; q < DEPTH; ++q) {
-        if constexpr (is_global(LS)) l.request(q);
-        if constexpr (is_global(RS)) r.request(q);
-    }
-    if constexpr (!is_global(LS)) l.request(0);
-    if constexpr (!is_global(RS)) r.request(0);
-#pragma unroll
-    for (int q = 0; q < NGROUP; ++q) {
-        if (q + DEPTH < NGROUP) {
-            if constexpr (is_global(LS)) l.request(q + DEPTH);
-            if constexpr (is_global(RS)) r.request(q + DEPTH);
-        }
-        if (q == NGROUP - 1 - TAIL_BACK) tail();
-        if (q + 1 < NGROUP) {
-            if constexpr (!is_global(LS)) l.request(q + 1);
-            if constexpr (!is_global(RS)) r.request(q + 1);
-        }
-        // requests first, then the group's matrix instructions: left alone, the scheduler sinks the
-        // requests to just in front of their first use
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int tm = 0; tm < 2; ++tm)
-#pragma unroll
-                for (int tn = 0; tn < 2; ++tn) {
-                    const float rv = NEGR ? -r.f[q][i][tn] : r.f[q][i][tn];
-                    if (ZERO && q == 0 && i == 0) {
-                        const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-                        acc.v[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x2f32(l.f[q][i][tm], rv, zero, 0, 0, 0);
-                    } else {
-                        acc.v[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x2f32(l.f[q][i][tm], rv, acc.v[tm][tn], 0, 0, 0);
-                    }
-                }
-        __builtin_amdgcn_sched_barrier(0);
-    }
+    Product<LS, RS> pr(L, ldl, R, ldr, p);
+    pr.begin();
+    pr.template run<ZERO, NEGR, TAIL_BACK>(acc, tail);
 }
 
 // A reduction variable is evaluated where this stands.  Without it the compiler is free to form the
@@ -410,7 +432,7 @@ __global__ __launch_bounds__(CS::NT, 2) void phase_A_stream_kernel(
 #pragma unroll
                     for (int r = 0; r < 16; ++r) accw.v[tm][tn][r] = gld(Wij, lb + CS::Pos::unif_boff(tm, tn, r, ldw));
         };
-        mma_stream<Src::GK, Src::GX, true, false, 1>(acc, Cij, ldw, Bj, B, p, reqW); // S = C B; Wbar requested behind it
+        mma_stream<Src::GK, Src::GX, true, false, STREAM_DEPTH>(acc, Cij, ldw, Bj, B, p, reqW); // S = C B; Wbar requested behind it
         float sq[2];
 #pragma unroll
         for (int tn = 0; tn < 2; ++tn) {
@@ -505,18 +527,8 @@ __global__ __launch_bounds__(CS::NT, 2) void phase_B_stream_kernel(
 #pragma unroll
                     for (int r = 0; r < 16; ++r) accw.v[tm][tn][r] = gld(Wij, lb + CS::Pos::unif_boff(tm, tn, r, ldw));
         };
-        mma_stream<Src::GK, Src::GX, true, false, 1>(acc, Ai, B, Cij, ldw, p, reqW); // S' = A C; Wbar requested behind it
+        mma_stream<Src::GK, Src::GX, true, false, STREAM_DEPTH>(acc, Ai, B, Cij, ldw, p, reqW); // S' = A C; Wbar requested behind it
         CS::store_acc(sm.X, acc, p); // (the previous block is done with X: barriers at its end)
-        if (Sp != nullptr) { // A and C do not change until the W' step: that step takes S' from here
-            float *Sij = Sp + (int64_t)i * B * d_in + (int64_t)j * B;
-            const uint32_t lb = opaque_u(wboff);
-#pragma unroll
-            for (int tm = 0; tm < 2; ++tm)
-#pragma unroll
-                for (int tn = 0; tn < 2; ++tn)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) gst(Sij, lb + CS::Pos::unif_boff(tm, tn, r, ldw), acc.v[tm][tn][r]);
-        }
         __syncthreads();
         mma_stream<Src::LK, Src::GX, false, true>(accw, sm.X, 0, Bj, B, p); // R = Wbar - S' B
         {
@@ -530,6 +542,21 @@ __global__ __launch_bounds__(CS::NT, 2) void phase_B_stream_kernel(
         }
         __syncthreads(); // scratch written by the whole workgroup (same CU, same L1: in order)
         mma_stream<Src::LX, Src::GX, false>(gacc, sm.X, 0, sc, B, p); // += S'^T (R D)
+        // A and C do not change until the W' step: that step takes S' from here.  Stores complete in
+        // issue order with the loads, so S' leaves from its LDS copy here, where the next global
+        // request is a whole product away (the symmetric product reads LDS only).
+        if (Sp != nullptr) {
+            float *Sij = Sp + (int64_t)i * B * d_in + (int64_t)j * B;
+            const uint32_t lb = opaque_u(wboff);
+            const float *x0 = sm.X + opaque(p.lane_off(CS::P));
+#pragma unroll
+            for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < 2; ++tn)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        gst(Sij, lb + CS::Pos::unif_boff(tm, tn, r, ldw), x0[CS::Pos::unif_off(tm, tn, r, CS::P)]);
+        }
         float f2 = sym_frob2_stream<true>(sm.X, p, tid, 2 * blockIdx.x >= gridDim.x), unused = 0.f; // || S'^T S' ||_F^2
         block_sum2(f2, unused, sm.red, tid); // (barriers: X and the scratch are free again)
         if (tid == 0) beta_part[i * nbj + j] = sqrtf(f2) * sqrtf(dn2);
