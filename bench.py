@@ -62,9 +62,9 @@ BF16_MFMA_PEAK = 2.5e15    # MI355X dense bf16 matrix peak, FLOP/s
 # same counter reads for a plain 256 MiB device copy (factors 2.000 and 1.000); see
 # profiles/chain_kernels_llama7b_attn_pmc.txt.  Keyed by (workload, kernel); other workloads: null.
 MEASURED_TRAFFIC_BYTES = {
-    ("llama7b_attn_4096x4096_b128_2:4_50it", "phase_WS"): (259.5 + 130.5) * 2 ** 20,
-    ("llama7b_attn_4096x4096_b128_2:4_50it", "phase_A"): (186.2 + 16.1) * 2 ** 20,
-    ("llama7b_attn_4096x4096_b128_2:4_50it", "phase_B"): (194.3 + 80.0) * 2 ** 20,
+    ("llama7b_attn_4096x4096_b128_2:4_50it", "phase_WS"): (252.0 + 128.0) * 2 ** 20,
+    ("llama7b_attn_4096x4096_b128_2:4_50it", "phase_A"): (226.7 + 96.1) * 2 ** 20,
+    ("llama7b_attn_4096x4096_b128_2:4_50it", "phase_B"): (226.0 + 160.0) * 2 ** 20,
 }
 
 
