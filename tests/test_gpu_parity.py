@@ -196,6 +196,15 @@ def test_factorize_general_nm(armor, torch, orc, N, M):
     check_factorization(armor, torch, orc, W, D, 64, N, M, 5, seed=4)
 
 
+@pytest.mark.parametrize("d_out,d_in,N,M", [(256, 384, 4, 8), (256, 384, 1, 2), (384, 256, 3, 4), (256, 256, 2, 8), (128, 128, 2, 4)])
+def test_factorize_block128_patterns(armor, torch, orc, d_out, d_in, N, M):
+    """d_block = 128 runs the streamed-operand chains, whose W' step takes the mask from an LDS copy with
+    16, 32 or 64 bytes per block row (M = 8, 4, 2); the last case is a single block (a grid of one)."""
+    W, X = make_layer(d_out, d_in, 300, seed=21, act_outliers=(0.01, 20.0))
+    D = np.diag(orc.gram(X)).astype(np.float32)
+    check_factorization(armor, torch, orc, W, D, 128, N, M, 4, seed=9)
+
+
 @pytest.mark.parametrize("d_out,d_in,N,M,iters", [(512, 768, 2, 4, 3), (768, 256, 4, 8, 3)])
 def test_factorize_block256(armor, torch, orc, d_out, d_in, N, M, iters):
     """d_block = 256 (the 70B-shaped stress config): sub-tiled chains with L2-resident scratch."""
