@@ -28,6 +28,8 @@ void launch_phase_B(const Dims &d, const float *Wbar, const float *C, const floa
 void launch_phase_A_stream(const Dims &d, const float *Wbar, const float *C, const float *A, const float *B,
                            const float *D, int nsplit, float *gpart, float *beta_part, float *loss_part,
                            float *scratch, hipStream_t s);
+void launch_phase_GS_stream(const Dims &d, const float *Wbar, const float *C, const float *A, const float *B,
+                            const float *D, float *Gout, float *loss_part, int grid_cap, hipStream_t s);
 void launch_phase_B_stream(const Dims &d, const float *Wbar, const float *C, const float *A, const float *B,
                            const float *D, int nsplit, float *gpart, float *beta_part, float *Sp, float *scratch,
                            hipStream_t s);

@@ -943,6 +943,10 @@ void launch_phase_FB(const Dims &d, const float *Wbar, float *C, const float *A,
 
 void launch_phase_GS(const Dims &d, const float *Wbar, const float *C, const float *A, const float *B, const float *D,
                      float *Gout, float *loss_part, int grid_cap, hipStream_t s) {
+    if (d.b == 128) { // the form with two workgroups per CU (chain_stream.hip)
+        launch_phase_GS_stream(d, Wbar, C, A, B, D, Gout, loss_part, 2 * grid_cap, s);
+        return;
+    }
     ARMOR_DISPATCH_B(d.b, {
         dim3 grid(std::min(d.nblocks, grid_cap)), block(Chain<BB>::NT);
         hipLaunchKernelGGL((phase_GS_kernel<BB>), grid, block, 0, s, Wbar, C, A, B, D, d.d_in, d.nbj, d.nblocks, Gout,

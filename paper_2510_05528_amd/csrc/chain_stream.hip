@@ -570,6 +570,77 @@ __global__ __launch_bounds__(CS::NT, 2) void phase_B_stream_kernel(
             for (int r = 0; r < 16; ++r) gst(gp, lb + CS::Pos::unif_boff(tm, tn, r, B), -2.f * gacc.v[tm][tn][r]);
 }
 
+// ------------------------------------------------------------------------------------------------
+// Core gradient at the current point (see phase_GS_kernel in chain.hip; after the joint-Adam step).
+// Per block:  S' = A C (both streamed), R = Wbar - S' B, U = (R D) B^T, G = A^T U; Gout = -2 G.
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(CS::NT, 2) void phase_GS_stream_kernel(
+    const float *__restrict__ Wbar, const float *__restrict__ C, const float *__restrict__ A,
+    const float *__restrict__ Bw, const float *__restrict__ D, int64_t d_in, int nbj, int nblocks,
+    float *__restrict__ Gout, float *__restrict__ loss_part) {
+    constexpr int B = SB;
+    __shared__ SmemGrad sm;
+    const int tid = threadIdx.x;
+    const CS::Pos p(tid);
+    const int ldw = (int)d_in;
+    const uint32_t wboff = p.lane_boff(ldw);
+    CS::Acc acc, accw;
+    for (int blk = blockIdx.x; blk < nblocks; blk += gridDim.x) {
+        const int i = blk / nbj, j = blk % nbj;
+        const float *Cij = C + (int64_t)i * B * d_in + (int64_t)j * B;
+        const float *Wij = Wbar + (int64_t)i * B * d_in + (int64_t)j * B;
+        const float *Ai = A + (int64_t)i * B * B, *Bj = Bw + (int64_t)j * B * B;
+        const float *Dj = D + (int64_t)j * B;
+        mma_stream<Src::GK, Src::GX, true>(acc, Ai, B, Cij, ldw, p, [&]() { // S' = A C; Wbar requested behind it
+            const uint32_t lb = opaque_u(wboff);
+#pragma unroll
+            for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < 2; ++tn)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) accw.v[tm][tn][r] = gld(Wij, lb + CS::Pos::unif_boff(tm, tn, r, ldw));
+        });
+        CS::store_acc(sm.X, acc, p); // (the previous block is done with X: barriers at its end)
+        __syncthreads();
+        mma_stream<Src::LK, Src::GX, false, true>(accw, sm.X, 0, Bj, B, p); // R = Wbar - S' B
+        float lsum = 0.f;
+#pragma unroll
+        for (int tn = 0; tn < 2; ++tn) {
+            const float dj = Dj[p.col(tn)];
+#pragma unroll
+            for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float res = accw.v[tm][tn][r];
+                    lsum += res * res * dj;
+                    accw.v[tm][tn][r] = res * dj;
+                }
+        }
+        settle(lsum);
+        __syncthreads();
+        CS::store_acc(sm.X, accw, p); // R D
+        __syncthreads();
+        mma_stream<Src::LK, Src::GK, true>(acc, sm.X, 0, Bj, B, p); // U = (R D) B^T
+        __syncthreads();
+        CS::store_acc(sm.X, acc, p);
+        __syncthreads();
+        mma_stream<Src::GX, Src::LX, true>(acc, Ai, B, sm.X, 0, p); // G = A^T U
+        {
+            float *Gij = Gout + (int64_t)i * B * d_in + (int64_t)j * B;
+            const uint32_t lb = opaque_u(wboff);
+#pragma unroll
+            for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < 2; ++tn)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) gst(Gij, lb + CS::Pos::unif_boff(tm, tn, r, ldw), -2.f * acc.v[tm][tn][r]);
+        }
+        float unused = 0.f;
+        block_sum2(lsum, unused, sm.red, tid); // (barriers: X is free again)
+        if (tid == 0) loss_part[blk] = lsum;
+    }
+}
+
 } // namespace stream
 
 using namespace stream;
@@ -598,6 +669,13 @@ void launch_phase_WS_stream(const Dims &d, const float *Wbar, float *C, const fl
     hipLaunchKernelGGL(phase_WS_stream_kernel, grid, block, 0, s, Wbar, C, A, B, D, AtA, K, mask, mask_group, fro2A,
                        d.nbi * gram_parts(d.b), fro2K, d.nbj * gram_parts(d.b), d.d_in, d.nbj, d.nblocks, Gout,
                        loss_part, Sp);
+}
+
+void launch_phase_GS_stream(const Dims &d, const float *Wbar, const float *C, const float *A, const float *B,
+                            const float *D, float *Gout, float *loss_part, int grid_cap, hipStream_t s) {
+    dim3 grid(std::min(d.nblocks, grid_cap)), block(CS::NT);
+    hipLaunchKernelGGL(phase_GS_stream_kernel, grid, block, 0, s, Wbar, C, A, B, D, d.d_in, d.nbj, d.nblocks, Gout,
+                       loss_part);
 }
 
 } // namespace armor
