@@ -160,8 +160,8 @@ FactorWs carve_factor(void *ws, const Dims &d, int mask_group, const armor_opts 
     Carver c(ws);
     const size_t P = (size_t)d.d_out * d.d_in, bb = (size_t)d.b * d.b;
     const bool adam = opts && opts->variant == 1, unstr = opts && opts->sparsity == 1;
-    // the sequential variant at d_block 128 runs its gradient phases with two workgroups per CU
-    const bool stream = !adam && d.b == 128;
+    // at d_block 128 the gradient phases run with two workgroups per CU (streamed-operand form)
+    const bool stream = d.b == 128;
     const int slots = chain_slots(d.b) * (stream ? 2 : 1);
     f.nsA = choose_nsplit(d.nbi, d.nbj, d.b, slots);
     f.nsB = choose_nsplit(d.nbj, d.nbi, d.b, slots);
@@ -451,7 +451,7 @@ armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const flo
                 if (big) launch_big_phase_FB(d, f.Wbar, S, A, B, f.D, mask, mask_group, f.mC, f.vC, lr, b1, b2, eps, t, f.nsA,
                                              f.gpart, f.gBpart, f.loss_part, slots, f.big_scratch, s);
                 else launch_phase_FB(d, f.Wbar, S, A, B, f.D, mask, mask_group, f.mC, f.vC, lr, b1, b2, eps, t, f.nsA,
-                                     f.gpart, f.gBpart, f.loss_part, s);
+                                     f.gpart, f.gBpart, f.loss_part, f.stream_scratch, s);
             }
             {
                 ProfScope ps(ARMOR_PROF_SMALL, s, true);

@@ -28,6 +28,10 @@ void launch_phase_B(const Dims &d, const float *Wbar, const float *C, const floa
 void launch_phase_A_stream(const Dims &d, const float *Wbar, const float *C, const float *A, const float *B,
                            const float *D, int nsplit, float *gpart, float *beta_part, float *loss_part,
                            float *scratch, hipStream_t s);
+void launch_phase_FB_stream(const Dims &d, const float *Wbar, float *C, const float *A, const float *B,
+                            const float *D, const uint8_t *mask, int mask_group, float *mC, float *vC,
+                            double lr, double b1, double b2, double eps, int64_t t, int nsplit, float *gApart,
+                            float *gBpart, float *loss_part, float *scratch, hipStream_t s);
 void launch_phase_GS_stream(const Dims &d, const float *Wbar, const float *C, const float *A, const float *B,
                             const float *D, float *Gout, float *loss_part, int grid_cap, hipStream_t s);
 void launch_phase_B_stream(const Dims &d, const float *Wbar, const float *C, const float *A, const float *B,
@@ -54,7 +58,8 @@ int chain_max_nsplit();
 // one partial per block, laid out [j][i]) and the Adam update of the core and its moments in place.
 void launch_phase_FB(const Dims &d, const float *Wbar, float *C, const float *A, const float *B, const float *D,
                      const uint8_t *mask, int mask_group, float *mC, float *vC, double lr, double b1, double b2,
-                     double eps, int64_t t, int nsplit, float *gApart, float *gBpart, float *loss_part, hipStream_t s);
+                     double eps, int64_t t, int nsplit, float *gApart, float *gBpart, float *loss_part,
+                     float *stream_scratch, hipStream_t s);
 // Core gradient at the current point: Gout = -2 A^T ((Wbar - A C B) D) B^T, block losses to loss_part.
 void launch_phase_GS(const Dims &d, const float *Wbar, const float *C, const float *A, const float *B, const float *D,
                      float *Gout, float *loss_part, int grid_cap, hipStream_t s);

@@ -932,7 +932,13 @@ void launch_wrapper_grams(const Dims &d, const float *A, const float *B, const f
 
 void launch_phase_FB(const Dims &d, const float *Wbar, float *C, const float *A, const float *B, const float *D,
                      const uint8_t *mask, int mask_group, float *mC, float *vC, double lr, double b1, double b2,
-                     double eps, int64_t t, int nsplit, float *gApart, float *gBpart, float *loss_part, hipStream_t s) {
+                     double eps, int64_t t, int nsplit, float *gApart, float *gBpart, float *loss_part,
+                     float *stream_scratch, hipStream_t s) {
+    if (d.b == 128 && stream_scratch != nullptr) { // the form with two workgroups per CU (chain_stream.hip)
+        launch_phase_FB_stream(d, Wbar, C, A, B, D, mask, mask_group, mC, vC, lr, b1, b2, eps, t, nsplit, gApart,
+                               gBpart, loss_part, stream_scratch, s);
+        return;
+    }
     const AdamCoef k = make_adam_coef(lr, b1, b2, eps, t);
     ARMOR_DISPATCH_B(d.b, {
         dim3 grid(d.nbi * nsplit), block(Chain<BB>::NT);

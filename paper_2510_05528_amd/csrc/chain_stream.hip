@@ -641,6 +641,162 @@ __global__ __launch_bounds__(CS::NT, 2) void phase_GS_stream_kernel(
     }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Forward/backward chain of the joint-Adam variant (see phase_FB_kernel in chain.hip).  Per block:
+//   S = C B                      both operands streamed; resident
+//   R D = (Wbar - A S) D         A^i streamed; Wbar is the accumulator's start; R D also to the scratch
+//   grad_A += (R D) S^T          R D streamed back from the scratch, S resident
+//   T = A^T (R D)                R D (still in registers) made resident; A^i streamed
+//   C^T T -> grad_B partial      T resident, the core tile streamed (it is in L2 since the first product)
+//   T B^T -> grad_W'             stays in the accumulator for the Adam update of the core, which runs
+//                                one 32 x 32 tile at a time with the next tile's moments and core
+//                                values already requested
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(CS::NT, 2) void phase_FB_stream_kernel(
+    const float *__restrict__ Wbar, float *__restrict__ C, const float *__restrict__ A,
+    const float *__restrict__ Bw, const float *__restrict__ D, const uint8_t *__restrict__ mask, int mask_group,
+    float *__restrict__ mC, float *__restrict__ vC, AdamCoef k, int64_t d_in, int nbi, int nbj, int nsplit,
+    float *__restrict__ gApart, float *__restrict__ gBpart, float *__restrict__ loss_part,
+    float *__restrict__ scratch) {
+    constexpr int B = SB;
+    __shared__ SmemStream sm;
+    const int tid = threadIdx.x;
+    const CS::Pos p(tid);
+    const int ldw = (int)d_in;
+    const uint32_t wboff = p.lane_boff(ldw);
+    const int i = blockIdx.x / nsplit, c = blockIdx.x % nsplit;
+    const int chunk = (nbj + nsplit - 1) / nsplit;
+    const int j0 = c * chunk, j1 = min(nbj, j0 + chunk);
+    const int64_t mrow = d_in / mask_group;
+    const int nb = B / mask_group; // mask bytes per block row: 16, 32 or 64
+    const uint32_t mhalf = (uint32_t)((tid >> 1) * 64 + (tid & 1) * (nb >> 1));
+    float *sc = scratch + (int64_t)blockIdx.x * B * B;
+    const float *Ai = A + (int64_t)i * B * B;
+    const uint32_t gb = p.lane_boff(B);
+    CS::Acc gacc, acc, accw;
+    gacc.zero();
+    for (int j = j0; j < j1; ++j) {
+        const int64_t boff = (int64_t)i * B * d_in + (int64_t)j * B;
+        float *Cij = C + boff, *mij = mC + boff, *vij = vC + boff;
+        const float *Wij = Wbar + boff;
+        const float *Bj = Bw + (int64_t)j * B * B, *Dj = D + (int64_t)j * B;
+        uint2 mreg[4];
+        mma_stream<Src::GK, Src::GX, true>(acc, Cij, ldw, Bj, B, p, [&]() { // S = C B; Wbar and the mask bytes behind it
+            const uint8_t *mb = mask + (int64_t)i * B * mrow + (int64_t)j * nb;
+            const uint32_t mo = (uint32_t)((tid >> 1) * (int)mrow + (tid & 1) * (nb >> 1));
+            const uint32_t lb = opaque_u(wboff);
+#pragma unroll
+            for (int it = 0; it < 4; ++it)
+                if (it * 16 < nb) mreg[it] = gld(reinterpret_cast<const uint2 *>(mb), mo + 8u * it);
+#pragma unroll
+            for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < 2; ++tn)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) accw.v[tm][tn][r] = gld(Wij, lb + CS::Pos::unif_boff(tm, tn, r, ldw));
+        });
+        CS::store_acc(sm.X, acc, p); // S   (the previous block is done with X and M: barriers at its end)
+#pragma unroll
+        for (int it = 0; it < 4; ++it)
+            if (it * 16 < nb) *reinterpret_cast<uint2 *>(reinterpret_cast<char *>(sm.M) + mhalf + 8u * it) = mreg[it];
+        __syncthreads();
+        mma_stream<Src::GK, Src::LX, false, true>(accw, Ai, B, sm.X, 0, p); // R = Wbar - A S
+        float lsum = 0.f;
+#pragma unroll
+        for (int tn = 0; tn < 2; ++tn) {
+            const float dj = Dj[p.col(tn)];
+#pragma unroll
+            for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float res = accw.v[tm][tn][r];
+                    lsum += res * res * dj;
+                    accw.v[tm][tn][r] = res * dj;
+                }
+        }
+        settle(lsum);
+        {
+            const uint32_t lb = opaque_u(gb);
+#pragma unroll
+            for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < 2; ++tn)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) gst(sc, lb + CS::Pos::unif_boff(tm, tn, r, B), accw.v[tm][tn][r]);
+        }
+        __syncthreads(); // scratch written by the whole workgroup (same CU, same L1: in order)
+        mma_stream<Src::GK, Src::LK, false>(gacc, sc, B, sm.X, 0, p); // grad_A += (R D) S^T
+        __syncthreads();
+        CS::store_acc(sm.X, accw, p); // R D
+        __syncthreads();
+        mma_stream<Src::GX, Src::LX, true>(acc, Ai, B, sm.X, 0, p); // T = A^T (R D)
+        __syncthreads();
+        CS::store_acc(sm.X, acc, p); // T
+        __syncthreads();
+        mma_stream<Src::GX, Src::LX, true>(accw, Cij, ldw, sm.X, 0, p); // C^T T
+        {
+            float *gbp = gBpart + ((int64_t)j * nbi + i) * B * B;
+            const uint32_t lb = opaque_u(gb);
+#pragma unroll
+            for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < 2; ++tn)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) gst(gbp, lb + CS::Pos::unif_boff(tm, tn, r, B), -2.f * accw.v[tm][tn][r]);
+        }
+        // Adam on the core, g = -2 (T B^T) (.) M, one 32 x 32 tile (tm, tn) at a time; moments also decay on
+        // pruned entries, whose core value is written back as it was.
+        float cv[2][16], mo[2][16], vo[2][16];
+        auto request_tile = [&](int slot, int tm, int tn) {
+            const uint32_t lb = opaque_u(wboff);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const uint32_t off = lb + CS::Pos::unif_boff(tm, tn, r, ldw);
+                cv[slot][r] = gld(Cij, off);
+                mo[slot][r] = gld(mij, off);
+                vo[slot][r] = gld(vij, off);
+            }
+        };
+        mma_stream<Src::LK, Src::GK, true, false, STREAM_DEPTH>(acc, sm.X, 0, Bj, B, p, [&]() { request_tile(0, 0, 0); }); // T B^T
+        {
+            const uint8_t *ml = reinterpret_cast<const uint8_t *>(sm.M);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int tm = t >> 1, tn = t & 1, slot = t & 1;
+                if (t + 1 < 4) request_tile(slot ^ 1, (t + 1) >> 1, (t + 1) & 1);
+                const uint32_t lb = opaque_u(wboff);
+                const uint32_t mo_l = opaque_u((uint32_t)((p.wm0 + p.kh * 4) * 64 + p.col(tn) / mask_group));
+                const int sh = p.col(tn) % mask_group;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const uint32_t off = lb + CS::Pos::unif_boff(tm, tn, r, ldw);
+                    const uint32_t mbyte = ml[mo_l + (uint32_t)((tm * 32 + (r >> 2) * 8 + (r & 3)) * 64)];
+                    const bool kp = (mbyte >> sh) & 1u;
+                    const float g = kp ? -2.f * acc.v[tm][tn][r] : 0.f;
+                    const float mn = k.b1 * mo[slot][r] + k.one_minus_b1 * g;
+                    const float vn = k.b2 * vo[slot][r] + k.one_minus_b2 * g * g;
+                    gst(mij, off, mn);
+                    gst(vij, off, vn);
+                    const float cn = cv[slot][r] - k.lr * (mn * k.inv_c1) / (sqrtf(vn * k.inv_c2) + k.eps);
+                    gst(Cij, off, kp ? cn : cv[slot][r]);
+                }
+                __builtin_amdgcn_sched_barrier(0); // one tile at a time: bounds what is in flight
+            }
+        }
+        float unused = 0.f;
+        block_sum2(lsum, unused, sm.red, tid); // (barriers: X, M and the scratch are free again)
+        if (tid == 0) loss_part[i * nbj + j] = lsum;
+    }
+    float *gp = gApart + (int64_t)blockIdx.x * B * B;
+    const uint32_t lb = opaque_u(gb);
+#pragma unroll
+    for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < 2; ++tn)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) gst(gp, lb + CS::Pos::unif_boff(tm, tn, r, B), -2.f * gacc.v[tm][tn][r]);
+}
+
 } // namespace stream
 
 using namespace stream;
@@ -676,6 +832,16 @@ void launch_phase_GS_stream(const Dims &d, const float *Wbar, const float *C, co
     dim3 grid(std::min(d.nblocks, grid_cap)), block(CS::NT);
     hipLaunchKernelGGL(phase_GS_stream_kernel, grid, block, 0, s, Wbar, C, A, B, D, d.d_in, d.nbj, d.nblocks, Gout,
                        loss_part);
+}
+
+void launch_phase_FB_stream(const Dims &d, const float *Wbar, float *C, const float *A, const float *B,
+                            const float *D, const uint8_t *mask, int mask_group, float *mC, float *vC,
+                            double lr, double b1, double b2, double eps, int64_t t, int nsplit, float *gApart,
+                            float *gBpart, float *loss_part, float *scratch, hipStream_t s) {
+    const AdamCoef k = make_adam_coef(lr, b1, b2, eps, t);
+    dim3 grid(d.nbi * nsplit), block(CS::NT);
+    hipLaunchKernelGGL(phase_FB_stream_kernel, grid, block, 0, s, Wbar, C, A, B, D, mask, mask_group, mC, vC, k,
+                       d.d_in, d.nbi, d.nbj, nsplit, gApart, gBpart, loss_part, scratch);
 }
 
 } // namespace armor
