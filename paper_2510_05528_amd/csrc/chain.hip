@@ -9,9 +9,9 @@
 // transposed or not).  Products run on v_mfma_f32_32x32x2_f32; each wave owns a (TM*32) x (TN*32)
 // patch of the b x b result in accumulator registers.  Only C, Wbar (HBM) and A^i, B^j (L2) are
 // read per block; intermediates never leave the CU.
-// At b = 128 the sequential variant runs the A, B and W' phases in a second form (chain_stream.hip:
-// one operand tile in LDS, the other streamed, two workgroups per CU); the kernels here then serve
-// b = 32 and 64, the joint-Adam chains, the unstructured W' step and the loss-only pass.
+// At b = 128 the A, B and W' phases and the two joint-Adam chains run in a second form
+// (chain_stream.hip: one operand tile in LDS, the other streamed, two workgroups per CU); the kernels
+// here then serve b = 32 and 64, the unstructured W' step and the loss-only pass.
 #include "chain_common.h"
 
 #include <algorithm>
