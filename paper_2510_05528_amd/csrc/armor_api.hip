@@ -126,7 +126,7 @@ struct Carver {
 };
 
 struct FactorWs {
-    float *Sp; // S' = A C handed from the B step to the W' step (sequential variant; at d_block <= 128 in N:M mode only)
+    float *Sp; // S' = A C handed from the B step to the W' step (sequential variant; at d_block < 128 in N:M mode only)
     float *Wbar, *G, *D, *gpart, *beta_part, *loss_part, *loss_part2, *K, *AtA, *colnorm2, *fro2A, *fro2K, *cn_partial,
         *r1, *r2;
     uint8_t *mask;
@@ -168,7 +168,7 @@ FactorWs carve_factor(void *ws, const Dims &d, int mask_group, const armor_opts 
     f.cn_chunks = colnorm_chunks(d.d_out);
     f.Wbar = c.take<float>(P);
     f.G = c.take<float>(P);
-    f.Sp = (!adam && (d.b > 128 || !unstr)) ? c.take<float>(P) : nullptr;
+    f.Sp = (!adam && (d.b >= 128 || !unstr)) ? c.take<float>(P) : nullptr;
     f.D = c.take<float>(d.d_in);
     f.gpart = c.take<float>(std::max((size_t)d.nbi * f.nsA, (size_t)d.nbj * f.nsB) * bb);
     f.stream_scratch = stream ? c.take<float>(std::max((size_t)d.nbi * f.nsA, (size_t)d.nbj * f.nsB) * bb) : nullptr;
@@ -497,7 +497,7 @@ armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const flo
         {
             ProfScope ps(ARMOR_PROF_PHASE_B, s, true);
             if (big) launch_big_phase_B(d, f.Wbar, S, A, B, f.D, f.nsB, f.gpart, f.beta_part, f.Sp, slots, f.big_scratch, s);
-            else launch_phase_B(d, f.Wbar, S, A, B, f.D, f.nsB, f.gpart, f.beta_part, unstructured ? nullptr : f.Sp, f.stream_scratch, s);
+            else launch_phase_B(d, f.Wbar, S, A, B, f.D, f.nsB, f.gpart, f.beta_part, f.Sp, f.stream_scratch, s);
         }
         {
             ProfScope ps(ARMOR_PROF_SMALL, s, true);
@@ -510,7 +510,7 @@ armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const flo
             ProfScope ps(ARMOR_PROF_PHASE_WS, s, true);
             if (big) launch_big_phase_WS(d, f.Wbar, S, A, B, f.D, f.AtA, f.K, mask, mask_group, f.fro2A, f.fro2K, nullptr,
                                          nullptr, f.Sp, false, slots, f.big_scratch, s);
-            else launch_phase_W(d, f.Wbar, S, A, B, f.D, mask, mask_group, f.fro2A, f.fro2K, slots, s);
+            else launch_phase_W(d, f.Wbar, S, A, B, f.D, mask, mask_group, f.fro2A, f.fro2K, f.Sp, slots, s);
         } else {
             // W' step fused with the core gradient at the updated core; then the sparse-core step (Alg. 3)
             {

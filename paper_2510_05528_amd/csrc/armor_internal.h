@@ -40,7 +40,7 @@ void launch_phase_B_stream(const Dims &d, const float *Wbar, const float *C, con
 // W' step of Alg. 2 alone (unstructured mode): C += (2/beta_W) (A^T ((Wbar - A C B) D) B^T) (.) M, beta_W
 // read from scalars[2].  grid_cap workgroups at most, each walking blocks w, w + grid, ...
 void launch_phase_W(const Dims &d, const float *Wbar, float *C, const float *A, const float *B, const float *D,
-                    const uint8_t *mask, int mask_group, const float *fro2A, const float *fro2K, int grid_cap,
+                    const uint8_t *mask, int mask_group, const float *fro2A, const float *fro2K, const float *Sp, int grid_cap,
                     hipStream_t s);
 // Per wrapper block: A^iT A^i, its diagonal ||A^i[:,p]||^2 and ||A^iT A^i||_F^2; K^j = B^j D^j B^jT, ||K^j||_F^2.
 void launch_wrapper_grams(const Dims &d, const float *A, const float *B, const float *D, float *colnorm2,

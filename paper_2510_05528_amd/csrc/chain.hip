@@ -912,8 +912,13 @@ void launch_phase_B(const Dims &d, const float *Wbar, const float *C, const floa
 }
 
 void launch_phase_W(const Dims &d, const float *Wbar, float *C, const float *A, const float *B, const float *D,
-                    const uint8_t *mask, int mask_group, const float *fro2A, const float *fro2K, int grid_cap,
-                    hipStream_t s) {
+                    const uint8_t *mask, int mask_group, const float *fro2A, const float *fro2K, const float *Sp,
+                    int grid_cap, hipStream_t s) {
+    if (d.b == 128 && Sp != nullptr) { // the form with two workgroups per CU (chain_stream.hip), stopping after the W' step
+        launch_phase_WS_stream(d, Wbar, C, A, B, D, nullptr, nullptr, mask, mask_group, fro2A, fro2K, nullptr, nullptr, Sp,
+                               2 * grid_cap, s);
+        return;
+    }
     ARMOR_DISPATCH_B(d.b, {
         dim3 grid(std::min(d.nblocks, grid_cap)), block(Chain<BB>::NT);
         hipLaunchKernelGGL((phase_W_kernel<BB>), grid, block, 0, s, Wbar, C, A, B, D, mask, mask_group, fro2A,

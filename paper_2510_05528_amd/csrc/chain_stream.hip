@@ -176,7 +176,9 @@ __device__ __forceinline__ void settle(float &v) { asm volatile("" : "+v"(v)); }
 //   G = A^T U            U resident, A^i streamed row-contiguous
 //   V = Delta K          Delta = G (.) M resident, K^j streamed
 //   Z = (A^T A) V        V resident, A^T A streamed
+// FUSED = false stops after the W' step itself (unstructured mode, where no sparse-core step follows).
 // ------------------------------------------------------------------------------------------------
+template <bool FUSED>
 __global__ __launch_bounds__(CS::NT, 2) void phase_WS_stream_kernel(
     const float *__restrict__ Wbar, float *__restrict__ C, const float *__restrict__ A,
     const float *__restrict__ Bw, const float *__restrict__ D, const float *__restrict__ AtA,
@@ -280,14 +282,21 @@ __global__ __launch_bounds__(CS::NT, 2) void phase_WS_stream_kernel(
                         const bool kp = (mbyte >> sh) & 1u;
                         keep[tm][tn] |= (kp ? 1u : 0u) << r;
                         const float dl = kp ? acc.v[tm][tn][r] : 0.f;
-                        dd += dl * dl;
-                        d0[CS::Pos::unif_off(tm, tn, r, CS::P)] = dl;
+                        if (FUSED) {
+                            dd += dl * dl;
+                            d0[CS::Pos::unif_off(tm, tn, r, CS::P)] = dl;
+                        }
                         // (pruned entries are written back as they were: no branch around the store, same lines)
                         gst(Cij, lb + CS::Pos::unif_boff(tm, tn, r, ldw), cv[tm][tn][r] + eta2 * dl);
                     }
                     keep[tm][tn] = opaque_u(keep[tm][tn]); // the masked values themselves are not kept in registers
                 }
             }
+        }
+        if constexpr (!FUSED) {
+            request_block(min(blk + (int)gridDim.x, nblocks - 1));
+            __syncthreads(); // X and M are free again
+            continue;
         }
         settle(dd);
         __syncthreads();
@@ -822,9 +831,14 @@ void launch_phase_WS_stream(const Dims &d, const float *Wbar, float *C, const fl
                             const float *fro2A, const float *fro2K, float *Gout, float *loss_part, const float *Sp,
                             int grid_cap, hipStream_t s) {
     dim3 grid(std::min(d.nblocks, grid_cap)), block(CS::NT);
-    hipLaunchKernelGGL(phase_WS_stream_kernel, grid, block, 0, s, Wbar, C, A, B, D, AtA, K, mask, mask_group, fro2A,
-                       d.nbi * gram_parts(d.b), fro2K, d.nbj * gram_parts(d.b), d.d_in, d.nbj, d.nblocks, Gout,
-                       loss_part, Sp);
+    if (Gout != nullptr)
+        hipLaunchKernelGGL(phase_WS_stream_kernel<true>, grid, block, 0, s, Wbar, C, A, B, D, AtA, K, mask, mask_group,
+                           fro2A, d.nbi * gram_parts(d.b), fro2K, d.nbj * gram_parts(d.b), d.d_in, d.nbj, d.nblocks,
+                           Gout, loss_part, Sp);
+    else // the W' step alone
+        hipLaunchKernelGGL(phase_WS_stream_kernel<false>, grid, block, 0, s, Wbar, C, A, B, D, AtA, K, mask, mask_group,
+                           fro2A, d.nbi * gram_parts(d.b), fro2K, d.nbj * gram_parts(d.b), d.d_in, d.nbj, d.nblocks,
+                           Gout, loss_part, Sp);
 }
 
 void launch_phase_GS_stream(const Dims &d, const float *Wbar, const float *C, const float *A, const float *B,
