@@ -93,6 +93,32 @@ def test_config3_mlp_shapes(env, orc):
     compare(armor, torch, orc, Wd, Dd, 128, 2, 4, 1, seed=0, long_iters=10)
 
 
+def test_adam_multi_block_chunks(env, orc):
+    """Joint-Adam variant where a workgroup of the forward/backward chain walks more than one block
+    (18 x 32 blocks of 128 on 512 workgroup slots: chunks of two column blocks) and the core-gradient
+    chain more than one block per workgroup.  One iteration from theta_0 is determined to rounding."""
+    armor, torch, dev = env
+    d_out, d_in, b = 2304, 4096, 128
+    W = synth.torch_weight(d_out, d_in, 51, dev)
+    D = (torch.rand(d_in, device=dev, generator=torch.Generator(device=dev).manual_seed(7)) + 0.5).float()
+    Wh, Dh = W.float().cpu().numpy(), D.cpu().numpy()
+    say("adam, chunks of two: %dx%d" % (d_out, d_in))
+    out = armor.factorize_layer(W, D, b, 2, 4, 1, seed=3, variant=1, lr=1e-3)
+    torch.cuda.synchronize()
+    ref = orc.factorize_layer_adam(Wh, Dh, b, 2, 4, 1, seed=3, lr=1e-3)
+    # Adam's first step is lr * sign(g) on every entry: an entry whose gradient is zero up to rounding may
+    # take either sign in any implementation.  Everything else agrees to rounding.
+    lr = 1e-3
+    for k, rk in (("A", "A"), ("B", "B"), ("S", "C")):
+        d = np.abs(out[k].cpu().numpy().astype(np.float64) - ref[rk])
+        nbad = int((d > 1e-6).sum())
+        say("   %s: max diff %.2e, entries off by more than 1e-6: %d of %d" % (k, d.max(), nbad, d.size))
+        assert d.max() <= 2 * lr * (1 + 1e-3) and nbad <= max(4, d.size // 100000), k
+    agree = float((armor.unpack_mask(out["mask_bits"].cpu().numpy(), 4) == ref["mask"]).mean())
+    assert agree >= 0.99999
+    np.testing.assert_allclose(out["loss_trace"].cpu().numpy(), ref["loss_trace"], rtol=1e-5)
+
+
 def test_config4_gqa_kv_shape(env, orc):
     """Llama-3-8B k/v projection: 1024x4096 (8 x 32 blocks), full parity over 3 iterations."""
     armor, torch, dev = env
