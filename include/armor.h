@@ -18,7 +18,7 @@
  *     stream), return a status code, never throw and never print.  Argument errors are detected
  *     on the host before any launch.  Results are deterministic: no floating-point atomics.
  *   - d_block must divide d_out and d_in and be one of 32, 64, 128, 256; M must divide d_block,
- *     1 <= N < M <= 8.
+ *     1 <= N < M <= 8; d_block * d_in <= 2^29 (a block row is addressed with 32-bit byte offsets).
  */
 #ifndef ARMOR_H
 #define ARMOR_H

@@ -145,6 +145,8 @@ armor_status validate_shape(int64_t d_out, int64_t d_in, int64_t b) {
     if (d_out % b != 0 || d_in % b != 0) return ARMOR_ERR_SHAPE;
     if (b != 32 && b != 64 && b != 128 && b != 256) return ARMOR_ERR_SHAPE;
     if (d_out / b > 1 << 20 || d_in / b > 1 << 20 || (d_out / b) * (d_in / b) > (int64_t)1 << 30) return ARMOR_ERR_SHAPE;
+    // the chain kernels address inside a block row with 32-bit byte offsets: b rows of d_in fp32 values
+    if (b * d_in > (int64_t)1 << 29) return ARMOR_ERR_SHAPE;
     return ARMOR_OK;
 }
 

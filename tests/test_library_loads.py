@@ -35,6 +35,8 @@ def test_status_strings_and_host_side_validation():
     assert lib.armor_factorize_workspace_bytes(256, 256, 48, 2, 4, None) == 0      # unsupported block size
     assert lib.armor_factorize_workspace_bytes(256, 256, 32, 4, 4, None) == 0      # N >= M
     assert lib.armor_factorize_workspace_bytes(256, 256, 32, 2, 3, None) == 0      # M not 2/4/8
+    assert lib.armor_factorize_workspace_bytes(128, 1 << 23, 128, 2, 4, None) == 0  # d_block * d_in beyond 2^29
+    assert lib.armor_factorize_workspace_bytes(128, 1 << 22, 128, 2, 4, None) > 0
     assert lib.armor_proxy_loss_workspace_bytes(128, 128, 64) > 0
     # null pointers / bad shapes are rejected without touching the device
     assert lib.armor_gram(None, 0, 16, 64, 64, None, 64, 0, None, 0, None) == 1
