@@ -11,7 +11,8 @@
 // read per block; intermediates never leave the CU.
 // At b = 128 the A, B and W' phases and the two joint-Adam chains run in a second form
 // (chain_stream.hip: one operand tile in LDS, the other streamed, two workgroups per CU); the kernels
-// here then serve b = 32 and 64, the unstructured W' step and the loss-only pass.
+// here serve b = 32 and 64, and at b = 128 the loss-only pass and the wrapper Grams.  The b = 128
+// geometry of chain_common.h (8 waves) is also what the sub-tiled b = 256 chains are built on.
 #include "chain_common.h"
 
 #include <algorithm>
@@ -879,32 +880,44 @@ int gram_parts(int b) { return b <= 128 ? b / 32 : 1; }
     default: break;                                      \
     }
 
+// b = 32 and 64 only: at b = 128 the phase runs in the streamed-operand form (chain_stream.hip)
+#define ARMOR_DISPATCH_B_SMALL(bval, ...)                \
+    switch (bval) {                                      \
+    case 32:  { constexpr int BB = 32;  __VA_ARGS__; } break; \
+    case 64:  { constexpr int BB = 64;  __VA_ARGS__; } break; \
+    default: break;                                      \
+    }
+
 void launch_phase_A(const Dims &d, const float *Wbar, const float *C, const float *A, const float *B,
                     const float *D, int nsplit, float *gpart, float *beta_part, float *loss_part,
                     bool loss_only, float *stream_scratch, hipStream_t s) {
-    if (d.b == 128 && !loss_only && stream_scratch != nullptr) { // the form with two workgroups per CU (chain_stream.hip)
+    if (loss_only) {
+        ARMOR_DISPATCH_B(d.b, {
+            dim3 grid(d.nbi * nsplit), block(Chain<BB>::NT);
+            hipLaunchKernelGGL((phase_A_kernel<BB, true>), grid, block, 0, s, Wbar, C, A, B, D, d.d_in, d.nbj, nsplit,
+                               gpart, beta_part, loss_part);
+        });
+        return;
+    }
+    if (d.b == 128) { // two workgroups per CU
         launch_phase_A_stream(d, Wbar, C, A, B, D, nsplit, gpart, beta_part, loss_part, stream_scratch, s);
         return;
     }
-    ARMOR_DISPATCH_B(d.b, {
+    ARMOR_DISPATCH_B_SMALL(d.b, {
         dim3 grid(d.nbi * nsplit), block(Chain<BB>::NT);
-        if (loss_only)
-            hipLaunchKernelGGL((phase_A_kernel<BB, true>), grid, block, 0, s, Wbar, C, A, B, D, d.d_in, d.nbj,
-                               nsplit, gpart, beta_part, loss_part);
-        else
-            hipLaunchKernelGGL((phase_A_kernel<BB, false>), grid, block, 0, s, Wbar, C, A, B, D, d.d_in, d.nbj,
-                               nsplit, gpart, beta_part, loss_part);
+        hipLaunchKernelGGL((phase_A_kernel<BB, false>), grid, block, 0, s, Wbar, C, A, B, D, d.d_in, d.nbj, nsplit,
+                           gpart, beta_part, loss_part);
     });
 }
 
 void launch_phase_B(const Dims &d, const float *Wbar, const float *C, const float *A, const float *B,
                     const float *D, int nsplit, float *gpart, float *beta_part, float *Sp, float *stream_scratch,
                     hipStream_t s) {
-    if (d.b == 128 && stream_scratch != nullptr) {
+    if (d.b == 128) {
         launch_phase_B_stream(d, Wbar, C, A, B, D, nsplit, gpart, beta_part, Sp, stream_scratch, s);
         return;
     }
-    ARMOR_DISPATCH_B(d.b, {
+    ARMOR_DISPATCH_B_SMALL(d.b, {
         dim3 grid(d.nbj * nsplit), block(Chain<BB>::NT);
         hipLaunchKernelGGL((phase_B_kernel<BB>), grid, block, 0, s, Wbar, C, A, B, D, d.d_in, d.nbi, d.nbj, nsplit,
                            gpart, beta_part, Sp);
@@ -914,12 +927,12 @@ void launch_phase_B(const Dims &d, const float *Wbar, const float *C, const floa
 void launch_phase_W(const Dims &d, const float *Wbar, float *C, const float *A, const float *B, const float *D,
                     const uint8_t *mask, int mask_group, const float *fro2A, const float *fro2K, const float *Sp,
                     int grid_cap, hipStream_t s) {
-    if (d.b == 128 && Sp != nullptr) { // the form with two workgroups per CU (chain_stream.hip), stopping after the W' step
+    if (d.b == 128) { // the streamed W' kernel, stopping after the W' step; S' comes from the B step
         launch_phase_WS_stream(d, Wbar, C, A, B, D, nullptr, nullptr, mask, mask_group, fro2A, fro2K, nullptr, nullptr, Sp,
                                2 * grid_cap, s);
         return;
     }
-    ARMOR_DISPATCH_B(d.b, {
+    ARMOR_DISPATCH_B_SMALL(d.b, {
         dim3 grid(std::min(d.nblocks, grid_cap)), block(Chain<BB>::NT);
         hipLaunchKernelGGL((phase_W_kernel<BB>), grid, block, 0, s, Wbar, C, A, B, D, mask, mask_group, fro2A,
                            d.nbi * gram_parts(d.b), fro2K, d.nbj * gram_parts(d.b), d.d_in, d.nbj, d.nblocks);
@@ -939,13 +952,13 @@ void launch_phase_FB(const Dims &d, const float *Wbar, float *C, const float *A,
                      const uint8_t *mask, int mask_group, float *mC, float *vC, double lr, double b1, double b2,
                      double eps, int64_t t, int nsplit, float *gApart, float *gBpart, float *loss_part,
                      float *stream_scratch, hipStream_t s) {
-    if (d.b == 128 && stream_scratch != nullptr) { // the form with two workgroups per CU (chain_stream.hip)
+    if (d.b == 128) {
         launch_phase_FB_stream(d, Wbar, C, A, B, D, mask, mask_group, mC, vC, lr, b1, b2, eps, t, nsplit, gApart,
                                gBpart, loss_part, stream_scratch, s);
         return;
     }
     const AdamCoef k = make_adam_coef(lr, b1, b2, eps, t);
-    ARMOR_DISPATCH_B(d.b, {
+    ARMOR_DISPATCH_B_SMALL(d.b, {
         dim3 grid(d.nbi * nsplit), block(Chain<BB>::NT);
         hipLaunchKernelGGL((phase_FB_kernel<BB>), grid, block, 0, s, Wbar, C, A, B, D, mask, mask_group, mC, vC, k,
                            d.d_in, d.nbi, d.nbj, nsplit, gApart, gBpart, loss_part);
@@ -954,11 +967,11 @@ void launch_phase_FB(const Dims &d, const float *Wbar, float *C, const float *A,
 
 void launch_phase_GS(const Dims &d, const float *Wbar, const float *C, const float *A, const float *B, const float *D,
                      float *Gout, float *loss_part, int grid_cap, hipStream_t s) {
-    if (d.b == 128) { // the form with two workgroups per CU (chain_stream.hip)
+    if (d.b == 128) {
         launch_phase_GS_stream(d, Wbar, C, A, B, D, Gout, loss_part, 2 * grid_cap, s);
         return;
     }
-    ARMOR_DISPATCH_B(d.b, {
+    ARMOR_DISPATCH_B_SMALL(d.b, {
         dim3 grid(std::min(d.nblocks, grid_cap)), block(Chain<BB>::NT);
         hipLaunchKernelGGL((phase_GS_kernel<BB>), grid, block, 0, s, Wbar, C, A, B, D, d.d_in, d.nbj, d.nblocks, Gout,
                            loss_part);
@@ -968,12 +981,12 @@ void launch_phase_GS(const Dims &d, const float *Wbar, const float *C, const flo
 void launch_phase_WS(const Dims &d, const float *Wbar, float *C, const float *A, const float *B, const float *D,
                      const float *AtA, const float *K, const uint8_t *mask, int mask_group, const float *fro2A,
                      const float *fro2K, float *Gout, float *loss_part, const float *Sp, int grid_cap, hipStream_t s) {
-    if (d.b == 128 && Sp != nullptr) { // the form with two workgroups per CU (chain_stream.hip)
+    if (d.b == 128) {
         launch_phase_WS_stream(d, Wbar, C, A, B, D, AtA, K, mask, mask_group, fro2A, fro2K, Gout, loss_part, Sp,
                                2 * grid_cap, s);
         return;
     }
-    ARMOR_DISPATCH_B(d.b, {
+    ARMOR_DISPATCH_B_SMALL(d.b, {
         dim3 grid(std::min(d.nblocks, grid_cap)), block(Chain<BB>::NT);
         hipLaunchKernelGGL((phase_WS_kernel<BB>), grid, block, 0, s, Wbar, C, A, B, D, AtA, K, mask, mask_group,
                            fro2A, d.nbi * gram_parts(d.b), fro2K, d.nbj * gram_parts(d.b), d.d_in, d.nbj, d.nblocks, Gout,
