@@ -329,6 +329,19 @@ def test_factorize_is_deterministic(armor, torch):
         assert torch.equal(a[k], b[k]), k
 
 
+def test_factorize_block128_deterministic_and_dead_channels(armor, torch, orc):
+    """d_block 128 (streamed chains, two workgroups per CU, global scratch): two runs agree bit for bit,
+    and input channels that never fire (D = 0: zero-weight columns of the loss) match the oracle."""
+    W, X = make_layer(256, 384, 300, seed=31, act_outliers=(0.01, 20.0))
+    D = np.diag(orc.gram(X)).astype(np.float32)
+    D[np.random.default_rng(5).choice(384, 24, replace=False)] = 0.0
+    a = armor.factorize_layer(dev(torch, W), dev(torch, D), 128, 2, 4, 4, seed=1)
+    b = armor.factorize_layer(dev(torch, W), dev(torch, D), 128, 2, 4, 4, seed=1)
+    for k in ("A", "S", "B", "mask_bits", "loss_trace"):
+        assert torch.equal(a[k], b[k]), k
+    check_factorization(armor, torch, orc, W, D, 128, 2, 4, 4, seed=1)
+
+
 def test_denormalize_and_pack(armor, torch, orc):
     W, X = make_layer(128, 128, 100, seed=9)
     D = (X.astype(np.float64) ** 2).sum(0).astype(np.float32)
