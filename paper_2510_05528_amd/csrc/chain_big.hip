@@ -340,6 +340,7 @@ __global__ __launch_bounds__(CH::NT) void big_phase_WS_kernel(
                         }
                     }
                 }
+            asm volatile("" : "+v"(dd)); // formed here: otherwise the masked values stay in registers until the sum is used
         });
         if (FUSED) {
             big_mma<NS, false, false, false, false>(sm, tid, p, s1, b, K + (int64_t)j * b * b, b, nullptr, NoPre(),
