@@ -191,26 +191,44 @@ def sparse_core_update(Wbar, A, B, D, C, mask, N, M, seed, t, selection=0):
     return C, mask, kap, pat
 
 
-def factorize_layer(W, D, b, N, M, n_iters, seed=0, selection=0, sparsity=0, keep=0):
-    """Whole outer loop.  Returns a dict with A, C (=S), B, mask, Wbar, r1, r2, loss_trace, loss_cont_trace."""
+def _start_state(init, d_out, d_in, b):
+    """Output buffers of the outer loop, pre-filled with the caller's starting point when one is given."""
+    if init is None:
+        A = np.empty((d_out // b, b, b), dtype=np.float32)
+        B = np.empty((d_in // b, b, b), dtype=np.float32)
+        C = np.empty((d_out, d_in), dtype=np.float32)
+        mask = np.empty((d_out, d_in), dtype=np.uint8)
+    else:
+        A, B, C = _f32(init["A"]).copy(), _f32(init["B"]).copy(), _f32(init["C"]).copy()
+        mask = np.ascontiguousarray(init["mask"], dtype=np.uint8).copy()
+        assert A.shape == (d_out // b, b, b) and B.shape == (d_in // b, b, b)
+        assert C.shape == (d_out, d_in) and mask.shape == (d_out, d_in)
+    return A, B, C, mask
+
+
+def factorize_layer(W, D, b, N, M, n_iters, seed=0, selection=0, sparsity=0, keep=0, init=None, iter_offset=0):
+    """Whole outer loop.  Returns a dict with A, C (=S), B, mask, Wbar, r1, r2, loss_trace, loss_cont_trace,
+    etas [n_iters, 3] (eta_A, eta_B, eta_W' of each iteration) and mask_changes [n_iters].
+    init: optional dict(A, C, B, mask) to start from instead of Eq. 3; iter_offset: iterations already done."""
     W, D = _f32(W), _f32(D)
     d_out, d_in = W.shape
-    A = np.empty((d_out // b, b, b), dtype=np.float32)
-    B = np.empty((d_in // b, b, b), dtype=np.float32)
-    C = np.empty((d_out, d_in), dtype=np.float32)
+    A, B, C, mask = _start_state(init, d_out, d_in, b)
     Wbar = np.empty((d_out, d_in), dtype=np.float32)
-    mask = np.empty((d_out, d_in), dtype=np.uint8)
     r1 = np.empty(d_in, dtype=np.float32)
     r2 = np.empty(d_out, dtype=np.float32)
     trace = np.zeros(n_iters + 1, dtype=np.float64)
     ctrace = np.zeros(max(n_iters, 1), dtype=np.float64)
-    lib().oracle_factorize_layer(_p(W, _f32p), _p(D, _f32p), _i64(d_out), _i64(d_in), _i64(b), ctypes.c_int(N),
-                                 ctypes.c_int(M), ctypes.c_int(n_iters), ctypes.c_uint64(seed),
-                                 ctypes.c_int(selection), ctypes.c_int(sparsity), _i64(keep), _p(A, _f32p),
-                                 _p(C, _f32p), _p(B, _f32p), _p(mask, _u8p), _p(Wbar, _f32p), _p(r1, _f32p),
-                                 _p(r2, _f32p), _p(trace, _f64p), _p(ctrace, _f64p))
+    etas = np.zeros((max(n_iters, 1), 3), dtype=np.float64)
+    changes = np.zeros(max(n_iters, 1), dtype=np.int64)
+    lib().oracle_factorize_layer_ex(_p(W, _f32p), _p(D, _f32p), _i64(d_out), _i64(d_in), _i64(b), ctypes.c_int(N),
+                                    ctypes.c_int(M), ctypes.c_int(n_iters), ctypes.c_uint64(seed),
+                                    ctypes.c_int(selection), ctypes.c_int(sparsity), _i64(keep),
+                                    ctypes.c_int(0 if init is None else 1), _i64(iter_offset), _p(A, _f32p),
+                                    _p(C, _f32p), _p(B, _f32p), _p(mask, _u8p), _p(Wbar, _f32p), _p(r1, _f32p),
+                                    _p(r2, _f32p), _p(trace, _f64p), _p(ctrace, _f64p), _p(etas, _f64p),
+                                    _p(changes, _i64p))
     return dict(A=A, C=C, B=B, mask=mask, Wbar=Wbar, r1=r1, r2=r2, loss_trace=trace,
-                loss_cont_trace=ctrace[:n_iters])
+                loss_cont_trace=ctrace[:n_iters], etas=etas[:n_iters], mask_changes=changes[:n_iters])
 
 
 def adam_update(Wbar, D, mask, A, C, B, state, t, lr=1e-4, b1=0.9, b2=0.999, eps=1e-8):
@@ -237,27 +255,27 @@ def adam_state(d_out, d_in, b):
 
 
 def factorize_layer_adam(W, D, b, N, M, n_iters, seed=0, selection=0, sparsity=0, keep=0, lr=1e-4, b1=0.9, b2=0.999,
-                         eps=1e-8):
-    """Outer loop with the joint Adam continuous step; same outputs as factorize_layer."""
+                         eps=1e-8, init=None, iter_offset=0):
+    """Outer loop with the joint Adam continuous step; same outputs as factorize_layer (no etas)."""
     W, D = _f32(W), _f32(D)
     d_out, d_in = W.shape
-    A = np.empty((d_out // b, b, b), dtype=np.float32)
-    B = np.empty((d_in // b, b, b), dtype=np.float32)
-    C = np.empty((d_out, d_in), dtype=np.float32)
+    A, B, C, mask = _start_state(init, d_out, d_in, b)
     Wbar = np.empty((d_out, d_in), dtype=np.float32)
-    mask = np.empty((d_out, d_in), dtype=np.uint8)
     r1 = np.empty(d_in, dtype=np.float32)
     r2 = np.empty(d_out, dtype=np.float32)
     trace = np.zeros(n_iters + 1, dtype=np.float64)
     ctrace = np.zeros(max(n_iters, 1), dtype=np.float64)
-    lib().oracle_factorize_layer_adam(_p(W, _f32p), _p(D, _f32p), _i64(d_out), _i64(d_in), _i64(b), ctypes.c_int(N),
-                                      ctypes.c_int(M), ctypes.c_int(n_iters), ctypes.c_uint64(seed),
-                                      ctypes.c_int(selection), ctypes.c_int(sparsity), _i64(keep),
-                                      ctypes.c_double(lr), ctypes.c_double(b1), ctypes.c_double(b2),
-                                      ctypes.c_double(eps), _p(A, _f32p), _p(C, _f32p), _p(B, _f32p), _p(mask, _u8p),
-                                      _p(Wbar, _f32p), _p(r1, _f32p), _p(r2, _f32p), _p(trace, _f64p), _p(ctrace, _f64p))
+    changes = np.zeros(max(n_iters, 1), dtype=np.int64)
+    lib().oracle_factorize_layer_adam_ex(_p(W, _f32p), _p(D, _f32p), _i64(d_out), _i64(d_in), _i64(b),
+                                         ctypes.c_int(N), ctypes.c_int(M), ctypes.c_int(n_iters),
+                                         ctypes.c_uint64(seed), ctypes.c_int(selection), ctypes.c_int(sparsity),
+                                         _i64(keep), ctypes.c_double(lr), ctypes.c_double(b1), ctypes.c_double(b2),
+                                         ctypes.c_double(eps), ctypes.c_int(0 if init is None else 1),
+                                         _i64(iter_offset), _p(A, _f32p), _p(C, _f32p), _p(B, _f32p),
+                                         _p(mask, _u8p), _p(Wbar, _f32p), _p(r1, _f32p), _p(r2, _f32p),
+                                         _p(trace, _f64p), _p(ctrace, _f64p), _p(changes, _i64p))
     return dict(A=A, C=C, B=B, mask=mask, Wbar=Wbar, r1=r1, r2=r2, loss_trace=trace,
-                loss_cont_trace=ctrace[:n_iters])
+                loss_cont_trace=ctrace[:n_iters], mask_changes=changes[:n_iters])
 
 
 def denormalize(A, B, r1, r2):

@@ -309,8 +309,8 @@ static void grad_beta_A(const double *Wb, const double *Ad, const double *Cd, co
         }
     }
     if (beta) {
-        double tot = 0.0;
-#pragma omp parallel for schedule(static) reduction(+ : tot)
+        double tot = 0.0, *term = dalloc(d.nbi * d.nbj); /* summed in block order below: reruns agree bit for bit */
+#pragma omp parallel for schedule(static)
         for (int64_t blk = 0; blk < d.nbi * d.nbj; ++blk) {
             int64_t i = blk / d.nbj, j = blk % d.nbj;
             double f2 = 0.0;
@@ -321,8 +321,10 @@ static void grad_beta_A(const double *Wb, const double *Ad, const double *Cd, co
                     for (int64_t c = 0; c < b; ++c) s += sp[c] * Dd[j * b + c] * sq[c];
                     f2 += s * s;
                 }
-            tot += sqrt(f2);
+            term[blk] = sqrt(f2);
         }
+        for (int64_t blk = 0; blk < d.nbi * d.nbj; ++blk) tot += term[blk];
+        free(term);
         *beta = 2.0 * tot;
     }
     free(S); free(R);
@@ -350,8 +352,8 @@ static void grad_beta_B(const double *Wb, const double *Ad, const double *Cd, co
         }
     }
     if (beta) {
-        double tot = 0.0;
-#pragma omp parallel for schedule(static) reduction(+ : tot)
+        double tot = 0.0, *term = dalloc(d.nbi * d.nbj);
+#pragma omp parallel for schedule(static)
         for (int64_t blk = 0; blk < d.nbi * d.nbj; ++blk) {
             int64_t i = blk / d.nbj, j = blk % d.nbj;
             double f2 = 0.0, dn = 0.0;
@@ -363,8 +365,10 @@ static void grad_beta_B(const double *Wb, const double *Ad, const double *Cd, co
                     f2 += s * s;
                 }
             for (int64_t c = 0; c < b; ++c) dn += Dd[j * b + c] * Dd[j * b + c];
-            tot += sqrt(f2) * sqrt(dn);
+            term[blk] = sqrt(f2) * sqrt(dn);
         }
+        for (int64_t blk = 0; blk < d.nbi * d.nbj; ++blk) tot += term[blk];
+        free(term);
         *beta = 2.0 * tot;
     }
     free(Sp); free(R);
@@ -664,26 +668,63 @@ void oracle_sparse_core_update(const float *Wbar, const float *A, const float *B
  * Sec. 4.5; `keep` entries kept).  loss_trace[0..n_iters] = L(theta_t); loss_cont_trace[t-1]
  * (optional, n_iters entries) = loss after the continuous step of iteration t.
  * Outputs stay in the normalised space; r1, r2 are returned for the denormalisation.
+ *
+ * Extended form (diagnostics and restart; no arithmetic of its own):
+ *   init_from   0: theta_0 by Eq. 3.  1: theta_0 = the caller's (A, C, B, mask) (normalised space;
+ *               C must be zero where mask is 0): Alg. 1 takes theta_0 as an input, so any feasible
+ *               point is a legitimate start, and a run cut in two pieces is the same run.
+ *   iter_offset iterations already done: iteration t of this call draws its groups with the
+ *               counter of iteration iter_offset + t.
+ *   etas        optional [n_iters][3]: the step sizes eta_A, eta_B, eta_W' = 1/beta of Eq. 9-11 that
+ *               iteration t used (0 when beta = 0).
+ *   mask_changes optional [n_iters]: groups whose kept set the sparse-core step changed.
  * ------------------------------------------------------------------------------------------ */
+static int64_t count_changed_groups(const uint8_t *before, const uint8_t *after, int64_t P, int M) {
+    int64_t n = 0;
+    for (int64_t g = 0; g < P / M; ++g) {
+        int differs = 0;
+        for (int p = 0; p < M; ++p) differs |= before[g * M + p] != after[g * M + p];
+        n += differs;
+    }
+    return n;
+}
+
+void oracle_factorize_layer_ex(const float *W, const float *D, int64_t d_out, int64_t d_in, int64_t b,
+                               int N, int M, int n_iters, uint64_t seed, int selection, int sparsity,
+                               int64_t keep, int init_from, int64_t iter_offset, float *A, float *C,
+                               float *B, uint8_t *mask, float *Wbar, float *r1, float *r2,
+                               double *loss_trace, double *loss_cont_trace, double *etas,
+                               int64_t *mask_changes) {
+    dims_t d = mk_dims(d_out, d_in, b);
+    int64_t P = d_out * d_in;
+    uint8_t *before = mask_changes ? (uint8_t *)malloc((size_t)P) : NULL;
+    oracle_normalize(W, d_out, d_in, Wbar, r1, r2);
+    if (!init_from) {
+        oracle_init_identity(A, d.nbi, b);
+        oracle_init_identity(B, d.nbj, b);
+        if (sparsity == 0) oracle_init_nm(Wbar, D, d_out, d_in, N, M, C, mask);
+        else oracle_init_unstructured(Wbar, D, d_out, d_in, keep, C, mask);
+    }
+    loss_trace[0] = oracle_proxy_loss(Wbar, A, C, B, D, d_out, d_in, b);
+    for (int t = 1; t <= n_iters; ++t) {
+        oracle_continuous_update(Wbar, D, mask, d_out, d_in, b, A, C, B, etas ? etas + 3 * (t - 1) : NULL);
+        if (loss_cont_trace) loss_cont_trace[t - 1] = oracle_proxy_loss(Wbar, A, C, B, D, d_out, d_in, b);
+        if (before) memcpy(before, mask, (size_t)P);
+        if (sparsity == 0)
+            oracle_sparse_core_update(Wbar, A, B, D, d_out, d_in, b, N, M, seed, iter_offset + t, selection, C,
+                                      mask, NULL, NULL);
+        if (mask_changes) mask_changes[t - 1] = sparsity == 0 ? count_changed_groups(before, mask, P, M) : 0;
+        loss_trace[t] = oracle_proxy_loss(Wbar, A, C, B, D, d_out, d_in, b);
+    }
+    free(before);
+}
+
 void oracle_factorize_layer(const float *W, const float *D, int64_t d_out, int64_t d_in, int64_t b,
                             int N, int M, int n_iters, uint64_t seed, int selection, int sparsity,
                             int64_t keep, float *A, float *C, float *B, uint8_t *mask, float *Wbar,
                             float *r1, float *r2, double *loss_trace, double *loss_cont_trace) {
-    dims_t d = mk_dims(d_out, d_in, b);
-    oracle_normalize(W, d_out, d_in, Wbar, r1, r2);
-    oracle_init_identity(A, d.nbi, b);
-    oracle_init_identity(B, d.nbj, b);
-    if (sparsity == 0) oracle_init_nm(Wbar, D, d_out, d_in, N, M, C, mask);
-    else oracle_init_unstructured(Wbar, D, d_out, d_in, keep, C, mask);
-    loss_trace[0] = oracle_proxy_loss(Wbar, A, C, B, D, d_out, d_in, b);
-    for (int t = 1; t <= n_iters; ++t) {
-        oracle_continuous_update(Wbar, D, mask, d_out, d_in, b, A, C, B, NULL);
-        if (loss_cont_trace) loss_cont_trace[t - 1] = oracle_proxy_loss(Wbar, A, C, B, D, d_out, d_in, b);
-        if (sparsity == 0)
-            oracle_sparse_core_update(Wbar, A, B, D, d_out, d_in, b, N, M, seed, t, selection, C, mask,
-                                      NULL, NULL);
-        loss_trace[t] = oracle_proxy_loss(Wbar, A, C, B, D, d_out, d_in, b);
-    }
+    oracle_factorize_layer_ex(W, D, d_out, d_in, b, N, M, n_iters, seed, selection, sparsity, keep, 0, 0, A, C, B,
+                              mask, Wbar, r1, r2, loss_trace, loss_cont_trace, NULL, NULL);
 }
 
 /* ------------------------------------------------------------------------------------------
@@ -728,31 +769,49 @@ void oracle_adam_update(const float *Wbar, const float *D, const uint8_t *mask, 
     free(Wb); free(Dd); free(Cd); free(Ad); free(Bd); free(gA); free(gB); free(G);
 }
 
-/* Alg. 1 with the joint Adam continuous step.  Same outputs as oracle_factorize_layer. */
-void oracle_factorize_layer_adam(const float *W, const float *D, int64_t d_out, int64_t d_in, int64_t b, int N,
-                                 int M, int n_iters, uint64_t seed, int selection, int sparsity, int64_t keep,
-                                 double lr, double b1, double b2, double eps, float *A, float *C, float *B,
-                                 uint8_t *mask, float *Wbar, float *r1, float *r2, double *loss_trace,
-                                 double *loss_cont_trace) {
+/* Alg. 1 with the joint Adam continuous step.  Same outputs as oracle_factorize_layer; init_from,
+ * iter_offset and mask_changes as in oracle_factorize_layer_ex (a start from a given point begins
+ * with zero moments and step count 1: the moments are not part of theta). */
+void oracle_factorize_layer_adam_ex(const float *W, const float *D, int64_t d_out, int64_t d_in, int64_t b, int N,
+                                    int M, int n_iters, uint64_t seed, int selection, int sparsity, int64_t keep,
+                                    double lr, double b1, double b2, double eps, int init_from, int64_t iter_offset,
+                                    float *A, float *C, float *B, uint8_t *mask, float *Wbar, float *r1, float *r2,
+                                    double *loss_trace, double *loss_cont_trace, int64_t *mask_changes) {
     dims_t d = mk_dims(d_out, d_in, b);
     int64_t P = d_out * d_in, na = d.nbi * b * b, nb = d.nbj * b * b;
     float *mA = (float *)calloc((size_t)na, 4), *vA = (float *)calloc((size_t)na, 4),
           *mB = (float *)calloc((size_t)nb, 4), *vB = (float *)calloc((size_t)nb, 4),
           *mC = (float *)calloc((size_t)P, 4), *vC = (float *)calloc((size_t)P, 4);
+    uint8_t *before = mask_changes ? (uint8_t *)malloc((size_t)P) : NULL;
     oracle_normalize(W, d_out, d_in, Wbar, r1, r2);
-    oracle_init_identity(A, d.nbi, b);
-    oracle_init_identity(B, d.nbj, b);
-    if (sparsity == 0) oracle_init_nm(Wbar, D, d_out, d_in, N, M, C, mask);
-    else oracle_init_unstructured(Wbar, D, d_out, d_in, keep, C, mask);
+    if (!init_from) {
+        oracle_init_identity(A, d.nbi, b);
+        oracle_init_identity(B, d.nbj, b);
+        if (sparsity == 0) oracle_init_nm(Wbar, D, d_out, d_in, N, M, C, mask);
+        else oracle_init_unstructured(Wbar, D, d_out, d_in, keep, C, mask);
+    }
     loss_trace[0] = oracle_proxy_loss(Wbar, A, C, B, D, d_out, d_in, b);
     for (int t = 1; t <= n_iters; ++t) {
         oracle_adam_update(Wbar, D, mask, d_out, d_in, b, A, C, B, mA, vA, mB, vB, mC, vC, lr, b1, b2, eps, t);
         if (loss_cont_trace) loss_cont_trace[t - 1] = oracle_proxy_loss(Wbar, A, C, B, D, d_out, d_in, b);
+        if (before) memcpy(before, mask, (size_t)P);
         if (sparsity == 0)
-            oracle_sparse_core_update(Wbar, A, B, D, d_out, d_in, b, N, M, seed, t, selection, C, mask, NULL, NULL);
+            oracle_sparse_core_update(Wbar, A, B, D, d_out, d_in, b, N, M, seed, iter_offset + t, selection, C, mask,
+                                      NULL, NULL);
+        if (mask_changes) mask_changes[t - 1] = sparsity == 0 ? count_changed_groups(before, mask, P, M) : 0;
         loss_trace[t] = oracle_proxy_loss(Wbar, A, C, B, D, d_out, d_in, b);
     }
+    free(before);
     free(mA); free(vA); free(mB); free(vB); free(mC); free(vC);
+}
+
+void oracle_factorize_layer_adam(const float *W, const float *D, int64_t d_out, int64_t d_in, int64_t b, int N,
+                                 int M, int n_iters, uint64_t seed, int selection, int sparsity, int64_t keep,
+                                 double lr, double b1, double b2, double eps, float *A, float *C, float *B,
+                                 uint8_t *mask, float *Wbar, float *r1, float *r2, double *loss_trace,
+                                 double *loss_cont_trace) {
+    oracle_factorize_layer_adam_ex(W, D, d_out, d_in, b, N, M, n_iters, seed, selection, sparsity, keep, lr, b1, b2,
+                                   eps, 0, 0, A, C, B, mask, Wbar, r1, r2, loss_trace, loss_cont_trace, NULL);
 }
 
 /* ------------------------------------------------------------------------------------------

@@ -489,6 +489,75 @@ def test_factorize_trace_monotone_and_mask_valid(orc, N, M, sel):
     assert tr[-1] == pytest.approx(dense_loss(out["Wbar"], out["A"], C, out["B"], D), rel=1e-9)
 
 
+def _normalized_inverse(Wbar, r1, r2):
+    """A weight whose normalisation is (close to) the given W-bar: W = diag(r2) Wbar diag(r1)."""
+    return (r2[:, None].astype(np.float64) * Wbar.astype(np.float64) * r1[None, :]).astype(np.float32)
+
+
+@pytest.mark.parametrize("N,M", [(2, 4), (4, 8)])
+def test_factorize_from_a_given_point_is_a_replay_of_the_two_steps(orc, N, M):
+    """Alg. 1 from a caller-supplied theta_0 (generic point, so every step moves and masks change):
+    the loop is exactly continuous_update then sparse_core_update, iteration after iteration; the step
+    sizes it reports are 1/beta of Eq. 9-11 evaluated by dense numpy algebra at the points of Lemma 1;
+    mask_changes counts the groups whose kept set moved; the iteration counter of the draw is offset."""
+    rng = np.random.default_rng(101 + N)
+    d_out, d_in, b, iters, off = 16, 24, 8, 4, 7
+    W = synth.make_weight(d_out, d_in, seed=5, outlier_frac=0.05)
+    _, D, A, B, C, mask = rand_state(rng, d_out, d_in, b, N=N, M=M, perturb=0.3)
+    C = (0.1 * C).astype(np.float32)
+    out = orc.factorize_layer(W, D, b, N, M, iters, seed=4, init=dict(A=A, B=B, C=C, mask=mask), iter_offset=off)
+    Wbar, _, _ = orc.normalize(W)
+    np.testing.assert_array_equal(out["Wbar"], Wbar)
+    a, c, bb, m = A, C, B, mask
+    assert out["loss_trace"][0] == pytest.approx(dense_loss(Wbar, a, c, bb, D), rel=1e-10)
+    total_changes = 0
+    for t in range(1, iters + 1):
+        bA, _, _ = _np_betas(Wbar, a, c, bb, D, b)
+        a1, c1, b1, etas = orc.continuous_update(Wbar, D, m, a, c, bb)
+        _, bB, _ = _np_betas(Wbar, a1, c, bb, D, b)          # B step sees the new A
+        _, _, bW = _np_betas(Wbar, a1, c, b1, D, b)          # W' step sees the new A and B
+        np.testing.assert_allclose(out["etas"][t - 1], [1 / bA, 1 / bB, 1 / bW], rtol=1e-9)
+        np.testing.assert_array_equal(out["etas"][t - 1], etas)
+        assert out["loss_cont_trace"][t - 1] == pytest.approx(dense_loss(Wbar, a1, c1, b1, D), rel=1e-10)
+        c2, m2, _, _ = orc.sparse_core_update(Wbar, a1, b1, D, c1, m, N, M, seed=4, t=off + t)
+        changed = int((m2.reshape(-1, M) != m.reshape(-1, M)).any(axis=1).sum())
+        assert out["mask_changes"][t - 1] == changed
+        total_changes += changed
+        a, c, bb, m = a1, c2, b1, m2
+        assert out["loss_trace"][t] == pytest.approx(dense_loss(Wbar, a, c, bb, D), rel=1e-10)
+    assert total_changes > 0                                   # the case does exercise mask moves
+    for k, v in (("A", a), ("C", c), ("B", bb), ("mask", m)):
+        np.testing.assert_array_equal(out[k], v)
+    # a different offset draws different groups
+    other = orc.factorize_layer(W, D, b, N, M, iters, seed=4, init=dict(A=A, B=B, C=C, mask=mask), iter_offset=0)
+    assert not np.array_equal(other["C"], out["C"])
+
+
+@pytest.mark.parametrize("adam", [False, True])
+def test_a_run_cut_in_two_is_the_same_run(orc, adam):
+    """theta_0 is an input of Alg. 1: stopping after k iterations and starting again from the result,
+    with the iteration counter carried over, gives the uninterrupted run (sequential variant: exactly;
+    the joint-Adam variant restarts its moments, so only its first leg and the structure agree)."""
+    d_out, d_in, b = 32, 48, 16
+    W = synth.make_weight(d_out, d_in, seed=1, outlier_frac=0.05)
+    D = (np.random.default_rng(0).random(d_in) + 0.5).astype(np.float32)
+    f = orc.factorize_layer_adam if adam else orc.factorize_layer
+    kw = dict(lr=1e-3) if adam else {}
+    whole = f(W, D, b, 2, 4, 5, seed=3, **kw)
+    first = f(W, D, b, 2, 4, 2, seed=3, **kw)
+    second = f(W, D, b, 2, 4, 3, seed=3, init=first, iter_offset=2, **kw)
+    np.testing.assert_array_equal(first["loss_trace"], whole["loss_trace"][:3])
+    assert second["loss_trace"][0] == first["loss_trace"][-1]
+    assert np.all(second["mask"].reshape(d_out, d_in // 4, 4).sum(-1) == 2)
+    if not adam:
+        for k in ("A", "C", "B", "mask"):
+            np.testing.assert_array_equal(second[k], whole[k])
+        np.testing.assert_array_equal(second["loss_trace"], whole["loss_trace"][2:])
+        np.testing.assert_array_equal(np.concatenate([first["etas"], second["etas"]]), whole["etas"])
+        np.testing.assert_array_equal(np.concatenate([first["mask_changes"], second["mask_changes"]]),
+                                      whole["mask_changes"])
+
+
 def test_factorize_unstructured_runs_continuous_step_only(orc):
     d_out, d_in, b = 16, 32, 8
     W = synth.make_weight(d_out, d_in, seed=2)
