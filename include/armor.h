@@ -38,7 +38,8 @@ typedef enum {
     ARMOR_ERR_WORKSPACE = 4, /* ws is NULL or ws_bytes too small */
     ARMOR_ERR_ALIGN = 5,     /* a device buffer is not 16-byte aligned */
     ARMOR_ERR_DEVICE = 6,    /* a HIP call failed; see armor_last_hip_error() */
-    ARMOR_ERR_UNSUPPORTED = 7 /* valid request that this build does not implement */
+    ARMOR_ERR_UNSUPPORTED = 7, /* valid request that this build does not implement */
+    ARMOR_ERR_NONFINITE = 8    /* opts->check_finite: W has a NaN/Inf entry, or a loss weight H_jj is NaN/Inf/negative */
 } armor_status;
 
 typedef enum { ARMOR_F32 = 0, ARMOR_BF16 = 1 } armor_dtype;
@@ -58,6 +59,14 @@ typedef struct {
     double adam_beta1;          /* 0 = 0.9   (the optimiser's published default; the paper gives none) */
     double adam_beta2;          /* 0 = 0.999 */
     double adam_eps;            /* 0 = 1e-8  */
+    int32_t init_from_outputs;  /* 1: theta_0 is not Eq. 3 but what the caller left in A, S, B and mask_bits (all
+                                   required then; normalised space; S zero wherever its mask bit is clear).  Alg. 1
+                                   takes theta_0 as an input: this is how a stopped run is continued.  The joint-Adam
+                                   variant starts again with zero moments and step count 1. */
+    int32_t check_finite;       /* 1: validate W and the loss weights first; the call then waits for the stream once
+                                   and returns ARMOR_ERR_NONFINITE before anything else is enqueued */
+    int64_t iter_offset;        /* iterations already done: iteration t of this call draws its groups (Alg. 3) with
+                                   the counter of iteration iter_offset + t; >= 0 */
 } armor_opts;
 
 const char *armor_status_string(armor_status s);
@@ -159,16 +168,25 @@ armor_status armor_proxy_loss(const float *Wbar, const float *A, const float *S,
  *   loss_trace output, n_iters+1 doubles in DEVICE memory, L(theta_0..theta_n) in the normalised
  *              space; loss_trace[0] is the loss of plain N:M pruning (Sec. 3.4).  May be NULL.
  *   loss_cont_trace  optional, n_iters doubles: loss after the continuous step of each iteration.
+ *   eta_trace  optional, 3 * n_iters doubles in DEVICE memory: the step sizes eta_A, eta_B, eta_W' = 1/beta of
+ *              Eq. 9-11 that iteration t applied, at [3(t-1) .. 3(t-1)+2] (0 where beta = 0).  Sequential
+ *              variant only (the joint-Adam variant leaves it untouched).
+ *   mask_changes  optional, n_iters int32 in DEVICE memory: number of groups whose kept set the sparse-core
+ *              step of iteration t changed (0 in unstructured mode).
  * With opts->denormalize = 0 (default) A, S, B live in the normalised space:
  *   W ~= diag(r2) (A S B) diag(r1).
+ * Errors: bad arguments as in the status codes above, found on the host before any launch; with
+ * opts->check_finite the inputs are also scanned on the device (ARMOR_ERR_NONFINITE).  Without it a NaN/Inf
+ * in W or H propagates into the outputs.
  */
 size_t armor_factorize_workspace_bytes(int64_t d_out, int64_t d_in, int64_t d_block, int N, int M,
                                        const armor_opts *opts);
 armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const float *H, int64_t ldh, int64_t d_out,
                                    int64_t d_in, int64_t d_block, int N, int M, int n_iters,
                                    const armor_opts *opts, float *A, float *S, float *B, uint8_t *mask_bits,
-                                   float *r1, float *r2, double *loss_trace, double *loss_cont_trace, void *ws,
-                                   size_t ws_bytes, void *hip_stream);
+                                   float *r1, float *r2, double *loss_trace, double *loss_cont_trace,
+                                   double *eta_trace, int32_t *mask_changes, void *ws, size_t ws_bytes,
+                                   void *hip_stream);
 
 /*
  * Compressed N:M storage of the core (the form an N:M sparse matmul consumes; Sec. 3.1 stores the

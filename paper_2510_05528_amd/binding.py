@@ -29,7 +29,8 @@ class ArmorOpts(ctypes.Structure):
     _fields_ = [("selection", ctypes.c_int32), ("sparsity", ctypes.c_int32), ("unstructured_keep", ctypes.c_int64),
                 ("seed", ctypes.c_uint64), ("denormalize", ctypes.c_int32), ("variant", ctypes.c_int32),
                 ("lr", ctypes.c_double), ("adam_beta1", ctypes.c_double), ("adam_beta2", ctypes.c_double),
-                ("adam_eps", ctypes.c_double)]
+                ("adam_eps", ctypes.c_double), ("init_from_outputs", ctypes.c_int32), ("check_finite", ctypes.c_int32),
+                ("iter_offset", ctypes.c_int64)]
 
 
 _lib = None
@@ -65,8 +66,8 @@ def load_library():
     lib.armor_factorize_workspace_bytes.restype = _sz
     lib.armor_factorize_workspace_bytes.argtypes = [_i64, _i64, _i64, _int, _int, ctypes.POINTER(ArmorOpts)]
     lib.armor_factorize_layer.argtypes = [_vp, _int, _vp, _i64, _i64, _i64, _i64, _int, _int, _int,
-                                          ctypes.POINTER(ArmorOpts), _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz,
-                                          _vp]
+                                          ctypes.POINTER(ArmorOpts), _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp,
+                                          _vp, _sz, _vp]
     lib.armor_pack_meta_row_bytes.argtypes = [_i64, _int, _int]
     lib.armor_pack_meta_row_bytes.restype = _i64
     lib.armor_pack_nm.argtypes = [_vp, _vp, _i64, _i64, _int, _int, _vp, _int, _vp, _vp]
@@ -232,8 +233,10 @@ def factorize_workspace_bytes(d_out, d_in, d_block, N, M, sparsity=0, variant=0)
 
 def factorize_layer(W, H, d_block, N, M, n_iters, seed=0, selection=0, sparsity=0, unstructured_keep=0,
                     denormalize=False, ws=None, want_cont_trace=False, variant=0, lr=0.0, adam_beta1=0.0,
-                    adam_beta2=0.0, adam_eps=0.0):
-    """Run the BCD loop.  Returns dict(A, S, B, mask_bits, r1, r2, loss_trace[, loss_cont_trace])."""
+                    adam_beta2=0.0, adam_eps=0.0, init=None, iter_offset=0, check_finite=False, want_diagnostics=False):
+    """Run the BCD loop.  Returns dict(A, S, B, mask_bits, r1, r2, loss_trace[, loss_cont_trace][, eta_trace,
+    mask_changes]).  init: optional dict(A, S, B, mask_bits) of device tensors to start from (they are
+    copied; the copies are updated and returned) instead of the initialisation of Eq. 3."""
     torch = _torch()
     lib = load_library()
     if not (W.is_cuda and W.is_contiguous()):
@@ -243,28 +246,50 @@ def factorize_layer(W, H, d_block, N, M, n_iters, seed=0, selection=0, sparsity=
     dev = W.device
     o = ArmorOpts(selection=selection, sparsity=sparsity, unstructured_keep=unstructured_keep, seed=seed,
                   denormalize=int(denormalize), variant=variant, lr=lr, adam_beta1=adam_beta1, adam_beta2=adam_beta2,
-                  adam_eps=adam_eps)
+                  adam_eps=adam_eps, init_from_outputs=0 if init is None else 1, check_finite=int(check_finite),
+                  iter_offset=iter_offset)
     nbytes = lib.armor_factorize_workspace_bytes(d_out, d_in, d_block, N, M, ctypes.byref(o))
     if nbytes == 0:
         _check(2)
     if ws is None or ws.numel() < nbytes:
         ws = torch.empty(nbytes, device=dev, dtype=torch.uint8)
     mg = 8 if sparsity == 1 else M
-    A = torch.empty((d_out // d_block, d_block, d_block), device=dev, dtype=torch.float32)
-    B = torch.empty((d_in // d_block, d_block, d_block), device=dev, dtype=torch.float32)
-    S = torch.empty((d_out, d_in), device=dev, dtype=torch.float32)
-    mask_bits = torch.empty((d_out, d_in // mg), device=dev, dtype=torch.uint8)
+    shapes = dict(A=(d_out // d_block, d_block, d_block), B=(d_in // d_block, d_block, d_block), S=(d_out, d_in),
+                  mask_bits=(d_out, d_in // mg))
+    if init is None:
+        A, B, S = (torch.empty(shapes[k], device=dev, dtype=torch.float32) for k in ("A", "B", "S"))
+        mask_bits = torch.empty(shapes["mask_bits"], device=dev, dtype=torch.uint8)
+    else:
+        for k, shp in shapes.items():
+            t = init[k]
+            want = torch.uint8 if k == "mask_bits" else torch.float32
+            if not (t.is_cuda and t.dtype == want and tuple(t.shape) == shp):
+                raise ArmorError("init[%r] must be a %s device tensor of shape %s" % (k, want, shp))
+        A, B, S, mask_bits = (init[k].contiguous().clone() for k in ("A", "B", "S", "mask_bits"))
     r1 = torch.empty(d_in, device=dev, dtype=torch.float32)
     r2 = torch.empty(d_out, device=dev, dtype=torch.float32)
     trace = torch.zeros(n_iters + 1, device=dev, dtype=torch.float64)
     ctrace = torch.zeros(max(n_iters, 1), device=dev, dtype=torch.float64) if want_cont_trace else None
+    etas = torch.zeros((max(n_iters, 1), 3), device=dev, dtype=torch.float64) if want_diagnostics else None
+    changes = torch.zeros(max(n_iters, 1), device=dev, dtype=torch.int32) if want_diagnostics else None
     _check(lib.armor_factorize_layer(_ptr(W), _dtype_code(W), _ptr(H), ldh, d_out, d_in, d_block, N, M, n_iters,
                                      ctypes.byref(o), _ptr(A), _ptr(S), _ptr(B), _ptr(mask_bits), _ptr(r1), _ptr(r2),
-                                     _ptr(trace), _ptr(ctrace), _ptr(ws), ws.numel(), _stream()))
+                                     _ptr(trace), _ptr(ctrace), _ptr(etas), _ptr(changes), _ptr(ws), ws.numel(),
+                                     _stream()))
     out = dict(A=A, S=S, B=B, mask_bits=mask_bits, r1=r1, r2=r2, loss_trace=trace, ws=ws)
     if want_cont_trace:
         out["loss_cont_trace"] = ctrace[:n_iters]
+    if want_diagnostics:
+        out["eta_trace"] = etas[:n_iters]
+        out["mask_changes"] = changes[:n_iters]
     return out
+
+
+def pack_mask(mask, M):
+    """Host helper: [d_out, d_in] 0/1 array -> [d_out, d_in/M] bytes (bit p = column p of the group kept)."""
+    m = np.asarray(mask, dtype=np.uint8)
+    g = m.reshape(m.shape[0], m.shape[1] // M, M).astype(np.uint32)
+    return (g << np.arange(M, dtype=np.uint32)).sum(-1).astype(np.uint8)
 
 
 def pack_nm(S, mask_bits, N, M, bf16=False):

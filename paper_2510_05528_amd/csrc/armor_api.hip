@@ -221,6 +221,7 @@ const char *armor_status_string(armor_status s) {
     case ARMOR_ERR_ALIGN: return "buffer not 16-byte aligned";
     case ARMOR_ERR_DEVICE: return "HIP error";
     case ARMOR_ERR_UNSUPPORTED: return "unsupported configuration";
+    case ARMOR_ERR_NONFINITE: return "non-finite entry in W or non-finite/negative loss weight";
     }
     return "unknown status";
 }
@@ -379,8 +380,8 @@ size_t armor_factorize_workspace_bytes(int64_t d_out, int64_t d_in, int64_t d_bl
 armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const float *H, int64_t ldh, int64_t d_out,
                                    int64_t d_in, int64_t d_block, int N, int M, int n_iters, const armor_opts *opts,
                                    float *A, float *S, float *B, uint8_t *mask_bits, float *r1, float *r2,
-                                   double *loss_trace, double *loss_cont_trace, void *ws, size_t ws_bytes,
-                                   void *hip_stream) {
+                                   double *loss_trace, double *loss_cont_trace, double *eta_trace,
+                                   int32_t *mask_changes, void *ws, size_t ws_bytes, void *hip_stream) {
     if (!W || !H || !A || !S || !B) return ARMOR_ERR_NULL;
     if (w_dtype != ARMOR_F32 && w_dtype != ARMOR_BF16) return ARMOR_ERR_DTYPE;
     armor_status st = validate_shape(d_out, d_in, d_block);
@@ -401,7 +402,13 @@ armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const flo
     }
     if (n_iters < 0 || (ldh != 0 && ldh < d_in)) return ARMOR_ERR_SHAPE;
     if (unstructured && d_in % 8 != 0) return ARMOR_ERR_SHAPE;
-    if ((int64_t)d_in * d_block >= ((int64_t)1 << 31)) return ARMOR_ERR_SHAPE; // 32-bit tile offsets
+    if (o.init_from_outputs < 0 || o.init_from_outputs > 1 || o.check_finite < 0 || o.check_finite > 1 ||
+        o.iter_offset < 0 || o.iter_offset + n_iters >= ((int64_t)1 << 31))
+        return ARMOR_ERR_SHAPE;
+    // the selection counter (iteration, block, group) must fit in 63 bits
+    if (!unstructured && (double)(o.iter_offset + n_iters + 1) * ((double)d_out * (double)d_in / M) >= 4.0e18)
+        return ARMOR_ERR_SHAPE;
+    if (o.init_from_outputs && !mask_bits) return ARMOR_ERR_NULL;
     const int mask_group = unstructured ? 8 : M;
     Dims d = make_dims(d_out, d_in, d_block);
     if (!ws) return ARMOR_ERR_WORKSPACE;
@@ -416,15 +423,27 @@ armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const flo
     // weights of Eq. 2
     if (ldh > 0) launch_diag(H, d_in, ldh, f.D, s);
     else if (hipMemcpyAsync(f.D, H, sizeof(float) * d_in, hipMemcpyDeviceToDevice, s) != hipSuccess) return check_hip();
+    if (o.check_finite) { // optional validation: the only place the call waits for the device
+        int32_t *flag = reinterpret_cast<int32_t *>(f.beta_part), bad = 0;
+        launch_zero(f.beta_part, 1, s);
+        launch_count_nonfinite(W, w_dtype == ARMOR_BF16, d_out * d_in, f.D, d_in, flag, s);
+        if (hipMemcpyAsync(&bad, flag, sizeof(bad), hipMemcpyDeviceToHost, s) != hipSuccess ||
+            hipStreamSynchronize(s) != hipSuccess) {
+            st = check_hip();
+            return st != ARMOR_OK ? st : ARMOR_ERR_DEVICE;
+        }
+        if (bad != 0) return ARMOR_ERR_NONFINITE;
+    }
+    if (mask_changes && n_iters > 0) launch_zero(reinterpret_cast<float *>(mask_changes), n_iters, s);
     // Alg. 1: normalise, initialise
     {
         ProfScope ps(ARMOR_PROF_NORMALIZE, s);
         launch_colnorm(W, w_dtype == ARMOR_BF16, d_out, d_in, f.cn_partial, f.cn_chunks, r1p, s);
         launch_rownorm_scale(W, w_dtype == ARMOR_BF16, d_out, d_in, f.cn_partial + (size_t)f.cn_chunks * d_in, r2p, f.Wbar, s);
     }
-    launch_init_identity(A, d.nbi, d.b, s);
-    launch_init_identity(B, d.nbj, d.b, s);
-    {
+    if (!o.init_from_outputs) {
+        launch_init_identity(A, d.nbi, d.b, s);
+        launch_init_identity(B, d.nbj, d.b, s);
         ProfScope ps(ARMOR_PROF_INIT, s);
         if (unstructured)
             launch_unstructured_init(f.Wbar, f.D, d_out, d_in, o.unstructured_keep, S, mask,
@@ -447,6 +466,7 @@ armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const flo
                      b2 = o.adam_beta2 > 0 ? o.adam_beta2 : 0.999, eps = o.adam_eps > 0 ? o.adam_eps : 1e-8;
         launch_zero(f.mA, 2 * ((int64_t)d.nbi + d.nbj) * d.b * d.b + 2 * d_out * d_in, s);
         for (int t = 1; t <= n_iters; ++t) {
+            const int64_t t_draw = o.iter_offset + t;
             // joint Adam continuous step (Sec. 3.3.1): all three gradients at theta_{t-1}
             {
                 ProfScope ps(ARMOR_PROF_PHASE_FB, s, t > 1);
@@ -475,8 +495,9 @@ armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const flo
                 }
                 {
                     ProfScope ps(ARMOR_PROF_SPARSE, s, true);
-                    launch_sparse_step(d, f.G, S, mask, f.K, f.colnorm2, N, M, o.selection, o.seed, t, f.loss_part2,
-                                       loss_cont_trace ? loss_cont_trace + (t - 1) : nullptr, s);
+                    launch_sparse_step(d, f.G, S, mask, f.K, f.colnorm2, N, M, o.selection, o.seed, t_draw, f.loss_part2,
+                                       loss_cont_trace ? loss_cont_trace + (t - 1) : nullptr,
+                                       mask_changes ? mask_changes + (t - 1) : nullptr, s);
                 }
             }
             if ((t & 15) == 0) {
@@ -486,6 +507,8 @@ armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const flo
         }
     }
     for (int t = 1; o.variant == 0 && t <= n_iters; ++t) {
+        const int64_t t_draw = o.iter_offset + t;
+        double *eta_t = eta_trace ? eta_trace + 3 * (size_t)(t - 1) : nullptr;
         // continuous step (Alg. 2), each gradient at the already-updated parameters (Lemma 1)
         {
             ProfScope ps(ARMOR_PROF_PHASE_A, s, t > 1);
@@ -494,7 +517,7 @@ armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const flo
         {
             ProfScope ps(ARMOR_PROF_SMALL, s, true);
             launch_update_wrapper(A, d.nbi, d.b, f.gpart, f.nsA, f.beta_part, d.nblocks, f.loss_part,
-                                  loss_trace ? loss_trace + (t - 1) : nullptr, s);
+                                  loss_trace ? loss_trace + (t - 1) : nullptr, eta_t, s);
         }
         {
             ProfScope ps(ARMOR_PROF_PHASE_B, s, true);
@@ -503,9 +526,11 @@ armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const flo
         }
         {
             ProfScope ps(ARMOR_PROF_SMALL, s, true);
-            launch_update_wrapper(B, d.nbj, d.b, f.gpart, f.nsB, f.beta_part, d.nblocks, nullptr, nullptr, s);
+            launch_update_wrapper(B, d.nbj, d.b, f.gpart, f.nsB, f.beta_part, d.nblocks, nullptr, nullptr,
+                                  eta_t ? eta_t + 1 : nullptr, s);
             if (big) launch_big_wrapper_grams(d, A, B, f.D, f.colnorm2, f.fro2A, f.AtA, f.K, f.fro2K, s);
             else launch_wrapper_grams(d, A, B, f.D, f.colnorm2, f.fro2A, f.AtA, f.K, f.fro2K, s);
+            if (eta_t) launch_eta_W_trace(d, f.fro2A, f.fro2K, eta_t + 2, s);
         }
         if (unstructured) {
             // Sec. 4.5: continuous step only.  W' step on the kept entries, no core-gradient follow-up.
@@ -524,8 +549,9 @@ armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const flo
             }
             {
                 ProfScope ps(ARMOR_PROF_SPARSE, s, true);
-                launch_sparse_step(d, f.G, S, mask, f.K, f.colnorm2, N, M, o.selection, o.seed, t, f.loss_part2,
-                                   loss_cont_trace ? loss_cont_trace + (t - 1) : nullptr, s);
+                launch_sparse_step(d, f.G, S, mask, f.K, f.colnorm2, N, M, o.selection, o.seed, t_draw, f.loss_part2,
+                                   loss_cont_trace ? loss_cont_trace + (t - 1) : nullptr,
+                                   mask_changes ? mask_changes + (t - 1) : nullptr, s);
             }
         }
         if ((t & 15) == 0) {

@@ -99,9 +99,10 @@ void launch_init_identity(float *A, int nblk, int b, hipStream_t s);
 void launch_init_nm(const float *Wbar, const float *D, int64_t d_out, int64_t d_in, int N, int M, float *C,
                     uint8_t *mask, hipStream_t s);
 void launch_diag(const float *H, int64_t d_in, int64_t ldh, float *D, hipStream_t s);
-// A -= (sum of partials)/beta, beta = 2 * sum(beta_part); optionally trace_out = sum(loss_part).
+// A -= (sum of partials)/beta, beta = 2 * sum(beta_part); optionally trace_out = sum(loss_part) and
+// eta_out = 1/beta.
 void launch_update_wrapper(float *A, int nblk, int b, const float *gpart, int nsplit, const float *beta_part,
-                           int nblocks, const float *loss_part, double *trace_out, hipStream_t s);
+                           int nblocks, const float *loss_part, double *trace_out, double *eta_out, hipStream_t s);
 void launch_adam_wrapper(float *X, float *m, float *v, int nblk, int b, const float *gpart, int nsplit, double lr,
                          double b1, double b2, double eps, int64_t t, int nblocks, const float *loss_part,
                          double *trace_out, hipStream_t s);
@@ -110,7 +111,12 @@ int gram_parts(int b);
 void launch_sum_to_double(const float *part, int n, double *out, hipStream_t s);
 void launch_sparse_step(const Dims &d, const float *G, float *C, uint8_t *mask, const float *K,
                         const float *colnorm2, int N, int M, int selection, uint64_t seed, int64_t t,
-                        const float *loss_part, double *loss_cont_out, hipStream_t s);
+                        const float *loss_part, double *loss_cont_out, int32_t *changes_out, hipStream_t s);
+// eta_out = 1 / beta_W' (Eq. 11) from the same partial sums and in the same order as the W' kernels take it.
+void launch_eta_W_trace(const Dims &d, const float *fro2A, const float *fro2K, double *eta_out, hipStream_t s);
+// flag[0] = number of NaN/Inf entries of W (d_out x d_in, fp32 or bf16) plus NaN/Inf/negative entries of D.
+void launch_count_nonfinite(const void *W, int bf16, int64_t n, const float *D, int64_t d_in, int32_t *flag,
+                            hipStream_t s);
 void launch_denormalize(float *A, float *B, const float *r1, const float *r2, int64_t d_out, int64_t d_in, int b,
                         hipStream_t s);
 void launch_pack_nm(const float *S, const uint8_t *mask, int64_t d_out, int64_t d_in, int N, int M, void *values,

@@ -872,6 +872,20 @@ int chain_max_nsplit() { return 64; }
 // partial squared norms the wrapper-Gram kernels leave per block (one per 32-column slab up to b = 128)
 int gram_parts(int b) { return b <= 128 ? b / 32 : 1; }
 
+// Diagnostic: the step size 1 / beta_W' (Eq. 11) exactly as the W' kernels derive it (they apply
+// 2 / beta_W' to the half gradient A^T (R D) B^T).
+__global__ __launch_bounds__(64) void eta_W_trace_kernel(const float *__restrict__ fro2A, int nA,
+                                                         const float *__restrict__ fro2K, int nK,
+                                                         double *__restrict__ eta_out) {
+    const float e = wave_eta_W(fro2A, nA, fro2K, nK);
+    if (threadIdx.x == 0) *eta_out = 0.5 * (double)e;
+}
+
+void launch_eta_W_trace(const Dims &d, const float *fro2A, const float *fro2K, double *eta_out, hipStream_t s) {
+    hipLaunchKernelGGL(eta_W_trace_kernel, dim3(1), dim3(64), 0, s, fro2A, d.nbi * gram_parts(d.b), fro2K,
+                       d.nbj * gram_parts(d.b), eta_out);
+}
+
 #define ARMOR_DISPATCH_B(bval, ...)                      \
     switch (bval) {                                      \
     case 32:  { constexpr int BB = 32;  __VA_ARGS__; } break; \

@@ -380,12 +380,14 @@ void launch_diag_x(const void *X, int bf16, int64_t n, int64_t d_in, int64_t ldx
 // wrapper update (Alg. 2):  X^(k) <- X^(k) - grad^(k) / beta,  beta = 2 * sum of the per-block
 // summands of Eq. 9 / Eq. 10, grad^(k) = sum of the nsplit partials the chain kernel left.
 // A zero beta leaves X unchanged.  Workgroup (k, q) updates 256 entries of block k, one per thread; every workgroup re-derives beta in the same fixed order.  Workgroup (0,0) also writes the loss of the previous
-// iterate (sum of the block losses) when trace_out is given.
+// iterate (sum of the block losses) when trace_out is given, and the step size 1/beta (0 when beta = 0)
+// when eta_out is given.
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void update_wrapper_kernel(float *__restrict__ X, int b, const float *__restrict__ gpart,
                                                              int nsplit, const float *__restrict__ beta_part,
                                                              int nblocks, const float *__restrict__ loss_part,
-                                                             double *__restrict__ trace_out) {
+                                                             double *__restrict__ trace_out,
+                                                             double *__restrict__ eta_out) {
     __shared__ double red[4];
     const int tid = threadIdx.x, k = blockIdx.x, q = blockIdx.y;
     const int bb = b * b, e = q * 256 + tid;
@@ -401,6 +403,7 @@ __global__ __launch_bounds__(256) void update_wrapper_kernel(float *__restrict__
     double s = 0.0;
     for (int i = tid; i < nblocks; i += 256) s += (double)beta_part[i];
     const double beta = 2.0 * block_sum_256(s, red);
+    if (eta_out != nullptr && k == 0 && q == 0 && tid == 0) *eta_out = beta > 0.0 ? 1.0 / beta : 0.0;
     if (trace_out != nullptr && k == 0 && q == 0) {
         double l = 0.0;
         for (int i = tid; i < nblocks; i += 256) l += (double)loss_part[i];
@@ -412,10 +415,10 @@ __global__ __launch_bounds__(256) void update_wrapper_kernel(float *__restrict__
 }
 
 void launch_update_wrapper(float *A, int nblk, int b, const float *gpart, int nsplit, const float *beta_part,
-                           int nblocks, const float *loss_part, double *trace_out, hipStream_t s) {
+                           int nblocks, const float *loss_part, double *trace_out, double *eta_out, hipStream_t s) {
     int nq = (b * b + 255) / 256;
     hipLaunchKernelGGL(update_wrapper_kernel, dim3(nblk, nq), dim3(256), 0, s, A, b, gpart, nsplit, beta_part, nblocks,
-                       loss_part, trace_out);
+                       loss_part, trace_out, eta_out);
 }
 
 // Adam update of a wrapper (joint-Adam variant, Sec. 3.3.1): g = sum of the partial gradients in a
@@ -454,6 +457,34 @@ void launch_adam_wrapper(float *X, float *m, float *v, int nblk, int b, const fl
     const double inv_c1 = 1.0 / (1.0 - pow(b1, (double)t)), inv_c2 = 1.0 / (1.0 - pow(b2, (double)t));
     hipLaunchKernelGGL(adam_wrapper_kernel, dim3(nblk, (b * b + 255) / 256), dim3(256), 0, s, X, m, v, b, gpart, nsplit,
                        lr, b1, b2, eps, inv_c1, inv_c2, nblocks, loss_part, trace_out);
+}
+
+// Input validation (optional): counts NaN/Inf entries of W and NaN/Inf/negative loss weights D_j = ||X_j||^2
+// (Eq. 2).  flag must be zero on entry; integer atomics only.
+template <bool BF16>
+__global__ __launch_bounds__(256) void count_nonfinite_kernel(const void *__restrict__ W, int64_t n,
+                                                              const float *__restrict__ D, int64_t d_in,
+                                                              int32_t *__restrict__ flag) {
+    int bad = 0;
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < n; e += stride) {
+        const float w = load_w<BF16>(W, e);
+        bad += !(fabsf(w) <= 3.402823466e38f);
+    }
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < d_in; e += stride) {
+        const float dj = D[e];
+        bad += !(dj >= 0.f && dj <= 3.402823466e38f);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) bad += __shfl_xor(bad, off, 64);
+    if ((threadIdx.x & 63) == 0 && bad != 0) atomicAdd(flag, bad);
+}
+
+void launch_count_nonfinite(const void *W, int bf16, int64_t n, const float *D, int64_t d_in, int32_t *flag,
+                            hipStream_t s) {
+    const int grid = (int)std::max<int64_t>(1, std::min<int64_t>((n + 255) / 256, 4096));
+    if (bf16) hipLaunchKernelGGL(count_nonfinite_kernel<true>, dim3(grid), dim3(256), 0, s, W, n, D, d_in, flag);
+    else hipLaunchKernelGGL(count_nonfinite_kernel<false>, dim3(grid), dim3(256), 0, s, W, n, D, d_in, flag);
 }
 
 __global__ __launch_bounds__(256) void zero_kernel(float *__restrict__ x, int64_t n) {
@@ -685,7 +716,8 @@ __global__ __launch_bounds__(256) void sparse_step_kernel(const float *__restric
                                                           const float *__restrict__ colnorm2, int64_t d_in, int b,
                                                           int nbj, int nblocks, uint64_t seed,
                                                           int64_t t, const float *__restrict__ loss_part,
-                                                          double *__restrict__ loss_cont_out) {
+                                                          double *__restrict__ loss_cont_out,
+                                                          int32_t *__restrict__ changes_out) {
     constexpr int NPAT = binom(M, N);
     __shared__ float s_key[4];
     __shared__ int s_kap[4];
@@ -833,16 +865,19 @@ __global__ __launch_bounds__(256) void sparse_step_kernel(const float *__restric
         }
 #pragma unroll
         for (int p = 0; p < M; ++p) crow[p] = out[p];
-        mask[((int64_t)i * b + ip) * (d_in / M) + ((int64_t)j * b + k0) / M] = (uint8_t)bits;
+        uint8_t *mbyte = mask + ((int64_t)i * b + ip) * (d_in / M) + ((int64_t)j * b + k0) / M;
+        // groups whose kept set moved in this iteration (an integer count: the order of the adds does not matter)
+        if (changes_out != nullptr && *mbyte != (uint8_t)bits) atomicAdd(changes_out, 1);
+        *mbyte = (uint8_t)bits;
     }
 }
 
 void launch_sparse_step(const Dims &d, const float *G, float *C, uint8_t *mask, const float *K,
                         const float *colnorm2, int N, int M, int selection, uint64_t seed, int64_t t,
-                        const float *loss_part, double *loss_cont_out, hipStream_t s) {
+                        const float *loss_part, double *loss_cont_out, int32_t *changes_out, hipStream_t s) {
 #define ARMOR_SPARSE_LAUNCH(n, m, sel)                                                                        \
     hipLaunchKernelGGL((sparse_step_kernel<n, m, sel>), dim3(d.nblocks), dim3(256), 0, s, G, C, mask, K, colnorm2,  \
-                       d.d_in, d.b, d.nbj, d.nblocks, seed, t, loss_part, loss_cont_out)
+                       d.d_in, d.b, d.nbj, d.nblocks, seed, t, loss_part, loss_cont_out, changes_out)
 #define ARMOR_SPARSE_CASE(n, m)                                                                               \
     if (N == n && M == m) {                                                                                   \
         switch (selection) {                                                                                  \

@@ -107,3 +107,20 @@ def torch_mlp_down_inputs(X, Wg, Wu, chunk=8192):
         x = X[s:s + chunk].float()
         out[s:s + chunk] = (torch.nn.functional.silu(x @ Wg.float().T) * (x @ Wu.float().T)).to(X.dtype)
     return out
+
+
+def make_state(d_out, d_in, b, N, M, seed=0, perturb=0.3, core_std=None):
+    """A generic feasible starting point for the iteration (not the initial point of the method):
+    wrappers I + perturb/sqrt(b) * N(0,1) (so their spectrum stays near 1 at any block size), a
+    uniformly random N-of-M mask per group and N(0, core_std^2) values on the kept entries
+    (core_std defaults to 1/sqrt(d_in), the scale of a row-normalised weight).
+    Returns (A [d_out/b,b,b], B [d_in/b,b,b], C [d_out,d_in], mask [d_out,d_in] uint8)."""
+    rng = np.random.default_rng([seed, 4])
+    sc = perturb / np.sqrt(b)
+    A = (np.eye(b)[None] + sc * rng.standard_normal((d_out // b, b, b))).astype(np.float32)
+    B = (np.eye(b)[None] + sc * rng.standard_normal((d_in // b, b, b))).astype(np.float32)
+    order = np.argsort(rng.random((d_out, d_in // M, M), dtype=np.float32), axis=-1)
+    mask = (order < N).astype(np.uint8).reshape(d_out, d_in)
+    std = core_std if core_std is not None else 1.0 / np.sqrt(d_in)
+    C = rng.standard_normal((d_out, d_in), dtype=np.float32) * np.float32(std) * mask
+    return A, B, C, mask

@@ -7,23 +7,14 @@ The oracle cannot run 50 iterations of this layer in seconds, so:
   * 50 iterations: properties that hold at any size (N:M structure, monotone trace, closed-form
     L_0) and the oracle's evaluation of the loss of the returned factors.
 """
-import sys
-
 import numpy as np
 import pytest
 
 from paper_2510_05528_amd import synth
+from parity_util import (assert_diagnostics_parity, assert_trace_parity, assert_update_parity, identity_blocks,
+                         relfro, say)
 
 pytestmark = pytest.mark.gpu
-
-
-def say(*a):
-    print(*a, flush=True)
-    sys.stdout.flush()
-
-
-def relfro(a, b):
-    return float(np.linalg.norm(a.astype(np.float64) - b.astype(np.float64)) / np.linalg.norm(b.astype(np.float64)))
 
 
 def test_config2_full_size(orc):
@@ -57,7 +48,8 @@ def test_config2_full_size(orc):
     Dh = D.cpu().numpy()
     ws = torch.empty(armor.factorize_workspace_bytes(d_out, d_in, b, N, M), device=dev, dtype=torch.uint8)
     say("config2: 2 iterations on GPU and oracle")
-    out2 = armor.factorize_layer(W, D, b, N, M, 2, seed=0, ws=ws, want_cont_trace=True)
+    C0_gpu = armor.factorize_layer(W, D, b, N, M, 0, seed=0, ws=ws)["S"].cpu().numpy()
+    out2 = armor.factorize_layer(W, D, b, N, M, 2, seed=0, ws=ws, want_cont_trace=True, want_diagnostics=True)
     torch.cuda.synchronize()
     ref2 = orc.factorize_layer(Wh, Dh, b, N, M, 2, seed=0)
     mask2 = armor.unpack_mask(out2["mask_bits"].cpu().numpy(), M)
@@ -66,8 +58,36 @@ def test_config2_full_size(orc):
     eS = relfro(out2["S"].cpu().numpy(), ref2["C"])
     say("   mask agreement %.7f relF A %.2e B %.2e S %.2e" % (agree, eA, eB, eS))
     assert agree >= 0.999 and eA <= 1e-3 and eB <= 1e-3 and eS <= 1e-3
-    np.testing.assert_allclose(out2["loss_trace"].cpu().numpy(), ref2["loss_trace"], rtol=1e-5)
-    np.testing.assert_allclose(out2["loss_cont_trace"].cpu().numpy(), ref2["loss_cont_trace"], rtol=1e-5)
+    # the updates of the two iterations, the loss decreases, the step sizes and the changed-group counts
+    C0 = orc.init_nm(ref2["Wbar"], Dh, N, M)[0]
+    for name, got, want, start, sg in (("A", out2["A"].cpu().numpy(), ref2["A"], identity_blocks(d_out // b, b), None),
+                                       ("B", out2["B"].cpu().numpy(), ref2["B"], identity_blocks(d_in // b, b), None),
+                                       ("S", out2["S"].cpu().numpy(), ref2["C"], C0, C0_gpu)):
+        # two iterations from Eq. 3 move the core of this 1024-block layer by less than an ulp per entry: its
+        # update is compared, but only the generic-point run below can discriminate on it
+        say("   " + assert_update_parity(name, got, want, start, 2, start_got=sg, min_margin=None if name == "S" else 10.0))
+    tr2 = out2["loss_trace"].cpu().numpy()
+    worst = assert_trace_parity(tr2, ref2["loss_trace"])
+    assert_trace_parity(np.concatenate([tr2[:1], out2["loss_cont_trace"].cpu().numpy()]),
+                        np.concatenate([ref2["loss_trace"][:1], ref2["loss_cont_trace"]]), "loss after the continuous step")
+    say("   loss %.9g -> %.9g, worst relative error of a decrease %.2e" % (tr2[0], tr2[-1], worst))
+    assert_diagnostics_parity(out2, ref2, 2, (d_out // b) * (d_in // b))
+
+    say("config2: one iteration from a generic point on GPU and oracle")
+    A0, B0, C0g, m0 = synth.make_state(d_out, d_in, b, N, M, seed=71)
+    ginit = dict(A=torch.from_numpy(A0).to(dev), B=torch.from_numpy(B0).to(dev), S=torch.from_numpy(C0g).to(dev),
+                 mask_bits=torch.from_numpy(armor.pack_mask(m0, M)).to(dev))
+    outg = armor.factorize_layer(W, D, b, N, M, 1, seed=0, ws=ws, want_cont_trace=True, want_diagnostics=True, init=ginit)
+    torch.cuda.synchronize()
+    refg = orc.factorize_layer(Wh, Dh, b, N, M, 1, seed=0, init=dict(A=A0, B=B0, C=C0g, mask=m0))
+    maskg = armor.unpack_mask(outg["mask_bits"].cpu().numpy(), M)
+    assert float((maskg == refg["mask"]).mean()) >= 0.999 and np.all(maskg.reshape(d_out, d_in // M, M).sum(-1) == N)
+    for name, got, want, start in (("A", outg["A"], refg["A"], A0), ("B", outg["B"], refg["B"], B0), ("S", outg["S"], refg["C"], C0g)):
+        say("   " + assert_update_parity(name, got.cpu().numpy(), want, start, 1))
+    assert_trace_parity(outg["loss_trace"].cpu().numpy(), refg["loss_trace"])
+    assert_diagnostics_parity(outg, refg, 1, (d_out // b) * (d_in // b))
+    say("   groups changed %s (oracle %s)" % (outg["mask_changes"].cpu().numpy().tolist(), refg["mask_changes"].tolist()))
+    del outg, ginit
 
     say("config2: 50 iterations on GPU")
     out = armor.factorize_layer(W, D, b, N, M, 50, seed=0, ws=ws, want_cont_trace=True)

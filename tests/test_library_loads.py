@@ -45,11 +45,20 @@ def test_status_strings_and_host_side_validation():
     assert lib.armor_gram(p, 0, 16, 48, 48, p, 48, 0, None, 0, None) == 2                   # d_in not a multiple of 32
     assert lib.armor_gram(p, 7, 16, 64, 64, p, 64, 0, None, 0, None) == 3                   # dtype
     assert lib.armor_factorize_layer(None, 0, None, 0, 64, 64, 32, 2, 4, 1, None, None, None, None, None, None, None,
-                                     None, None, None, 0, None) == 1
+                                     None, None, None, None, None, 0, None) == 1
     assert lib.armor_factorize_layer(p, 0, p, 0, 64, 64, 32, 2, 4, 1, None, p, p, p, None, None, None, None, None, None,
-                                     0, None) == 4                                # no workspace
-    assert lib.armor_factorize_layer(p, 0, p, 0, 64, 60, 32, 2, 4, 1, None, p, p, p, None, None, None, None, None, p,
-                                     1 << 30, None) == 2
+                                     None, None, 0, None) == 4                    # no workspace
+    assert lib.armor_factorize_layer(p, 0, p, 0, 64, 60, 32, 2, 4, 1, None, p, p, p, None, None, None, None, None, None,
+                                     None, p, 1 << 30, None) == 2
+    # starting from the caller's state needs its mask; negative / absurd iteration offsets are rejected
+    o = binding.ArmorOpts(init_from_outputs=1)
+    assert lib.armor_factorize_layer(p, 0, p, 0, 64, 64, 32, 2, 4, 1, ctypes.byref(o), p, p, p, None, None, None, None,
+                                     None, None, None, p, 1 << 30, None) == 1
+    for bad in (binding.ArmorOpts(iter_offset=-1), binding.ArmorOpts(iter_offset=1 << 31),
+                binding.ArmorOpts(init_from_outputs=2), binding.ArmorOpts(check_finite=-1)):
+        assert lib.armor_factorize_layer(p, 0, p, 0, 64, 64, 32, 2, 4, 1, ctypes.byref(bad), p, p, p, p, None, None,
+                                         None, None, None, None, p, 1 << 30, None) == 2
+    assert lib.armor_status_string(8).startswith(b"non-finite")
     assert lib.armor_pack_nm(p, p, 4, 16, 2, 5, p, 0, p, None) == 2
     assert lib.armor_pack_meta_row_bytes(4096, 2, 4) == 512 and lib.armor_pack_meta_row_bytes(72, 5, 8) == 23
     assert lib.armor_pack_meta_row_bytes(70, 1, 2) == 5 and lib.armor_pack_meta_row_bytes(70, 2, 4) == 0
