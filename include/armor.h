@@ -39,7 +39,8 @@ typedef enum {
     ARMOR_ERR_ALIGN = 5,     /* a device buffer is not 16-byte aligned */
     ARMOR_ERR_DEVICE = 6,    /* a HIP call failed; see armor_last_hip_error() */
     ARMOR_ERR_UNSUPPORTED = 7, /* valid request that this build does not implement */
-    ARMOR_ERR_NONFINITE = 8    /* opts->check_finite: W has a NaN/Inf entry, or a loss weight H_jj is NaN/Inf/negative */
+    ARMOR_ERR_NONFINITE = 8,   /* opts->check_finite: W has a NaN/Inf entry, or a loss weight H_jj is NaN/Inf/negative */
+    ARMOR_ERR_TOO_LARGE = 9    /* armor_proxy_loss_noalloc: the problem needs more than the library's fixed scratch */
 } armor_status;
 
 typedef enum { ARMOR_F32 = 0, ARMOR_BF16 = 1 } armor_dtype;
@@ -154,6 +155,25 @@ size_t armor_proxy_loss_workspace_bytes(int64_t d_out, int64_t d_in, int64_t d_b
 armor_status armor_proxy_loss(const float *Wbar, const float *A, const float *S, const float *B, const float *H,
                               int64_t ldh, int64_t d_out, int64_t d_in, int64_t d_block, double *loss_out,
                               void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * armor_proxy_loss for callers that cannot allocate or supply a workspace: code under HIP graph capture,
+ * tight serving/monitoring loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and the same
+ * result as armor_proxy_loss, but the scratch (loss weights, identity wrappers for a NULL A / B, per-block
+ * partial losses, chain scratch at d_block 256) is a fixed 32 MiB array inside the library's device image --
+ * every GPU the library runs on holds one copy until the process ends -- whose device address is looked up on
+ * the first call on each device.  No hipMalloc / hipFree or other allocating call is made.
+ *   Limit: d_in*4 + (A ? 0 : d_out*d_block*4) + (B ? 0 : d_in*d_block*4) + 4*blocks (+ at d_block 256 at least
+ *   one 512 KiB chain scratch; as many workgroups run as fit) must fit in 32 MiB, else ARMOR_ERR_TOO_LARGE and
+ *   nothing is enqueued (e.g. 4096 x 4096 at d_block 128 needs 4.2 MiB; 28672 x 8192 at d_block 256 fits only
+ *   with both wrappers given).
+ *   All calls on one GPU share the array and it keeps the previous call's contents; every location is written
+ *   before it is read, so nothing has to be cleared, but two calls that overlap on one GPU (different streams or
+ *   threads) race: serialise them.  The first call on a device should be made outside a stream capture.
+ */
+armor_status armor_proxy_loss_noalloc(const float *Wbar, const float *A, const float *S, const float *B,
+                                      const float *H, int64_t ldh, int64_t d_out, int64_t d_in, int64_t d_block,
+                                      double *loss_out, void *hip_stream);
 
 /*
  * The whole BCD loop (Alg. 1): normalise W, initialise by Eq. 3 (A = B = I, top-N of every group by

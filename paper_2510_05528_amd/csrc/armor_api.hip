@@ -7,6 +7,7 @@
 
 #include <algorithm>
 #include <cstring>
+#include <mutex>
 #include <vector>
 
 using namespace armor;
@@ -222,6 +223,7 @@ const char *armor_status_string(armor_status s) {
     case ARMOR_ERR_DEVICE: return "HIP error";
     case ARMOR_ERR_UNSUPPORTED: return "unsupported configuration";
     case ARMOR_ERR_NONFINITE: return "non-finite entry in W or non-finite/negative loss weight";
+    case ARMOR_ERR_TOO_LARGE: return "problem needs more than the fixed scratch of the allocation-free entry point";
     }
     return "unknown status";
 }
@@ -324,16 +326,46 @@ armor_status armor_normalize(const void *W, armor_dtype w_dtype, int64_t d_out, 
     return check_hip();
 }
 
+// Scratch layout of the proxy-loss evaluation: the loss weights D, identity wrappers standing in for a
+// NULL A / B, one partial loss per block, and at d_block 256 the chain scratch of `big_wgs` workgroups.
+struct LossWs {
+    float *D, *Ai, *Bi, *loss_part, *big;
+    size_t bytes;
+};
+
+static LossWs carve_loss(void *base, const Dims &d, bool need_Ai, bool need_Bi, int big_wgs) {
+    LossWs w;
+    Carver c(base);
+    w.D = c.take<float>(d.d_in);
+    w.Ai = need_Ai ? c.take<float>((size_t)d.nbi * d.b * d.b) : nullptr;
+    w.Bi = need_Bi ? c.take<float>((size_t)d.nbj * d.b * d.b) : nullptr;
+    w.loss_part = c.take<float>(d.nblocks);
+    w.big = d.b > 128 ? c.take<float>(big_scratch_floats(d, big_wgs)) : nullptr;
+    w.bytes = c.off + 256;
+    return w;
+}
+
+// Enqueues Eq. 2 on scratch carved by carve_loss.  Every scratch location is written before it is read.
+static armor_status enqueue_proxy_loss(const float *Wbar, const float *A, const float *S, const float *B, const float *H,
+                                       int64_t ldh, const Dims &d, double *loss_out, const LossWs &w, int big_wgs,
+                                       hipStream_t s) {
+    if (ldh > 0) launch_diag(H, d.d_in, ldh, w.D, s);
+    else if (hipMemcpyAsync(w.D, H, sizeof(float) * d.d_in, hipMemcpyDeviceToDevice, s) != hipSuccess) return check_hip();
+    if (!A) { launch_init_identity(w.Ai, d.nbi, d.b, s); A = w.Ai; }
+    if (!B) { launch_init_identity(w.Bi, d.nbj, d.b, s); B = w.Bi; }
+    if (d.b > 128)
+        launch_big_phase_A(d, Wbar, S, A, B, w.D, choose_nsplit(d.nbi, d.nbj, d.b), nullptr, nullptr, w.loss_part, true,
+                           big_wgs, w.big, s);
+    else
+        launch_phase_A(d, Wbar, S, A, B, w.D, choose_nsplit(d.nbi, d.nbj, d.b), nullptr, nullptr, w.loss_part, true, nullptr, s);
+    launch_sum_to_double(w.loss_part, d.nblocks, loss_out, s);
+    return check_hip();
+}
+
 size_t armor_proxy_loss_workspace_bytes(int64_t d_out, int64_t d_in, int64_t d_block) {
     if (validate_shape(d_out, d_in, d_block) != ARMOR_OK) return 0;
     Dims d = make_dims(d_out, d_in, d_block);
-    Carver c(nullptr);
-    c.take<float>(d.d_in);
-    c.take<float>((size_t)d.nbi * d.b * d.b);
-    c.take<float>((size_t)d.nbj * d.b * d.b);
-    c.take<float>(d.nblocks);
-    if (d.b > 128) c.take<float>(big_scratch_floats(d, chain_slots(d.b)));
-    return c.off + 256;
+    return carve_loss(nullptr, d, true, true, chain_slots(d.b)).bytes;
 }
 
 armor_status armor_proxy_loss(const float *Wbar, const float *A, const float *S, const float *B, const float *H,
@@ -346,25 +378,65 @@ armor_status armor_proxy_loss(const float *Wbar, const float *A, const float *S,
     if (!ws || ws_bytes < armor_proxy_loss_workspace_bytes(d_out, d_in, d_block)) return ARMOR_ERR_WORKSPACE;
     if (!aligned16(Wbar) || !aligned16(S) || !aligned16(ws) || (A && !aligned16(A)) || (B && !aligned16(B)))
         return ARMOR_ERR_ALIGN;
-    hipStream_t s = (hipStream_t)hip_stream;
     Dims d = make_dims(d_out, d_in, d_block);
-    Carver c(ws);
-    float *D = c.take<float>(d.d_in);
-    float *Ai = c.take<float>((size_t)d.nbi * d.b * d.b);
-    float *Bi = c.take<float>((size_t)d.nbj * d.b * d.b);
-    float *loss_part = c.take<float>(d.nblocks);
-    float *big = d.b > 128 ? c.take<float>(big_scratch_floats(d, chain_slots(d.b))) : nullptr;
-    if (ldh > 0) launch_diag(H, d_in, ldh, D, s);
-    else if (hipMemcpyAsync(D, H, sizeof(float) * d_in, hipMemcpyDeviceToDevice, s) != hipSuccess) return check_hip();
-    if (!A) { launch_init_identity(Ai, d.nbi, d.b, s); A = Ai; }
-    if (!B) { launch_init_identity(Bi, d.nbj, d.b, s); B = Bi; }
-    if (d.b > 128)
-        launch_big_phase_A(d, Wbar, S, A, B, D, choose_nsplit(d.nbi, d.nbj, d.b), nullptr, nullptr, loss_part, true,
-                           chain_slots(d.b), big, s);
-    else
-        launch_phase_A(d, Wbar, S, A, B, D, choose_nsplit(d.nbi, d.nbj, d.b), nullptr, nullptr, loss_part, true, nullptr, s);
-    launch_sum_to_double(loss_part, d.nblocks, loss_out, s);
-    return check_hip();
+    const int big_wgs = chain_slots(d.b);
+    return enqueue_proxy_loss(Wbar, A, S, B, H, ldh, d, loss_out, carve_loss(ws, d, true, true, big_wgs), big_wgs,
+                              (hipStream_t)hip_stream);
+}
+
+// ---- allocation-free evaluation of Eq. 2 ---------------------------------------------------------
+// The scratch of armor_proxy_loss_noalloc lives in the library's own device image, one copy per GPU,
+// held until the process ends.  Host code must not use the array's name as an address: the device
+// address is looked up once per device and only that pointer is handed to kernels and copies.
+#define ARMOR_NOALLOC_SCRATCH_BYTES ((size_t)32 << 20)
+static __device__ __align__(256) unsigned char scratch[ARMOR_NOALLOC_SCRATCH_BYTES];
+
+static armor_status noalloc_scratch(void **out) {
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static void *ptr[kMaxDevices] = {};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        armor_status st = check_hip();
+        return st != ARMOR_OK ? st : ARMOR_ERR_DEVICE;
+    }
+    std::lock_guard<std::mutex> lock(mu);
+    if (ptr[dev] == nullptr) { // first call on this device (the current one): resolve its copy of the array
+        void *p = nullptr;
+        hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || p == nullptr) {
+            g_last_hip_error = (int)e;
+            (void)hipGetLastError();
+            return ARMOR_ERR_DEVICE;
+        }
+        ptr[dev] = p;
+    }
+    *out = ptr[dev];
+    return ARMOR_OK;
+}
+
+armor_status armor_proxy_loss_noalloc(const float *Wbar, const float *A, const float *S, const float *B,
+                                      const float *H, int64_t ldh, int64_t d_out, int64_t d_in, int64_t d_block,
+                                      double *loss_out, void *hip_stream) {
+    if (!Wbar || !S || !H || !loss_out) return ARMOR_ERR_NULL;
+    armor_status st = validate_shape(d_out, d_in, d_block);
+    if (st != ARMOR_OK) return st;
+    if (ldh != 0 && ldh < d_in) return ARMOR_ERR_SHAPE;
+    if (!aligned16(Wbar) || !aligned16(S) || (A && !aligned16(A)) || (B && !aligned16(B))) return ARMOR_ERR_ALIGN;
+    Dims d = make_dims(d_out, d_in, d_block);
+    // at d_block 256 as many workgroups as the fixed scratch has room for (each needs 2 b^2 floats)
+    int big_wgs = chain_slots(d.b);
+    if (d.b > 128) {
+        const size_t fixed = carve_loss(nullptr, d, !A, !B, 0).bytes, per_wg = big_scratch_floats(d, 1) * sizeof(float);
+        if (fixed + per_wg > ARMOR_NOALLOC_SCRATCH_BYTES) return ARMOR_ERR_TOO_LARGE;
+        big_wgs = (int)std::min<size_t>((size_t)big_wgs, (ARMOR_NOALLOC_SCRATCH_BYTES - fixed) / per_wg);
+    }
+    if (carve_loss(nullptr, d, !A, !B, big_wgs).bytes > ARMOR_NOALLOC_SCRATCH_BYTES) return ARMOR_ERR_TOO_LARGE;
+    void *base = nullptr;
+    st = noalloc_scratch(&base);
+    if (st != ARMOR_OK) return st;
+    return enqueue_proxy_loss(Wbar, A, S, B, H, ldh, d, loss_out, carve_loss(base, d, !A, !B, big_wgs), big_wgs,
+                              (hipStream_t)hip_stream);
 }
 
 size_t armor_factorize_workspace_bytes(int64_t d_out, int64_t d_in, int64_t d_block, int N, int M,

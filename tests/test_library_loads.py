@@ -59,6 +59,11 @@ def test_status_strings_and_host_side_validation():
         assert lib.armor_factorize_layer(p, 0, p, 0, 64, 64, 32, 2, 4, 1, ctypes.byref(bad), p, p, p, p, None, None,
                                          None, None, None, None, p, 1 << 30, None) == 2
     assert lib.armor_status_string(8).startswith(b"non-finite")
+    # the allocation-free loss: argument errors and the fixed-scratch limit are host-side checks
+    assert lib.armor_proxy_loss_noalloc(None, None, None, None, None, 0, 64, 64, 32, None, None) == 1
+    assert lib.armor_proxy_loss_noalloc(p, None, p, None, p, 0, 64, 60, 32, p, None) == 2
+    assert lib.armor_proxy_loss_noalloc(p, None, p, None, p, 0, 16384, 16384, 256, p, None) == 9   # 2 x 16 MiB of identities
+    assert b"fixed scratch" in lib.armor_status_string(9)
     assert lib.armor_pack_nm(p, p, 4, 16, 2, 5, p, 0, p, None) == 2
     assert lib.armor_pack_meta_row_bytes(4096, 2, 4) == 512 and lib.armor_pack_meta_row_bytes(72, 5, 8) == 23
     assert lib.armor_pack_meta_row_bytes(70, 1, 2) == 5 and lib.armor_pack_meta_row_bytes(70, 2, 4) == 0
