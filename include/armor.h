@@ -30,7 +30,10 @@
 extern "C" {
 #endif
 
-typedef enum {
+/* Status and dtype codes travel as 32-bit integers (any value a caller passes is representable and is
+ * validated; an out-of-range value of a C++ enumeration type would be undefined behaviour). */
+typedef int32_t armor_status;
+enum {
     ARMOR_OK = 0,
     ARMOR_ERR_NULL = 1,      /* a required pointer is NULL */
     ARMOR_ERR_SHAPE = 2,     /* d_block does not divide d_out/d_in, M does not divide d_block, bad N/M, ... */
@@ -41,9 +44,10 @@ typedef enum {
     ARMOR_ERR_UNSUPPORTED = 7, /* valid request that this build does not implement */
     ARMOR_ERR_NONFINITE = 8,   /* opts->check_finite: W has a NaN/Inf entry, or a loss weight H_jj is NaN/Inf/negative */
     ARMOR_ERR_TOO_LARGE = 9    /* armor_proxy_loss_noalloc: the problem needs more than the library's fixed scratch */
-} armor_status;
+};
 
-typedef enum { ARMOR_F32 = 0, ARMOR_BF16 = 1 } armor_dtype;
+typedef int32_t armor_dtype;
+enum { ARMOR_F32 = 0, ARMOR_BF16 = 1 };
 
 /* Options of armor_factorize_layer.  Zero-initialise for the defaults. */
 typedef struct {
