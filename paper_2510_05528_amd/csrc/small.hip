@@ -552,39 +552,38 @@ __device__ __forceinline__ float neg_log_uniform(uint64_t z) {
     return x < 0.0625f ? poly : big;
 }
 
-// w = G^+ q for a symmetric PSD N x N matrix (Moore-Penrose, eigenvalues <= 1e-12 * max dropped),
-// returns q^T G^+ q.  N = 2: closed form; N >= 3: triangular solves when G is provably far from the drop
-// threshold, else cyclic Jacobi; fully unrolled so everything stays in registers.
+// w = G^+ q for a symmetric PSD N x N matrix (Moore-Penrose: eigenvalues <= 1e-12 * the largest are
+// treated as zero), returns q^T G^+ q.  Everything is unrolled so that it stays in registers.
+//   N = 2: eigenvalues from trace and determinant.  lambda_max = h + r with h = (a+d)/2, r = |((a-d)/2, b)|,
+//          lambda_min = det / lambda_max (no cancellation).  Both kept: G^+ = adj(G)/det.  Only the larger
+//          kept: G is lambda_max v v^T up to the dropped part, so G^+ = G / lambda_max^2.
+//   N >= 3: L D L^T when G is provably far from the drop threshold, otherwise a one-sided Jacobi
+//          orthogonalisation (Hestenes): plane rotations V make the columns of U = G V mutually orthogonal;
+//          then G = U V^T, the column norms sigma_k are the eigenvalues of the PSD matrix, and
+//          G^+ q = sum_k v_k (u_k . q) / sigma_k^2 over the kept k.
 template <int N> __device__ double pinv_solve(double (&G)[N][N], const double (&q)[N], double (&w)[N]) {
     if (N == 1) {
         w[0] = G[0][0] > 0.0 ? q[0] / G[0][0] : 0.0;
         return w[0] * q[0];
     }
-    if (N == 2) { // one Jacobi rotation diagonalises a symmetric 2 x 2 matrix exactly
+    if (N == 2) {
         const double a = G[0][0], b = G[0][N - 1], d = G[N - 1][N - 1];
-        double c = 1.0, sn = 0.0, t = 0.0;
-        if (b != 0.0) {
-            const double theta = (d - a) / (2.0 * b);
-            t = (theta >= 0.0 ? 1.0 : -1.0) / (fabs(theta) + sqrt(theta * theta + 1.0));
-            c = 1.0 / sqrt(t * t + 1.0);
-            sn = t * c;
-        }
-        const double lam[2] = {a - t * b, d + t * b};      // eigenvalues
-        const double vec[2][2] = {{c, -sn}, {sn, c}};       // their eigenvectors
-        const double lmax = fmax(lam[0], lam[1]);
+        const double h = 0.5 * (a + d), e = 0.5 * (a - d);
+        const double lmax = h + sqrt(e * e + b * b);
         w[0] = 0.0;
         w[N - 1] = 0.0;
-        if (lmax <= 0.0) return 0.0;
-        double gain = 0.0;
-#pragma unroll
-        for (int k = 0; k < 2; ++k)
-            if (lam[k] > 1e-12 * lmax) {
-                const double proj = vec[k][0] * q[0] + vec[k][1] * q[N - 1], pl = proj / lam[k];
-                w[0] += vec[k][0] * pl;
-                w[N - 1] += vec[k][1] * pl;
-                gain += proj * pl;
-            }
-        return gain;
+        if (!(lmax > 0.0)) return 0.0;
+        const double det = a * d - b * b, lmin = det / lmax;
+        if (lmin > 1e-12 * lmax) {
+            const double inv = 1.0 / det;
+            w[0] = (d * q[0] - b * q[N - 1]) * inv;
+            w[N - 1] = (a * q[N - 1] - b * q[0]) * inv;
+        } else {
+            const double inv = 1.0 / (lmax * lmax);
+            w[0] = (a * q[0] + b * q[N - 1]) * inv;
+            w[N - 1] = (b * q[0] + d * q[N - 1]) * inv;
+        }
+        return q[0] * w[0] + q[N - 1] * w[N - 1];
     }
     {
         // Fast path.  With pivots d_k of G = L D L^T and rho_k = d_k / G_kk (the pivots of the unit-
@@ -640,74 +639,81 @@ template <int N> __device__ double pinv_solve(double (&G)[N][N], const double (&
             return gain;
         }
     }
+    // One-sided Jacobi.  U starts as G (its columns), V as the identity; a rotation of columns (i, j) by the
+    // angle that zeroes their inner product is applied to both, so U = G V throughout.
     double V[N][N];
 #pragma unroll
-    for (int p = 0; p < N; ++p)
+    for (int i = 0; i < N; ++i)
 #pragma unroll
-        for (int r = 0; r < N; ++r) V[p][r] = (p == r) ? 1.0 : 0.0;
-    for (int sweep = 0; sweep < 60; ++sweep) {
-        double off = 0.0, dg = 0.0;
+        for (int j = 0; j < N; ++j) V[i][j] = i == j ? 1.0 : 0.0;
+    for (int pass = 0; pass < 40; ++pass) {
+        bool turned = false;
 #pragma unroll
-        for (int p = 0; p < N; ++p)
+        for (int i = 0; i < N - 1; ++i)
 #pragma unroll
-            for (int r = 0; r < N; ++r) {
-                if (p != r) off += G[p][r] * G[p][r];
-                else dg += G[p][r] * G[p][r];
-            }
-        if (off <= 1e-30 * dg || off == 0.0) break;
+            for (int j = i + 1; j < N; ++j) {
+                double nii = 0.0, njj = 0.0, nij = 0.0;
 #pragma unroll
-        for (int p = 0; p < N - 1; ++p)
-#pragma unroll
-            for (int r = p + 1; r < N; ++r) {
-                double apq = G[p][r];
-                if (apq != 0.0) {
-                    double theta = (G[r][r] - G[p][p]) / (2.0 * apq);
-                    double t = (theta >= 0.0 ? 1.0 : -1.0) / (fabs(theta) + sqrt(theta * theta + 1.0));
-                    double c = 1.0 / sqrt(t * t + 1.0), s = t * c;
+                for (int k = 0; k < N; ++k) {
+                    nii += G[k][i] * G[k][i];
+                    njj += G[k][j] * G[k][j];
+                    nij += G[k][i] * G[k][j];
+                }
+                if (nij * nij > 1e-30 * nii * njj) { // columns not yet orthogonal to working precision
+                    const double zeta = (njj - nii) / (2.0 * nij);
+                    const double tn = copysign(1.0, zeta) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
+                    const double cs = 1.0 / sqrt(1.0 + tn * tn), sn = cs * tn;
 #pragma unroll
                     for (int k = 0; k < N; ++k) {
-                        double gkp = G[k][p], gkq = G[k][r];
-                        G[k][p] = c * gkp - s * gkq;
-                        G[k][r] = s * gkp + c * gkq;
+                        const double ui = G[k][i], uj = G[k][j], vi = V[k][i], vj = V[k][j];
+                        G[k][i] = cs * ui - sn * uj;
+                        G[k][j] = sn * ui + cs * uj;
+                        V[k][i] = cs * vi - sn * vj;
+                        V[k][j] = sn * vi + cs * vj;
                     }
-#pragma unroll
-                    for (int k = 0; k < N; ++k) {
-                        double gpk = G[p][k], gqk = G[r][k];
-                        G[p][k] = c * gpk - s * gqk;
-                        G[r][k] = s * gpk + c * gqk;
-                    }
-#pragma unroll
-                    for (int k = 0; k < N; ++k) {
-                        double vkp = V[k][p], vkq = V[k][r];
-                        V[k][p] = c * vkp - s * vkq;
-                        V[k][r] = s * vkp + c * vkq;
-                    }
+                    turned = true;
                 }
             }
+        if (!turned) break;
     }
-    double lmax = 0.0;
+    double sig2[N], smax2 = 0.0;
 #pragma unroll
-    for (int k = 0; k < N; ++k) lmax = fmax(lmax, G[k][k]);
+    for (int j = 0; j < N; ++j) {
+        double n2 = 0.0;
 #pragma unroll
-    for (int p = 0; p < N; ++p) w[p] = 0.0;
+        for (int k = 0; k < N; ++k) n2 += G[k][j] * G[k][j];
+        sig2[j] = n2;
+        smax2 = fmax(smax2, n2);
+    }
+#pragma unroll
+    for (int i = 0; i < N; ++i) w[i] = 0.0;
+    if (!(smax2 > 0.0)) return 0.0;
     double gain = 0.0;
-    if (lmax <= 0.0) return 0.0;
 #pragma unroll
-    for (int k = 0; k < N; ++k) {
-        double lam = G[k][k];
-        if (lam > 1e-12 * lmax) {
-            double proj = 0.0;
+    for (int j = 0; j < N; ++j)
+        if (sig2[j] > 1e-24 * smax2) { // sigma_j > 1e-12 sigma_max
+            double uq = 0.0, vq = 0.0;
 #pragma unroll
-            for (int p = 0; p < N; ++p) proj += V[p][k] * q[p];
+            for (int k = 0; k < N; ++k) {
+                uq += G[k][j] * q[k];
+                vq += V[k][j] * q[k];
+            }
+            const double coef = uq / sig2[j];
 #pragma unroll
-            for (int p = 0; p < N; ++p) w[p] += V[p][k] * proj / lam;
-            gain += proj * proj / lam;
+            for (int i = 0; i < N; ++i) w[i] += V[i][j] * coef;
+            gain += vq * coef;
         }
-    }
     return gain;
 }
 
 constexpr int binom(int n, int k) { return (k == 0 || k == n) ? 1 : binom(n - 1, k - 1) + binom(n - 1, k); }
+// n, k <= 7 at run time: C(n, k) by the product formula (exact in integers at every step)
+__device__ __forceinline__ int binom_rt(int n, int k) {
+    if (k < 0 || k > n) return 0;
+    int c = 1;
+    for (int t = 1; t <= k; ++t) c = c * (n - k + t) / t;
+    return c;
+}
 
 // SEL = the selection heuristic (a template argument: the pass over the groups then has no branches)
 template <int N, int M, int SEL>
@@ -826,13 +832,18 @@ __global__ __launch_bounds__(256) void sparse_step_kernel(const float *__restric
     static_assert(NPAT <= 128, "the sweep threads must fit in the workgroup from any wave offset");
     const int sw = (tid - 64 * (blk & 3)) & 255; // sweep-thread index
     if (sw < NPAT) {
+        // the sw-th N-subset of {0..M-1} in lexicographic order, by the combinatorial number system: at
+        // position x take the smallest admissible element e for which the subsets that start with it,
+        // C(M-1-e, N-1-x) of them, cover the remaining rank
+        int rank = sw, e = 0;
 #pragma unroll
-        for (int p = 0; p < N; ++p) sub[p] = p;
-        for (int step = 0; step < sw; ++step) { // advance to the sw-th subset
-            int p = N - 1;
-            while (p >= 0 && sub[p] == M - N + p) --p;
-            ++sub[p];
-            for (int r = p + 1; r < N; ++r) sub[r] = sub[r - 1] + 1;
+        for (int x = 0; x < N; ++x) {
+            for (;; ++e) {
+                const int below = binom_rt(M - 1 - e, N - 1 - x);
+                if (rank < below) break;
+                rank -= below;
+            }
+            sub[x] = e++;
         }
         double Gs[N][N], qs[N];
 #pragma unroll

@@ -242,6 +242,41 @@ def test_step_from_a_generic_point(armor, torch, orc, d_out, d_in, b, N, M, iter
         assert relfro(ref[k], start) > 1e-3, k          # the oracle did move every parameter well beyond the bar
 
 
+def rank_deficient_state(d_out, d_in, b, N, M, seed):
+    """A feasible point whose every group has fewer than N distinct rows of B: the first N-1 rows of a group are
+    identical (their core columns too, all kept), the N-th is on its own, the pruned M-N rows are identical.
+    Identical kept columns receive identical gradients and pruned rows none, so the continuous step keeps the
+    duplicates exact and EVERY pattern of the sparse-core step has a singular B' D B'^T (Eq. 7/8 with a true
+    pseudo-inverse; the minimum-norm weights are unique)."""
+    A, B, _, _ = synth.make_state(d_out, d_in, b, N, M, seed=seed)
+    rng = np.random.default_rng(seed)
+    B = B.reshape(d_in // b, b // M, M, b).copy()
+    B[:, :, 1:N - 1, :] = B[:, :, 0:1, :]
+    B[:, :, N + 1:, :] = B[:, :, N:N + 1, :]
+    mask = np.zeros((d_out, d_in // M, M), np.uint8)
+    mask[:, :, :N] = 1
+    C = (rng.standard_normal((d_out, d_in // M, M)) / np.sqrt(d_in)).astype(np.float32)
+    C[:, :, 1:N - 1] = C[:, :, 0:1]
+    return A, B.reshape(d_in // b, b, b), (C * mask).reshape(d_out, d_in), mask.reshape(d_out, d_in)
+
+
+@pytest.mark.parametrize("d_out,d_in,b,N,M", [(128, 192, 64, 4, 8), (256, 128, 128, 6, 8), (96, 160, 32, 3, 4), (128, 128, 64, 3, 8)])
+def test_sparse_step_with_singular_patterns(armor, torch, orc, d_out, d_in, b, N, M):
+    """The pseudo-inverse branch of Eq. 7/8 on the device: a group has three distinct rows of B, so for N >= 4
+    every pattern's B' D B'^T is singular and the written weights come from the pseudo-inverse; for N = 3 the
+    singular patterns only compete with the regular ones, and must lose."""
+    W, X = make_layer(d_out, d_in, 300, seed=3, act_outliers=(0.01, 20.0))
+    D = np.diag(orc.gram(X)).astype(np.float32)
+    init = rank_deficient_state(d_out, d_in, b, N, M, seed=5)
+    out, ref = check_factorization(armor, torch, orc, W, D, b, N, M, 1, seed=2, init=init)
+    assert ref["mask_changes"][0] > 0
+    np.testing.assert_array_equal(armor.unpack_mask(out["mask_bits"].cpu().numpy(), M), ref["mask"])
+    if N >= 4:                    # three distinct rows, fewer than N: the refit groups carry equal weights on duplicates
+        S, m0 = out["S"].cpu().numpy().reshape(d_out, d_in // M, M), init[3].reshape(d_out, d_in // M, M)
+        changed = (ref["mask"].reshape(d_out, d_in // M, M) != m0).any(-1)
+        assert np.all(S[changed][:, 0] == S[changed][:, 1])
+
+
 @pytest.mark.parametrize("d_out,d_in,b,N,M", [(3072, 3072, 128, 2, 4), (4352, 4096, 256, 2, 4)])
 def test_step_from_a_generic_point_many_blocks(armor, torch, orc, d_out, d_in, b, N, M):
     """The same with more blocks than resident workgroups (576 blocks of 128 on 512 slots; 272 blocks of
