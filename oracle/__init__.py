@@ -46,6 +46,11 @@ def lib():
     return _lib
 
 
+def set_threads(n):
+    """Number of OpenMP threads the oracle's parallel loops use from now on."""
+    ctypes.CDLL("libgomp.so.1").omp_set_num_threads(int(n))
+
+
 def _f32(a):
     a = np.ascontiguousarray(a, dtype=np.float32)
     return a

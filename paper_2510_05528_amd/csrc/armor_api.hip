@@ -135,6 +135,8 @@ struct FactorWs {
     float *big_scratch;
     float *stream_scratch; // one b x b tile per workgroup of a gradient phase (streamed-operand form, d_block 128)
     float *mA, *vA, *mB, *vB, *mC, *vC, *gBpart;
+    WrapperPlanes planes; // bf16 pieces of the wrapper-sized operands (d_block 128, sequential variant)
+    bool use_planes;
     int nsA, nsB, cn_chunks;
     size_t bytes;
 };
@@ -165,7 +167,7 @@ FactorWs carve_factor(void *ws, const Dims &d, int mask_group, const armor_opts 
     const bool adam = opts && opts->variant == 1, unstr = opts && opts->sparsity == 1;
     // at d_block 128 the gradient phases run with two workgroups per CU (streamed-operand form)
     const bool stream = d.b == 128;
-    const int slots = chain_slots(d.b) * (stream ? 2 : 1);
+    const int slots = chain_slots(d.b) * (stream ? (adam ? 2 : stream_wgs_per_cu()) : 1);
     f.nsA = choose_nsplit(d.nbi, d.nbj, d.b, slots);
     f.nsB = choose_nsplit(d.nbj, d.nbi, d.b, slots);
     f.cn_chunks = colnorm_chunks(d.d_out);
@@ -190,6 +192,17 @@ FactorWs carve_factor(void *ws, const Dims &d, int mask_group, const armor_opts 
     f.unstructured = (opts && opts->sparsity == 1)
                          ? c.take<char>(unstructured_init_ws_bytes(d.d_out, d.d_in)) : nullptr;
     f.big_scratch = d.b > 128 ? c.take<float>(big_scratch_floats(d, chain_slots(d.b))) : nullptr;
+    f.planes = WrapperPlanes{};
+    f.use_planes = stream && !adam && stream_uses_planes();
+    if (f.use_planes) {
+        const size_t per = (size_t)3 * bb;
+        f.planes.A = c.take<uint16_t>(per * d.nbi);
+        f.planes.AT = c.take<uint16_t>(per * d.nbi);
+        f.planes.AtA = c.take<uint16_t>(per * d.nbi);
+        f.planes.B = c.take<uint16_t>(per * d.nbj);
+        f.planes.BT = c.take<uint16_t>(per * d.nbj);
+        f.planes.K = c.take<uint16_t>(per * d.nbj);
+    }
     f.mA = f.vA = f.mB = f.vB = f.mC = f.vC = f.gBpart = nullptr;
     if (opts && opts->variant == 1) { // Adam moments (one contiguous run, zeroed together) + per-block grad_B partials
         const size_t na = (size_t)d.nbi * bb, nb = (size_t)d.nbj * bb;
@@ -357,7 +370,8 @@ static armor_status enqueue_proxy_loss(const float *Wbar, const float *A, const 
         launch_big_phase_A(d, Wbar, S, A, B, w.D, choose_nsplit(d.nbi, d.nbj, d.b), nullptr, nullptr, w.loss_part, true,
                            big_wgs, w.big, s);
     else
-        launch_phase_A(d, Wbar, S, A, B, w.D, choose_nsplit(d.nbi, d.nbj, d.b), nullptr, nullptr, w.loss_part, true, nullptr, s);
+        launch_phase_A(d, Wbar, S, A, B, w.D, choose_nsplit(d.nbi, d.nbj, d.b), nullptr, nullptr, w.loss_part, true, nullptr,
+                       nullptr, s);
     launch_sum_to_double(w.loss_part, d.nblocks, loss_out, s);
     return check_hip();
 }
@@ -528,11 +542,17 @@ armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const flo
 
     const bool big = d.b > 128;
     const int slots = chain_slots(d.b);
+    const WrapperPlanes *pl = f.use_planes ? &f.planes : nullptr;
     auto run_phase_A = [&](bool loss_only) {
         if (big) launch_big_phase_A(d, f.Wbar, S, A, B, f.D, f.nsA, f.gpart, f.beta_part, f.loss_part, loss_only, slots,
                                     f.big_scratch, s);
-        else launch_phase_A(d, f.Wbar, S, A, B, f.D, f.nsA, f.gpart, f.beta_part, f.loss_part, loss_only, f.stream_scratch, s);
+        else launch_phase_A(d, f.Wbar, S, A, B, f.D, f.nsA, f.gpart, f.beta_part, f.loss_part, loss_only, f.stream_scratch,
+                            pl, s);
     };
+    if (pl) { // pieces of theta_0's wrappers
+        const PlaneJob jobs[2] = {{A, d.nbi, f.planes.A, f.planes.AT}, {B, d.nbj, f.planes.B, f.planes.BT}};
+        launch_make_planes(jobs, 2, s);
+    }
     if (o.variant == 1) {
         const double lr = o.lr > 0 ? o.lr : 1e-4, b1 = o.adam_beta1 > 0 ? o.adam_beta1 : 0.9,
                      b2 = o.adam_beta2 > 0 ? o.adam_beta2 : 0.999, eps = o.adam_eps > 0 ? o.adam_eps : 1e-8;
@@ -590,11 +610,15 @@ armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const flo
             ProfScope ps(ARMOR_PROF_SMALL, s, true);
             launch_update_wrapper(A, d.nbi, d.b, f.gpart, f.nsA, f.beta_part, d.nblocks, f.loss_part,
                                   loss_trace ? loss_trace + (t - 1) : nullptr, eta_t, s);
+            if (pl) {
+                const PlaneJob job = {A, d.nbi, f.planes.A, f.planes.AT};
+                launch_make_planes(&job, 1, s);
+            }
         }
         {
             ProfScope ps(ARMOR_PROF_PHASE_B, s, true);
             if (big) launch_big_phase_B(d, f.Wbar, S, A, B, f.D, f.nsB, f.gpart, f.beta_part, f.Sp, slots, f.big_scratch, s);
-            else launch_phase_B(d, f.Wbar, S, A, B, f.D, f.nsB, f.gpart, f.beta_part, f.Sp, f.stream_scratch, s);
+            else launch_phase_B(d, f.Wbar, S, A, B, f.D, f.nsB, f.gpart, f.beta_part, f.Sp, f.stream_scratch, pl, s);
         }
         {
             ProfScope ps(ARMOR_PROF_SMALL, s, true);
@@ -602,6 +626,11 @@ armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const flo
                                   eta_t ? eta_t + 1 : nullptr, s);
             if (big) launch_big_wrapper_grams(d, A, B, f.D, f.colnorm2, f.fro2A, f.AtA, f.K, f.fro2K, s);
             else launch_wrapper_grams(d, A, B, f.D, f.colnorm2, f.fro2A, f.AtA, f.K, f.fro2K, s);
+            if (pl) {
+                const PlaneJob jobs[3] = {{B, d.nbj, f.planes.B, f.planes.BT}, {f.K, d.nbj, f.planes.K, nullptr},
+                                          {f.AtA, d.nbi, f.planes.AtA, nullptr}};
+                launch_make_planes(jobs, 3, s);
+            }
             if (eta_t) launch_eta_W_trace(d, f.fro2A, f.fro2K, eta_t + 2, s);
         }
         if (unstructured) {
@@ -609,7 +638,7 @@ armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const flo
             ProfScope ps(ARMOR_PROF_PHASE_WS, s, true);
             if (big) launch_big_phase_WS(d, f.Wbar, S, A, B, f.D, f.AtA, f.K, mask, mask_group, f.fro2A, f.fro2K, nullptr,
                                          nullptr, f.Sp, false, slots, f.big_scratch, s);
-            else launch_phase_W(d, f.Wbar, S, A, B, f.D, mask, mask_group, f.fro2A, f.fro2K, f.Sp, slots, s);
+            else launch_phase_W(d, f.Wbar, S, A, B, f.D, mask, mask_group, f.fro2A, f.fro2K, f.Sp, slots, pl, s);
         } else {
             // W' step fused with the core gradient at the updated core; then the sparse-core step (Alg. 3)
             {
@@ -617,7 +646,7 @@ armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const flo
                 if (big) launch_big_phase_WS(d, f.Wbar, S, A, B, f.D, f.AtA, f.K, mask, mask_group, f.fro2A, f.fro2K, f.G,
                                              f.loss_part2, f.Sp, true, slots, f.big_scratch, s);
                 else launch_phase_WS(d, f.Wbar, S, A, B, f.D, f.AtA, f.K, mask, mask_group, f.fro2A, f.fro2K, f.G,
-                                     f.loss_part2, f.Sp, slots, s);
+                                     f.loss_part2, f.Sp, slots, pl, s);
             }
             {
                 ProfScope ps(ARMOR_PROF_SPARSE, s, true);

@@ -13,21 +13,38 @@ struct Dims {
     int nblocks;  // nbi * nbj
 };
 
+// The wrapper-sized operands of the d_block 128 streamed chains cut into three bf16 pieces each
+// (chain_stream.hip; all NULL when that path's fp32 matrix instruction is compiled in): A^i and B^j in both
+// orientations, K^j = B^j D^j B^jT and A^iT A^i (symmetric).  Each array holds 3 * 128 * 128 16-bit values per block.
+struct WrapperPlanes {
+    uint16_t *A, *AT, *B, *BT, *K, *AtA;
+};
+bool stream_uses_planes();
+int stream_wgs_per_cu(); // workgroups per CU the sequential-variant streamed kernels are built for
+// pieces of the nblk blocks of X [nblk][128][128]: P = of X[x][k] (k = column), PT = of X[k][x] (may be NULL);
+// up to three matrices per launch
+struct PlaneJob {
+    const float *X;
+    int nblk;
+    uint16_t *P, *PT;
+};
+void launch_make_planes(const PlaneJob *job, int njobs, hipStream_t s);
+
 // ---- fused per-block chains (chain.hip) -------------------------------------------------------
 // A-phase of Alg. 2: per block S = C B, R = Wbar - A S, partial grad_A, ||S D S^T||_F, block loss.
 void launch_phase_A(const Dims &d, const float *Wbar, const float *C, const float *A, const float *B,
                     const float *D, int nsplit, float *gpart, float *beta_part, float *loss_part,
-                    bool loss_only, float *stream_scratch, hipStream_t s);
+                    bool loss_only, float *stream_scratch, const WrapperPlanes *planes, hipStream_t s);
 // B-phase: S' = A C, R = Wbar - S' B, partial grad_B, ||S'^T S'||_F ||D^j||_F.
 void launch_phase_B(const Dims &d, const float *Wbar, const float *C, const float *A, const float *B,
                     const float *D, int nsplit, float *gpart, float *beta_part, float *Sp, float *stream_scratch,
-                    hipStream_t s);
+                    const WrapperPlanes *planes, hipStream_t s);
 // The same phases at d_block 128 with one operand streamed from global memory and two workgroups
 // per CU (chain_stream.hip); launch_phase_A / _B / _WS go there when given the scratch (A, B: one
 // b x b tile per workgroup) or S' (W' step).
 void launch_phase_A_stream(const Dims &d, const float *Wbar, const float *C, const float *A, const float *B,
                            const float *D, int nsplit, float *gpart, float *beta_part, float *loss_part,
-                           float *scratch, hipStream_t s);
+                           float *scratch, const WrapperPlanes *planes, hipStream_t s);
 void launch_phase_FB_stream(const Dims &d, const float *Wbar, float *C, const float *A, const float *B,
                             const float *D, const uint8_t *mask, int mask_group, float *mC, float *vC,
                             double lr, double b1, double b2, double eps, int64_t t, int nsplit, float *gApart,
@@ -36,12 +53,12 @@ void launch_phase_GS_stream(const Dims &d, const float *Wbar, const float *C, co
                             const float *D, float *Gout, float *loss_part, int grid_cap, hipStream_t s);
 void launch_phase_B_stream(const Dims &d, const float *Wbar, const float *C, const float *A, const float *B,
                            const float *D, int nsplit, float *gpart, float *beta_part, float *Sp, float *scratch,
-                           hipStream_t s);
+                           const WrapperPlanes *planes, hipStream_t s);
 // W' step of Alg. 2 alone (unstructured mode): C += (2/beta_W) (A^T ((Wbar - A C B) D) B^T) (.) M, beta_W
 // read from scalars[2].  grid_cap workgroups at most, each walking blocks w, w + grid, ...
 void launch_phase_W(const Dims &d, const float *Wbar, float *C, const float *A, const float *B, const float *D,
                     const uint8_t *mask, int mask_group, const float *fro2A, const float *fro2K, const float *Sp, int grid_cap,
-                    hipStream_t s);
+                    const WrapperPlanes *planes, hipStream_t s);
 // Per wrapper block: A^iT A^i, its diagonal ||A^i[:,p]||^2 and ||A^iT A^i||_F^2; K^j = B^j D^j B^jT, ||K^j||_F^2.
 void launch_wrapper_grams(const Dims &d, const float *A, const float *B, const float *D, float *colnorm2,
                           float *fro2A, float *AtA, float *K, float *fro2K, hipStream_t s);
@@ -49,10 +66,12 @@ void launch_wrapper_grams(const Dims &d, const float *A, const float *B, const f
 // Gout = -2 (G - (2/beta_W) (A^T A)(G (.) M) K), block loss after the continuous step to loss_part.
 void launch_phase_WS(const Dims &d, const float *Wbar, float *C, const float *A, const float *B, const float *D,
                      const float *AtA, const float *K, const uint8_t *mask, int mask_group, const float *fro2A,
-                     const float *fro2K, float *Gout, float *loss_part, const float *Sp, int grid_cap, hipStream_t s);
+                     const float *fro2K, float *Gout, float *loss_part, const float *Sp, int grid_cap,
+                     const WrapperPlanes *planes, hipStream_t s);
 void launch_phase_WS_stream(const Dims &d, const float *Wbar, float *C, const float *A, const float *B, const float *D,
                      const float *AtA, const float *K, const uint8_t *mask, int mask_group, const float *fro2A,
-                     const float *fro2K, float *Gout, float *loss_part, const float *Sp, int grid_cap, hipStream_t s);
+                     const float *fro2K, float *Gout, float *loss_part, const float *Sp, int grid_cap,
+                     const WrapperPlanes *planes, hipStream_t s);
 int chain_max_nsplit();
 // Joint-Adam forward/backward pass: gradients of A (gApart, nsplit chunks per row block), B (gBpart,
 // one partial per block, laid out [j][i]) and the Adam update of the core and its moments in place.

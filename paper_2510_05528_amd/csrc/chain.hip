@@ -904,7 +904,7 @@ void launch_eta_W_trace(const Dims &d, const float *fro2A, const float *fro2K, d
 
 void launch_phase_A(const Dims &d, const float *Wbar, const float *C, const float *A, const float *B,
                     const float *D, int nsplit, float *gpart, float *beta_part, float *loss_part,
-                    bool loss_only, float *stream_scratch, hipStream_t s) {
+                    bool loss_only, float *stream_scratch, const WrapperPlanes *planes, hipStream_t s) {
     if (loss_only) {
         ARMOR_DISPATCH_B(d.b, {
             dim3 grid(d.nbi * nsplit), block(Chain<BB>::NT);
@@ -914,7 +914,7 @@ void launch_phase_A(const Dims &d, const float *Wbar, const float *C, const floa
         return;
     }
     if (d.b == 128) { // two workgroups per CU
-        launch_phase_A_stream(d, Wbar, C, A, B, D, nsplit, gpart, beta_part, loss_part, stream_scratch, s);
+        launch_phase_A_stream(d, Wbar, C, A, B, D, nsplit, gpart, beta_part, loss_part, stream_scratch, planes, s);
         return;
     }
     ARMOR_DISPATCH_B_SMALL(d.b, {
@@ -926,9 +926,9 @@ void launch_phase_A(const Dims &d, const float *Wbar, const float *C, const floa
 
 void launch_phase_B(const Dims &d, const float *Wbar, const float *C, const float *A, const float *B,
                     const float *D, int nsplit, float *gpart, float *beta_part, float *Sp, float *stream_scratch,
-                    hipStream_t s) {
+                    const WrapperPlanes *planes, hipStream_t s) {
     if (d.b == 128) {
-        launch_phase_B_stream(d, Wbar, C, A, B, D, nsplit, gpart, beta_part, Sp, stream_scratch, s);
+        launch_phase_B_stream(d, Wbar, C, A, B, D, nsplit, gpart, beta_part, Sp, stream_scratch, planes, s);
         return;
     }
     ARMOR_DISPATCH_B_SMALL(d.b, {
@@ -940,10 +940,10 @@ void launch_phase_B(const Dims &d, const float *Wbar, const float *C, const floa
 
 void launch_phase_W(const Dims &d, const float *Wbar, float *C, const float *A, const float *B, const float *D,
                     const uint8_t *mask, int mask_group, const float *fro2A, const float *fro2K, const float *Sp,
-                    int grid_cap, hipStream_t s) {
+                    int grid_cap, const WrapperPlanes *planes, hipStream_t s) {
     if (d.b == 128) { // the streamed W' kernel, stopping after the W' step; S' comes from the B step
         launch_phase_WS_stream(d, Wbar, C, A, B, D, nullptr, nullptr, mask, mask_group, fro2A, fro2K, nullptr, nullptr, Sp,
-                               2 * grid_cap, s);
+                               stream_wgs_per_cu() * grid_cap, planes, s);
         return;
     }
     ARMOR_DISPATCH_B_SMALL(d.b, {
@@ -994,10 +994,11 @@ void launch_phase_GS(const Dims &d, const float *Wbar, const float *C, const flo
 
 void launch_phase_WS(const Dims &d, const float *Wbar, float *C, const float *A, const float *B, const float *D,
                      const float *AtA, const float *K, const uint8_t *mask, int mask_group, const float *fro2A,
-                     const float *fro2K, float *Gout, float *loss_part, const float *Sp, int grid_cap, hipStream_t s) {
+                     const float *fro2K, float *Gout, float *loss_part, const float *Sp, int grid_cap,
+                     const WrapperPlanes *planes, hipStream_t s) {
     if (d.b == 128) {
         launch_phase_WS_stream(d, Wbar, C, A, B, D, AtA, K, mask, mask_group, fro2A, fro2K, Gout, loss_part, Sp,
-                               2 * grid_cap, s);
+                               stream_wgs_per_cu() * grid_cap, planes, s);
         return;
     }
     ARMOR_DISPATCH_B_SMALL(d.b, {

@@ -29,6 +29,51 @@ constexpr int SB = 128;
 using CS = Chain<SB, CfgStream>;
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
+// Matrix instruction of the products.  0: v_mfma_f32_32x32x2_f32 on the fp32 operands.  1: every fp32
+// operand value is cut EXACTLY into three bf16 pieces (x = x1 + x2 + x3: the top 8 significant bits,
+// the next 8, the last 8, by truncation) and a product x y is formed as the six partial products
+// x1 y1 + x1 y2 + x2 y1 + x1 y3 + x2 y2 + x3 y1 on v_mfma_f32_32x32x16_bf16 (fp32 accumulation); the
+// three dropped ones are below 2^-23 |x y|, the size of one fp32 rounding.  Sixteen inner indices
+// then cost six 8-pass instructions instead of eight 16-pass ones.
+#ifndef ARMOR_STREAM_BF16X3
+#define ARMOR_STREAM_BF16X3 1
+#endif
+constexpr bool SPLIT_BF16 = ARMOR_STREAM_BF16X3 != 0;
+// Workgroups per CU, and how far ahead (in groups of 8 inner indices) a product on the bf16 instruction
+// requests its global operands: pre-cut wrapper pieces are used as they arrive (one pair of groups ahead);
+// block data is cut one pair before it is used, so it is requested two pairs ahead.  (One workgroup per CU
+// with all 512 registers and requests three to four pairs ahead measured 8 % slower: the second workgroup's
+// products cover this one's epilogues.)
+constexpr int SEQ_WGS = 2;
+constexpr int SPLIT_DEPTH_PIECES = 2, SPLIT_DEPTH_DATA = 4;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
+
+// Eight floats (the inner indices one lane supplies to a 16-deep matrix instruction) as three vectors
+// of eight bf16: pieces 1, 2, 3 of the exact three-way cut.
+struct Pieces {
+    uint32_t p1[4], p2[4], p3[4];
+};
+__device__ __forceinline__ uintx4 vec4(const uint32_t (&a)[4]) {
+    uintx4 v = {a[0], a[1], a[2], a[3]};
+    return v;
+}
+__device__ __forceinline__ void cut3(const float (&x)[8], Pieces &o) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const uint32_t ua = __float_as_uint(x[2 * e]), ub = __float_as_uint(x[2 * e + 1]);
+        o.p1[e] = __builtin_amdgcn_perm(ub, ua, 0x07060302u); // the two upper halves
+        const float ra = x[2 * e] - __uint_as_float(ua & 0xffff0000u), rb = x[2 * e + 1] - __uint_as_float(ub & 0xffff0000u);
+        const uint32_t va = __float_as_uint(ra), vb = __float_as_uint(rb);
+        o.p2[e] = __builtin_amdgcn_perm(vb, va, 0x07060302u);
+        const float sa = ra - __uint_as_float(va & 0xffff0000u), sb = rb - __uint_as_float(vb & 0xffff0000u);
+        o.p3[e] = __builtin_amdgcn_perm(__float_as_uint(sb), __float_as_uint(sa), 0x07060302u); // at most 8 bits left: exact
+    }
+}
+__device__ __forceinline__ floatx16 mfma_bf16(const uintx4 &a, const uintx4 &b, const floatx16 &c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
 struct SmemStream {
     float X[CS::TILE_FLOATS];
     float red[16];
@@ -43,8 +88,12 @@ enum class Src {
     GX, // global memory, x contiguous: g[k * ld + x]
     LK, // LDS tile of pitch P, k contiguous: T[x * P + k]
     LX, // LDS tile of pitch P, x contiguous: T[k * P + x]
+    GP, // global memory, a wrapper-sized matrix already cut into its three bf16 pieces (make_planes_kernel),
+        // stored in the order the lanes ask for it: P[piece][run of 16 inner indices][lane half h][x][8], 16-bit
+        // elements, the eight being k = 16 run + 4 h + i and 16 run + 8 + 4 h + i (i = 0..3): what lane (x, h)
+        // supplies for that run.  One load instruction of a wave then reads two contiguous 512-byte stretches.
 };
-constexpr bool is_global(Src s) { return s == Src::GK || s == Src::GX; }
+constexpr bool is_global(Src s) { return s == Src::GK || s == Src::GX || s == Src::GP; }
 
 constexpr int NGROUP = SB / 8;
 
@@ -56,15 +105,30 @@ template <Src S> struct Operand {
     uint32_t tile; // the same kind of offset from tile 0 to tile 1
     uint32_t ld4;  // bytes per k step (GX)
     float f[NGROUP][4][2];
+    uintx4 pc[NGROUP / 2][3][2]; // GP: pieces of a pair of groups, [pair][piece][tile]
 
     __device__ __forceinline__ Operand(const float *b, int ld, int x0, int kh) : base(b) {
         if constexpr (S == Src::GK) { lane = opaque_u(4u * (uint32_t)(x0 * ld + 4 * kh)); tile = 4u * 32u * (uint32_t)ld; ld4 = 0; }
         if constexpr (S == Src::GX) { lane = opaque_u(4u * (uint32_t)(4 * kh * ld + x0)); tile = 4u * 32u; ld4 = 4u * (uint32_t)ld; }
         if constexpr (S == Src::LK) { lane = opaque_u((uint32_t)(x0 * CS::P + 4 * kh)); tile = 32u * CS::P; ld4 = 0; }
         if constexpr (S == Src::LX) { lane = opaque_u((uint32_t)(4 * kh * CS::P + x0)); tile = 32u; ld4 = 0; }
+        if constexpr (S == Src::GP) { lane = opaque_u(16u * (uint32_t)(kh * SB + x0)); tile = 16u * 32u; ld4 = 0; }
     }
     // a quarter of group q's requests (part 0..3), or all of them (part < 0)
     __device__ __forceinline__ void request(int q, int part = -1) {
+        if constexpr (S == Src::GP) { // one 16-byte load per piece and tile for the pair of groups (q, q + 1), q even
+            if (q % 2 == 0) {
+#pragma unroll
+                for (int pi = 0; pi < 3; ++pi)
+#pragma unroll
+                    for (int t = 0; t < 2; ++t) {
+                        if (part >= 0 && part != pi) continue;
+                        pc[q / 2][pi][t] = gld(reinterpret_cast<const uintx4 *>(base),
+                                               lane + t * tile + (uint32_t)pi * (2u * SB * SB) + (32u * SB) * (uint32_t)(q / 2));
+                    }
+            }
+            return;
+        }
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
             if constexpr (S == Src::GK) {
@@ -109,14 +173,128 @@ template <Src LS, Src RS> struct Product {
         : l(L, ldl, p.wm0 + p.l32, p.kh), r(R, ldr, p.wn0 + p.l32, p.kh) {}
     // the global operands' first DEPTH groups
     __device__ __forceinline__ void begin() {
+        if constexpr (SPLIT_BF16) {
+#pragma unroll
+            for (int q = 0; q < NGROUP; ++q) {
+                if (is_global(LS) && q < depth_of(LS)) l.request(q);
+                if (is_global(RS) && q < depth_of(RS)) r.request(q);
+            }
+            return;
+        }
 #pragma unroll
         for (int q = 0; q < DEPTH; ++q) {
             if constexpr (is_global(LS)) l.request(q);
             if constexpr (is_global(RS)) r.request(q);
         }
     }
+    // The same product on the bf16 matrix instruction (see SPLIT_BF16), two groups (16 inner indices) per trip,
+    // six rounds of four matrix instructions each (one per 32 x 32 tile of the wave's patch).  Cutting is plain
+    // vector arithmetic, about four instructions per matrix instruction, and the matrix pipe is a separate
+    // unit: the pieces of pair q + 1 are cut in rounds 2..5 of pair q, one instruction group between two
+    // matrix instructions, so both units stay busy from one wave.  Block data from global memory is therefore
+    // requested two pairs ahead (it is cut one pair ahead), pre-cut wrapper pieces one pair ahead, LDS operands
+    // in rounds 0..1 of the pair before.
+    static constexpr int depth_of(Src s) { return s == Src::GP ? SPLIT_DEPTH_PIECES : SPLIT_DEPTH_DATA; }
+    static __device__ __forceinline__ void cut_pair(float a, float b, bool neg, uint32_t &o1, uint32_t &o2, uint32_t &o3) {
+        if (neg) { a = -a; b = -b; }
+        const uint32_t ua = __float_as_uint(a), ub = __float_as_uint(b);
+        o1 = __builtin_amdgcn_perm(ub, ua, 0x07060302u);
+        const float ra = a - __uint_as_float(ua & 0xffff0000u), rb = b - __uint_as_float(ub & 0xffff0000u);
+        const uint32_t va = __float_as_uint(ra), vb = __float_as_uint(rb);
+        o2 = __builtin_amdgcn_perm(vb, va, 0x07060302u);
+        const float sa = ra - __uint_as_float(va & 0xffff0000u), sb = rb - __uint_as_float(vb & 0xffff0000u);
+        o3 = __builtin_amdgcn_perm(__float_as_uint(sb), __float_as_uint(sa), 0x07060302u);
+    }
+    template <bool ZERO, bool NEGR, int TAIL_BACK, class Tail>
+    __device__ __forceinline__ void run_split(CS::Acc &acc, Tail &&tail) {
+        static_assert(NGROUP % 2 == 0, "groups are taken in pairs");
+        static_assert(!(LS == Src::GP && RS == Src::GP), "one operand of a product is block data");
+        constexpr bool CUT_L = LS != Src::GP, CUT_R = RS != Src::GP;
+        constexpr bool NEG_L = NEGR && !CUT_R, NEG_R = NEGR && CUT_R; // a negated product negates a cut operand
+        constexpr int DL = depth_of(LS), DR = depth_of(RS);
+        constexpr int UNITS = (CUT_L ? 8 : 0) + (CUT_R ? 8 : 0), PER_ROUND = UNITS / 4; // (tile, element pair) units
+        Pieces cl[2][2], cr[2][2]; // cut pieces, [pair parity][tile]
+        // unit u of the pieces of pair q (groups q, q + 1)
+        auto cut_unit = [&](int q, int u) {
+            const int buf = (q / 2) & 1;
+            if (CUT_L && u < 8) {
+                const int t = u >> 2, e = u & 3;
+                cut_pair(l.f[q + (2 * e) / 4][(2 * e) % 4][t], l.f[q + (2 * e + 1) / 4][(2 * e + 1) % 4][t], NEG_L,
+                         cl[buf][t].p1[e], cl[buf][t].p2[e], cl[buf][t].p3[e]);
+            } else {
+                const int v = CUT_L ? u - 8 : u, t = v >> 2, e = v & 3;
+                cut_pair(r.f[q + (2 * e) / 4][(2 * e) % 4][t], r.f[q + (2 * e + 1) / 4][(2 * e + 1) % 4][t], NEG_R,
+                         cr[buf][t].p1[e], cr[buf][t].p2[e], cr[buf][t].p3[e]);
+            }
+        };
+        if constexpr (!is_global(LS)) { l.request(0); l.request(1); }
+        if constexpr (!is_global(RS)) { r.request(0); r.request(1); }
+#pragma unroll
+        for (int u = 0; u < UNITS; ++u) cut_unit(0, u);
+#pragma unroll
+        for (int q = 0; q < NGROUP; q += 2) {
+            const int buf = (q / 2) & 1;
+            constexpr int NC = 6;
+#pragma unroll
+            for (int c = 0; c < NC; ++c) {
+                // requests of later pairs, spread over the rounds
+                if (c < 4) {
+#pragma unroll
+                    for (int g = 0; g < 2; ++g) {
+                        if (is_global(LS) && q + g + DL < NGROUP) l.request(q + g + DL, c);
+                        if (is_global(RS) && q + g + DR < NGROUP) r.request(q + g + DR, c);
+                    }
+                }
+                if (c < 2 && q + 2 < NGROUP) { // LDS operands of the next pair: half of each group per round
+#pragma unroll
+                    for (int g = 0; g < 2; ++g)
+#pragma unroll
+                        for (int part = 2 * c; part < 2 * c + 2; ++part) {
+                            if constexpr (!is_global(LS)) l.request(q + g + 2, part);
+                            if constexpr (!is_global(RS)) r.request(q + g + 2, part);
+                        }
+                }
+                if (c == NC - 1 && q <= NGROUP - 1 - TAIL_BACK && q + 2 > NGROUP - 1 - TAIL_BACK) tail();
+                // the next pair's pieces
+                if (c >= 2 && q + 2 < NGROUP) {
+#pragma unroll
+                    for (int u = (c - 2) * PER_ROUND; u < (c - 1) * PER_ROUND; ++u) cut_unit(q + 2, u);
+                }
+#pragma unroll
+                for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+                    for (int tn = 0; tn < 2; ++tn) {
+                        // small partial products first: (3,1) (1,3) (2,2) (2,1) (1,2) (1,1)
+                        uintx4 a, b;
+                        if constexpr (CUT_L) a = c == 0 ? vec4(cl[buf][tm].p3) : (c == 2 || c == 3) ? vec4(cl[buf][tm].p2) : vec4(cl[buf][tm].p1);
+                        else a = l.pc[q / 2][c == 0 ? 2 : (c == 2 || c == 3) ? 1 : 0][tm];
+                        if constexpr (CUT_R) b = c == 1 ? vec4(cr[buf][tn].p3) : (c == 2 || c == 4) ? vec4(cr[buf][tn].p2) : vec4(cr[buf][tn].p1);
+                        else b = r.pc[q / 2][c == 1 ? 2 : (c == 2 || c == 4) ? 1 : 0][tn];
+                        if (ZERO && q == 0 && c == 0) {
+                            const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                            acc.v[tm][tn] = mfma_bf16(a, b, zero);
+                        } else {
+                            acc.v[tm][tn] = mfma_bf16(a, b, acc.v[tm][tn]);
+                        }
+                    }
+                // issue order inside the round: a matrix instruction, then a share of the vector and memory
+                // instructions, four times
+#pragma unroll
+                for (int m = 0; m < 4; ++m) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                         // one matrix instruction
+                    __builtin_amdgcn_sched_group_barrier(0x002, (11 * PER_ROUND + 3) / 4, 0);  // vector arithmetic
+                    __builtin_amdgcn_sched_group_barrier(0x120, 4, 0);                         // memory / LDS reads
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    }
     template <bool ZERO, bool NEGR = false, int TAIL_BACK = STREAM_DEPTH, class Tail = NoTail>
     __device__ __forceinline__ void run(CS::Acc &acc, Tail &&tail = Tail()) {
+        if constexpr (SPLIT_BF16) {
+            run_split<ZERO, NEGR, TAIL_BACK>(acc, tail);
+            return;
+        }
         if constexpr (!is_global(LS)) l.request(0);
         if constexpr (!is_global(RS)) r.request(0);
 #pragma unroll
@@ -167,6 +345,61 @@ __device__ __forceinline__ void mma_stream(CS::Acc &acc, const float *L, int ldl
 // sum where it is used, after later products, and keeps every addend in a register until then.
 __device__ __forceinline__ void settle(float &v) { asm volatile("" : "+v"(v)); }
 
+// A wrapper-sized operand (A^i, B^j, K^j, A^iT A^i: shared by a whole row or column of blocks) is cut into
+// its bf16 pieces once per iteration by make_planes_kernel and streamed as pieces; block data is cut where
+// it is used.  With the fp32 matrix instruction the same operand is streamed as fp32.
+template <Src FP32_FORM> constexpr Src wrapper_src() { return SPLIT_BF16 ? Src::GP : FP32_FORM; }
+__device__ __forceinline__ const float *wrapper_ptr(const float *fp32, const uint16_t *planes, int blk) {
+    if constexpr (SPLIT_BF16) return reinterpret_cast<const float *>(planes + (int64_t)blk * 3 * SB * SB);
+    else return fp32 + (int64_t)blk * SB * SB;
+}
+
+// X [nblk][128][128] fp32 -> P = pieces of op(x, k) = X[x][k] (k = column: stands in for the GK form) and
+// PT = pieces of op(x, k) = X[k][x] (k = row: the GX form; optional), both in the GP layout.
+// Workgroup (blk, 32 values of x); thread -> (x, run of 16 inner indices), x fastest so stores are contiguous.
+// Up to three matrices per launch (blockIdx.x runs over all their blocks).
+struct PlaneJobs {
+    const float *X[3];
+    uint16_t *P[3], *PT[3];
+    int first[4]; // first[j] .. first[j + 1]: the blocks of job j
+};
+__global__ __launch_bounds__(256) void make_planes_kernel(PlaneJobs jobs) {
+    const int tid = threadIdx.x;
+    const int job = (int)blockIdx.x >= jobs.first[2] ? 2 : ((int)blockIdx.x >= jobs.first[1] ? 1 : 0);
+    const int blk = blockIdx.x - jobs.first[job];
+    const float *__restrict__ X = jobs.X[job];
+    uint16_t *__restrict__ P = jobs.P[job], *__restrict__ PT = jobs.PT[job];
+    const int x = 32 * blockIdx.y + (tid & 31), run = tid >> 5;
+    const float *Xb = X + (int64_t)blk * SB * SB;
+    auto emit = [&](uint16_t *out, const float (&v)[16]) {
+        float h0[8], h1[8]; // what lane half 0 / 1 supplies: k 0..3, 8..11 / 4..7, 12..15 of the run
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { h0[e] = v[e]; h0[4 + e] = v[8 + e]; h1[e] = v[4 + e]; h1[4 + e] = v[12 + e]; }
+        Pieces a, b;
+        cut3(h0, a);
+        cut3(h1, b);
+        uint16_t *o = out + (int64_t)blk * 3 * SB * SB + ((run * 2) * SB + x) * 8;
+        *reinterpret_cast<uintx4 *>(o) = vec4(a.p1);
+        *reinterpret_cast<uintx4 *>(o + SB * 8) = vec4(b.p1);
+        *reinterpret_cast<uintx4 *>(o + SB * SB) = vec4(a.p2);
+        *reinterpret_cast<uintx4 *>(o + SB * SB + SB * 8) = vec4(b.p2);
+        *reinterpret_cast<uintx4 *>(o + 2 * SB * SB) = vec4(a.p3);
+        *reinterpret_cast<uintx4 *>(o + 2 * SB * SB + SB * 8) = vec4(b.p3);
+    };
+    float v[16];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const floatx4 q = *reinterpret_cast<const floatx4 *>(Xb + x * SB + 16 * run + 4 * e);
+        v[4 * e] = q[0]; v[4 * e + 1] = q[1]; v[4 * e + 2] = q[2]; v[4 * e + 3] = q[3];
+    }
+    emit(P, v);
+    if (PT != nullptr) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) v[e] = Xb[(16 * run + e) * SB + x];
+        emit(PT, v);
+    }
+}
+
 // ------------------------------------------------------------------------------------------------
 // W' step fused with the core gradient at the updated core (see phase_WS_kernel in chain.hip for the
 // identities).  Per block, with S' = A C handed over by the B step:
@@ -179,12 +412,13 @@ __device__ __forceinline__ void settle(float &v) { asm volatile("" : "+v"(v)); }
 // FUSED = false stops after the W' step itself (unstructured mode, where no sparse-core step follows).
 // ------------------------------------------------------------------------------------------------
 template <bool FUSED>
-__global__ __launch_bounds__(CS::NT, 2) void phase_WS_stream_kernel(
+__global__ __launch_bounds__(CS::NT, SEQ_WGS) void phase_WS_stream_kernel(
     const float *__restrict__ Wbar, float *__restrict__ C, const float *__restrict__ A,
     const float *__restrict__ Bw, const float *__restrict__ D, const float *__restrict__ AtA,
     const float *__restrict__ K, const uint8_t *__restrict__ mask, int mask_group,
     const float *__restrict__ fro2A, int nA, const float *__restrict__ fro2K, int nK, int64_t d_in, int nbj,
-    int nblocks, float *__restrict__ Gout, float *__restrict__ loss_part, const float *__restrict__ Sp) {
+    int nblocks, float *__restrict__ Gout, float *__restrict__ loss_part, const float *__restrict__ Sp,
+    WrapperPlanes pl) {
     constexpr int B = SB;
     __shared__ SmemStream sm;
     const int tid = threadIdx.x;
@@ -224,10 +458,9 @@ __global__ __launch_bounds__(CS::NT, 2) void phase_WS_stream_kernel(
         const int i = blk / nbj, j = blk % nbj;
         float *Cij = C + (int64_t)i * B * d_in + (int64_t)j * B;
         const float *Sij = Sp + (int64_t)i * B * d_in + (int64_t)j * B;
-        const float *Ai = A + (int64_t)i * B * B, *Bj = Bw + (int64_t)j * B * B;
         const float *Dj = D + (int64_t)j * B;
         float lsum = 0.f;
-        mma_stream<Src::GK, Src::GX, false, true>(accw, Sij, ldw, Bj, B, p); // R = Wbar - S' B
+        mma_stream<Src::GK, wrapper_src<Src::GX>(), false, true>(accw, Sij, ldw, wrapper_ptr(Bw, pl.BT, j), B, p); // R = Wbar - S' B
 #pragma unroll
         for (int tn = 0; tn < 2; ++tn) {
             const float dj = Dj[p.col(tn)];
@@ -246,13 +479,13 @@ __global__ __launch_bounds__(CS::NT, 2) void phase_WS_stream_kernel(
         for (int it = 0; it < 4; ++it)
             if (it * 16 < nb) *reinterpret_cast<uint2 *>(reinterpret_cast<char *>(sm.M) + mhalf + 8u * it) = mreg[it];
         __syncthreads();
-        mma_stream<Src::LK, Src::GK, true>(acc, sm.X, 0, Bj, B, p); // U = (R D) B^T
+        mma_stream<Src::LK, wrapper_src<Src::GK>(), true>(acc, sm.X, 0, wrapper_ptr(Bw, pl.B, j), B, p); // U = (R D) B^T
         __syncthreads();
         CS::store_acc(sm.X, acc, p);
         __syncthreads();
         // current core values in the accumulator layout, requested behind the product's last operands
         float cv[2][2][16];
-        mma_stream<Src::GX, Src::LX, true, false, STREAM_DEPTH>(acc, Ai, B, sm.X, 0, p, [&]() { // G = A^T U   (stays in acc)
+        mma_stream<wrapper_src<Src::GX>(), Src::LX, true, false, STREAM_DEPTH>(acc, wrapper_ptr(A, pl.AT, i), B, sm.X, 0, p, [&]() { // G = A^T U   (stays in acc)
             const uint32_t lb = opaque_u(wboff);
 #pragma unroll
             for (int tm = 0; tm < 2; ++tm)
@@ -300,11 +533,11 @@ __global__ __launch_bounds__(CS::NT, 2) void phase_WS_stream_kernel(
         }
         settle(dd);
         __syncthreads();
-        mma_stream<Src::LK, Src::GX, true>(acc2, sm.X, 0, K + (int64_t)j * B * B, B, p); // V = Delta K
+        mma_stream<Src::LK, wrapper_src<Src::GX>(), true>(acc2, sm.X, 0, wrapper_ptr(K, pl.K, j), B, p); // V = Delta K
         __syncthreads();
         CS::store_acc(sm.X, acc2, p);
         __syncthreads();
-        mma_stream<Src::GK, Src::LX, true>(acc2, AtA + (int64_t)i * B * B, B, sm.X, 0, p); // Z = (A^T A) V
+        mma_stream<wrapper_src<Src::GK>(), Src::LX, true>(acc2, wrapper_ptr(AtA, pl.AtA, i), B, sm.X, 0, p); // Z = (A^T A) V
         request_block(min(blk + (int)gridDim.x, nblocks - 1)); // (the last block asks for itself again: harmless)
         float dz = 0.f;
         {
@@ -374,7 +607,35 @@ template <bool XT> __device__ __forceinline__ float sym_frob2_stream(const float
     floatx16 t0, t1, t2;
 #pragma unroll
     for (int r = 0; r < 16; ++r) { t0[r] = 0.f; t1[r] = 0.f; t2[r] = 0.f; }
-    if (three) {
+    if constexpr (SPLIT_BF16) {
+        // 16 inner indices per trip: lane half h supplies indices 16 kb + 8 h .. + 7 of every operand
+        auto frag = [&](const float *o, int kb, Pieces &pc) {
+            float v[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = o[(16 * kb + 7 * p.kh + e) * ks]; // o already points at index h
+            cut3(v, pc);
+        };
+        auto six = [&](floatx16 &t, const Pieces &a, const Pieces &b) {
+            t = mfma_bf16(vec4(a.p3), vec4(b.p1), t);
+            t = mfma_bf16(vec4(a.p1), vec4(b.p3), t);
+            t = mfma_bf16(vec4(a.p2), vec4(b.p2), t);
+            t = mfma_bf16(vec4(a.p2), vec4(b.p1), t);
+            t = mfma_bf16(vec4(a.p1), vec4(b.p2), t);
+            t = mfma_bf16(vec4(a.p1), vec4(b.p1), t);
+        };
+#pragma unroll 2
+        for (int kb = 0; kb < SB / 16; ++kb) {
+            Pieces pa0, pb0, pa1, pb1;
+            frag(a0, kb, pa0); frag(b0, kb, pb0); frag(a1, kb, pa1); frag(b1, kb, pb1);
+            six(t0, pa0, pb0);
+            six(t1, pa1, pb1);
+            if (three) {
+                Pieces pa2, pb2;
+                frag(a2, kb, pa2); frag(b2, kb, pb2);
+                six(t2, pa2, pb2);
+            }
+        }
+    } else if (three) {
 #pragma unroll 8
         for (int k = 0; k < SB; k += 2) {
             t0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[k * ks], b0[k * ks], t0, 0, 0, 0);
@@ -407,11 +668,11 @@ struct SmemGrad {
 //                                    (it stays in L2) and comes back as the streamed operand
 //   || (S sqrt D)(S sqrt D)^T ||_F   both operands resident
 // ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(CS::NT, 2) void phase_A_stream_kernel(
+__global__ __launch_bounds__(CS::NT, SEQ_WGS) void phase_A_stream_kernel(
     const float *__restrict__ Wbar, const float *__restrict__ C, const float *__restrict__ A,
     const float *__restrict__ Bw, const float *__restrict__ D, int64_t d_in, int nbj, int nsplit,
     float *__restrict__ gpart, float *__restrict__ beta_part, float *__restrict__ loss_part,
-    float *__restrict__ scratch) {
+    float *__restrict__ scratch, WrapperPlanes pl) {
     constexpr int B = SB;
     __shared__ SmemGrad sm;
     const int tid = threadIdx.x;
@@ -422,7 +683,7 @@ __global__ __launch_bounds__(CS::NT, 2) void phase_A_stream_kernel(
     const int chunk = (nbj + nsplit - 1) / nsplit;
     const int j0 = c * chunk, j1 = min(nbj, j0 + chunk);
     float *sc = scratch + (int64_t)blockIdx.x * B * B;
-    const float *Ai = A + (int64_t)i * B * B;
+    const float *Ai = wrapper_ptr(A, pl.A, i);
     CS::Acc gacc, acc, accw;
     gacc.zero();
     float *gp = gpart + (int64_t)blockIdx.x * B * B;
@@ -430,7 +691,7 @@ __global__ __launch_bounds__(CS::NT, 2) void phase_A_stream_kernel(
     for (int j = j0; j < j1; ++j) {
         const float *Cij = C + (int64_t)i * B * d_in + (int64_t)j * B;
         const float *Wij = Wbar + (int64_t)i * B * d_in + (int64_t)j * B;
-        const float *Bj = Bw + (int64_t)j * B * B;
+        const float *Bj = wrapper_ptr(Bw, pl.BT, j);
         const bool first = j == j0;
         auto reqW = [&]() {
             const uint32_t lb = opaque_u(wboff);
@@ -441,7 +702,7 @@ __global__ __launch_bounds__(CS::NT, 2) void phase_A_stream_kernel(
 #pragma unroll
                     for (int r = 0; r < 16; ++r) accw.v[tm][tn][r] = gld(Wij, lb + CS::Pos::unif_boff(tm, tn, r, ldw));
         };
-        mma_stream<Src::GK, Src::GX, true, false, STREAM_DEPTH>(acc, Cij, ldw, Bj, B, p, reqW); // S = C B; Wbar requested behind it
+        mma_stream<Src::GK, wrapper_src<Src::GX>(), true, false, STREAM_DEPTH>(acc, Cij, ldw, Bj, B, p, reqW); // S = C B; Wbar requested behind it
         float sq[2];
 #pragma unroll
         for (int tn = 0; tn < 2; ++tn) {
@@ -459,7 +720,7 @@ __global__ __launch_bounds__(CS::NT, 2) void phase_A_stream_kernel(
             for (int tm = 0; tm < 2; ++tm)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) accw.v[tm][tn][r] *= sq[tn];
-        mma_stream<Src::GK, Src::LX, false, true>(accw, Ai, B, sm.X, 0, p); // R sqrt(D)
+        mma_stream<wrapper_src<Src::GK>(), Src::LX, false, true>(accw, Ai, B, sm.X, 0, p); // R sqrt(D)
         float lsum = frob2(accw);
         settle(lsum);
         {
@@ -496,11 +757,11 @@ __global__ __launch_bounds__(CS::NT, 2) void phase_A_stream_kernel(
 //   gacc += S'^T (R D)           R D through the workgroup's global scratch
 //   || S'^T S' ||_F              both operands resident
 // ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(CS::NT, 2) void phase_B_stream_kernel(
+__global__ __launch_bounds__(CS::NT, SEQ_WGS) void phase_B_stream_kernel(
     const float *__restrict__ Wbar, const float *__restrict__ C, const float *__restrict__ A,
     const float *__restrict__ Bw, const float *__restrict__ D, int64_t d_in, int nbi, int nbj, int nsplit,
     float *__restrict__ gpart, float *__restrict__ beta_part, float *__restrict__ Sp,
-    float *__restrict__ scratch) {
+    float *__restrict__ scratch, WrapperPlanes pl) {
     constexpr int B = SB;
     __shared__ SmemGrad sm;
     const int tid = threadIdx.x;
@@ -511,7 +772,7 @@ __global__ __launch_bounds__(CS::NT, 2) void phase_B_stream_kernel(
     const int chunk = (nbi + nsplit - 1) / nsplit;
     const int i0 = c * chunk, i1 = min(nbi, i0 + chunk);
     float *sc = scratch + (int64_t)blockIdx.x * B * B;
-    const float *Bj = Bw + (int64_t)j * B * B, *Dj = D + (int64_t)j * B;
+    const float *Bj = wrapper_ptr(Bw, pl.BT, j), *Dj = D + (int64_t)j * B;
     float dj[2];
 #pragma unroll
     for (int tn = 0; tn < 2; ++tn) dj[tn] = Dj[p.col(tn)];
@@ -525,7 +786,7 @@ __global__ __launch_bounds__(CS::NT, 2) void phase_B_stream_kernel(
     for (int i = i0; i < i1; ++i) {
         const float *Cij = C + (int64_t)i * B * d_in + (int64_t)j * B;
         const float *Wij = Wbar + (int64_t)i * B * d_in + (int64_t)j * B;
-        const float *Ai = A + (int64_t)i * B * B;
+        const float *Ai = wrapper_ptr(A, pl.A, i);
         const bool first = i == i0;
         auto reqW = [&]() {
             const uint32_t lb = opaque_u(wboff);
@@ -536,10 +797,10 @@ __global__ __launch_bounds__(CS::NT, 2) void phase_B_stream_kernel(
 #pragma unroll
                     for (int r = 0; r < 16; ++r) accw.v[tm][tn][r] = gld(Wij, lb + CS::Pos::unif_boff(tm, tn, r, ldw));
         };
-        mma_stream<Src::GK, Src::GX, true, false, STREAM_DEPTH>(acc, Ai, B, Cij, ldw, p, reqW); // S' = A C; Wbar requested behind it
+        mma_stream<wrapper_src<Src::GK>(), Src::GX, true, false, STREAM_DEPTH>(acc, Ai, B, Cij, ldw, p, reqW); // S' = A C; Wbar requested behind it
         CS::store_acc(sm.X, acc, p); // (the previous block is done with X: barriers at its end)
         __syncthreads();
-        mma_stream<Src::LK, Src::GX, false, true>(accw, sm.X, 0, Bj, B, p); // R = Wbar - S' B
+        mma_stream<Src::LK, wrapper_src<Src::GX>(), false, true>(accw, sm.X, 0, Bj, B, p); // R = Wbar - S' B
         {
             const uint32_t lb = opaque_u(gb);
 #pragma unroll
@@ -812,33 +1073,52 @@ using namespace stream;
 
 void launch_phase_A_stream(const Dims &d, const float *Wbar, const float *C, const float *A, const float *B,
                            const float *D, int nsplit, float *gpart, float *beta_part, float *loss_part,
-                           float *scratch, hipStream_t s) {
+                           float *scratch, const WrapperPlanes *planes, hipStream_t s) {
     dim3 grid(d.nbi * nsplit), block(CS::NT);
     hipLaunchKernelGGL(phase_A_stream_kernel, grid, block, 0, s, Wbar, C, A, B, D, d.d_in, d.nbj, nsplit, gpart,
-                       beta_part, loss_part, scratch);
+                       beta_part, loss_part, scratch, planes ? *planes : WrapperPlanes{});
+}
+
+bool stream_uses_planes() { return SPLIT_BF16; }
+int stream_wgs_per_cu() { return SEQ_WGS; }
+
+void launch_make_planes(const PlaneJob *job, int njobs, hipStream_t s) {
+    PlaneJobs jobs = {};
+    int total = 0;
+    for (int j = 0; j < 3; ++j) {
+        jobs.first[j] = total;
+        if (j < njobs) {
+            jobs.X[j] = job[j].X; jobs.P[j] = job[j].P; jobs.PT[j] = job[j].PT;
+            total += job[j].nblk;
+        }
+    }
+    jobs.first[3] = total;
+    for (int j = njobs; j < 3; ++j) jobs.first[j] = total;
+    if (total > 0) hipLaunchKernelGGL(make_planes_kernel, dim3(total, SB / 32), dim3(256), 0, s, jobs);
 }
 
 void launch_phase_B_stream(const Dims &d, const float *Wbar, const float *C, const float *A, const float *B,
                            const float *D, int nsplit, float *gpart, float *beta_part, float *Sp, float *scratch,
-                           hipStream_t s) {
+                           const WrapperPlanes *planes, hipStream_t s) {
     dim3 grid(d.nbj * nsplit), block(CS::NT);
     hipLaunchKernelGGL(phase_B_stream_kernel, grid, block, 0, s, Wbar, C, A, B, D, d.d_in, d.nbi, d.nbj, nsplit, gpart,
-                       beta_part, Sp, scratch);
+                       beta_part, Sp, scratch, planes ? *planes : WrapperPlanes{});
 }
 
 void launch_phase_WS_stream(const Dims &d, const float *Wbar, float *C, const float *A, const float *B,
                             const float *D, const float *AtA, const float *K, const uint8_t *mask, int mask_group,
                             const float *fro2A, const float *fro2K, float *Gout, float *loss_part, const float *Sp,
-                            int grid_cap, hipStream_t s) {
+                            int grid_cap, const WrapperPlanes *planes, hipStream_t s) {
     dim3 grid(std::min(d.nblocks, grid_cap)), block(CS::NT);
+    const WrapperPlanes pl = planes ? *planes : WrapperPlanes{};
     if (Gout != nullptr)
         hipLaunchKernelGGL(phase_WS_stream_kernel<true>, grid, block, 0, s, Wbar, C, A, B, D, AtA, K, mask, mask_group,
                            fro2A, d.nbi * gram_parts(d.b), fro2K, d.nbj * gram_parts(d.b), d.d_in, d.nbj, d.nblocks,
-                           Gout, loss_part, Sp);
+                           Gout, loss_part, Sp, pl);
     else // the W' step alone
         hipLaunchKernelGGL(phase_WS_stream_kernel<false>, grid, block, 0, s, Wbar, C, A, B, D, AtA, K, mask, mask_group,
                            fro2A, d.nbi * gram_parts(d.b), fro2K, d.nbj * gram_parts(d.b), d.d_in, d.nbj, d.nblocks,
-                           Gout, loss_part, Sp);
+                           Gout, loss_part, Sp, pl);
 }
 
 void launch_phase_GS_stream(const Dims &d, const float *Wbar, const float *C, const float *A, const float *B,
