@@ -474,18 +474,24 @@ __global__ __launch_bounds__(CS::NT, SEQ_WGS) void phase_WS_stream_kernel(
                 }
         }
         settle(lsum);
+        // (a product's first wrapper pieces are asked for in front of the hand-over that precedes it: they travel
+        // underneath the LDS stores and the barrier)
+        Product<Src::LK, wrapper_src<Src::GK>()> prU(sm.X, 0, wrapper_ptr(Bw, pl.B, j), B, p);
+        prU.begin();
         CS::store_acc(sm.X, accw, p); // R D   (the previous block is done with X and M: barriers at its end)
 #pragma unroll
         for (int it = 0; it < 4; ++it)
             if (it * 16 < nb) *reinterpret_cast<uint2 *>(reinterpret_cast<char *>(sm.M) + mhalf + 8u * it) = mreg[it];
         __syncthreads();
-        mma_stream<Src::LK, wrapper_src<Src::GK>(), true>(acc, sm.X, 0, wrapper_ptr(Bw, pl.B, j), B, p); // U = (R D) B^T
+        prU.template run<true>(acc); // U = (R D) B^T
+        Product<wrapper_src<Src::GX>(), Src::LX> prG(wrapper_ptr(A, pl.AT, i), B, sm.X, 0, p);
+        prG.begin();
         __syncthreads();
         CS::store_acc(sm.X, acc, p);
         __syncthreads();
         // current core values in the accumulator layout, requested behind the product's last operands
         float cv[2][2][16];
-        mma_stream<wrapper_src<Src::GX>(), Src::LX, true, false, STREAM_DEPTH>(acc, wrapper_ptr(A, pl.AT, i), B, sm.X, 0, p, [&]() { // G = A^T U   (stays in acc)
+        prG.template run<true, false, STREAM_DEPTH>(acc, [&]() { // G = A^T U   (stays in acc)
             const uint32_t lb = opaque_u(wboff);
 #pragma unroll
             for (int tm = 0; tm < 2; ++tm)
@@ -532,12 +538,16 @@ __global__ __launch_bounds__(CS::NT, SEQ_WGS) void phase_WS_stream_kernel(
             continue;
         }
         settle(dd);
+        Product<Src::LK, wrapper_src<Src::GX>()> prV(sm.X, 0, wrapper_ptr(K, pl.K, j), B, p);
+        prV.begin();
         __syncthreads();
-        mma_stream<Src::LK, wrapper_src<Src::GX>(), true>(acc2, sm.X, 0, wrapper_ptr(K, pl.K, j), B, p); // V = Delta K
+        prV.template run<true>(acc2); // V = Delta K
+        Product<wrapper_src<Src::GK>(), Src::LX> prZ(wrapper_ptr(AtA, pl.AtA, i), B, sm.X, 0, p);
+        prZ.begin();
         __syncthreads();
         CS::store_acc(sm.X, acc2, p);
         __syncthreads();
-        mma_stream<wrapper_src<Src::GK>(), Src::LX, true>(acc2, wrapper_ptr(AtA, pl.AtA, i), B, sm.X, 0, p); // Z = (A^T A) V
+        prZ.template run<true>(acc2); // Z = (A^T A) V
         request_block(min(blk + (int)gridDim.x, nblocks - 1)); // (the last block asks for itself again: harmless)
         float dz = 0.f;
         {
@@ -588,32 +598,32 @@ __device__ __forceinline__ float frob2(const CS::Acc &acc) {
 
 // Squared Frobenius norm of the symmetric product X X^T (XT = false) or X^T X (XT = true) of the
 // resident tile, as this lane's share of the sum: only the 10 upper-triangular 32 x 32 tiles of the
-// 4 x 4 grid are formed, off-diagonal ones counted twice.  Two waves take three tiles and two take
-// two; `flip` swaps the two kinds (callers pass it for the second half of the grid, which is what
-// lands in the CUs' second slots), so that the two workgroups of a CU put their heavy waves on
-// different SIMDs.  Both operands come from LDS: no global request is outstanding behind this.
+// 4 x 4 grid are formed, off-diagonal ones counted twice.  Both operands of a tile are 32-row slices of
+// the same matrix, so a wave cuts each slice it needs once per 16 inner indices and uses it on either side:
+//   wave 0: slices 0, 1    -> tiles (0,0) (0,1) (1,1)        wave 2: slices 0, 2, 3 -> tiles (0,2) (0,3)
+//   wave 1: slices 2, 3    -> tiles (2,2) (2,3) (3,3)        wave 3: slices 1, 2, 3 -> tiles (1,2) (1,3)
+// (three tiles from two slices, or two tiles from three: 18 / 12 matrix instructions and 88 / 132 cutting
+// instructions per 16 inner indices).  `flip` swaps the two kinds (callers pass it for the second half of
+// the grid, which is what lands in the CUs' second slots), so that the two workgroups of a CU put their
+// heavy waves on different SIMDs.  Both operands come from LDS: no global request is outstanding behind
+// this.  The slices of the next 16 inner indices are read and cut underneath the current matrix instructions.
 template <bool XT> __device__ __forceinline__ float sym_frob2_stream(const float *X, const CS::Pos &p, int tid, bool flip) {
     const int w = (tid >> 6) ^ (flip ? 2 : 0);
-    // wave -> tiles (row tile, column tile): w0 (0,0)(0,1)(1,1), w1 (0,2)(0,3)(1,2), w2 (1,3)(2,3), w3 (2,2)(3,3)
-    const int r0 = w == 0 ? 0 : w == 1 ? 0 : w == 2 ? 1 : 2, c0 = w == 0 ? 0 : w == 1 ? 2 : w == 2 ? 3 : 2;
-    const int r1 = w == 0 ? 0 : w == 1 ? 0 : w == 2 ? 2 : 3, c1 = w == 0 ? 1 : w == 1 ? 3 : 3;
-    const int r2 = 1, c2 = w == 0 ? 1 : 2;
-    const bool three = w < 2;
-    const int xs = XT ? 1 : CS::P, ks = XT ? CS::P : 1; // strides of the tile index and of k
-    const float *base = X + p.l32 * xs + p.kh * ks;
-    const float *a0 = base + 32 * r0 * xs, *b0 = base + 32 * c0 * xs;
-    const float *a1 = base + 32 * r1 * xs, *b1 = base + 32 * c1 * xs;
-    const float *a2 = base + 32 * r2 * xs, *b2 = base + 32 * c2 * xs;
-    floatx16 t0, t1, t2;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) { t0[r] = 0.f; t1[r] = 0.f; t2[r] = 0.f; }
+    const int xs = XT ? 1 : CS::P, ks = XT ? CS::P : 1; // strides of the slice row index and of k
+    const float *base = X + p.l32 * xs;
     if constexpr (SPLIT_BF16) {
-        // 16 inner indices per trip: lane half h supplies indices 16 kb + 8 h .. + 7 of every operand
-        auto frag = [&](const float *o, int kb, Pieces &pc) {
-            float v[8];
+        const bool tri = w < 2;                       // triangle on two slices, or a row of two tiles on three
+        const int s0 = tri ? 2 * w : w - 2, s1 = tri ? 2 * w + 1 : 2, s2 = 3;
+        const float *sl[3] = {base + 32 * s0 * xs, base + 32 * s1 * xs, base + 32 * s2 * xs};
+        floatx16 t0, t1, t2;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) v[e] = o[(16 * kb + 7 * p.kh + e) * ks]; // o already points at index h
-            cut3(v, pc);
+        for (int r = 0; r < 16; ++r) { t0[r] = 0.f; t1[r] = 0.f; t2[r] = 0.f; }
+        float raw[2][3][8];
+        Pieces pc[2][3];
+        // lane half h supplies indices 16 kb + 8 h .. + 7 of every slice
+        auto read = [&](int kb, int g) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) raw[kb & 1][g][e] = sl[g][(16 * kb + 8 * p.kh + e) * ks];
         };
         auto six = [&](floatx16 &t, const Pieces &a, const Pieces &b) {
             t = mfma_bf16(vec4(a.p3), vec4(b.p1), t);
@@ -623,36 +633,83 @@ template <bool XT> __device__ __forceinline__ float sym_frob2_stream(const float
             t = mfma_bf16(vec4(a.p1), vec4(b.p2), t);
             t = mfma_bf16(vec4(a.p1), vec4(b.p1), t);
         };
-#pragma unroll 2
-        for (int kb = 0; kb < SB / 16; ++kb) {
-            Pieces pa0, pb0, pa1, pb1;
-            frag(a0, kb, pa0); frag(b0, kb, pb0); frag(a1, kb, pa1); frag(b1, kb, pb1);
-            six(t0, pa0, pb0);
-            six(t1, pa1, pb1);
-            if (three) {
-                Pieces pa2, pb2;
-                frag(a2, kb, pa2); frag(b2, kb, pb2);
-                six(t2, pa2, pb2);
+        if (tri) {
+            read(0, 0); read(0, 1);
+            cut3(raw[0][0], pc[0][0]); cut3(raw[0][1], pc[0][1]);
+            read(1, 0); read(1, 1);
+#pragma unroll
+            for (int kb = 0; kb < SB / 16; ++kb) {
+                const int cur = kb & 1, nxt = cur ^ 1;
+                if (kb + 1 < SB / 16) { cut3(raw[nxt][0], pc[nxt][0]); cut3(raw[nxt][1], pc[nxt][1]); }
+                if (kb + 2 < SB / 16) { read(kb + 2, 0); read(kb + 2, 1); }
+                six(t0, pc[cur][0], pc[cur][0]);
+                six(t1, pc[cur][0], pc[cur][1]);
+                six(t2, pc[cur][1], pc[cur][1]);
+#pragma unroll
+                for (int m = 0; m < 18; ++m) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        } else {
+            read(0, 0); read(0, 1); read(0, 2);
+            cut3(raw[0][0], pc[0][0]); cut3(raw[0][1], pc[0][1]); cut3(raw[0][2], pc[0][2]);
+            read(1, 0); read(1, 1); read(1, 2);
+#pragma unroll
+            for (int kb = 0; kb < SB / 16; ++kb) {
+                const int cur = kb & 1, nxt = cur ^ 1;
+                if (kb + 1 < SB / 16) { cut3(raw[nxt][0], pc[nxt][0]); cut3(raw[nxt][1], pc[nxt][1]); cut3(raw[nxt][2], pc[nxt][2]); }
+                if (kb + 2 < SB / 16) { read(kb + 2, 0); read(kb + 2, 1); read(kb + 2, 2); }
+                six(t0, pc[cur][0], pc[cur][1]);
+                six(t1, pc[cur][0], pc[cur][2]);
+#pragma unroll
+                for (int m = 0; m < 12; ++m) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, 11, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                }
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
-    } else if (three) {
-#pragma unroll 8
-        for (int k = 0; k < SB; k += 2) {
-            t0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[k * ks], b0[k * ks], t0, 0, 0, 0);
-            t1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[k * ks], b1[k * ks], t1, 0, 0, 0);
-            t2 = __builtin_amdgcn_mfma_f32_32x32x2f32(a2[k * ks], b2[k * ks], t2, 0, 0, 0);
-        }
-    } else {
-#pragma unroll 8
-        for (int k = 0; k < SB; k += 2) {
-            t0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[k * ks], b0[k * ks], t0, 0, 0, 0);
-            t1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[k * ks], b1[k * ks], t1, 0, 0, 0);
-        }
-    }
-    float s0 = 0.f, s1 = 0.f, s2 = 0.f;
+        float q0 = 0.f, q1 = 0.f, q2 = 0.f;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) { s0 += t0[r] * t0[r]; s1 += t1[r] * t1[r]; s2 += t2[r] * t2[r]; }
-    return (r0 == c0 ? s0 : 2.f * s0) + (r1 == c1 ? s1 : 2.f * s1) + (r2 == c2 ? s2 : 2.f * s2);
+        for (int r = 0; r < 16; ++r) { q0 += t0[r] * t0[r]; q1 += t1[r] * t1[r]; q2 += t2[r] * t2[r]; }
+        // triangle: two diagonal tiles and one off-diagonal; row: two off-diagonal tiles (t2 stays zero)
+        return tri ? q0 + 2.f * q1 + q2 : 2.f * (q0 + q1);
+    } else {
+        // wave -> tiles (row tile, column tile): w0 (0,0)(0,1)(1,1), w1 (0,2)(0,3)(1,2), w2 (1,3)(2,3), w3 (2,2)(3,3)
+        const int r0 = w == 0 ? 0 : w == 1 ? 0 : w == 2 ? 1 : 2, c0 = w == 0 ? 0 : w == 1 ? 2 : w == 2 ? 3 : 2;
+        const int r1 = w == 0 ? 0 : w == 1 ? 0 : w == 2 ? 2 : 3, c1 = w == 0 ? 1 : w == 1 ? 3 : 3;
+        const int r2 = 1, c2 = w == 0 ? 1 : 2;
+        const bool three = w < 2;
+        const float *bk = base + p.kh * ks;
+        const float *a0 = bk + 32 * r0 * xs, *b0 = bk + 32 * c0 * xs;
+        const float *a1 = bk + 32 * r1 * xs, *b1 = bk + 32 * c1 * xs;
+        const float *a2 = bk + 32 * r2 * xs, *b2 = bk + 32 * c2 * xs;
+        floatx16 t0, t1, t2;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { t0[r] = 0.f; t1[r] = 0.f; t2[r] = 0.f; }
+        if (three) {
+#pragma unroll 8
+            for (int k = 0; k < SB; k += 2) {
+                t0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[k * ks], b0[k * ks], t0, 0, 0, 0);
+                t1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[k * ks], b1[k * ks], t1, 0, 0, 0);
+                t2 = __builtin_amdgcn_mfma_f32_32x32x2f32(a2[k * ks], b2[k * ks], t2, 0, 0, 0);
+            }
+        } else {
+#pragma unroll 8
+            for (int k = 0; k < SB; k += 2) {
+                t0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[k * ks], b0[k * ks], t0, 0, 0, 0);
+                t1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[k * ks], b1[k * ks], t1, 0, 0, 0);
+            }
+        }
+        float s0 = 0.f, s1 = 0.f, s2 = 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { s0 += t0[r] * t0[r]; s1 += t1[r] * t1[r]; s2 += t2[r] * t2[r]; }
+        return (r0 == c0 ? s0 : 2.f * s0) + (r1 == c1 ? s1 : 2.f * s1) + (r2 == c2 ? s2 : 2.f * s2);
+    }
 }
 
 struct SmemGrad {
