@@ -4,7 +4,7 @@
 // global memory that is written and re-read by the same workgroup only and therefore stays in
 // L2; every sub-product streams its two operand sub-tiles through the two LDS tile slots.
 // At b = 256 each product has 64 flop/B of arithmetic intensity even unfused, so the extra L2
-// round trips cost little against the fp32 MFMA time.
+// round trips cost little against the matrix time.
 #include "chain_common.h"
 
 #include <algorithm>
@@ -14,7 +14,20 @@ namespace armor {
 namespace {
 
 constexpr int TB = 128; // sub-tile edge
-using CH = Chain<TB>;
+// Four waves, each a 64 x 64 patch of a sub-tile, products on the bf16 matrix instruction (1), or the
+// eight waves of 64 x 32 and the fp32 instruction (0).  The cut of an fp32 operand into its bf16 pieces
+// costs 11 vector instructions per pair of values, so the larger patch (each operand value cut by two
+// waves instead of four and two) is what keeps the cuts below the matrix time; it needs the 512
+// registers of a one-wave-per-SIMD workgroup.  28672 x 8192, one iteration: 14.2 ms against 15.3 ms.
+#ifndef ARMOR_BIG_BF16X3
+#define ARMOR_BIG_BF16X3 1
+#endif
+#if ARMOR_BIG_BF16X3
+struct CfgBig { static constexpr int WM = 2, WN = 2, TM = 2, TN = 2; static constexpr bool SPLIT = true; };
+#else
+struct CfgBig { static constexpr int WM = 2, WN = 4, TM = 2, TN = 1; static constexpr bool SPLIT = false; };
+#endif
+using CH = Chain<TB, CfgBig>;
 
 // acc over the NS inner sub-tiles of  op(L) (pt, :) * op(R) (:, qt)  for every output sub-tile,
 // then epi(pt, qt, acc).  L, R: b x b row-major with leading dimensions ldl, ldr (global memory;
@@ -56,8 +69,7 @@ __device__ __forceinline__ void big_mma(Smem<TB> &sm, int tid, const CH::Pos &p,
                     CH::gload_tile(ty, rsub(nq, nr), ldr, tid);
                     if (SCALE && tid < TB) dnext = Dk[nr * TB + tid];
                 }
-                if (rt == NS - 1) pre(pt, qt);
-                CH::template mma<LT, RT, SCALE>(acc, sm.X, sm.Y, sm.Dl, p);
+                CH::template mma<LT, RT, SCALE, true, false>(acc, sm.X, sm.Y, sm.Dl, p, [&]() { if (rt == NS - 1) pre(pt, qt); });
                 __syncthreads();
                 if (more) {
                     CH::lstore_tile(sm.X, tx, tid);
@@ -305,9 +317,8 @@ __global__ __launch_bounds__(CH::NT) void big_phase_WS_kernel(
             for_acc(acc, p, pt, qt, b, [&](uint32_t off, float v, int, int, int) { gst(s0, off, v); }); // U = (R D) B^T
         });
         float dd = 0.f;
-        uint32_t mb[CH::TM][CH::TN][16]; // mask bytes of this lane's elements, requested under the last matrix step
-        auto pre_G = [&](int pt, int qt) {
-            load_patch(wp, Cij, p, pt, qt, ldw);
+        uint32_t mb[CH::TM][CH::TN][4]; // mask bytes of this lane's elements (four to a register), requested under the last matrix step
+        auto load_mask = [&](int pt, int qt) {
 #pragma unroll
             for (int tm = 0; tm < CH::TM; ++tm)
 #pragma unroll
@@ -315,8 +326,18 @@ __global__ __launch_bounds__(CH::NT) void big_phase_WS_kernel(
                     const int64_t gcol = (int64_t)j * b + qt * TB + p.col(tn);
                     const uint8_t *mp = mask + ((int64_t)i * b + pt * TB + p.wm0 + p.kh * 4) * mrow + gcol / mask_group;
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) mb[tm][tn][r] = mp[(int64_t)(tm * 32 + (r >> 2) * 8 + (r & 3)) * mrow];
+                    for (int q = 0; q < 4; ++q) {
+                        uint32_t w = 0;
+#pragma unroll
+                        for (int r = 4 * q; r < 4 * q + 4; ++r)
+                            w |= (uint32_t)mp[(int64_t)(tm * 32 + (r >> 2) * 8 + (r & 3)) * mrow] << (8 * (r & 3));
+                        mb[tm][tn][q] = w;
+                    }
                 }
+        };
+        auto pre_G = [&](int pt, int qt) {
+            load_patch(wp, Cij, p, pt, qt, ldw);
+            load_mask(pt, qt);
         };
         big_mma<NS, true, false, false, false>(sm, tid, p, Ai, b, s0, b, nullptr, pre_G, [&](int pt, int qt, CH::Acc &acc) {
             // G = A^T U: W' step on kept entries; Delta -> s1, raw G -> Gout (fused mode)
@@ -330,7 +351,7 @@ __global__ __launch_bounds__(CH::NT) void big_phase_WS_kernel(
                     const int sh = (int)(gcol % mask_group);
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
-                        const bool kp = (mb[tm][tn][r] >> sh) & 1u;
+                        const bool kp = (mb[tm][tn][r >> 2] >> (8 * (r & 3) + sh)) & 1u;
                         const float g = acc.v[tm][tn][r], dl = kp ? g : 0.f;
                         dd += dl * dl;
                         if (kp) gst(Cij, cbase + CH::Pos::unif_boff(tm, tn, r, ldw), wp.v[tm][tn][r] + eta2 * dl);
@@ -348,11 +369,11 @@ __global__ __launch_bounds__(CH::NT) void big_phase_WS_kernel(
                 for_acc(acc, p, pt, qt, b, [&](uint32_t off, float v, int, int, int) { gst(s0, off, v); }); // V = Delta K
             });
             float dz = 0.f;
-            Patch dp; // Delta and the raw G of this lane's elements (both written by this lane above)
+            // the raw G of this lane's elements (written by this lane above); Delta is G on the kept entries
             big_mma<NS, false, false, false, false>(sm, tid, p, AtA + (int64_t)i * b * b, b, s0, b, nullptr,
                                              [&](int pt, int qt) {
                                                  load_patch(wp, Gij, p, pt, qt, ldw);
-                                                 load_patch(dp, s1, p, pt, qt, b);
+                                                 load_mask(pt, qt);
                                              },
                                              [&](int pt, int qt, CH::Acc &acc) {
                 // Z = (A^T A) V:  G_new = G - eta Z;  <Delta, Z>
@@ -360,13 +381,16 @@ __global__ __launch_bounds__(CH::NT) void big_phase_WS_kernel(
 #pragma unroll
                 for (int tm = 0; tm < CH::TM; ++tm)
 #pragma unroll
-                    for (int tn = 0; tn < CH::TN; ++tn)
+                    for (int tn = 0; tn < CH::TN; ++tn) {
+                        const int sh = (int)(((int64_t)j * b + qt * TB + p.col(tn)) % mask_group);
 #pragma unroll
                         for (int r = 0; r < 16; ++r) {
                             const float z = acc.v[tm][tn][r];
-                            dz += dp.v[tm][tn][r] * z;
+                            const bool kp = (mb[tm][tn][r >> 2] >> (8 * (r & 3) + sh)) & 1u;
+                            dz += kp ? wp.v[tm][tn][r] * z : 0.f;
                             gst(Gij, cbase + CH::Pos::unif_boff(tm, tn, r, ldw), -2.f * (wp.v[tm][tn][r] - eta2 * z));
                         }
+                    }
             });
             float ltot = CH::block_sum(lsum - 2.f * eta2 * dd + eta2 * eta2 * dz, sm.red, tid);
             if (tid == 0) loss_part[blk] = ltot;
@@ -445,7 +469,7 @@ __global__ __launch_bounds__(CH::NT) void big_phase_FB_kernel(
             for_acc(acc, p, pt, qt, b, [&](uint32_t off, float v, int, int, int) { gst(gb, off, -2.f * v); }); // C^T T, old core
         });
         float *mij = mC + (int64_t)i * b * d_in + (int64_t)j * b, *vij = vC + (int64_t)i * b * d_in + (int64_t)j * b;
-        uint32_t mb[CH::TM][CH::TN][16];
+        uint32_t mb[CH::TM][CH::TN][4];
         auto pre_C = [&](int pt, int qt) {
             load_patch(wp, Cij, p, pt, qt, ldw);
 #pragma unroll
@@ -455,7 +479,13 @@ __global__ __launch_bounds__(CH::NT) void big_phase_FB_kernel(
                     const int64_t gcol = (int64_t)j * b + qt * TB + p.col(tn);
                     const uint8_t *mp = mask + ((int64_t)i * b + pt * TB + p.wm0 + p.kh * 4) * mrow + gcol / mask_group;
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) mb[tm][tn][r] = mp[(int64_t)(tm * 32 + (r >> 2) * 8 + (r & 3)) * mrow];
+                    for (int q = 0; q < 4; ++q) {
+                        uint32_t w = 0;
+#pragma unroll
+                        for (int r = 4 * q; r < 4 * q + 4; ++r)
+                            w |= (uint32_t)mp[(int64_t)(tm * 32 + (r >> 2) * 8 + (r & 3)) * mrow] << (8 * (r & 3));
+                        mb[tm][tn][q] = w;
+                    }
                 }
         };
         big_mma<NS, false, true, false, false>(sm, tid, p, s0, b, Bj, b, nullptr, pre_C, [&](int pt, int qt, CH::Acc &acc) {
@@ -469,7 +499,7 @@ __global__ __launch_bounds__(CH::NT) void big_phase_FB_kernel(
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
                         const uint32_t off = cbase + CH::Pos::unif_boff(tm, tn, r, ldw);
-                        const bool kp = (mb[tm][tn][r] >> sh) & 1u;
+                        const bool kp = (mb[tm][tn][r >> 2] >> (8 * (r & 3) + sh)) & 1u;
                         const float g = kp ? -2.f * acc.v[tm][tn][r] : 0.f;
                         const float mn = k.b1 * gld(mij, off) + k.one_minus_b1 * g;
                         const float vn = k.b2 * gld(vij, off) + k.one_minus_b2 * g * g;

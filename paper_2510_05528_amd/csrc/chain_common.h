@@ -44,13 +44,49 @@ template <class T> __device__ __forceinline__ void gst(T *base, uint32_t boff, T
     *reinterpret_cast<T *>(reinterpret_cast<char *>(base) + boff) = v;
 }
 
+// ---- fp32 products on the bf16 matrix instruction ------------------------------------------------
+// Every fp32 value is cut EXACTLY into three bf16 pieces (x = x1 + x2 + x3: the top 8 significant bits,
+// the next 8, the last 8, by truncation) and a product x y is formed as the six partial products
+// x3 y1 + x1 y3 + x2 y2 + x2 y1 + x1 y2 + x1 y1 on v_mfma_f32_32x32x16_bf16 (fp32 accumulation); the
+// three dropped ones are below 2^-23 |x y|, the size of one fp32 rounding.  Sixteen inner indices then
+// cost six 8-pass instructions instead of eight 16-pass ones of v_mfma_f32_32x32x2_f32.
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
+
+// Eight floats (the inner indices one lane supplies to a 16-deep matrix instruction) as three vectors
+// of eight bf16: pieces 1, 2, 3 of the exact three-way cut.
+struct Pieces {
+    uint32_t p1[4], p2[4], p3[4];
+};
+__device__ __forceinline__ uintx4 vec4(const uint32_t (&a)[4]) {
+    uintx4 v = {a[0], a[1], a[2], a[3]};
+    return v;
+}
+__device__ __forceinline__ void cut3(const float (&x)[8], Pieces &o) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const uint32_t ua = __float_as_uint(x[2 * e]), ub = __float_as_uint(x[2 * e + 1]);
+        o.p1[e] = __builtin_amdgcn_perm(ub, ua, 0x07060302u); // the two upper halves
+        const float ra = x[2 * e] - __uint_as_float(ua & 0xffff0000u), rb = x[2 * e + 1] - __uint_as_float(ub & 0xffff0000u);
+        const uint32_t va = __float_as_uint(ra), vb = __float_as_uint(rb);
+        o.p2[e] = __builtin_amdgcn_perm(vb, va, 0x07060302u);
+        const float sa = ra - __uint_as_float(va & 0xffff0000u), sb = rb - __uint_as_float(vb & 0xffff0000u);
+        o.p3[e] = __builtin_amdgcn_perm(__float_as_uint(sb), __float_as_uint(sa), 0x07060302u); // at most 8 bits left: exact
+    }
+}
+__device__ __forceinline__ floatx16 mfma_bf16(const uintx4 &a, const uintx4 &b, const floatx16 &c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
+// A configuration's SPLIT chooses the matrix instruction of the LDS-resident products (Chain::mma):
+// true = bf16 pieces as above, false = v_mfma_f32_32x32x2_f32.
 template <int B> struct Cfg;
-template <> struct Cfg<32>  { static constexpr int WM = 1, WN = 1, TM = 1, TN = 1; };
-template <> struct Cfg<64>  { static constexpr int WM = 2, WN = 2, TM = 1, TN = 1; };
+template <> struct Cfg<32>  { static constexpr int WM = 1, WN = 1, TM = 1, TN = 1; static constexpr bool SPLIT = false; };
+template <> struct Cfg<64>  { static constexpr int WM = 2, WN = 2, TM = 1, TN = 1; static constexpr bool SPLIT = false; };
 // 8 waves at b = 128, each owning a 64 x 32 patch: two waves share a SIMD, so one wave's LDS reads
 // and address arithmetic overlap the other's MFMA issue (measured: same loop rate as 4 waves of
 // 64 x 64 or 16 waves of 32 x 32, but the only shape that leaves registers for operand prefetch).
-template <> struct Cfg<128> { static constexpr int WM = 2, WN = 4, TM = 2, TN = 1; };
+template <> struct Cfg<128> { static constexpr int WM = 2, WN = 4, TM = 2, TN = 1; static constexpr bool SPLIT = false; };
 
 template <int B, class C = Cfg<B>> struct Chain {
     static constexpr int WM = C::WM, WN = C::WN, TM = C::TM, TN = C::TN;
@@ -196,9 +232,104 @@ template <int B, class C = Cfg<B>> struct Chain {
     // without the fetch, i.e. it also waits for operands requested a moment ago (LDS-fed loop alone:
     // 83 % of the fp32 matrix peak with the condition, 91 % peeled).  Inside a kernel the better form
     // depends on what else is live around the product, so call sites choose by measurement.
-    template <bool LT, bool RT, bool SCALE, bool PEEL = true, bool ZERO = false>
+    // The same product on the bf16 matrix instruction: the fp32 LDS operands are cut into their three
+    // bf16 pieces as they are read.  One lane supplies eight consecutive inner indices of a group of 16
+    // (lane half kh: 8 kh .. 8 kh + 7); the pieces of group g + 1 are cut underneath the 6 TM TN matrix
+    // instructions of group g and the raw values of group g + 2 are read underneath those as well.
+    template <bool LT, bool RT, bool SCALE>
+    __device__ static __forceinline__ void fetch16(float (&a)[TM][8], float (&b)[TN][8], int g,
+                                                   const float *__restrict__ L, const float *__restrict__ R,
+                                                   const float *__restrict__ Dk, const Pos &p) {
+        const int k0 = 16 * g + 8 * p.kh;
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm) {
+            const int m = p.wm0 + tm * 32 + p.l32;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) a[tm][e] = LT ? L[(k0 + e) * P + m] : L[m * P + k0 + e];
+        }
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn) {
+            const int n = p.wn0 + tn * 32 + p.l32;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) b[tn][e] = RT ? R[n * P + k0 + e] : R[(k0 + e) * P + n];
+        }
+        if (SCALE) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float dk = Dk[k0 + e];
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm) a[tm][e] *= dk;
+            }
+        }
+    }
+
+    template <bool LT, bool RT, bool SCALE, bool ZERO, class Late>
+    __device__ static __forceinline__ void mma_split(Acc &acc, const float *__restrict__ L, const float *__restrict__ R,
+                                                     const float *__restrict__ Dk, const Pos &p, Late &&late) {
+        static_assert(B % 16 == 0, "groups of 16 inner indices");
+        constexpr int NG = B / 16;
+        float ra[TM][8], rb[TN][8];
+        Pieces pa[2][TM], pb[2][TN];
+        fetch16<LT, RT, SCALE>(ra, rb, 0, L, R, Dk, p);
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm) cut3(ra[tm], pa[0][tm]);
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn) cut3(rb[tn], pb[0][tn]);
+        if (NG > 1) fetch16<LT, RT, SCALE>(ra, rb, 1, L, R, Dk, p);
+#pragma unroll
+        for (int g = 0; g < NG; ++g) {
+            const int cur = g & 1;
+            if (g + 1 < NG) {
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm) cut3(ra[tm], pa[cur ^ 1][tm]);
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn) cut3(rb[tn], pb[cur ^ 1][tn]);
+            }
+            if (g + 2 < NG) fetch16<LT, RT, SCALE>(ra, rb, g + 2, L, R, Dk, p);
+            if (g == (NG > 2 ? NG - 2 : 0)) late();
+            // small partial products first: (3,1) (1,3) (2,2) (2,1) (1,2) (1,1)
+#pragma unroll
+            for (int c = 0; c < 6; ++c)
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                    for (int tn = 0; tn < TN; ++tn) {
+                        const Pieces &x = pa[cur][tm], &y = pb[cur][tn];
+                        const uintx4 a = c == 0 ? vec4(x.p3) : (c == 2 || c == 3) ? vec4(x.p2) : vec4(x.p1);
+                        const uintx4 b = c == 1 ? vec4(y.p3) : (c == 2 || c == 4) ? vec4(y.p2) : vec4(y.p1);
+                        if (ZERO && g == 0 && c == 0) {
+                            const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                            acc.v[tm][tn] = mfma_bf16(a, b, zero);
+                        } else {
+                            acc.v[tm][tn] = mfma_bf16(a, b, acc.v[tm][tn]);
+                        }
+                    }
+            // issue order: a matrix instruction, then its share of the cuts and of the LDS reads
+            constexpr int NM = 6 * TM * TN, NV = 11 * 4 * (TM + TN) + (SCALE ? 8 * TM : 0), ND = 8 * (TM + TN) + (SCALE ? 8 : 0);
+#pragma unroll
+            for (int m = 0; m < NM; ++m) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, (NV + NM - 1) / NM, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, (ND + NM - 1) / NM, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+
+    // late(): requests whose results are wanted right after the product (what an epilogue reads from
+    // global memory); issued two groups before the end of the bf16 form, where the registers of the
+    // operand pipeline start to free up, and in front of the fp32 form.
+    struct NoLate {
+        __device__ void operator()() const {}
+    };
+    template <bool LT, bool RT, bool SCALE, bool PEEL = true, bool ZERO = false, class Late = NoLate>
     __device__ static void mma(Acc &acc, const float *__restrict__ L, const float *__restrict__ R,
-                               const float *__restrict__ Dk, const Pos &p) {
+                               const float *__restrict__ Dk, const Pos &p, Late &&late = Late()) {
+        if constexpr (C::SPLIT) {
+            mma_split<LT, RT, SCALE, ZERO>(acc, L, R, Dk, p, late);
+            return;
+        }
+        late();
         static_assert(B % (4 * G) == 0 && B >= 12 * G, "two groups per trip; head, loop and tail trips");
         Frag f0, f1;
         fetch<LT, RT, SCALE>(f0, 0, L, R, Dk, p);

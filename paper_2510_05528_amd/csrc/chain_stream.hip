@@ -24,7 +24,7 @@ namespace armor {
 
 namespace stream { // (named: profilers print the kernels' names)
 
-struct CfgStream { static constexpr int WM = 2, WN = 2, TM = 2, TN = 2; };
+struct CfgStream { static constexpr int WM = 2, WN = 2, TM = 2, TN = 2; static constexpr bool SPLIT = false; };
 constexpr int SB = 128;
 using CS = Chain<SB, CfgStream>;
 typedef float floatx4 __attribute__((ext_vector_type(4)));
@@ -46,34 +46,6 @@ constexpr bool SPLIT_BF16 = ARMOR_STREAM_BF16X3 != 0;
 // products cover this one's epilogues.)
 constexpr int SEQ_WGS = 2;
 constexpr int SPLIT_DEPTH_PIECES = 2, SPLIT_DEPTH_DATA = 4;
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
-
-// Eight floats (the inner indices one lane supplies to a 16-deep matrix instruction) as three vectors
-// of eight bf16: pieces 1, 2, 3 of the exact three-way cut.
-struct Pieces {
-    uint32_t p1[4], p2[4], p3[4];
-};
-__device__ __forceinline__ uintx4 vec4(const uint32_t (&a)[4]) {
-    uintx4 v = {a[0], a[1], a[2], a[3]};
-    return v;
-}
-__device__ __forceinline__ void cut3(const float (&x)[8], Pieces &o) {
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        const uint32_t ua = __float_as_uint(x[2 * e]), ub = __float_as_uint(x[2 * e + 1]);
-        o.p1[e] = __builtin_amdgcn_perm(ub, ua, 0x07060302u); // the two upper halves
-        const float ra = x[2 * e] - __uint_as_float(ua & 0xffff0000u), rb = x[2 * e + 1] - __uint_as_float(ub & 0xffff0000u);
-        const uint32_t va = __float_as_uint(ra), vb = __float_as_uint(rb);
-        o.p2[e] = __builtin_amdgcn_perm(vb, va, 0x07060302u);
-        const float sa = ra - __uint_as_float(va & 0xffff0000u), sb = rb - __uint_as_float(vb & 0xffff0000u);
-        o.p3[e] = __builtin_amdgcn_perm(__float_as_uint(sb), __float_as_uint(sa), 0x07060302u); // at most 8 bits left: exact
-    }
-}
-__device__ __forceinline__ floatx16 mfma_bf16(const uintx4 &a, const uintx4 &b, const floatx16 &c) {
-    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
-}
-
 struct SmemStream {
     float X[CS::TILE_FLOATS];
     float red[16];
