@@ -575,7 +575,7 @@ armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const flo
                                     nullptr, s);
                 if (!unstructured) {
                     if (big) launch_big_wrapper_grams(d, A, B, f.D, f.colnorm2, f.fro2A, f.AtA, f.K, f.fro2K, s);
-                    else launch_wrapper_grams(d, A, B, f.D, f.colnorm2, f.fro2A, f.AtA, f.K, f.fro2K, s);
+                    else launch_wrapper_grams(d, A, B, f.D, f.colnorm2, f.fro2A, f.AtA, f.K, f.fro2K, nullptr, nullptr, s);
                 }
             }
             if (!unstructured) {
@@ -609,11 +609,8 @@ armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const flo
         {
             ProfScope ps(ARMOR_PROF_SMALL, s, true);
             launch_update_wrapper(A, d.nbi, d.b, f.gpart, f.nsA, f.beta_part, d.nblocks, f.loss_part,
-                                  loss_trace ? loss_trace + (t - 1) : nullptr, eta_t, s);
-            if (pl) {
-                const PlaneJob job = {A, d.nbi, f.planes.A, f.planes.AT};
-                launch_make_planes(&job, 1, s);
-            }
+                                  loss_trace ? loss_trace + (t - 1) : nullptr, eta_t, pl ? f.planes.A : nullptr,
+                                  pl ? f.planes.AT : nullptr, s);
         }
         {
             ProfScope ps(ARMOR_PROF_PHASE_B, s, true);
@@ -623,14 +620,10 @@ armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const flo
         {
             ProfScope ps(ARMOR_PROF_SMALL, s, true);
             launch_update_wrapper(B, d.nbj, d.b, f.gpart, f.nsB, f.beta_part, d.nblocks, nullptr, nullptr,
-                                  eta_t ? eta_t + 1 : nullptr, s);
+                                  eta_t ? eta_t + 1 : nullptr, pl ? f.planes.B : nullptr, pl ? f.planes.BT : nullptr, s);
             if (big) launch_big_wrapper_grams(d, A, B, f.D, f.colnorm2, f.fro2A, f.AtA, f.K, f.fro2K, s);
-            else launch_wrapper_grams(d, A, B, f.D, f.colnorm2, f.fro2A, f.AtA, f.K, f.fro2K, s);
-            if (pl) {
-                const PlaneJob jobs[3] = {{B, d.nbj, f.planes.B, f.planes.BT}, {f.K, d.nbj, f.planes.K, nullptr},
-                                          {f.AtA, d.nbi, f.planes.AtA, nullptr}};
-                launch_make_planes(jobs, 3, s);
-            }
+            else launch_wrapper_grams(d, A, B, f.D, f.colnorm2, f.fro2A, f.AtA, f.K, f.fro2K, pl ? f.planes.AtA : nullptr,
+                                      pl ? f.planes.K : nullptr, s);
             if (eta_t) launch_eta_W_trace(d, f.fro2A, f.fro2K, eta_t + 2, s);
         }
         if (unstructured) {

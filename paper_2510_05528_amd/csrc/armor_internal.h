@@ -60,8 +60,10 @@ void launch_phase_W(const Dims &d, const float *Wbar, float *C, const float *A, 
                     const uint8_t *mask, int mask_group, const float *fro2A, const float *fro2K, const float *Sp, int grid_cap,
                     const WrapperPlanes *planes, hipStream_t s);
 // Per wrapper block: A^iT A^i, its diagonal ||A^i[:,p]||^2 and ||A^iT A^i||_F^2; K^j = B^j D^j B^jT, ||K^j||_F^2.
+// PAtA / PK (d_block 128 only, else null): the two results also as bf16 plane sets.
 void launch_wrapper_grams(const Dims &d, const float *A, const float *B, const float *D, float *colnorm2,
-                          float *fro2A, float *AtA, float *K, float *fro2K, hipStream_t s);
+                          float *fro2A, float *AtA, float *K, float *fro2K, uint16_t *PAtA, uint16_t *PK,
+                          hipStream_t s);
 // W' step fused with the core gradient at the updated core (N:M mode): C += (2/beta_W) G (.) M,
 // Gout = -2 (G - (2/beta_W) (A^T A)(G (.) M) K), block loss after the continuous step to loss_part.
 void launch_phase_WS(const Dims &d, const float *Wbar, float *C, const float *A, const float *B, const float *D,
@@ -120,8 +122,10 @@ void launch_init_nm(const float *Wbar, const float *D, int64_t d_out, int64_t d_
 void launch_diag(const float *H, int64_t d_in, int64_t ldh, float *D, hipStream_t s);
 // A -= (sum of partials)/beta, beta = 2 * sum(beta_part); optionally trace_out = sum(loss_part) and
 // eta_out = 1/beta.
+// P / PT (d_block 128 only, else null): the kernel also writes the updated wrapper's bf16 plane sets.
 void launch_update_wrapper(float *A, int nblk, int b, const float *gpart, int nsplit, const float *beta_part,
-                           int nblocks, const float *loss_part, double *trace_out, double *eta_out, hipStream_t s);
+                           int nblocks, const float *loss_part, double *trace_out, double *eta_out, uint16_t *P,
+                           uint16_t *PT, hipStream_t s);
 void launch_adam_wrapper(float *X, float *m, float *v, int nblk, int b, const float *gpart, int nsplit, double lr,
                          double b1, double b2, double eps, int64_t t, int nblocks, const float *loss_part,
                          double *trace_out, hipStream_t s);

@@ -802,7 +802,7 @@ template <int B>
 __global__ __launch_bounds__((B / 32) * 64) void wrapper_grams_kernel(
     const float *__restrict__ A, const float *__restrict__ Bw, const float *__restrict__ D, int nbi,
     float *__restrict__ colnorm2, float *__restrict__ fro2A, float *__restrict__ AtA, float *__restrict__ K,
-    float *__restrict__ fro2K) {
+    float *__restrict__ fro2K, uint16_t *__restrict__ PAtA, uint16_t *__restrict__ PK) {
     // One workgroup per (block, 32-column slab of the result), one wave per 32 x 32 tile of the slab:
     // the b x b products are few (d_out/b + d_in/b), so each is spread over b/32 compute units.
     using CH = Chain<B>;
@@ -855,12 +855,32 @@ __global__ __launch_bounds__((B / 32) * 64) void wrapper_grams_kernel(
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) f2 += __shfl_xor(f2, off, 64);
+    uint16_t *planes = isA ? PAtA : PK;
+    const bool emit = B == PLANE_B && planes != nullptr; // uniform over the workgroup
+    if (emit) {
+        // The result also as bf16 pieces for the d_block 128 chains.  Both results are symmetric, so the slab
+        // (all rows, columns 32 ct .. + 32) holds op(x, k) = M[x][k] for the two runs of 16 inner indices
+        // inside it; it goes through LDS (the operand tile is dead) to turn "one column per lane" into
+        // "sixteen columns of one row per thread".
+        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < 16; ++r) X[(32 * rt + (r >> 2) * 8 + kh * 4 + (r & 3)) * 33 + l32] = acc[r];
+    }
     if (lane == 0) red[w] = f2;
     __syncthreads();
     if (tid == 0) {
         float s = 0.f;
         for (int q = 0; q < NS; ++q) s += red[q];
         (isA ? fro2A : fro2K)[idx * NS + ct] = s;
+    }
+    if constexpr (B == PLANE_B) {
+        if (emit) {
+            const int x = tid & (B - 1), rl = tid / B; // 256 threads: 128 rows x 2 runs
+            float v[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) v[i] = X[x * 33 + 16 * rl + i];
+            plane_emit(planes + (int64_t)idx * 3 * B * B, 2 * ct + rl, x, v);
+        }
     }
 }
 
@@ -954,11 +974,12 @@ void launch_phase_W(const Dims &d, const float *Wbar, float *C, const float *A, 
 }
 
 void launch_wrapper_grams(const Dims &d, const float *A, const float *B, const float *D, float *colnorm2,
-                          float *fro2A, float *AtA, float *K, float *fro2K, hipStream_t s) {
+                          float *fro2A, float *AtA, float *K, float *fro2K, uint16_t *PAtA, uint16_t *PK,
+                          hipStream_t s) {
     ARMOR_DISPATCH_B(d.b, {
         dim3 grid((d.nbi + d.nbj) * (BB / 32)), block((BB / 32) * 64);
         hipLaunchKernelGGL((wrapper_grams_kernel<BB>), grid, block, 0, s, A, B, D, d.nbi, colnorm2, fro2A, AtA, K,
-                           fro2K);
+                           fro2K, PAtA, PK);
     });
 }
 

@@ -343,21 +343,7 @@ __global__ __launch_bounds__(256) void make_planes_kernel(PlaneJobs jobs) {
     uint16_t *__restrict__ P = jobs.P[job], *__restrict__ PT = jobs.PT[job];
     const int x = 32 * blockIdx.y + (tid & 31), run = tid >> 5;
     const float *Xb = X + (int64_t)blk * SB * SB;
-    auto emit = [&](uint16_t *out, const float (&v)[16]) {
-        float h0[8], h1[8]; // what lane half 0 / 1 supplies: k 0..3, 8..11 / 4..7, 12..15 of the run
-#pragma unroll
-        for (int e = 0; e < 4; ++e) { h0[e] = v[e]; h0[4 + e] = v[8 + e]; h1[e] = v[4 + e]; h1[4 + e] = v[12 + e]; }
-        Pieces a, b;
-        cut3(h0, a);
-        cut3(h1, b);
-        uint16_t *o = out + (int64_t)blk * 3 * SB * SB + ((run * 2) * SB + x) * 8;
-        *reinterpret_cast<uintx4 *>(o) = vec4(a.p1);
-        *reinterpret_cast<uintx4 *>(o + SB * 8) = vec4(b.p1);
-        *reinterpret_cast<uintx4 *>(o + SB * SB) = vec4(a.p2);
-        *reinterpret_cast<uintx4 *>(o + SB * SB + SB * 8) = vec4(b.p2);
-        *reinterpret_cast<uintx4 *>(o + 2 * SB * SB) = vec4(a.p3);
-        *reinterpret_cast<uintx4 *>(o + 2 * SB * SB + SB * 8) = vec4(b.p3);
-    };
+    auto emit = [&](uint16_t *out, const float (&v)[16]) { plane_emit(out + (int64_t)blk * 3 * SB * SB, run, x, v); };
     float v[16];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {

@@ -2,6 +2,7 @@
 // initialisation (Eq. 3), wrapper updates (Alg. 2), the sparse-core step (Alg. 3, Eq. 6-8),
 // denormalisation and N:M packing.  gfx950; 64-wide waves; every reduction has a fixed order.
 #include "armor_internal.h"
+#include "planes.h"
 
 #include <algorithm>
 #include <cmath>
@@ -414,8 +415,78 @@ __global__ __launch_bounds__(256) void update_wrapper_kernel(float *__restrict__
     X[(int64_t)k * bb + e] = (float)((double)xold - g / beta);
 }
 
+// The same update at d_block = 128 for the chains that take the wrapper as bf16 pieces: workgroup (k, q) owns
+// the 16-row strip q of block k (thread t: row t / 16, eight columns from 8 (t % 16)), writes the fp32 values
+// and, through LDS, the strip's entries of both plane sets: P (op(x, k) = X[x][k]: rows of the strip, all eight
+// runs) and PT (op(x, k) = X[k][x]: the strip's rows are run q of every column).  Same sums in the same order
+// as update_wrapper_kernel.
+__global__ __launch_bounds__(256) void update_wrapper_planes_kernel(float *__restrict__ X, const float *__restrict__ gpart,
+                                                                    int nsplit, const float *__restrict__ beta_part,
+                                                                    int nblocks, const float *__restrict__ loss_part,
+                                                                    double *__restrict__ trace_out,
+                                                                    double *__restrict__ eta_out,
+                                                                    uint16_t *__restrict__ P, uint16_t *__restrict__ PT) {
+    constexpr int b = PLANE_B, bb = b * b;
+    __shared__ double red[4];
+    __shared__ float T[16][b + 1];
+    const int tid = threadIdx.x, k = blockIdx.x, q = blockIdx.y;
+    const int row = tid >> 4, col = 8 * (tid & 15);
+    const int e = (16 * q + row) * b + col;
+    double g[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) g[u] = 0.0;
+#pragma unroll 4
+    for (int c = 0; c < nsplit; ++c) {
+        const float4 *src = reinterpret_cast<const float4 *>(gpart + ((int64_t)k * nsplit + c) * bb + e);
+        const float4 lo = src[0], hi = src[1];
+        g[0] += (double)lo.x; g[1] += (double)lo.y; g[2] += (double)lo.z; g[3] += (double)lo.w;
+        g[4] += (double)hi.x; g[5] += (double)hi.y; g[6] += (double)hi.z; g[7] += (double)hi.w;
+    }
+    float4 *xp = reinterpret_cast<float4 *>(X + (int64_t)k * bb + e);
+    const float4 xlo = xp[0], xhi = xp[1];
+    const float xold[8] = {xlo.x, xlo.y, xlo.z, xlo.w, xhi.x, xhi.y, xhi.z, xhi.w};
+    double s = 0.0;
+    for (int i = tid; i < nblocks; i += 256) s += (double)beta_part[i];
+    const double beta = 2.0 * block_sum_256(s, red);
+    if (eta_out != nullptr && k == 0 && q == 0 && tid == 0) *eta_out = beta > 0.0 ? 1.0 / beta : 0.0;
+    if (trace_out != nullptr && k == 0 && q == 0) {
+        double l = 0.0;
+        for (int i = tid; i < nblocks; i += 256) l += (double)loss_part[i];
+        l = block_sum_256(l, red);
+        if (tid == 0) *trace_out = l;
+    }
+    if (!(beta > 0.0)) return; // X and its pieces stay as they are (uniform over the workgroup)
+    float xn[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+        xn[u] = (float)((double)xold[u] - g[u] / beta);
+        T[row][col + u] = xn[u];
+    }
+    xp[0] = make_float4(xn[0], xn[1], xn[2], xn[3]);
+    xp[1] = make_float4(xn[4], xn[5], xn[6], xn[7]);
+    __syncthreads();
+    float v[16];
+    if (tid < b) { // P: 16 rows x 8 runs; thread -> (x = strip row t % 16, run t / 16)
+        const int x = tid & 15, run = tid >> 4;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) v[i] = T[x][16 * run + i];
+        plane_emit(P + (int64_t)k * 3 * bb, run, 16 * q + x, v);
+    } else if (PT != nullptr) { // PT: the strip is run q of all 128 columns; thread -> column t - 128
+        const int x = tid - b;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) v[i] = T[i][x];
+        plane_emit(PT + (int64_t)k * 3 * bb, q, x, v);
+    }
+}
+
 void launch_update_wrapper(float *A, int nblk, int b, const float *gpart, int nsplit, const float *beta_part,
-                           int nblocks, const float *loss_part, double *trace_out, double *eta_out, hipStream_t s) {
+                           int nblocks, const float *loss_part, double *trace_out, double *eta_out, uint16_t *P,
+                           uint16_t *PT, hipStream_t s) {
+    if (P != nullptr && b == PLANE_B) {
+        hipLaunchKernelGGL(update_wrapper_planes_kernel, dim3(nblk, b / 16), dim3(256), 0, s, A, gpart, nsplit, beta_part,
+                           nblocks, loss_part, trace_out, eta_out, P, PT);
+        return;
+    }
     int nq = (b * b + 255) / 256;
     hipLaunchKernelGGL(update_wrapper_kernel, dim3(nblk, nq), dim3(256), 0, s, A, b, gpart, nsplit, beta_part, nblocks,
                        loss_part, trace_out, eta_out);
