@@ -828,12 +828,16 @@ __global__ __launch_bounds__(256) void sparse_step_kernel(const float *__restric
         for (int u = 0; u < U; ++u) { // unconditional loads (index clamped): a group past the end is dropped below
             const int kap = min(kap0 + u * 256, gpb - 1);
             const float *g = Gij + (int64_t)(kap >> gsh) * d_in + (kap & (gpr - 1)) * M;
-            if (M == 4) {
-                float4 x = *reinterpret_cast<const float4 *>(g);
-                v[u][0] = x.x; v[u][1] = x.y; v[u][2] = x.z; v[u][3] = x.w;
-            } else {
+            if constexpr (M % 4 == 0) { // 16-byte loads (a group starts at a multiple of M columns)
 #pragma unroll
-                for (int p = 0; p < M; ++p) v[u][p] = g[p];
+                for (int h = 0; h < M / 4; ++h) {
+                    const float4 x = reinterpret_cast<const float4 *>(g)[h];
+                    v[u][4 * h] = x.x; v[u][4 * h + 1] = x.y; v[u][4 * h + 2] = x.z; v[u][4 * h + 3] = x.w;
+                }
+            } else {
+                const float2 x = *reinterpret_cast<const float2 *>(g);
+                v[u][0] = x.x; v[u][1] = x.y;
+                static_assert(M % 4 == 0 || M == 2, "group sizes are 2, 4 or 8");
             }
         }
 #pragma unroll
