@@ -140,6 +140,15 @@ def reconstruct(A, C, B):
     return out
 
 
+def proxy_loss_full_h(Wbar, A, C, B, H):
+    """The layer-wise objective against the whole Gram matrix H = X^T X (Sec. 2; Eq. 2 keeps only its
+    diagonal):  tr(R H R^T) = ||R X^T||_F^2  with R = Wbar - A C B.  The definition written out in fp64."""
+    R = np.asarray(_f32(Wbar), dtype=np.float64) - reconstruct(A, C, B)
+    H = np.asarray(H, dtype=np.float64)
+    assert H.shape == (R.shape[1], R.shape[1])
+    return float(np.sum((R @ H) * R))
+
+
 def _grad(fn, Wbar, A, C, B, D, shape):
     Wbar, A, C, B, D = _f32(Wbar), _f32(A), _f32(C), _f32(B), _f32(D)
     d_out, d_in = Wbar.shape

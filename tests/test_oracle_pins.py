@@ -139,6 +139,43 @@ def test_loss_matches_dense_algebra_and_is_nonnegative(orc):
     np.testing.assert_allclose(orc.reconstruct(A, C, B), dense(A) @ C.astype(np.float64) @ dense(B), rtol=1e-12, atol=1e-14)
 
 
+def test_full_gram_loss_is_the_activation_error_and_reduces_to_eq2(orc):
+    """tr(R H R^T) (Sec. 2, the objective before Eq. 2 drops the off-diagonal of H): equals the squared output
+    error ||R X^T||_F^2 on the activations that made H, the plain triple sum on a tiny case whose residual is
+    built entry by entry, and the proxy loss of Eq. 2 when H is diagonal."""
+    d_out, d_in, b, N, M = 64, 96, 16, 2, 4
+    rng = np.random.default_rng(2)
+    Wbar, D, A, B, C, mask = rand_state(rng, d_out, d_in, b, N, M)
+    X = rng.standard_normal((40, d_in))
+    X[:, ::7] *= 5.0  # correlated, badly scaled channels: off-diagonal terms matter
+    X += 0.5 * X[:, [0]]
+    H = X.T @ X
+    R = Wbar.astype(np.float64) - dense(A) @ C.astype(np.float64) @ dense(B)
+    got = orc.proxy_loss_full_h(Wbar, A, C, B, H)
+    assert np.isclose(got, np.linalg.norm(R @ X.T) ** 2, rtol=1e-12)
+    assert abs(got - orc.proxy_loss(Wbar, A, C, B, np.diag(H))) > 0.05 * got  # the off-diagonal part is not negligible here
+    # diagonal H: Eq. 2
+    assert np.isclose(orc.proxy_loss_full_h(Wbar, A, C, B, np.diag(D.astype(np.float64))), orc.proxy_loss(Wbar, A, C, B, D), rtol=1e-12)
+    # tiny case, entry by entry: R_ij = W_ij - sum_{p,q in the blocks} A^i[r,p] C[p,q] B^j[q,c]
+    d_out, d_in, b = 4, 8, 2
+    Wt, Dt, At, Bt, Ct, _ = rand_state(rng, d_out, d_in, b, 1, 2)
+    Ht = rng.standard_normal((d_in, 5)); Ht = Ht @ Ht.T
+    Rt = np.zeros((d_out, d_in))
+    for i in range(d_out):
+        for j in range(d_in):
+            bi, bj = i // b, j // b
+            s = 0.0
+            for pp in range(b):
+                for q in range(b):
+                    s += float(At[bi, i % b, pp]) * float(Ct[bi * b + pp, bj * b + q]) * float(Bt[bj, q, j % b])
+            Rt[i, j] = float(Wt[i, j]) - s
+    brute = sum(Rt[i, j] * Ht[j, k] * Rt[i, k] for i in range(d_out) for j in range(d_in) for k in range(d_in))
+    assert np.isclose(orc.proxy_loss_full_h(Wt, At, Ct, Bt, Ht), brute, rtol=1e-12)
+    # exact factorization: zero
+    I_A = np.tile(np.eye(b, dtype=np.float32), (d_out // b, 1, 1)); I_B = np.tile(np.eye(b, dtype=np.float32), (d_in // b, 1, 1))
+    assert orc.proxy_loss_full_h(Wt, I_A, Wt, I_B, Ht) == 0.0
+
+
 def test_diagonal_wrappers_commute_with_mask(orc):
     """App. A, Eq. 4: diag(a) (W' . M) diag(b) = (diag(a) W' diag(b)) . M, as an identity of the loss."""
     rng = np.random.default_rng(9)
