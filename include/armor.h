@@ -180,6 +180,29 @@ armor_status armor_proxy_loss_noalloc(const float *Wbar, const float *A, const f
                                       double *loss_out, void *hip_stream);
 
 /*
+ * The layer-wise objective against the WHOLE Gram matrix (Sec. 2 states the objective with the activations
+ * themselves; Eq. 2, the proxy the method optimises, keeps only its diagonal):
+ *     L_H = tr(R H R^T) = || R X^T ||_F^2  for H = X^T X,   R = Wbar - A S B.
+ * Evaluation only -- the block decomposition of Eq. 5 needs a diagonal weight, so no step of Alg. 1-3 uses
+ * this value; it tells how far the diagonal proxy is from the full second-order objective for a given
+ * factorization.  For a diagonal H it equals armor_proxy_loss.
+ *   Wbar, S: dense [d_out x d_in] fp32;  A [d_out/b][b][b] or NULL (= identity);  B [d_in/b][b][b] or NULL;
+ *   H: [d_in x d_in] fp32, symmetric, leading dimension ldh >= d_in, ldh a multiple of 4 (all of it is read;
+ *      express it in the same coordinates as Wbar: after the normalisation of Sec. 3.2, H_jk r1_j r1_k);
+ *   loss_out: one double in DEVICE memory;  ws: armor_proxy_loss_full_h_workspace_bytes() bytes of device
+ *   memory (holds R: 4*d_out*d_in bytes plus what armor_proxy_loss needs), 16-byte aligned like Wbar, S, H.
+ * Cost: the forward chain of armor_proxy_loss plus one d_out x d_in x d_in product (fp32 operands as three
+ * bf16 pieces each on the bf16 matrix instruction when d_out and d_in are multiples of 128, else the fp32
+ * matrix instruction on 32 x 32 tiles); per-tile sums in fp32, their total in fp64.
+ * Errors: ARMOR_ERR_NULL, ARMOR_ERR_SHAPE (shape rules of armor_proxy_loss; ldh), ARMOR_ERR_WORKSPACE,
+ * ARMOR_ERR_ALIGN; nothing is enqueued on error.
+ */
+size_t armor_proxy_loss_full_h_workspace_bytes(int64_t d_out, int64_t d_in, int64_t d_block);
+armor_status armor_proxy_loss_full_h(const float *Wbar, const float *A, const float *S, const float *B,
+                                     const float *H, int64_t ldh, int64_t d_out, int64_t d_in, int64_t d_block,
+                                     double *loss_out, void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
  * The whole BCD loop (Alg. 1): normalise W, initialise by Eq. 3 (A = B = I, top-N of every group by
  * Wbar^2 * H_jj), then n_iters times { continuous update (Alg. 2: sequential gradient steps on A, B,
  * W' with step 1/beta, App. D) ; sparse-core update (Alg. 3: one group per block, all C(M,N) masks,

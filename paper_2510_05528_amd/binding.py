@@ -16,7 +16,8 @@ EXPORTED = ["armor_status_string", "armor_last_hip_error", "armor_profile_enable
             "armor_gram_workspace_bytes", "armor_gram", "armor_gram_diag",
             "armor_gram_diag_x_workspace_bytes", "armor_gram_diag_x",
             "armor_normalize_workspace_bytes", "armor_normalize", "armor_proxy_loss_workspace_bytes",
-            "armor_proxy_loss", "armor_proxy_loss_noalloc", "armor_factorize_workspace_bytes", "armor_factorize_layer", "armor_pack_nm",
+            "armor_proxy_loss", "armor_proxy_loss_noalloc", "armor_proxy_loss_full_h_workspace_bytes",
+            "armor_proxy_loss_full_h", "armor_factorize_workspace_bytes", "armor_factorize_layer", "armor_pack_nm",
             "armor_pack_meta_row_bytes", "armor_to_bf16", "armor_apply_prepared_bytes", "armor_apply_prepare",
             "armor_apply_workspace_bytes", "armor_apply_packed"]
 
@@ -64,6 +65,9 @@ def load_library():
     lib.armor_proxy_loss_workspace_bytes.argtypes = [_i64, _i64, _i64]
     lib.armor_proxy_loss.argtypes = [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _i64, _vp, _vp, _sz, _vp]
     lib.armor_proxy_loss_noalloc.argtypes = [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _i64, _vp, _vp]
+    lib.armor_proxy_loss_full_h_workspace_bytes.restype = _sz
+    lib.armor_proxy_loss_full_h_workspace_bytes.argtypes = [_i64, _i64, _i64]
+    lib.armor_proxy_loss_full_h.argtypes = [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _i64, _vp, _vp, _sz, _vp]
     lib.armor_factorize_workspace_bytes.restype = _sz
     lib.armor_factorize_workspace_bytes.argtypes = [_i64, _i64, _i64, _int, _int, ctypes.POINTER(ArmorOpts)]
     lib.armor_factorize_layer.argtypes = [_vp, _int, _vp, _i64, _i64, _i64, _i64, _int, _int, _int,
@@ -239,6 +243,25 @@ def proxy_loss_noalloc(Wbar, A, S, B, H, d_block=None, out=None):
         out = torch.zeros(1, device=Wbar.device, dtype=torch.float64)
     _check(lib.armor_proxy_loss_noalloc(_ptr(Wbar), _ptr(A), _ptr(S), _ptr(B), _ptr(H), ldh, d_out, d_in, b, _ptr(out),
                                         _stream()))
+    return out
+
+
+def proxy_loss_full_h(Wbar, A, S, B, H, d_block=None, ws=None):
+    """armor_proxy_loss_full_h: tr(R H R^T) with R = Wbar - A S B and the whole Gram matrix H [d_in, d_in]
+    (row stride a multiple of 4), as a 1-element float64 device tensor.  A or B may be None (identity)."""
+    torch = _torch()
+    lib = load_library()
+    _dev_f32(Wbar, "Wbar"), _dev_f32(S, "S")
+    d_out, d_in = Wbar.shape
+    b = d_block or (A.shape[-1] if A is not None else B.shape[-1])
+    if not (H.is_cuda and H.dtype == torch.float32 and H.dim() == 2 and H.shape == (d_in, d_in) and H.stride(1) == 1):
+        raise ArmorError("H must be a [d_in, d_in] fp32 device tensor with unit column stride")
+    out = torch.zeros(1, device=Wbar.device, dtype=torch.float64)
+    nbytes = lib.armor_proxy_loss_full_h_workspace_bytes(d_out, d_in, b)
+    if ws is None:
+        ws = torch.empty(max(nbytes, 256), device=Wbar.device, dtype=torch.uint8)
+    _check(lib.armor_proxy_loss_full_h(_ptr(Wbar), _ptr(A), _ptr(S), _ptr(B), _ptr(H), H.stride(0), d_out, d_in, b,
+                                       _ptr(out), _ptr(ws), ws.numel(), _stream()))
     return out
 
 

@@ -398,6 +398,62 @@ armor_status armor_proxy_loss(const float *Wbar, const float *A, const float *S,
                               (hipStream_t)hip_stream);
 }
 
+// ---- loss against the whole Gram matrix: tr(R H R^T) ------------------------------------------------
+// Scratch: all-ones loss weights (the residual pass then leaves R itself), identity wrappers for a NULL A / B,
+// the per-block losses of that pass (unused), chain scratch at d_block 256, R, one partial per output tile.
+struct FullHWs {
+    LossWs l;
+    float *R, *part;
+    size_t bytes;
+};
+
+static FullHWs carve_full_h(void *base, const Dims &d, int big_wgs) {
+    FullHWs w;
+    w.l = carve_loss(base, d, true, true, big_wgs);
+    Carver c(base);
+    c.off = w.l.bytes;
+    w.R = c.take<float>((size_t)d.d_out * d.d_in);
+    w.part = c.take<float>((size_t)full_h_parts(d.d_out, d.d_in));
+    w.bytes = c.off + 256;
+    return w;
+}
+
+size_t armor_proxy_loss_full_h_workspace_bytes(int64_t d_out, int64_t d_in, int64_t d_block) {
+    if (validate_shape(d_out, d_in, d_block) != ARMOR_OK) return 0;
+    Dims d = make_dims(d_out, d_in, d_block);
+    return carve_full_h(nullptr, d, chain_slots(d.b)).bytes;
+}
+
+armor_status armor_proxy_loss_full_h(const float *Wbar, const float *A, const float *S, const float *B, const float *H,
+                                     int64_t ldh, int64_t d_out, int64_t d_in, int64_t d_block, double *loss_out,
+                                     void *ws, size_t ws_bytes, void *hip_stream) {
+    if (!Wbar || !S || !H || !loss_out) return ARMOR_ERR_NULL;
+    armor_status st = validate_shape(d_out, d_in, d_block);
+    if (st != ARMOR_OK) return st;
+    if (ldh < d_in || ldh % 4 != 0 || ldh > INT32_MAX) return ARMOR_ERR_SHAPE; // 16-byte row loads of H
+    if (!ws || ws_bytes < armor_proxy_loss_full_h_workspace_bytes(d_out, d_in, d_block)) return ARMOR_ERR_WORKSPACE;
+    if (!aligned16(Wbar) || !aligned16(S) || !aligned16(H) || !aligned16(ws) || (A && !aligned16(A)) ||
+        (B && !aligned16(B)))
+        return ARMOR_ERR_ALIGN;
+    Dims d = make_dims(d_out, d_in, d_block);
+    hipStream_t s = (hipStream_t)hip_stream;
+    const int big_wgs = chain_slots(d.b);
+    const FullHWs w = carve_full_h(ws, d, big_wgs);
+    launch_fill(w.l.D, d.d_in, 1.f, s);
+    if (!A) { launch_init_identity(w.l.Ai, d.nbi, d.b, s); A = w.l.Ai; }
+    if (!B) { launch_init_identity(w.l.Bi, d.nbj, d.b, s); B = w.l.Bi; }
+    // the loss-only forward pass with unit weights leaves R = Wbar - A S B in its gradient argument
+    if (d.b > 128)
+        launch_big_phase_A(d, Wbar, S, A, B, w.l.D, choose_nsplit(d.nbi, d.nbj, d.b), w.R, nullptr, w.l.loss_part, true,
+                           big_wgs, w.l.big, s);
+    else
+        launch_phase_A(d, Wbar, S, A, B, w.l.D, choose_nsplit(d.nbi, d.nbj, d.b), w.R, nullptr, w.l.loss_part, true, nullptr,
+                       nullptr, s);
+    launch_full_h_loss(w.R, d.d_out, d.d_in, H, ldh, w.part, chain_slots(128), s);
+    launch_sum_to_double(w.part, (int)full_h_parts(d.d_out, d.d_in), loss_out, s);
+    return check_hip();
+}
+
 // ---- allocation-free evaluation of Eq. 2 ---------------------------------------------------------
 // The scratch of armor_proxy_loss_noalloc lives in the library's own device image, one copy per GPU,
 // held until the process ends.  Host code must not use the array's name as an address: the device

@@ -130,6 +130,14 @@ void launch_adam_wrapper(float *X, float *m, float *v, int nblk, int b, const fl
                          double b1, double b2, double eps, int64_t t, int nblocks, const float *loss_part,
                          double *trace_out, hipStream_t s);
 void launch_zero(float *x, int64_t n, hipStream_t s);
+void launch_fill(float *x, int64_t n, float v, hipStream_t s);
+
+// ---- loss against the whole Gram matrix (full_h.hip) ---------------------------------------------
+// tile edge used for d_out x d_in, number of per-tile partial sums, and the launch:  part[tile] = <R_tile, (R H)_tile>
+int full_h_tile(int64_t d_out, int64_t d_in);
+int64_t full_h_parts(int64_t d_out, int64_t d_in);
+void launch_full_h_loss(const float *R, int64_t d_out, int64_t d_in, const float *H, int64_t ldh, float *part,
+                        int grid_cap, hipStream_t s);
 int gram_parts(int b);
 void launch_sum_to_double(const float *part, int n, double *out, hipStream_t s);
 void launch_sparse_step(const Dims &d, const float *G, float *C, uint8_t *mask, const float *K,

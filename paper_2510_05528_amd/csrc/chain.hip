@@ -35,7 +35,8 @@ namespace armor {
 //   gpart[(i*nsplit + c)][b][b] = -2 * that sum          (partial grad_A^(i))
 //   beta_part[i*nbj + j] = || S^(i,j) D^(j) S^(i,j)T ||_F (Eq. 9 summand / 2)
 //   loss_part[i*nbj + j] = sum (R^(i,j))^2 D^(j)          (Eq. 5 summand)
-// LOSS_ONLY stops after the block loss.
+// LOSS_ONLY stops after the block loss; a non-null gpart then receives the residual R sqrt(D) itself,
+// laid out like Wbar (the full-matrix loss evaluation passes D = 1 and reads R from it).
 // ------------------------------------------------------------------------------------------------
 template <int B, bool LOSS_ONLY>
 __global__ __launch_bounds__(Chain<B>::NT) void phase_A_kernel(
@@ -105,6 +106,15 @@ __global__ __launch_bounds__(Chain<B>::NT) void phase_A_kernel(
                     acc.v[tm][tn][r] = res;
                 }
             }
+        if (LOSS_ONLY && gpart != nullptr) { // the loss-only pass can leave R sqrt(D) (d_out x d_in, like Wbar) in gpart
+            float *Rij = gpart + (int64_t)i * B * d_in + (int64_t)j * B;
+#pragma unroll
+            for (int tm = 0; tm < CH::TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < CH::TN; ++tn)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) gst(Rij, lb + CH::Pos::unif_boff(tm, tn, r, ldw), acc.v[tm][tn][r]);
+        }
         float ltot = CH::block_sum(lsum, sm.red, tid); // (has barriers: every wave is done reading Y)
         if (tid == 0) loss_part[i * nbj + j] = ltot;
         if (!LOSS_ONLY) {

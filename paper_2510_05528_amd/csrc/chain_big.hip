@@ -158,6 +158,10 @@ __global__ __launch_bounds__(CH::NT) void big_phase_A_kernel(
                     }
                 }
             if (!LOSS_ONLY) for_acc(acc, p, pt, qt, b, [&](uint32_t off, float v, int, int, int) { gst(s1, off, v); });
+            else if (gpart != nullptr) // loss-only pass: R D of the block, laid out like Wbar (see phase_A_kernel)
+                for_acc(acc, p, pt, qt, ldw, [&](uint32_t off, float v, int, int, int) {
+                    gst(gpart + (int64_t)i * b * d_in + (int64_t)j * b, off, v);
+                });
         });
         float ltot = CH::block_sum(lsum, sm.red, tid);
         if (tid == 0) loss_part[i * nbj + j] = ltot;

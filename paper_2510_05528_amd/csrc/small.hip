@@ -562,6 +562,15 @@ __global__ __launch_bounds__(256) void zero_kernel(float *__restrict__ x, int64_
     for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < n; e += (int64_t)gridDim.x * 256) x[e] = 0.f;
 }
 
+__global__ __launch_bounds__(256) void fill_kernel(float *__restrict__ x, int64_t n, float v) {
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < n; e += (int64_t)gridDim.x * 256) x[e] = v;
+}
+
+void launch_fill(float *x, int64_t n, float v, hipStream_t s) {
+    int grid = (int)std::min<int64_t>((n + 255) / 256, 65536);
+    if (grid > 0) hipLaunchKernelGGL(fill_kernel, dim3(grid), dim3(256), 0, s, x, n, v);
+}
+
 void launch_zero(float *x, int64_t n, hipStream_t s) {
     int grid = (int)std::min<int64_t>((n + 255) / 256, 65536);
     if (n > 0) hipLaunchKernelGGL(zero_kernel, dim3(grid), dim3(256), 0, s, x, n);

@@ -124,6 +124,41 @@ def test_proxy_loss(armor, torch, orc, d_out, d_in, b):
     assert got == pytest.approx(expect, rel=2e-5)
 
 
+@pytest.mark.parametrize("d_out,d_in,b", [(64, 96, 32), (192, 160, 32), (128, 192, 64), (256, 384, 128), (384, 256, 64),
+                                          (512, 768, 256), (1024, 1536, 128)])
+def test_full_gram_loss(armor, torch, orc, d_out, d_in, b):
+    """tr(R H R^T) against the oracle: correlated activations (the off-diagonal part of H carries a good share of
+    the value), H handed over with a padded row pitch; shapes on the 32-wide tile path and on the 128-wide one."""
+    say("full_gram_loss", d_out, d_in, b)
+    rng = np.random.default_rng(5)
+    v = np.sign(rng.standard_normal(d_in)).astype(np.float32)
+    # a factor all channels share, in the activations and (weaker) in the rows of the weight: the residual
+    # then correlates with it and the off-diagonal part of H carries most of the value
+    Wbar = (rng.standard_normal((d_out, d_in)) + 0.5 * rng.standard_normal((d_out, 1)) * v[None, :]).astype(np.float32)
+    X = rng.standard_normal((2 * d_in, d_in)).astype(np.float32)
+    X[:, ::5] *= 4.0
+    X += rng.standard_normal((2 * d_in, 1)).astype(np.float32) * v[None, :]
+    H = (X.astype(np.float64).T @ X.astype(np.float64)).astype(np.float32)
+    D = np.diag(H).copy()
+    A = (np.eye(b)[None] + 0.1 * rng.standard_normal((d_out // b, b, b))).astype(np.float32)
+    B = (np.eye(b)[None] + 0.1 * rng.standard_normal((d_in // b, b, b))).astype(np.float32)
+    C, _ = orc.init_nm(Wbar, D, 2, 4)
+    ref = orc.proxy_loss_full_h(Wbar, A, C, B, H)
+    assert abs(ref - orc.proxy_loss(Wbar, A, C, B, D)) > 0.5 * ref  # not the diagonal loss in disguise
+    Hd = torch.zeros((d_in, d_in + 4), device="cuda", dtype=torch.float32)  # row pitch d_in + 4
+    Hd[:, :d_in] = dev(torch, H)
+    got = armor.proxy_loss_full_h(dev(torch, Wbar), dev(torch, A), dev(torch, C), dev(torch, B), Hd[:, :d_in]).item()
+    assert got == pytest.approx(ref, rel=2e-5)
+    # identity wrappers (NULL): R = Wbar - C
+    got = armor.proxy_loss_full_h(dev(torch, Wbar), None, dev(torch, C), None, dev(torch, H), d_block=b).item()
+    R = Wbar.astype(np.float64) - C
+    assert got == pytest.approx(float(np.sum((R @ H.astype(np.float64)) * R)), rel=2e-5)
+    # a diagonal H gives Eq. 2, and an exact factorization gives zero
+    got = armor.proxy_loss_full_h(dev(torch, Wbar), dev(torch, A), dev(torch, C), dev(torch, B), dev(torch, np.diag(D).astype(np.float32))).item()
+    assert got == pytest.approx(orc.proxy_loss(Wbar, A, C, B, D), rel=2e-5)
+    assert armor.proxy_loss_full_h(dev(torch, Wbar), None, dev(torch, Wbar), None, dev(torch, H), d_block=b).item() == 0.0
+
+
 def check_factorization(armor, torch, orc, W, D, b, N, M, n_iters, seed, selection=0, tag="", init=None, iter_offset=0):
     """One run on both sides from the same start (Eq. 3, or `init` = (A, B, C, mask) numpy arrays)."""
     d_out, d_in = W.shape

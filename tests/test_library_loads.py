@@ -59,6 +59,13 @@ def test_status_strings_and_host_side_validation():
         assert lib.armor_factorize_layer(p, 0, p, 0, 64, 64, 32, 2, 4, 1, ctypes.byref(bad), p, p, p, p, None, None,
                                          None, None, None, None, p, 1 << 30, None) == 2
     assert lib.armor_status_string(8).startswith(b"non-finite")
+    # the loss against the whole Gram matrix: its workspace also holds the residual
+    assert lib.armor_proxy_loss_full_h_workspace_bytes(128, 128, 64) > lib.armor_proxy_loss_workspace_bytes(128, 128, 64) + 4 * 128 * 128
+    assert lib.armor_proxy_loss_full_h_workspace_bytes(128, 100, 64) == 0
+    assert lib.armor_proxy_loss_full_h(None, None, None, None, None, 64, 64, 64, 32, None, None, 0, None) == 1
+    assert lib.armor_proxy_loss_full_h(p, None, p, None, p, 63, 64, 64, 32, p, p, 1 << 30, None) == 2   # ldh < d_in
+    assert lib.armor_proxy_loss_full_h(p, None, p, None, p, 66, 64, 64, 32, p, p, 1 << 30, None) == 2   # ldh not a multiple of 4
+    assert lib.armor_proxy_loss_full_h(p, None, p, None, p, 64, 64, 64, 32, p, p, 16, None) == 4        # workspace too small
     # the allocation-free loss: argument errors and the fixed-scratch limit are host-side checks
     assert lib.armor_proxy_loss_noalloc(None, None, None, None, None, 0, 64, 64, 32, None, None) == 1
     assert lib.armor_proxy_loss_noalloc(p, None, p, None, p, 0, 64, 60, 32, p, None) == 2
