@@ -444,11 +444,9 @@ armor_status armor_proxy_loss_full_h(const float *Wbar, const float *A, const fl
     if (!B) { launch_init_identity(w.l.Bi, d.nbj, d.b, s); B = w.l.Bi; }
     // the loss-only forward pass with unit weights leaves R = Wbar - A S B in its gradient argument
     if (d.b > 128)
-        launch_big_phase_A(d, Wbar, S, A, B, w.l.D, choose_nsplit(d.nbi, d.nbj, d.b), w.R, nullptr, w.l.loss_part, true,
-                           big_wgs, w.l.big, s);
+        launch_big_residual(d, Wbar, S, A, B, w.l.D, choose_nsplit(d.nbi, d.nbj, d.b), w.R, w.l.loss_part, big_wgs, w.l.big, s);
     else
-        launch_phase_A(d, Wbar, S, A, B, w.l.D, choose_nsplit(d.nbi, d.nbj, d.b), w.R, nullptr, w.l.loss_part, true, nullptr,
-                       nullptr, s);
+        launch_residual(d, Wbar, S, A, B, w.l.D, choose_nsplit(d.nbi, d.nbj, d.b), w.R, w.l.loss_part, s);
     launch_full_h_loss(w.R, d.d_out, d.d_in, H, ldh, w.part, chain_slots(128), s);
     launch_sum_to_double(w.part, (int)full_h_parts(d.d_out, d.d_in), loss_out, s);
     return check_hip();

@@ -132,6 +132,14 @@ void launch_adam_wrapper(float *X, float *m, float *v, int nblk, int b, const fl
 void launch_zero(float *x, int64_t n, hipStream_t s);
 void launch_fill(float *x, int64_t n, float v, hipStream_t s);
 
+// Loss-only forward pass that can also leave the residual R sqrt(D) (R D at d_block 256) in Rout, a d_out x d_in
+// matrix with leading dimension d_in (chain.hip: d_block <= 128; chain_big.hip: 256).  Rout may be null.
+void launch_residual(const Dims &d, const float *Wbar, const float *C, const float *A, const float *B, const float *D,
+                     int nsplit, float *Rout, float *loss_part, hipStream_t s);
+void launch_big_residual(const Dims &d, const float *Wbar, const float *C, const float *A, const float *B,
+                         const float *D, int nsplit, float *Rout, float *loss_part, int grid_cap, float *scratch,
+                         hipStream_t s);
+
 // ---- loss against the whole Gram matrix (full_h.hip) ---------------------------------------------
 // tile edge used for d_out x d_in, number of per-tile partial sums, and the launch:  part[tile] = <R_tile, (R H)_tile>
 int full_h_tile(int64_t d_out, int64_t d_in);

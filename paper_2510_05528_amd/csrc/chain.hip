@@ -932,15 +932,22 @@ void launch_eta_W_trace(const Dims &d, const float *fro2A, const float *fro2K, d
     default: break;                                      \
     }
 
+// Loss-only forward pass (d_block <= 128): block losses to loss_part and, if Rout is given, the residual
+// R sqrt(D) as a d_out x d_in matrix (leading dimension d_in).
+void launch_residual(const Dims &d, const float *Wbar, const float *C, const float *A, const float *B, const float *D,
+                     int nsplit, float *Rout, float *loss_part, hipStream_t s) {
+    ARMOR_DISPATCH_B(d.b, {
+        dim3 grid(d.nbi * nsplit), block(Chain<BB>::NT);
+        hipLaunchKernelGGL((phase_A_kernel<BB, true>), grid, block, 0, s, Wbar, C, A, B, D, d.d_in, d.nbj, nsplit, Rout,
+                           (float *)nullptr, loss_part);
+    });
+}
+
 void launch_phase_A(const Dims &d, const float *Wbar, const float *C, const float *A, const float *B,
                     const float *D, int nsplit, float *gpart, float *beta_part, float *loss_part,
                     bool loss_only, float *stream_scratch, const WrapperPlanes *planes, hipStream_t s) {
-    if (loss_only) {
-        ARMOR_DISPATCH_B(d.b, {
-            dim3 grid(d.nbi * nsplit), block(Chain<BB>::NT);
-            hipLaunchKernelGGL((phase_A_kernel<BB, true>), grid, block, 0, s, Wbar, C, A, B, D, d.d_in, d.nbj, nsplit,
-                               gpart, beta_part, loss_part);
-        });
+    if (loss_only) { // (the kernel's gradient argument doubles as the residual output in this mode: never the partials)
+        launch_residual(d, Wbar, C, A, B, D, nsplit, nullptr, loss_part, s);
         return;
     }
     if (d.b == 128) { // two workgroups per CU

@@ -606,12 +606,21 @@ void launch_big_phase_A(const Dims &d, const float *Wbar, const float *C, const 
                         int grid_cap, float *scratch, hipStream_t s) {
     const int nitems = d.nbi * nsplit;
     dim3 grid(std::min(nitems, grid_cap)), block(CH::NT);
-    if (loss_only)
+    if (loss_only) // (the kernel's gradient argument doubles as the residual output in this mode: never the partials)
         hipLaunchKernelGGL((big_phase_A_kernel<2, true>), grid, block, 0, s, Wbar, C, A, B, D, d.d_in, d.nbj, nsplit,
-                           nitems, gpart, beta_part, loss_part, scratch);
+                           nitems, (float *)nullptr, beta_part, loss_part, scratch);
     else
         hipLaunchKernelGGL((big_phase_A_kernel<2, false>), grid, block, 0, s, Wbar, C, A, B, D, d.d_in, d.nbj, nsplit,
                            nitems, gpart, beta_part, loss_part, scratch);
+}
+
+// Loss-only forward pass at d_block 256 that also leaves the residual R D in Rout (d_out x d_in, leading dimension d_in).
+void launch_big_residual(const Dims &d, const float *Wbar, const float *C, const float *A, const float *B,
+                         const float *D, int nsplit, float *Rout, float *loss_part, int grid_cap, float *scratch,
+                         hipStream_t s) {
+    const int nitems = d.nbi * nsplit;
+    hipLaunchKernelGGL((big_phase_A_kernel<2, true>), dim3(std::min(nitems, grid_cap)), dim3(CH::NT), 0, s, Wbar, C, A, B, D,
+                       d.d_in, d.nbj, nsplit, nitems, Rout, (float *)nullptr, loss_part, scratch);
 }
 
 void launch_big_phase_B(const Dims &d, const float *Wbar, const float *C, const float *A, const float *B,
