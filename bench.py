@@ -57,6 +57,14 @@ APPLY_WORKLOADS = {
     "llama70b_gate_apply_8192tok_b256_2:4": (28672, 8192, 8192, 256),
 }
 
+# The layer-wise objective against the whole Gram matrix, tr(R H R^T), for a given factorization (evaluation
+# only; not part of the method's loop and not the default bench line): (d_out, d_in, d_block).
+FULL_GRAM_WORKLOADS = {
+    "llama7b_attn_full_gram_loss_4096x4096_b128": (4096, 4096, 128),
+    "llama3_8b_gate_full_gram_loss_14336x4096_b128": (14336, 4096, 128),
+    "llama70b_attn_full_gram_loss_8192x8192_b256": (8192, 8192, 256),
+}
+
 FP32_MFMA_PEAK = 157.3e12  # MI355X dense fp32 matrix peak, FLOP/s
 BF16_MFMA_PEAK = 2.5e15    # MI355X dense bf16 matrix peak, FLOP/s
 
@@ -283,12 +291,74 @@ def run_apply_workload(args, armor, synth, torch, dev):
     print(json.dumps(result))
 
 
+def run_full_gram_workload(args, armor, synth, torch, dev):
+    """One step = one armor_proxy_loss_full_h call: the forward chain that leaves R = Wbar - A S B, then <R, R H>."""
+    import numpy as np
+    d_out, d_in, b = FULL_GRAM_WORKLOADS[args.workload]
+    g = torch.Generator(device=dev)
+    g.manual_seed(0)
+    W = synth.torch_weight(d_out, d_in, 0, dev, bf16=False).float().contiguous()
+    X = synth.torch_calibration(8192, d_in, 0, dev, outlier_frac=0.005, outlier_scale=20.0, dtype=torch.float32)
+    H = (X.T @ X).contiguous()
+    S = (W * (torch.rand((d_out, d_in), device=dev, generator=g) > 0.5)).contiguous()
+    A = (torch.eye(b, device=dev).repeat(d_out // b, 1, 1) + 0.02 * torch.randn((d_out // b, b, b), device=dev, generator=g)).contiguous()
+    Bw = (torch.eye(b, device=dev).repeat(d_in // b, 1, 1) + 0.02 * torch.randn((d_in // b, b, b), device=dev, generator=g)).contiguous()
+    ws = torch.empty(armor.load_library().armor_proxy_loss_full_h_workspace_bytes(d_out, d_in, b), device=dev, dtype=torch.uint8)
+    for _ in range(args.warmup):
+        out = armor.proxy_loss_full_h(W, A, S, Bw, H, ws=ws)
+    torch.cuda.synchronize()
+    armor.profile_enable(True)
+    armor.profile_read()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        out = armor.proxy_loss_full_h(W, A, S, Bw, H, ws=ws)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    prof = armor.profile_read()
+    armor.profile_enable(False)
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    kernels = {k: {"launches": int(cn), "avg_ms": ms / cn} for k, (ms, cn) in prof.items() if cn > 0}
+    flops = 2.0 * d_out * d_in * d_in                       # R H; the reduction <R, R H> rides in its epilogue
+    k_ms = kernels["full_gram_loss"]["avg_ms"]
+    split = d_out % 128 == 0 and d_in % 128 == 0            # 128-wide tiles: six bf16 partial products per fp32 product
+    achieved = (6.0 if split else 1.0) * flops / (k_ms * 1e-3) / 1e12
+    peak = (BF16_MFMA_PEAK if split else FP32_MFMA_PEAK) / 1e12
+    result = {
+        "metric": "full-Gram loss evaluations/s", "value": 1e3 / ms_per_step, "unit": "evaluations/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": args.workload, "d_out": d_out, "d_in": d_in, "d_block": b,
+                   "step": "armor_proxy_loss_full_h (forward chain leaving R, then <R, R H>)"},
+        "loss": float(out.item()),
+        "roofline": {"bound": "mfma", "kernel": "full_h_loss_kernel", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
+                     "frac": achieved / peak, "traffic": None,
+                     "flops_counted": "executed bf16 flops per launch (6 partial products per fp32 product)" if split else "fp32 flops",
+                     "algorithmic_flops_per_launch": flops, "avg_launch_ms": k_ms,
+                     "fp32_equivalent": {"achieved": flops / (k_ms * 1e-3) / 1e12, "peak": FP32_MFMA_PEAK / 1e12,
+                                         "frac": flops / (k_ms * 1e-3) / FP32_MFMA_PEAK}},
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        oracle.build()
+        rows = 256                                              # the oracle on a slice of rows (the value is a sum over rows)
+        c0 = time.perf_counter()
+        ref = oracle.proxy_loss_full_h(W[:rows].cpu().numpy(), A[:rows // b].cpu().numpy(), S[:rows].cpu().numpy(),
+                                       Bw.cpu().numpy(), H.cpu().numpy())
+        c1 = time.perf_counter()
+        got = armor.proxy_loss_full_h(W[:rows].contiguous(), A[:rows // b].contiguous(), S[:rows].contiguous(), Bw, H).item()
+        result["cpu_baseline"] = {"value": rows / d_out / (c1 - c0), "unit": "evaluations/s", "cores": os.cpu_count(), "kind": "oracle",
+                                  "sample": "the first %d of %d rows (the value is a sum over rows), scaled; %.1f s wall" % (rows, d_out, c1 - c0),
+                                  "rel_err_vs_gpu_on_the_sample": abs(got - ref) / abs(ref)}
+    print(json.dumps(result))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None, help="timed steps (default 3; 100 for the ~1 ms apply workloads)")
     ap.add_argument("--warmup", type=int, default=None, help="untimed steps first (default 1; 20 for the apply workloads)")
-    ap.add_argument("--workload", default=DEFAULT, choices=sorted(WORKLOADS) + sorted(BLOCK_WORKLOADS) + sorted(APPLY_WORKLOADS))
+    ap.add_argument("--workload", default=DEFAULT, choices=sorted(WORKLOADS) + sorted(BLOCK_WORKLOADS) + sorted(APPLY_WORKLOADS) + sorted(FULL_GRAM_WORKLOADS))
     ap.add_argument("--variant", default="gd", choices=["gd", "adam"],
                     help="continuous step: sequential 1/beta gradient steps (default; the monotone variant) or the "
                          "joint Adam step the authors run in practice (lr 1e-4)")
@@ -304,7 +374,7 @@ def main():
                     help="only run a plain device copy of known size (256 MiB read + 256 MiB written, 3 times) "
                          "so that rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings can be scaled")
     args = ap.parse_args()
-    short = args.workload in APPLY_WORKLOADS  # a step of ~1 ms: a few of them would time the clock ramp
+    short = args.workload in APPLY_WORKLOADS or args.workload in FULL_GRAM_WORKLOADS  # a step of ~1 ms: a few of them would time the clock ramp
     if args.steps is None:
         args.steps = 100 if short else 3
     if args.warmup is None:
@@ -336,6 +406,9 @@ def main():
         return
     if args.workload in APPLY_WORKLOADS:
         run_apply_workload(args, armor, synth, torch, dev)
+        return
+    if args.workload in FULL_GRAM_WORKLOADS:
+        run_full_gram_workload(args, armor, synth, torch, dev)
         return
     d_out, d_in, n_tok, b, N, M, n_iters, w_bf16, x_bf16, ofrac, oscale = WORKLOADS[args.workload]
     workload_name = args.workload + ("_adam" if args.variant == "adam" else "")

@@ -104,7 +104,9 @@ int armor_last_hip_error(void);
 #define ARMOR_PROF_APPLY_PRE 11  /* armor_apply_packed: U = X B^T */
 #define ARMOR_PROF_APPLY_MAIN 12 /* armor_apply_packed: Y = (U S^T) A^T */
 #define ARMOR_PROF_DIAG_X 13     /* armor_gram_diag_x */
-#define ARMOR_PROF_KINDS 14
+#define ARMOR_PROF_RESIDUAL 14   /* armor_proxy_loss_full_h: forward chain that leaves R */
+#define ARMOR_PROF_FULL_H 15     /* armor_proxy_loss_full_h: <R, R H> */
+#define ARMOR_PROF_KINDS 16
 armor_status armor_profile_enable(int on);
 armor_status armor_profile_read(double *ms_total /*host [ARMOR_PROF_KINDS]*/, int64_t *launches /*host*/);
 

@@ -10,7 +10,7 @@ _LIB_PATH = os.path.join(_HERE, "libarmor.so")
 ARMOR_F32, ARMOR_BF16 = 0, 1
 
 PROF_KINDS = ["gram", "phase_A", "phase_B", "phase_WS", "sparse_step", "phase_FB", "phase_GS", "normalize", "init",
-              "pack_nm", "small_kernels", "apply_pre", "apply_main", "gram_diag_x"]
+              "pack_nm", "small_kernels", "apply_pre", "apply_main", "gram_diag_x", "residual", "full_gram_loss"]
 
 EXPORTED = ["armor_status_string", "armor_last_hip_error", "armor_profile_enable", "armor_profile_read",
             "armor_gram_workspace_bytes", "armor_gram", "armor_gram_diag",

@@ -443,11 +443,18 @@ armor_status armor_proxy_loss_full_h(const float *Wbar, const float *A, const fl
     if (!A) { launch_init_identity(w.l.Ai, d.nbi, d.b, s); A = w.l.Ai; }
     if (!B) { launch_init_identity(w.l.Bi, d.nbj, d.b, s); B = w.l.Bi; }
     // the loss-only forward pass with unit weights leaves R = Wbar - A S B in its gradient argument
-    if (d.b > 128)
-        launch_big_residual(d, Wbar, S, A, B, w.l.D, choose_nsplit(d.nbi, d.nbj, d.b), w.R, w.l.loss_part, big_wgs, w.l.big, s);
-    else
-        launch_residual(d, Wbar, S, A, B, w.l.D, choose_nsplit(d.nbi, d.nbj, d.b), w.R, w.l.loss_part, s);
-    launch_full_h_loss(w.R, d.d_out, d.d_in, H, ldh, w.part, chain_slots(128), s);
+    {
+        ProfScope ps(ARMOR_PROF_RESIDUAL, s);
+        if (d.b > 128)
+            launch_big_residual(d, Wbar, S, A, B, w.l.D, choose_nsplit(d.nbi, d.nbj, d.b), w.R, w.l.loss_part, big_wgs,
+                                w.l.big, s);
+        else
+            launch_residual(d, Wbar, S, A, B, w.l.D, choose_nsplit(d.nbi, d.nbj, d.b), w.R, w.l.loss_part, s);
+    }
+    {
+        ProfScope ps(ARMOR_PROF_FULL_H, s);
+        launch_full_h_loss(w.R, d.d_out, d.d_in, H, ldh, w.part, chain_slots(128), s);
+    }
     launch_sum_to_double(w.part, (int)full_h_parts(d.d_out, d.d_in), loss_out, s);
     return check_hip();
 }
