@@ -220,10 +220,12 @@ def _start_state(init, d_out, d_in, b):
     return A, B, C, mask
 
 
-def factorize_layer(W, D, b, N, M, n_iters, seed=0, selection=0, sparsity=0, keep=0, init=None, iter_offset=0):
+def factorize_layer(W, D, b, N, M, n_iters, seed=0, selection=0, sparsity=0, keep=0, init=None, iter_offset=0, tol=0.0):
     """Whole outer loop.  Returns a dict with A, C (=S), B, mask, Wbar, r1, r2, loss_trace, loss_cont_trace,
-    etas [n_iters, 3] (eta_A, eta_B, eta_W' of each iteration) and mask_changes [n_iters].
-    init: optional dict(A, C, B, mask) to start from instead of Eq. 3; iter_offset: iterations already done."""
+    etas [n_iters, 3] (eta_A, eta_B, eta_W' of each iteration), mask_changes [n_iters] and iters_done.
+    init: optional dict(A, C, B, mask) to start from instead of Eq. 3; iter_offset: iterations already done.
+    tol: the tolerance input of Alg. 1 (stop after the first iteration t with L_{t-1} - L_t <= tol * L_0; 0 = never);
+    the traces are cut to the iterations that ran."""
     W, D = _f32(W), _f32(D)
     d_out, d_in = W.shape
     A, B, C, mask = _start_state(init, d_out, d_in, b)
@@ -234,15 +236,17 @@ def factorize_layer(W, D, b, N, M, n_iters, seed=0, selection=0, sparsity=0, kee
     ctrace = np.zeros(max(n_iters, 1), dtype=np.float64)
     etas = np.zeros((max(n_iters, 1), 3), dtype=np.float64)
     changes = np.zeros(max(n_iters, 1), dtype=np.int64)
+    done = ctypes.c_int(0)
     lib().oracle_factorize_layer_ex(_p(W, _f32p), _p(D, _f32p), _i64(d_out), _i64(d_in), _i64(b), ctypes.c_int(N),
                                     ctypes.c_int(M), ctypes.c_int(n_iters), ctypes.c_uint64(seed),
                                     ctypes.c_int(selection), ctypes.c_int(sparsity), _i64(keep),
                                     ctypes.c_int(0 if init is None else 1), _i64(iter_offset), _p(A, _f32p),
                                     _p(C, _f32p), _p(B, _f32p), _p(mask, _u8p), _p(Wbar, _f32p), _p(r1, _f32p),
                                     _p(r2, _f32p), _p(trace, _f64p), _p(ctrace, _f64p), _p(etas, _f64p),
-                                    _p(changes, _i64p))
-    return dict(A=A, C=C, B=B, mask=mask, Wbar=Wbar, r1=r1, r2=r2, loss_trace=trace,
-                loss_cont_trace=ctrace[:n_iters], etas=etas[:n_iters], mask_changes=changes[:n_iters])
+                                    _p(changes, _i64p), ctypes.c_double(tol), ctypes.byref(done))
+    n = done.value
+    return dict(A=A, C=C, B=B, mask=mask, Wbar=Wbar, r1=r1, r2=r2, loss_trace=trace[:n + 1],
+                loss_cont_trace=ctrace[:n], etas=etas[:n], mask_changes=changes[:n], iters_done=n)
 
 
 def adam_update(Wbar, D, mask, A, C, B, state, t, lr=1e-4, b1=0.9, b2=0.999, eps=1e-8):

@@ -694,7 +694,11 @@ void oracle_factorize_layer_ex(const float *W, const float *D, int64_t d_out, in
                                int64_t keep, int init_from, int64_t iter_offset, float *A, float *C,
                                float *B, uint8_t *mask, float *Wbar, float *r1, float *r2,
                                double *loss_trace, double *loss_cont_trace, double *etas,
-                               int64_t *mask_changes) {
+                               int64_t *mask_changes, double tol, int *iters_done) {
+    /* tol: the tolerance input of Alg. 1, which the listing declares and never uses.  Reading: the loop ends
+     * after the first iteration t whose decrease is within it, L_{t-1} - L_t <= tol * L_0 (tol = 0: all n_iters
+     * iterations run, also when the loss stops moving); iters_done receives that t, entries of the traces
+     * after it are left untouched. */
     dims_t d = mk_dims(d_out, d_in, b);
     int64_t P = d_out * d_in;
     uint8_t *before = mask_changes ? (uint8_t *)malloc((size_t)P) : NULL;
@@ -706,6 +710,7 @@ void oracle_factorize_layer_ex(const float *W, const float *D, int64_t d_out, in
         else oracle_init_unstructured(Wbar, D, d_out, d_in, keep, C, mask);
     }
     loss_trace[0] = oracle_proxy_loss(Wbar, A, C, B, D, d_out, d_in, b);
+    if (iters_done) *iters_done = 0;
     for (int t = 1; t <= n_iters; ++t) {
         oracle_continuous_update(Wbar, D, mask, d_out, d_in, b, A, C, B, etas ? etas + 3 * (t - 1) : NULL);
         if (loss_cont_trace) loss_cont_trace[t - 1] = oracle_proxy_loss(Wbar, A, C, B, D, d_out, d_in, b);
@@ -715,6 +720,8 @@ void oracle_factorize_layer_ex(const float *W, const float *D, int64_t d_out, in
                                       mask, NULL, NULL);
         if (mask_changes) mask_changes[t - 1] = sparsity == 0 ? count_changed_groups(before, mask, P, M) : 0;
         loss_trace[t] = oracle_proxy_loss(Wbar, A, C, B, D, d_out, d_in, b);
+        if (iters_done) *iters_done = t;
+        if (tol > 0.0 && loss_trace[t - 1] - loss_trace[t] <= tol * loss_trace[0]) break;
     }
     free(before);
 }
@@ -724,7 +731,7 @@ void oracle_factorize_layer(const float *W, const float *D, int64_t d_out, int64
                             int64_t keep, float *A, float *C, float *B, uint8_t *mask, float *Wbar,
                             float *r1, float *r2, double *loss_trace, double *loss_cont_trace) {
     oracle_factorize_layer_ex(W, D, d_out, d_in, b, N, M, n_iters, seed, selection, sparsity, keep, 0, 0, A, C, B,
-                              mask, Wbar, r1, r2, loss_trace, loss_cont_trace, NULL, NULL);
+                              mask, Wbar, r1, r2, loss_trace, loss_cont_trace, NULL, NULL, 0.0, NULL);
 }
 
 /* ------------------------------------------------------------------------------------------

@@ -570,6 +570,38 @@ def test_factorize_from_a_given_point_is_a_replay_of_the_two_steps(orc, N, M):
     assert not np.array_equal(other["C"], out["C"])
 
 
+def test_tolerance_stop_is_the_full_run_cut_at_the_first_small_decrease(orc):
+    """The tolerance input of Alg. 1 (declared in the listing, never used in it), read as: the loop ends after
+    the first iteration whose decrease is within it, L_{t-1} - L_t <= tol * L_0.  The stopped run must be the
+    full run cut at that iteration, found here from the full run's own loss trace."""
+    d_out, d_in, b = 32, 48, 16
+    W = synth.make_weight(d_out, d_in, seed=1, outlier_frac=0.05)
+    D = (np.random.default_rng(0).random(d_in) + 0.5).astype(np.float32)
+    n = 12
+    full = orc.factorize_layer(W, D, b, 2, 4, n, seed=3)
+    L = full["loss_trace"]
+    assert full["iters_done"] == n and len(L) == n + 1
+    dec = (L[:-1] - L[1:]) / L[0]
+    # a tolerance that at least one iteration in the middle of the run meets and the first ones do not
+    tol = float(np.sort(dec[2:])[len(dec[2:]) // 2])
+    tol = max(tol, float(np.nextafter(dec[:2].min(), 0)) * 0.5) if dec[:2].min() > tol else tol
+    stop = 1 + int(np.argmax(dec <= tol))
+    assert 1 <= stop < n
+    cut = orc.factorize_layer(W, D, b, 2, 4, n, seed=3, tol=tol)
+    assert cut["iters_done"] == stop
+    np.testing.assert_array_equal(cut["loss_trace"], L[:stop + 1])
+    prefix = orc.factorize_layer(W, D, b, 2, 4, stop, seed=3)
+    for k in ("A", "C", "B", "mask"):
+        np.testing.assert_array_equal(cut[k], prefix[k])
+    assert len(cut["etas"]) == stop and len(cut["mask_changes"]) == stop
+    # a tolerance nothing meets changes nothing; one that everything meets stops after the first iteration
+    none = orc.factorize_layer(W, D, b, 2, 4, n, seed=3, tol=float(dec.min()) * 0.5 if dec.min() > 0 else 1e-300)
+    assert none["iters_done"] == n or dec.min() <= 0
+    first = orc.factorize_layer(W, D, b, 2, 4, n, seed=3, tol=1.0)
+    assert first["iters_done"] == 1
+    np.testing.assert_array_equal(first["loss_trace"], L[:2])
+
+
 @pytest.mark.parametrize("adam", [False, True])
 def test_a_run_cut_in_two_is_the_same_run(orc, adam):
     """theta_0 is an input of Alg. 1: stopping after k iterations and starting again from the result,
