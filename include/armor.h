@@ -72,9 +72,21 @@ typedef struct {
                                    and returns ARMOR_ERR_NONFINITE before anything else is enqueued */
     int64_t iter_offset;        /* iterations already done: iteration t of this call draws its groups (Alg. 3) with
                                    the counter of iteration iter_offset + t; >= 0 */
+    double tol;                 /* the tolerance input of Alg. 1 (the listing declares it and never uses it): > 0 ends
+                                   the loop after the first iteration t whose decrease is within it,
+                                   L_{t-1} - L_t <= tol * L_0; 0 (default) runs all n_iters.  L_t is known one forward
+                                   pass later, so with tol > 0 every iteration copies one double to the host and waits
+                                   for the stream (the only synchronisation inside the loop); the forward pass that
+                                   found the stop is discarded and the outputs are theta_t.  Trace entries of
+                                   iterations that did not run repeat the final loss (loss_trace, loss_cont_trace) or
+                                   are 0 (eta_trace, mask_changes); armor_last_iteration_count() tells how many ran.
+                                   Sequential variant only (joint Adam updates the core inside its forward/backward
+                                   kernel and cannot discard a pass): ARMOR_ERR_UNSUPPORTED with variant = 1. */
 } armor_opts;
 
 const char *armor_status_string(armor_status s);
+/* Iterations the last armor_factorize_layer call of the calling thread ran (n_iters unless opts->tol ended it). host. */
+int64_t armor_last_iteration_count(void);
 /* hipError_t (as int) of the last failed HIP call made by this library on the calling thread. host. */
 int armor_last_hip_error(void);
 

@@ -12,7 +12,7 @@ ARMOR_F32, ARMOR_BF16 = 0, 1
 PROF_KINDS = ["gram", "phase_A", "phase_B", "phase_WS", "sparse_step", "phase_FB", "phase_GS", "normalize", "init",
               "pack_nm", "small_kernels", "apply_pre", "apply_main", "gram_diag_x", "residual", "full_gram_loss"]
 
-EXPORTED = ["armor_status_string", "armor_last_hip_error", "armor_profile_enable", "armor_profile_read",
+EXPORTED = ["armor_status_string", "armor_last_hip_error", "armor_last_iteration_count", "armor_profile_enable", "armor_profile_read",
             "armor_gram_workspace_bytes", "armor_gram", "armor_gram_diag",
             "armor_gram_diag_x_workspace_bytes", "armor_gram_diag_x",
             "armor_normalize_workspace_bytes", "armor_normalize", "armor_proxy_loss_workspace_bytes",
@@ -31,7 +31,7 @@ class ArmorOpts(ctypes.Structure):
                 ("seed", ctypes.c_uint64), ("denormalize", ctypes.c_int32), ("variant", ctypes.c_int32),
                 ("lr", ctypes.c_double), ("adam_beta1", ctypes.c_double), ("adam_beta2", ctypes.c_double),
                 ("adam_eps", ctypes.c_double), ("init_from_outputs", ctypes.c_int32), ("check_finite", ctypes.c_int32),
-                ("iter_offset", ctypes.c_int64)]
+                ("iter_offset", ctypes.c_int64), ("tol", ctypes.c_double)]
 
 
 _lib = None
@@ -49,6 +49,7 @@ def load_library():
     lib.armor_status_string.restype = ctypes.c_char_p
     lib.armor_status_string.argtypes = [_int]
     lib.armor_last_hip_error.restype = _int
+    lib.armor_last_iteration_count.restype = _i64
     lib.armor_profile_enable.argtypes = [_int]
     lib.armor_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
     lib.armor_gram_workspace_bytes.restype = _sz
@@ -273,10 +274,13 @@ def factorize_workspace_bytes(d_out, d_in, d_block, N, M, sparsity=0, variant=0)
 
 def factorize_layer(W, H, d_block, N, M, n_iters, seed=0, selection=0, sparsity=0, unstructured_keep=0,
                     denormalize=False, ws=None, want_cont_trace=False, variant=0, lr=0.0, adam_beta1=0.0,
-                    adam_beta2=0.0, adam_eps=0.0, init=None, iter_offset=0, check_finite=False, want_diagnostics=False):
-    """Run the BCD loop.  Returns dict(A, S, B, mask_bits, r1, r2, loss_trace[, loss_cont_trace][, eta_trace,
-    mask_changes]).  init: optional dict(A, S, B, mask_bits) of device tensors to start from (they are
-    copied; the copies are updated and returned) instead of the initialisation of Eq. 3."""
+                    adam_beta2=0.0, adam_eps=0.0, init=None, iter_offset=0, check_finite=False, want_diagnostics=False,
+                    tol=0.0):
+    """Run the BCD loop.  Returns dict(A, S, B, mask_bits, r1, r2, loss_trace, iters_done[, loss_cont_trace]
+    [, eta_trace, mask_changes]).  init: optional dict(A, S, B, mask_bits) of device tensors to start from (they
+    are copied; the copies are updated and returned) instead of the initialisation of Eq. 3.  tol > 0: the
+    tolerance of Alg. 1 (the loop ends after the first iteration whose loss decrease is <= tol * L_0); the
+    traces are then cut to the iterations that ran."""
     torch = _torch()
     lib = load_library()
     if not (W.is_cuda and W.is_contiguous()):
@@ -287,7 +291,7 @@ def factorize_layer(W, H, d_block, N, M, n_iters, seed=0, selection=0, sparsity=
     o = ArmorOpts(selection=selection, sparsity=sparsity, unstructured_keep=unstructured_keep, seed=seed,
                   denormalize=int(denormalize), variant=variant, lr=lr, adam_beta1=adam_beta1, adam_beta2=adam_beta2,
                   adam_eps=adam_eps, init_from_outputs=0 if init is None else 1, check_finite=int(check_finite),
-                  iter_offset=iter_offset)
+                  iter_offset=iter_offset, tol=tol)
     nbytes = lib.armor_factorize_workspace_bytes(d_out, d_in, d_block, N, M, ctypes.byref(o))
     if nbytes == 0:
         _check(2)
@@ -316,12 +320,13 @@ def factorize_layer(W, H, d_block, N, M, n_iters, seed=0, selection=0, sparsity=
                                      ctypes.byref(o), _ptr(A), _ptr(S), _ptr(B), _ptr(mask_bits), _ptr(r1), _ptr(r2),
                                      _ptr(trace), _ptr(ctrace), _ptr(etas), _ptr(changes), _ptr(ws), ws.numel(),
                                      _stream()))
-    out = dict(A=A, S=S, B=B, mask_bits=mask_bits, r1=r1, r2=r2, loss_trace=trace, ws=ws)
+    done = int(lib.armor_last_iteration_count())
+    out = dict(A=A, S=S, B=B, mask_bits=mask_bits, r1=r1, r2=r2, loss_trace=trace[:done + 1], ws=ws, iters_done=done)
     if want_cont_trace:
-        out["loss_cont_trace"] = ctrace[:n_iters]
+        out["loss_cont_trace"] = ctrace[:done]
     if want_diagnostics:
-        out["eta_trace"] = etas[:n_iters]
-        out["mask_changes"] = changes[:n_iters]
+        out["eta_trace"] = etas[:done]
+        out["mask_changes"] = changes[:done]
     return out
 
 

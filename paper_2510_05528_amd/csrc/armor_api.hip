@@ -130,6 +130,7 @@ struct FactorWs {
     float *Sp; // S' = A C handed from the B step to the W' step (sequential variant; at d_block < 128 in N:M mode only)
     float *Wbar, *G, *D, *gpart, *beta_part, *loss_part, *loss_part2, *K, *AtA, *colnorm2, *fro2A, *fro2K, *cn_partial,
         *r1, *r2;
+    double *tol_loss; // the loss the tolerance test of Alg. 1 reads back
     uint8_t *mask;
     void *unstructured;
     float *big_scratch;
@@ -180,6 +181,7 @@ FactorWs carve_factor(void *ws, const Dims &d, int mask_group, const armor_opts 
     f.beta_part = c.take<float>(d.nblocks);
     f.loss_part = c.take<float>(d.nblocks);
     f.loss_part2 = c.take<float>(d.nblocks);
+    f.tol_loss = c.take<double>(2);
     f.K = c.take<float>((size_t)d.nbj * bb);
     f.AtA = c.take<float>((size_t)d.nbi * bb);
     f.colnorm2 = c.take<float>(d.d_out);
@@ -242,6 +244,9 @@ const char *armor_status_string(armor_status s) {
 }
 
 int armor_last_hip_error(void) { return g_last_hip_error; }
+
+static thread_local int64_t g_last_iterations = 0;
+int64_t armor_last_iteration_count(void) { return g_last_iterations; }
 
 armor_status armor_profile_enable(int on) {
     g_prof.on = on != 0;
@@ -556,6 +561,8 @@ armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const flo
     if (!unstructured && (double)(o.iter_offset + n_iters + 1) * ((double)d_out * (double)d_in / M) >= 4.0e18)
         return ARMOR_ERR_SHAPE;
     if (o.init_from_outputs && !mask_bits) return ARMOR_ERR_NULL;
+    if (!(o.tol >= 0.0) || o.tol > 1.0) return ARMOR_ERR_SHAPE; // (a NaN fails the first test)
+    if (o.tol > 0.0 && o.variant == 1) return ARMOR_ERR_UNSUPPORTED;
     const int mask_group = unstructured ? 8 : M;
     Dims d = make_dims(d_out, d_in, d_block);
     if (!ws) return ARMOR_ERR_WORKSPACE;
@@ -659,6 +666,8 @@ armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const flo
             }
         }
     }
+    int iters_done = n_iters;
+    double L0 = 0.0, Lprev = 0.0; // host copies of L_0 and L_{t-2} (tolerance test only)
     for (int t = 1; o.variant == 0 && t <= n_iters; ++t) {
         const int64_t t_draw = o.iter_offset + t;
         double *eta_t = eta_trace ? eta_trace + 3 * (size_t)(t - 1) : nullptr;
@@ -666,6 +675,24 @@ armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const flo
         {
             ProfScope ps(ARMOR_PROF_PHASE_A, s, t > 1);
             run_phase_A(false);
+        }
+        if (o.tol > 0.0) {
+            // The A phase has just left the block losses of theta_{t-1}: L_{t-1} is known now, one forward pass
+            // after the iteration that produced it.  The tolerance test of Alg. 1 is the one place where the
+            // loop waits for the device.
+            double Lcur = 0.0;
+            launch_sum_to_double(f.loss_part, d.nblocks, f.tol_loss, s);
+            if (hipMemcpyAsync(&Lcur, f.tol_loss, sizeof(double), hipMemcpyDeviceToHost, s) != hipSuccess ||
+                hipStreamSynchronize(s) != hipSuccess) {
+                st = check_hip();
+                return st != ARMOR_OK ? st : ARMOR_ERR_DEVICE;
+            }
+            if (t == 1) L0 = Lcur;
+            else if (Lprev - Lcur <= o.tol * L0) { // iteration t - 1 moved the loss by no more than the tolerance
+                iters_done = t - 1;
+                break;
+            }
+            Lprev = Lcur;
         }
         {
             ProfScope ps(ARMOR_PROF_SMALL, s, true);
@@ -714,7 +741,14 @@ armor_status armor_factorize_layer(const void *W, armor_dtype w_dtype, const flo
             if (st != ARMOR_OK) return st;
         }
     }
-    if (loss_trace) {
+    g_last_iterations = iters_done;
+    if (iters_done < n_iters) {
+        // ended by the tolerance: the outputs are theta_{iters_done}, whose loss the discarded forward pass left
+        // in tol_loss; entries of iterations that did not run repeat it (step sizes: 0; mask changes are 0 already)
+        if (loss_trace) launch_broadcast_double(loss_trace + iters_done, n_iters + 1 - iters_done, f.tol_loss, s);
+        if (loss_cont_trace) launch_broadcast_double(loss_cont_trace + iters_done, n_iters - iters_done, f.tol_loss, s);
+        if (eta_trace) launch_zero(reinterpret_cast<float *>(eta_trace + 3 * (size_t)iters_done), 6 * (int64_t)(n_iters - iters_done), s);
+    } else if (loss_trace) {
         run_phase_A(true);
         launch_sum_to_double(f.loss_part, d.nblocks, loss_trace + n_iters, s);
     }

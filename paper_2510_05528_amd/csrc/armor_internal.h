@@ -148,6 +148,7 @@ void launch_full_h_loss(const float *R, int64_t d_out, int64_t d_in, const float
                         int grid_cap, hipStream_t s);
 int gram_parts(int b);
 void launch_sum_to_double(const float *part, int n, double *out, hipStream_t s);
+void launch_broadcast_double(double *dst, int64_t n, const double *src, hipStream_t s); // dst[0..n) = *src
 void launch_sparse_step(const Dims &d, const float *G, float *C, uint8_t *mask, const float *K,
                         const float *colnorm2, int N, int M, int selection, uint64_t seed, int64_t t,
                         const float *loss_part, double *loss_cont_out, int32_t *changes_out, hipStream_t s);

@@ -585,6 +585,17 @@ __global__ __launch_bounds__(256) void sum_to_double_kernel(const float *__restr
     if (threadIdx.x == 0) *out = a;
 }
 
+// dst[0 .. n) = *src (src may be one of them)
+__global__ __launch_bounds__(256) void broadcast_double_kernel(double *__restrict__ dst, int64_t n, const double *src) {
+    const double v = *src;
+    __syncthreads();
+    for (int64_t e = threadIdx.x; e < n; e += 256) dst[e] = v;
+}
+
+void launch_broadcast_double(double *dst, int64_t n, const double *src, hipStream_t s) {
+    if (n > 0) hipLaunchKernelGGL(broadcast_double_kernel, dim3(1), dim3(256), 0, s, dst, n, src);
+}
+
 void launch_sum_to_double(const float *part, int n, double *out, hipStream_t s) {
     hipLaunchKernelGGL(sum_to_double_kernel, dim3(1), dim3(256), 0, s, part, n, out);
 }

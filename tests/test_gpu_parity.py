@@ -354,6 +354,51 @@ def test_a_stopped_run_continues_bit_for_bit(armor, torch, d_out, d_in, b):
         assert torch.equal(first[k], again[k]), k
 
 
+@pytest.mark.parametrize("d_out,d_in,b,unstructured", [(128, 192, 64, False), (256, 256, 32, False), (384, 256, 128, False),
+                                                       (512, 512, 256, False), (128, 192, 64, True)])
+def test_tolerance_stop_matches_the_oracle(armor, torch, orc, d_out, d_in, b, unstructured):
+    """opts.tol, the tolerance input of Alg. 1: the run ends after the first iteration t with
+    L_{t-1} - L_t <= tol * L_0, at the same t as the oracle, and what it returns is bit for bit the run of
+    exactly t iterations; trace entries are cut to t."""
+    W, X = make_layer(d_out, d_in, 200, seed=12)
+    D = (X.astype(np.float64) ** 2).sum(0).astype(np.float32)
+    n = 10
+    kw = dict(sparsity=1, keep=d_out * d_in // 2) if unstructured else {}
+    gkw = dict(sparsity=1, unstructured_keep=d_out * d_in // 2) if unstructured else {}
+    full = orc.factorize_layer(W, D, b, 2, 4, n, seed=2, **kw)
+    L = full["loss_trace"]
+    dec = (L[:-1] - L[1:]) / L[0]
+    # a tolerance between two consecutive decreases of the oracle's run (they shrink by 3 .. 10 % per iteration
+    # here), 1.5 % or more away from both: the two sides' decreases agree to 1e-3 or better, so rounding cannot
+    # move the stop
+    k = 5
+    assert np.all(np.diff(dec) < 0) and dec[k] < 0.98 * dec[k - 1]
+    tol = float(np.sqrt(dec[k - 1] * dec[k]))
+    stop = k + 1                                             # iteration k + 1 is the first within the tolerance
+    say("tolerance stop", d_out, d_in, b, "tol %.3e" % tol, "expected stop after iteration", stop, "decreases", dec[:stop + 1])
+    ref = orc.factorize_layer(W, D, b, 2, 4, n, seed=2, tol=tol, **kw)
+    assert ref["iters_done"] == stop
+    Wd, Dd = dev(torch, W), dev(torch, D)
+    out = armor.factorize_layer(Wd, Dd, b, 2, 4, n, seed=2, tol=tol, want_cont_trace=True, want_diagnostics=True, **gkw)
+    assert out["iters_done"] == stop
+    assert out["loss_trace"].numel() == stop + 1 and out["eta_trace"].shape[0] == stop and out["mask_changes"].numel() == stop
+    exact = armor.factorize_layer(Wd, Dd, b, 2, 4, stop, seed=2, want_cont_trace=True, want_diagnostics=True, **gkw)
+    for key in ("A", "S", "B", "mask_bits", "loss_cont_trace", "eta_trace", "mask_changes"):
+        assert torch.equal(out[key], exact[key]), key
+    # (the last loss comes from the forward pass of the discarded iteration here and from the loss-only pass
+    # there: the same value from two kernels at d_block 128 and 256)
+    assert torch.equal(out["loss_trace"][:-1], exact["loss_trace"][:-1])
+    np.testing.assert_allclose(out["loss_trace"][-1].item(), exact["loss_trace"][-1].item(), rtol=2e-6)
+    assert_trace_parity(out["loss_trace"].cpu().numpy(), ref["loss_trace"])
+    eye_a, eye_b = identity_blocks(d_out // b, b), identity_blocks(d_in // b, b)
+    say("  ", assert_update_parity("A", out["A"].cpu().numpy(), ref["A"], eye_a, stop))
+    say("  ", assert_update_parity("B", out["B"].cpu().numpy(), ref["B"], eye_b, stop))
+    # tol = 0 runs everything; the joint-Adam variant cannot discard a pass and refuses a tolerance
+    assert armor.factorize_layer(Wd, Dd, b, 2, 4, 3, seed=2, **gkw)["iters_done"] == 3
+    with pytest.raises(armor.ArmorError, match="status 7"):
+        armor.factorize_layer(Wd, Dd, b, 2, 4, 3, seed=2, tol=1e-3, variant=1, **gkw)
+
+
 def test_check_finite_rejects_bad_inputs(armor, torch):
     """opts.check_finite: NaN/Inf in W, NaN/Inf/negative loss weights -> ARMOR_ERR_NONFINITE (status 8),
     outputs untouched; clean inputs pass and give the same result as without the check."""

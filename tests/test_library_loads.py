@@ -55,9 +55,13 @@ def test_status_strings_and_host_side_validation():
     assert lib.armor_factorize_layer(p, 0, p, 0, 64, 64, 32, 2, 4, 1, ctypes.byref(o), p, p, p, None, None, None, None,
                                      None, None, None, p, 1 << 30, None) == 1
     for bad in (binding.ArmorOpts(iter_offset=-1), binding.ArmorOpts(iter_offset=1 << 31),
-                binding.ArmorOpts(init_from_outputs=2), binding.ArmorOpts(check_finite=-1)):
+                binding.ArmorOpts(init_from_outputs=2), binding.ArmorOpts(check_finite=-1),
+                binding.ArmorOpts(tol=-1e-3), binding.ArmorOpts(tol=float("nan")), binding.ArmorOpts(tol=2.0)):
         assert lib.armor_factorize_layer(p, 0, p, 0, 64, 64, 32, 2, 4, 1, ctypes.byref(bad), p, p, p, p, None, None,
                                          None, None, None, None, p, 1 << 30, None) == 2
+    tol_adam = binding.ArmorOpts(tol=1e-3, variant=1)   # the joint-Adam variant cannot discard a forward pass
+    assert lib.armor_factorize_layer(p, 0, p, 0, 64, 64, 32, 2, 4, 1, ctypes.byref(tol_adam), p, p, p, p, None, None,
+                                     None, None, None, None, p, 1 << 30, None) == 7
     assert lib.armor_status_string(8).startswith(b"non-finite")
     # the loss against the whole Gram matrix: its workspace also holds the residual
     assert lib.armor_proxy_loss_full_h_workspace_bytes(128, 128, 64) > lib.armor_proxy_loss_workspace_bytes(128, 128, 64) + 4 * 128 * 128
