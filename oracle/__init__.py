@@ -140,6 +140,14 @@ def reconstruct(A, C, B):
     return out
 
 
+def factor_sizes(d_out, d_in, b, N=2, M=4):
+    """Entry counts of the factorized layer (Sec. 3.1): the wrappers are stored as (d_out/b) x b x b and
+    (d_in/b) x b x b tensors, the core keeps N of every M entries of a d_out x d_in matrix.  One multiply-add per
+    stored entry and token, so the same counts give the work of y = A (S (B x)) (Sec. 4.4)."""
+    assert d_out % b == 0 and d_in % b == 0 and d_in % M == 0
+    return dict(wrappers=(d_out // b) * b * b + (d_in // b) * b * b, core=d_out * (d_in // M) * N, dense=d_out * d_in)
+
+
 def proxy_loss_full_h(Wbar, A, C, B, H):
     """The layer-wise objective against the whole Gram matrix H = X^T X (Sec. 2; Eq. 2 keeps only its
     diagonal):  tr(R H R^T) = ||R X^T||_F^2  with R = Wbar - A C B.  The definition written out in fp64."""

@@ -139,6 +139,38 @@ def test_loss_matches_dense_algebra_and_is_nonnegative(orc):
     np.testing.assert_allclose(orc.reconstruct(A, C, B), dense(A) @ C.astype(np.float64) @ dense(B), rtol=1e-12, atol=1e-14)
 
 
+def test_wrapper_overheads_printed_in_the_paper(orc):
+    """tests/golden/wrapper_overhead.txt: the relative parameter overhead of the wrappers over all linear layers of
+    a decoder block (caption of the perplexity table), and the flop overhead and theoretical speedup of one 2:4
+    layer (Sec. 4.4), all at d_block 128, reproduced from the entry counts of the factorized format and from the
+    shapes the factorization itself returns."""
+    import os
+    rows = [l.split() for l in open(os.path.join(os.path.dirname(__file__), "golden", "wrapper_overhead.txt"))
+            if l.strip() and not l.startswith("#")]
+    assert len(rows) == 5
+    for kind, name, *nums in rows:
+        if kind == "params":
+            hidden, inter, kv, printed = int(nums[0]), int(nums[1]), int(nums[2]), float(nums[3])
+            layers = [(hidden, hidden), (kv, hidden), (kv, hidden), (hidden, hidden),    # q, k, v, o
+                      (inter, hidden), (inter, hidden), (hidden, inter)]                 # gate, up, down
+            sizes = [orc.factor_sizes(do, di, 128) for do, di in layers]
+            o = 100.0 * sum(s["wrappers"] for s in sizes) / sum(s["dense"] for s in sizes)
+            assert round(o, 2) == printed, (name, o)
+        else:
+            d_out, d_in, printed = int(nums[0]), int(nums[1]), float(nums[2])
+            s = orc.factor_sizes(d_out, d_in, 128, 2, 4)
+            if kind == "flops":
+                assert round(100.0 * s["wrappers"] / s["dense"], 1) == printed
+            else:
+                assert round(s["dense"] / (s["core"] + s["wrappers"]), 2) == printed
+    # the counts are those of the tensors the factorization returns
+    W = synth.make_weight(64, 96, seed=0)
+    D = np.ones(96, dtype=np.float32)
+    out = orc.factorize_layer(W, D, 16, 2, 4, 0)
+    s = orc.factor_sizes(64, 96, 16)
+    assert out["A"].size + out["B"].size == s["wrappers"] and int(out["mask"].sum()) == s["core"] and out["C"].size == s["dense"]
+
+
 def test_full_gram_loss_is_the_activation_error_and_reduces_to_eq2(orc):
     """tr(R H R^T) (Sec. 2, the objective before Eq. 2 drops the off-diagonal of H): equals the squared output
     error ||R X^T||_F^2 on the activations that made H, the plain triple sum on a tiny case whose residual is
