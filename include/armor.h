@@ -17,6 +17,9 @@
  *   - Calls are asynchronous on `hip_stream` (a hipStream_t passed as void*; NULL = default
  *     stream), return a status code, never throw and never print.  Argument errors are detected
  *     on the host before any launch.  Results are deterministic: no floating-point atomics.
+ *     Two options of armor_factorize_layer make it wait for the stream: check_finite (once, before any
+ *     work) and tol (once per iteration); armor_proxy_loss_noalloc takes its scratch from an array inside
+ *     the library instead of a workspace argument.
  *   - d_block must divide d_out and d_in and be one of 32, 64, 128, 256; M must divide d_block,
  *     1 <= N < M <= 8; d_block * d_in <= 2^29 (a block row is addressed with 32-bit byte offsets).
  */
