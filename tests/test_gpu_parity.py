@@ -399,6 +399,35 @@ def test_tolerance_stop_matches_the_oracle(armor, torch, orc, d_out, d_in, b, un
         armor.factorize_layer(Wd, Dd, b, 2, 4, 3, seed=2, tol=1e-3, variant=1, **gkw)
 
 
+@pytest.mark.parametrize("b,variant", [(32, 0), (128, 0), (256, 0), (128, 1)])
+def test_all_zero_weight_stays_put(armor, torch, orc, b, variant):
+    """W = 0: every norm of Sec. 3.2 is replaced by 1, the core is zero, the betas of Eq. 9-10 are zero and the
+    wrapper updates are skipped (sequential variant), every selection score is zero and Alg. 3 takes group 0 of each
+    block.  Nothing may become NaN; the result is A = B = I, S = 0, loss 0 on both sides."""
+    d_out, d_in = 2 * b, 3 * b
+    W = np.zeros((d_out, d_in), dtype=np.float32)
+    D = (np.random.default_rng(0).random(d_in) + 0.5).astype(np.float32)
+    out = armor.factorize_layer(dev(torch, W), dev(torch, D), b, 2, 4, 3, seed=1, variant=variant, want_cont_trace=True,
+                                want_diagnostics=variant == 0)
+    torch.cuda.synchronize()
+    f = orc.factorize_layer_adam if variant == 1 else orc.factorize_layer
+    ref = f(W, D, b, 2, 4, 3, seed=1)
+    for k, rk in (("A", "A"), ("B", "B"), ("S", "C")):
+        got = out[k].cpu().numpy()
+        assert np.all(np.isfinite(got)), k
+        np.testing.assert_array_equal(got, ref[rk])
+    np.testing.assert_array_equal(out["A"].cpu().numpy(), identity_blocks(d_out // b, b))
+    assert float(out["loss_trace"].abs().max()) == 0.0 and float(out["loss_cont_trace"].abs().max()) == 0.0
+    mask = armor.unpack_mask(out["mask_bits"].cpu().numpy(), 4)
+    assert np.all(mask.reshape(d_out, d_in // 4, 4).sum(-1) == 2)
+    if variant == 0:
+        eta = out["eta_trace"].cpu().numpy()
+        assert np.all(eta[:, :2] == 0.0)                      # beta_A = beta_B = 0: steps skipped, reported as 0
+        np.testing.assert_allclose(eta, ref["etas"], rtol=1e-5)   # beta_W' = 2 ||I|| ||D|| is not zero
+        assert np.array_equal(out["mask_changes"].cpu().numpy(), ref["mask_changes"])
+    np.testing.assert_array_equal(out["r1"].cpu().numpy(), np.ones(d_in, dtype=np.float32))
+
+
 def test_check_finite_rejects_bad_inputs(armor, torch):
     """opts.check_finite: NaN/Inf in W, NaN/Inf/negative loss weights -> ARMOR_ERR_NONFINITE (status 8),
     outputs untouched; clean inputs pass and give the same result as without the check."""
